@@ -1,0 +1,405 @@
+"""CPU oracle for the vAttention decode step.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 NumPy implementation of what one decode step computes for
+one (sequence, query head): Algorithm 1 (vAttention) with Algorithm 2
+(budget_X) inlined, in the paper's order and notation.  It exists to check the
+HIP library; nothing in the product path may import it, and it imports
+nothing from the product.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg call it.
+
+Notation (Section 4.1): K, V in R^{n x d}, q in R^{1 x d};
+s_i = sm_scale * <K[i], q>, w_i = exp(s_i - m) with m = max_i s_i (the shift
+cancels in every ratio below), r_i = w_i V[i].  I_s, I_l, I_t are the sink,
+local-window and top-k index sets, I_f their (disjoint) union, n_s the number
+of residual tokens, I_bs the base sample and I_dyn the final sample, b its
+size.
+
+Pinned by tests/test_oracle_*.py against: the published Philox4x32-10
+known-answer vectors, textbook normal quantiles, dense attention from library
+routines (Eq. 1), brute-force enumeration of all samples on tiny inputs,
+textbook simple-random-sampling variance, closed-form budgets on constructed
+populations, and the (epsilon, delta) coverage of Definition 4.1.
+No function in this file is "parity unpinned".
+
+Readings of the paper taken where it is silent (each also listed in the design
+notes): softmax scale is an explicit factor sm_scale; sink / window are absolute
+token counts; top-k is taken over the tokens outside sink and window, so the
+three sets are disjoint and n_f is the sum of their sizes; sampling is without
+replacement; the base sample holds floor(f_b * n_s) tokens (at least 2) and
+sample variances divide by (b0 - 1); D and ||N|| in the budget formulas are
+the full quantities D_f + residual estimate; the budget is ceil(b*), lower
+capped by the base sample size and upper capped by n_s; I_dyn is a fresh draw
+independent of I_bs.
+"""
+from __future__ import annotations
+
+import math
+from itertools import combinations
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+TARGET_D = 0
+TARGET_N = 1
+TARGET_SDPA = 2
+
+_M0 = 0xD2511F53
+_M1 = 0xCD9E8D57
+_W0 = 0x9E3779B9
+_W1 = 0xBB67AE85
+_MASK32 = 0xFFFFFFFF
+
+
+# --------------------------------------------------------------------------
+# Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+# as 1, 2, 3", SC'11).  Counter-based: output = bijection_key(counter).
+# --------------------------------------------------------------------------
+def philox4x32_10(ctr: Sequence, key: Sequence[int]) -> List[np.ndarray]:
+    """Ten Philox-4x32 rounds.
+
+    ctr: four uint32 arrays (or ints) of one shape; key: two Python ints.
+    Each round multiplies words 0 and 2 by fixed odd constants, keeps the low
+    halves and mixes the high halves with words 1, 3 and the round key; the
+    key is advanced by the Weyl constants between rounds.
+    """
+    c0, c1, c2, c3 = (np.asarray(c, dtype=np.uint64) & np.uint64(_MASK32) for c in ctr)
+    k0 = int(key[0]) & _MASK32
+    k1 = int(key[1]) & _MASK32
+    mask = np.uint64(_MASK32)
+    sh = np.uint64(32)
+    for _ in range(10):
+        p0 = np.uint64(_M0) * c0
+        p1 = np.uint64(_M1) * c2
+        hi0, lo0 = p0 >> sh, p0 & mask
+        hi1, lo1 = p1 >> sh, p1 & mask
+        c0, c1, c2, c3 = hi1 ^ c1 ^ np.uint64(k0), lo1, hi0 ^ c3 ^ np.uint64(k1), lo0
+        k0 = (k0 + _W0) & _MASK32
+        k1 = (k1 + _W1) & _MASK32
+    return [c.astype(np.uint32) for c in (c0, c1, c2, c3)]
+
+
+def token_keys(n: int, seed: int, head: int, stream: int) -> np.ndarray:
+    """32-bit sampling key u_i of every token i < n.
+
+    Token i reads word (i mod 4) of Philox4x32-10 applied to the counter
+    (i div 4, stream, head, 0) under the key (low 32 bits of seed, high 32 bits
+    of seed).  `head` is the query-head index, `stream` separates the base
+    sample (0) from the final sample (1).
+    """
+    nblk = (n + 3) // 4
+    blk = np.arange(nblk, dtype=np.uint64)
+    out = philox4x32_10(
+        (blk, np.full(nblk, stream, np.uint64), np.full(nblk, head, np.uint64), np.zeros(nblk, np.uint64)),
+        (int(seed) & _MASK32, (int(seed) >> 32) & _MASK32),
+    )
+    return np.stack(out, axis=1).reshape(-1)[:n]
+
+
+def uniform_sample(residual: np.ndarray, c: int, keys: np.ndarray) -> np.ndarray:
+    """uniform-sample of Algorithms 1 and 2: c residual tokens, without replacement.
+
+    Every token carries an independent uniform 32-bit key; the sample is the c
+    residual tokens with the smallest (key, index) pairs, which is a uniformly
+    distributed c-subset.  Returned in ascending index order.
+    """
+    c = int(c)
+    if c <= 0:
+        return np.empty(0, dtype=np.int64)
+    u = keys[residual]
+    order = np.lexsort((residual, u))  # primary key u, ties by index
+    return np.sort(residual[order[:c]])
+
+
+# --------------------------------------------------------------------------
+# Normal quantile
+# --------------------------------------------------------------------------
+def upper_tail_quantile(t: float) -> float:
+    """z with 1 - Phi(z) = t for the standard normal, by bisection on erfc(z / sqrt 2) / 2 = t.
+
+    Working with the upper tail keeps Phi^{-1}(1 - delta/2) accurate for small delta,
+    where 1 - delta/2 itself would lose digits.
+    """
+    if not (0.0 < t < 1.0):
+        raise ValueError("t must be in (0, 1)")
+    lo, hi = -40.0, 40.0
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if 0.5 * math.erfc(mid / math.sqrt(2.0)) > t:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
+
+
+def normal_quantile(p: float) -> float:
+    """Phi^{-1}(p) for the standard normal."""
+    if not (0.0 < p < 1.0):
+        raise ValueError("p must be in (0, 1)")
+    return -upper_tail_quantile(p) if p < 0.5 else upper_tail_quantile(1.0 - p)
+
+
+# --------------------------------------------------------------------------
+# Attention pieces
+# --------------------------------------------------------------------------
+def scores(q: np.ndarray, K: np.ndarray, sm_scale: float) -> np.ndarray:
+    """s_i = sm_scale * <K[i], q> for all i (the exponent of Eq. 1), fp64."""
+    return np.float64(sm_scale) * (np.asarray(K, np.float64) @ np.asarray(q, np.float64))
+
+
+def dense_sdpa(q: np.ndarray, K: np.ndarray, V: np.ndarray, sm_scale: float):
+    """Eq. 1: full softmax attention of one query over all n tokens.  Returns (O, lse)."""
+    s = scores(q, K, sm_scale)
+    m = s.max()
+    w = np.exp(s - m)
+    D = w.sum()
+    N = w @ np.asarray(V, np.float64)
+    return N / D, m + math.log(D)
+
+
+def deterministic_set(s: np.ndarray, sink: int, window: int, k: int):
+    """Lines 1-5 of Algorithm 1 with oracle top-k.
+
+    I_s = first `sink` tokens, I_l = last `window` tokens (not overlapping
+    I_s), I_t = the k largest scores among the tokens in between (ties go to
+    the lower index).  Returns (I_s, I_l, I_t ascending, residual ascending).
+    """
+    n = s.shape[0]
+    ns_ = min(int(sink), n)
+    nl_ = min(int(window), n - ns_)
+    I_s = np.arange(0, ns_, dtype=np.int64)
+    I_l = np.arange(n - nl_, n, dtype=np.int64)
+    mid = np.arange(ns_, n - nl_, dtype=np.int64)
+    kk = min(max(int(k), 0), mid.shape[0])
+    if kk > 0:
+        order = np.lexsort((mid, -s[mid]))  # descending score, ties by lower index
+        I_t = np.sort(mid[order[:kk]])
+    else:
+        I_t = np.empty(0, dtype=np.int64)
+    member = np.zeros(n, dtype=bool)
+    member[I_t] = True
+    residual = mid[~member[mid]]
+    return I_s, I_l, I_t, residual
+
+
+def topk_count(n: int, sink: int, window: int, topk_abs: int, topk_frac: float) -> int:
+    """k = topk_abs if positive else floor(f_t * n)  (Algorithm 1's f_t n, rounded down)."""
+    if topk_abs > 0:
+        return int(topk_abs)
+    return int(math.floor(np.float64(np.float32(topk_frac)) * n))
+
+
+def base_count(n_s: int, base_abs: int, base_frac: float) -> int:
+    """b0' = min(max(b0, 2), n_s) with b0 = base_abs if positive else floor(f_b * n_s)."""
+    b0 = int(base_abs) if base_abs > 0 else int(math.floor(np.float64(np.float32(base_frac)) * n_s))
+    return min(max(b0, 2), int(n_s))
+
+
+def sample_stats(s: np.ndarray, V: Optional[np.ndarray], m: float, I_f: np.ndarray,
+                 I_bs: np.ndarray, n_s: int, need_num: bool) -> Dict[str, float]:
+    """get-stats / compute-stats of Algorithm 2.
+
+    D_f, N_f are exact sums over I_f.  From the base sample: mean and unbiased
+    variance of w (sigma^2), mean vector of r and the trace of its unbiased
+    covariance estimate (Tr Sigma).  D_hat = D_f + n_s * mean(w),
+    N_hat = N_f + n_s * mean(r).
+    """
+    w_f = np.exp(s[I_f] - m)
+    D_f = float(w_f.sum())
+    b0 = int(I_bs.shape[0])
+    w_b = np.exp(s[I_bs] - m)
+    w_bar = float(w_b.mean()) if b0 > 0 else 0.0
+    sigma2 = float(((w_b - w_bar) ** 2).sum() / (b0 - 1)) if b0 > 1 else 0.0
+    out = dict(D_f=D_f, w_bar=w_bar, sigma2=sigma2, D_hat=D_f + n_s * w_bar,
+               tr_sigma=0.0, N_hat_sq=0.0)
+    if need_num:
+        V64 = np.asarray(V, np.float64)
+        N_f = w_f @ V64[I_f]
+        r_b = w_b[:, None] * V64[I_bs]
+        r_bar = r_b.mean(axis=0) if b0 > 0 else np.zeros(V64.shape[1])
+        tr = float(((r_b - r_bar[None, :]) ** 2).sum() / (b0 - 1)) if b0 > 1 else 0.0
+        N_hat = N_f + n_s * r_bar
+        out.update(tr_sigma=tr, N_hat_sq=float(N_hat @ N_hat))
+    return out
+
+
+def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, target: int) -> float:
+    """b* of Algorithm 2.
+
+    Denominator (Corollary for D):  b* = (Phi^{-1}(1 - delta/2) * n_s * sigma / (eps * D))^2.
+    Numerator   (Corollary for N):  same with sqrt(Tr Sigma) and ||N||_2.
+    SDPA (Theorem 4.3): the minimisation over (eps', delta') is taken at
+    delta' = delta/2, where max(b_D(eps'/2), b_N((eps - eps')/2)) is smallest
+    when the two are equal: eps' = eps * rho_D / (rho_D + rho_N), giving
+    b* = (2 * Phi^{-1}(1 - delta/4) * (rho_D + rho_N) / eps)^2.  That choice is
+    a feasible point of the theorem's minimum, so its guarantee applies.
+    """
+    eps = float(np.float64(np.float32(epsilon)))
+    dlt = float(np.float64(np.float32(delta)))
+    rho_D = n_s * math.sqrt(stats["sigma2"]) / stats["D_hat"]
+    if target == TARGET_D:
+        return (upper_tail_quantile(dlt / 2.0) * rho_D / eps) ** 2
+    nn = math.sqrt(stats["N_hat_sq"])
+    num = n_s * math.sqrt(stats["tr_sigma"])
+    rho_N = (num / nn) if nn > 0.0 else (math.inf if num > 0.0 else 0.0)
+    if target == TARGET_N:
+        return (upper_tail_quantile(dlt / 2.0) * rho_N / eps) ** 2
+    if target == TARGET_SDPA:
+        return (2.0 * upper_tail_quantile(dlt / 4.0) * (rho_D + rho_N) / eps) ** 2
+    raise ValueError("unknown target")
+
+
+def clamp_budget(b_star: float, b0: int, n_s: int, cap_frac: float) -> int:
+    """b = min(n_s, max(b0', min(ceil(b*), ceil(cap_frac * n_s)))).
+
+    The budget is lower capped by the base sample size (as the paper does in
+    its experiments) and cannot exceed the residual count when sampling
+    without replacement.  cap_frac = 1 leaves it uncapped.
+    """
+    cap = int(math.ceil(np.float64(np.float32(cap_frac)) * n_s))
+    if not math.isfinite(b_star) or b_star >= n_s:
+        want = n_s
+    else:
+        want = int(math.ceil(b_star))
+    return int(min(n_s, max(b0, min(want, cap))))
+
+
+def estimate(s: np.ndarray, V: np.ndarray, m: float, I_f: np.ndarray, I_dyn: np.ndarray, n_s: int):
+    """N and D of Section 4.1 for given index sets: exact over I_f plus (n_s/b) * sampled sums.
+
+    Returns (N_hat, D_hat) in the e^{-m}-shifted scale.  With b = 0 the sampled
+    part is absent (Eq. 2).
+    """
+    V64 = np.asarray(V, np.float64)
+    w_f = np.exp(s[I_f] - m)
+    D = float(w_f.sum())
+    N = w_f @ V64[I_f]
+    b = int(I_dyn.shape[0])
+    if b > 0:
+        w_d = np.exp(s[I_dyn] - m)
+        scale = n_s / b
+        D = D + scale * float(w_d.sum())
+        N = N + scale * (w_d @ V64[I_dyn])
+    return N, D
+
+
+def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head: int,
+                params: Dict[str, float], s: Optional[np.ndarray] = None,
+                forced_topk: Optional[np.ndarray] = None,
+                forced_b: Optional[int] = None) -> Dict[str, object]:
+    """Algorithm 1 for one (sequence, query head).
+
+    q: [d], K, V: [n, d] (values already rounded to the storage precision).
+    `s` may carry precomputed scores of the same inputs.  forced_topk /
+    forced_b replace the top-k set / the budget by a caller-chosen legal
+    alternative (see topk_alternatives, budget_alternatives) and recompute
+    everything downstream; they are never taken from another implementation's
+    output.
+    """
+    n = K.shape[0]
+    sm_scale = float(params["sm_scale"])
+    target = int(params.get("target", TARGET_D))
+    if s is None:
+        s = scores(q, K, sm_scale)
+    m = float(s.max())
+    k = topk_count(n, int(params["sink"]), int(params["window"]),
+                   int(params.get("topk_abs", 0)), float(params.get("topk_frac", 0.0)))
+    I_s, I_l, I_t, residual = deterministic_set(s, int(params["sink"]), int(params["window"]), k)
+    if forced_topk is not None:
+        I_t = np.sort(np.asarray(forced_topk, dtype=np.int64))
+        mid = np.arange(I_s.shape[0], n - I_l.shape[0], dtype=np.int64)
+        member = np.zeros(n, dtype=bool)
+        member[I_t] = True
+        residual = mid[~member[mid]]
+    I_f = np.concatenate([I_s, I_l, I_t])
+    n_s = int(residual.shape[0])
+    res: Dict[str, object] = dict(n=n, m=m, I_s=I_s, I_l=I_l, I_t=I_t, n_s=n_s, scores=s)
+    if n_s == 0:
+        N, D = estimate(s, V, m, I_f, np.empty(0, np.int64), 0)
+        res.update(I_bs=np.empty(0, np.int64), I_dyn=np.empty(0, np.int64), b0=0, b=0,
+                   b_star=0.0, stats=dict(D_f=D, w_bar=0.0, sigma2=0.0, D_hat=D, tr_sigma=0.0, N_hat_sq=0.0),
+                   O=N / D, lse=m + math.log(D), D_out=D, N_out=N)
+        return res
+    b0 = base_count(n_s, int(params.get("base_abs", 0)), float(params.get("base_frac", 0.0)))
+    keys0 = token_keys(n, seed, head, 0)
+    I_bs = uniform_sample(residual, b0, keys0)
+    st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
+    b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target)
+    b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
+    if forced_b is not None:
+        b = int(forced_b)
+    keys1 = token_keys(n, seed, head, 1)
+    I_dyn = uniform_sample(residual, b, keys1)
+    N, D = estimate(s, V, m, I_f, I_dyn, n_s)
+    res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st,
+               O=N / D, lse=m + math.log(D), D_out=D, N_out=N)
+    return res
+
+
+# --------------------------------------------------------------------------
+# Legal alternatives where floating point decides an integer
+# --------------------------------------------------------------------------
+def topk_alternatives(s: np.ndarray, sink: int, window: int, k: int, rel_tol: float = 1e-5,
+                      limit: int = 256) -> List[np.ndarray]:
+    """All top-k sets that differ from the oracle's only by swaps among near-tied scores.
+
+    A score is "near-tied" with the k-th largest score tau when
+    |s_i - tau| <= rel_tol * max(|s_i|, |tau|).  Tokens clearly above tau are in
+    every legal set, tokens clearly below in none; the near-tied ones may be
+    chosen in any combination that fills the set to k.  The oracle's own
+    choice comes first.  Raises if there are more than `limit` combinations.
+    """
+    n = s.shape[0]
+    I_s, I_l, I_t, _ = deterministic_set(s, sink, window, k)
+    if I_t.shape[0] == 0:
+        return [I_t]
+    mid = np.arange(I_s.shape[0], n - I_l.shape[0], dtype=np.int64)
+    if I_t.shape[0] == mid.shape[0]:
+        return [I_t]
+    tau = s[I_t].min()
+    near = np.abs(s[mid] - tau) <= rel_tol * np.maximum(np.abs(s[mid]), abs(tau))
+    amb = mid[near]
+    sel = np.zeros(n, dtype=bool)
+    sel[I_t] = True
+    sure = I_t[~np.isin(I_t, amb)]
+    need = I_t.shape[0] - sure.shape[0]
+    # tokens above tau but outside the tolerance band are "sure"; ambiguous ones not selected lie below
+    if math.comb(amb.shape[0], need) > limit:
+        raise RuntimeError("too many near-tied top-k alternatives")
+    alts = [I_t]
+    for combo in combinations(amb.tolist(), need):
+        cand = np.sort(np.concatenate([sure, np.asarray(combo, dtype=np.int64)]))
+        if not np.array_equal(cand, I_t):
+            alts.append(cand)
+    return alts
+
+
+def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-4) -> List[int]:
+    """Budgets a correct fp32-statistics implementation may reach: b for b*(1 +- rel_tol)."""
+    outs = []
+    for f in (1.0, 1.0 - rel_tol, 1.0 + rel_tol):
+        v = clamp_budget(b_star * f, b0, n_s, cap_frac)
+        if v not in outs:
+            outs.append(v)
+    return outs
+
+
+# --------------------------------------------------------------------------
+# Whole-batch driver
+# --------------------------------------------------------------------------
+def decode(q: np.ndarray, K: np.ndarray, V: np.ndarray, seq_lens: np.ndarray, seeds: np.ndarray,
+           params: Dict[str, float], heads: Optional[Sequence] = None) -> Dict[tuple, Dict[str, object]]:
+    """One decode step for a batch: q [B, Hq, d], K, V [B, Hkv, n_max, d] (fp32/fp64 values).
+
+    Query head h reads KV head h // (Hq / Hkv).  Returns {(b, h): decode_head result}.
+    `heads` restricts the (b, h) pairs computed.
+    """
+    B, Hq, _ = q.shape
+    Hkv = K.shape[1]
+    g = Hq // Hkv
+    out = {}
+    pairs = heads if heads is not None else [(b, h) for b in range(B) for h in range(Hq)]
+    for (b, h) in pairs:
+        n = int(seq_lens[b])
+        out[(b, h)] = decode_head(q[b, h], K[b, h // g, :n], V[b, h // g, :n],
+                                  seed=int(seeds[b]), head=h, params=params)
+    return out

@@ -1,0 +1,466 @@
+"""Pins for the CPU oracle: each part is checked against something other than itself.
+
+Published known-answer vectors (Philox), textbook quantiles, library dense
+attention (Eq. 1), brute-force enumeration on tiny inputs, textbook
+simple-random-sampling moments, and hand-computed budgets on constructed
+populations (Corollaries for N and D, Theorem 4.3).
+"""
+import itertools
+import math
+import os
+import statistics
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import vatt_oracle as vo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _params(**over):
+    p = dict(sink=2, window=3, topk_abs=4, topk_frac=0.0, base_abs=4, base_frac=0.0,
+             epsilon=0.05, delta=0.05, target=vo.TARGET_D, sm_scale=1.0, budget_cap_frac=1.0)
+    p.update(over)
+    return p
+
+
+def _rand_head(rng, n, d, scale=1.0):
+    q = rng.standard_normal(d)
+    K = rng.standard_normal((n, d)) * scale
+    V = rng.standard_normal((n, d))
+    return q, K, V
+
+
+# ---------------------------------------------------------------- Philox ----
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        vals = [int(x, 16) for x in r]
+        out = vo.philox4x32_10([np.array([v], dtype=np.uint64) for v in vals[:4]], vals[4:6])
+        assert [int(o[0]) for o in out] == vals[6:10]
+
+
+def test_philox_is_a_bijection_on_a_small_slice():
+    # distinct counters under one key never collide (counter-mode bijection)
+    blk = np.arange(4096, dtype=np.uint64)
+    out = vo.philox4x32_10((blk, blk * 0, blk * 0, blk * 0), (123, 456))
+    packed = (out[0].astype(np.uint64) << np.uint64(32)) | out[1].astype(np.uint64)
+    packed2 = (out[2].astype(np.uint64) << np.uint64(32)) | out[3].astype(np.uint64)
+    assert len(set(zip(packed.tolist(), packed2.tolist()))) == 4096
+
+
+def test_token_keys_counter_layout():
+    seed = (0xDEADBEEF << 32) | 0x12345678
+    keys = vo.token_keys(23, seed, head=5, stream=1)
+    assert keys.dtype == np.uint32 and keys.shape == (23,)
+    for i in (0, 1, 3, 4, 7, 22):
+        blk = vo.philox4x32_10(
+            [np.array([c], dtype=np.uint64) for c in (i // 4, 1, 5, 0)], (0x12345678, 0xDEADBEEF))
+        assert int(keys[i]) == int(blk[i % 4][0])
+    # stream, head and seed each change the keys
+    assert not np.array_equal(keys, vo.token_keys(23, seed, 5, 0))
+    assert not np.array_equal(keys, vo.token_keys(23, seed, 6, 1))
+    assert not np.array_equal(keys, vo.token_keys(23, seed + 1, 5, 1))
+    assert not np.array_equal(keys, vo.token_keys(23, seed + (1 << 32), 5, 1))
+
+
+def test_token_keys_look_uniform():
+    keys = vo.token_keys(1 << 16, 99, 3, 0).astype(np.float64) / 2.0 ** 32
+    assert abs(keys.mean() - 0.5) < 4 * math.sqrt(1 / 12 / 65536)
+    hist, _ = np.histogram(keys, bins=64, range=(0, 1))
+    chi2 = ((hist - 1024.0) ** 2 / 1024.0).sum()
+    assert chi2 < 130.0  # chi2(63) 99.999 % point is ~ 121
+
+
+# ------------------------------------------------------- normal quantile ----
+def test_normal_quantile_textbook_values():
+    for line in open(os.path.join(GOLDEN, "normal_quantiles.txt")):
+        if line.startswith("#"):
+            continue
+        p, z = map(float, line.split())
+        assert abs(vo.normal_quantile(p) - z) < 1e-6
+
+
+def test_normal_quantile_against_libraries():
+    for p in [1e-6, 0.01, 0.2, 0.5, 0.8, 0.9, 0.95, 0.975, 0.9875, 0.999]:
+        z = vo.normal_quantile(p)
+        assert abs(z - scipy.special.ndtri(p)) < 1e-9 * max(1.0, abs(z))
+        assert abs(z - statistics.NormalDist().inv_cdf(p)) < 1e-7 * max(1.0, abs(z))
+    # the upper-tail form stays accurate where 1 - t is no longer representable
+    for t in [0.3, 0.025, 0.0125, 1e-4, 1e-9, 1e-15]:
+        z = vo.upper_tail_quantile(t)
+        assert abs(z + scipy.special.ndtri(t)) < 1e-11 * max(1.0, abs(z))
+    assert vo.normal_quantile(0.3) == pytest.approx(-vo.normal_quantile(0.7), abs=1e-12)
+
+
+# ------------------------------------------------------ dense attention -----
+def test_dense_sdpa_matches_library_softmax_attention():
+    rng = np.random.default_rng(0)
+    q, K, V = _rand_head(rng, 257, 16)
+    scale = 0.25
+    O, lse = vo.dense_sdpa(q, K, V, scale)
+    a = scipy.special.softmax(scale * (K @ q))
+    assert np.allclose(O, a @ V, rtol=1e-12, atol=1e-14)
+    assert lse == pytest.approx(scipy.special.logsumexp(scale * (K @ q)), rel=1e-13)
+    tO = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None, None, None, :], torch.from_numpy(K)[None, None],
+        torch.from_numpy(V)[None, None], scale=scale)
+    assert np.allclose(O, tO.numpy().reshape(-1), rtol=1e-10, atol=1e-13)
+
+
+def test_scores_operand_order_and_scale():
+    # asymmetric shapes: a transposed operand or a dropped scale cannot pass
+    K = np.array([[1.0, 2.0, 3.0], [0.0, -1.0, 0.5]])
+    q = np.array([2.0, 0.5, -1.0])
+    assert np.allclose(vo.scores(q, K, 0.5), [0.5 * (2 + 1 - 3), 0.5 * (0 - 0.5 - 0.5)])
+
+
+# --------------------------------------------------- deterministic set ------
+def test_deterministic_set_vs_sort_and_bruteforce():
+    rng = np.random.default_rng(1)
+    for n, sink, window, k in [(64, 4, 8, 5), (50, 0, 0, 7), (40, 3, 0, 0), (33, 5, 6, 100), (10, 8, 8, 3), (6, 0, 9, 2)]:
+        s = rng.standard_normal(n)
+        I_s, I_l, I_t, R = vo.deterministic_set(s, sink, window, k)
+        ns_ = min(sink, n)
+        nl_ = min(window, n - ns_)
+        assert I_s.tolist() == list(range(ns_))
+        assert I_l.tolist() == list(range(n - nl_, n))
+        mid = list(range(ns_, n - nl_))
+        kk = min(k, len(mid))
+        brute = sorted(sorted(mid, key=lambda i: (-s[i], i))[:kk])
+        assert I_t.tolist() == brute
+        if kk:
+            arg = np.argsort(-s[ns_:n - nl_], kind="stable")[:kk] + ns_
+            assert sorted(arg.tolist()) == brute
+        assert sorted(I_s.tolist() + I_l.tolist() + I_t.tolist() + R.tolist()) == list(range(n))
+        if len(R) and kk:
+            assert s[R].max() <= s[I_t].min()
+
+
+def test_topk_ties_go_to_lower_index():
+    s = np.array([9.0, 1.0, 5.0, 5.0, 5.0, 0.0, 5.0, 9.0])
+    _, _, I_t, R = vo.deterministic_set(s, 1, 1, 2)
+    assert I_t.tolist() == [2, 3]
+    assert R.tolist() == [1, 4, 5, 6]
+
+
+def test_topk_and_base_counts():
+    assert vo.topk_count(32768, 128, 128, 0, 0.025) == 819
+    assert vo.topk_count(131072, 128, 512, 0, 0.01) == 1310
+    assert vo.topk_count(1024, 4, 32, 32, 0.5) == 32
+    assert vo.base_count(31693, 0, 0.025) == 792
+    assert vo.base_count(100, 0, 0.0) == 2      # f_b = 0 still leaves two tokens for a variance
+    assert vo.base_count(1, 0, 0.5) == 1
+    assert vo.base_count(10, 64, 0.0) == 10
+
+
+# ------------------------------------------------------------- sampler ------
+def test_uniform_sample_invariants():
+    n = 500
+    residual = np.setdiff1d(np.arange(10, 480), np.arange(50, 400, 7))
+    keys = vo.token_keys(n, 42, 2, 0)
+    prev = np.empty(0, dtype=np.int64)
+    for c in [0, 1, 2, 17, 100, len(residual)]:
+        smp = vo.uniform_sample(residual, c, keys)
+        assert smp.shape[0] == c
+        assert np.all(np.diff(smp) > 0)                  # ascending, no duplicates
+        assert np.all(np.isin(smp, residual))            # only residual tokens
+        assert np.all(np.isin(prev, smp))                # prefix property: sample(c) in sample(c+1)
+        prev = smp
+    # the sample is the c smallest keys: every chosen key <= every unchosen key
+    smp = vo.uniform_sample(residual, 60, keys)
+    rest = np.setdiff1d(residual, smp)
+    assert keys[smp].max() <= keys[rest].min()
+    assert np.array_equal(smp, vo.uniform_sample(residual, 60, vo.token_keys(n, 42, 2, 0)))
+
+
+def test_uniform_sample_is_uniform_over_subsets():
+    # n_s = 5, c = 2: each of the 10 subsets should appear with probability 1/10
+    residual = np.array([2, 3, 5, 6, 7])
+    counts = {}
+    trials = 20000
+    for seed in range(trials):
+        smp = tuple(vo.uniform_sample(residual, 2, vo.token_keys(9, seed, 0, 1)).tolist())
+        counts[smp] = counts.get(smp, 0) + 1
+    assert len(counts) == 10
+    chi2 = sum((c - trials / 10) ** 2 / (trials / 10) for c in counts.values())
+    assert chi2 < 33.7  # chi2(9) 99.99 % point
+
+
+def test_uniform_sample_inclusion_frequency():
+    residual = np.arange(8, 72)
+    c, trials = 16, 6000
+    hits = np.zeros(80)
+    for seed in range(trials):
+        hits[vo.uniform_sample(residual, c, vo.token_keys(80, 1000 + seed, 4, 0))] += 1
+    p = c / len(residual)
+    z = (hits[residual] - trials * p) / math.sqrt(trials * p * (1 - p))
+    assert np.abs(z).max() < 4.5
+    assert hits[:8].sum() == 0 and hits[72:].sum() == 0
+
+
+# ------------------------------------------------- estimator, brute force ---
+def test_estimator_mean_over_all_subsets_is_exact():
+    rng = np.random.default_rng(3)
+    n, d = 20, 3
+    q, K, V = _rand_head(rng, n, d)
+    s = vo.scores(q, K, 0.7)
+    m = s.max()
+    I_s, I_l, I_t, R = vo.deterministic_set(s, 2, 3, 4)
+    I_f = np.concatenate([I_s, I_l, I_t])
+    n_s = len(R)
+    assert n_s == 11
+    w = np.exp(s - m)
+    D_true = w.sum()
+    N_true = w @ V
+    for b in (1, 3, 5, n_s):
+        Ds, Ns = [], []
+        for combo in itertools.combinations(R.tolist(), b):
+            N, D = vo.estimate(s, V, m, I_f, np.array(combo), n_s)
+            Ds.append(D)
+            Ns.append(N)
+        assert np.mean(Ds) == pytest.approx(D_true, rel=1e-12)
+        assert np.allclose(np.mean(Ns, axis=0), N_true, rtol=1e-11, atol=1e-13)
+        # textbook variance of the expansion estimator under sampling without replacement
+        S2 = w[R].var(ddof=1)
+        assert np.var(Ds) == pytest.approx(n_s ** 2 * (1 - b / n_s) * S2 / b, rel=1e-9, abs=1e-18)
+
+
+def test_estimate_with_empty_sample_is_softmax_over_I_f():
+    rng = np.random.default_rng(4)
+    q, K, V = _rand_head(rng, 30, 4)
+    s = vo.scores(q, K, 1.0)
+    I_f = np.array([0, 1, 7, 28, 29])
+    N, D = vo.estimate(s, V, s.max(), I_f, np.empty(0, np.int64), 25)
+    a = scipy.special.softmax(s[I_f])
+    assert np.allclose(N / D, a @ V[I_f], rtol=1e-12)
+
+
+# ------------------------------------------------- whole step, check (a) ----
+@pytest.mark.parametrize("target", [vo.TARGET_D, vo.TARGET_N, vo.TARGET_SDPA])
+def test_full_budget_equals_dense(target):
+    rng = np.random.default_rng(5)
+    n, d = 300, 8
+    q, K, V = _rand_head(rng, n, d)
+    V = V + 1.0
+    # a base sample that already covers the residual forces b = n_s
+    r = vo.decode_head(q, K, V, seed=11, head=0,
+                       params=_params(sink=5, window=9, topk_abs=20, base_abs=10 ** 6, target=target, sm_scale=0.4))
+    O, lse = vo.dense_sdpa(q, K, V, 0.4)
+    assert r["b"] == r["n_s"] == n - 34
+    assert np.allclose(r["O"], O, rtol=1e-12, atol=1e-14)
+    assert r["lse"] == pytest.approx(lse, rel=1e-13)
+    # a tiny epsilon reaches the same through the budget formula
+    r2 = vo.decode_head(q, K, V, seed=11, head=0,
+                        params=_params(sink=5, window=9, topk_abs=20, base_abs=8, epsilon=1e-7, target=target, sm_scale=0.4))
+    assert r2["b"] == r2["n_s"]
+    assert np.allclose(r2["O"], O, rtol=1e-12, atol=1e-14)
+
+
+def test_no_residual_is_exact_softmax():
+    rng = np.random.default_rng(6)
+    q, K, V = _rand_head(rng, 12, 4)
+    for p in (_params(sink=8, window=8), _params(sink=2, window=3, topk_abs=50)):
+        r = vo.decode_head(q, K, V, seed=1, head=0, params=p)
+        O, lse = vo.dense_sdpa(q, K, V, 1.0)
+        assert r["n_s"] == 0 and r["b"] == 0
+        assert np.allclose(r["O"], O, rtol=1e-13)
+        assert r["lse"] == pytest.approx(lse, rel=1e-14)
+
+
+def test_output_is_importance_weighted_softmax_of_eq3():
+    # Eq. 3 written out: weights exp(s_i)/p_i over S = [I_f, I_dyn], p = [1, b/n_s]
+    rng = np.random.default_rng(7)
+    q, K, V = _rand_head(rng, 200, 6)
+    r = vo.decode_head(q, K, V, seed=3, head=1, params=_params(sink=4, window=6, topk_abs=10, base_abs=12, sm_scale=0.5))
+    s = 0.5 * (K @ q)
+    I_f = np.concatenate([r["I_s"], r["I_l"], r["I_t"]])
+    S = np.concatenate([I_f, r["I_dyn"]])
+    p = np.concatenate([np.ones(len(I_f)), np.full(r["b"], r["b"] / r["n_s"])])
+    a = np.exp(s[S]) / p
+    a = a / a.sum()
+    assert np.allclose(r["O"], a @ V[S], rtol=1e-11)
+    assert r["lse"] == pytest.approx(math.log((np.exp(s[S]) / p).sum()), rel=1e-12)
+    assert len(np.intersect1d(I_f, r["I_dyn"])) == 0
+    assert len(np.intersect1d(I_f, r["I_bs"])) == 0
+
+
+# ------------------------------------------------------ budget formulas -----
+def _scalar_head(s_values, v_values=None):
+    """A head whose scores are exactly s_values: d = 1, q = [1], K[i] = [s_i]."""
+    s_values = np.asarray(s_values, dtype=np.float64)
+    K = s_values[:, None]
+    V = np.ones_like(K) if v_values is None else np.asarray(v_values, np.float64)[:, None]
+    return np.array([1.0]), K, V
+
+
+def test_constant_residual_needs_no_samples():
+    s = np.concatenate([[3.0, 2.0], np.full(40, -1.0), [0.5, 0.7]])
+    q, K, V = _scalar_head(s)
+    r = vo.decode_head(q, K, V, seed=0, head=0, params=_params(sink=2, window=2, topk_abs=0, base_abs=6))
+    assert r["stats"]["sigma2"] == pytest.approx(0.0, abs=1e-30)
+    assert r["b_star"] == pytest.approx(0.0, abs=1e-20)
+    assert r["b"] == r["b0"] == 6
+    # and the estimate is then exact whatever the sample
+    O, _ = vo.dense_sdpa(q, K, V, 1.0)
+    assert np.allclose(r["O"], O, rtol=1e-13)
+
+
+def test_two_valued_residual_budget_by_hand_target_D():
+    # residual: a tokens with weight alpha, c tokens with weight beta; base sample = whole residual,
+    # so sigma is the population value and D_hat = D exactly.
+    a, c = 30, 70
+    sa, sb = math.log(0.5), math.log(0.1)          # weights relative to the max score 0
+    s = np.concatenate([[0.0], np.full(a, sa), np.full(c, sb), [math.log(0.25)]])
+    q, K, V = _scalar_head(s)
+    eps, dlt = 0.05, 0.1
+    r = vo.decode_head(q, K, V, seed=9, head=0,
+                       params=_params(sink=1, window=1, topk_abs=0, base_abs=1000, epsilon=eps, delta=dlt))
+    n_s = a + c
+    mean = (a * 0.5 + c * 0.1) / n_s
+    S2 = (a * (0.5 - mean) ** 2 + c * (0.1 - mean) ** 2) / (n_s - 1)
+    D = 1.0 + 0.25 + a * 0.5 + c * 0.1
+    # the interface carries delta as a 32-bit float: 0.1 is stored as 0.100000001490116
+    z = scipy.special.ndtri(1.0 - np.float64(np.float32(dlt)) / 2.0)
+    assert z == pytest.approx(1.6448536269514722, rel=1e-8)  # Phi^{-1}(0.95)
+    hand = (z * n_s * math.sqrt(S2) / (np.float64(np.float32(eps)) * D)) ** 2
+    assert r["n_s"] == n_s and r["b0"] == n_s
+    assert r["stats"]["sigma2"] == pytest.approx(S2, rel=1e-12)
+    assert r["stats"]["D_hat"] == pytest.approx(D, rel=1e-12)
+    assert r["b_star"] == pytest.approx(hand, rel=1e-9)
+    assert r["b"] == n_s  # lower cap by the base sample
+
+
+def test_two_valued_residual_budget_by_hand_target_N_and_SDPA():
+    a, c = 25, 55
+    s = np.concatenate([[0.0], np.full(a, math.log(0.5)), np.full(c, math.log(0.2)), [math.log(0.25)]])
+    v = np.concatenate([[2.0], np.full(a, 1.0), np.full(c, 3.0), [-1.0]])
+    q, K, V = _scalar_head(s, v)
+    eps, dlt = 0.1, 0.2
+    n_s = a + c
+    # r_i = w_i v_i: 0.5 and 0.6
+    rm = (a * 0.5 + c * 0.6) / n_s
+    tr = (a * (0.5 - rm) ** 2 + c * (0.6 - rm) ** 2) / (n_s - 1)
+    N = 1.0 * 2.0 + 0.25 * -1.0 + a * 0.5 + c * 0.6
+    wm = (a * 0.5 + c * 0.2) / n_s
+    S2 = (a * (0.5 - wm) ** 2 + c * (0.2 - wm) ** 2) / (n_s - 1)
+    D = 1.0 + 0.25 + a * 0.5 + c * 0.2
+    e = float(np.float64(np.float32(eps)))
+    dl = float(np.float64(np.float32(dlt)))
+    rN = vo.decode_head(q, K, V, seed=9, head=0,
+                        params=_params(sink=1, window=1, topk_abs=0, base_abs=1000, epsilon=eps, delta=dlt, target=vo.TARGET_N))
+    z = scipy.special.ndtri(1 - dl / 2)
+    assert rN["stats"]["tr_sigma"] == pytest.approx(tr, rel=1e-12)
+    assert rN["stats"]["N_hat_sq"] == pytest.approx(N * N, rel=1e-12)
+    assert rN["b_star"] == pytest.approx((z * n_s * math.sqrt(tr) / (e * abs(N))) ** 2, rel=1e-9)
+    rS = vo.decode_head(q, K, V, seed=9, head=0,
+                        params=_params(sink=1, window=1, topk_abs=0, base_abs=1000, epsilon=eps, delta=dlt, target=vo.TARGET_SDPA))
+    rho_D = n_s * math.sqrt(S2) / D
+    rho_N = n_s * math.sqrt(tr) / abs(N)
+    z4 = scipy.special.ndtri(1 - dl / 4)
+    assert rS["b_star"] == pytest.approx((2 * z4 * (rho_D + rho_N) / e) ** 2, rel=1e-9)
+
+    # Theorem 4.3: b_SDPA is min over (eps', delta') of max(b_D(eps'/2, delta'), b_N((eps-eps')/2, delta-delta')).
+    # The closed form is that expression at delta' = delta/2 minimised over eps'; a grid search of the
+    # theorem's expression at delta' = delta/2 must agree, and no grid point with another delta' is
+    # required to be worse -- only the closed form must be a feasible value (>= the global minimum).
+    def bD(e_, d_):
+        return (scipy.special.ndtri(1 - d_ / 2) * rho_D / e_) ** 2
+
+    def bN(e_, d_):
+        return (scipy.special.ndtri(1 - d_ / 2) * rho_N / e_) ** 2
+
+    grid_e = np.linspace(1e-4, e - 1e-4, 20001)
+    at_half = min(max(bD(x / 2, dl / 2), bN((e - x) / 2, dl / 2)) for x in grid_e)
+    assert rS["b_star"] == pytest.approx(at_half, rel=1e-4)
+    glob = min(max(bD(x / 2, y), bN((e - x) / 2, dl - y))
+               for x in np.linspace(1e-3, e - 1e-3, 400) for y in np.linspace(1e-3, dl - 1e-3, 100))
+    assert rS["b_star"] >= glob * (1 - 1e-9)
+
+
+def test_budget_scales_as_the_formula_says():
+    # b* ~ (z/eps)^2: halving eps quadruples b*, and delta enters only through the quantile
+    rng = np.random.default_rng(8)
+    q, K, V = _rand_head(rng, 400, 8, scale=0.5)
+    base = _params(sink=4, window=4, topk_abs=10, base_abs=50, epsilon=0.1, delta=0.1, sm_scale=0.35)
+    r1 = vo.decode_head(q, K, V, seed=2, head=0, params=base)
+    r2 = vo.decode_head(q, K, V, seed=2, head=0, params=dict(base, epsilon=0.05))
+    r3 = vo.decode_head(q, K, V, seed=2, head=0, params=dict(base, delta=0.02))
+    e1, e2 = np.float64(np.float32(0.1)), np.float64(np.float32(0.05))
+    assert r2["b_star"] / r1["b_star"] == pytest.approx((e1 / e2) ** 2, rel=1e-12)
+    zq = lambda d_: scipy.special.ndtri(1 - np.float64(np.float32(d_)) / 2)
+    assert r3["b_star"] / r1["b_star"] == pytest.approx((zq(0.02) / zq(0.1)) ** 2, rel=1e-9)
+    # the statistics are those of the base sample, recomputed here from their definitions
+    s = 0.35 * (K @ q)
+    w = np.exp(s - s.max())
+    I_f = np.concatenate([r1["I_s"], r1["I_l"], r1["I_t"]])
+    assert r1["stats"]["sigma2"] == pytest.approx(np.var(w[r1["I_bs"]], ddof=1), rel=1e-12)
+    assert r1["stats"]["D_hat"] == pytest.approx(w[I_f].sum() + r1["n_s"] * w[r1["I_bs"]].mean(), rel=1e-12)
+    rN = vo.decode_head(q, K, V, seed=2, head=0, params=dict(base, target=vo.TARGET_N))
+    rr = w[rN["I_bs"], None] * V[rN["I_bs"]]
+    assert rN["stats"]["tr_sigma"] == pytest.approx(np.trace(np.cov(rr.T, ddof=1)), rel=1e-11)
+    Nh = w[I_f] @ V[I_f] + rN["n_s"] * rr.mean(axis=0)
+    assert rN["stats"]["N_hat_sq"] == pytest.approx(Nh @ Nh, rel=1e-11)
+
+
+def test_shift_invariance():
+    # appending a constant coordinate to K and q adds the same constant to every score:
+    # selections, budget and output must not move
+    rng = np.random.default_rng(9)
+    q, K, V = _rand_head(rng, 300, 8, scale=0.6)
+    p = _params(sink=4, window=8, topk_abs=12, base_abs=30, epsilon=0.02, sm_scale=0.5)
+    r1 = vo.decode_head(q, K, V, seed=5, head=2, params=p)
+    q2 = np.concatenate([q, [2.0]])
+    K2 = np.concatenate([K, np.full((300, 1), 7.0)], axis=1)
+    r2 = vo.decode_head(q2, K2, V, seed=5, head=2, params=p)
+    for key in ("I_t", "I_bs", "I_dyn"):
+        assert np.array_equal(r1[key], r2[key])
+    assert r1["b"] == r2["b"] and r1["b_star"] == pytest.approx(r2["b_star"], rel=1e-9)
+    assert np.allclose(r1["O"], r2["O"], rtol=1e-10)
+    assert r2["lse"] - r1["lse"] == pytest.approx(0.5 * 14.0, rel=1e-10)
+
+
+def test_clamp_budget_cases():
+    assert vo.clamp_budget(0.0, 32, 1000, 1.0) == 32          # lower cap
+    assert vo.clamp_budget(100.2, 32, 1000, 1.0) == 101        # ceil
+    assert vo.clamp_budget(100.0, 32, 1000, 1.0) == 100        # exact integer stays
+    assert vo.clamp_budget(5000.0, 32, 1000, 1.0) == 1000      # cannot exceed the residual
+    assert vo.clamp_budget(float("inf"), 32, 1000, 1.0) == 1000
+    assert vo.clamp_budget(float("nan"), 32, 1000, 1.0) == 1000
+    assert vo.clamp_budget(800.0, 32, 1000, 0.5) == 500        # explicit cap
+    assert vo.clamp_budget(800.0, 600, 1000, 0.5) == 600       # lower cap wins over the explicit cap
+    assert vo.clamp_budget(3.0, 2, 2, 1.0) == 2
+
+
+def test_alternatives_enumerate_near_ties():
+    s = np.array([5.0, 4.0, 3.0, 3.0 + 1e-7, 2.0, 1.0, 0.0])
+    alts = vo.topk_alternatives(s, 0, 0, 3, rel_tol=1e-5)
+    assert [a.tolist() for a in alts] == [[0, 1, 3], [0, 1, 2]]
+    assert len(vo.topk_alternatives(s, 0, 0, 2, rel_tol=1e-5)) == 1
+    assert vo.budget_alternatives(100.000001, 10, 1000, 1.0) == [101, 100]
+    assert vo.budget_alternatives(100.5, 10, 1000, 1.0) == [101]
+    r = vo.decode_head(*_scalar_head(s), seed=1, head=0,
+                       params=_params(sink=0, window=0, topk_abs=3, base_abs=2), forced_topk=alts[1])
+    assert r["I_t"].tolist() == [0, 1, 2] and 3 not in r["I_t"] and r["n_s"] == 4
+
+
+def test_decode_batch_maps_gqa_heads():
+    rng = np.random.default_rng(10)
+    B, Hq, Hkv, n, d = 2, 4, 2, 64, 8
+    q = rng.standard_normal((B, Hq, d))
+    K = rng.standard_normal((B, Hkv, n, d))
+    V = rng.standard_normal((B, Hkv, n, d))
+    lens = np.array([64, 40])
+    seeds = np.array([7, 8], dtype=np.uint64)
+    p = _params(sink=2, window=2, topk_abs=4, base_abs=6, sm_scale=0.3)
+    out = vo.decode(q, K, V, lens, seeds, p)
+    assert set(out) == {(b, h) for b in range(B) for h in range(Hq)}
+    one = vo.decode_head(q[1, 3], K[1, 1, :40], V[1, 1, :40], seed=8, head=3, params=p)
+    assert np.array_equal(out[(1, 3)]["I_dyn"], one["I_dyn"])
+    assert np.allclose(out[(1, 3)]["O"], one["O"])
+    # heads of one group share K but not their samples
+    assert not np.array_equal(out[(0, 0)]["I_bs"], out[(0, 1)]["I_bs"])
