@@ -1,0 +1,192 @@
+/*
+ * vatt.h -- C ABI of libvatt: the decode step of verified sparse attention
+ * (vAttention, arXiv 2510.05688) on one AMD MI355X (gfx950).
+ *
+ * One call of vatt_decode is one layer's attention for one decode step of a
+ * batch: for every (sequence, query head) it runs Algorithm 1 of the paper
+ * with Algorithm 2 inlined:
+ *
+ *   score     s_i = sm_scale * <K[i], q>                       (exponent of Eq. 1)
+ *   I_f       sink tokens + local window + exact top-k of the tokens in
+ *             between                                          (Alg. 1, lines 1-5)
+ *   I_bs      base sample of the residual tokens               (Alg. 2, line 1)
+ *   stats     sigma^2, D (and Tr Sigma, ||N||) from I_f, I_bs  (Alg. 2, get-stats)
+ *   b         CLT budget for the verified quantity X           (Corollaries for N and D,
+ *                                                               Theorem 4.3)
+ *   I_dyn     b residual tokens, uniform without replacement   (Alg. 1, line 7)
+ *   O         N/D with N = N_f + (n_s/b) sum_{I_dyn} w_i V[i],
+ *             D = D_f + (n_s/b) sum_{I_dyn} w_i                 (Section 4.1; Eq. 3)
+ *
+ * Conventions
+ *   - Every function returns VATT_OK (0) or a negative VATT_E_* code.  Argument
+ *     errors are found on the host before anything is launched.
+ *   - "device" pointers are HIP device memory of the plan's device, owned by
+ *     the caller; "host" pointers are ordinary process memory.  The library
+ *     owns only the opaque plan (host memory).
+ *   - vatt_decode, vatt_dense_decode, vatt_append_kv only enqueue kernels on
+ *     the given HIP stream: no allocation, no synchronisation, no host read of
+ *     device data.  A plan and its workspace may be used by one stream at a
+ *     time.
+ *   - bf16 tensors are raw 16-bit patterns (upper half of an IEEE binary32).
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - Everything after the score pass is per query head: each query head has
+ *     its own top-k set, samples and budget (the paper's guarantee is per head).
+ *
+ * KV layouts
+ *   contiguous: K, V are [batch, n_kv_heads, n_max, head_dim]
+ *   paged:      K, V are [num_blocks, n_kv_heads, page_size, head_dim];
+ *               block_table is int32 [batch, ceil(n_max / page_size)] and maps
+ *               logical page p of sequence b to a physical block.  Entries
+ *               outside [0, num_blocks) are clamped into range by the kernels
+ *               (the result for that sequence is then meaningless, but no
+ *               access leaves the allocation).
+ *
+ * Sampler
+ *   Token i of (sequence, query head h) gets the 32-bit key
+ *       u_i = Philox4x32-10(counter = (i >> 2, stream, h, 0),
+ *                           key = (seed & 0xffffffff, seed >> 32))[i & 3]
+ *   with the sequence's seed for this call, stream 0 for the base sample and 1
+ *   for the final sample.  A sample of size c is the c residual tokens with the
+ *   smallest (u_i, i); it is a uniform c-subset, independent of scheduling, and
+ *   reproducible from (seed, sequence, head).
+ */
+#ifndef VATT_H_
+#define VATT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  VATT_OK = 0,
+  VATT_E_INVALID_ARG = -1,       /* NULL pointer, non-positive size, epsilon/delta outside (0,1), ... */
+  VATT_E_UNSUPPORTED_SHAPE = -2, /* head_dim not in {64,128}, group size not in {1,2,4,8}, ...        */
+  VATT_E_WORKSPACE_TOO_SMALL = -3,
+  VATT_E_HIP = -4,               /* a HIP runtime call failed (launch error, wrong device, ...)       */
+  VATT_E_NO_DEVICE = -5          /* no HIP device / the HIP runtime is unusable                        */
+};
+
+enum { VATT_TARGET_D = 0, VATT_TARGET_N = 1, VATT_TARGET_SDPA = 2 };
+enum { VATT_LAYOUT_CONTIGUOUS = 0, VATT_LAYOUT_PAGED = 1 };
+
+/* Parameters of Algorithm 1 (its "Require" line) plus shapes.  Plain data, copied by vatt_plan_create. */
+typedef struct vatt_params {
+  int32_t batch;         /* B: sequences per call                                                    */
+  int32_t n_q_heads;     /* Hq                                                                        */
+  int32_t n_kv_heads;    /* Hkv; Hq % Hkv == 0 and Hq / Hkv in {1,2,4,8}                              */
+  int32_t head_dim;      /* d in {64, 128}                                                            */
+  int32_t n_max;         /* capacity in tokens per sequence; sizes workspace and index buffers        */
+  int32_t kv_layout;     /* VATT_LAYOUT_*                                                             */
+  int32_t page_size;     /* tokens per block when paged (power of two, 8..256); ignored otherwise     */
+  int32_t num_blocks;    /* physical blocks in the paged cache; ignored when contiguous               */
+  int32_t sink;          /* |I_s|: absolute token count (the paper's experiments use 128)             */
+  int32_t window;        /* |I_l|: absolute token count                                               */
+  int32_t topk_abs;      /* k = topk_abs if > 0 else floor(topk_frac * n)            (f_t of Alg. 1)  */
+  float   topk_frac;
+  int32_t base_abs;      /* b0 = base_abs if > 0 else floor(base_frac * n_s), then clamped to [2,n_s] */
+  float   base_frac;     /*                                                         (f_b of Alg. 2)  */
+  float   epsilon;       /* in (0,1)                                                                  */
+  float   delta;         /* in (0,1)                                                                  */
+  int32_t target;        /* VATT_TARGET_*: which quantity is kept (epsilon, delta)-verified           */
+  float   sm_scale;      /* softmax scale; 0 means 1/sqrt(head_dim)                                   */
+  float   budget_cap_frac; /* b <= ceil(cap * n_s); 1 = uncapped (the paper); must be in (0,1]        */
+} vatt_params;
+
+typedef struct vatt_plan vatt_plan;
+
+/* Regions of the workspace that tests and tools may want to read (see vatt_plan_workspace_offset). */
+enum {
+  VATT_WS_SCORES = 0 /* float [B, Hq, n_max_padded]: s_i of the last vatt_decode call */
+};
+
+/*
+ * Host only.  Validates the parameters, fixes launch geometry for the given device and computes the
+ * workspace layout.  `device` is a HIP device ordinal; pass -1 to plan for a 256-CU gfx950 without
+ * touching the HIP runtime (the plan can then be queried but not used to launch).
+ * On success *out owns a plan to be released with vatt_plan_destroy.
+ */
+int vatt_plan_create(const vatt_params* params, int device, vatt_plan** out);
+void vatt_plan_destroy(vatt_plan* plan);
+
+/*
+ * Options (host only).  VATT_OPT_EXACT_SAMPLER_ONLY = 1 makes the sampler skip its fast path (a verified
+ * guess of the key threshold) and always run the slower exact radix descent; results are identical.
+ * It exists so that the slow path can be exercised on purpose.
+ */
+enum { VATT_OPT_EXACT_SAMPLER_ONLY = 1 };
+int vatt_plan_set_option(vatt_plan* plan, int option, int value);
+
+/* Bytes of device workspace every launching call needs (256-byte aligned base). */
+size_t vatt_plan_workspace_bytes(const vatt_plan* plan);
+/* Byte offset of a VATT_WS_* region inside the workspace, or (size_t)-1 for an unknown region. */
+size_t vatt_plan_workspace_offset(const vatt_plan* plan, int region);
+/* Row stride, in floats, of the VATT_WS_SCORES region (n_max rounded up). */
+size_t vatt_plan_score_stride(const vatt_plan* plan);
+
+/*
+ * Layout of out_idx: per (sequence, query head) `vatt_plan_index_capacity` int32 slots holding five
+ * segments at fixed offsets, each filled from its start in ascending token order:
+ *   segment 0 sink, 1 window, 2 top-k, 3 base sample, 4 final sample.
+ * vatt_plan_index_segment returns the offset (in ints) of a segment, or -1.
+ */
+size_t vatt_plan_index_capacity(const vatt_plan* plan);
+int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment);
+
+/*
+ * One vAttention decode step (Algorithm 1) for the whole batch.
+ *   q            device, bf16 [B, Hq, d]
+ *   k, v         device, bf16 cache in the plan's layout
+ *   block_table  device, int32 [B, ceil(n_max / page_size)]; NULL when contiguous
+ *   seq_lens     device, int32 [B]; tokens valid in each sequence, 1 <= n <= n_max
+ *                (values outside are clamped by the kernels)
+ *   seq_seeds    device, uint64 [B]; sampler seed of each sequence for this call
+ *   workspace    device, 256-byte aligned; contents are scratch
+ *   workspace_bytes  size of that buffer; less than vatt_plan_workspace_bytes is VATT_E_WORKSPACE_TOO_SMALL
+ *   out_o        device, float [B, Hq, d]
+ *   out_lse      device, float [B, Hq] or NULL: ln of the estimated denominator, ln(D), of Section 4.1
+ *   out_idx      device, int32 [B, Hq, index_capacity]
+ *   out_counts   device, int32 [B, Hq, 8] = { |I_s|, |I_l|, |I_t|, |I_bs|, b, n_s, n, flags }
+ *                flags bit 0: the final sample needed the slow exact path (informational)
+ *   out_budget_raw device, double [B, Hq] or NULL: b* before rounding and clamping
+ *   out_stats    device, float [B, Hq, 4] or NULL = { D_hat, sigma^2, Tr Sigma, ||N_hat||^2 }, all in the
+ *                scale where the largest score of the head has weight 1 (w_i = exp(s_i - max s))
+ *   stream       hipStream_t
+ */
+int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v,
+                const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                void* workspace, size_t workspace_bytes, float* out_o, float* out_lse, int32_t* out_idx,
+                int32_t* out_counts, double* out_budget_raw, float* out_stats, void* stream);
+
+/*
+ * Dense decode attention (Eq. 1) on the same cache: the sparsity speed-up denominator.
+ * Arguments as in vatt_decode.  out_lse may be NULL.
+ */
+int vatt_dense_decode(vatt_plan* plan, const void* q, const void* k, const void* v,
+                      const int32_t* block_table, const int32_t* seq_lens, void* workspace,
+                      size_t workspace_bytes, float* out_o, float* out_lse, void* stream);
+
+/*
+ * Score pass alone (first step of Algorithm 1 with oracle top-k): fills the VATT_WS_SCORES region of the
+ * workspace with s_i for every (sequence, query head, i < n).  Exposed for stage-wise parity checks and
+ * for timing the K scan on its own.
+ */
+int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* block_table,
+               const int32_t* seq_lens, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Append one token per sequence: writes k_new, v_new (device, bf16 [B, Hkv, d]) at position seq_lens[b]
+ * of the cache and then increments seq_lens[b] (device, int32 [B]).  A sequence already at n_max is
+ * left unchanged.
+ */
+int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
+                   const int32_t* block_table, int32_t* seq_lens, void* stream);
+
+const char* vatt_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VATT_H_ */

@@ -1,0 +1,312 @@
+// C ABI of libvatt: parameter validation, plan geometry, workspace layout and the launch sequences.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "vatt_internal.h"
+
+namespace vatt {
+
+size_t head_kernel_lds_bytes(int n_max);
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// z with 1 - Phi(z) = t: safeguarded Newton on f(z) = erfc(z / sqrt 2) / 2 - t, f'(z) = -phi(z).
+double upper_tail_quantile(double t) {
+  double lo = -40.0, hi = 40.0, z = 0.0;
+  for (int it = 0; it < 200; ++it) {
+    const double f = 0.5 * std::erfc(z * M_SQRT1_2) - t;
+    if (f > 0.0) lo = z; else hi = z;
+    const double pdf = std::exp(-0.5 * z * z) * 0.3989422804014326779;
+    double zn = (pdf > 1e-300) ? z + f / pdf : 0.5 * (lo + hi);
+    if (!(zn > lo && zn < hi)) zn = 0.5 * (lo + hi);
+    if (std::fabs(zn - z) <= 1e-16 * std::fmax(1.0, std::fabs(z))) {
+      z = zn;
+      break;
+    }
+    z = zn;
+  }
+  return z;
+}
+
+int ilog2_exact(int x) {
+  int s = 0;
+  while ((1 << s) < x) ++s;
+  return ((1 << s) == x) ? s : -1;
+}
+
+int validate(const vatt_params& p) {
+  if (p.batch <= 0 || p.n_q_heads <= 0 || p.n_kv_heads <= 0 || p.n_max <= 0) return VATT_E_INVALID_ARG;
+  if (p.head_dim != 64 && p.head_dim != 128) return VATT_E_UNSUPPORTED_SHAPE;
+  if (p.n_q_heads % p.n_kv_heads != 0) return VATT_E_INVALID_ARG;
+  const int g = p.n_q_heads / p.n_kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 8) return VATT_E_UNSUPPORTED_SHAPE;
+  if (p.kv_layout != VATT_LAYOUT_CONTIGUOUS && p.kv_layout != VATT_LAYOUT_PAGED) return VATT_E_INVALID_ARG;
+  if (p.kv_layout == VATT_LAYOUT_PAGED) {
+    if (p.page_size < 8 || p.page_size > 256 || ilog2_exact(p.page_size) < 0) return VATT_E_INVALID_ARG;
+    if (p.num_blocks <= 0) return VATT_E_INVALID_ARG;
+  }
+  if (p.sink < 0 || p.window < 0 || p.topk_abs < 0 || p.base_abs < 0) return VATT_E_INVALID_ARG;
+  if (!(p.topk_frac >= 0.f && p.topk_frac <= 1.f) || !(p.base_frac >= 0.f && p.base_frac <= 1.f))
+    return VATT_E_INVALID_ARG;
+  if (!(p.epsilon > 0.f && p.epsilon < 1.f) || !(p.delta > 0.f && p.delta < 1.f)) return VATT_E_INVALID_ARG;
+  if (p.target != VATT_TARGET_D && p.target != VATT_TARGET_N && p.target != VATT_TARGET_SDPA)
+    return VATT_E_INVALID_ARG;
+  if (!(p.sm_scale >= 0.f) || !std::isfinite(p.sm_scale)) return VATT_E_INVALID_ARG;
+  if (!(p.budget_cap_frac > 0.f && p.budget_cap_frac <= 1.f)) return VATT_E_INVALID_ARG;
+  if ((int64_t)p.n_max > (int64_t)1 << 24) return VATT_E_UNSUPPORTED_SHAPE;
+  return VATT_OK;
+}
+
+int build_plan(Plan& pl, const vatt_params& p, int device) {
+  pl.p = p;
+  pl.device = device;
+  pl.num_cus = 256;
+  if (device >= 0) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count <= 0) return VATT_E_NO_DEVICE;
+    if (device >= count) return VATT_E_INVALID_ARG;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return VATT_E_HIP;
+    pl.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  pl.group = p.n_q_heads / p.n_kv_heads;
+  pl.sm_scale = p.sm_scale > 0.f ? p.sm_scale : (float)(1.0 / std::sqrt((double)p.head_dim));
+  pl.eps = (double)p.epsilon;
+  pl.cap_frac = (double)p.budget_cap_frac;
+  pl.z_half = upper_tail_quantile((double)p.delta / 2.0);
+  pl.z_quarter = upper_tail_quantile((double)p.delta / 4.0);
+  pl.sel.sink = p.sink;
+  pl.sel.window = p.window;
+  pl.sel.topk_abs = p.topk_abs;
+  pl.sel.base_abs = p.base_abs;
+  pl.sel.topk_frac = (double)p.topk_frac;
+  pl.sel.base_frac = (double)p.base_frac;
+  pl.force_slow_sampler = 0;
+
+  const int n_max = p.n_max;
+  pl.n_pad = (int)align_up((size_t)n_max, 256);
+  int k_max = p.topk_abs > 0 ? p.topk_abs : (int)std::floor((double)p.topk_frac * (double)n_max);
+  pl.k_max = std::min(std::max(k_max, 0), n_max);
+  int b0_max = p.base_abs > 0 ? p.base_abs : (int)std::floor((double)p.base_frac * (double)n_max);
+  pl.b0_max = std::min(std::max(b0_max, 2), n_max);
+  const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
+  pl.b_max = std::max(pl.b0_max, cap_max);
+
+  // top-k chunking: a chunk is what one workgroup keeps in registers; the per-head merge holds at most
+  // kSelElems * kHeadThreads candidates
+  const int merge_cap = kSelElems * kHeadThreads;
+  pl.chunk_threads = kChunkThreadsSmall;
+  pl.chunk_len = kChunkThreadsSmall * kSelElems;
+  pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
+  pl.cand_cap = std::max(1, std::min(pl.k_max, pl.chunk_len));
+  if ((int64_t)pl.n_chunks * pl.cand_cap > merge_cap) {
+    pl.chunk_threads = kChunkThreadsLarge;
+    pl.chunk_len = kChunkThreadsLarge * kSelElems;
+    pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
+    pl.cand_cap = std::max(1, std::min(pl.k_max, pl.chunk_len));
+    if ((int64_t)pl.n_chunks * pl.cand_cap > merge_cap) return VATT_E_UNSUPPORTED_SHAPE;
+  }
+
+  const int heads = p.batch * p.n_q_heads;
+  const int want_blocks = 2 * pl.num_cus;
+  pl.gather_splits = std::min(32, std::max(1, (want_blocks + heads - 1) / heads));
+  pl.vstat_splits = pl.gather_splits;
+  const int kv_heads = p.batch * p.n_kv_heads;
+  const int max_dense = std::max(1, (n_max + 255) / 256);
+  pl.dense_splits = std::min(std::min(128, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
+
+  pl.seg_off[0] = 0;
+  pl.seg_off[1] = p.sink;
+  pl.seg_off[2] = (int64_t)p.sink + p.window;
+  pl.seg_off[3] = pl.seg_off[2] + pl.k_max;
+  pl.seg_off[4] = pl.seg_off[3] + pl.b0_max;
+  pl.idx_cap = align_up((size_t)(pl.seg_off[4] + pl.b_max), 4);
+  pl.head_lds_bytes = head_kernel_lds_bytes(n_max);
+  if (pl.head_lds_bytes > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  };
+  pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float));
+  pl.off_chunk_max = take((size_t)heads * pl.n_chunks * sizeof(float));
+  pl.off_cand = take((size_t)heads * pl.n_chunks * pl.cand_cap * sizeof(uint64_t));
+  pl.off_cand_cnt = take((size_t)heads * pl.n_chunks * sizeof(int32_t));
+  pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
+  pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
+  pl.off_gather_cnt = take((size_t)heads * sizeof(int32_t));
+  pl.off_vstat_part = take((size_t)heads * pl.vstat_splits * (2 * p.head_dim + 2) * sizeof(double));
+  pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
+  pl.ws_bytes = off;
+
+  KVLayout L;
+  std::memset(&L, 0, sizeof(L));
+  L.head_dim = p.head_dim;
+  if (p.kv_layout == VATT_LAYOUT_PAGED) {
+    L.page_shift = ilog2_exact(p.page_size);
+    L.pages_per_seq = (n_max + p.page_size - 1) / p.page_size;
+    L.num_blocks = p.num_blocks;
+    L.head_stride = (int64_t)p.page_size * p.head_dim;
+    L.block_stride = (int64_t)p.n_kv_heads * p.page_size * p.head_dim;
+  } else {
+    L.head_stride = (int64_t)n_max * p.head_dim;
+    L.seq_stride = (int64_t)p.n_kv_heads * n_max * p.head_dim;
+    L.num_blocks = 1;
+  }
+  pl.kv_k = L;
+  pl.kv_v = L;
+  return VATT_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_common(const vatt_plan* plan, const void* ws, size_t ws_bytes, const int32_t* block_table) {
+  if (!plan || !ws) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  if (ws_bytes < plan->pl.ws_bytes) return VATT_E_WORKSPACE_TOO_SMALL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return VATT_E_INVALID_ARG;
+  if (plan->pl.p.kv_layout == VATT_LAYOUT_PAGED && !block_table) return VATT_E_INVALID_ARG;
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return VATT_E_HIP;
+  if (cur != plan->pl.device) return VATT_E_HIP;
+  return VATT_OK;
+}
+
+#define VATT_LAUNCH(expr)                    \
+  do {                                       \
+    if ((expr) != hipSuccess) return VATT_E_HIP; \
+  } while (0)
+
+}  // namespace
+}  // namespace vatt
+
+using namespace vatt;
+
+extern "C" {
+
+int vatt_plan_create(const vatt_params* params, int device, vatt_plan** out) {
+  if (!params || !out) return VATT_E_INVALID_ARG;
+  *out = nullptr;
+  int rc = validate(*params);
+  if (rc != VATT_OK) return rc;
+  vatt_plan* plan = new (std::nothrow) vatt_plan;
+  if (!plan) return VATT_E_INVALID_ARG;
+  std::memset(static_cast<void*>(plan), 0, sizeof(*plan));
+  rc = build_plan(plan->pl, *params, device);
+  if (rc == VATT_OK && device >= 0) {
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) rc = VATT_E_HIP;
+    if (rc == VATT_OK && cur != device && hipSetDevice(device) != hipSuccess) rc = VATT_E_HIP;
+    if (rc == VATT_OK && set_kernel_attributes(plan->pl) != hipSuccess) rc = VATT_E_HIP;
+    if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+  }
+  if (rc != VATT_OK) {
+    delete plan;
+    return rc;
+  }
+  *out = plan;
+  return VATT_OK;
+}
+
+void vatt_plan_destroy(vatt_plan* plan) { delete plan; }
+
+size_t vatt_plan_workspace_bytes(const vatt_plan* plan) { return plan ? plan->pl.ws_bytes : 0; }
+
+size_t vatt_plan_workspace_offset(const vatt_plan* plan, int region) {
+  if (!plan) return (size_t)-1;
+  if (region == VATT_WS_SCORES) return plan->pl.off_scores;
+  return (size_t)-1;
+}
+
+size_t vatt_plan_score_stride(const vatt_plan* plan) { return plan ? (size_t)plan->pl.n_pad : 0; }
+
+size_t vatt_plan_index_capacity(const vatt_plan* plan) { return plan ? plan->pl.idx_cap : 0; }
+
+int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment) {
+  if (!plan || segment < 0 || segment > 4) return -1;
+  return plan->pl.seg_off[segment];
+}
+
+int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
+  if (!plan) return VATT_E_INVALID_ARG;
+  if (option == VATT_OPT_EXACT_SAMPLER_ONLY) {
+    plan->pl.force_slow_sampler = value ? 1 : 0;
+    return VATT_OK;
+  }
+  return VATT_E_INVALID_ARG;
+}
+
+int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* block_table, const int32_t* seq_lens,
+               void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_common(plan, workspace, workspace_bytes, block_table);
+  if (rc != VATT_OK) return rc;
+  if (!q || !k || !seq_lens || !aligned16(q) || !aligned16(k)) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
+int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, const int32_t* block_table,
+                const int32_t* seq_lens, const uint64_t* seq_seeds, void* workspace, size_t workspace_bytes,
+                float* out_o, float* out_lse, int32_t* out_idx, int32_t* out_counts, double* out_budget_raw,
+                float* out_stats, void* stream) {
+  int rc = check_common(plan, workspace, workspace_bytes, block_table);
+  if (rc != VATT_OK) return rc;
+  if (!q || !k || !v || !seq_lens || !seq_seeds || !out_o || !out_idx || !out_counts) return VATT_E_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
+  const Plan& pl = plan->pl;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
+  VATT_LAUNCH(launch_chunk_topk(pl, seq_lens, workspace, st));
+  if (pl.p.target == VATT_TARGET_D) {
+    VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
+  } else {
+    VATT_LAUNCH(launch_head(pl, 1, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
+    VATT_LAUNCH(launch_vstats(pl, v, block_table, workspace, out_idx, st));
+    VATT_LAUNCH(launch_head(pl, 2, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
+  }
+  VATT_LAUNCH(launch_gather(pl, v, block_table, workspace, out_idx, out_o, out_lse, st));
+  return VATT_OK;
+}
+
+int vatt_dense_decode(vatt_plan* plan, const void* q, const void* k, const void* v, const int32_t* block_table,
+                      const int32_t* seq_lens, void* workspace, size_t workspace_bytes, float* out_o,
+                      float* out_lse, void* stream) {
+  int rc = check_common(plan, workspace, workspace_bytes, block_table);
+  if (rc != VATT_OK) return rc;
+  if (!q || !k || !v || !seq_lens || !out_o) return VATT_E_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_dense(plan->pl, q, k, v, block_table, seq_lens, workspace, out_o, out_lse,
+                           static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
+int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
+                   const int32_t* block_table, int32_t* seq_lens, void* stream) {
+  if (!plan) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  if (plan->pl.p.kv_layout == VATT_LAYOUT_PAGED && !block_table) return VATT_E_INVALID_ARG;
+  if (!k_new || !v_new || !k || !v || !seq_lens) return VATT_E_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_append(plan->pl, k_new, v_new, k, v, block_table, seq_lens, static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
+const char* vatt_status_string(int status) {
+  switch (status) {
+    case VATT_OK: return "ok";
+    case VATT_E_INVALID_ARG: return "invalid argument";
+    case VATT_E_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case VATT_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case VATT_E_HIP: return "HIP runtime error";
+    case VATT_E_NO_DEVICE: return "no usable HIP device";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

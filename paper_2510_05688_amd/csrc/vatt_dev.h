@@ -1,0 +1,157 @@
+// Device-side helpers shared by the vatt kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vatt {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------
+// KV cache addressing.  Contiguous: [B, Hkv, n_max, d].  Paged: [blocks, Hkv, page, d]
+// with a block table [B, pages_per_seq].
+// ---------------------------------------------------------------------------
+struct KVLayout {
+  const int32_t* block_table;  // nullptr when contiguous
+  int64_t seq_stride;          // contiguous: Hkv * n_max * d        (elements)
+  int64_t head_stride;         // contiguous: n_max * d; paged: page * d
+  int64_t block_stride;        // paged: Hkv * page * d
+  int32_t page_shift;          // log2(page)
+  int32_t pages_per_seq;
+  int32_t num_blocks;
+  int32_t head_dim;
+};
+
+template <bool PAGED>
+__device__ __forceinline__ int64_t kv_row_offset(const KVLayout& L, int b, int kvh, int i) {
+  if constexpr (PAGED) {
+    const int page = i >> L.page_shift;
+    int blk = L.block_table[(int64_t)b * L.pages_per_seq + page];
+    blk = min(max(blk, 0), L.num_blocks - 1);
+    const int within = i & ((1 << L.page_shift) - 1);
+    return (int64_t)blk * L.block_stride + (int64_t)kvh * L.head_stride + (int64_t)within * L.head_dim;
+  } else {
+    return (int64_t)b * L.seq_stride + (int64_t)kvh * L.head_stride + (int64_t)i * L.head_dim;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// bf16 pairs packed in a 32-bit word -> two fp32 values (exact).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---------------------------------------------------------------------------
+// Cross-lane sums inside groups of 8 or 16 adjacent lanes, on the DPP path.
+// After the call every lane of the group holds the group's sum.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(LANES == 8 || LANES == 16, "group of 8 or 16 lanes");
+  v += dpp_f32<0xB1>(v);   // quad_perm [1,0,3,2]: partner lane ^ 1
+  v += dpp_f32<0x4E>(v);   // quad_perm [2,3,0,1]: partner lane ^ 2
+  v += dpp_f32<0x141>(v);  // row_half_mirror: the other quad of the 8-lane half
+  if constexpr (LANES == 16) v += dpp_f32<0x140>(v);  // row_mirror: the other half of the 16-lane row
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ---------------------------------------------------------------------------
+// Order-preserving map fp32 -> uint32 (ascending).  -0 must have been folded into +0.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t float_order_key(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_from_order_key(uint32_t k) {
+  const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(u);
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of
+//   (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0)),
+// the key advancing by the Weyl constants between rounds.
+// ---------------------------------------------------------------------------
+struct Philox4 {
+  uint32_t v[4];
+};
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                  uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)c0 * 0xD2511F53ull;
+    const uint64_t p1 = (uint64_t)c2 * 0xCD9E8D57ull;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  Philox4 o;
+  o.v[0] = c0;
+  o.v[1] = c1;
+  o.v[2] = c2;
+  o.v[3] = c3;
+  return o;
+}
+
+// ---------------------------------------------------------------------------
+// Per-head sizes of Algorithm 1, lines 1-5, derived from the sequence length alone.
+// ---------------------------------------------------------------------------
+struct HeadSizes {
+  int n, n_sink, n_win, mid_lo, mid_hi, k, n_s, b0;
+};
+
+struct SelectParams {
+  int32_t sink, window, topk_abs, base_abs;
+  double topk_frac, base_frac;  // the float parameters widened exactly
+};
+
+__device__ __forceinline__ HeadSizes head_sizes(int n, const SelectParams& p) {
+  HeadSizes h;
+  h.n = n;
+  h.n_sink = min(p.sink, n);
+  h.n_win = min(p.window, n - h.n_sink);
+  h.mid_lo = h.n_sink;
+  h.mid_hi = n - h.n_win;
+  const int m = h.mid_hi - h.mid_lo;
+  int k = p.topk_abs > 0 ? p.topk_abs : (int)floor(p.topk_frac * (double)n);
+  h.k = min(max(k, 0), m);
+  h.n_s = m - h.k;
+  int b0 = p.base_abs > 0 ? p.base_abs : (int)floor(p.base_frac * (double)h.n_s);
+  h.b0 = min(max(b0, 2), h.n_s);
+  return h;
+}
+
+}  // namespace vatt

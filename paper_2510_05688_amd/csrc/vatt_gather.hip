@@ -1,0 +1,258 @@
+// Sparse attention over the selected tokens: SDPA_{S,p} of Eq. 3 with S = [I_f, I_dyn], p = [1, b/n_s],
+// computed as the N and D sums of Section 4.1:
+//   N = sum_{I_f} w_i V[i] + (n_s/b) sum_{I_dyn} w_i V[i],   D likewise without V,   O = N / D,
+// with w_i = exp(s_i - m), m the head's largest score (so every weight is <= 1 and partial sums of
+// different workgroups add directly).  Also the V-side statistics of Algorithm 2 for the numerator and
+// SDPA targets (N_f, sum r_i and sum ||r_i||^2 over the base sample, r_i = w_i V[i]).
+//
+// grid = (splits, query heads, sequences).  A workgroup walks its slice of the head's token list 16 rows
+// (d = 128) at a time: d/8 adjacent lanes read one 256-byte V row with one 16-byte load each.  The last
+// workgroup of a head to finish adds the per-split partials in split order and writes O and ln D.
+#include "vatt_internal.h"
+
+namespace vatt {
+namespace {
+
+struct GatherArgs {
+  const uint16_t* v;
+  KVLayout L;
+  const float* scores;
+  const HeadRec* head_rec;
+  const int32_t* idx;
+  float* part;        // [B*Hq][splits][d + 4]
+  int32_t* counters;  // [B*Hq], zeroed by the per-head kernel
+  double* vpart;      // [B*Hq][splits][2d + 2]
+  float* out_o;
+  float* out_lse;
+  int64_t seg_topk, seg_base, seg_dyn, idx_cap;
+  int n_pad, Hq, group, splits;
+};
+
+// Token and weight factor of list position p for a head:
+// [sink | window | top-k | tail) where the tail is the final sample (scaled by n_s/b) or, for the
+// statistics pass, the base sample (unscaled).
+__device__ __forceinline__ int list_token(const HeadRec& r, const int32_t* idx, int64_t seg_topk, int64_t seg_tail,
+                                          int p, bool* in_tail) {
+  *in_tail = false;
+  if (p < r.n_sink) return p;
+  p -= r.n_sink;
+  if (p < r.n_win) return r.n - r.n_win + p;
+  p -= r.n_win;
+  if (p < r.k) return idx[seg_topk + p];
+  p -= r.k;
+  *in_tail = true;
+  return idx[seg_tail + p];
+}
+
+template <int D, bool PAGED, bool STATS>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
+  constexpr int LPR = D / 8;
+  constexpr int RPW = kWave / LPR;
+  constexpr int WAVES = kGatherThreads / kWave;
+  constexpr int RPB = RPW * WAVES;  // rows per workgroup step
+  constexpr int U = 4;              // independent rows in flight per lane
+
+  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int bh = b * A.Hq + h;
+  const int kvh = h / A.group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, rsub = lane / LPR;
+
+  const HeadRec r = A.head_rec[bh];
+  const int32_t* idx = A.idx + (int64_t)bh * A.idx_cap;
+  const float* row = A.scores + (int64_t)bh * A.n_pad;
+  const int total = r.n_sink + r.n_win + r.k + r.b;
+  const int per = (total + A.splits - 1) / A.splits;
+  const int p_lo = split * per, p_hi = min(p_lo + per, total);
+  const int64_t seg_tail = STATS ? A.seg_base : A.seg_dyn;
+  const float tail_scale = STATS ? 1.0f : r.scale;
+
+  float acc[8], acc2[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = acc2[c] = 0.f;
+  float dsum = 0.f, r2 = 0.f;
+
+  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
+    int tok[U];
+    float w[U];
+    bool tail[U];
+    uint4 vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = p0 + u * RPB;
+      tok[u] = -1;
+      tail[u] = false;
+      if (p < p_hi) tok[u] = list_token(r, idx, A.seg_topk, seg_tail, p, &tail[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      w[u] = 0.f;
+      vv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (tok[u] >= 0) {
+        const int t = min(tok[u], r.n - 1);
+        w[u] = row[t];
+        vv[u] = *reinterpret_cast<const uint4*>(A.v + kv_row_offset<PAGED>(A.L, b, kvh, t) + sub * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (tok[u] >= 0) {
+        const float wt = expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f);
+        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+        if (STATS && tail[u]) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float a = wt * bf16_lo(ww[c]), bb = wt * bf16_hi(ww[c]);
+            acc2[2 * c] += a;
+            acc2[2 * c + 1] += bb;
+            r2 += a * a + bb * bb;
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            acc[2 * c] += wt * bf16_lo(ww[c]);
+            acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+          }
+          if (sub == 0) dsum += wt;
+        }
+      }
+    }
+  }
+
+  // rows of one wave sit in lane groups rsub = 0 .. RPW-1: add them, then add the waves through LDS
+#pragma unroll
+  for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      acc[c] += __shfl_xor(acc[c], o);
+      if (STATS) acc2[c] += __shfl_xor(acc2[c], o);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    dsum += __shfl_xor(dsum, o);
+    if (STATS) r2 += __shfl_xor(r2, o);
+  }
+  __shared__ float s_acc[WAVES][D];
+  __shared__ float s_acc2[STATS ? WAVES : 1][STATS ? D : 1];
+  __shared__ float s_d[WAVES], s_r2[WAVES];
+  __shared__ int s_last;
+  if (rsub == 0) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      s_acc[wave][sub * 8 + c] = acc[c];
+      if (STATS) s_acc2[wave][sub * 8 + c] = acc2[c];
+    }
+  }
+  if (lane == 0) {
+    s_d[wave] = dsum;
+    s_r2[wave] = r2;
+  }
+  __syncthreads();
+
+  if (STATS) {
+    double* out = A.vpart + ((int64_t)bh * A.splits + split) * (2 * D + 2);
+    if (tid < D) {
+      double a = 0.0, a2 = 0.0;
+#pragma unroll
+      for (int w2 = 0; w2 < WAVES; ++w2) {
+        a += (double)s_acc[w2][tid];
+        a2 += (double)s_acc2[w2][tid];
+      }
+      out[tid] = a;
+      out[D + tid] = a2;
+    }
+    if (tid == 0) {
+      double t = 0.0;
+#pragma unroll
+      for (int w2 = 0; w2 < WAVES; ++w2) t += (double)s_r2[w2];
+      out[2 * D] = t;
+      out[2 * D + 1] = 0.0;
+    }
+    return;
+  }
+
+  float* part = A.part + ((int64_t)bh * A.splits + split) * (D + 4);
+  if (tid < D) {
+    float a = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < WAVES; ++w2) a += s_acc[w2][tid];
+    part[tid] = a;
+  }
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < WAVES; ++w2) t += s_d[w2];
+    part[D] = t;
+  }
+  // publish the partial, then take a ticket; the last workgroup of the head reduces
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int ticket = __hip_atomic_fetch_add(&A.counters[bh], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (ticket == A.splits - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  const float* all = A.part + (int64_t)bh * A.splits * (D + 4);
+  float dtot = 0.f;
+  for (int s = 0; s < A.splits; ++s) dtot += __hip_atomic_load(all + s * (D + 4) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid < D) {
+    float a = 0.f;
+    for (int s = 0; s < A.splits; ++s) a += __hip_atomic_load(all + s * (D + 4) + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    A.out_o[(int64_t)bh * D + tid] = a / dtot;
+  }
+  if (tid == 0 && A.out_lse) A.out_lse[bh] = r.m + logf(dtot);
+}
+
+template <int D, bool STATS>
+hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
+                           const int32_t* out_idx, float* out_o, float* out_lse, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  char* w = static_cast<char*>(ws);
+  GatherArgs A;
+  A.v = static_cast<const uint16_t*>(v);
+  A.L = pl.kv_v;
+  A.L.block_table = block_table;
+  A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
+  A.head_rec = reinterpret_cast<const HeadRec*>(w + pl.off_head_rec);
+  A.idx = out_idx;
+  A.part = reinterpret_cast<float*>(w + pl.off_gather_part);
+  A.counters = reinterpret_cast<int32_t*>(w + pl.off_gather_cnt);
+  A.vpart = reinterpret_cast<double*>(w + pl.off_vstat_part);
+  A.out_o = out_o;
+  A.out_lse = out_lse;
+  A.seg_topk = pl.seg_off[2];
+  A.seg_base = pl.seg_off[3];
+  A.seg_dyn = pl.seg_off[4];
+  A.idx_cap = (int64_t)pl.idx_cap;
+  A.n_pad = pl.n_pad;
+  A.Hq = p.n_q_heads;
+  A.group = pl.group;
+  A.splits = STATS ? pl.vstat_splits : pl.gather_splits;
+  dim3 grid(A.splits, p.n_q_heads, p.batch);
+  if (p.kv_layout == VATT_LAYOUT_PAGED)
+    hipLaunchKernelGGL((gather_kernel<D, true, STATS>), grid, dim3(kGatherThreads), 0, st, A);
+  else
+    hipLaunchKernelGGL((gather_kernel<D, false, STATS>), grid, dim3(kGatherThreads), 0, st, A);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gather(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
+                         const int32_t* out_idx, float* out_o, float* out_lse, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_gather_d<128, false>(pl, v, block_table, ws, out_idx, out_o, out_lse, st);
+  if (pl.p.head_dim == 64) return launch_gather_d<64, false>(pl, v, block_table, ws, out_idx, out_o, out_lse, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_vstats(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
+                         const int32_t* out_idx, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_gather_d<128, true>(pl, v, block_table, ws, out_idx, nullptr, nullptr, st);
+  if (pl.p.head_dim == 64) return launch_gather_d<64, true>(pl, v, block_table, ws, out_idx, nullptr, nullptr, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace vatt

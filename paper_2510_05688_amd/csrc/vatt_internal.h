@@ -1,0 +1,76 @@
+// Host-side plan and the launchers each kernel file exports to the API file.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/vatt.h"
+#include "vatt_dev.h"
+
+namespace vatt {
+
+constexpr int kScoreTile = 256;       // keys per score-kernel workgroup
+constexpr int kSelElems = 32;         // composites a thread keeps in registers during a select
+constexpr int kChunkThreadsSmall = 256;
+constexpr int kChunkThreadsLarge = 1024;
+constexpr int kHeadThreads = 1024;    // workgroup size of the per-head kernel
+constexpr int kListCap = 4096;        // LDS list of uncertain sampling candidates
+constexpr int kGatherThreads = 256;
+constexpr int kDenseThreads = 256;
+
+// What the per-head kernel leaves for the gather kernel.
+struct HeadRec {
+  float m;        // max score of the head
+  float scale;    // n_s / b (0 when b == 0)
+  int32_t n, n_sink, n_win, k, b, n_s;
+};
+
+struct Plan {
+  vatt_params p;
+  int device;         // -1: geometry only
+  int num_cus;
+  int group;          // Hq / Hkv
+  float sm_scale;
+  double z_half;      // Phi^{-1}(1 - delta/2)
+  double z_quarter;   // Phi^{-1}(1 - delta/4)
+  double eps, cap_frac;
+  SelectParams sel;
+  // sizes
+  int n_pad;          // score row stride (floats)
+  int k_max, b0_max, b_max;
+  int chunk_threads, chunk_len, n_chunks, cand_cap;  // top-k chunking
+  int gather_splits, dense_splits, vstat_splits;
+  size_t idx_cap;
+  int64_t seg_off[5];
+  size_t head_lds_bytes;
+  int force_slow_sampler;  // test hook: skip the sampler's fast path
+  // workspace offsets (bytes)
+  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_head_rec, off_gather_part,
+      off_gather_cnt, off_vstat_part, off_dense_part, ws_bytes;
+  KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
+};
+
+// Every launcher returns a hipError_t from hipGetLastError() after the launch.
+hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                        const int32_t* seq_lens, void* ws, hipStream_t st);
+hipError_t launch_chunk_topk(const Plan& pl, const int32_t* seq_lens, void* ws, hipStream_t st);
+// phase 0: everything (target D); phase 1: through the base sample; phase 2: budget and final sample.
+hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
+                       int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                       hipStream_t st);
+hipError_t launch_vstats(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
+                         const int32_t* out_idx, hipStream_t st);
+hipError_t launch_gather(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
+                         const int32_t* out_idx, float* out_o, float* out_lse, hipStream_t st);
+hipError_t launch_dense(const Plan& pl, const void* q, const void* k, const void* v, const int32_t* block_table,
+                        const int32_t* seq_lens, void* ws, float* out_o, float* out_lse, hipStream_t st);
+hipError_t launch_append(const Plan& pl, const void* k_new, const void* v_new, void* k, void* v,
+                         const int32_t* block_table, int32_t* seq_lens, hipStream_t st);
+hipError_t set_kernel_attributes(const Plan& pl);
+
+}  // namespace vatt
+
+struct vatt_plan {
+  vatt::Plan pl;
+};

@@ -1,0 +1,138 @@
+// Score pass: s_i = sm_scale * <K[i], q_h> for every key and every query head of the GQA group,
+// reading each K row from HBM once per group (first step of Algorithm 1 with exact top-k; the
+// exponent of Eq. 1).
+//
+// Work split: grid = (key tiles of 256, KV heads, sequences); a workgroup of 4 waves owns 256
+// consecutive keys.  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
+// each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
+// segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
+// (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
+// the DPP path, and the tile's G x 256 scores are staged in LDS so that they leave as full
+// 1 KiB rows.
+#include "vatt_internal.h"
+
+namespace vatt {
+namespace {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc,
+                                         false);
+}
+
+template <int D, int G, bool PAGED>
+__global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                    KVLayout L, const int32_t* __restrict__ seq_lens,
+                                                    float* __restrict__ scores, int n_pad, int n_max, int Hq,
+                                                    float sm_scale) {
+  constexpr int LPR = D / 8;             // lanes per K row
+  constexpr int RPW = kWave / LPR;       // rows per wave load
+  constexpr int ROWS_PER_WAVE = kScoreTile / 4;
+  constexpr int LOADS = ROWS_PER_WAVE / RPW;
+  constexpr int BATCH = LOADS < 8 ? LOADS : 8;
+
+  const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int n = min(max(seq_lens[b], 0), n_max);
+  const int tile_lo = tile * kScoreTile;
+  if (tile_lo >= n) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR;   // which 8-column slice of the row
+  const int rsub = lane / LPR;  // which row of the wave load
+
+  __shared__ float s_tile[G][kScoreTile];
+
+  uint32_t qw[G][4];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const uint4 t = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + (int64_t)kvh * G + g) * D + sub * 8);
+    qw[g][0] = t.x;
+    qw[g][1] = t.y;
+    qw[g][2] = t.z;
+    qw[g][3] = t.w;
+  }
+
+#pragma unroll
+  for (int u0 = 0; u0 < LOADS; u0 += BATCH) {
+    uint4 kv[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int row = wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
+      const int i = tile_lo + row;
+      if (i < n) {
+        kv[u] = *reinterpret_cast<const uint4*>(k + kv_row_offset<PAGED>(L, b, kvh, i) + sub * 8);
+      } else {
+        kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int row = wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
+      float mine = 0.f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float a = 0.f;
+        a = dot2_bf16(kv[u].x, qw[g][0], a);
+        a = dot2_bf16(kv[u].y, qw[g][1], a);
+        a = dot2_bf16(kv[u].z, qw[g][2], a);
+        a = dot2_bf16(kv[u].w, qw[g][3], a);
+        a = group_sum<LPR>(a);
+        if (sub == g) mine = a;
+      }
+      // adding +0 folds a possible -0 into +0 so that the bit pattern orders like the value
+      if (sub < G) s_tile[sub][row] = mine * sm_scale + 0.0f;
+    }
+  }
+  __syncthreads();
+  const int i = tile_lo + tid;
+  if (i < n) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][tid];
+    }
+  }
+}
+
+template <int D, int G>
+hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                     const int32_t* seq_lens, void* ws, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
+  KVLayout L = pl.kv_k;
+  L.block_table = block_table;
+  float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_scores);
+  if (p.kv_layout == VATT_LAYOUT_PAGED) {
+    hipLaunchKernelGGL((score_kernel<D, G, true>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+                       static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
+                       pl.sm_scale);
+  } else {
+    hipLaunchKernelGGL((score_kernel<D, G, false>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
+                       static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
+                       pl.sm_scale);
+  }
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_d(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                    const int32_t* seq_lens, void* ws, hipStream_t st) {
+  switch (pl.group) {
+    case 1: return launch_dg<D, 1>(pl, q, k, block_table, seq_lens, ws, st);
+    case 2: return launch_dg<D, 2>(pl, q, k, block_table, seq_lens, ws, st);
+    case 4: return launch_dg<D, 4>(pl, q, k, block_table, seq_lens, ws, st);
+    case 8: return launch_dg<D, 8>(pl, q, k, block_table, seq_lens, ws, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                        const int32_t* seq_lens, void* ws, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_d<128>(pl, q, k, block_table, seq_lens, ws, st);
+  if (pl.p.head_dim == 64) return launch_d<64>(pl, q, k, block_table, seq_lens, ws, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace vatt

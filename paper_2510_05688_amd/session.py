@@ -1,0 +1,117 @@
+"""Device buffers for one plan: allocation and upload only (PyTorch as the memory allocator).
+
+No arithmetic of the method happens here; every call goes straight to the C ABI.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as vb
+
+
+def _bf16_from_bits(bits: np.ndarray, device) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.to(device).view(torch.bfloat16)
+
+
+class DecodeSession:
+    """Owns a plan, its workspace and output buffers on one GPU."""
+
+    def __init__(self, params: Dict, device: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("DecodeSession needs a GPU; there is no CPU path")
+        self.device = torch.device("cuda", device)
+        torch.cuda.set_device(self.device)
+        self.params = dict(params)
+        self.plan = vb.vatt_plan_create(self.params, device)
+        p = self.params
+        self.B, self.Hq, self.Hkv, self.d = p["batch"], p["n_q_heads"], p["n_kv_heads"], p["head_dim"]
+        self.n_max = p["n_max"]
+        self.paged = p.get("kv_layout", 0) == vb.VATT_LAYOUT_PAGED
+        self.idx_cap = vb.vatt_plan_index_capacity(self.plan)
+        self.seg = [vb.vatt_plan_index_segment(self.plan, s) for s in range(5)]
+        self.ws_bytes = vb.vatt_plan_workspace_bytes(self.plan)
+        dev = self.device
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.out_o = torch.empty(self.B, self.Hq, self.d, dtype=torch.float32, device=dev)
+        self.out_lse = torch.empty(self.B, self.Hq, dtype=torch.float32, device=dev)
+        self.out_idx = torch.empty(self.B, self.Hq, self.idx_cap, dtype=torch.int32, device=dev)
+        self.out_counts = torch.empty(self.B, self.Hq, 8, dtype=torch.int32, device=dev)
+        self.out_budget_raw = torch.empty(self.B, self.Hq, dtype=torch.float64, device=dev)
+        self.out_stats = torch.empty(self.B, self.Hq, 4, dtype=torch.float32, device=dev)
+        self.dense_o = torch.empty(self.B, self.Hq, self.d, dtype=torch.float32, device=dev)
+        self.dense_lse = torch.empty(self.B, self.Hq, dtype=torch.float32, device=dev)
+        self.block_table: Optional[torch.Tensor] = None
+        self.q = self.k = self.v = self.seq_lens = self.seq_seeds = None
+
+    def close(self):
+        if self.plan:
+            vb.vatt_plan_destroy(self.plan)
+            self.plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- uploads -----------------------------------------------------------
+    def upload(self, q_bits, k_bits, v_bits, seq_lens, seeds, block_table=None):
+        dev = self.device
+        self.q = _bf16_from_bits(q_bits, dev)
+        self.k = _bf16_from_bits(k_bits, dev)
+        self.v = _bf16_from_bits(v_bits, dev)
+        self.seq_lens = torch.from_numpy(np.ascontiguousarray(seq_lens, dtype=np.int32)).to(dev)
+        self.seq_seeds = torch.from_numpy(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64)).to(dev)
+        self.block_table = None
+        if block_table is not None:
+            self.block_table = torch.from_numpy(np.ascontiguousarray(block_table, dtype=np.int32)).to(dev)
+        return self
+
+    def set_seeds(self, seeds):
+        self.seq_seeds = torch.from_numpy(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64)).to(self.device)
+
+    def _stream(self):
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    # ---- calls ---------------------------------------------------------------
+    def decode(self, q=None, k=None, v=None):
+        vb.vatt_decode(self.plan, self.q if q is None else q, self.k if k is None else k,
+                       self.v if v is None else v, self.block_table, self.seq_lens, self.seq_seeds,
+                       self.workspace, self.out_o, self.out_lse, self.out_idx, self.out_counts,
+                       self.out_budget_raw, self.out_stats, self._stream())
+
+    def dense(self, q=None, k=None, v=None):
+        vb.vatt_dense_decode(self.plan, self.q if q is None else q, self.k if k is None else k,
+                             self.v if v is None else v, self.block_table, self.seq_lens, self.workspace,
+                             self.dense_o, self.dense_lse, self._stream())
+
+    def score(self, q=None, k=None):
+        vb.vatt_score(self.plan, self.q if q is None else q, self.k if k is None else k, self.block_table,
+                      self.seq_lens, self.workspace, self._stream())
+
+    def append(self, k_new_bits, v_new_bits):
+        kn = _bf16_from_bits(k_new_bits, self.device)
+        vn = _bf16_from_bits(v_new_bits, self.device)
+        vb.vatt_append_kv(self.plan, kn, vn, self.k, self.v, self.block_table, self.seq_lens, self._stream())
+
+    # ---- read-back -----------------------------------------------------------
+    def scores_host(self) -> np.ndarray:
+        """float32 [B, Hq, n_max] view of the score region of the workspace (copied to host)."""
+        off = vb.vatt_plan_workspace_offset(self.plan, vb.VATT_WS_SCORES)
+        stride = vb.vatt_plan_score_stride(self.plan)
+        nbytes = self.B * self.Hq * stride * 4
+        t = self.workspace[off:off + nbytes].view(torch.float32).view(self.B, self.Hq, stride)
+        return t[:, :, :self.n_max].cpu().numpy()
+
+    def results_host(self) -> Dict[str, np.ndarray]:
+        torch.cuda.synchronize(self.device)
+        return dict(
+            O=self.out_o.cpu().numpy(), lse=self.out_lse.cpu().numpy(), idx=self.out_idx.cpu().numpy(),
+            counts=self.out_counts.cpu().numpy(), b_star=self.out_budget_raw.cpu().numpy(),
+            stats=self.out_stats.cpu().numpy(), seg=list(self.seg),
+        )

@@ -1,0 +1,124 @@
+"""GPU parity at the full sizes of the benchmark configurations (same launch configuration as bench.py)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from workloads.configs import append_tokens
+from oracle import vatt_oracle as vo
+from parity import check_all, gpu_segments, head_inputs, say
+from util import plan_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(wl, **over):
+    from paper_2510_05688_amd.session import DecodeSession
+    sess = DecodeSession(plan_params(wl, **over))
+    sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    return sess
+
+
+def _properties(wl, res, params=None):
+    """Checks that hold for every head at any size, without the oracle's scores."""
+    params = wl.params if params is None else params
+    for b in range(wl.batch):
+        n = int(wl.seq_lens[b])
+        k = vo.topk_count(n, params["sink"], params["window"], params.get("topk_abs", 0), params.get("topk_frac", 0.0))
+        for h in range(wl.n_q_heads):
+            g = gpu_segments(res, b, h)
+            n_sink = min(params["sink"], n)
+            n_win = min(params["window"], n - n_sink)
+            mid = n - n_sink - n_win
+            assert len(g["I_s"]) == n_sink and len(g["I_l"]) == n_win and len(g["I_t"]) == min(k, mid)
+            assert g["n_s"] == mid - len(g["I_t"])
+            assert g["b0"] == vo.base_count(g["n_s"], params.get("base_abs", 0), params.get("base_frac", 0.0)) or g["n_s"] == 0
+            assert g["b0"] <= g["b"] <= g["n_s"]
+            for key in ("I_t", "I_bs", "I_dyn"):
+                a = g[key]
+                assert np.all(np.diff(a) > 0), key
+                if len(a):
+                    assert a[0] >= n_sink and a[-1] < n - n_win
+            assert len(np.intersect1d(g["I_t"], g["I_bs"])) == 0 and len(np.intersect1d(g["I_t"], g["I_dyn"])) == 0
+            assert np.all(np.isfinite(res["O"][b, h]))
+
+
+@pytest.mark.timeout(300)
+def test_config2_llama8b_32k_all_heads():
+    say("config 2 (B=1, 32/8 heads, n=32768)")
+    wl = workloads.config2()
+    sess = _session(wl)
+    sess.decode()
+    res = sess.results_host()
+    _properties(wl, res)
+    reps = check_all(wl, res, gpu_scores=sess.scores_host(), label="config2")
+    # budgets: with the denominator target every head sits at the base sample size (see the design notes)
+    say("config2 budgets: %s" % sorted(set((r["b"], r["b0"]) for r in reps)))
+    sess.dense()
+    torch.cuda.synchronize()
+    dense_o = sess.dense_o.cpu().numpy()
+    for h in range(0, 32, 5):
+        q, K, V, n = head_inputs(wl, 0, h)
+        ro, _ = vo.dense_sdpa(q, K, V, wl.params["sm_scale"])
+        assert np.linalg.norm(dense_o[0, h] - ro) / np.linalg.norm(ro) <= 2e-3
+    sess.close()
+
+
+@pytest.mark.timeout(600)
+def test_config3_batch16_sampled_heads():
+    say("config 3 (B=16)")
+    wl = workloads.config3()
+    sess = _session(wl)
+    sess.decode()
+    res = sess.results_host()
+    _properties(wl, res)
+    rng = np.random.default_rng(0)
+    heads = [(int(rng.integers(16)), int(rng.integers(32))) for _ in range(48)] + [(0, 0), (15, 31)]
+    check_all(wl, res, heads=heads, label="config3")
+    sess.close()
+
+
+@pytest.mark.timeout(600)
+def test_config4_long_context():
+    say("config 4 (B=4, n=131072)")
+    wl = workloads.config4()
+    sess = _session(wl)
+    sess.decode()
+    res = sess.results_host()
+    _properties(wl, res)
+    rng = np.random.default_rng(1)
+    heads = [(int(rng.integers(4)), int(rng.integers(32))) for _ in range(24)] + [(0, 0), (3, 31)]
+    check_all(wl, res, heads=heads, label="config4")
+    sess.close()
+
+
+@pytest.mark.timeout(600)
+def test_config5_ragged_paged_decode_loop():
+    say("config 5 (ragged, paged, append loop; B=8 here, 6 steps)")
+    from paper_2510_05688_amd.session import DecodeSession
+    steps = 6
+    wl = workloads.config5(batch=8, steps=256)
+    k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=3)
+    sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]))
+    sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+    base_seeds = wl.seeds.copy()
+    for step in range(steps):
+        if step > 0:
+            k_new, v_new = append_tokens(5, step, wl.batch, wl.n_kv_heads, wl.head_dim)
+            sess.append(k_new, v_new)
+            for b in range(wl.batch):     # mirror the append in the host copy the oracle reads
+                n = int(wl.seq_lens[b])
+                wl.k_bits[b, :, n] = k_new[b]
+                wl.v_bits[b, :, n] = v_new[b]
+            wl.seq_lens = wl.seq_lens + 1
+        wl.seeds = base_seeds + np.uint64(7919 * step)
+        sess.set_seeds(wl.seeds)
+        sess.decode()
+        res = sess.results_host()
+        assert np.array_equal(sess.seq_lens.cpu().numpy(), wl.seq_lens)
+        if step in (0, 1, steps - 1):
+            _properties(wl, res)
+            rng = np.random.default_rng(step)
+            heads = [(int(rng.integers(wl.batch)), int(rng.integers(32))) for _ in range(10)]
+            check_all(wl, res, heads=heads, label="config5/step%d" % step)
+    sess.close()

@@ -1,0 +1,248 @@
+"""GPU parity: libvatt (through its C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from workloads.configs import default_params, append_tokens
+from oracle import vatt_oracle as vo
+from parity import check_all, check_head, gpu_segments, head_inputs, say, score_tolerance
+from util import plan_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(wl, **over):
+    from paper_2510_05688_amd.session import DecodeSession
+    sess = DecodeSession(plan_params(wl, **over))
+    sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    return sess
+
+
+def _paged_session(wl, page=16, seed=0):
+    from paper_2510_05688_amd.session import DecodeSession
+    k_pages, v_pages, table = workloads.to_paged(wl, page=page, seed=seed)
+    sess = DecodeSession(plan_params(wl, paged=True, page=page, num_blocks=k_pages.shape[0]))
+    sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+    return sess
+
+
+def _run(sess):
+    sess.decode()
+    return sess.results_host()
+
+
+# ------------------------------------------------------------------ scores ---
+@pytest.mark.parametrize("d,hq,hkv,n,lens", [
+    (128, 8, 2, 3000, [3000, 2963]),        # G = 4, ragged tail, several tiles
+    (128, 4, 4, 777, [777, 1]),             # G = 1, one-token sequence
+    (128, 16, 2, 1500, [1500, 1029]),       # G = 8
+    (64, 4, 2, 2100, [2100, 517]),          # d = 64, G = 2
+    (64, 8, 1, 600, [600, 256]),            # d = 64, G = 8
+])
+def test_score_pass(d, hq, hkv, n, lens):
+    say("score pass d=%d Hq=%d Hkv=%d n=%d" % (d, hq, hkv, n))
+    wl = workloads.small_gqa(seed=11, batch=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n=n, seq_lens=lens)
+    for paged in (False, True):
+        sess = _paged_session(wl, page=16 if n % 16 == 0 else 8) if (paged and n % 8 == 0) else _session(wl)
+        sess.score()
+        torch.cuda.synchronize()
+        gs = sess.scores_host()
+        for b in range(2):
+            for h in range(hq):
+                q, K, V, nn = head_inputs(wl, b, h)
+                s = vo.scores(q, K, wl.params["sm_scale"])
+                err = np.abs(gs[b, h, :nn] - s)
+                assert np.all(err <= score_tolerance(q, K, wl.params["sm_scale"])), (b, h, err.max())
+        sess.close()
+
+
+# ------------------------------------------------------ whole step, small ----
+SMALL_CASES = {
+    "default": dict(),
+    "target_N": dict(target=1, epsilon=0.2),
+    "target_SDPA": dict(target=2, epsilon=0.3),
+    "no_sink_no_window": dict(sink=0, window=0),
+    "no_topk": dict(topk_frac=0.0),
+    "no_base_rate": dict(base_frac=0.0),
+    "abs_counts": dict(topk_abs=40, base_abs=64),
+    "tight_eps": dict(epsilon=0.01, delta=0.01),
+    "capped": dict(epsilon=0.005, budget_cap_frac=0.3),
+    "window_covers_all": dict(sink=2000, window=2000),
+    "topk_covers_all": dict(topk_abs=100000),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL_CASES))
+def test_decode_small(name):
+    over = SMALL_CASES[name]
+    say("decode small case %s" % name)
+    wl = workloads.small_gqa(seed=7, **over)
+    sess = _session(wl)
+    res = _run(sess)
+    check_all(wl, res, gpu_scores=sess.scores_host(), label="small/" + name)
+    sess.close()
+
+
+def test_decode_small_mean_shifted_values_all_targets():
+    # V ~ N(1, 1): the numerator has a mean component, so the N and SDPA budgets are not clamped
+    for target, eps in ((0, 0.05), (1, 0.1), (2, 0.25)):
+        say("decode small mean-shifted target %d" % target)
+        p = default_params(128, sink=16, window=24, target=target, epsilon=eps, delta=0.1, base_abs=64, base_frac=0.0)
+        wl = workloads.make_workload("shifted", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, n_max=4096,
+                                     seq_lens=[4096, 3333], seed=13, params=p, v_mean=1.0, all_flat=True)
+        sess = _session(wl)
+        res = _run(sess)
+        reps = check_all(wl, res, label="shifted/target%d" % target)
+        assert sum(r["b"] > r["b0"] for r in reps) >= len(reps) // 2, "budgets should come from the formula"
+        sess.close()
+
+
+def test_tiny_sequences():
+    say("decode tiny sequences")
+    p = default_params(64, sink=4, window=4, topk_abs=3, topk_frac=0.0, base_abs=2, base_frac=0.0)
+    wl = workloads.make_workload("tiny", batch=6, n_q_heads=2, n_kv_heads=2, head_dim=64, n_max=64,
+                                 seq_lens=[1, 2, 7, 9, 12, 64], seed=3, params=p, all_flat=True)
+    sess = _session(wl)
+    res = _run(sess)
+    check_all(wl, res, label="tiny")
+    sess.close()
+
+
+def test_d64_group8():
+    say("decode d=64 G=8")
+    wl = workloads.small_gqa(seed=21, batch=1, n_q_heads=8, n_kv_heads=1, head_dim=64, n=5000, seq_lens=[4999])
+    sess = _session(wl)
+    res = _run(sess)
+    check_all(wl, res, gpu_scores=sess.scores_host(), label="d64g8")
+    sess.close()
+
+
+def test_config1_tiny_single_head():
+    say("config 1")
+    wl = workloads.config1()
+    sess = _session(wl)
+    res = _run(sess)
+    reps = check_all(wl, res, gpu_scores=sess.scores_host(), label="config1")
+    assert reps[0]["b"] == 32 and reps[0]["n_s"] == 1024 - 4 - 32 - 32
+    sess.close()
+
+
+# ------------------------------------------------------- layout, determinism --
+def test_paged_equals_contiguous_bit_for_bit():
+    say("paged vs contiguous")
+    wl = workloads.small_gqa(seed=5, batch=3, n=4096, seq_lens=[4096, 3001, 130])
+    a = _session(wl)
+    ra = _run(a)
+    b = _paged_session(wl, page=16, seed=9)
+    rb = _run(b)
+    for key in ("O", "lse", "counts", "b_star", "stats"):
+        assert np.array_equal(ra[key], rb[key]), key
+    for bb in range(3):
+        for h in range(wl.n_q_heads):
+            ga, gb = gpu_segments(ra, bb, h), gpu_segments(rb, bb, h)
+            for key in ("I_t", "I_bs", "I_dyn"):
+                assert np.array_equal(ga[key], gb[key]), (bb, h, key)
+    check_all(wl, rb, label="paged")
+    a.close()
+    b.close()
+
+
+def test_same_seed_same_bits_and_other_seed_other_sample():
+    say("determinism")
+    wl = workloads.small_gqa(seed=6, batch=2, n=6000)
+    sess = _session(wl)
+    r1 = _run(sess)
+    r2 = _run(sess)
+    for key in ("O", "lse", "idx", "counts", "b_star", "stats"):
+        assert np.array_equal(r1[key], r2[key]), key
+    sess.set_seeds(wl.seeds + np.uint64(1000))
+    r3 = _run(sess)
+    g1, g3 = gpu_segments(r1, 0, 0), gpu_segments(r3, 0, 0)
+    assert np.array_equal(g1["I_t"], g3["I_t"])
+    assert not np.array_equal(g1["I_bs"], g3["I_bs"]) and not np.array_equal(g1["I_dyn"], g3["I_dyn"])
+    sess.close()
+
+
+def test_exact_sampler_path_gives_identical_results():
+    say("exact sampler path")
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=8, batch=2, n=9000, epsilon=0.02)
+    sess = _session(wl)
+    fast = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_EXACT_SAMPLER_ONLY, 1)
+    slow = _run(sess)
+    assert np.all(slow["counts"][..., 7] == 1) and np.all(fast["counts"][..., 7] == 0)
+    for key in ("O", "lse", "b_star", "stats"):
+        assert np.array_equal(fast[key], slow[key]), key
+    assert np.array_equal(fast["counts"][..., :7], slow["counts"][..., :7])
+    for b in range(2):
+        for h in range(wl.n_q_heads):
+            gf, gs_ = gpu_segments(fast, b, h), gpu_segments(slow, b, h)
+            for key in ("I_t", "I_bs", "I_dyn"):
+                assert np.array_equal(gf[key], gs_[key]), (b, h, key)
+    check_all(wl, slow, label="exact-sampler")
+    sess.close()
+
+
+# ---------------------------------------------------- dense, and check (a) ----
+def test_dense_decode_matches_eq1():
+    say("dense decode")
+    for wl in (workloads.small_gqa(seed=9, batch=2, n=5000, seq_lens=[5000, 1234]),
+               workloads.small_gqa(seed=10, batch=1, n_q_heads=8, n_kv_heads=1, head_dim=64, n=900, seq_lens=[900])):
+        for paged in (False, True):
+            sess = _paged_session(wl, page=8) if paged and wl.n_max % 8 == 0 else _session(wl)
+            sess.dense()
+            torch.cuda.synchronize()
+            O, L = sess.dense_o.cpu().numpy(), sess.dense_lse.cpu().numpy()
+            for b in range(wl.batch):
+                for h in range(wl.n_q_heads):
+                    q, K, V, n = head_inputs(wl, b, h)
+                    ro, rl = vo.dense_sdpa(q, K, V, wl.params["sm_scale"])
+                    assert np.linalg.norm(O[b, h] - ro) / np.linalg.norm(ro) <= 2e-3, (b, h)
+                    assert abs(L[b, h] - rl) <= 2e-3
+            sess.close()
+
+
+def test_budget_covering_the_residual_equals_dense():
+    say("check (a) on the GPU")
+    wl = workloads.small_gqa(seed=12, batch=2, n=4000, base_abs=10 ** 6)
+    sess = _session(wl)
+    res = _run(sess)
+    sess.dense()
+    torch.cuda.synchronize()
+    dense_o = sess.dense_o.cpu().numpy()
+    for b in range(2):
+        for h in range(wl.n_q_heads):
+            g = gpu_segments(res, b, h)
+            assert g["b"] == g["n_s"] == g["b0"]
+            q, K, V, n = head_inputs(wl, b, h)
+            ro, rl = vo.dense_sdpa(q, K, V, wl.params["sm_scale"])
+            assert np.linalg.norm(res["O"][b, h] - ro) / np.linalg.norm(ro) <= 2e-3
+            assert np.linalg.norm(res["O"][b, h] - dense_o[b, h]) / np.linalg.norm(ro) <= 2e-3
+    check_all(wl, res, label="full-budget")
+    sess.close()
+
+
+# ----------------------------------------------------------- error handling ---
+def test_launch_argument_errors_are_caught_on_the_host():
+    say("argument errors")
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=2, batch=1, n=512, seq_lens=[512])
+    sess = _session(wl)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(vb.VattError) as e:
+        vb.vatt_score(sess.plan, sess.q, sess.k, None, sess.seq_lens, small)
+    assert e.value.status == vb.VATT_E_WORKSPACE_TOO_SMALL
+    with pytest.raises(vb.VattError) as e:
+        vb.vatt_score(sess.plan, sess.q, sess.k, None, sess.seq_lens, sess.workspace[128:])
+    assert e.value.status in (vb.VATT_E_INVALID_ARG, vb.VATT_E_WORKSPACE_TOO_SMALL)
+    with pytest.raises(vb.VattError) as e:
+        vb.vatt_decode(sess.plan, sess.q, sess.k, None, None, sess.seq_lens, sess.seq_seeds, sess.workspace,
+                       sess.out_o, None, sess.out_idx, sess.out_counts, None, None)
+    assert e.value.status == vb.VATT_E_INVALID_ARG
+    # optional outputs may be NULL
+    vb.vatt_decode(sess.plan, sess.q, sess.k, sess.v, None, sess.seq_lens, sess.seq_seeds, sess.workspace,
+                   sess.out_o, None, sess.out_idx, sess.out_counts, None, None)
+    torch.cuda.synchronize()
+    sess.close()

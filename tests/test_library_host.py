@@ -1,0 +1,108 @@
+"""Host-side checks of libvatt that need no GPU: exported symbols, parameter validation, plan geometry."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+from paper_2510_05688_amd import binding as vb  # noqa: E402
+
+
+def _base(**over):
+    p = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, n_max=32768, kv_layout=0, page_size=0,
+             num_blocks=0, sink=128, window=128, topk_abs=0, topk_frac=0.025, base_abs=0, base_frac=0.025,
+             epsilon=0.05, delta=0.05, target=0, sm_scale=0.0, budget_cap_frac=1.0)
+    p.update(over)
+    return p
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "vatt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(vatt_[a-z_]+)\s*\(", header))
+    assert declared == set(vb.EXPORTS), declared ^ set(vb.EXPORTS)
+    lib = ctypes.CDLL(vb.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    assert vb.vatt_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert vb.vatt_status_string(code) not in ("ok", "unknown status")
+    assert vb.vatt_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(batch=0), vb.VATT_E_INVALID_ARG),
+    (dict(head_dim=96), vb.VATT_E_UNSUPPORTED_SHAPE),
+    (dict(n_q_heads=30), vb.VATT_E_INVALID_ARG),
+    (dict(n_q_heads=48, n_kv_heads=8), vb.VATT_E_UNSUPPORTED_SHAPE),   # group of 6
+    (dict(epsilon=0.0), vb.VATT_E_INVALID_ARG),
+    (dict(epsilon=1.0), vb.VATT_E_INVALID_ARG),
+    (dict(delta=-0.1), vb.VATT_E_INVALID_ARG),
+    (dict(target=3), vb.VATT_E_INVALID_ARG),
+    (dict(sink=-1), vb.VATT_E_INVALID_ARG),
+    (dict(topk_frac=1.5), vb.VATT_E_INVALID_ARG),
+    (dict(budget_cap_frac=0.0), vb.VATT_E_INVALID_ARG),
+    (dict(kv_layout=1, page_size=12, num_blocks=10), vb.VATT_E_INVALID_ARG),
+    (dict(kv_layout=1, page_size=16, num_blocks=0), vb.VATT_E_INVALID_ARG),
+    (dict(kv_layout=2), vb.VATT_E_INVALID_ARG),
+    (dict(n_max=1 << 25), vb.VATT_E_UNSUPPORTED_SHAPE),
+    (dict(n_max=1 << 20, topk_frac=0.5), vb.VATT_E_UNSUPPORTED_SHAPE),  # merge would not fit one workgroup
+])
+def test_plan_create_rejects_bad_parameters(over, code):
+    with pytest.raises(vb.VattError) as e:
+        vb.vatt_plan_create(_base(**over), -1)
+    assert e.value.status == code
+
+
+def test_plan_geometry_config2():
+    plan = vb.vatt_plan_create(_base(), -1)
+    try:
+        # segments: sink 128 | window 128 | top-k floor(0.025 * 32768) = 819 | base floor(0.025 * 32768) = 819 | dyn
+        assert [vb.vatt_plan_index_segment(plan, s) for s in range(5)] == [0, 128, 256, 1075, 1894]
+        assert vb.vatt_plan_index_segment(plan, 5) == -1
+        assert vb.vatt_plan_index_capacity(plan) >= 1894 + 32768
+        assert vb.vatt_plan_score_stride(plan) == 32768
+        ws = vb.vatt_plan_workspace_bytes(plan)
+        assert ws >= 32 * 32768 * 4 and ws % 256 == 0
+        assert vb.vatt_plan_workspace_offset(plan, vb.VATT_WS_SCORES) % 256 == 0
+        assert vb.vatt_plan_workspace_offset(plan, 77) == 2 ** 64 - 1
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_EXACT_SAMPLER_ONLY, 1)
+        with pytest.raises(vb.VattError):
+            vb.vatt_plan_set_option(plan, 99, 1)
+    finally:
+        vb.vatt_plan_destroy(plan)
+
+
+def test_capped_budget_shrinks_index_buffer():
+    plan = vb.vatt_plan_create(_base(budget_cap_frac=0.25), -1)
+    try:
+        assert vb.vatt_plan_index_capacity(plan) < 1894 + 8192 + 8
+    finally:
+        vb.vatt_plan_destroy(plan)
+
+
+def test_geometry_only_plan_cannot_launch():
+    plan = vb.vatt_plan_create(_base(), -1)
+    try:
+        class Fake:
+            def data_ptr(self):
+                return 256
+
+            def numel(self):
+                return 1 << 30
+
+            def element_size(self):
+                return 1
+        f = Fake()
+        with pytest.raises(vb.VattError) as e:
+            vb.vatt_score(plan, f, f, None, f, f, None)
+        assert e.value.status == vb.VATT_E_NO_DEVICE
+        with pytest.raises(vb.VattError) as e:
+            vb.vatt_decode(plan, f, f, f, None, f, f, f, f, f, f, f, f, f, None)
+        assert e.value.status == vb.VATT_E_NO_DEVICE
+    finally:
+        vb.vatt_plan_destroy(plan)

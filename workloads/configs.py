@@ -252,7 +252,9 @@ def small_gqa(seed: int = 7, batch: int = 2, n_q_heads: int = 8, n_kv_heads: int
     """Small GQA case for element-by-element parity: several tiles and a ragged tail."""
     if seq_lens is None:
         seq_lens = [n - 37 * b for b in range(batch)]
-    p = default_params(head_dim, sink=16, window=24, **over)
+    kw = dict(sink=16, window=24)
+    kw.update(over)
+    p = default_params(head_dim, **kw)
     return make_workload("small_gqa", batch=batch, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
                          head_dim=head_dim, n_max=n, seq_lens=seq_lens, seed=seed, params=p,
                          plant_frac=0.004)
