@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the vAttention decode step (libvatt) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4] [--no-cpu]
+
+A step is one vatt_decode call: the whole hot path (score pass, chunk top-k, per-head selection / base
+sample / statistics / budget / final sample, gather) for one layer and one batch of synthetic input that
+is already resident in HBM.  Calls cycle through `--buffers` distinct copies of the KV cache so that no
+call finds its K/V in the 256 MB last-level cache.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+LLAMA8B_LAYERS = 32
+
+
+def plan_params(wl):
+    p = wl.params
+    return dict(batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+                n_max=wl.n_max, kv_layout=0, page_size=0, num_blocks=0, sink=int(p["sink"]), window=int(p["window"]),
+                topk_abs=int(p["topk_abs"]), topk_frac=float(p["topk_frac"]), base_abs=int(p["base_abs"]),
+                base_frac=float(p["base_frac"]), epsilon=float(p["epsilon"]), delta=float(p["delta"]),
+                target=int(p["target"]), sm_scale=float(p["sm_scale"]), budget_cap_frac=float(p["budget_cap_frac"]))
+
+
+def time_calls(fn, n_calls, torch):
+    """Average milliseconds per call of fn(i), bracketed by events on the current stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(n_calls):
+        fn(i)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / n_calls
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands, one thread, on whole heads of the same workload until ~budget_s have passed."""
+    import numpy as np
+    from oracle import vatt_oracle as vo
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)
+    except Exception:
+        limiter = None
+    g = wl.n_q_heads // wl.n_kv_heads
+    q_all = wl.q_f32()
+    t0 = time.perf_counter()
+    done = 0
+    total_heads = wl.batch * wl.n_q_heads
+    while True:
+        b, h = divmod(done % total_heads, wl.n_q_heads)
+        n = int(wl.seq_lens[b])
+        vo.decode_head(q_all[b, h].astype(np.float64), wl.k_f32(b, h // g, n).astype(np.float64),
+                       wl.v_f32(b, h // g, n).astype(np.float64), seed=int(wl.seeds[b]), head=h, params=wl.params)
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or done >= 4 * total_heads:
+            break
+    if limiter is not None:
+        limiter.unregister() if hasattr(limiter, "unregister") else None
+    us_per_layer = el / done * total_heads * 1e6
+    return dict(value=us_per_layer, unit="us/layer", cores=1, kind="oracle",
+                sample="%d (sequence, head) units of the same workload in %.1f s, scaled to the %d units of one layer"
+                       % (done, el, total_heads))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score' or 'dense' in the timed loop")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the step shards by sequence and "
+              "KV head without communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    from paper_2510_05688_amd.session import DecodeSession
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU path exists for the product)", file=sys.stderr)
+        sys.exit(2)
+
+    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
+    sess = DecodeSession(plan_params(wl))
+    sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
+    kv_bytes = 2 * B * Hkv * n * d * 2
+    nbuf = args.buffers if args.buffers > 0 else max(2, min(32, int(80e9 // kv_bytes)))
+    ks = [sess.k] + [sess.k.clone() for _ in range(nbuf - 1)]
+    vs = [sess.v] + [sess.v.clone() for _ in range(nbuf - 1)]
+
+    def step(i):
+        sess.decode(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    def score_only(i):
+        sess.score(k=ks[i % nbuf])
+
+    def dense(i):
+        sess.dense(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    if args.only:
+        fn = dict(decode=step, score=score_only, dense=dense)[args.only]
+        for i in range(args.warmup):
+            fn(i)
+        ms = time_calls(fn, args.steps, torch)
+        print(json.dumps({"only": args.only, "ms_per_call": ms, "steps": args.steps}))
+        return
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter()
+    ms_step = time_calls(step, args.steps, torch)
+    t_wall = time.perf_counter() - t_wall
+    res = sess.results_host()
+    counts = res["counts"].reshape(-1, 8).astype(np.int64)
+
+    for i in range(args.warmup):
+        score_only(i)
+    ms_score = time_calls(score_only, args.steps, torch)
+    for i in range(args.warmup):
+        dense(i)
+    ms_dense = time_calls(dense, args.steps, torch)
+
+    # algorithmic bytes of one layer, from the returned counts
+    n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
+    b_dyn = counts[:, 4]
+    seq_n = np.asarray(wl.seq_lens, dtype=np.int64)
+    k_scan = int(Hkv * d * 2 * seq_n.sum())
+    score_rw = int(2 * Hq * 4 * seq_n.sum())
+    v_rows = int(((n_f + b_dyn) * d * 2).sum())
+    if int(wl.params["target"]) != 0:
+        v_rows += int(((n_f + counts[:, 3]) * d * 2).sum())
+    path_bytes = k_scan + score_rw + v_rows
+    score_kernel_bytes = k_scan + score_rw // 2 + B * Hq * d * 2
+    dense_bytes = 2 * k_scan
+
+    us_layer = ms_step * 1e3
+    out = {
+        "metric": "vattention_decode_us_per_layer",
+        "value": us_layer,
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 K/V, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n": n,
+                   "sink": int(wl.params["sink"]), "window": int(wl.params["window"]),
+                   "topk_frac": float(wl.params["topk_frac"]), "base_frac": float(wl.params["base_frac"]),
+                   "epsilon": float(wl.params["epsilon"]), "delta": float(wl.params["delta"]),
+                   "target": "denominator", "kv_buffers_cycled": nbuf},
+        "tokens_per_s_attention_only": B / (us_layer * 1e-6 * LLAMA8B_LAYERS),
+        "path_hbm_gbps": path_bytes / (ms_step * 1e-3) / 1e9,
+        "path_bytes": path_bytes,
+        "path_frac_of_hbm_peak": path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "dense_decode_us_per_layer": ms_dense * 1e3,
+        "dense_hbm_gbps": dense_bytes / (ms_dense * 1e-3) / 1e9,
+        "speedup_vs_dense": ms_dense / ms_step,
+        "token_density": float(((n_f + b_dyn) / np.repeat(seq_n, Hq)).mean()),
+        "budget_b": {"min": int(b_dyn.min()), "mean": float(b_dyn.mean()), "max": int(b_dyn.max()),
+                     "base_b0_mean": float(counts[:, 3].mean())},
+        "wall_s_timed_region": t_wall,
+        "roofline": {
+            "kernel": "score_kernel (K scan, shared across the GQA group)",
+            "bound": "hbm",
+            "achieved": score_kernel_bytes / (ms_score * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": score_kernel_bytes / (ms_score * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "traffic": None,
+            "bytes_per_launch": score_kernel_bytes,
+            "us_per_launch": ms_score * 1e3,
+        },
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
