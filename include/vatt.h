@@ -99,7 +99,8 @@ typedef struct vatt_plan vatt_plan;
 
 /* Regions of the workspace that tests and tools may want to read (see vatt_plan_workspace_offset). */
 enum {
-  VATT_WS_SCORES = 0 /* float [B, Hq, n_max_padded]: s_i of the last vatt_decode call */
+  VATT_WS_SCORES = 0, /* float [B, Hq, n_max_padded]: s_i of the last vatt_decode call                  */
+  VATT_WS_DEBUG = 1   /* uint64 [512]: phase clock stamps, written only by builds made with -DVATT_TIMING */
 };
 
 /*
@@ -149,7 +150,9 @@ int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment);
  *   out_lse      device, float [B, Hq] or NULL: ln of the estimated denominator, ln(D), of Section 4.1
  *   out_idx      device, int32 [B, Hq, index_capacity]
  *   out_counts   device, int32 [B, Hq, 8] = { |I_s|, |I_l|, |I_t|, |I_bs|, b, n_s, n, flags }
- *                flags bit 0: the final sample needed the slow exact path (informational)
+ *                flags (informational): bit 0 final sample drawn by the slow exact descent, bit 1 base sample
+ *                drawn by an in-kernel sweep instead of the prepared candidate list, bit 2 base sample by the
+ *                slow descent, bit 3 final sample by an in-kernel sweep
  *   out_budget_raw device, double [B, Hq] or NULL: b* before rounding and clamping
  *   out_stats    device, float [B, Hq, 4] or NULL = { D_hat, sigma^2, Tr Sigma, ||N_hat||^2 }, all in the
  *                scale where the largest score of the head has weight 1 (w_i = exp(s_i - max s))

@@ -23,6 +23,7 @@ VATT_E_NO_DEVICE = -5
 VATT_TARGET_D, VATT_TARGET_N, VATT_TARGET_SDPA = 0, 1, 2
 VATT_LAYOUT_CONTIGUOUS, VATT_LAYOUT_PAGED = 0, 1
 VATT_WS_SCORES = 0
+VATT_WS_DEBUG = 1
 VATT_OPT_EXACT_SAMPLER_ONLY = 1
 
 EXPORTS = [

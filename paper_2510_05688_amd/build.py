@@ -18,7 +18,8 @@ FLAGS = [
 
 def _compile(src):
     obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("VATT_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -DVATT_TIMING for phase stamps
+    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "not a recognized feature" not in l)
     if r.returncode != 0:

@@ -8,7 +8,7 @@
 
 namespace vatt {
 
-size_t head_kernel_lds_bytes(int n_max);
+size_t head_kernel_lds_bytes(int n_max, int head_threads);
 
 namespace {
 
@@ -96,20 +96,37 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
 
-  // top-k chunking: a chunk is what one workgroup keeps in registers; the per-head merge holds at most
-  // kSelElems * kHeadThreads candidates
-  const int merge_cap = kSelElems * kHeadThreads;
-  pl.chunk_threads = kChunkThreadsSmall;
-  pl.chunk_len = kChunkThreadsSmall * kSelElems;
-  pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
-  pl.cand_cap = std::max(1, std::min(pl.k_max, pl.chunk_len));
-  if ((int64_t)pl.n_chunks * pl.cand_cap > merge_cap) {
-    pl.chunk_threads = kChunkThreadsLarge;
-    pl.chunk_len = kChunkThreadsLarge * kSelElems;
+  // top-k chunking: a chunk is what one stage-1 workgroup keeps in registers (kChunkElems per thread).
+  // Small workgroups have the lowest per-pass overhead; when a head would then have more candidates than
+  // a small per-head workgroup can merge, chunks (and, if still needed, the merge) use 1024 threads.
+  pl.stage_threads = 256;
+  pl.head_threads = 256;
+  auto set_chunks = [&]() {
+    pl.chunk_len = pl.stage_threads * kChunkElems;
     pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
-    pl.cand_cap = std::max(1, std::min(pl.k_max, pl.chunk_len));
-    if ((int64_t)pl.n_chunks * pl.cand_cap > merge_cap) return VATT_E_UNSUPPORTED_SHAPE;
+    // a chunk may hand over its top-k plus the rest of the last bucket: leave a quarter of headroom
+    pl.cand_cap = std::max(1, std::min(pl.k_max + std::max(64, pl.k_max / 4), pl.chunk_len));
+  };
+  set_chunks();
+  if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads) {
+    pl.stage_threads = 1024;
+    set_chunks();
+    if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads) {
+      pl.head_threads = 1024;
+      if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads)
+        return VATT_E_UNSUPPORTED_SHAPE;
+    }
   }
+  pl.key_slice_len = 8 * pl.stage_threads;  // two Philox blocks (eight tokens) per thread and stream
+  pl.n_key_slices = (n_max + pl.key_slice_len - 1) / pl.key_slice_len;
+  // sampler candidate lists: room for the design count plus six standard deviations, the share of top-k
+  // tokens that stage 1 cannot exclude yet, and slack; a list that would be too long is not built
+  auto key_list_cap = [&](double c) {
+    const double need = (c + 6.0 * (std::sqrt(c) + 1.0) + 8.0) * 1.25 + 64.0;
+    return need > (double)kKeyListMax ? 0 : (int)std::ceil(need);
+  };
+  pl.key_cap[0] = key_list_cap((double)pl.b0_max);
+  pl.key_cap[1] = key_list_cap(2.0 * (double)pl.b0_max + 64.0);
 
   const int heads = p.batch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
@@ -125,7 +142,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.seg_off[3] = pl.seg_off[2] + pl.k_max;
   pl.seg_off[4] = pl.seg_off[3] + pl.b0_max;
   pl.idx_cap = align_up((size_t)(pl.seg_off[4] + pl.b_max), 4);
-  pl.head_lds_bytes = head_kernel_lds_bytes(n_max);
+  pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads);
   if (pl.head_lds_bytes > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
 
   size_t off = 0;
@@ -138,9 +155,11 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.off_chunk_max = take((size_t)heads * pl.n_chunks * sizeof(float));
   pl.off_cand = take((size_t)heads * pl.n_chunks * pl.cand_cap * sizeof(uint64_t));
   pl.off_cand_cnt = take((size_t)heads * pl.n_chunks * sizeof(int32_t));
+  pl.off_key_list = take((size_t)heads * 2 * std::max(1, std::max(pl.key_cap[0], pl.key_cap[1])) * sizeof(uint64_t));
+  pl.off_key_cnt = take((size_t)heads * 2 * sizeof(uint32_t));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
-  pl.off_gather_cnt = take((size_t)heads * sizeof(int32_t));
+  pl.off_debug = take(512 * sizeof(uint64_t));
   pl.off_vstat_part = take((size_t)heads * pl.vstat_splits * (2 * p.head_dim + 2) * sizeof(double));
   pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
   pl.ws_bytes = off;
@@ -221,6 +240,7 @@ size_t vatt_plan_workspace_bytes(const vatt_plan* plan) { return plan ? plan->pl
 size_t vatt_plan_workspace_offset(const vatt_plan* plan, int region) {
   if (!plan) return (size_t)-1;
   if (region == VATT_WS_SCORES) return plan->pl.off_scores;
+  if (region == VATT_WS_DEBUG) return plan->pl.off_debug;
   return (size_t)-1;
 }
 
@@ -262,7 +282,7 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
-  VATT_LAUNCH(launch_chunk_topk(pl, seq_lens, workspace, st));
+  VATT_LAUNCH(launch_stage1(pl, seq_lens, seq_seeds, workspace, st));
   if (pl.p.target == VATT_TARGET_D) {
     VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   } else {

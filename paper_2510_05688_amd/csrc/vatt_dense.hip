@@ -171,22 +171,33 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   }
 }
 
+// Log-sum-exp merge of the per-split partials of one head.  Two thread halves take alternate splits so
+// that their loads are independent and can be in flight together.
 template <int D>
-__global__ __launch_bounds__(D) void dense_merge_kernel(const float* __restrict__ part, int splits, int Hq,
-                                                        float* __restrict__ out_o, float* __restrict__ out_lse) {
+__global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restrict__ part, int splits, int Hq,
+                                                            float* __restrict__ out_o, float* __restrict__ out_lse) {
   const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
-  const int c = threadIdx.x;
+  const int c = threadIdx.x % D, half = threadIdx.x / D;
   const float* p = part + (int64_t)bh * splits * (D + 4);
-  float mall = kNegBig;
-  for (int s = 0; s < splits; ++s) mall = fmaxf(mall, p[s * (D + 4) + D]);
-  float a = 0.f, l = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float sc = __expf(p[s * (D + 4) + D] - mall);
-    a += p[s * (D + 4) + c] * sc;
-    l += p[s * (D + 4) + D + 1] * sc;
+  __shared__ float s_m[128], s_l[128], s_a[D];
+  for (int s = threadIdx.x; s < splits; s += 2 * D) {
+    s_m[s] = p[s * (D + 4) + D];
+    s_l[s] = p[s * (D + 4) + D + 1];
   }
-  out_o[(int64_t)bh * D + c] = a / l;
-  if (c == 0 && out_lse) out_lse[bh] = mall + logf(l);
+  __syncthreads();
+  float mall = kNegBig;
+  for (int s = 0; s < splits; ++s) mall = fmaxf(mall, s_m[s]);
+  float a = 0.f;
+#pragma unroll 8
+  for (int s = half; s < splits; s += 2) a += p[s * (D + 4) + c] * __expf(s_m[s] - mall);
+  if (half == 1) s_a[c] = a;
+  __syncthreads();
+  if (half == 0) {
+    float l = 0.f;
+    for (int s = 0; s < splits; ++s) l += s_l[s] * __expf(s_m[s] - mall);
+    out_o[(int64_t)bh * D + c] = (a + s_a[c]) / l;
+    if (c == 0 && out_lse) out_lse[bh] = mall + logf(l);
+  }
 }
 
 template <int D, int G>
@@ -199,7 +210,7 @@ hipError_t launch_dense_dg(const Plan& pl, DenseArgs& A, hipStream_t st) {
     hipLaunchKernelGGL((dense_kernel<D, G, false>), grid, dim3(kDenseThreads), 0, st, A);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(D), 0, st, A.part, pl.dense_splits,
+  hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(2 * D), 0, st, A.part, pl.dense_splits,
                      p.n_q_heads, A.out_o, A.out_lse);
   return hipGetLastError();
 }

@@ -8,6 +8,21 @@ namespace vatt {
 
 constexpr int kWave = 64;
 
+// Optional phase timing for kernel development: built with -DVATT_TIMING, thread 0 of workgroup 0 stores
+// the shader clock at numbered points into the VATT_WS_DEBUG region of the workspace.  Compiled out
+// otherwise.
+#ifdef VATT_TIMING
+#define VATT_STAMP(buf, id)                                                               \
+  do {                                                                                    \
+    if ((buf) && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) \
+      (buf)[id] = __builtin_readcyclecounter();                                           \
+  } while (0)
+#else
+#define VATT_STAMP(buf, id) \
+  do {                      \
+  } while (0)
+#endif
+
 // ---------------------------------------------------------------------------
 // KV cache addressing.  Contiguous: [B, Hkv, n_max, d].  Paged: [blocks, Hkv, page, d]
 // with a block table [B, pages_per_seq].
@@ -58,6 +73,51 @@ __device__ __forceinline__ float group_sum(float v) {
   v += dpp_f32<0x4E>(v);   // quad_perm [2,3,0,1]: partner lane ^ 2
   v += dpp_f32<0x141>(v);  // row_half_mirror: the other quad of the 8-lane half
   if constexpr (LANES == 16) v += dpp_f32<0x140>(v);  // row_mirror: the other half of the 16-lane row
+  return v;
+}
+
+// Wave-wide sum of a 32-bit integer, returned as a wave-uniform value: four DPP adds leave each row of
+// 16 lanes with its row sum, four lane reads add the rows.  Every lane of the wave must be active.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  v += dpp_u32<0xB1>(v);
+  v += dpp_u32<0x4E>(v);
+  v += dpp_u32<0x141>(v);
+  v += dpp_u32<0x140>(v);
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+         (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  v = min(v, dpp_u32<0xB1>(v));
+  v = min(v, dpp_u32<0x4E>(v));
+  v = min(v, dpp_u32<0x141>(v));
+  v = min(v, dpp_u32<0x140>(v));
+  return min(min((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
+             min((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, dpp_u32<0xB1>(v));
+  v = max(v, dpp_u32<0x4E>(v));
+  v = max(v, dpp_u32<0x141>(v));
+  v = max(v, dpp_u32<0x140>(v));
+  return max(max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
+             max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave on the DPP path: shifts by 1, 2, 4, 8 inside each row of
+// 16 lanes (lanes shifted in from outside the row read 0), then the last lane of row 0/2 is added to row
+// 1/3 and the last lane of the lower half to the upper half.  Every lane of the wave must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
   return v;
 }
 

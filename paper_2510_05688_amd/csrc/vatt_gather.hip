@@ -6,8 +6,9 @@
 // SDPA targets (N_f, sum r_i and sum ||r_i||^2 over the base sample, r_i = w_i V[i]).
 //
 // grid = (splits, query heads, sequences).  A workgroup walks its slice of the head's token list 16 rows
-// (d = 128) at a time: d/8 adjacent lanes read one 256-byte V row with one 16-byte load each.  The last
-// workgroup of a head to finish adds the per-split partials in split order and writes O and ln D.
+// (d = 128) at a time: d/8 adjacent lanes read one 256-byte V row with one 16-byte load each.  With more
+// than one split per head a small second kernel adds the per-split partials in split order and writes
+// O and ln D (a kernel boundary is the cheapest device-wide ordering point on this chip).
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -20,7 +21,6 @@ struct GatherArgs {
   const HeadRec* head_rec;
   const int32_t* idx;
   float* part;        // [B*Hq][splits][d + 4]
-  int32_t* counters;  // [B*Hq], zeroed by the per-head kernel
   double* vpart;      // [B*Hq][splits][2d + 2]
   float* out_o;
   float* out_lse;
@@ -136,7 +136,6 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   __shared__ float s_acc[WAVES][D];
   __shared__ float s_acc2[STATS ? WAVES : 1][STATS ? D : 1];
   __shared__ float s_d[WAVES], s_r2[WAVES];
-  __shared__ int s_last;
   if (rsub == 0) {
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
@@ -173,37 +172,44 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   }
 
   float* part = A.part + ((int64_t)bh * A.splits + split) * (D + 4);
+  float dtot = 0.f;
+#pragma unroll
+  for (int w2 = 0; w2 < WAVES; ++w2) dtot += s_d[w2];
   if (tid < D) {
     float a = 0.f;
 #pragma unroll
     for (int w2 = 0; w2 < WAVES; ++w2) a += s_acc[w2][tid];
-    part[tid] = a;
+    if (A.splits == 1) {
+      A.out_o[(int64_t)bh * D + tid] = a / dtot;  // one workgroup per head: finished here
+    } else {
+      part[tid] = a;
+    }
   }
   if (tid == 0) {
-    float t = 0.f;
-#pragma unroll
-    for (int w2 = 0; w2 < WAVES; ++w2) t += s_d[w2];
-    part[D] = t;
+    if (A.splits == 1) {
+      if (A.out_lse) A.out_lse[bh] = r.m + logf(dtot);
+    } else {
+      part[D] = dtot;
+    }
   }
-  // publish the partial, then take a ticket; the last workgroup of the head reduces
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int ticket = __hip_atomic_fetch_add(&A.counters[bh], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (ticket == A.splits - 1) ? 1 : 0;
+}
+
+// Adds the per-split partial sums of a head in split order: O = N / D, lse = m + ln D.
+template <int D>
+__global__ __launch_bounds__(D) void gather_merge_kernel(const float* __restrict__ part,
+                                                         const HeadRec* __restrict__ head_rec, int splits, int Hq,
+                                                         float* __restrict__ out_o, float* __restrict__ out_lse) {
+  const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
+  const int c = threadIdx.x;
+  const float* p = part + (int64_t)bh * splits * (D + 4);
+  float a = 0.f, dtot = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < splits; ++s) {
+    a += p[s * (D + 4) + c];
+    dtot += p[s * (D + 4) + D];
   }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  const float* all = A.part + (int64_t)bh * A.splits * (D + 4);
-  float dtot = 0.f;
-  for (int s = 0; s < A.splits; ++s) dtot += __hip_atomic_load(all + s * (D + 4) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (tid < D) {
-    float a = 0.f;
-    for (int s = 0; s < A.splits; ++s) a += __hip_atomic_load(all + s * (D + 4) + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    A.out_o[(int64_t)bh * D + tid] = a / dtot;
-  }
-  if (tid == 0 && A.out_lse) A.out_lse[bh] = r.m + logf(dtot);
+  out_o[(int64_t)bh * D + c] = a / dtot;
+  if (c == 0 && out_lse) out_lse[bh] = head_rec[bh].m + logf(dtot);
 }
 
 template <int D, bool STATS>
@@ -219,7 +225,6 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   A.head_rec = reinterpret_cast<const HeadRec*>(w + pl.off_head_rec);
   A.idx = out_idx;
   A.part = reinterpret_cast<float*>(w + pl.off_gather_part);
-  A.counters = reinterpret_cast<int32_t*>(w + pl.off_gather_cnt);
   A.vpart = reinterpret_cast<double*>(w + pl.off_vstat_part);
   A.out_o = out_o;
   A.out_lse = out_lse;
@@ -236,6 +241,10 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
     hipLaunchKernelGGL((gather_kernel<D, true, STATS>), grid, dim3(kGatherThreads), 0, st, A);
   else
     hipLaunchKernelGGL((gather_kernel<D, false, STATS>), grid, dim3(kGatherThreads), 0, st, A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || STATS || A.splits == 1) return e;
+  hipLaunchKernelGGL((gather_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(D), 0, st, A.part, A.head_rec,
+                     A.splits, p.n_q_heads, out_o, out_lse);
   return hipGetLastError();
 }
 

@@ -11,11 +11,10 @@
 namespace vatt {
 
 constexpr int kScoreTile = 256;       // keys per score-kernel workgroup
-constexpr int kSelElems = 32;         // composites a thread keeps in registers during a select
-constexpr int kChunkThreadsSmall = 256;
-constexpr int kChunkThreadsLarge = 1024;
-constexpr int kHeadThreads = 1024;    // workgroup size of the per-head kernel
-constexpr int kListCap = 4096;        // LDS list of uncertain sampling candidates
+constexpr int kChunkElems = 32;       // score-row elements a thread holds while a chunk's top-k is selected
+constexpr int kMergeElemsMax = 32;    // top-k candidates a thread holds while a head merges them
+constexpr int kListCap = 4096;        // LDS list of the in-kernel sampler sweep
+constexpr int kKeyListMax = 8192;     // largest sampler candidate list stage 1 may build per (head, stream)
 constexpr int kGatherThreads = 256;
 constexpr int kDenseThreads = 256;
 
@@ -39,22 +38,26 @@ struct Plan {
   // sizes
   int n_pad;          // score row stride (floats)
   int k_max, b0_max, b_max;
-  int chunk_threads, chunk_len, n_chunks, cand_cap;  // top-k chunking
+  int stage_threads, chunk_len, n_chunks, cand_cap;  // top-k chunking (stage 1 workgroup size, chunk length)
+  int key_slice_len, n_key_slices;                    // sampler key generation
+  int head_threads;                                   // workgroup size of the per-head kernel
+  int key_cap[2];     // capacity of the sampler candidate list of stream 0 / 1 (0 = not built)
   int gather_splits, dense_splits, vstat_splits;
   size_t idx_cap;
   int64_t seg_off[5];
   size_t head_lds_bytes;
   int force_slow_sampler;  // test hook: skip the sampler's fast path
   // workspace offsets (bytes)
-  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_head_rec, off_gather_part,
-      off_gather_cnt, off_vstat_part, off_dense_part, ws_bytes;
+  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_key_list, off_key_cnt, off_head_rec, off_gather_part,
+      off_debug, off_vstat_part, off_dense_part, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };
 
 // Every launcher returns a hipError_t from hipGetLastError() after the launch.
 hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                         const int32_t* seq_lens, void* ws, hipStream_t st);
-hipError_t launch_chunk_topk(const Plan& pl, const int32_t* seq_lens, void* ws, hipStream_t st);
+hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
+                         hipStream_t st);
 // phase 0: everything (target D); phase 1: through the base sample; phase 2: budget and final sample.
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
