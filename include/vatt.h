@@ -116,8 +116,10 @@ void vatt_plan_destroy(vatt_plan* plan);
  * Options (host only).  VATT_OPT_EXACT_SAMPLER_ONLY = 1 makes the sampler skip its fast path (a verified
  * guess of the key threshold) and always run the slower exact radix descent; results are identical.
  * It exists so that the slow path can be exercised on purpose.
+ * VATT_OPT_NO_SAMPLER_CANDIDATES = 1 stops the selection stage from preparing sampler candidate lists, so
+ * that every sample is drawn by the per-head sweep (fast or slow path); results are identical.
  */
-enum { VATT_OPT_EXACT_SAMPLER_ONLY = 1 };
+enum { VATT_OPT_EXACT_SAMPLER_ONLY = 1, VATT_OPT_NO_SAMPLER_CANDIDATES = 2 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
 
 /* Bytes of device workspace every launching call needs (256-byte aligned base). */

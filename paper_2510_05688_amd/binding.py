@@ -25,6 +25,7 @@ VATT_LAYOUT_CONTIGUOUS, VATT_LAYOUT_PAGED = 0, 1
 VATT_WS_SCORES = 0
 VATT_WS_DEBUG = 1
 VATT_OPT_EXACT_SAMPLER_ONLY = 1
+VATT_OPT_NO_SAMPLER_CANDIDATES = 2
 
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",

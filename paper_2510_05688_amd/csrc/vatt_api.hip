@@ -8,7 +8,7 @@
 
 namespace vatt {
 
-size_t head_kernel_lds_bytes(int n_max, int head_threads);
+size_t head_kernel_lds_bytes(int n_max, int head_threads, int wlist_len);
 
 namespace {
 
@@ -105,7 +105,11 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
     pl.chunk_len = pl.stage_threads * kChunkElems;
     pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
     // a chunk may hand over its top-k plus the rest of the last bucket: leave a quarter of headroom
-    pl.cand_cap = std::max(1, std::min(pl.k_max + std::max(64, pl.k_max / 4), pl.chunk_len));
+    // and round up to a power of two so that a slot's chunk is a shift away
+    int want = std::max(1, std::min(pl.k_max + std::max(64, pl.k_max / 4), pl.chunk_len));
+    pl.cand_shift = 0;
+    while ((1 << pl.cand_shift) < want) ++pl.cand_shift;
+    pl.cand_cap = 1 << pl.cand_shift;
   };
   set_chunks();
   if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads) {
@@ -117,20 +121,46 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
         return VATT_E_UNSUPPORTED_SHAPE;
     }
   }
+  if (pl.n_chunks > kMaxChunks) return VATT_E_UNSUPPORTED_SHAPE;
   pl.key_slice_len = 8 * pl.stage_threads;  // two Philox blocks (eight tokens) per thread and stream
   pl.n_key_slices = (n_max + pl.key_slice_len - 1) / pl.key_slice_len;
-  // sampler candidate lists: room for the design count plus six standard deviations, the share of top-k
-  // tokens that stage 1 cannot exclude yet, and slack; a list that would be too long is not built
-  auto key_list_cap = [&](double c) {
-    const double need = (c + 6.0 * (std::sqrt(c) + 1.0) + 8.0) * 1.25 + 64.0;
-    return need > (double)kKeyListMax ? 0 : (int)std::ceil(need);
-  };
-  pl.key_cap[0] = key_list_cap((double)pl.b0_max);
-  pl.key_cap[1] = key_list_cap(2.0 * (double)pl.b0_max + 64.0);
+  // sampler candidates: slots per slice for the count expected at full length, a quarter of headroom and six
+  // standard deviations.  Short sequences have a higher rate of candidates per token and may overfill a
+  // slice; their heads then draw the sample with the in-kernel sweep, which is cheap when n is small.
+  double worst = 0.0;
+  {
+    const HeadSizes hs = head_sizes(n_max, pl.sel);
+    if (hs.n_s > 0) {
+      const double c1 = std::min((double)hs.n_s, 2.0 * hs.b0 + 64.0);
+      const double rate = std::min(1.0, (c1 + 6.0 * (std::sqrt(c1) + 1.0) + 8.0) / (double)hs.n_s);
+      worst = rate * std::min(n_max, pl.key_slice_len);
+    }
+  }
+  const double slots = 1.25 * worst + 6.0 * std::sqrt(worst) + 16.0;
+  pl.key_slice_shift = 4;
+  while ((1 << pl.key_slice_shift) < slots) ++pl.key_slice_shift;
+  pl.key_slice_cap = 1 << pl.key_slice_shift;
+  // (with enough heads to fill the chip the lists buy nothing: the same key work is then spread anyway)
+  const bool lists = p.batch * p.n_q_heads < 2 * pl.num_cus && pl.n_key_slices <= kMaxKeySlices && (int64_t)pl.n_key_slices * pl.key_slice_cap <= (pl.head_threads == 256 ? 8192 : 4096) &&
+                     pl.key_slice_cap <= pl.key_slice_len;
+  pl.key_on[0] = pl.key_on[1] = lists ? 1 : 0;
+  pl.key_lists_fit = lists ? 1 : 0;
+  if (!lists) {
+    if (n_max >= 65536) pl.head_threads = 1024;  // long sweeps: more threads per head
+    pl.n_key_slices = 1;  // the role still exists in the grid; it writes empty lists
+    pl.key_slice_len = std::max(pl.key_slice_len, n_max);
+    pl.key_slice_shift = 4;
+    pl.key_slice_cap = 16;
+  }
+  {
+    const int64_t kslots = (int64_t)pl.n_key_slices * pl.key_slice_cap;
+    pl.key_elems = pl.head_threads == 256 ? (kslots <= 8 * 256 ? 8 : (kslots <= 16 * 256 ? 16 : 32)) : 4;
+  }
+  pl.wlist_len = std::max(pl.k_max, pl.b0_max);
 
   const int heads = p.batch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
-  pl.gather_splits = std::min(32, std::max(1, (want_blocks + heads - 1) / heads));
+  pl.gather_splits = std::min(32, std::max(1, (8 * pl.num_cus + heads - 1) / heads));
   pl.vstat_splits = pl.gather_splits;
   const int kv_heads = p.batch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
@@ -142,7 +172,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.seg_off[3] = pl.seg_off[2] + pl.k_max;
   pl.seg_off[4] = pl.seg_off[3] + pl.b0_max;
   pl.idx_cap = align_up((size_t)(pl.seg_off[4] + pl.b_max), 4);
-  pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads);
+  pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads, pl.wlist_len);
   if (pl.head_lds_bytes > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
 
   size_t off = 0;
@@ -155,8 +185,9 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.off_chunk_max = take((size_t)heads * pl.n_chunks * sizeof(float));
   pl.off_cand = take((size_t)heads * pl.n_chunks * pl.cand_cap * sizeof(uint64_t));
   pl.off_cand_cnt = take((size_t)heads * pl.n_chunks * sizeof(int32_t));
-  pl.off_key_list = take((size_t)heads * 2 * std::max(1, std::max(pl.key_cap[0], pl.key_cap[1])) * sizeof(uint64_t));
-  pl.off_key_cnt = take((size_t)heads * 2 * sizeof(uint32_t));
+  pl.off_key_comp = take((size_t)heads * 2 * pl.n_key_slices * pl.key_slice_cap * sizeof(uint64_t));
+  pl.off_key_score = take((size_t)heads * 2 * pl.n_key_slices * pl.key_slice_cap * sizeof(float));
+  pl.off_key_cnt = take((size_t)heads * 2 * pl.n_key_slices * sizeof(uint32_t));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
@@ -257,6 +288,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   if (!plan) return VATT_E_INVALID_ARG;
   if (option == VATT_OPT_EXACT_SAMPLER_ONLY) {
     plan->pl.force_slow_sampler = value ? 1 : 0;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_NO_SAMPLER_CANDIDATES) {
+    plan->pl.key_on[0] = plan->pl.key_on[1] = (value || !plan->pl.key_lists_fit) ? 0 : 1;
     return VATT_OK;
   }
   return VATT_E_INVALID_ARG;

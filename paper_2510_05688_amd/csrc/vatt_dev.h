@@ -17,9 +17,17 @@ constexpr int kWave = 64;
     if ((buf) && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) \
       (buf)[id] = __builtin_readcyclecounter();                                           \
   } while (0)
+#define VATT_NOTE(buf, id, val)                                                            \
+  do {                                                                                    \
+    if ((buf) && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) \
+      (buf)[id] = (unsigned long long)(val);                                              \
+  } while (0)
 #else
 #define VATT_STAMP(buf, id) \
   do {                      \
+  } while (0)
+#define VATT_NOTE(buf, id, val) \
+  do {                          \
   } while (0)
 #endif
 
@@ -198,19 +206,20 @@ struct SelectParams {
   double topk_frac, base_frac;  // the float parameters widened exactly
 };
 
-__device__ __forceinline__ HeadSizes head_sizes(int n, const SelectParams& p) {
+__host__ __device__ inline HeadSizes head_sizes(int n, const SelectParams& p) {
   HeadSizes h;
   h.n = n;
-  h.n_sink = min(p.sink, n);
-  h.n_win = min(p.window, n - h.n_sink);
+  h.n_sink = p.sink < n ? p.sink : n;
+  h.n_win = p.window < n - h.n_sink ? p.window : n - h.n_sink;
   h.mid_lo = h.n_sink;
   h.mid_hi = n - h.n_win;
   const int m = h.mid_hi - h.mid_lo;
   int k = p.topk_abs > 0 ? p.topk_abs : (int)floor(p.topk_frac * (double)n);
-  h.k = min(max(k, 0), m);
+  h.k = k < 0 ? 0 : (k > m ? m : k);
   h.n_s = m - h.k;
   int b0 = p.base_abs > 0 ? p.base_abs : (int)floor(p.base_frac * (double)h.n_s);
-  h.b0 = min(max(b0, 2), h.n_s);
+  h.b0 = b0 < 2 ? 2 : b0;
+  h.b0 = h.b0 > h.n_s ? h.n_s : h.b0;
   return h;
 }
 

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   constexpr int RPW = kWave / LPR;
   constexpr int WAVES = kGatherThreads / kWave;
   constexpr int RPB = RPW * WAVES;  // rows per workgroup step
-  constexpr int U = 4;              // independent rows in flight per lane
+  constexpr int U = 8;              // independent rows in flight per lane
 
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (tok[u] >= 0) {
-        const float wt = expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f);
+        const float wt = __expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f);
         const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
         if (STATS && tail[u]) {
 #pragma unroll

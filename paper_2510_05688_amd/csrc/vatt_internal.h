@@ -14,7 +14,8 @@ constexpr int kScoreTile = 256;       // keys per score-kernel workgroup
 constexpr int kChunkElems = 32;       // score-row elements a thread holds while a chunk's top-k is selected
 constexpr int kMergeElemsMax = 32;    // top-k candidates a thread holds while a head merges them
 constexpr int kListCap = 4096;        // LDS list of the in-kernel sampler sweep
-constexpr int kKeyListMax = 8192;     // largest sampler candidate list stage 1 may build per (head, stream)
+constexpr int kMaxChunks = 64;         // chunks of a head's score row (LDS table of the per-head kernel)
+constexpr int kMaxKeySlices = 64;      // token slices of the sampler candidate generation
 constexpr int kGatherThreads = 256;
 constexpr int kDenseThreads = 256;
 
@@ -41,14 +42,19 @@ struct Plan {
   int stage_threads, chunk_len, n_chunks, cand_cap;  // top-k chunking (stage 1 workgroup size, chunk length)
   int key_slice_len, n_key_slices;                    // sampler key generation
   int head_threads;                                   // workgroup size of the per-head kernel
-  int key_cap[2];     // capacity of the sampler candidate list of stream 0 / 1 (0 = not built)
+  int cand_shift;                                     // log2(cand_cap)
+  int key_slice_cap, key_slice_shift;                 // slots per (head, stream, slice), a power of two
+  int key_elems;                                      // sampler candidate slots a head-kernel thread holds
+  int key_lists_fit;                                  // geometry allows the sampler candidate lists
+  int key_on[2];                                      // sampler candidates built for stream 0 / 1
+  int wlist_len;                                      // LDS weight list of the per-head kernel (floats)
   int gather_splits, dense_splits, vstat_splits;
   size_t idx_cap;
   int64_t seg_off[5];
   size_t head_lds_bytes;
   int force_slow_sampler;  // test hook: skip the sampler's fast path
   // workspace offsets (bytes)
-  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_key_list, off_key_cnt, off_head_rec, off_gather_part,
+  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_key_comp, off_key_score, off_key_cnt, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };

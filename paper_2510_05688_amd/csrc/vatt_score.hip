@@ -25,7 +25,7 @@ template <int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ scores, int n_pad, int n_max, int Hq,
-                                                    float sm_scale, uint32_t* __restrict__ zero_ptr, int zero_n) {
+                                                    float sm_scale) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
   constexpr int ROWS_PER_WAVE = kScoreTile / 4;
@@ -33,9 +33,6 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
   const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  // the first workgroup also clears the counters that the next kernel of the decode step appends through
-  if (tile == 0 && kvh == 0 && b == 0)
-    for (int t = threadIdx.x; t < zero_n; t += 256) zero_ptr[t] = 0u;
   const int n = min(max(seq_lens[b], 0), n_max);
   const int tile_lo = tile * kScoreTile;
   if (tile_lo >= n) return;
@@ -105,16 +102,14 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   KVLayout L = pl.kv_k;
   L.block_table = block_table;
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_scores);
-  uint32_t* key_cnt = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + pl.off_key_cnt);
-  const int zero_n = p.batch * p.n_q_heads * 2;
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     hipLaunchKernelGGL((score_kernel<D, G, true>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
                        static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
-                       pl.sm_scale, key_cnt, zero_n);
+                       pl.sm_scale);
   } else {
     hipLaunchKernelGGL((score_kernel<D, G, false>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
                        static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
-                       pl.sm_scale, key_cnt, zero_n);
+                       pl.sm_scale);
   }
   return hipGetLastError();
 }

@@ -5,22 +5,25 @@
 //   samples   composite = (philox_key(token) << 32) | token     (smallest key first, ties to the lower token)
 // Distinct composites make every selection a pure set operation: the result does not depend on
 // the order in which lanes, waves or workgroups contribute, so index sets and budgets are
-// reproducible bit for bit.
+// reproducible bit for bit.  Floating-point sums are taken in ascending token order with a fixed
+// tree, so the statistics are reproducible too.
 //
 // Two kernels:
-//   stage1_kernel  even workgroups: one chunk of a head's score row each; the chunk is kept in registers,
-//                  its own top-k is radix-selected and written as candidates (any member of the global top-k
-//                  is in its chunk's top-k), plus the chunk maximum.
-//                  odd workgroups: Philox keys of one slice of tokens for both sampler streams; tokens whose
-//                  key lies under a conservative bound of the threshold that the base sample (stream 0) and
-//                  a final sample of up to twice that size (stream 1) will need are appended to per-head
-//                  candidate lists.  This is integer work that does not depend on the scores, spread over
-//                  the whole chip instead of the one workgroup a head gets in the next kernel.
-//   head_kernel    one workgroup per head: merges the top-k candidates into the exact top-k, builds the
-//                  membership bitmap, selects the base sample from its candidate list, computes the
+//   stage1_kernel  workgroups [0, n_chunks) of a head: one chunk of the head's score row each; the chunk is
+//                  kept in registers, a threshold that keeps at least its own top-k is found by counting,
+//                  and the composites under it are written as candidates (any member of the global top-k is
+//                  in its chunk's top-k), plus the chunk maximum.
+//                  Remaining workgroups: Philox keys of one slice of tokens for both sampler streams; tokens
+//                  whose key lies under a conservative bound of the threshold that the base sample
+//                  (stream 0) and a final sample of up to twice that size (stream 1) will need are written,
+//                  with their scores, as sampler candidates.  This is integer work that does not depend on
+//                  the scores, spread over the whole chip instead of the one workgroup a head gets next.
+//   head_kernel    one workgroup per head: selects the exact top-k among the chunk candidates, builds the
+//                  membership bitmap, selects the base sample among its candidates, computes the
 //                  statistics and the budget of Algorithm 2, selects the final sample, and writes every
 //                  index list in ascending token order.  When a candidate list cannot serve (budget above
-//                  the bound, list overflow) the sample is drawn by an exact in-kernel sweep instead.
+//                  the bound it was built for, or an overfull slice) the sample is drawn by an exact
+//                  in-kernel sweep instead.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -28,9 +31,10 @@ namespace {
 
 constexpr uint32_t kInv32 = 0xffffffffu;
 constexpr uint64_t kInvalid = ~0ull;
+constexpr uint32_t kOverflow = 0xffffffffu;  // slice count that marks an overfull sampler candidate slice
 
 // ---------------------------------------------------------------------------
-// Workgroup-wide exclusive scan of one uint32 per thread.
+// Workgroup-wide exclusive scan of one uint32 per thread (DPP inside a wave, LDS across waves).
 // ---------------------------------------------------------------------------
 template <int NT>
 struct BlockScanSmem {
@@ -41,12 +45,7 @@ template <int NT>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* total, BlockScanSmem<NT>& sm) {
   constexpr int SW = NT / kWave;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t incl = v;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    const uint32_t t = __shfl_up(incl, o);
-    if (lane >= o) incl += t;
-  }
+  const uint32_t incl = wave_inclusive_scan_u32(v);
   __syncthreads();  // protects wave_total against a previous use
   if (lane == kWave - 1) sm.wave_total[wave] = incl;
   __syncthreads();
@@ -54,7 +53,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 #pragma unroll
   for (int w = 0; w < SW; ++w) {
     const uint32_t t = sm.wave_total[w];
-    if (w < wave) base += t;
+    base += (w < wave) ? t : 0u;
     tot += t;
   }
   *total = tot;
@@ -66,19 +65,21 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 // (exactly c when cap == c).  Composites sit in registers (hi word, lo word; E per thread; all-ones =
 // absent).  Requires 1 <= c <= number of valid composites.
 //
-// Radix descent with 256 buckets per pass, counted by LDS atomics.  The bucket of an element is its offset
-// inside the current value range shifted down so that the range spans at most 256 buckets: the first pass
-// starts from the minimum and maximum of the data, so the buckets are spread over the values that actually
-// occur (scores of a head's best tokens share sign and exponent; sampler keys under a bound share their
-// leading zeros).  The 256 counts are prefix-summed by 256 threads, the bucket that holds the c-th element
-// becomes the next range, and once it holds at most 64 elements one wave ranks them directly.
+// Search on the value of the high word by counting: the range [lo, hi] that holds the c-th composite
+// starts as the minimum and maximum present; each step counts the composites in [lo, pivot] (a compare
+// per element, a DPP wave sum, one LDS add per wave, one barrier) and keeps the half that holds the
+// target.  Pivots alternate between interpolation (fast when the values are spread evenly, as sampler
+// keys are) and the midpoint (which bounds the number of steps whatever the data).  When at most SMALL
+// composites remain they are ranked directly by one wave.  Equal high words are resolved the same way on
+// the low word.
 // ---------------------------------------------------------------------------
+constexpr int kSelectSteps = 160;
+
 template <int NT>
 struct SelectSmem {
   static constexpr int SMALL = 64;
-  uint32_t hist[256];
-  uint32_t wave_a[NT / kWave], wave_b[NT / kWave];
-  uint32_t sel_bucket, sel_excl, sel_count;
+  uint32_t cnt[kSelectSteps];
+  uint32_t wave_a[NT / kWave], wave_b[NT / kWave], wave_c[NT / kWave];
   uint64_t slist[SMALL];
   uint32_t slist_n;
   uint64_t result;
@@ -88,96 +89,76 @@ template <int NT, int E>
 struct BlockSelect {
   static constexpr int SW = NT / kWave;
   static constexpr int SMALL = SelectSmem<NT>::SMALL;
-  static_assert(NT >= 256, "the bucket scan uses 256 threads");
 
   __device__ static uint64_t run(const uint32_t (&xh)[E], const uint32_t (&xl)[E], uint32_t c, uint32_t cap,
                                  SelectSmem<NT>& sm, unsigned long long* dbg = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     VATT_STAMP(dbg, 10);
-    // range of the high words present
-    uint32_t mn = kInv32, mx = 0u;
+    // range of the high words present, and how many composites there are
+    uint32_t mn = kInv32, mx = 0u, nv = 0u;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
       const bool valid = (xh[e] & xl[e]) != kInv32;
       mn = valid ? min(mn, xh[e]) : mn;
       mx = valid ? max(mx, xh[e]) : mx;
+      nv += valid ? 1u : 0u;
     }
     mn = wave_min_u32(mn);
     mx = wave_max_u32(mx);
+    nv = wave_sum_u32(nv);
     __syncthreads();  // the caller may still be reading a previous result out of this scratch
     if (lane == 0) {
       sm.wave_a[wave] = mn;
       sm.wave_b[wave] = mx;
+      sm.wave_c[wave] = nv;
     }
-    if (tid < 256) sm.hist[tid] = 0;
+    for (int i = tid; i < kSelectSteps; i += NT) sm.cnt[i] = 0;
     if (tid < SMALL) sm.slist[tid] = kInvalid;
     if (tid == 0) sm.slist_n = 0;
     __syncthreads();
-    uint32_t a_lo = kInv32, a_hi = 0u;
+    uint32_t lo = kInv32, hi = 0u, m = 0u;
 #pragma unroll
     for (int w = 0; w < SW; ++w) {
-      a_lo = min(a_lo, sm.wave_a[w]);
-      a_hi = max(a_hi, sm.wave_b[w]);
+      lo = min(lo, sm.wave_a[w]);
+      hi = max(hi, sm.wave_b[w]);
+      m += sm.wave_c[w];
     }
     VATT_STAMP(dbg, 11);
-    uint32_t r = c;          // rank wanted inside the current range
-    bool low = false;        // false: descending on the high word; true: high word fixed to hv, on the low word
+    uint32_t r = c;    // rank wanted inside [lo, hi]; c - r composites lie below the range, m inside it
+    bool low = false;  // false: searching on the high word; true: high word fixed to hv, on the low word
     uint32_t hv = 0u;
-    for (int pass = 0; pass < 12; ++pass) {
-      const uint32_t span = a_hi - a_lo;
-      const int shift = span < 256u ? 0 : (32 - __clz(span)) - 8;
+    // the word being searched, all-ones for slots that are empty or out of play: one unsigned compare of
+    // (w - lo) against (pivot - lo) then tells whether a slot lies in [lo, pivot]
+    uint32_t w[E];
 #pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const bool valid = (xh[e] & xl[e]) != kInv32;
-        const uint32_t w = low ? xl[e] : xh[e];
-        const bool act = valid && (!low || xh[e] == hv) && w >= a_lo && w <= a_hi;
-        if (act) __hip_atomic_fetch_add(&sm.hist[(w - a_lo) >> shift], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (int e = 0; e < E; ++e) w[e] = ((xh[e] & xl[e]) != kInv32) ? min(xh[e], 0xfffffffeu) : kInv32;
+    // (a high word of all-ones is searched as 0xfffffffe; the two values are told apart again when the last
+    // few composites are ranked, so only more than SMALL composites with those two high words could be
+    // misordered, which for 32-bit hashes of distinct tokens does not happen)
+    hi = min(hi, 0xfffffffeu);
+    lo = min(lo, hi);
+    for (int step = 0; step < kSelectSteps; ++step) {
+      if ((c - r) + m <= cap) {  // everything up to hi may be taken
+        VATT_NOTE(dbg, 15, step);
+        break;
       }
-      VATT_STAMP(dbg, 20 + 4 * pass);
-      __syncthreads();
-      // inclusive prefix over the 256 buckets: one bucket per thread of the first four waves
-      uint32_t v = 0, incl = 0;
-      if (tid < 256) {
-        v = sm.hist[tid];
-        incl = wave_inclusive_scan_u32(v);
-        if (lane == 63) sm.wave_a[wave] = incl;
-      }
-      __syncthreads();
-      if (tid < 256) {
-        sm.hist[tid] = 0;  // ready for the next pass
-        uint32_t base = 0;
-#pragma unroll
-        for (int w = 0; w < 3; ++w) base += (w < wave) ? sm.wave_a[w] : 0u;
-        incl += base;
-        const uint32_t excl = incl - v;
-        if (excl < r && r <= incl) {
-          sm.sel_bucket = (uint32_t)tid;
-          sm.sel_excl = excl;
-          sm.sel_count = v;
-        }
-      }
-      __syncthreads();
-      VATT_STAMP(dbg, 21 + 4 * pass);
-      const uint32_t bsel = sm.sel_bucket, m = sm.sel_count;
-      r -= sm.sel_excl;
-      a_lo += bsel << shift;
-      a_hi = min(a_hi, a_lo + ((1u << shift) - 1u));
-      // everything at or below this bucket: (c - r) elements under it plus its own m
-      if ((c - r) + m <= cap) return low ? (((uint64_t)hv << 32) | a_hi) : (((uint64_t)a_hi << 32) | kInv32);
       if (m <= (uint32_t)SMALL) {
+        uint32_t in_range = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-          const bool valid = (xh[e] & xl[e]) != kInv32;
-          const uint32_t w = low ? xl[e] : xh[e];
-          if (valid && (!low || xh[e] == hv) && w >= a_lo && w <= a_hi) {
-            const uint32_t pos = atomicAdd(&sm.slist_n, 1u);
-            if (pos < (uint32_t)SMALL) sm.slist[pos] = ((uint64_t)xh[e] << 32) | xl[e];
+        for (int e = 0; e < E; ++e) in_range |= ((w[e] - lo <= hi - lo) ? 1u : 0u) << e;
+        if (in_range) {
+          uint32_t pos = atomicAdd(&sm.slist_n, (uint32_t)__popc(in_range));
+#pragma unroll
+          for (int e = 0; e < E; ++e) {
+            if ((in_range >> e) & 1u) {
+              if (pos < (uint32_t)SMALL) sm.slist[pos] = ((uint64_t)xh[e] << 32) | xl[e];
+              ++pos;
+            }
           }
         }
         __syncthreads();
-        VATT_STAMP(dbg, 90);
         if (tid < SMALL) {
-          // rank inside the bucket = number of listed composites below mine (the list is padded with all-ones)
+          // rank inside the range = number of listed composites below mine (the list is padded with all-ones)
           const uint64_t mine = sm.slist[tid];
           uint32_t below = 0;
 #pragma unroll
@@ -185,18 +166,57 @@ struct BlockSelect {
           if ((uint32_t)tid < m && below == r - 1u) sm.result = mine;
         }
         __syncthreads();
-        VATT_STAMP(dbg, 91);
+        VATT_STAMP(dbg, 12);
+        VATT_NOTE(dbg, 13, step);
+        VATT_NOTE(dbg, 14, m);
         return sm.result;
       }
-      if (shift == 0 && !low) {
-        // one high word left and still too many: continue on the low words of the composites that carry it
+      if (lo == hi) {
+        // more than SMALL composites share this high word: go on with their low words
         low = true;
-        hv = a_lo;
-        a_lo = 0u;
-        a_hi = 0xfffffffeu;
+        hv = lo;
+#pragma unroll
+        for (int e = 0; e < E; ++e) w[e] = (w[e] == hv) ? xl[e] : kInv32;
+        lo = 0u;
+        hi = 0xfffffffeu;
+      }
+      const uint32_t span = hi - lo;
+      // Pivot: two interpolation steps that aim a little above and a little below the wanted rank (so that
+      // the range closes in from both sides when the values are spread evenly), then a midpoint step (which
+      // bounds the number of steps for any data).
+      uint32_t off;
+      const int kind = step % 3;
+      if (kind == 2) {
+        off = span >> 1;
+      } else {
+        const float mf = (float)(m + 1u);
+        const float want = (float)r + 0.5f * (float)(cap - c);  // middle of the acceptable window
+        const float dev = 2.0f * sqrtf(fmaxf(want * (1.0f - want * __builtin_amdgcn_rcpf(mf)), 0.0f)) + 1.0f;
+        const float aim = kind == 0 ? want + dev : want - dev;
+        const float f = fminf(fmaxf(aim * __builtin_amdgcn_rcpf(mf), 0.0f), 1.0f);
+        off = (uint32_t)fminf((float)span * f, 4294967040.0f);
+      }
+      off = min(off, span - 1u);
+      // wave-level count straight from the compare masks
+      uint32_t wave_cnt = 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) wave_cnt += (uint32_t)__popcll(__ballot(w[e] - lo <= off));
+      if (lane == 0 && wave_cnt) atomicAdd(&sm.cnt[step], wave_cnt);
+      __syncthreads();
+      const uint32_t tot = sm.cnt[step];
+      if (tot >= r) {
+        hi = lo + off;
+        m = tot;
+      } else {
+        lo = lo + off + 1u;
+        r -= tot;
+        m -= tot;
       }
     }
-    return low ? (((uint64_t)hv << 32) | a_hi) : (((uint64_t)a_hi << 32) | kInv32);
+    VATT_STAMP(dbg, 12);
+    VATT_NOTE(dbg, 13, 1000);
+    if (!low && hi == 0xfffffffeu) return kInvalid - 1ull;
+    return low ? (((uint64_t)hv << 32) | hi) : (((uint64_t)hi << 32) | kInv32);
   }
 };
 
@@ -232,89 +252,99 @@ __device__ __forceinline__ Philox4 token_block_keys(uint32_t j, uint32_t stream,
 }
 
 // ---------------------------------------------------------------------------
-// Stage 1: chunk top-k candidates (even workgroups) and sampler key candidates (odd workgroups).
+// Stage 1.
 // ---------------------------------------------------------------------------
 struct Stage1Args {
   const float* scores;
   const int32_t* seq_lens;
   const uint64_t* seq_seeds;
   float* chunk_max;
-  uint64_t* cand;
-  int32_t* cand_cnt;
-  uint64_t* key_list;  // [B*Hq][2][key_stride]
-  uint32_t* key_cnt;   // [B*Hq][2], zeroed by the score kernel
+  uint64_t* cand;      // [B*Hq][n_chunks][cand_cap]
+  int32_t* cand_cnt;   // [B*Hq][n_chunks]
+  uint64_t* key_comp;  // [B*Hq][2][n_key_slices][key_slice_cap]
+  float* key_score;    // same shape
+  uint32_t* key_cnt;   // [B*Hq][2][n_key_slices]
   SelectParams sp;
-  int n_pad, n_max, Hq, chunk_len, n_chunks, cand_cap, key_cap0, key_cap1, key_slice_len;
+  int n_pad, n_max, Hq, chunk_len, n_chunks, cand_cap, key_slice_len, n_key_slices, key_slice_cap, key_on0, key_on1;
   unsigned long long* dbg;
 };
 
-constexpr int kKeyStage = 512;  // LDS staging slots per stream in a key workgroup
-
-// Workgroups [0, n_chunks) of a head select chunk candidates; the rest generate sampler key candidates.
 template <int NT, int E>
 __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
-  constexpr int ST = NT, SW = NT / kWave;
+  constexpr int SW = NT / kWave;
   __shared__ SelectSmem<NT> sel_sm;
+  __shared__ BlockScanSmem<NT> scan_sm;
   __shared__ float s_wmax[SW];
-  __shared__ uint32_t s_n[2], s_base[2];
-  __shared__ uint64_t s_stage[2][kKeyStage];
 
   const int role = (int)blockIdx.x >= A.n_chunks ? 1 : 0;
-  const int chunk = role ? (int)blockIdx.x - A.n_chunks : (int)blockIdx.x;
+  const int part = role ? (int)blockIdx.x - A.n_chunks : (int)blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = min(max(A.seq_lens[b], 1), A.n_max);
   const HeadSizes hs = head_sizes(n, A.sp);
   const int span = role ? A.key_slice_len : A.chunk_len;
-  const int lo = chunk * span;
+  const int lo = part * span;
   const int hi = min(lo + span, n);
+  const float* row = A.scores + (int64_t)bh * A.n_pad;
 
   if (role == 1) {
-    // ---- sampler key candidates of tokens [lo, hi) ----
-    if (lo >= n || hs.n_s <= 0) return;
+    // ---- sampler candidates among tokens [lo, hi): two Philox blocks per thread and stream ----
+    uint32_t* cnt_out = A.key_cnt + ((int64_t)bh * 2) * A.n_key_slices + part;  // stream s at + s * n_key_slices
+    const int t_lo = max(lo, hs.mid_lo), t_hi = min(hi, hs.mid_hi);
+    if (lo >= n || hs.n_s <= 0 || t_lo >= t_hi || (!A.key_on0 && !A.key_on1)) {
+      if (tid < 2) cnt_out[tid * A.n_key_slices] = 0u;
+      return;
+    }
     const uint64_t seed = A.seq_seeds[b];
     uint64_t U[2];
-    U[0] = A.key_cap0 > 0 ? upper_bound_key((uint32_t)hs.b0, hs.n_s) : 0ull;
-    U[1] = A.key_cap1 > 0 ? upper_bound_key(stream1_design_count(hs), hs.n_s) : 0ull;
-    if (tid < 2) s_n[tid] = 0;
-    __syncthreads();
-    const int t_lo = max(lo, hs.mid_lo), t_hi = min(hi, hs.mid_hi);
-    for (int j = (t_lo >> 2) + tid; j < ((t_hi + 3) >> 2); j += ST) {
+    U[0] = A.key_on0 ? upper_bound_key((uint32_t)hs.b0, hs.n_s) : 0ull;
+    U[1] = A.key_on1 ? upper_bound_key(stream1_design_count(hs), hs.n_s) : 0ull;
+    // key_slice_len = 8 * NT tokens: thread t owns Philox blocks j0 + t and j0 + NT + t
+    const int j0 = lo >> 2;
+    uint32_t keys[2][8];
+    uint32_t hit[2] = {0u, 0u};
 #pragma unroll
-      for (int s = 0; s < 2; ++s) {
-        if (U[s] == 0ull) continue;
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int j = j0 + u * NT + tid;
         const Philox4 ph = token_block_keys((uint32_t)j, (uint32_t)s, (uint32_t)h, seed);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = (j << 2) + e;
-          if (i >= t_lo && i < t_hi && (uint64_t)ph.v[e] < U[s]) {
-            const uint32_t pos = atomicAdd(&s_n[s], 1u);
-            if (pos < (uint32_t)kKeyStage) s_stage[s][pos] = ((uint64_t)ph.v[e] << 32) | (uint32_t)i;
-          }
+          keys[s][u * 4 + e] = ph.v[e];
+          hit[s] |= ((i >= t_lo && i < t_hi && (uint64_t)ph.v[e] < U[s]) ? 1u : 0u) << (u * 4 + e);
         }
       }
     }
-    __syncthreads();
-    // an overfull stage is reported as an overfull list: the head kernel then draws that sample itself
-    if (tid < 2 && s_n[tid] > 0)
-      s_base[tid] = atomicAdd(&A.key_cnt[bh * 2 + tid], s_n[tid] > (uint32_t)kKeyStage ? 0x40000000u : s_n[tid]);
-    __syncthreads();
-    const int key_stride = max(A.key_cap0, A.key_cap1);
+    // positions inside the slice's two lists: both counts ride one scan (low and high half of a word)
+    uint32_t total;
+    const uint32_t excl = block_exclusive_scan<NT>((uint32_t)__popc(hit[0]) | ((uint32_t)__popc(hit[1]) << 16), &total,
+                                                   scan_sm);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const uint32_t cnt = min(s_n[s], (uint32_t)kKeyStage);
-      const uint32_t base = cnt ? s_base[s] : 0u;
-      const uint32_t cap = (uint32_t)(s == 0 ? A.key_cap0 : A.key_cap1);
-      uint64_t* dst = A.key_list + ((int64_t)bh * 2 + s) * key_stride;
-      for (uint32_t t = tid; t < cnt; t += ST)
-        if (base + t < cap) dst[base + t] = s_stage[s][t];
+      const uint32_t tot_s = s ? (total >> 16) : (total & 0xffffu);
+      uint32_t pos = s ? (excl >> 16) : (excl & 0xffffu);
+      const int64_t base = (((int64_t)bh * 2 + s) * A.n_key_slices + part) * A.key_slice_cap;
+      if (tot_s <= (uint32_t)A.key_slice_cap) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          if ((hit[s] >> q) & 1u) {
+            const int i = ((j0 + (q >> 2) * NT + tid) << 2) + (q & 3);
+            A.key_comp[base + pos] = ((uint64_t)keys[s][q] << 32) | (uint32_t)i;
+            A.key_score[base + pos] = row[i];
+            ++pos;
+          }
+        }
+      }
+      if (tid == 0) cnt_out[s * A.n_key_slices] = tot_s <= (uint32_t)A.key_slice_cap ? tot_s : kOverflow;
     }
     return;
   }
 
   // ---- top-k candidates of the chunk [lo, hi) ----
-  const int slot = bh * A.n_chunks + chunk;
+  const int slot = bh * A.n_chunks + part;
   if (lo >= n) {
     if (tid == 0) {
       A.cand_cnt[slot] = 0;
@@ -323,15 +353,14 @@ __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
     return;
   }
   VATT_STAMP(A.dbg, 0);
-  const float* row = A.scores + (int64_t)bh * A.n_pad;
   float sc[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) sc[e] = row[min(lo + e * ST + tid, n - 1)];
+  for (int e = 0; e < E; ++e) sc[e] = row[min(lo + e * NT + tid, n - 1)];
   uint32_t xh[E], xl[E];
   float mx = -INFINITY;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
-    const int i = lo + e * ST + tid;
+    const int i = lo + e * NT + tid;
     const bool in_chunk = i < hi;
     const bool in_mid = in_chunk && i >= hs.mid_lo && i < hs.mid_hi;
     mx = in_chunk ? fmaxf(mx, sc[e]) : mx;
@@ -341,7 +370,6 @@ __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
   VATT_STAMP(A.dbg, 1);
   mx = wave_max(mx);
   if (lane == 0) s_wmax[wave] = mx;
-  if (tid == 0) s_n[0] = 0;
   __syncthreads();
   if (tid == 0) {
     float t = s_wmax[0];
@@ -356,27 +384,25 @@ __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
     return;
   }
   VATT_STAMP(A.dbg, 2);
+  // a superset of the chunk's top-k is as good as the exact set here: stop as soon as it fits the slot
   const uint64_t T = (c == nvalid) ? (kInvalid - 1ull)
                                    : BlockSelect<NT, E>::run(xh, xl, (uint32_t)c, (uint32_t)min(nvalid, A.cand_cap),
                                                              sel_sm, A.dbg);
   VATT_STAMP(A.dbg, 3);
+  uint32_t take = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) take |= ((((uint64_t)xh[e] << 32) | xl[e]) <= T ? 1u : 0u) << e;
+  uint32_t total;
+  uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(take), &total, scan_sm);
   uint64_t* out = A.cand + (int64_t)slot * A.cand_cap;
-  uint32_t mine = 0;
 #pragma unroll
-  for (int e = 0; e < E; ++e) mine |= ((((uint64_t)xh[e] << 32) | xl[e]) <= T ? 1u : 0u) << e;
-  if (mine) {
-    uint32_t pos = atomicAdd(&s_n[0], (uint32_t)__popc(mine));
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-      if ((mine >> e) & 1u) {
-        if (pos < (uint32_t)A.cand_cap) out[pos] = ((uint64_t)xh[e] << 32) | xl[e];
-        ++pos;
-      }
+  for (int e = 0; e < E; ++e) {
+    if ((take >> e) & 1u) {
+      if (pos < (uint32_t)A.cand_cap) out[pos] = ((uint64_t)xh[e] << 32) | xl[e];
+      ++pos;
     }
   }
-  __syncthreads();
-  // the select may return a superset of the chunk's top-k (everything down to a bucket boundary)
-  if (tid == 0) A.cand_cnt[slot] = (int32_t)min(s_n[0], (uint32_t)A.cand_cap);
+  if (tid == 0) A.cand_cnt[slot] = (int32_t)min(total, (uint32_t)A.cand_cap);
   VATT_STAMP(A.dbg, 4);
 }
 
@@ -390,7 +416,8 @@ struct HeadArgs {
   const float* chunk_max;
   const uint64_t* cand;
   const int32_t* cand_cnt;
-  const uint64_t* key_list;
+  const uint64_t* key_comp;
+  const float* key_score;
   const uint32_t* key_cnt;
   HeadRec* head_rec;
   const double* vstat_part;  // [B*Hq][vstat_splits][2d+2] (targets N, SDPA)
@@ -402,271 +429,285 @@ struct HeadArgs {
   double z_half, z_quarter, eps, cap_frac;
   int64_t seg_topk, seg_base, seg_dyn, seg_sink, seg_win;
   int64_t idx_cap;
-  int n_pad, n_max, Hq, n_chunks, cand_cap, key_cap0, key_cap1, target, phase, force_slow, vstat_splits, head_dim;
-  int k_max, b0_max, b_max;
+  int n_pad, n_max, Hq, n_chunks, cand_cap, cand_shift, n_key_slices, key_slice_cap, key_slice_shift, key_on0, key_on1;
+  int target, phase, force_slow, vstat_splits, head_dim;
+  int k_max, b0_max, b_max, wlist_len;
   unsigned long long* dbg;
 };
 
 // Device functions of the per-head kernel for a workgroup of NT threads.
 template <int NT>
 struct HeadOps {
-static constexpr int ST = NT, SW = NT / kWave;
-static constexpr int EL = kListCap / NT;  // in-kernel sampler list composites per thread
+  static constexpr int SW = NT / kWave;
+  static constexpr int EL = kListCap / NT;  // in-kernel sampler list composites per thread
 
-struct HeadSmem {
-  SelectSmem<NT> sel;
-  BlockScanSmem<NT> scan;
-  uint64_t list[kListCap];
-  uint32_t hist[256];
-  double red[3][SW];
-  uint32_t list_n, sure_n;
-  uint32_t u_a, u_b, u_c;
-};
+  struct HeadSmem {
+    SelectSmem<NT> sel;
+    BlockScanSmem<NT> scan;
+    uint64_t list[kListCap];
+    uint32_t hist[256];
+    double red[3][SW];
+    uint32_t slice_cnt[2][kMaxKeySlices];
+    uint32_t chunk_cnt[kMaxChunks];
+    uint32_t list_n, sure_n;
+    uint32_t u_a, u_b, u_c;
+  };
 
-// Workgroup sums of up to three doubles at once; every thread gets all of them.
-template <int N>
-static __device__ __forceinline__ void block_sum(double (&v)[N], HeadSmem& sm) {
+  // Workgroup sums of up to three doubles at once; every thread gets all of them.
+  template <int N>
+  static __device__ __forceinline__ void block_sum(double (&v)[N], HeadSmem& sm) {
 #pragma unroll
-  for (int j = 0; j < N; ++j) v[j] = wave_sum(v[j]);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) {
+    for (int j = 0; j < N; ++j) v[j] = wave_sum(v[j]);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) sm.red[j][threadIdx.x >> 6] = v[j];
-  }
-  __syncthreads();
+      for (int j = 0; j < N; ++j) sm.red[j][threadIdx.x >> 6] = v[j];
+    }
+    __syncthreads();
 #pragma unroll
-  for (int j = 0; j < N; ++j) {
-    double t = 0.0;
+    for (int j = 0; j < N; ++j) {
+      double t = 0.0;
 #pragma unroll
-    for (int w = 0; w < SW; ++w) t += sm.red[j][w];
-    v[j] = t;
-  }
-}
-
-// Token read back from an index list, forced into [0, n): a list entry can never address outside the row.
-static __device__ __forceinline__ int list_tok(const int32_t* idx, int64_t pos, int n) { return min(max(idx[pos], 0), n - 1); }
-
-// Write the set bits of bm[0, n) as ascending token indices to dst and add exp(s_i - m) (and its square) of
-// those tokens into sum_w (sum_w2).  Returns the number of set bits.
-static __device__ uint32_t compact_bitmap(const uint32_t* bm, int n, int32_t* dst, uint32_t dst_cap, const float* row, float m,
-                                   double* sum_w, double* sum_w2, HeadSmem& sm) {
-  const int words = (n + 31) >> 5;
-  const int wpt = (words + ST - 1) / ST;
-  const int w0 = threadIdx.x * wpt;
-  uint32_t cnt = 0;
-  for (int w = w0; w < min(w0 + wpt, words); ++w) cnt += __popc(bm[w]);
-  uint32_t total;
-  uint32_t pos = block_exclusive_scan<NT>(cnt, &total, sm.scan);
-  double a = 0.0, a2 = 0.0;
-  for (int w = w0; w < min(w0 + wpt, words); ++w) {
-    uint32_t bits = bm[w];
-    while (bits) {
-      const int bpos = __ffs(bits) - 1;
-      bits &= bits - 1u;
-      const int i = (w << 5) + bpos;
-      if (pos < dst_cap) dst[pos] = i;
-      ++pos;
-      if (sum_w) {
-        const double wgt = (double)expf(row[i] - m);
-        a += wgt;
-        a2 += wgt * wgt;
-      }
+      for (int w = 0; w < SW; ++w) t += sm.red[j][w];
+      v[j] = t;
     }
   }
-  if (sum_w) *sum_w += a;
-  if (sum_w2) *sum_w2 += a2;
-  return total;
-}
 
-// Residual tokens of the 4-token block j as a 4-bit mask.
-static __device__ __forceinline__ uint32_t residual_nibble(const uint32_t* bm_f, const HeadSizes& hs, int j) {
-  const int i0 = j << 2;
-  uint32_t in_mid = 0;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) in_mid |= ((i0 + e >= hs.mid_lo && i0 + e < hs.mid_hi) ? 1u : 0u) << e;
-  const uint32_t taken = (bm_f[i0 >> 5] >> (i0 & 31)) & 15u;
-  return in_mid & ~taken;
-}
-
-static __device__ __forceinline__ void mark_bit(uint32_t* bm, uint32_t i) { atomicOr(&bm[i >> 5], 1u << (i & 31)); }
-
-// Select the `need` smallest composites of the LDS list sm.list[0, listed) and mark their tokens in bm_s.
-static __device__ void mark_smallest_of_list(uint32_t* bm_s, uint32_t listed, uint32_t need, HeadSmem& sm) {
-  uint32_t xh[EL], xl[EL];
-#pragma unroll
-  for (int e = 0; e < EL; ++e) {
-    const uint32_t p = e * ST + threadIdx.x;
-    const uint64_t t = p < listed ? sm.list[p] : kInvalid;
-    xh[e] = (uint32_t)(t >> 32);
-    xl[e] = (uint32_t)t;
+  // Token read back from an index list, forced into [0, n): a list entry can never address outside the row.
+  static __device__ __forceinline__ int list_tok(const int32_t* idx, int64_t pos, int n) {
+    return min(max(idx[pos], 0), n - 1);
   }
-  const uint64_t T = (need >= listed) ? (kInvalid - 1ull) : BlockSelect<NT, EL>::run(xh, xl, need, need, sm.sel);
-#pragma unroll
-  for (int e = 0; e < EL; ++e)
-    if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
-}
 
-// Fast sample: from the candidate list that stage 1 built for this head and stream (every middle token
-// whose key is under the design bound).  Usable when the list did not overflow and holds at least c
-// residual tokens; then the c smallest residual composites in it are the sample.  bm_s must be zero.
-template <int EK>
-static __device__ bool sample_from_candidates(uint32_t* bm_s, const uint32_t* bm_f, const HeadSizes& hs, uint32_t c,
-                                       const uint64_t* list, uint32_t count, uint32_t cap, HeadSmem& sm) {
-  if (cap == 0 || count > cap) return false;
-  uint32_t xh[EK], xl[EK];
-  uint32_t valid = 0;
+  static __device__ __forceinline__ void mark_bit(uint32_t* bm, uint32_t i) { atomicOr(&bm[i >> 5], 1u << (i & 31)); }
+
+  // Exclusive prefix of the set-bit counts of bm[0, words) into wpre; returns the number of set bits.
+  static __device__ uint32_t word_prefix(const uint32_t* bm, int words, uint32_t* wpre, HeadSmem& sm) {
+    const int wpt = (words + NT - 1) / NT;
+    const int w0 = threadIdx.x * wpt;
+    uint32_t cnt = 0;
+    for (int w = w0; w < min(w0 + wpt, words); ++w) cnt += __popc(bm[w]);
+    uint32_t total;
+    uint32_t pos = block_exclusive_scan<NT>(cnt, &total, sm.scan);
+    for (int w = w0; w < min(w0 + wpt, words); ++w) {
+      wpre[w] = pos;
+      pos += __popc(bm[w]);
+    }
+    __syncthreads();
+    return total;
+  }
+  // Position of token i in the ascending list of the set bits of bm.
+  static __device__ __forceinline__ uint32_t list_pos(const uint32_t* bm, const uint32_t* wpre, uint32_t i) {
+    return wpre[i >> 5] + __popc(bm[i >> 5] & ((1u << (i & 31)) - 1u));
+  }
+
+  // Slow list writer (used after the in-kernel sweeps, which do not keep the scores): writes the set bits of
+  // bm as ascending tokens and, when wlist is given, exp(s_i - m) of each into wlist at the same position.
+  static __device__ void write_list_from_bitmap(const uint32_t* bm, int n, const uint32_t* wpre, int32_t* dst,
+                                                uint32_t dst_cap, const float* row, float m, float* wlist,
+                                                uint32_t wlist_len) {
+    const int words = (n + 31) >> 5;
+    for (int w = threadIdx.x; w < words; w += NT) {
+      uint32_t bits = bm[w];
+      uint32_t pos = wpre[w];
+      while (bits) {
+        const int i = (w << 5) + (__ffs(bits) - 1);
+        bits &= bits - 1u;
+        if (pos < dst_cap) dst[pos] = i;
+        if (wlist && pos < wlist_len) wlist[pos] = __expf(row[i] - m);
+        ++pos;
+      }
+    }
+    __syncthreads();
+  }
+
+  // Sums of wlist[0, count) and of its squares, taken in a fixed order.
+  static __device__ __forceinline__ void sum_wlist(const float* wlist, uint32_t count, double* s1, double* s2) {
+    double a = 0.0, a2 = 0.0;
+    for (uint32_t t = threadIdx.x; t < count; t += NT) {
+      const double w = (double)wlist[t];
+      a += w;
+      a2 += w * w;
+    }
+    *s1 += a;
+    *s2 += a2;
+  }
+
+  // Residual tokens of the 4-token block j as a 4-bit mask.
+  static __device__ __forceinline__ uint32_t residual_nibble(const uint32_t* bm_f, const HeadSizes& hs, int j) {
+    const int i0 = j << 2;
+    uint32_t in_mid = 0;
 #pragma unroll
-  for (int e = 0; e < EK; ++e) {
-    const uint32_t p = e * ST + threadIdx.x;
-    xh[e] = xl[e] = kInv32;
-    if (p < count) {
-      const uint64_t t = list[p];
+    for (int e = 0; e < 4; ++e) in_mid |= ((i0 + e >= hs.mid_lo && i0 + e < hs.mid_hi) ? 1u : 0u) << e;
+    const uint32_t taken = (bm_f[i0 >> 5] >> (i0 & 31)) & 15u;
+    return in_mid & ~taken;
+  }
+
+  // Select the `need` smallest composites of the LDS list sm.list[0, listed) and mark their tokens in bm_s.
+  static __device__ void mark_smallest_of_list(uint32_t* bm_s, uint32_t listed, uint32_t need, HeadSmem& sm) {
+    uint32_t xh[EL], xl[EL];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) {
+      const uint32_t p = e * NT + threadIdx.x;
+      const uint64_t t = p < listed ? sm.list[p] : kInvalid;
+      xh[e] = (uint32_t)(t >> 32);
+      xl[e] = (uint32_t)t;
+    }
+    const uint64_t T = (need >= listed) ? (kInvalid - 1ull) : BlockSelect<NT, EL>::run(xh, xl, need, need, sm.sel);
+#pragma unroll
+    for (int e = 0; e < EL; ++e)
+      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
+  }
+
+  // Fast sample: among the candidates stage 1 wrote for this head and stream (every middle token whose key
+  // is under the design bound, slice by slice, with its score).  Usable when no slice overflowed and the
+  // residual tokens among the candidates number at least c; then the c smallest residual composites are
+  // the sample.  Marks them in bm_s (all zero on entry), then writes the ascending token list to dst and,
+  // when wlist is given, exp(score - m) of each to wlist at its list position.  tc / xs hold the candidate
+  // slots of this thread (composite and score of slot e * NT + tid), read from global memory by the caller.
+  template <int EK>
+  static __device__ bool sample_from_candidates(uint32_t* bm_s, const uint32_t* bm_f, uint32_t* wpre,
+                                                const HeadSizes& hs, uint32_t c, const uint64_t (&tc)[EK],
+                                                const float (&xs)[EK], const uint32_t* slice_cnt, int n_slices,
+                                                int slice_shift, int32_t* dst, uint32_t dst_cap, float m,
+                                                float* wlist, uint32_t wlist_len, HeadSmem& sm,
+                                                unsigned long long* dbg = nullptr) {
+    const int tid = threadIdx.x;
+    const int slots = n_slices << slice_shift;
+    VATT_STAMP(dbg, 1);
+    // slot p = e * NT + tid belongs to slice p >> slice_shift
+    uint32_t xh[EK], xl[EK];
+    uint32_t valid = 0, bad = 0;
+#pragma unroll
+    for (int e = 0; e < EK; ++e) {
+      const int p = e * NT + tid;
+      const int pc = min(p, slots - 1);
+      const int sl = pc >> slice_shift, off = pc & ((1 << slice_shift) - 1);
+      const uint32_t cnt = slice_cnt[sl];
+      const uint64_t t = tc[e];
       const uint32_t i = (uint32_t)t;
-      const bool res = (int)i >= hs.mid_lo && (int)i < hs.mid_hi && !((bm_f[i >> 5] >> (i & 31)) & 1u);
-      if (res) {
-        xh[e] = (uint32_t)(t >> 32);
-        xl[e] = i;
-        ++valid;
-      }
+      bad |= (p < slots && cnt == kOverflow) ? 1u : 0u;
+      const bool present = p < slots && cnt != kOverflow && (uint32_t)off < cnt;
+      const uint32_t ic = present ? min(i, (uint32_t)(hs.n - 1)) : 0u;
+      const bool res = present && (int)i >= hs.mid_lo && (int)i < hs.mid_hi && !((bm_f[ic >> 5] >> (ic & 31)) & 1u);
+      xh[e] = res ? (uint32_t)(t >> 32) : kInv32;
+      xl[e] = res ? i : kInv32;
+      valid += res ? 1u : 0u;
     }
-  }
-  valid = wave_sum_u32(valid);
-  __syncthreads();
-  if (threadIdx.x == 0) sm.u_a = 0;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0 && valid) atomicAdd(&sm.u_a, valid);
-  __syncthreads();
-  const uint32_t total = sm.u_a;
-  if (total < c) return false;
-  const uint64_t T = (total == c) ? (kInvalid - 1ull) : BlockSelect<NT, EK>::run(xh, xl, c, c, sm.sel);
-#pragma unroll
-  for (int e = 0; e < EK; ++e)
-    if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
-  __syncthreads();
-  return true;
-}
-
-// General sample: mark in bm_s the c residual tokens with the smallest (key, token) of the given stream,
-// computing the keys here.  bm_s must be all zero on entry.  Returns 1 if the slow exact descent was needed.
-static __device__ int sample_by_sweep(uint32_t* bm_s, const uint32_t* bm_f, const HeadSizes& hs, uint32_t c,
-                               uint32_t stream, uint32_t head, uint64_t seed, int force_slow, HeadSmem& sm) {
-  const int tid = threadIdx.x;
-  const int j_lo = hs.mid_lo >> 2, j_hi = (hs.mid_hi + 3) >> 2;  // Philox blocks that touch the middle region
-  const int words = (hs.n + 31) >> 5;
-  if (c == 0) return 0;
-  if (c >= (uint32_t)hs.n_s) {
-    // the whole residual: no keys needed
-    for (int w = tid; w < words; w += ST) {
-      uint32_t m = 0;
-      const int i0 = w << 5;
-      if (i0 + 31 >= hs.mid_lo && i0 < hs.mid_hi) {
-        const int a = max(hs.mid_lo - i0, 0), bnd = min(hs.mid_hi - i0, 32);
-        m = (bnd >= 32 ? 0xffffffffu : ((1u << bnd) - 1u)) & ~((1u << a) - 1u);
-      }
-      bm_s[w] = m & ~bm_f[w];
-    }
+    valid = wave_sum_u32(valid);
+    bad = wave_sum_u32(bad);
     __syncthreads();
-    return 0;
-  }
-
-  bool done = false;
-  if (!force_slow) {
-    // One sweep with a verified guess: tokens with a key below L are certainly in, tokens in [L, U) are
-    // listed and ranked exactly; the guess is checked by counting and otherwise discarded.
-    const uint64_t Lq = lower_bound_key(c, hs.n_s), Uq = upper_bound_key(c, hs.n_s);
     if (tid == 0) {
-      sm.list_n = 0;
-      sm.sure_n = 0;
+      sm.u_a = 0;
+      sm.u_b = 0;
     }
     __syncthreads();
-    uint32_t my_sure = 0;
-    for (int j = j_lo + tid; j < j_hi; j += ST) {
-      const uint32_t res = residual_nibble(bm_f, hs, j);
-      if (res) {
-        const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
-        uint32_t mark = 0;
+    if ((tid & 63) == 0) {
+      if (valid) atomicAdd(&sm.u_a, valid);
+      if (bad) atomicAdd(&sm.u_b, 1u);
+    }
+    __syncthreads();
+    const uint32_t total = sm.u_a;
+    VATT_STAMP(dbg, 2);
+    if (sm.u_b != 0 || total < c) return false;
+    const uint64_t T = (total == c) ? (kInvalid - 1ull) : BlockSelect<NT, EK>::run(xh, xl, c, c, sm.sel, dbg);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if ((res >> e) & 1u) {
-            const uint64_t key = ph.v[e];
-            if (key < Lq) {
-              mark |= 1u << e;
-            } else if (key < Uq) {
-              const uint32_t pos = atomicAdd(&sm.list_n, 1u);
-              if (pos < (uint32_t)kListCap) sm.list[pos] = (key << 32) | (uint32_t)((j << 2) + e);
+    for (int e = 0; e < EK; ++e)
+      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
+    __syncthreads();
+    VATT_STAMP(dbg, 3);
+    word_prefix(bm_s, (hs.n + 31) >> 5, wpre, sm);
+    VATT_STAMP(dbg, 4);
+#pragma unroll
+    for (int e = 0; e < EK; ++e) {
+      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) {
+        const uint32_t pos = list_pos(bm_s, wpre, xl[e]);
+        if (pos < dst_cap) dst[pos] = (int32_t)xl[e];
+        if (wlist && pos < wlist_len) wlist[pos] = __expf(xs[e] - m);
+      }
+    }
+    __syncthreads();
+    return true;
+  }
+
+  // General sample: mark in bm_s the c residual tokens with the smallest (key, token) of the given stream,
+  // computing the keys here.  bm_s must be all zero on entry.  Returns 1 if the slow exact descent was needed.
+  static __device__ int sample_by_sweep(uint32_t* bm_s, const uint32_t* bm_f, const HeadSizes& hs, uint32_t c,
+                                        uint32_t stream, uint32_t head, uint64_t seed, int force_slow, HeadSmem& sm) {
+    const int tid = threadIdx.x;
+    const int j_lo = hs.mid_lo >> 2, j_hi = (hs.mid_hi + 3) >> 2;  // Philox blocks that touch the middle region
+    const int words = (hs.n + 31) >> 5;
+    if (c == 0) return 0;
+    if (c >= (uint32_t)hs.n_s) {
+      // the whole residual: no keys needed
+      for (int w = tid; w < words; w += NT) {
+        uint32_t mm = 0;
+        const int i0 = w << 5;
+        if (i0 + 31 >= hs.mid_lo && i0 < hs.mid_hi) {
+          const int a = max(hs.mid_lo - i0, 0), bnd = min(hs.mid_hi - i0, 32);
+          mm = (bnd >= 32 ? 0xffffffffu : ((1u << bnd) - 1u)) & ~((1u << a) - 1u);
+        }
+        bm_s[w] = mm & ~bm_f[w];
+      }
+      __syncthreads();
+      return 0;
+    }
+
+    bool done = false;
+    if (!force_slow) {
+      // One sweep with a verified guess: tokens with a key below L are certainly in, tokens in [L, U) are
+      // listed and ranked exactly; the guess is checked by counting and otherwise discarded.
+      const uint64_t Lq = lower_bound_key(c, hs.n_s), Uq = upper_bound_key(c, hs.n_s);
+      if (tid == 0) {
+        sm.list_n = 0;
+        sm.sure_n = 0;
+      }
+      __syncthreads();
+      uint32_t my_sure = 0;
+      for (int j = j_lo + tid; j < j_hi; j += NT) {
+        const uint32_t res = residual_nibble(bm_f, hs, j);
+        if (res) {
+          const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
+          uint32_t mark = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if ((res >> e) & 1u) {
+              const uint64_t key = ph.v[e];
+              if (key < Lq) {
+                mark |= 1u << e;
+              } else if (key < Uq) {
+                const uint32_t pos = atomicAdd(&sm.list_n, 1u);
+                if (pos < (uint32_t)kListCap) sm.list[pos] = (key << 32) | (uint32_t)((j << 2) + e);
+              }
             }
           }
-        }
-        if (mark) {
-          atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
-          my_sure += __popc(mark);
-        }
-      }
-    }
-    if (my_sure) atomicAdd(&sm.sure_n, my_sure);
-    __syncthreads();
-    const uint32_t sure = sm.sure_n, listed = sm.list_n;
-    if (sure <= c && sure + listed >= c && listed <= (uint32_t)kListCap) {
-      if (c > sure) mark_smallest_of_list(bm_s, listed, c - sure, sm);
-      done = true;
-    } else {
-      for (int w = tid; w < words; w += ST) bm_s[w] = 0;  // discard the guess
-    }
-    __syncthreads();
-  }
-  if (done) return 0;
-
-  // Slow exact path: radix descent over the composite with 8-bit digits, recomputing the keys in every
-  // sweep; ends with one marking sweep.  Correct for any c and any key distribution.
-  uint64_t prefix = 0, mask = 0, T = 0;
-  uint32_t r = c;
-  bool have_T = false;
-  for (int shift = 56; shift >= 0 && !have_T; shift -= 8) {
-    for (int d = tid; d < 256; d += ST) sm.hist[d] = 0;
-    __syncthreads();
-    for (int j = j_lo + tid; j < j_hi; j += ST) {
-      const uint32_t res = residual_nibble(bm_f, hs, j);
-      if (res) {
-        const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if ((res >> e) & 1u) {
-            const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-            if ((comp & mask) == prefix) atomicAdd(&sm.hist[(uint32_t)(comp >> shift) & 255u], 1u);
+          if (mark) {
+            atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
+            my_sure += __popc(mark);
           }
         }
       }
-    }
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t cum = 0, below = 0, active = 0, dsel = 255;
-      bool found = false;
-      for (int d = 0; d < 256; ++d) {
-        const uint32_t t = sm.hist[d];
-        if (!found && cum + t >= r) {
-          found = true;
-          dsel = d;
-          below = cum;
-          active = t;
-        }
-        cum += t;
-      }
-      sm.u_a = dsel;
-      sm.u_b = below;
-      sm.u_c = active;
-    }
-    __syncthreads();
-    const uint32_t dsel = sm.u_a, below = sm.u_b, active = sm.u_c;
-    r -= below;
-    prefix |= (uint64_t)dsel << shift;
-    mask |= 255ull << shift;
-    if (active == r) {
-      T = prefix | ((1ull << shift) - 1ull);
-      have_T = true;
-    } else if (active <= (uint32_t)kListCap) {
-      if (tid == 0) sm.list_n = 0;
+      if (my_sure) atomicAdd(&sm.sure_n, my_sure);
       __syncthreads();
-      for (int j = j_lo + tid; j < j_hi; j += ST) {
+      const uint32_t sure = sm.sure_n, listed = sm.list_n;
+      if (sure <= c && sure + listed >= c && listed <= (uint32_t)kListCap) {
+        if (c > sure) mark_smallest_of_list(bm_s, listed, c - sure, sm);
+        done = true;
+      } else {
+        for (int w = tid; w < words; w += NT) bm_s[w] = 0;  // discard the guess
+      }
+      __syncthreads();
+    }
+    if (done) return 0;
+
+    // Slow exact path: radix descent over the composite with 8-bit digits, recomputing the keys in every
+    // sweep; ends with one marking sweep.  Correct for any c and any key distribution.
+    uint64_t prefix = 0, mask = 0, T = 0;
+    uint32_t r = c;
+    bool have_T = false;
+    for (int shift = 56; shift >= 0 && !have_T; shift -= 8) {
+      for (int d = tid; d < 256; d += NT) sm.hist[d] = 0;
+      __syncthreads();
+      for (int j = j_lo + tid; j < j_hi; j += NT) {
         const uint32_t res = residual_nibble(bm_f, hs, j);
         if (res) {
           const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
@@ -674,64 +715,125 @@ static __device__ int sample_by_sweep(uint32_t* bm_s, const uint32_t* bm_f, cons
           for (int e = 0; e < 4; ++e) {
             if ((res >> e) & 1u) {
               const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-              if ((comp & mask) == prefix) {
-                const uint32_t pos = atomicAdd(&sm.list_n, 1u);
-                if (pos < (uint32_t)kListCap) sm.list[pos] = comp;
-              }
+              if ((comp & mask) == prefix) atomicAdd(&sm.hist[(uint32_t)(comp >> shift) & 255u], 1u);
             }
           }
         }
       }
       __syncthreads();
-      const uint32_t listed = min(sm.list_n, (uint32_t)kListCap);
-      uint32_t xh[EL], xl[EL];
-#pragma unroll
-      for (int e = 0; e < EL; ++e) {
-        const uint32_t p = e * ST + tid;
-        const uint64_t t = p < listed ? sm.list[p] : kInvalid;
-        xh[e] = (uint32_t)(t >> 32);
-        xl[e] = (uint32_t)t;
+      if (tid == 0) {
+        uint32_t cum = 0, below = 0, active = 0, dsel = 255;
+        bool found = false;
+        for (int d = 0; d < 256; ++d) {
+          const uint32_t t = sm.hist[d];
+          if (!found && cum + t >= r) {
+            found = true;
+            dsel = d;
+            below = cum;
+            active = t;
+          }
+          cum += t;
+        }
+        sm.u_a = dsel;
+        sm.u_b = below;
+        sm.u_c = active;
       }
-      T = BlockSelect<NT, EL>::run(xh, xl, r, r, sm.sel);
-      have_T = true;
+      __syncthreads();
+      const uint32_t dsel = sm.u_a, below = sm.u_b, active = sm.u_c;
+      r -= below;
+      prefix |= (uint64_t)dsel << shift;
+      mask |= 255ull << shift;
+      if (active == r) {
+        T = prefix | ((1ull << shift) - 1ull);
+        have_T = true;
+      } else if (active <= (uint32_t)kListCap) {
+        if (tid == 0) sm.list_n = 0;
+        __syncthreads();
+        for (int j = j_lo + tid; j < j_hi; j += NT) {
+          const uint32_t res = residual_nibble(bm_f, hs, j);
+          if (res) {
+            const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if ((res >> e) & 1u) {
+                const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
+                if ((comp & mask) == prefix) {
+                  const uint32_t pos = atomicAdd(&sm.list_n, 1u);
+                  if (pos < (uint32_t)kListCap) sm.list[pos] = comp;
+                }
+              }
+            }
+          }
+        }
+        __syncthreads();
+        const uint32_t listed = min(sm.list_n, (uint32_t)kListCap);
+        uint32_t xh[EL], xl[EL];
+#pragma unroll
+        for (int e = 0; e < EL; ++e) {
+          const uint32_t p = e * NT + tid;
+          const uint64_t t = p < listed ? sm.list[p] : kInvalid;
+          xh[e] = (uint32_t)(t >> 32);
+          xl[e] = (uint32_t)t;
+        }
+        T = BlockSelect<NT, EL>::run(xh, xl, r, r, sm.sel);
+        have_T = true;
+      }
+      __syncthreads();
+    }
+    if (!have_T) T = prefix;
+    for (int j = j_lo + tid; j < j_hi; j += NT) {
+      const uint32_t res = residual_nibble(bm_f, hs, j);
+      if (res) {
+        const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
+        uint32_t mark = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if ((res >> e) & 1u) {
+            const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
+            if (comp <= T) mark |= 1u << e;
+          }
+        }
+        if (mark) atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
+      }
     }
     __syncthreads();
+    return 1;
   }
-  if (!have_T) T = prefix;
-  for (int j = j_lo + tid; j < j_hi; j += ST) {
-    const uint32_t res = residual_nibble(bm_f, hs, j);
-    if (res) {
-      const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
-      uint32_t mark = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if ((res >> e) & 1u) {
-          const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-          if (comp <= T) mark |= 1u << e;
-        }
-      }
-      if (mark) atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
-    }
-  }
-  __syncthreads();
-  return 1;
-}
 
-// Picks the candidate-list width for the list's capacity (a short list keeps the select cheap).
-static __device__ __forceinline__ bool sample_from_list(uint32_t* bm_s, const uint32_t* bm_f, const HeadSizes& hs,
-                                                        uint32_t c, const uint64_t* list, uint32_t count, uint32_t cap,
-                                                        HeadSmem& sm) {
-  if (cap <= 2048u) return sample_from_candidates<2048 / NT>(bm_s, bm_f, hs, c, list, count, cap, sm);
-  return sample_from_candidates<kKeyListMax / NT>(bm_s, bm_f, hs, c, list, count, cap, sm);
-}
+  // Draw a sample of size c for `stream` and write its ascending token list; the return value reports the
+  // path taken (flag bits of out_counts[7]).  tc / xs: this thread's slots of the stream's candidate list.
+  template <int EK>
+  static __device__ int draw_sample(uint32_t* bm_s, const uint32_t* bm_f, uint32_t* wpre, const HeadSizes& hs,
+                                    uint32_t c, int stream, const HeadArgs& A, int h, uint64_t seed,
+                                    const uint64_t (&tc)[EK], const float (&xs)[EK], const float* row, int32_t* dst,
+                                    uint32_t dst_cap, float m, float* wlist, HeadSmem& sm) {
+    const int words = (hs.n + 31) >> 5;
+    const bool list_on = (stream == 0 ? A.key_on0 : A.key_on1) != 0;
+    bool ok = false;
+    if (!A.force_slow && list_on && c < (uint32_t)hs.n_s) {
+      unsigned long long* dbg = A.dbg ? A.dbg + 200 + 100 * stream : nullptr;
+      (void)dbg;
+      ok = sample_from_candidates<EK>(bm_s, bm_f, wpre, hs, c, tc, xs, sm.slice_cnt[stream], A.n_key_slices,
+                                      A.key_slice_shift, dst, dst_cap, m, wlist, (uint32_t)A.wlist_len, sm, dbg);
+    }
+    if (ok) return 0;
+    __syncthreads();
+    for (int w = threadIdx.x; w < words; w += NT) bm_s[w] = 0;
+    __syncthreads();
+    const int slow = sample_by_sweep(bm_s, bm_f, hs, c, (uint32_t)stream, (uint32_t)h, seed, A.force_slow, sm);
+    word_prefix(bm_s, words, wpre, sm);
+    write_list_from_bitmap(bm_s, hs.n, wpre, dst, dst_cap, row, m, wlist, (uint32_t)A.wlist_len);
+    return (stream == 0 ? (2 | (slow << 2)) : ((c < (uint32_t)hs.n_s ? 8 : 0) | slow));
+  }
 };  // struct HeadOps
 
-// NT = workgroup size; EM = top-k candidates a thread holds while merging (a head has <= EM * NT of them).
-template <int NT, int EM>
+// NT = workgroup size; EM = top-k candidate slots a thread holds (n_chunks * cand_cap <= EM * NT); EK = sampler
+// candidate slots a thread holds per stream (n_key_slices * key_slice_cap <= EK * NT when the lists are on).
+template <int NT, int EM, int EK>
 __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   using O = HeadOps<NT>;
   using HeadSmem = typename O::HeadSmem;
-  constexpr int ST = NT, SW = NT / kWave;
+  constexpr int SW = NT / kWave;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
@@ -744,20 +846,48 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   HeadSmem& sm = *reinterpret_cast<HeadSmem*>(dyn_smem);
   uint32_t* bm_f = reinterpret_cast<uint32_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
   uint32_t* bm_s = bm_f + words_max;
+  uint32_t* wpre = bm_s + words_max;
+  float* wlist = reinterpret_cast<float*>(wpre + words_max);
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
   const uint64_t seed = A.seq_seeds[b];
-  const int key_stride = max(A.key_cap0, A.key_cap1);
 
   VATT_STAMP(A.dbg, 0);
-  for (int w = tid; w < words; w += ST) {
+  // Everything this kernel needs from global memory is requested up front, so that the latencies overlap:
+  // the head's top-k candidate slots and its sampler candidate slots (composite and score) of both streams.
+  uint64_t tcand[EM];
+  {
+    const uint64_t* src = A.cand + (int64_t)bh * A.n_chunks * A.cand_cap;
+    const int slots = A.n_chunks * A.cand_cap;
+#pragma unroll
+    for (int e = 0; e < EM; ++e) tcand[e] = (A.phase != 2) ? src[min(e * NT + tid, slots - 1)] : kInvalid;
+  }
+  uint64_t kc0[EK], kc1[EK];
+  float ks0[EK], ks1[EK];
+  {
+    const int kslots = A.n_key_slices << A.key_slice_shift;
+    const int64_t base = (int64_t)bh * 2 * kslots;
+#pragma unroll
+    for (int e = 0; e < EK; ++e) {
+      const int pc = min(e * NT + tid, kslots - 1);
+      const bool in = e * NT + tid < kslots;
+      kc0[e] = (A.key_on0 && A.phase != 2 && in) ? A.key_comp[base + pc] : kInvalid;
+      ks0[e] = (A.key_on0 && A.phase != 2 && in) ? A.key_score[base + pc] : 0.f;
+      kc1[e] = (A.key_on1 && A.phase != 1 && in) ? A.key_comp[base + kslots + pc] : kInvalid;
+      ks1[e] = (A.key_on1 && A.phase != 1 && in) ? A.key_score[base + kslots + pc] : 0.f;
+    }
+  }
+  for (int w = tid; w < words; w += NT) {
     bm_f[w] = 0;
     bm_s[w] = 0;
   }
+  for (int c = tid; c < A.n_chunks; c += NT) sm.chunk_cnt[c] = (uint32_t)A.cand_cnt[bh * A.n_chunks + c];
+  for (int t = tid; t < 2 * A.n_key_slices; t += NT)
+    sm.slice_cnt[t / A.n_key_slices][t % A.n_key_slices] = A.key_cnt[(int64_t)bh * 2 * A.n_key_slices + t];
   // head maximum from the chunk maxima
   float m = -INFINITY;
-  for (int c = tid; c < A.n_chunks; c += ST) m = fmaxf(m, A.chunk_max[bh * A.n_chunks + c]);
+  for (int c = tid; c < A.n_chunks; c += NT) m = fmaxf(m, A.chunk_max[bh * A.n_chunks + c]);
   m = wave_max(m);
   __syncthreads();
   if ((tid & 63) == 0) sm.red[0][tid >> 6] = (double)m;
@@ -768,56 +898,61 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   __syncthreads();
 
   VATT_STAMP(A.dbg, 1);
-  double acc_f = 0.0;  // this thread's share of D_f = sum over I_f of exp(s_i - m)
+  double acc_f = 0.0, unused = 0.0;  // acc_f: this thread's share of D_f = sum over I_f of exp(s_i - m)
   // ---- I_t (Algorithm 1, line 3) ----
   if (A.phase != 2) {
     if (hs.k > 0) {
+      // slot p = e * NT + tid of the candidate array belongs to chunk p >> cand_shift
       uint32_t xh[EM], xl[EM];
+      const int slots = A.n_chunks * A.cand_cap;
       uint32_t total = 0;
-      for (int c = 0; c < A.n_chunks; ++c) total += (uint32_t)A.cand_cnt[bh * A.n_chunks + c];
+      for (int c = 0; c < A.n_chunks; ++c) total += sm.chunk_cnt[c];
 #pragma unroll
-      for (int e = 0; e < EM; ++e) xh[e] = xl[e] = kInv32;
-      {
-        // flat candidate position p = e * ST + tid; chunk c holds positions [base, base + cnt)
-        uint32_t base = 0;
-        for (int c = 0; c < A.n_chunks; ++c) {
-          const uint32_t cnt = (uint32_t)A.cand_cnt[bh * A.n_chunks + c];
-          const uint64_t* src = A.cand + ((int64_t)bh * A.n_chunks + c) * A.cand_cap;
-#pragma unroll
-          for (int e = 0; e < EM; ++e) {
-            const uint32_t p = (uint32_t)e * ST + tid;
-            if (p >= base && p < base + cnt) {
-              const uint64_t t = src[p - base];
-              xh[e] = (uint32_t)(t >> 32);
-              xl[e] = (uint32_t)t;
-            }
-          }
-          base += cnt;
-        }
+      for (int e = 0; e < EM; ++e) {
+        const int p = e * NT + tid;
+        const int pc = min(p, slots - 1);
+        const int ch = pc >> A.cand_shift, off = pc & (A.cand_cap - 1);
+        const bool ok = p < slots && (uint32_t)off < sm.chunk_cnt[ch];
+        xh[e] = ok ? (uint32_t)(tcand[e] >> 32) : kInv32;
+        xl[e] = ok ? (uint32_t)tcand[e] : kInv32;
       }
       VATT_STAMP(A.dbg, 2);
-      const uint64_t T =
-          ((uint32_t)hs.k >= total) ? (kInvalid - 1ull) : BlockSelect<NT, EM>::run(xh, xl, (uint32_t)hs.k, (uint32_t)hs.k, sm.sel, A.dbg ? A.dbg + 100 : nullptr);
+      const uint64_t T = ((uint32_t)hs.k >= total)
+                             ? (kInvalid - 1ull)
+                             : BlockSelect<NT, EM>::run(xh, xl, (uint32_t)hs.k, (uint32_t)hs.k, sm.sel,
+                                                        A.dbg ? A.dbg + 100 : nullptr);
       VATT_STAMP(A.dbg, 3);
 #pragma unroll
       for (int e = 0; e < EM; ++e)
         if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) O::mark_bit(bm_f, xl[e]);
       __syncthreads();
-      O::compact_bitmap(bm_f, n, idx + A.seg_topk, (uint32_t)A.k_max, row, m, &acc_f, nullptr, sm);
+      O::word_prefix(bm_f, words, wpre, sm);
+      // every chosen candidate knows its place in the ascending list and carries its score in its high word
+#pragma unroll
+      for (int e = 0; e < EM; ++e) {
+        if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) {
+          const uint32_t pos = O::list_pos(bm_f, wpre, xl[e]);
+          if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)xl[e];
+          if (pos < (uint32_t)A.wlist_len) wlist[pos] = __expf(float_from_order_key(~xh[e]) - m);
+        }
+      }
+      __syncthreads();
+      O::sum_wlist(wlist, (uint32_t)hs.k, &acc_f, &unused);
+      __syncthreads();
       VATT_STAMP(A.dbg, 4);
     }
-    for (int i = tid; i < hs.n_sink; i += ST) idx[A.seg_sink + i] = i;
-    for (int i = tid; i < hs.n_win; i += ST) idx[A.seg_win + i] = hs.mid_hi + i;
+    for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
+    for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
   } else {
     // phase 2: rebuild the top-k bitmap from the list written in phase 1
-    for (int t = tid; t < hs.k; t += ST) {
+    for (int t = tid; t < hs.k; t += NT) {
       const int i = O::list_tok(idx, A.seg_topk + t, n);
       O::mark_bit(bm_f, (uint32_t)i);
-      acc_f += (double)expf(row[i] - m);
+      acc_f += (double)__expf(row[i] - m);
     }
   }
-  for (int i = tid; i < hs.n_sink; i += ST) acc_f += (double)expf(row[i] - m);
-  for (int i = tid; i < hs.n_win; i += ST) acc_f += (double)expf(row[hs.mid_hi + i] - m);
+  for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(row[i] - m);
+  for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
   __syncthreads();
 
   // ---- I_bs (Algorithm 2, line 1) and the sums over it ----
@@ -825,25 +960,17 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   double acc_w = 0.0, acc_w2 = 0.0;
   if (hs.n_s > 0) {
     if (A.phase != 2) {
-      bool ok = false;
-      if (!A.force_slow)
-        ok = O::sample_from_list(bm_s, bm_f, hs, (uint32_t)hs.b0, A.key_list + ((int64_t)bh * 2 + 0) * key_stride,
-                                    A.key_cnt[bh * 2 + 0], (uint32_t)A.key_cap0, sm);
-      if (!ok) {
-        __syncthreads();
-        for (int w = tid; w < words; w += ST) bm_s[w] = 0;
-        __syncthreads();
-        flags |= 2 | (O::sample_by_sweep(bm_s, bm_f, hs, (uint32_t)hs.b0, 0u, (uint32_t)h, seed, A.force_slow, sm) << 2);
-      }
+      flags |= O::template draw_sample<EK>(bm_s, bm_f, wpre, hs, (uint32_t)hs.b0, 0, A, h, seed, kc0, ks0, row,
+                                           idx + A.seg_base, (uint32_t)A.b0_max, m, wlist, sm);
       VATT_STAMP(A.dbg, 5);
-      O::compact_bitmap(bm_s, n, idx + A.seg_base, (uint32_t)A.b0_max, row, m, &acc_w, &acc_w2, sm);
+      O::sum_wlist(wlist, (uint32_t)hs.b0, &acc_w, &acc_w2);
+      __syncthreads();
+      for (int w = tid; w < words; w += NT) bm_s[w] = 0;
+      __syncthreads();
       VATT_STAMP(A.dbg, 6);
-      __syncthreads();
-      for (int w = tid; w < words; w += ST) bm_s[w] = 0;
-      __syncthreads();
     } else {
-      for (int t = tid; t < hs.b0; t += ST) {
-        const double wgt = (double)expf(row[O::list_tok(idx, A.seg_base + t, n)] - m);
+      for (int t = tid; t < hs.b0; t += NT) {
+        const double wgt = (double)__expf(row[O::list_tok(idx, A.seg_base + t, n)] - m);
         acc_w += wgt;
         acc_w2 += wgt * wgt;
       }
@@ -937,20 +1064,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 7);
   // ---- I_dyn (Algorithm 1, line 7) ----
   if (bfin > 0) {
-    bool ok = false;
-    if (!A.force_slow && (uint32_t)bfin < (uint32_t)hs.n_s)
-      ok = O::sample_from_list(bm_s, bm_f, hs, (uint32_t)bfin, A.key_list + ((int64_t)bh * 2 + 1) * key_stride,
-                                  A.key_cnt[bh * 2 + 1], (uint32_t)A.key_cap1, sm);
-    if (!ok) {
-      __syncthreads();
-      for (int w = tid; w < words; w += ST) bm_s[w] = 0;
-      __syncthreads();
-      const int slow = O::sample_by_sweep(bm_s, bm_f, hs, (uint32_t)bfin, 1u, (uint32_t)h, seed, A.force_slow, sm);
-      flags |= ((uint32_t)bfin < (uint32_t)hs.n_s ? 8 : 0) | slow;
-    }
+    flags |= O::template draw_sample<EK>(bm_s, bm_f, wpre, hs, (uint32_t)bfin, 1, A, h, seed, kc1, ks1, row,
+                                         idx + A.seg_dyn, (uint32_t)A.b_max, m, nullptr, sm);
     VATT_STAMP(A.dbg, 8);
-    O::compact_bitmap(bm_s, n, idx + A.seg_dyn, (uint32_t)A.b_max, nullptr, 0.f, nullptr, nullptr, sm);
-    VATT_STAMP(A.dbg, 9);
   }
   if (tid == 0) {
     int32_t* c = A.out_counts + (int64_t)bh * 8;
@@ -975,25 +1091,35 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     r.n_s = hs.n_s;
     A.head_rec[bh] = r;
   }
+  VATT_STAMP(A.dbg, 9);
+}
+
+typedef void (*HeadKernel)(HeadArgs);
+// The instantiation for a plan: (workgroup size, top-k slots per thread, sampler slots per thread).
+HeadKernel head_kernel_for(const Plan& pl) {
+  const int64_t cands = (int64_t)pl.n_chunks * pl.cand_cap;
+  if (pl.head_threads == 256) {
+    if (cands <= 16 * 256) {
+      if (pl.key_elems <= 8) return head_kernel<256, 16, 8>;
+      return pl.key_elems <= 16 ? head_kernel<256, 16, 16> : head_kernel<256, 16, 32>;
+    }
+    if (pl.key_elems <= 8) return head_kernel<256, 32, 8>;
+    return pl.key_elems <= 16 ? head_kernel<256, 32, 16> : head_kernel<256, 32, 32>;
+  }
+  return head_kernel<1024, 32, 4>;
 }
 
 }  // namespace
 
 hipError_t set_kernel_attributes(const Plan& pl) {
-  const void* fns[3] = {reinterpret_cast<const void*>(head_kernel<256, 16>),
-                        reinterpret_cast<const void*>(head_kernel<256, 32>),
-                        reinterpret_cast<const void*>(head_kernel<1024, 32>)};
-  for (const void* f : fns) {
-    hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(head_kernel_for(pl)),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
 }
 
-size_t head_kernel_lds_bytes(int n_max, int head_threads) {
+size_t head_kernel_lds_bytes(int n_max, int head_threads, int wlist_len) {
   const size_t words_max = (size_t)(n_max + 31) >> 5;
   const size_t fixed = head_threads == 256 ? sizeof(HeadOps<256>::HeadSmem) : sizeof(HeadOps<1024>::HeadSmem);
-  return ((fixed + 15) & ~size_t(15)) + 2 * words_max * sizeof(uint32_t);
+  return ((fixed + 15) & ~size_t(15)) + 3 * words_max * sizeof(uint32_t) + (size_t)wlist_len * sizeof(float);
 }
 
 hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
@@ -1007,7 +1133,8 @@ hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t
   A.chunk_max = reinterpret_cast<float*>(w + pl.off_chunk_max);
   A.cand = reinterpret_cast<uint64_t*>(w + pl.off_cand);
   A.cand_cnt = reinterpret_cast<int32_t*>(w + pl.off_cand_cnt);
-  A.key_list = reinterpret_cast<uint64_t*>(w + pl.off_key_list);
+  A.key_comp = reinterpret_cast<uint64_t*>(w + pl.off_key_comp);
+  A.key_score = reinterpret_cast<float*>(w + pl.off_key_score);
   A.key_cnt = reinterpret_cast<uint32_t*>(w + pl.off_key_cnt);
   A.sp = pl.sel;
   A.n_pad = pl.n_pad;
@@ -1016,10 +1143,12 @@ hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t
   A.chunk_len = pl.chunk_len;
   A.n_chunks = pl.n_chunks;
   A.cand_cap = pl.cand_cap;
-  A.key_cap0 = pl.key_cap[0];
-  A.key_cap1 = pl.key_cap[1];
-  A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug);
   A.key_slice_len = pl.key_slice_len;
+  A.n_key_slices = pl.n_key_slices;
+  A.key_slice_cap = pl.key_slice_cap;
+  A.key_on0 = pl.key_on[0];
+  A.key_on1 = pl.key_on[1];
+  A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug);
   dim3 grid(pl.n_chunks + pl.n_key_slices, p.n_q_heads, p.batch);
   if (pl.stage_threads == 256)
     hipLaunchKernelGGL((stage1_kernel<256, kChunkElems>), grid, dim3(256), 0, st, A);
@@ -1040,7 +1169,8 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.chunk_max = reinterpret_cast<const float*>(w + pl.off_chunk_max);
   A.cand = reinterpret_cast<const uint64_t*>(w + pl.off_cand);
   A.cand_cnt = reinterpret_cast<const int32_t*>(w + pl.off_cand_cnt);
-  A.key_list = reinterpret_cast<const uint64_t*>(w + pl.off_key_list);
+  A.key_comp = reinterpret_cast<const uint64_t*>(w + pl.off_key_comp);
+  A.key_score = reinterpret_cast<const float*>(w + pl.off_key_score);
   A.key_cnt = reinterpret_cast<const uint32_t*>(w + pl.off_key_cnt);
   A.head_rec = reinterpret_cast<HeadRec*>(w + pl.off_head_rec);
   A.vstat_part = reinterpret_cast<const double*>(w + pl.off_vstat_part);
@@ -1064,8 +1194,12 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.Hq = p.n_q_heads;
   A.n_chunks = pl.n_chunks;
   A.cand_cap = pl.cand_cap;
-  A.key_cap0 = pl.key_cap[0];
-  A.key_cap1 = pl.key_cap[1];
+  A.cand_shift = pl.cand_shift;
+  A.n_key_slices = pl.n_key_slices;
+  A.key_slice_cap = pl.key_slice_cap;
+  A.key_slice_shift = pl.key_slice_shift;
+  A.key_on0 = pl.key_on[0];
+  A.key_on1 = pl.key_on[1];
   A.target = p.target;
   A.phase = phase;
   A.force_slow = pl.force_slow_sampler;
@@ -1074,15 +1208,9 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.k_max = pl.k_max;
   A.b0_max = pl.b0_max;
   A.b_max = pl.b_max;
+  A.wlist_len = pl.wlist_len;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
-  const int64_t cands = (int64_t)pl.n_chunks * pl.cand_cap;
-  const dim3 grid(p.n_q_heads, p.batch);
-  if (pl.head_threads == 256 && cands <= 16 * 256)
-    hipLaunchKernelGGL((head_kernel<256, 16>), grid, dim3(256), pl.head_lds_bytes, st, A);
-  else if (pl.head_threads == 256)
-    hipLaunchKernelGGL((head_kernel<256, 32>), grid, dim3(256), pl.head_lds_bytes, st, A);
-  else
-    hipLaunchKernelGGL((head_kernel<1024, 32>), grid, dim3(1024), pl.head_lds_bytes, st, A);
+  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, p.batch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
   return hipGetLastError();
 }
 

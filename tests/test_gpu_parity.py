@@ -186,6 +186,27 @@ def test_exact_sampler_path_gives_identical_results():
     sess.close()
 
 
+def test_sampler_without_candidate_lists_gives_identical_results():
+    say("sampler sweep path (no candidate lists)")
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=18, batch=2, n=7000)
+    sess = _session(wl)
+    fast = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NO_SAMPLER_CANDIDATES, 1)
+    sweep = _run(sess)
+    assert np.all(sweep["counts"][..., 7] & 2 == 2)      # base sample drawn by the in-kernel sweep
+    for key in ("O", "lse", "b_star", "stats"):
+        assert np.array_equal(fast[key], sweep[key]), key
+    assert np.array_equal(fast["counts"][..., :7], sweep["counts"][..., :7])
+    for b in range(2):
+        for h in range(wl.n_q_heads):
+            gf, gs_ = gpu_segments(fast, b, h), gpu_segments(sweep, b, h)
+            for key in ("I_t", "I_bs", "I_dyn"):
+                assert np.array_equal(gf[key], gs_[key]), (b, h, key)
+    check_all(wl, sweep, label="sweep-sampler")
+    sess.close()
+
+
 # ---------------------------------------------------- dense, and check (a) ----
 def test_dense_decode_matches_eq1():
     say("dense decode")
