@@ -76,8 +76,8 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
       ok[u] = i < hi;
       kk[u] = vv[u] = make_uint4(0u, 0u, 0u, 0u);
       if (ok[u]) {
-        kk[u] = *reinterpret_cast<const uint4*>(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, i) + sub * 8);
-        vv[u] = *reinterpret_cast<const uint4*>(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, i) + sub * 8);
+        kk[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, i) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, i) + sub * 8);
       }
     }
     float s[G][U];

