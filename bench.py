@@ -19,6 +19,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+
+# HBM bytes per score-kernel launch from two rocprofv3 --pmc runs of `bench.py --only score` (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for `bench.py --only copy`, a
+# 256 MiB device copy: FETCH_SIZE reads 131083.5 KiB for its 262144 KiB (factor 1.99983), WRITE_SIZE 262144
+# (factor 1).  Score kernel at config 2: FETCH_SIZE 32825.5, WRITE_SIZE 4096.0; at config 3: 524825.9 and 65536.0.  The summaries are kept under
+# profiles/.  Only the configurations that were measured have a figure.
+SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32825.5 * 262144.0 / 131083.5 + 4096.0) * 1024),
+                              "config3": int((524825.9 * 262144.0 / 131083.5 + 65536.0) * 1024)}
 LLAMA8B_LAYERS = 32
 
 
@@ -65,7 +73,7 @@ def cpu_baseline(wl, budget_s=12.0):
                        wl.v_f32(b, h // g, n).astype(np.float64), seed=int(wl.seeds[b]), head=h, params=wl.params)
         done += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or done >= 4 * total_heads:
+        if el >= budget_s:
             break
     if limiter is not None:
         limiter.unregister() if hasattr(limiter, "unregister") else None
@@ -83,11 +91,11 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
     ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score' or 'dense' in the timed loop")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the step shards by sequence and "
-              "KV head without communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "KV head without communication). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -118,7 +126,12 @@ def main():
         sess.dense(k=ks[i % nbuf], v=vs[i % nbuf])
 
     if args.only:
-        fn = dict(decode=step, score=score_only, dense=dense)[args.only]
+        if args.only == "copy":
+            # plain device copy of known size: calibrates the HBM byte counters of the profiler
+            src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+            dsts = [torch.empty_like(src) for _ in range(4)]
+        fn = dict(decode=step, score=score_only, dense=dense,
+                  copy=lambda i: dsts[i % 4].copy_(src) if args.only == "copy" else None)[args.only]
         for i in range(args.warmup):
             fn(i)
         ms = time_calls(fn, args.steps, torch)
@@ -191,7 +204,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": score_kernel_bytes / (ms_score * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get("config%d" % args.config),
             "bytes_per_launch": score_kernel_bytes,
             "us_per_launch": ms_score * 1e3,
         },
