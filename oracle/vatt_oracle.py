@@ -25,7 +25,9 @@ Readings of the paper taken where it is silent (each also listed in the design
 notes): softmax scale is an explicit factor sm_scale; sink / window are absolute
 token counts; top-k is taken over the tokens outside sink and window, so the
 three sets are disjoint and n_f is the sum of their sizes; sampling is without
-replacement; the base sample holds floor(f_b * n_s) tokens (at least 2) and
+replacement, by sequential uniform draws from the middle region that skip
+top-k members and repeats (the paper only says "uniform sample"; the cost is
+proportional to the sample, not to the context); the base sample holds floor(f_b * n_s) tokens (at least 2) and
 sample variances divide by (b0 - 1); D and ||N|| in the budget formulas are
 the full quantities D_f + residual estimate; the budget is ceil(b*), lower
 capped by the base sample size and upper capped by n_s; I_dyn is a fresh draw
@@ -78,36 +80,103 @@ def philox4x32_10(ctr: Sequence, key: Sequence[int]) -> List[np.ndarray]:
     return [c.astype(np.uint32) for c in (c0, c1, c2, c3)]
 
 
-def token_keys(n: int, seed: int, head: int, stream: int) -> np.ndarray:
-    """32-bit sampling key u_i of every token i < n.
+def draw_words(j_lo: int, j_hi: int, seed: int, head: int, stream: int) -> np.ndarray:
+    """Words u_j, j in [j_lo, j_hi), of the sampler's draw sequence.
 
-    Token i reads word (i mod 4) of Philox4x32-10 applied to the counter
-    (i div 4, stream, head, 0) under the key (low 32 bits of seed, high 32 bits
+    Draw j reads word (j mod 4) of Philox4x32-10 applied to the counter
+    (j div 4, stream, head, 0) under the key (low 32 bits of seed, high 32 bits
     of seed).  `head` is the query-head index, `stream` separates the base
     sample (0) from the final sample (1).
     """
-    nblk = (n + 3) // 4
-    blk = np.arange(nblk, dtype=np.uint64)
+    b_lo, b_hi = j_lo // 4, (j_hi + 3) // 4
+    nblk = max(b_hi - b_lo, 0)
+    blk = np.arange(b_lo, b_lo + nblk, dtype=np.uint64)
     out = philox4x32_10(
         (blk, np.full(nblk, stream, np.uint64), np.full(nblk, head, np.uint64), np.zeros(nblk, np.uint64)),
         (int(seed) & _MASK32, (int(seed) >> 32) & _MASK32),
     )
-    return np.stack(out, axis=1).reshape(-1)[:n]
+    return np.stack(out, axis=1).reshape(-1)[j_lo - 4 * b_lo: j_hi - 4 * b_lo]
 
 
-def uniform_sample(residual: np.ndarray, c: int, keys: np.ndarray) -> np.ndarray:
-    """uniform-sample of Algorithms 1 and 2: c residual tokens, without replacement.
+def bounded_draw(u, L: int, bits: int = 32):
+    """Map uniform `bits`-bit words to [0, L) without bias (multiply-and-reject).
 
-    Every token carries an independent uniform 32-bit key; the sample is the c
-    residual tokens with the smallest (key, index) pairs, which is a uniformly
-    distributed c-subset.  Returned in ascending index order.
+    With x = u * L, the value is the high part x >> bits; the word is rejected
+    when the low part x mod 2^bits is below 2^bits mod L.  Every value of
+    [0, L) then keeps exactly floor(2^bits / L) words, so an accepted value
+    is exactly uniform.  Returns (accepted, value), arrays like u.
     """
+    u = np.asarray(u, dtype=np.uint64)
+    x = u * np.uint64(L)
+    low = x & np.uint64((1 << bits) - 1)
+    thr = (1 << bits) % int(L)
+    return low >= np.uint64(thr), (x >> np.uint64(bits)).astype(np.int64)
+
+
+def default_draw_cap(L: int) -> int:
+    """Draws after which the sampler stops drawing and completes the sample in index order.
+
+    With at least half of the residual still free, a draw is accepted with
+    probability >= 1 / (2 L); 64 L draws then fail to deliver one token with
+    probability about e^-32.  The cap only exists so that the procedure is finite.
+    """
+    return 64 * int(L) + 4096
+
+
+def uniform_sample(residual: np.ndarray, c: int, *, mid_lo: int, mid_len: int, seed: int, head: int,
+                   stream: int, draw_cap: Optional[int] = None) -> np.ndarray:
+    """uniform-sample of Algorithms 1 and 2: c residual tokens, uniformly, without replacement.
+
+    Sequential draws: draw j proposes the token mid_lo + bounded_draw(u_j,
+    mid_len) of the middle region (the tokens outside sink and window); it is
+    accepted when the word is not rejected by bounded_draw, the token is a
+    residual token (not in the top-k set) and it has not been accepted before.
+    Drawing uniformly from the tokens not yet chosen, one at a time, is simple
+    random sampling without replacement.
+
+    c <= n_s / 2: the sample is the first c accepted tokens.
+    c >  n_s / 2: the first n_s - c accepted tokens are left out and the
+                  sample is the rest of the residual (the complement of a
+                  uniform subset is a uniform subset), so that the number of
+                  draws stays proportional to min(c, n_s - c).
+    If `draw_cap` draws (default_draw_cap) do not suffice, the missing tokens
+    are the lowest-index residual tokens not yet accepted.
+    Returned in ascending index order.
+    """
+    residual = np.asarray(residual, dtype=np.int64)
+    n_s = int(residual.shape[0])
     c = int(c)
     if c <= 0:
         return np.empty(0, dtype=np.int64)
-    u = keys[residual]
-    order = np.lexsort((residual, u))  # primary key u, ties by index
-    return np.sort(residual[order[:c]])
+    if c >= n_s:
+        return residual.copy()
+    invert = 2 * c > n_s
+    want = n_s - c if invert else c
+    cap = default_draw_cap(mid_len) if draw_cap is None else int(draw_cap)
+    is_res = set(residual.tolist())
+    chosen: List[int] = []
+    chosen_set = set()
+    j = 0
+    while len(chosen) < want and j < cap:
+        j_hi = min(j + 4096, cap)
+        ok, val = bounded_draw(draw_words(j, j_hi, seed, head, stream), mid_len)
+        for a, v in zip(ok.tolist(), val.tolist()):
+            if not a:
+                continue
+            t = mid_lo + v
+            if t in is_res and t not in chosen_set:
+                chosen.append(t)
+                chosen_set.add(t)
+                if len(chosen) == want:
+                    break
+        j = j_hi
+    if len(chosen) < want:
+        rest = [t for t in residual.tolist() if t not in chosen_set]
+        chosen.extend(rest[: want - len(chosen)])
+    chosen_arr = np.asarray(chosen, dtype=np.int64)
+    if invert:
+        return np.setdiff1d(residual, chosen_arr)
+    return np.sort(chosen_arr)
 
 
 # --------------------------------------------------------------------------
@@ -320,15 +389,17 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
                    O=N / D, lse=m + math.log(D), D_out=D, N_out=N)
         return res
     b0 = base_count(n_s, int(params.get("base_abs", 0)), float(params.get("base_frac", 0.0)))
-    keys0 = token_keys(n, seed, head, 0)
-    I_bs = uniform_sample(residual, b0, keys0)
+    mid_lo, mid_len = int(I_s.shape[0]), n - int(I_s.shape[0]) - int(I_l.shape[0])
+    draw_cap = params.get("draw_cap")
+    I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
+                          draw_cap=draw_cap)
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
     b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target)
     b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
     if forced_b is not None:
         b = int(forced_b)
-    keys1 = token_keys(n, seed, head, 1)
-    I_dyn = uniform_sample(residual, b, keys1)
+    I_dyn = uniform_sample(residual, b, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
+                           draw_cap=draw_cap)
     N, D = estimate(s, V, m, I_f, I_dyn, n_s)
     res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st,
                O=N / D, lse=m + math.log(D), D_out=D, N_out=N)

@@ -53,27 +53,46 @@ def test_philox_is_a_bijection_on_a_small_slice():
     assert len(set(zip(packed.tolist(), packed2.tolist()))) == 4096
 
 
-def test_token_keys_counter_layout():
+def test_draw_words_counter_layout():
     seed = (0xDEADBEEF << 32) | 0x12345678
-    keys = vo.token_keys(23, seed, head=5, stream=1)
-    assert keys.dtype == np.uint32 and keys.shape == (23,)
-    for i in (0, 1, 3, 4, 7, 22):
+    words = vo.draw_words(0, 23, seed, head=5, stream=1)
+    assert words.dtype == np.uint32 and words.shape == (23,)
+    for j in (0, 1, 3, 4, 7, 22):
         blk = vo.philox4x32_10(
-            [np.array([c], dtype=np.uint64) for c in (i // 4, 1, 5, 0)], (0x12345678, 0xDEADBEEF))
-        assert int(keys[i]) == int(blk[i % 4][0])
-    # stream, head and seed each change the keys
-    assert not np.array_equal(keys, vo.token_keys(23, seed, 5, 0))
-    assert not np.array_equal(keys, vo.token_keys(23, seed, 6, 1))
-    assert not np.array_equal(keys, vo.token_keys(23, seed + 1, 5, 1))
-    assert not np.array_equal(keys, vo.token_keys(23, seed + (1 << 32), 5, 1))
+            [np.array([c], dtype=np.uint64) for c in (j // 4, 1, 5, 0)], (0x12345678, 0xDEADBEEF))
+        assert int(words[j]) == int(blk[j % 4][0])
+    # any window of the sequence is the same sequence
+    assert np.array_equal(vo.draw_words(5, 19, seed, 5, 1), words[5:19])
+    assert vo.draw_words(7, 7, seed, 5, 1).shape == (0,)
+    # stream, head and seed each change the words
+    assert not np.array_equal(words, vo.draw_words(0, 23, seed, 5, 0))
+    assert not np.array_equal(words, vo.draw_words(0, 23, seed, 6, 1))
+    assert not np.array_equal(words, vo.draw_words(0, 23, seed + 1, 5, 1))
+    assert not np.array_equal(words, vo.draw_words(0, 23, seed + (1 << 32), 5, 1))
 
 
-def test_token_keys_look_uniform():
-    keys = vo.token_keys(1 << 16, 99, 3, 0).astype(np.float64) / 2.0 ** 32
-    assert abs(keys.mean() - 0.5) < 4 * math.sqrt(1 / 12 / 65536)
-    hist, _ = np.histogram(keys, bins=64, range=(0, 1))
+def test_draw_words_look_uniform():
+    u = vo.draw_words(0, 1 << 16, 99, 3, 0).astype(np.float64) / 2.0 ** 32
+    assert abs(u.mean() - 0.5) < 4 * math.sqrt(1 / 12 / 65536)
+    hist, _ = np.histogram(u, bins=64, range=(0, 1))
     chi2 = ((hist - 1024.0) ** 2 / 1024.0).sum()
     assert chi2 < 130.0  # chi2(63) 99.999 % point is ~ 121
+
+
+def test_bounded_draw_is_exactly_uniform_by_enumeration():
+    # all 2^12 words of a 12-bit generator: every value keeps exactly floor(4096 / L) words
+    for L in (1, 2, 3, 7, 10, 100, 1000, 4095, 4096):
+        ok, val = vo.bounded_draw(np.arange(4096), L, bits=12)
+        assert val.min() >= 0 and val.max() < L
+        kept = np.bincount(val[ok], minlength=L)
+        assert np.all(kept == 4096 // L)
+        assert int((~ok).sum()) == 4096 % L
+    # 32-bit words: the value is floor(u L / 2^32), rejection is rare
+    rng = np.random.default_rng(0)
+    u = rng.integers(0, 1 << 32, size=1000, dtype=np.uint64)
+    ok, val = vo.bounded_draw(u, 32512)
+    assert [int(v) for v in val] == [(int(x) * 32512) >> 32 for x in u]
+    assert ok.all()  # 2^32 mod 32512 words out of 2^32 are rejected
 
 
 # ------------------------------------------------------- normal quantile ----
@@ -159,48 +178,88 @@ def test_topk_and_base_counts():
 
 
 # ------------------------------------------------------------- sampler ------
+def _sample(residual, c, seed, head=0, stream=0, lo=None, L=None, cap=None):
+    residual = np.asarray(residual)
+    lo = int(residual.min()) if lo is None else lo
+    L = int(residual.max()) - lo + 1 if L is None else L
+    return vo.uniform_sample(residual, c, mid_lo=lo, mid_len=L, seed=seed, head=head, stream=stream, draw_cap=cap)
+
+
+def test_uniform_sample_worked_example_from_the_published_vector():
+    # Philox4x32-10 of the all-zero counter under the all-zero key is 6627e8d5 e169c58d bc57ac4c 9b00dbd8
+    # (first row of the known-answer file).  With a middle region of 10 tokens starting at token 5 the first
+    # four draws of (seed 0, head 0, stream 0) propose floor(u * 10 / 2^32) = 3, 8, 7, 6 -> tokens 8, 13, 12, 11.
+    assert [(w * 10) >> 32 for w in (0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8)] == [3, 8, 7, 6]
+    residual = np.arange(5, 15)
+    assert _sample(residual, 1, 0, lo=5, L=10).tolist() == [8]
+    assert _sample(residual, 3, 0, lo=5, L=10).tolist() == [8, 12, 13]
+    assert _sample(residual, 4, 0, lo=5, L=10).tolist() == [8, 11, 12, 13]
+    # token 13 in the top-k set (not residual): its draw is skipped
+    no13 = np.setdiff1d(residual, [13])
+    assert _sample(no13, 3, 0, lo=5, L=10).tolist() == [8, 11, 12]
+    # more than half of the residual: the first n_s - c accepted tokens are the ones left out
+    assert _sample(residual, 9, 0, lo=5, L=10).tolist() == np.setdiff1d(residual, [8]).tolist()
+    assert _sample(residual, 7, 0, lo=5, L=10).tolist() == np.setdiff1d(residual, [8, 13, 12]).tolist()
+    assert _sample(residual, 10, 0, lo=5, L=10).tolist() == residual.tolist()
+    assert _sample(residual, 0, 0, lo=5, L=10).tolist() == []
+
+
 def test_uniform_sample_invariants():
-    n = 500
     residual = np.setdiff1d(np.arange(10, 480), np.arange(50, 400, 7))
-    keys = vo.token_keys(n, 42, 2, 0)
+    n_s = len(residual)
     prev = np.empty(0, dtype=np.int64)
-    for c in [0, 1, 2, 17, 100, len(residual)]:
-        smp = vo.uniform_sample(residual, c, keys)
+    for c in [0, 1, 2, 17, 100, n_s // 2]:
+        smp = _sample(residual, c, 42, head=2, lo=10, L=470)
         assert smp.shape[0] == c
         assert np.all(np.diff(smp) > 0)                  # ascending, no duplicates
         assert np.all(np.isin(smp, residual))            # only residual tokens
-        assert np.all(np.isin(prev, smp))                # prefix property: sample(c) in sample(c+1)
+        assert np.all(np.isin(prev, smp))                # first-c-accepted: sample(c) lies in sample(c+1)
         prev = smp
-    # the sample is the c smallest keys: every chosen key <= every unchosen key
-    smp = vo.uniform_sample(residual, 60, keys)
-    rest = np.setdiff1d(residual, smp)
-    assert keys[smp].max() <= keys[rest].min()
-    assert np.array_equal(smp, vo.uniform_sample(residual, 60, vo.token_keys(n, 42, 2, 0)))
+    prev = residual
+    for c in [n_s, n_s - 1, n_s - 30, n_s // 2 + 1]:     # complement regime shrinks the same way
+        smp = _sample(residual, c, 42, head=2, lo=10, L=470)
+        assert smp.shape[0] == c and np.all(np.diff(smp) > 0) and np.all(np.isin(smp, residual))
+        assert np.all(np.isin(smp, prev))
+        prev = smp
+    assert np.array_equal(_sample(residual, 60, 42, head=2, lo=10, L=470), _sample(residual, 60, 42, head=2, lo=10, L=470))
+    assert not np.array_equal(_sample(residual, 60, 42, head=2, lo=10, L=470), _sample(residual, 60, 42, head=2, stream=1, lo=10, L=470))
 
 
-def test_uniform_sample_is_uniform_over_subsets():
-    # n_s = 5, c = 2: each of the 10 subsets should appear with probability 1/10
+def test_uniform_sample_draw_cap_completes_in_index_order():
+    residual = np.arange(5, 15)
+    # cap of two draws: tokens 8 and 13 are accepted, the rest of a sample of 4 is filled from the low end
+    assert _sample(residual, 4, 0, lo=5, L=10, cap=2).tolist() == [5, 6, 8, 13]
+    assert _sample(residual, 4, 0, lo=5, L=10, cap=0).tolist() == [5, 6, 7, 8]
+    # complement regime: tokens left out are 8 (drawn) and then 5, 6 (filled)
+    assert _sample(residual, 7, 0, lo=5, L=10, cap=1).tolist() == [7, 9, 10, 11, 12, 13, 14]
+
+
+@pytest.mark.parametrize("c", [2, 3])
+def test_uniform_sample_is_uniform_over_subsets(c):
+    # n_s = 5 inside a middle region of 7 tokens; c = 2 (direct) and c = 3 (complement): each of the 10
+    # subsets should appear with probability 1/10
     residual = np.array([2, 3, 5, 6, 7])
     counts = {}
     trials = 20000
     for seed in range(trials):
-        smp = tuple(vo.uniform_sample(residual, 2, vo.token_keys(9, seed, 0, 1)).tolist())
+        smp = tuple(_sample(residual, c, seed, stream=1, lo=2, L=7).tolist())
         counts[smp] = counts.get(smp, 0) + 1
     assert len(counts) == 10
-    chi2 = sum((c - trials / 10) ** 2 / (trials / 10) for c in counts.values())
+    chi2 = sum((v - trials / 10) ** 2 / (trials / 10) for v in counts.values())
     assert chi2 < 33.7  # chi2(9) 99.99 % point
 
 
-def test_uniform_sample_inclusion_frequency():
-    residual = np.arange(8, 72)
-    c, trials = 16, 6000
+@pytest.mark.parametrize("c", [16, 40])
+def test_uniform_sample_inclusion_frequency(c):
+    residual = np.setdiff1d(np.arange(8, 76), [20, 21, 40, 63])   # 64 residual tokens in a region of 68
+    trials = 6000
     hits = np.zeros(80)
     for seed in range(trials):
-        hits[vo.uniform_sample(residual, c, vo.token_keys(80, 1000 + seed, 4, 0))] += 1
+        hits[_sample(residual, c, 1000 + seed, head=4, lo=8, L=68)] += 1
     p = c / len(residual)
     z = (hits[residual] - trials * p) / math.sqrt(trials * p * (1 - p))
     assert np.abs(z).max() < 4.5
-    assert hits[:8].sum() == 0 and hits[72:].sum() == 0
+    assert hits[:8].sum() == 0 and hits[76:].sum() == 0 and hits[[20, 21, 40, 63]].sum() == 0
 
 
 # ------------------------------------------------- estimator, brute force ---
