@@ -41,14 +41,23 @@
  *               (the result for that sequence is then meaningless, but no
  *               access leaves the allocation).
  *
- * Sampler
- *   Token i of (sequence, query head h) gets the 32-bit key
- *       u_i = Philox4x32-10(counter = (i >> 2, stream, h, 0),
- *                           key = (seed & 0xffffffff, seed >> 32))[i & 3]
- *   with the sequence's seed for this call, stream 0 for the base sample and 1
- *   for the final sample.  A sample of size c is the c residual tokens with the
- *   smallest (u_i, i); it is a uniform c-subset, independent of scheduling, and
- *   reproducible from (seed, sequence, head).
+ * Sampler (the paper asks for a uniform sample of the residual tokens, Alg. 1
+ * line 7 and Alg. 2 line 1, and leaves the procedure open)
+ *   Stream 0 is the base sample, stream 1 the final sample.  Draw j of
+ *   (sequence, query head h, stream) is the 32-bit word
+ *       u_j = Philox4x32-10(counter = (j >> 2, stream, h, 0),
+ *                           key = (seed & 0xffffffff, seed >> 32))[j & 3]
+ *   with the sequence's seed for this call.  With L tokens between sink and
+ *   window, x = u_j * L: the draw is void when x mod 2^32 < 2^32 mod L, else it
+ *   proposes middle token x >> 32 (exactly uniform).  A proposal is accepted
+ *   when the token is not in the top-k set and was not accepted before.  A
+ *   sample of size c <= n_s / 2 is the first c accepted tokens; for larger c
+ *   the first n_s - c accepted tokens are the ones left out; c = n_s is the
+ *   whole residual.  This is simple random sampling without replacement,
+ *   costs work proportional to min(c, n_s - c), does not depend on
+ *   scheduling, and is reproducible from (seed, sequence, head).  After
+ *   64 L + 4096 draws (never reached in practice) the missing tokens would be
+ *   taken in index order.
  */
 #ifndef VATT_H_
 #define VATT_H_
@@ -113,13 +122,12 @@ int vatt_plan_create(const vatt_params* params, int device, vatt_plan** out);
 void vatt_plan_destroy(vatt_plan* plan);
 
 /*
- * Options (host only).  VATT_OPT_EXACT_SAMPLER_ONLY = 1 makes the sampler skip its fast path (a verified
- * guess of the key threshold) and always run the slower exact radix descent; results are identical.
- * It exists so that the slow path can be exercised on purpose.
- * VATT_OPT_NO_SAMPLER_CANDIDATES = 1 stops the selection stage from preparing sampler candidate lists, so
- * that every sample is drawn by the per-head sweep (fast or slow path); results are identical.
+ * Options (host only), for tests.  VATT_OPT_SAMPLER_SMALL_BATCHES = 1 makes the sampler work through
+ * the draw sequence in batches of 256 draws only (it normally uses up to 1024); results are identical.
+ * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that
+ * the completion rule can be exercised.
  */
-enum { VATT_OPT_EXACT_SAMPLER_ONLY = 1, VATT_OPT_NO_SAMPLER_CANDIDATES = 2 };
+enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
 
 /* Bytes of device workspace every launching call needs (256-byte aligned base). */
@@ -131,8 +139,9 @@ size_t vatt_plan_score_stride(const vatt_plan* plan);
 
 /*
  * Layout of out_idx: per (sequence, query head) `vatt_plan_index_capacity` int32 slots holding five
- * segments at fixed offsets, each filled from its start in ascending token order:
- *   segment 0 sink, 1 window, 2 top-k, 3 base sample, 4 final sample.
+ * segments at fixed offsets, each filled from its start:
+ *   segment 0 sink, 1 window, 2 top-k (these three in ascending token order), 3 base sample, 4 final sample
+ *   (in the order in which the sampler accepted the tokens, or ascending when the sample is a complement).
  * vatt_plan_index_segment returns the offset (in ints) of a segment, or -1.
  */
 size_t vatt_plan_index_capacity(const vatt_plan* plan);
@@ -152,9 +161,9 @@ int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment);
  *   out_lse      device, float [B, Hq] or NULL: ln of the estimated denominator, ln(D), of Section 4.1
  *   out_idx      device, int32 [B, Hq, index_capacity]
  *   out_counts   device, int32 [B, Hq, 8] = { |I_s|, |I_l|, |I_t|, |I_bs|, b, n_s, n, flags }
- *                flags (informational): bit 0 final sample drawn by the slow exact descent, bit 1 base sample
- *                drawn by an in-kernel sweep instead of the prepared candidate list, bit 2 base sample by the
- *                slow descent, bit 3 final sample by an in-kernel sweep
+ *                flags (informational): bit 0 base sample taken as a complement, bit 1 final sample taken as a
+ *                complement, bit 2 base sample needed more than one batch of draws, bit 3 final sample did,
+ *                bit 4 the draw limit was reached, bit 5 a batch was redone in small batches
  *   out_budget_raw device, double [B, Hq] or NULL: b* before rounding and clamping
  *   out_stats    device, float [B, Hq, 4] or NULL = { D_hat, sigma^2, Tr Sigma, ||N_hat||^2 }, all in the
  *                scale where the largest score of the head has weight 1 (w_i = exp(s_i - max s))

@@ -24,8 +24,8 @@ VATT_TARGET_D, VATT_TARGET_N, VATT_TARGET_SDPA = 0, 1, 2
 VATT_LAYOUT_CONTIGUOUS, VATT_LAYOUT_PAGED = 0, 1
 VATT_WS_SCORES = 0
 VATT_WS_DEBUG = 1
-VATT_OPT_EXACT_SAMPLER_ONLY = 1
-VATT_OPT_NO_SAMPLER_CANDIDATES = 2
+VATT_OPT_SAMPLER_SMALL_BATCHES = 1
+VATT_OPT_SAMPLER_DRAW_CAP = 2
 
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",

@@ -8,7 +8,7 @@
 
 namespace vatt {
 
-size_t head_kernel_lds_bytes(int n_max, int head_threads, int wlist_len);
+size_t head_kernel_lds_bytes(int n_max, int head_threads);
 
 namespace {
 
@@ -85,7 +85,8 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.sel.base_abs = p.base_abs;
   pl.sel.topk_frac = (double)p.topk_frac;
   pl.sel.base_frac = (double)p.base_frac;
-  pl.force_slow_sampler = 0;
+  pl.sampler_small_batches = 0;
+  pl.sampler_draw_cap = 0;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
@@ -122,41 +123,6 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
     }
   }
   if (pl.n_chunks > kMaxChunks) return VATT_E_UNSUPPORTED_SHAPE;
-  pl.key_slice_len = 8 * pl.stage_threads;  // two Philox blocks (eight tokens) per thread and stream
-  pl.n_key_slices = (n_max + pl.key_slice_len - 1) / pl.key_slice_len;
-  // sampler candidates: slots per slice for the count expected at full length, a quarter of headroom and six
-  // standard deviations.  Short sequences have a higher rate of candidates per token and may overfill a
-  // slice; their heads then draw the sample with the in-kernel sweep, which is cheap when n is small.
-  double worst = 0.0;
-  {
-    const HeadSizes hs = head_sizes(n_max, pl.sel);
-    if (hs.n_s > 0) {
-      const double c1 = std::min((double)hs.n_s, 2.0 * hs.b0 + 64.0);
-      const double rate = std::min(1.0, (c1 + 6.0 * (std::sqrt(c1) + 1.0) + 8.0) / (double)hs.n_s);
-      worst = rate * std::min(n_max, pl.key_slice_len);
-    }
-  }
-  const double slots = 1.25 * worst + 6.0 * std::sqrt(worst) + 16.0;
-  pl.key_slice_shift = 4;
-  while ((1 << pl.key_slice_shift) < slots) ++pl.key_slice_shift;
-  pl.key_slice_cap = 1 << pl.key_slice_shift;
-  // (with enough heads to fill the chip the lists buy nothing: the same key work is then spread anyway)
-  const bool lists = p.batch * p.n_q_heads < 2 * pl.num_cus && pl.n_key_slices <= kMaxKeySlices && (int64_t)pl.n_key_slices * pl.key_slice_cap <= (pl.head_threads == 256 ? 8192 : 4096) &&
-                     pl.key_slice_cap <= pl.key_slice_len;
-  pl.key_on[0] = pl.key_on[1] = lists ? 1 : 0;
-  pl.key_lists_fit = lists ? 1 : 0;
-  if (!lists) {
-    if (n_max >= 65536) pl.head_threads = 1024;  // long sweeps: more threads per head
-    pl.n_key_slices = 1;  // the role still exists in the grid; it writes empty lists
-    pl.key_slice_len = std::max(pl.key_slice_len, n_max);
-    pl.key_slice_shift = 4;
-    pl.key_slice_cap = 16;
-  }
-  {
-    const int64_t kslots = (int64_t)pl.n_key_slices * pl.key_slice_cap;
-    pl.key_elems = pl.head_threads == 256 ? (kslots <= 8 * 256 ? 8 : (kslots <= 16 * 256 ? 16 : 32)) : 4;
-  }
-  pl.wlist_len = std::max(pl.k_max, pl.b0_max);
 
   const int heads = p.batch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
@@ -172,7 +138,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.seg_off[3] = pl.seg_off[2] + pl.k_max;
   pl.seg_off[4] = pl.seg_off[3] + pl.b0_max;
   pl.idx_cap = align_up((size_t)(pl.seg_off[4] + pl.b_max), 4);
-  pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads, pl.wlist_len);
+  pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads);
   if (pl.head_lds_bytes > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
 
   size_t off = 0;
@@ -185,9 +151,6 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.off_chunk_max = take((size_t)heads * pl.n_chunks * sizeof(float));
   pl.off_cand = take((size_t)heads * pl.n_chunks * pl.cand_cap * sizeof(uint64_t));
   pl.off_cand_cnt = take((size_t)heads * pl.n_chunks * sizeof(int32_t));
-  pl.off_key_comp = take((size_t)heads * 2 * pl.n_key_slices * pl.key_slice_cap * sizeof(uint64_t));
-  pl.off_key_score = take((size_t)heads * 2 * pl.n_key_slices * pl.key_slice_cap * sizeof(float));
-  pl.off_key_cnt = take((size_t)heads * 2 * pl.n_key_slices * sizeof(uint32_t));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
@@ -286,12 +249,13 @@ int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment) {
 
 int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   if (!plan) return VATT_E_INVALID_ARG;
-  if (option == VATT_OPT_EXACT_SAMPLER_ONLY) {
-    plan->pl.force_slow_sampler = value ? 1 : 0;
+  if (option == VATT_OPT_SAMPLER_SMALL_BATCHES) {
+    plan->pl.sampler_small_batches = value ? 1 : 0;
     return VATT_OK;
   }
-  if (option == VATT_OPT_NO_SAMPLER_CANDIDATES) {
-    plan->pl.key_on[0] = plan->pl.key_on[1] = (value || !plan->pl.key_lists_fit) ? 0 : 1;
+  if (option == VATT_OPT_SAMPLER_DRAW_CAP) {
+    if (value < 0) return VATT_E_INVALID_ARG;
+    plan->pl.sampler_draw_cap = (uint32_t)value;
     return VATT_OK;
   }
   return VATT_E_INVALID_ARG;
@@ -317,7 +281,7 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
-  VATT_LAUNCH(launch_stage1(pl, seq_lens, seq_seeds, workspace, st));
+  VATT_LAUNCH(launch_stage1(pl, seq_lens, workspace, st));
   if (pl.p.target == VATT_TARGET_D) {
     VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   } else {

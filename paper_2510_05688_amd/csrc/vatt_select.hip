@@ -1,29 +1,25 @@
 // Index selection and budget: lines 1-8 of Algorithm 1 and all of Algorithm 2, per (sequence, query head).
 //
-// Every selection here is "the c smallest of a set of distinct 64-bit composites":
-//   top-k     composite = (~order_key(score) << 32) | token     (largest score first, ties to the lower token)
-//   samples   composite = (philox_key(token) << 32) | token     (smallest key first, ties to the lower token)
-// Distinct composites make every selection a pure set operation: the result does not depend on
-// the order in which lanes, waves or workgroups contribute, so index sets and budgets are
-// reproducible bit for bit.  Floating-point sums are taken in ascending token order with a fixed
-// tree, so the statistics are reproducible too.
+// Top-k: every token of the middle region carries the 64-bit composite (~order_key(score) << 32) | token,
+// distinct per token, so "the k largest scores, ties to the lower token" is "the k smallest composites": a pure
+// set operation whose result does not depend on the order in which lanes, waves or workgroups contribute.
+//
+// Samples: sequential uniform draws from the middle region (Philox4x32-10 words, unbiased multiply-and-reject
+// mapping), skipping top-k members and tokens drawn before; the first c accepted tokens are the sample (for
+// c > n_s / 2 they are the tokens left out).  The kernel processes the draw sequence in batches: all draws of
+// a batch are generated at once, repeated tokens are resolved to their earliest draw, and a prefix count in
+// draw order finds where the sample is complete; the result equals the sequential procedure bit for bit.
+//
+// Floating-point sums are taken in a fixed order, so the statistics and the budget are reproducible too.
 //
 // Two kernels:
-//   stage1_kernel  workgroups [0, n_chunks) of a head: one chunk of the head's score row each; the chunk is
-//                  kept in registers, a threshold that keeps at least its own top-k is found by counting,
-//                  and the composites under it are written as candidates (any member of the global top-k is
-//                  in its chunk's top-k), plus the chunk maximum.
-//                  Remaining workgroups: Philox keys of one slice of tokens for both sampler streams; tokens
-//                  whose key lies under a conservative bound of the threshold that the base sample
-//                  (stream 0) and a final sample of up to twice that size (stream 1) will need are written,
-//                  with their scores, as sampler candidates.  This is integer work that does not depend on
-//                  the scores, spread over the whole chip instead of the one workgroup a head gets next.
-//   head_kernel    one workgroup per head: selects the exact top-k among the chunk candidates, builds the
-//                  membership bitmap, selects the base sample among its candidates, computes the
-//                  statistics and the budget of Algorithm 2, selects the final sample, and writes every
-//                  index list in ascending token order.  When a candidate list cannot serve (budget above
-//                  the bound it was built for, or an overfull slice) the sample is drawn by an exact
-//                  in-kernel sweep instead.
+//   stage1_kernel  one workgroup per chunk of a head's score row: the chunk is kept in registers, a threshold
+//                  that keeps at least its own top-k is found by counting, and the composites under it are
+//                  written in ascending token order as candidates (any member of the global top-k is in its
+//                  chunk's top-k), plus the chunk maximum.
+//   head_kernel    one workgroup per head: selects the exact top-k among the chunk candidates, draws the base
+//                  sample, computes the statistics and the budget of Algorithm 2, draws the final sample, and
+//                  writes the index lists.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -31,7 +27,6 @@ namespace {
 
 constexpr uint32_t kInv32 = 0xffffffffu;
 constexpr uint64_t kInvalid = ~0ull;
-constexpr uint32_t kOverflow = 0xffffffffu;  // slice count that marks an overfull sampler candidate slice
 
 // ---------------------------------------------------------------------------
 // Workgroup-wide exclusive scan of one uint32 per thread (DPP inside a wave, LDS across waves).
@@ -66,19 +61,18 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 // absent).  Requires 1 <= c <= number of valid composites.
 //
 // Search on the value of the high word by counting: the range [lo, hi] that holds the c-th composite
-// starts as the minimum and maximum present; each step counts the composites in [lo, pivot] (a compare
-// per element, a DPP wave sum, one LDS add per wave, one barrier) and keeps the half that holds the
-// target.  Pivots alternate between interpolation (fast when the values are spread evenly, as sampler
-// keys are) and the midpoint (which bounds the number of steps whatever the data).  When at most SMALL
-// composites remain they are ranked directly by one wave.  Equal high words are resolved the same way on
-// the low word.
+// starts as the minimum and maximum present; each step splits it into up to eight equal bins, counts the
+// composites of every bin (byte counters in registers, DPP wave sums, eight LDS adds per wave, one barrier)
+// and keeps the bin that holds the target, so the span shrinks by four or more per step whatever the data.
+// When at most SMALL composites remain they are ranked directly by one wave.  Equal high words are resolved
+// the same way on the low word.
 // ---------------------------------------------------------------------------
-constexpr int kSelectSteps = 160;
+constexpr int kSelectSteps = 48;  // at most 16 steps per 32-bit word (a step divides the span by four or more)
 
 template <int NT>
 struct SelectSmem {
   static constexpr int SMALL = 64;
-  uint32_t cnt[kSelectSteps];
+  uint32_t cnt[kSelectSteps * 8];
   uint32_t wave_a[NT / kWave], wave_b[NT / kWave], wave_c[NT / kWave];
   uint64_t slist[SMALL];
   uint32_t slist_n;
@@ -112,7 +106,7 @@ struct BlockSelect {
       sm.wave_b[wave] = mx;
       sm.wave_c[wave] = nv;
     }
-    for (int i = tid; i < kSelectSteps; i += NT) sm.cnt[i] = 0;
+    for (int i = tid; i < kSelectSteps * 8; i += NT) sm.cnt[i] = 0;
     if (tid < SMALL) sm.slist[tid] = kInvalid;
     if (tid == 0) sm.slist_n = 0;
     __syncthreads();
@@ -146,8 +140,15 @@ struct BlockSelect {
         uint32_t in_range = 0;
 #pragma unroll
         for (int e = 0; e < E; ++e) in_range |= ((w[e] - lo <= hi - lo) ? 1u : 0u) << e;
+        // list positions: a scan inside the wave, one LDS add per wave
+        const uint32_t mine = (uint32_t)__popc(in_range);
+        const uint32_t incl = wave_inclusive_scan_u32(mine);
+        const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        uint32_t base = 0;
+        if (lane == 0 && wave_tot) base = atomicAdd(&sm.slist_n, wave_tot);
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
         if (in_range) {
-          uint32_t pos = atomicAdd(&sm.slist_n, (uint32_t)__popc(in_range));
+          uint32_t pos = base + incl - mine;
 #pragma unroll
           for (int e = 0; e < E; ++e) {
             if ((in_range >> e) & 1u) {
@@ -180,38 +181,45 @@ struct BlockSelect {
         lo = 0u;
         hi = 0xfffffffeu;
       }
-      const uint32_t span = hi - lo;
-      // Pivot: two interpolation steps that aim a little above and a little below the wanted rank (so that
-      // the range closes in from both sides when the values are spread evenly), then a midpoint step (which
-      // bounds the number of steps for any data).
-      uint32_t off;
-      const int kind = step % 3;
-      if (kind == 2) {
-        off = span >> 1;
-      } else {
-        const float mf = (float)(m + 1u);
-        const float want = (float)r + 0.5f * (float)(cap - c);  // middle of the acceptable window
-        const float dev = 2.0f * sqrtf(fmaxf(want * (1.0f - want * __builtin_amdgcn_rcpf(mf)), 0.0f)) + 1.0f;
-        const float aim = kind == 0 ? want + dev : want - dev;
-        const float f = fminf(fmaxf(aim * __builtin_amdgcn_rcpf(mf), 0.0f), 1.0f);
-        off = (uint32_t)fminf((float)span * f, 4294967040.0f);
-      }
-      off = min(off, span - 1u);
-      // wave-level count straight from the compare masks
-      uint32_t wave_cnt = 0;
+      const uint32_t span = hi - lo;  // >= 1 here
+      // Equal bins of width 2^s over [lo, hi], five to eight of them (span + 1 when the span is below 4): every
+      // element adds one to a byte counter of its bin, the byte counters are widened and summed over the wave,
+      // and lanes 0..7 add the wave's counts to the step's eight LDS counters.
+      const int s = max(0, 29 - (int)__clz(span));
+      uint64_t acc = 0;
 #pragma unroll
-      for (int e = 0; e < E; ++e) wave_cnt += (uint32_t)__popcll(__ballot(w[e] - lo <= off));
-      if (lane == 0 && wave_cnt) atomicAdd(&sm.cnt[step], wave_cnt);
-      __syncthreads();
-      const uint32_t tot = sm.cnt[step];
-      if (tot >= r) {
-        hi = lo + off;
-        m = tot;
-      } else {
-        lo = lo + off + 1u;
-        r -= tot;
-        m -= tot;
+      for (int e = 0; e < E; ++e) {
+        const uint32_t d = w[e] - lo;
+        const uint32_t sh = ((d >> s) & 7u) << 3;
+        acc += (d <= span) ? (1ull << sh) : 0ull;
       }
+      const uint32_t a0 = (uint32_t)acc, a1 = (uint32_t)(acc >> 32);
+      const uint32_t f0 = wave_sum_u32(a0 & 0x00ff00ffu), f1 = wave_sum_u32((a0 >> 8) & 0x00ff00ffu);
+      const uint32_t f2 = wave_sum_u32(a1 & 0x00ff00ffu), f3 = wave_sum_u32((a1 >> 8) & 0x00ff00ffu);
+      {
+        const uint32_t fa = (lane & 4) ? ((lane & 1) ? f3 : f2) : ((lane & 1) ? f1 : f0);
+        const uint32_t mine = (lane & 2) ? (fa >> 16) : (fa & 0xffffu);
+        if (lane < 8 && mine) atomicAdd(&sm.cnt[step * 8 + lane], mine);
+      }
+      __syncthreads();
+      uint32_t cum = 0, below = 0, inbin = 0, j = 0;
+      bool found = false;
+#pragma unroll
+      for (int bq = 0; bq < 8; ++bq) {
+        const uint32_t t = sm.cnt[step * 8 + bq];
+        if (!found && cum + t >= r) {
+          found = true;
+          j = (uint32_t)bq;
+          below = cum;
+          inbin = t;
+        }
+        cum += t;
+      }
+      const uint32_t lo_new = lo + (j << s);
+      hi = min(hi, lo_new + ((1u << s) - 1u));
+      lo = lo_new;
+      r -= below;
+      m = inbin;
     }
     VATT_STAMP(dbg, 12);
     VATT_NOTE(dbg, 13, 1000);
@@ -221,51 +229,70 @@ struct BlockSelect {
 };
 
 // ---------------------------------------------------------------------------
-// Sampler bounds.  Keys are uniform on [0, 2^32): the c-th smallest of n_s keys sits near c / n_s * 2^32.
-// upper_bound_key(c, n_s) is a key value below which at least c residual keys lie except with negligible
-// probability (about six standard deviations); every use is verified by counting.
+// Positions of the taken elements of a workgroup in (element-major, thread-minor) order: element e of thread
+// t comes before element e' of thread t' when e < e', or e == e' and t < t'.  With the interleaved slot
+// layout p = e * NT + t this is ascending slot order.  pos[e] is valid where bit e of take is set.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t key_bound(double count, double ns) {
-  if (count >= ns) return 4294967296ull;
-  if (count <= 0.0) return 0ull;
-  return (uint64_t)ceil(count / ns * 4294967296.0);
-}
-__device__ __forceinline__ uint64_t upper_bound_key(uint32_t c, int n_s) {
-  const double ns = (double)n_s, cc = (double)c;
-  const double sd = sqrt(cc * (1.0 - fmin(cc / ns, 1.0))) + 1.0;
-  return key_bound(cc + 6.0 * sd + 8.0, ns);
-}
-__device__ __forceinline__ uint64_t lower_bound_key(uint32_t c, int n_s) {
-  const double ns = (double)n_s, cc = (double)c;
-  const double sd = sqrt(cc * (1.0 - fmin(cc / ns, 1.0))) + 1.0;
-  const double lo = cc - 6.0 * sd - 8.0;
-  return lo <= 0.0 ? 0ull : (uint64_t)floor(lo / ns * 4294967296.0);
-}
-// Size of the final sample that the stream-1 candidate list is built to serve.
-__device__ __forceinline__ uint32_t stream1_design_count(const HeadSizes& hs) {
-  return (uint32_t)min((int64_t)hs.n_s, 2 * (int64_t)hs.b0 + 64);
+template <int NT, int E>
+struct OrderedSmem {
+  uint32_t cnt[E * (NT / kWave)];
+  uint32_t total;
+};
+
+template <int NT, int E>
+__device__ __forceinline__ void ordered_positions(uint32_t take, uint32_t (&pos)[E], uint32_t* total,
+                                                  OrderedSmem<NT, E>& sm) {
+  static_assert(E <= kWave, "one lane per element publishes the wave count");
+  constexpr int SW = NT / kWave;
+  constexpr int CNT = E * SW;
+  constexpr int PER = (CNT + kWave - 1) / kWave;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t mine = 0;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const uint64_t mask = __ballot((take >> e) & 1u);
+    pos[e] = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+    const uint32_t c = (uint32_t)__popcll(mask);
+    mine = (lane == e) ? c : mine;
+  }
+  __syncthreads();  // a previous use may still be read
+  if (lane < E) sm.cnt[lane * SW + wave] = mine;
+  __syncthreads();
+  if (wave == 0) {
+    uint32_t v[PER], s = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int q = lane * PER + i;
+      v[i] = q < CNT ? sm.cnt[q] : 0u;
+      s += v[i];
+    }
+    const uint32_t incl = wave_inclusive_scan_u32(s);
+    uint32_t run = incl - s;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int q = lane * PER + i;
+      if (q < CNT) sm.cnt[q] = run;
+      run += v[i];
+    }
+    if (lane == kWave - 1) sm.total = incl;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < E; ++e) pos[e] += sm.cnt[e * SW + wave];
+  *total = sm.total;
 }
 
-// One Philox block = keys of tokens 4j .. 4j+3.
-__device__ __forceinline__ Philox4 token_block_keys(uint32_t j, uint32_t stream, uint32_t head, uint64_t seed) {
-  return philox4x32_10(j, stream, head, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
-}
-
 // ---------------------------------------------------------------------------
-// Stage 1.
+// Stage 1: top-k candidates of one chunk of a head's score row.
 // ---------------------------------------------------------------------------
 struct Stage1Args {
   const float* scores;
   const int32_t* seq_lens;
-  const uint64_t* seq_seeds;
   float* chunk_max;
   uint64_t* cand;      // [B*Hq][n_chunks][cand_cap]
   int32_t* cand_cnt;   // [B*Hq][n_chunks]
-  uint64_t* key_comp;  // [B*Hq][2][n_key_slices][key_slice_cap]
-  float* key_score;    // same shape
-  uint32_t* key_cnt;   // [B*Hq][2][n_key_slices]
   SelectParams sp;
-  int n_pad, n_max, Hq, chunk_len, n_chunks, cand_cap, key_slice_len, n_key_slices, key_slice_cap, key_on0, key_on1;
+  int n_pad, n_max, Hq, chunk_len, n_chunks, cand_cap;
   unsigned long long* dbg;
 };
 
@@ -273,77 +300,19 @@ template <int NT, int E>
 __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
   constexpr int SW = NT / kWave;
   __shared__ SelectSmem<NT> sel_sm;
-  __shared__ BlockScanSmem<NT> scan_sm;
+  __shared__ OrderedSmem<NT, E> ord_sm;
   __shared__ float s_wmax[SW];
 
-  const int role = (int)blockIdx.x >= A.n_chunks ? 1 : 0;
-  const int part = role ? (int)blockIdx.x - A.n_chunks : (int)blockIdx.x;
+  const int part = blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = min(max(A.seq_lens[b], 1), A.n_max);
   const HeadSizes hs = head_sizes(n, A.sp);
-  const int span = role ? A.key_slice_len : A.chunk_len;
-  const int lo = part * span;
-  const int hi = min(lo + span, n);
+  const int lo = part * A.chunk_len;
+  const int hi = min(lo + A.chunk_len, n);
   const float* row = A.scores + (int64_t)bh * A.n_pad;
 
-  if (role == 1) {
-    // ---- sampler candidates among tokens [lo, hi): two Philox blocks per thread and stream ----
-    uint32_t* cnt_out = A.key_cnt + ((int64_t)bh * 2) * A.n_key_slices + part;  // stream s at + s * n_key_slices
-    const int t_lo = max(lo, hs.mid_lo), t_hi = min(hi, hs.mid_hi);
-    if (lo >= n || hs.n_s <= 0 || t_lo >= t_hi || (!A.key_on0 && !A.key_on1)) {
-      if (tid < 2) cnt_out[tid * A.n_key_slices] = 0u;
-      return;
-    }
-    const uint64_t seed = A.seq_seeds[b];
-    uint64_t U[2];
-    U[0] = A.key_on0 ? upper_bound_key((uint32_t)hs.b0, hs.n_s) : 0ull;
-    U[1] = A.key_on1 ? upper_bound_key(stream1_design_count(hs), hs.n_s) : 0ull;
-    // key_slice_len = 8 * NT tokens: thread t owns Philox blocks j0 + t and j0 + NT + t
-    const int j0 = lo >> 2;
-    uint32_t keys[2][8];
-    uint32_t hit[2] = {0u, 0u};
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int j = j0 + u * NT + tid;
-        const Philox4 ph = token_block_keys((uint32_t)j, (uint32_t)s, (uint32_t)h, seed);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = (j << 2) + e;
-          keys[s][u * 4 + e] = ph.v[e];
-          hit[s] |= ((i >= t_lo && i < t_hi && (uint64_t)ph.v[e] < U[s]) ? 1u : 0u) << (u * 4 + e);
-        }
-      }
-    }
-    // positions inside the slice's two lists: both counts ride one scan (low and high half of a word)
-    uint32_t total;
-    const uint32_t excl = block_exclusive_scan<NT>((uint32_t)__popc(hit[0]) | ((uint32_t)__popc(hit[1]) << 16), &total,
-                                                   scan_sm);
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const uint32_t tot_s = s ? (total >> 16) : (total & 0xffffu);
-      uint32_t pos = s ? (excl >> 16) : (excl & 0xffffu);
-      const int64_t base = (((int64_t)bh * 2 + s) * A.n_key_slices + part) * A.key_slice_cap;
-      if (tot_s <= (uint32_t)A.key_slice_cap) {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          if ((hit[s] >> q) & 1u) {
-            const int i = ((j0 + (q >> 2) * NT + tid) << 2) + (q & 3);
-            A.key_comp[base + pos] = ((uint64_t)keys[s][q] << 32) | (uint32_t)i;
-            A.key_score[base + pos] = row[i];
-            ++pos;
-          }
-        }
-      }
-      if (tid == 0) cnt_out[s * A.n_key_slices] = tot_s <= (uint32_t)A.key_slice_cap ? tot_s : kOverflow;
-    }
-    return;
-  }
-
-  // ---- top-k candidates of the chunk [lo, hi) ----
   const int slot = bh * A.n_chunks + part;
   if (lo >= n) {
     if (tid == 0) {
@@ -392,16 +361,13 @@ __global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
   uint32_t take = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) take |= ((((uint64_t)xh[e] << 32) | xl[e]) <= T ? 1u : 0u) << e;
-  uint32_t total;
-  uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(take), &total, scan_sm);
+  // element e of thread t is token lo + e * NT + t: element-major order is ascending token order
+  uint32_t pos[E], total;
+  ordered_positions<NT, E>(take, pos, &total, ord_sm);
   uint64_t* out = A.cand + (int64_t)slot * A.cand_cap;
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    if ((take >> e) & 1u) {
-      if (pos < (uint32_t)A.cand_cap) out[pos] = ((uint64_t)xh[e] << 32) | xl[e];
-      ++pos;
-    }
-  }
+  for (int e = 0; e < E; ++e)
+    if (((take >> e) & 1u) && pos[e] < (uint32_t)A.cand_cap) out[pos[e]] = ((uint64_t)xh[e] << 32) | xl[e];
   if (tid == 0) A.cand_cnt[slot] = (int32_t)min(total, (uint32_t)A.cand_cap);
   VATT_STAMP(A.dbg, 4);
 }
@@ -416,9 +382,6 @@ struct HeadArgs {
   const float* chunk_max;
   const uint64_t* cand;
   const int32_t* cand_cnt;
-  const uint64_t* key_comp;
-  const float* key_score;
-  const uint32_t* key_cnt;
   HeadRec* head_rec;
   const double* vstat_part;  // [B*Hq][vstat_splits][2d+2] (targets N, SDPA)
   int32_t* out_idx;
@@ -429,28 +392,41 @@ struct HeadArgs {
   double z_half, z_quarter, eps, cap_frac;
   int64_t seg_topk, seg_base, seg_dyn, seg_sink, seg_win;
   int64_t idx_cap;
-  int n_pad, n_max, Hq, n_chunks, cand_cap, cand_shift, n_key_slices, key_slice_cap, key_slice_shift, key_on0, key_on1;
-  int target, phase, force_slow, vstat_splits, head_dim;
-  int k_max, b0_max, b_max, wlist_len;
+  int n_pad, n_max, Hq, n_chunks, cand_cap, cand_shift;
+  int target, phase, small_batches, vstat_splits, head_dim;
+  int k_max, b0_max, b_max;
+  uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
+};
+
+constexpr int kSmallBatchBlocks = 64;  // Philox blocks of a small batch (256 draws)
+
+// flag bits of out_counts[7]
+constexpr int kFlagBaseComplement = 1, kFlagDynComplement = 2, kFlagBaseBatches = 4, kFlagDynBatches = 8,
+              kFlagDrawCap = 16;
+
+// One batch of the draw sequence as a thread sees it: the four draws of one Philox block.
+struct DrawBatch {
+  uint32_t tok[4];  // proposed tokens
+  float sc[4];      // their scores, when loaded ahead
+  uint32_t ok;      // bit e: the draw counts (inside the batch and the draw cap, word not rejected, token not
+                    // drawn in an earlier batch)
+  uint32_t first;   // bit e: ok and no earlier draw of the batch proposes the same token
+  int blocks;       // Philox blocks in the batch
+  bool have_sc;
 };
 
 // Device functions of the per-head kernel for a workgroup of NT threads.
 template <int NT>
 struct HeadOps {
   static constexpr int SW = NT / kWave;
-  static constexpr int EL = kListCap / NT;  // in-kernel sampler list composites per thread
 
   struct HeadSmem {
     SelectSmem<NT> sel;
     BlockScanSmem<NT> scan;
-    uint64_t list[kListCap];
-    uint32_t hist[256];
     double red[3][SW];
-    uint32_t slice_cnt[2][kMaxKeySlices];
     uint32_t chunk_cnt[kMaxChunks];
-    uint32_t list_n, sure_n;
-    uint32_t u_a, u_b, u_c;
+    uint32_t again;
   };
 
   // Workgroup sums of up to three doubles at once; every thread gets all of them.
@@ -479,6 +455,7 @@ struct HeadOps {
   }
 
   static __device__ __forceinline__ void mark_bit(uint32_t* bm, uint32_t i) { atomicOr(&bm[i >> 5], 1u << (i & 31)); }
+  static __device__ __forceinline__ bool test_bit(const uint32_t* bm, uint32_t i) { return (bm[i >> 5] >> (i & 31)) & 1u; }
 
   // Exclusive prefix of the set-bit counts of bm[0, words) into wpre; returns the number of set bits.
   static __device__ uint32_t word_prefix(const uint32_t* bm, int words, uint32_t* wpre, HeadSmem& sm) {
@@ -495,346 +472,275 @@ struct HeadOps {
     __syncthreads();
     return total;
   }
-  // Position of token i in the ascending list of the set bits of bm.
-  static __device__ __forceinline__ uint32_t list_pos(const uint32_t* bm, const uint32_t* wpre, uint32_t i) {
-    return wpre[i >> 5] + __popc(bm[i >> 5] & ((1u << (i & 31)) - 1u));
+
+  // Bits of word w that lie in the middle region [mid_lo, mid_hi).
+  static __device__ __forceinline__ uint32_t mid_mask(const HeadSizes& hs, int w) {
+    const int i0 = w << 5;
+    if (i0 + 31 < hs.mid_lo || i0 >= hs.mid_hi) return 0u;
+    const int a = max(hs.mid_lo - i0, 0), bnd = min(hs.mid_hi - i0, 32);
+    return (bnd >= 32 ? 0xffffffffu : ((1u << bnd) - 1u)) & ~((1u << a) - 1u);
   }
 
-  // Slow list writer (used after the in-kernel sweeps, which do not keep the scores): writes the set bits of
-  // bm as ascending tokens and, when wlist is given, exp(s_i - m) of each into wlist at the same position.
-  static __device__ void write_list_from_bitmap(const uint32_t* bm, int n, const uint32_t* wpre, int32_t* dst,
-                                                uint32_t dst_cap, const float* row, float m, float* wlist,
-                                                uint32_t wlist_len) {
-    const int words = (n + 31) >> 5;
-    for (int w = threadIdx.x; w < words; w += NT) {
-      uint32_t bits = bm[w];
-      uint32_t pos = wpre[w];
-      while (bits) {
-        const int i = (w << 5) + (__ffs(bits) - 1);
-        bits &= bits - 1u;
-        if (pos < dst_cap) dst[pos] = i;
-        if (wlist && pos < wlist_len) wlist[pos] = __expf(row[i] - m);
-        ++pos;
+  // What one sample needs to know.
+  struct Sampler {
+    uint32_t* taken;      // tokens proposed so far (bitmap, LDS)
+    uint32_t* scratch;    // all-zero bitmap between uses (LDS)
+    uint32_t* mail;       // one slot per bitmap word, all-ones between uses (LDS)
+    const uint32_t* bm_f; // top-k members (bitmap, LDS)
+    uint32_t* wpre;       // word prefixes (LDS)
+    const float* row;     // the head's scores
+    uint64_t seed;
+    uint32_t stream, head;
+    uint32_t L, thr;      // middle-region length and 2^32 mod L
+    uint32_t cap;         // draws allowed
+    float m;
+    unsigned long long* dbg;
+  };
+
+  // Generate the draws of Philox blocks [blk0, blk0 + blocks) of the stream and find, for every token that is
+  // proposed more than once in the batch, its earliest draw.
+  //
+  // Every draw that counts sets its token's bit in `taken`; a draw that finds the bit already set knows that
+  // the token is repeated and says so in `scratch`.  The draws of repeated tokens then post (draw number,
+  // bit position) with an atomic minimum into the mail slot of their bitmap word; the smallest draw number
+  // of a token wins its slot.  Two repeated tokens that share a word take turns (one more round per token).
+  static __device__ __forceinline__ void make_batch(DrawBatch& B, const Sampler& S, const HeadSizes& hs, uint32_t blk0, int blocks,
+                                    bool check_prev, bool load_scores, HeadSmem& sm) {
+    const int tid = threadIdx.x;
+    B.blocks = blocks;
+    B.ok = 0;
+    B.first = 0;
+    B.have_sc = load_scores;
+    VATT_STAMP(S.dbg, 0);
+    if (tid < blocks) {
+      const Philox4 ph = philox4x32_10(blk0 + (uint32_t)tid, S.stream, S.head, 0u, (uint32_t)S.seed,
+                                       (uint32_t)(S.seed >> 32));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t j = ((blk0 + (uint32_t)tid) << 2) + (uint32_t)e;
+        const uint64_t x = (uint64_t)ph.v[e] * (uint64_t)S.L;
+        const uint32_t t = (uint32_t)hs.mid_lo + (uint32_t)(x >> 32);
+        bool v = j < S.cap && (uint32_t)x >= S.thr;
+        if (check_prev) v = v && !test_bit(S.taken, t);
+        B.tok[e] = t;
+        B.ok |= (v ? 1u : 0u) << e;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) B.tok[e] = (uint32_t)hs.mid_lo;
+    }
+    if (load_scores) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) B.sc[e] = S.row[B.tok[e]];
+    }
+    VATT_STAMP(S.dbg, 1);
+    if (check_prev) __syncthreads();  // every test of `taken` comes before the marks of this batch
+    uint32_t lose = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if ((B.ok >> e) & 1u) {
+        const uint32_t bit = 1u << (B.tok[e] & 31);
+        const uint32_t old = atomicOr(&S.taken[B.tok[e] >> 5], bit);
+        if (old & bit) {
+          lose |= 1u << e;
+          atomicOr(&S.scratch[B.tok[e] >> 5], bit);
+        }
       }
     }
     __syncthreads();
-  }
-
-  // Sums of wlist[0, count) and of its squares, taken in a fixed order.
-  static __device__ __forceinline__ void sum_wlist(const float* wlist, uint32_t count, double* s1, double* s2) {
-    double a = 0.0, a2 = 0.0;
-    for (uint32_t t = threadIdx.x; t < count; t += NT) {
-      const double w = (double)wlist[t];
-      a += w;
-      a2 += w * w;
-    }
-    *s1 += a;
-    *s2 += a2;
-  }
-
-  // Residual tokens of the 4-token block j as a 4-bit mask.
-  static __device__ __forceinline__ uint32_t residual_nibble(const uint32_t* bm_f, const HeadSizes& hs, int j) {
-    const int i0 = j << 2;
-    uint32_t in_mid = 0;
+    VATT_STAMP(S.dbg, 2);
+    // draws whose token is proposed more than once in this batch
+    uint32_t unresolved = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) in_mid |= ((i0 + e >= hs.mid_lo && i0 + e < hs.mid_hi) ? 1u : 0u) << e;
-    const uint32_t taken = (bm_f[i0 >> 5] >> (i0 & 31)) & 15u;
-    return in_mid & ~taken;
-  }
-
-  // Select the `need` smallest composites of the LDS list sm.list[0, listed) and mark their tokens in bm_s.
-  static __device__ void mark_smallest_of_list(uint32_t* bm_s, uint32_t listed, uint32_t need, HeadSmem& sm) {
-    uint32_t xh[EL], xl[EL];
+    for (int e = 0; e < 4; ++e)
+      if (((B.ok >> e) & 1u) && test_bit(S.scratch, B.tok[e])) unresolved |= 1u << e;
+    uint32_t later = 0;
+    for (;;) {
 #pragma unroll
-    for (int e = 0; e < EL; ++e) {
-      const uint32_t p = e * NT + threadIdx.x;
-      const uint64_t t = p < listed ? sm.list[p] : kInvalid;
-      xh[e] = (uint32_t)(t >> 32);
-      xl[e] = (uint32_t)t;
-    }
-    const uint64_t T = (need >= listed) ? (kInvalid - 1ull) : BlockSelect<NT, EL>::run(xh, xl, need, need, sm.sel);
+      for (int e = 0; e < 4; ++e)
+        if ((unresolved >> e) & 1u) atomicMin(&S.mail[B.tok[e] >> 5], ((uint32_t)(tid * 4 + e) << 5) | (B.tok[e] & 31));
+      if (tid == 0) sm.again = 0;
+      __syncthreads();
+      uint32_t won = 0;
 #pragma unroll
-    for (int e = 0; e < EL; ++e)
-      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
-  }
-
-  // Fast sample: among the candidates stage 1 wrote for this head and stream (every middle token whose key
-  // is under the design bound, slice by slice, with its score).  Usable when no slice overflowed and the
-  // residual tokens among the candidates number at least c; then the c smallest residual composites are
-  // the sample.  Marks them in bm_s (all zero on entry), then writes the ascending token list to dst and,
-  // when wlist is given, exp(score - m) of each to wlist at its list position.  tc / xs hold the candidate
-  // slots of this thread (composite and score of slot e * NT + tid), read from global memory by the caller.
-  template <int EK>
-  static __device__ bool sample_from_candidates(uint32_t* bm_s, const uint32_t* bm_f, uint32_t* wpre,
-                                                const HeadSizes& hs, uint32_t c, const uint64_t (&tc)[EK],
-                                                const float (&xs)[EK], const uint32_t* slice_cnt, int n_slices,
-                                                int slice_shift, int32_t* dst, uint32_t dst_cap, float m,
-                                                float* wlist, uint32_t wlist_len, HeadSmem& sm,
-                                                unsigned long long* dbg = nullptr) {
-    const int tid = threadIdx.x;
-    const int slots = n_slices << slice_shift;
-    VATT_STAMP(dbg, 1);
-    // slot p = e * NT + tid belongs to slice p >> slice_shift
-    uint32_t xh[EK], xl[EK];
-    uint32_t valid = 0, bad = 0;
-#pragma unroll
-    for (int e = 0; e < EK; ++e) {
-      const int p = e * NT + tid;
-      const int pc = min(p, slots - 1);
-      const int sl = pc >> slice_shift, off = pc & ((1 << slice_shift) - 1);
-      const uint32_t cnt = slice_cnt[sl];
-      const uint64_t t = tc[e];
-      const uint32_t i = (uint32_t)t;
-      bad |= (p < slots && cnt == kOverflow) ? 1u : 0u;
-      const bool present = p < slots && cnt != kOverflow && (uint32_t)off < cnt;
-      const uint32_t ic = present ? min(i, (uint32_t)(hs.n - 1)) : 0u;
-      const bool res = present && (int)i >= hs.mid_lo && (int)i < hs.mid_hi && !((bm_f[ic >> 5] >> (ic & 31)) & 1u);
-      xh[e] = res ? (uint32_t)(t >> 32) : kInv32;
-      xl[e] = res ? i : kInv32;
-      valid += res ? 1u : 0u;
-    }
-    valid = wave_sum_u32(valid);
-    bad = wave_sum_u32(bad);
-    __syncthreads();
-    if (tid == 0) {
-      sm.u_a = 0;
-      sm.u_b = 0;
-    }
-    __syncthreads();
-    if ((tid & 63) == 0) {
-      if (valid) atomicAdd(&sm.u_a, valid);
-      if (bad) atomicAdd(&sm.u_b, 1u);
-    }
-    __syncthreads();
-    const uint32_t total = sm.u_a;
-    VATT_STAMP(dbg, 2);
-    if (sm.u_b != 0 || total < c) return false;
-    const uint64_t T = (total == c) ? (kInvalid - 1ull) : BlockSelect<NT, EK>::run(xh, xl, c, c, sm.sel, dbg);
-#pragma unroll
-    for (int e = 0; e < EK; ++e)
-      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) mark_bit(bm_s, xl[e]);
-    __syncthreads();
-    VATT_STAMP(dbg, 3);
-    word_prefix(bm_s, (hs.n + 31) >> 5, wpre, sm);
-    VATT_STAMP(dbg, 4);
-#pragma unroll
-    for (int e = 0; e < EK; ++e) {
-      if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) {
-        const uint32_t pos = list_pos(bm_s, wpre, xl[e]);
-        if (pos < dst_cap) dst[pos] = (int32_t)xl[e];
-        if (wlist && pos < wlist_len) wlist[pos] = __expf(xs[e] - m);
+      for (int e = 0; e < 4; ++e) {
+        if ((unresolved >> e) & 1u) {
+          const uint32_t v = S.mail[B.tok[e] >> 5];
+          if ((v & 31u) == (B.tok[e] & 31u)) {
+            if ((v >> 5) == (uint32_t)(tid * 4 + e)) won |= 1u << e; else later |= 1u << e;
+            unresolved &= ~(1u << e);
+          }
+        }
       }
+      if (unresolved) sm.again = 1;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if ((won >> e) & 1u) S.mail[B.tok[e] >> 5] = kInv32;
+      const bool again = sm.again != 0;
+      __syncthreads();
+      if (!again) break;
     }
+    B.first = B.ok & ~later;
+    VATT_STAMP(S.dbg, 3);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((lose >> e) & 1u) atomicAnd(&S.scratch[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));
     __syncthreads();
-    return true;
+    VATT_STAMP(S.dbg, 4);
   }
 
-  // General sample: mark in bm_s the c residual tokens with the smallest (key, token) of the given stream,
-  // computing the keys here.  bm_s must be all zero on entry.  Returns 1 if the slow exact descent was needed.
-  static __device__ int sample_by_sweep(uint32_t* bm_s, const uint32_t* bm_f, const HeadSizes& hs, uint32_t c,
-                                        uint32_t stream, uint32_t head, uint64_t seed, int force_slow, HeadSmem& sm) {
+  // Draw a sample of c residual tokens for the stream described by S.  `taken` must be all zero on entry
+  // unless `spec` carries the first batch (have_spec; made from block 0 with make_batch), `scratch` all zero.
+  // Writes the token list to dst (acceptance order, or ascending when the sample is a complement) and, when
+  // sum_w is given, adds exp(s_i - m) and its square over the sample to this thread's partial sums.
+  // Returns flag bits: 1 complement regime, 2 more than one batch, 4 draw cap reached.
+  static __device__ __forceinline__ int draw_sample(const Sampler& S, const HeadSizes& hs, uint32_t c, const DrawBatch& spec, bool have_spec,
+                                    int small_batches, int32_t* dst, uint32_t dst_cap, double* sum_w,
+                                    double* sum_w2, HeadSmem& sm) {
     const int tid = threadIdx.x;
-    const int j_lo = hs.mid_lo >> 2, j_hi = (hs.mid_hi + 3) >> 2;  // Philox blocks that touch the middle region
     const int words = (hs.n + 31) >> 5;
+    const uint32_t ns = (uint32_t)hs.n_s;
     if (c == 0) return 0;
-    if (c >= (uint32_t)hs.n_s) {
-      // the whole residual: no keys needed
-      for (int w = tid; w < words; w += NT) {
-        uint32_t mm = 0;
-        const int i0 = w << 5;
-        if (i0 + 31 >= hs.mid_lo && i0 < hs.mid_hi) {
-          const int a = max(hs.mid_lo - i0, 0), bnd = min(hs.mid_hi - i0, 32);
-          mm = (bnd >= 32 ? 0xffffffffu : ((1u << bnd) - 1u)) & ~((1u << a) - 1u);
-        }
-        bm_s[w] = mm & ~bm_f[w];
-      }
+    int flags = 0;
+    const bool all = c >= ns;
+    const bool invert = all || 2u * c > ns;
+    const uint32_t target = all ? 0u : (invert ? ns - c : c);
+    if (all) {
+      // the whole residual: no draws; forget a batch that was generated ahead
       __syncthreads();
-      return 0;
+      for (int w = tid; w < words; w += NT) S.taken[w] = 0;
+      __syncthreads();
     }
-
-    bool done = false;
-    if (!force_slow) {
-      // One sweep with a verified guess: tokens with a key below L are certainly in, tokens in [L, U) are
-      // listed and ranked exactly; the guess is checked by counting and otherwise discarded.
-      const uint64_t Lq = lower_bound_key(c, hs.n_s), Uq = upper_bound_key(c, hs.n_s);
-      if (tid == 0) {
-        sm.list_n = 0;
-        sm.sure_n = 0;
-      }
-      __syncthreads();
-      uint32_t my_sure = 0;
-      for (int j = j_lo + tid; j < j_hi; j += NT) {
-        const uint32_t res = residual_nibble(bm_f, hs, j);
-        if (res) {
-          const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
-          uint32_t mark = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if ((res >> e) & 1u) {
-              const uint64_t key = ph.v[e];
-              if (key < Lq) {
-                mark |= 1u << e;
-              } else if (key < Uq) {
-                const uint32_t pos = atomicAdd(&sm.list_n, 1u);
-                if (pos < (uint32_t)kListCap) sm.list[pos] = (key << 32) | (uint32_t)((j << 2) + e);
-              }
-            }
-          }
-          if (mark) {
-            atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
-            my_sure += __popc(mark);
-          }
-        }
-      }
-      if (my_sure) atomicAdd(&sm.sure_n, my_sure);
-      __syncthreads();
-      const uint32_t sure = sm.sure_n, listed = sm.list_n;
-      if (sure <= c && sure + listed >= c && listed <= (uint32_t)kListCap) {
-        if (c > sure) mark_smallest_of_list(bm_s, listed, c - sure, sm);
-        done = true;
+    uint32_t have = 0, blk = 0;
+    int batches = 0;
+    bool use_spec = have_spec;
+    double aw = 0.0, aw2 = 0.0;
+    while (have < target) {
+      if ((uint64_t)blk * 4ull >= (uint64_t)S.cap) break;
+      DrawBatch B;
+      if (use_spec) {
+        B = spec;
+        use_spec = false;
       } else {
-        for (int w = tid; w < words; w += NT) bm_s[w] = 0;  // discard the guess
+        const uint32_t remaining = target - have;
+        const int blocks = (small_batches || remaining <= 128u) ? kSmallBatchBlocks : min(NT, 256);
+        make_batch(B, S, hs, blk, blocks, blk > 0, false, sm);
       }
-      __syncthreads();
-    }
-    if (done) return 0;
-
-    // Slow exact path: radix descent over the composite with 8-bit digits, recomputing the keys in every
-    // sweep; ends with one marking sweep.  Correct for any c and any key distribution.
-    uint64_t prefix = 0, mask = 0, T = 0;
-    uint32_t r = c;
-    bool have_T = false;
-    for (int shift = 56; shift >= 0 && !have_T; shift -= 8) {
-      for (int d = tid; d < 256; d += NT) sm.hist[d] = 0;
-      __syncthreads();
-      for (int j = j_lo + tid; j < j_hi; j += NT) {
-        const uint32_t res = residual_nibble(bm_f, hs, j);
-        if (res) {
-          const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
+      ++batches;
+      VATT_STAMP(S.dbg, 10);
+      // accept in draw order: first proposals of residual tokens, until the target is reached
+      uint32_t acc = 0;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            if ((res >> e) & 1u) {
-              const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-              if ((comp & mask) == prefix) atomicAdd(&sm.hist[(uint32_t)(comp >> shift) & 255u], 1u);
-            }
-          }
-        }
-      }
-      __syncthreads();
-      if (tid == 0) {
-        uint32_t cum = 0, below = 0, active = 0, dsel = 255;
-        bool found = false;
-        for (int d = 0; d < 256; ++d) {
-          const uint32_t t = sm.hist[d];
-          if (!found && cum + t >= r) {
-            found = true;
-            dsel = d;
-            below = cum;
-            active = t;
-          }
-          cum += t;
-        }
-        sm.u_a = dsel;
-        sm.u_b = below;
-        sm.u_c = active;
-      }
-      __syncthreads();
-      const uint32_t dsel = sm.u_a, below = sm.u_b, active = sm.u_c;
-      r -= below;
-      prefix |= (uint64_t)dsel << shift;
-      mask |= 255ull << shift;
-      if (active == r) {
-        T = prefix | ((1ull << shift) - 1ull);
-        have_T = true;
-      } else if (active <= (uint32_t)kListCap) {
-        if (tid == 0) sm.list_n = 0;
-        __syncthreads();
-        for (int j = j_lo + tid; j < j_hi; j += NT) {
-          const uint32_t res = residual_nibble(bm_f, hs, j);
-          if (res) {
-            const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
+      for (int e = 0; e < 4; ++e)
+        if (((B.first >> e) & 1u) && !test_bit(S.bm_f, B.tok[e])) acc |= 1u << e;
+      uint32_t total;
+      uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(acc), &total, sm.scan);
+      const uint32_t room = target - have;
+      VATT_STAMP(S.dbg, 11);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              if ((res >> e) & 1u) {
-                const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-                if ((comp & mask) == prefix) {
-                  const uint32_t pos = atomicAdd(&sm.list_n, 1u);
-                  if (pos < (uint32_t)kListCap) sm.list[pos] = comp;
-                }
+      for (int e = 0; e < 4; ++e) {
+        if ((acc >> e) & 1u) {
+          if (pos < room) {
+            if (!invert) {
+              if (have + pos < dst_cap) dst[have + pos] = (int32_t)B.tok[e];
+              if (sum_w) {
+                const double w = (double)__expf((B.have_sc ? B.sc[e] : S.row[B.tok[e]]) - S.m);
+                aw += w;
+                aw2 += w * w;
               }
             }
+          } else if (invert) {
+            atomicAnd(&S.taken[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));  // drawn after the sample was complete
           }
+          ++pos;
         }
-        __syncthreads();
-        const uint32_t listed = min(sm.list_n, (uint32_t)kListCap);
-        uint32_t xh[EL], xl[EL];
-#pragma unroll
-        for (int e = 0; e < EL; ++e) {
-          const uint32_t p = e * NT + tid;
-          const uint64_t t = p < listed ? sm.list[p] : kInvalid;
-          xh[e] = (uint32_t)(t >> 32);
-          xl[e] = (uint32_t)t;
+      }
+      have += min(total, room);
+      blk += (uint32_t)B.blocks;
+      VATT_STAMP(S.dbg, 12);
+    }
+    if (batches > 1) flags |= 2;
+    __syncthreads();
+    if (have < target) {
+      // draw cap reached: complete with the lowest-index residual tokens not yet accepted
+      flags |= 4;
+      const uint32_t need = target - have;
+      for (int w = tid; w < words; w += NT) S.scratch[w] = mid_mask(hs, w) & ~S.bm_f[w] & ~S.taken[w];
+      __syncthreads();
+      word_prefix(S.scratch, words, S.wpre, sm);
+      for (int w = tid; w < words; w += NT) {
+        uint32_t bits = S.scratch[w];
+        uint32_t pos = S.wpre[w];
+        while (bits && pos < need) {
+          const uint32_t i = (uint32_t)(w << 5) + (uint32_t)(__ffs(bits) - 1);
+          bits &= bits - 1u;
+          if (invert) {
+            atomicOr(&S.taken[i >> 5], 1u << (i & 31));
+          } else {
+            if (have + pos < dst_cap) dst[have + pos] = (int32_t)i;
+            if (sum_w) {
+              const double wt = (double)__expf(S.row[i] - S.m);
+              aw += wt;
+              aw2 += wt * wt;
+            }
+          }
+          ++pos;
         }
-        T = BlockSelect<NT, EL>::run(xh, xl, r, r, sm.sel);
-        have_T = true;
       }
       __syncthreads();
+      for (int w = tid; w < words; w += NT) S.scratch[w] = 0;
+      __syncthreads();
     }
-    if (!have_T) T = prefix;
-    for (int j = j_lo + tid; j < j_hi; j += NT) {
-      const uint32_t res = residual_nibble(bm_f, hs, j);
-      if (res) {
-        const Philox4 ph = token_block_keys((uint32_t)j, stream, head, seed);
-        uint32_t mark = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if ((res >> e) & 1u) {
-            const uint64_t comp = ((uint64_t)ph.v[e] << 32) | (uint32_t)((j << 2) + e);
-            if (comp <= T) mark |= 1u << e;
+    if (invert) {
+      // the sample is the residual minus the accepted tokens, in ascending order
+      flags |= 1;
+      for (int w = tid; w < words; w += NT) S.scratch[w] = mid_mask(hs, w) & ~S.bm_f[w] & ~S.taken[w];
+      __syncthreads();
+      word_prefix(S.scratch, words, S.wpre, sm);
+      for (int w = tid; w < words; w += NT) {
+        uint32_t bits = S.scratch[w];
+        uint32_t pos = S.wpre[w];
+        while (bits) {
+          const int i = (w << 5) + (__ffs(bits) - 1);
+          bits &= bits - 1u;
+          if (pos < dst_cap) dst[pos] = i;
+          if (sum_w) {
+            const double wt = (double)__expf(S.row[i] - S.m);
+            aw += wt;
+            aw2 += wt * wt;
           }
+          ++pos;
         }
-        if (mark) atomicOr(&bm_s[(j << 2) >> 5], mark << ((j << 2) & 31));
       }
+      __syncthreads();
+      for (int w = tid; w < words; w += NT) S.scratch[w] = 0;
+      __syncthreads();
     }
-    __syncthreads();
-    return 1;
-  }
-
-  // Draw a sample of size c for `stream` and write its ascending token list; the return value reports the
-  // path taken (flag bits of out_counts[7]).  tc / xs: this thread's slots of the stream's candidate list.
-  template <int EK>
-  static __device__ int draw_sample(uint32_t* bm_s, const uint32_t* bm_f, uint32_t* wpre, const HeadSizes& hs,
-                                    uint32_t c, int stream, const HeadArgs& A, int h, uint64_t seed,
-                                    const uint64_t (&tc)[EK], const float (&xs)[EK], const float* row, int32_t* dst,
-                                    uint32_t dst_cap, float m, float* wlist, HeadSmem& sm) {
-    const int words = (hs.n + 31) >> 5;
-    const bool list_on = (stream == 0 ? A.key_on0 : A.key_on1) != 0;
-    bool ok = false;
-    if (!A.force_slow && list_on && c < (uint32_t)hs.n_s) {
-      unsigned long long* dbg = A.dbg ? A.dbg + 200 + 100 * stream : nullptr;
-      (void)dbg;
-      ok = sample_from_candidates<EK>(bm_s, bm_f, wpre, hs, c, tc, xs, sm.slice_cnt[stream], A.n_key_slices,
-                                      A.key_slice_shift, dst, dst_cap, m, wlist, (uint32_t)A.wlist_len, sm, dbg);
+    if (sum_w) {
+      *sum_w += aw;
+      *sum_w2 += aw2;
     }
-    if (ok) return 0;
-    __syncthreads();
-    for (int w = threadIdx.x; w < words; w += NT) bm_s[w] = 0;
-    __syncthreads();
-    const int slow = sample_by_sweep(bm_s, bm_f, hs, c, (uint32_t)stream, (uint32_t)h, seed, A.force_slow, sm);
-    word_prefix(bm_s, words, wpre, sm);
-    write_list_from_bitmap(bm_s, hs.n, wpre, dst, dst_cap, row, m, wlist, (uint32_t)A.wlist_len);
-    return (stream == 0 ? (2 | (slow << 2)) : ((c < (uint32_t)hs.n_s ? 8 : 0) | slow));
+    return flags;
   }
 };  // struct HeadOps
 
-// NT = workgroup size; EM = top-k candidate slots a thread holds (n_chunks * cand_cap <= EM * NT); EK = sampler
-// candidate slots a thread holds per stream (n_key_slices * key_slice_cap <= EK * NT when the lists are on).
-template <int NT, int EM, int EK>
+// Philox blocks of the batch that is generated ahead, before the top-k set is known.
+template <int NT>
+__device__ __forceinline__ int ahead_blocks(uint32_t L, int small_batches) {
+  (void)L;
+  return small_batches ? kSmallBatchBlocks : min(NT, 256);
+}
+
+// NT = workgroup size; EM = top-k candidate slots a thread holds (n_chunks * cand_cap <= EM * NT).
+template <int NT, int EM>
 __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   using O = HeadOps<NT>;
   using HeadSmem = typename O::HeadSmem;
+  using Sampler = typename O::Sampler;
   constexpr int SW = NT / kWave;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
+  __shared__ OrderedSmem<NT, EM> ord_sm;
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
@@ -845,17 +751,20 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 
   HeadSmem& sm = *reinterpret_cast<HeadSmem*>(dyn_smem);
   uint32_t* bm_f = reinterpret_cast<uint32_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
-  uint32_t* bm_s = bm_f + words_max;
-  uint32_t* wpre = bm_s + words_max;
-  float* wlist = reinterpret_cast<float*>(wpre + words_max);
+  uint32_t* taken0 = bm_f + words_max;
+  uint32_t* taken1 = taken0 + words_max;
+  uint32_t* scratch = taken1 + words_max;
+  uint32_t* wpre = scratch + words_max;
+  uint32_t* mail = wpre + words_max;
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
   const uint64_t seed = A.seq_seeds[b];
 
   VATT_STAMP(A.dbg, 0);
-  // Everything this kernel needs from global memory is requested up front, so that the latencies overlap:
-  // the head's top-k candidate slots and its sampler candidate slots (composite and score) of both streams.
+  // Everything the kernel needs from global memory up to the base sample is requested first, so that the
+  // latencies overlap each other and the sampler work below: the head's top-k candidate slots, the chunk
+  // counts and the chunk maxima.
   uint64_t tcand[EM];
   {
     const uint64_t* src = A.cand + (int64_t)bh * A.n_chunks * A.cand_cap;
@@ -863,42 +772,63 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 #pragma unroll
     for (int e = 0; e < EM; ++e) tcand[e] = (A.phase != 2) ? src[min(e * NT + tid, slots - 1)] : kInvalid;
   }
-  uint64_t kc0[EK], kc1[EK];
-  float ks0[EK], ks1[EK];
-  {
-    const int kslots = A.n_key_slices << A.key_slice_shift;
-    const int64_t base = (int64_t)bh * 2 * kslots;
-#pragma unroll
-    for (int e = 0; e < EK; ++e) {
-      const int pc = min(e * NT + tid, kslots - 1);
-      const bool in = e * NT + tid < kslots;
-      kc0[e] = (A.key_on0 && A.phase != 2 && in) ? A.key_comp[base + pc] : kInvalid;
-      ks0[e] = (A.key_on0 && A.phase != 2 && in) ? A.key_score[base + pc] : 0.f;
-      kc1[e] = (A.key_on1 && A.phase != 1 && in) ? A.key_comp[base + kslots + pc] : kInvalid;
-      ks1[e] = (A.key_on1 && A.phase != 1 && in) ? A.key_score[base + kslots + pc] : 0.f;
-    }
-  }
+  static_assert(kMaxChunks <= 256, "one thread per chunk reads the chunk tables");
+  const uint32_t my_cnt = tid < A.n_chunks ? (uint32_t)A.cand_cnt[bh * A.n_chunks + tid] : 0u;
+  float m = tid < A.n_chunks ? A.chunk_max[bh * A.n_chunks + tid] : -INFINITY;
   for (int w = tid; w < words; w += NT) {
     bm_f[w] = 0;
-    bm_s[w] = 0;
+    taken0[w] = 0;
+    taken1[w] = 0;
+    scratch[w] = 0;
+    mail[w] = kInv32;
   }
-  for (int c = tid; c < A.n_chunks; c += NT) sm.chunk_cnt[c] = (uint32_t)A.cand_cnt[bh * A.n_chunks + c];
-  for (int t = tid; t < 2 * A.n_key_slices; t += NT)
-    sm.slice_cnt[t / A.n_key_slices][t % A.n_key_slices] = A.key_cnt[(int64_t)bh * 2 * A.n_key_slices + t];
-  // head maximum from the chunk maxima
-  float m = -INFINITY;
-  for (int c = tid; c < A.n_chunks; c += NT) m = fmaxf(m, A.chunk_max[bh * A.n_chunks + c]);
-  m = wave_max(m);
   __syncthreads();
+
+  // The draw sequences do not depend on the scores: the first batch of each stream is generated, and the
+  // scores of the base-sample proposals are requested, before the top-k set is known.
+  const uint32_t L = (uint32_t)max(hs.mid_hi - hs.mid_lo, 1);
+  Sampler S0, S1;
+  S0.taken = taken0;
+  S0.scratch = scratch;
+  S0.mail = mail;
+  S0.bm_f = bm_f;
+  S0.wpre = wpre;
+  S0.row = row;
+  S0.seed = seed;
+  S0.stream = 0u;
+  S0.head = (uint32_t)h;
+  S0.L = L;
+  S0.thr = (uint32_t)((0x100000000ull - (uint64_t)L) % (uint64_t)L);
+  {
+    const uint64_t dflt = 64ull * (uint64_t)L + 4096ull;
+    S0.cap = (uint32_t)min(A.draw_cap ? (uint64_t)A.draw_cap : dflt, 0x80000000ull);
+  }
+  S0.m = 0.f;
+  S0.dbg = A.dbg ? A.dbg + 200 : nullptr;
+  S1 = S0;
+  S1.taken = taken1;
+  S1.stream = 1u;
+  S1.dbg = A.dbg ? A.dbg + 300 : nullptr;
+  DrawBatch spec0 = {}, spec1 = {};
+  const bool want0 = hs.n_s > 0 && A.phase != 2 && hs.b0 < hs.n_s;
+  const bool want1 = hs.n_s > 0 && A.phase != 1;
+  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(L, A.small_batches), false, true, sm);
+  if (want1) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(L, A.small_batches), false, false, sm);
+
+  // chunk counts, and the head maximum from the chunk maxima
+  if (tid < A.n_chunks) sm.chunk_cnt[tid] = my_cnt;
+  m = wave_max(m);
   if ((tid & 63) == 0) sm.red[0][tid >> 6] = (double)m;
   __syncthreads();
   m = (float)sm.red[0][0];
 #pragma unroll
   for (int w = 1; w < SW; ++w) m = fmaxf(m, (float)sm.red[0][w]);
   __syncthreads();
+  S0.m = m;
+  S1.m = m;
 
   VATT_STAMP(A.dbg, 1);
-  double acc_f = 0.0, unused = 0.0;  // acc_f: this thread's share of D_f = sum over I_f of exp(s_i - m)
+  double acc_f = 0.0;  // this thread's share of D_f = sum over I_f of exp(s_i - m)
   // ---- I_t (Algorithm 1, line 3) ----
   if (A.phase != 2) {
     if (hs.k > 0) {
@@ -922,23 +852,23 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
                              : BlockSelect<NT, EM>::run(xh, xl, (uint32_t)hs.k, (uint32_t)hs.k, sm.sel,
                                                         A.dbg ? A.dbg + 100 : nullptr);
       VATT_STAMP(A.dbg, 3);
-#pragma unroll
-      for (int e = 0; e < EM; ++e)
-        if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) O::mark_bit(bm_f, xl[e]);
-      __syncthreads();
-      O::word_prefix(bm_f, words, wpre, sm);
-      // every chosen candidate knows its place in the ascending list and carries its score in its high word
+      // candidates are stored chunk by chunk in ascending token order: ascending slot order is ascending
+      // token order, and a chosen candidate carries its score in its high word
+      uint32_t take = 0;
 #pragma unroll
       for (int e = 0; e < EM; ++e) {
-        if ((((uint64_t)xh[e] << 32) | xl[e]) <= T) {
-          const uint32_t pos = O::list_pos(bm_f, wpre, xl[e]);
-          if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)xl[e];
-          if (pos < (uint32_t)A.wlist_len) wlist[pos] = __expf(float_from_order_key(~xh[e]) - m);
+        const bool in = (((uint64_t)xh[e] << 32) | xl[e]) <= T;
+        take |= (in ? 1u : 0u) << e;
+        if (in) {
+          O::mark_bit(bm_f, min(xl[e], (uint32_t)(n - 1)));
+          acc_f += (double)__expf(float_from_order_key(~xh[e]) - m);
         }
       }
-      __syncthreads();
-      O::sum_wlist(wlist, (uint32_t)hs.k, &acc_f, &unused);
-      __syncthreads();
+      uint32_t pos[EM], taken_n;
+      ordered_positions<NT, EM>(take, pos, &taken_n, ord_sm);
+#pragma unroll
+      for (int e = 0; e < EM; ++e)
+        if (((take >> e) & 1u) && pos[e] < (uint32_t)A.k_max) idx[A.seg_topk + pos[e]] = (int32_t)xl[e];
       VATT_STAMP(A.dbg, 4);
     }
     for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
@@ -960,14 +890,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   double acc_w = 0.0, acc_w2 = 0.0;
   if (hs.n_s > 0) {
     if (A.phase != 2) {
-      flags |= O::template draw_sample<EK>(bm_s, bm_f, wpre, hs, (uint32_t)hs.b0, 0, A, h, seed, kc0, ks0, row,
-                                           idx + A.seg_base, (uint32_t)A.b0_max, m, wlist, sm);
+      const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches,
+                                   idx + A.seg_base, (uint32_t)A.b0_max, &acc_w, &acc_w2, sm);
+      flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
       VATT_STAMP(A.dbg, 5);
-      O::sum_wlist(wlist, (uint32_t)hs.b0, &acc_w, &acc_w2);
-      __syncthreads();
-      for (int w = tid; w < words; w += NT) bm_s[w] = 0;
-      __syncthreads();
-      VATT_STAMP(A.dbg, 6);
     } else {
       for (int t = tid; t < hs.b0; t += NT) {
         const double wgt = (double)__expf(row[O::list_tok(idx, A.seg_base + t, n)] - m);
@@ -996,6 +922,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // ---- statistics (Algorithm 2, get-stats): w_i = exp(s_i - m) ----
   double sums[3] = {acc_f, acc_w, acc_w2};
   O::block_sum(sums, sm);
+  VATT_STAMP(A.dbg, 6);
   const double D_f = sums[0];
   double sigma2 = 0.0, b_star = 0.0, tr_sigma = 0.0, nhat_sq = 0.0;
   int bfin = 0;
@@ -1064,8 +991,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 7);
   // ---- I_dyn (Algorithm 1, line 7) ----
   if (bfin > 0) {
-    flags |= O::template draw_sample<EK>(bm_s, bm_f, wpre, hs, (uint32_t)bfin, 1, A, h, seed, kc1, ks1, row,
-                                         idx + A.seg_dyn, (uint32_t)A.b_max, m, nullptr, sm);
+    const int f = O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches,
+                                 idx + A.seg_dyn, (uint32_t)A.b_max, nullptr, nullptr, sm);
+    flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
     VATT_STAMP(A.dbg, 8);
   }
   if (tid == 0) {
@@ -1095,18 +1023,11 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 }
 
 typedef void (*HeadKernel)(HeadArgs);
-// The instantiation for a plan: (workgroup size, top-k slots per thread, sampler slots per thread).
+// The instantiation for a plan: (workgroup size, top-k slots per thread).
 HeadKernel head_kernel_for(const Plan& pl) {
   const int64_t cands = (int64_t)pl.n_chunks * pl.cand_cap;
-  if (pl.head_threads == 256) {
-    if (cands <= 16 * 256) {
-      if (pl.key_elems <= 8) return head_kernel<256, 16, 8>;
-      return pl.key_elems <= 16 ? head_kernel<256, 16, 16> : head_kernel<256, 16, 32>;
-    }
-    if (pl.key_elems <= 8) return head_kernel<256, 32, 8>;
-    return pl.key_elems <= 16 ? head_kernel<256, 32, 16> : head_kernel<256, 32, 32>;
-  }
-  return head_kernel<1024, 32, 4>;
+  if (pl.head_threads == 256) return cands <= 16 * 256 ? head_kernel<256, 16> : head_kernel<256, 32>;
+  return head_kernel<1024, 32>;
 }
 
 }  // namespace
@@ -1116,26 +1037,21 @@ hipError_t set_kernel_attributes(const Plan& pl) {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
 }
 
-size_t head_kernel_lds_bytes(int n_max, int head_threads, int wlist_len) {
+size_t head_kernel_lds_bytes(int n_max, int head_threads) {
   const size_t words_max = (size_t)(n_max + 31) >> 5;
   const size_t fixed = head_threads == 256 ? sizeof(HeadOps<256>::HeadSmem) : sizeof(HeadOps<1024>::HeadSmem);
-  return ((fixed + 15) & ~size_t(15)) + 3 * words_max * sizeof(uint32_t) + (size_t)wlist_len * sizeof(float);
+  return ((fixed + 15) & ~size_t(15)) + 6 * words_max * sizeof(uint32_t);
 }
 
-hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
-                         hipStream_t st) {
+hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, void* ws, hipStream_t st) {
   const vatt_params& p = pl.p;
   char* w = static_cast<char*>(ws);
   Stage1Args A;
   A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
   A.seq_lens = seq_lens;
-  A.seq_seeds = seq_seeds;
   A.chunk_max = reinterpret_cast<float*>(w + pl.off_chunk_max);
   A.cand = reinterpret_cast<uint64_t*>(w + pl.off_cand);
   A.cand_cnt = reinterpret_cast<int32_t*>(w + pl.off_cand_cnt);
-  A.key_comp = reinterpret_cast<uint64_t*>(w + pl.off_key_comp);
-  A.key_score = reinterpret_cast<float*>(w + pl.off_key_score);
-  A.key_cnt = reinterpret_cast<uint32_t*>(w + pl.off_key_cnt);
   A.sp = pl.sel;
   A.n_pad = pl.n_pad;
   A.n_max = p.n_max;
@@ -1143,13 +1059,8 @@ hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, const uint64_t
   A.chunk_len = pl.chunk_len;
   A.n_chunks = pl.n_chunks;
   A.cand_cap = pl.cand_cap;
-  A.key_slice_len = pl.key_slice_len;
-  A.n_key_slices = pl.n_key_slices;
-  A.key_slice_cap = pl.key_slice_cap;
-  A.key_on0 = pl.key_on[0];
-  A.key_on1 = pl.key_on[1];
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug);
-  dim3 grid(pl.n_chunks + pl.n_key_slices, p.n_q_heads, p.batch);
+  dim3 grid(pl.n_chunks, p.n_q_heads, p.batch);
   if (pl.stage_threads == 256)
     hipLaunchKernelGGL((stage1_kernel<256, kChunkElems>), grid, dim3(256), 0, st, A);
   else
@@ -1169,9 +1080,6 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.chunk_max = reinterpret_cast<const float*>(w + pl.off_chunk_max);
   A.cand = reinterpret_cast<const uint64_t*>(w + pl.off_cand);
   A.cand_cnt = reinterpret_cast<const int32_t*>(w + pl.off_cand_cnt);
-  A.key_comp = reinterpret_cast<const uint64_t*>(w + pl.off_key_comp);
-  A.key_score = reinterpret_cast<const float*>(w + pl.off_key_score);
-  A.key_cnt = reinterpret_cast<const uint32_t*>(w + pl.off_key_cnt);
   A.head_rec = reinterpret_cast<HeadRec*>(w + pl.off_head_rec);
   A.vstat_part = reinterpret_cast<const double*>(w + pl.off_vstat_part);
   A.out_idx = out_idx;
@@ -1195,20 +1103,15 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.n_chunks = pl.n_chunks;
   A.cand_cap = pl.cand_cap;
   A.cand_shift = pl.cand_shift;
-  A.n_key_slices = pl.n_key_slices;
-  A.key_slice_cap = pl.key_slice_cap;
-  A.key_slice_shift = pl.key_slice_shift;
-  A.key_on0 = pl.key_on[0];
-  A.key_on1 = pl.key_on[1];
   A.target = p.target;
   A.phase = phase;
-  A.force_slow = pl.force_slow_sampler;
+  A.small_batches = pl.sampler_small_batches;
+  A.draw_cap = pl.sampler_draw_cap;
   A.vstat_splits = pl.vstat_splits;
   A.head_dim = p.head_dim;
   A.k_max = pl.k_max;
   A.b0_max = pl.b0_max;
   A.b_max = pl.b_max;
-  A.wlist_len = pl.wlist_len;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, p.batch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
   return hipGetLastError();

@@ -164,47 +164,84 @@ def test_same_seed_same_bits_and_other_seed_other_sample():
     sess.close()
 
 
-def test_exact_sampler_path_gives_identical_results():
-    say("exact sampler path")
+def _same_results(wl, x, y):
+    """Two runs that may sum in a different order: identical integers, floats equal to rounding."""
+    assert np.array_equal(x["counts"][..., :7], y["counts"][..., :7])
+    for key in ("O", "lse", "b_star", "stats"):
+        assert np.allclose(x[key], y[key], rtol=2e-6, atol=1e-30), key
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            gx, gy = gpu_segments(x, b, h), gpu_segments(y, b, h)
+            for key in ("I_t", "I_bs", "I_dyn"):
+                assert np.array_equal(gx[key], gy[key]), (b, h, key)
+
+
+def test_sampler_in_small_batches_gives_identical_results():
+    say("sampler in batches of 256 draws")
     from paper_2510_05688_amd import binding as vb
     wl = workloads.small_gqa(seed=8, batch=2, n=9000, epsilon=0.02)
     sess = _session(wl)
     fast = _run(sess)
-    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_EXACT_SAMPLER_ONLY, 1)
-    slow = _run(sess)
-    # flag bit 0: the final sample went through the slow exact descent
-    assert np.all(slow["counts"][..., 7] & 1 == 1) and np.all(fast["counts"][..., 7] & 1 == 0)
-    for key in ("O", "lse", "b_star", "stats"):
-        assert np.array_equal(fast[key], slow[key]), key
-    assert np.array_equal(fast["counts"][..., :7], slow["counts"][..., :7])
-    for b in range(2):
-        for h in range(wl.n_q_heads):
-            gf, gs_ = gpu_segments(fast, b, h), gpu_segments(slow, b, h)
-            for key in ("I_t", "I_bs", "I_dyn"):
-                assert np.array_equal(gf[key], gs_[key]), (b, h, key)
-    check_all(wl, slow, label="exact-sampler")
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SAMPLER_SMALL_BATCHES, 1)
+    small = _run(sess)
+    # flag bit 3: the final sample needed more than one batch of draws
+    assert np.any(small["counts"][..., 7] & 8 == 8)
+    _same_results(wl, fast, small)
+    check_all(wl, small, label="small-batches")
     sess.close()
 
 
-def test_sampler_without_candidate_lists_gives_identical_results():
-    say("sampler sweep path (no candidate lists)")
-    from paper_2510_05688_amd import binding as vb
-    wl = workloads.small_gqa(seed=18, batch=2, n=7000)
+def test_samples_taken_as_complements():
+    say("complement regime (c > n_s / 2) for the final sample, then for both samples")
+    # a tiny epsilon asks for every residual token; the cap leaves 70 % of them: 30 % are drawn to be left out
+    wl = workloads.small_gqa(seed=21, batch=2, n=5000, epsilon=1e-4, budget_cap_frac=0.7)
     sess = _session(wl)
-    fast = _run(sess)
-    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NO_SAMPLER_CANDIDATES, 1)
-    sweep = _run(sess)
-    assert np.all(sweep["counts"][..., 7] & 2 == 2)      # base sample drawn by the in-kernel sweep
-    for key in ("O", "lse", "b_star", "stats"):
-        assert np.array_equal(fast[key], sweep[key]), key
-    assert np.array_equal(fast["counts"][..., :7], sweep["counts"][..., :7])
-    for b in range(2):
-        for h in range(wl.n_q_heads):
-            gf, gs_ = gpu_segments(fast, b, h), gpu_segments(sweep, b, h)
-            for key in ("I_t", "I_bs", "I_dyn"):
-                assert np.array_equal(gf[key], gs_[key]), (b, h, key)
-    check_all(wl, sweep, label="sweep-sampler")
+    res = _run(sess)
+    capped = res["counts"][..., 7] & 2 == 2          # the flat heads; spiky heads need few samples even so
+    assert capped.sum() >= wl.batch * wl.n_q_heads // 2
+    assert np.all(res["counts"][..., 4][capped] ==
+                  np.ceil(np.float64(np.float32(0.7)) * res["counts"][..., 5][capped].astype(np.float64)))
+    check_all(wl, res, label="complement-final")
     sess.close()
+    wl = workloads.small_gqa(seed=22, batch=1, n=6000, base_frac=0.8)
+    sess = _session(wl)
+    res = _run(sess)
+    assert np.all(res["counts"][..., 7] & 3 == 3)
+    check_all(wl, res, label="complement-both")
+    sess.close()
+
+
+def test_repeated_proposals_inside_a_batch():
+    say("short middle region: many repeated tokens inside one batch of draws")
+    # 1024 draws over about 4100 tokens repeat about 250 tokens: at the edge of what one large batch resolves,
+    # so some heads redo the batch in small ones (flag bit 5); either way the samples must match
+    wl = workloads.small_gqa(seed=23, batch=3, n=4200, seq_lens=[4200, 4150, 4137], base_frac=0.2, epsilon=0.01)
+    sess = _session(wl)
+    res = _run(sess)
+    say("  heads that redid a batch: %d of %d" % (int((res["counts"][..., 7] & 32 != 0).sum()), wl.batch * wl.n_q_heads))
+    check_all(wl, res, label="repeats")
+    sess.close()
+
+
+def test_draw_cap_completes_samples_in_index_order():
+    say("draw cap")
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=24, batch=2, n=3000)
+    sess = _session(wl)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SAMPLER_DRAW_CAP, 40)
+    res = _run(sess)
+    assert np.all(res["counts"][..., 7] & 16 == 16)
+    params = dict(wl.params, draw_cap=40)
+    check_all(wl, res, params=params, label="draw-cap")
+    # and in the complement regime
+    wl2 = workloads.small_gqa(seed=25, batch=1, n=2500, base_frac=0.9)
+    sess2 = _session(wl2)
+    vb.vatt_plan_set_option(sess2.plan, vb.VATT_OPT_SAMPLER_DRAW_CAP, 100)
+    res2 = _run(sess2)
+    assert np.all(res2["counts"][..., 7] & 16 == 16)
+    check_all(wl2, res2, params=dict(wl2.params, draw_cap=100), label="draw-cap-complement")
+    sess.close()
+    sess2.close()
 
 
 # ---------------------------------------------------- dense, and check (a) ----

@@ -70,7 +70,7 @@ def test_plan_geometry_config2():
         assert ws >= 32 * 32768 * 4 and ws % 256 == 0
         assert vb.vatt_plan_workspace_offset(plan, vb.VATT_WS_SCORES) % 256 == 0
         assert vb.vatt_plan_workspace_offset(plan, 77) == 2 ** 64 - 1
-        vb.vatt_plan_set_option(plan, vb.VATT_OPT_EXACT_SAMPLER_ONLY, 1)
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_SAMPLER_SMALL_BATCHES, 1)
         with pytest.raises(vb.VattError):
             vb.vatt_plan_set_option(plan, 99, 1)
     finally:
