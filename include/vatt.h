@@ -126,8 +126,11 @@ void vatt_plan_destroy(vatt_plan* plan);
  * the draw sequence in batches of 256 draws only (it normally uses up to 1024); results are identical.
  * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that
  * the completion rule can be exercised.
+ * VATT_OPT_TOPK_GENERAL_PATH = 1 makes the top-k selection skip its usual shortcut (a lower bound of the
+ * threshold from the largest scores of every 16 keys) and take the general path, a histogram over the whole
+ * score row, which otherwise only serves short or unusual rows; results are identical.
  */
-enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2 };
+enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
 
 /* Bytes of device workspace every launching call needs (256-byte aligned base). */
@@ -163,7 +166,7 @@ int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment);
  *   out_counts   device, int32 [B, Hq, 8] = { |I_s|, |I_l|, |I_t|, |I_bs|, b, n_s, n, flags }
  *                flags (informational): bit 0 base sample taken as a complement, bit 1 final sample taken as a
  *                complement, bit 2 base sample needed more than one batch of draws, bit 3 final sample did,
- *                bit 4 the draw limit was reached, bit 5 a batch was redone in small batches
+ *                bit 4 the draw limit was reached, bit 5 the top-k selection took its general path
  *   out_budget_raw device, double [B, Hq] or NULL: b* before rounding and clamping
  *   out_stats    device, float [B, Hq, 4] or NULL = { D_hat, sigma^2, Tr Sigma, ||N_hat||^2 }, all in the
  *                scale where the largest score of the head has weight 1 (w_i = exp(s_i - max s))

@@ -26,6 +26,7 @@ VATT_WS_SCORES = 0
 VATT_WS_DEBUG = 1
 VATT_OPT_SAMPLER_SMALL_BATCHES = 1
 VATT_OPT_SAMPLER_DRAW_CAP = 2
+VATT_OPT_TOPK_GENERAL_PATH = 3
 
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",

@@ -9,6 +9,7 @@
 namespace vatt {
 
 size_t head_kernel_lds_bytes(int n_max, int head_threads);
+size_t head_kernel_static_lds_bytes();
 
 namespace {
 
@@ -86,10 +87,12 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.sel.topk_frac = (double)p.topk_frac;
   pl.sel.base_frac = (double)p.base_frac;
   pl.sampler_small_batches = 0;
+  pl.topk_general_path = 0;
   pl.sampler_draw_cap = 0;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
+  pl.n_sub = (int)align_up((size_t)n_max, kScoreTile) / kSubTile;
   int k_max = p.topk_abs > 0 ? p.topk_abs : (int)std::floor((double)p.topk_frac * (double)n_max);
   pl.k_max = std::min(std::max(k_max, 0), n_max);
   int b0_max = p.base_abs > 0 ? p.base_abs : (int)std::floor((double)p.base_frac * (double)n_max);
@@ -97,32 +100,21 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
 
-  // top-k chunking: a chunk is what one stage-1 workgroup keeps in registers (kChunkElems per thread).
-  // Small workgroups have the lowest per-pass overhead; when a head would then have more candidates than
-  // a small per-head workgroup can merge, chunks (and, if still needed, the merge) use 1024 threads.
-  pl.stage_threads = 256;
-  pl.head_threads = 256;
-  auto set_chunks = [&]() {
-    pl.chunk_len = pl.stage_threads * kChunkElems;
-    pl.n_chunks = (n_max + pl.chunk_len - 1) / pl.chunk_len;
-    // a chunk may hand over its top-k plus the rest of the last bucket: leave a quarter of headroom
-    // and round up to a power of two so that a slot's chunk is a shift away
-    int want = std::max(1, std::min(pl.k_max + std::max(64, pl.k_max / 4), pl.chunk_len));
-    pl.cand_shift = 0;
-    while ((1 << pl.cand_shift) < want) ++pl.cand_shift;
-    pl.cand_cap = 1 << pl.cand_shift;
-  };
-  set_chunks();
-  if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads) {
-    pl.stage_threads = 1024;
-    set_chunks();
-    if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads) {
-      pl.head_threads = 1024;
-      if ((int64_t)pl.n_chunks * pl.cand_cap > (int64_t)kMergeElemsMax * pl.head_threads)
-        return VATT_E_UNSUPPORTED_SHAPE;
-    }
+  // the per-head kernel keeps rows of up to 32768 scores in registers (256 threads x 32 or 128 scores) and
+  // streams longer rows with 1024 threads
+  if (n_max <= 32 * 256) {
+    pl.head_threads = 256;
+    pl.head_resident = 32;
+  } else if (n_max <= 128 * 256) {
+#ifndef VATT_HEAD_NT
+#define VATT_HEAD_NT 512
+#endif
+    pl.head_threads = VATT_HEAD_NT;
+    pl.head_resident = 32768 / VATT_HEAD_NT;
+  } else {
+    pl.head_threads = 1024;
+    pl.head_resident = 0;
   }
-  if (pl.n_chunks > kMaxChunks) return VATT_E_UNSUPPORTED_SHAPE;
 
   const int heads = p.batch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
@@ -139,7 +131,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   pl.seg_off[4] = pl.seg_off[3] + pl.b0_max;
   pl.idx_cap = align_up((size_t)(pl.seg_off[4] + pl.b_max), 4);
   pl.head_lds_bytes = head_kernel_lds_bytes(n_max, pl.head_threads);
-  if (pl.head_lds_bytes > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
+  if (pl.head_lds_bytes + head_kernel_static_lds_bytes() > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
 
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -147,10 +139,10 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
     off = align_up(off + bytes, 256);
     return o;
   };
-  pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float));
-  pl.off_chunk_max = take((size_t)heads * pl.n_chunks * sizeof(float));
-  pl.off_cand = take((size_t)heads * pl.n_chunks * pl.cand_cap * sizeof(uint64_t));
-  pl.off_cand_cnt = take((size_t)heads * pl.n_chunks * sizeof(int32_t));
+  // (the per-head kernel reads whole register tiles of a row, up to 32768 floats from the row's start,
+  // whatever the row length: the region is padded so that the last row's tile stays inside the workspace)
+  pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float) + (size_t)32768 * sizeof(float));
+  pl.off_sub_max = take((size_t)heads * pl.n_sub * sizeof(float));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
@@ -253,6 +245,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     plan->pl.sampler_small_batches = value ? 1 : 0;
     return VATT_OK;
   }
+  if (option == VATT_OPT_TOPK_GENERAL_PATH) {
+    plan->pl.topk_general_path = value ? 1 : 0;
+    return VATT_OK;
+  }
   if (option == VATT_OPT_SAMPLER_DRAW_CAP) {
     if (value < 0) return VATT_E_INVALID_ARG;
     plan->pl.sampler_draw_cap = (uint32_t)value;
@@ -281,7 +277,6 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
-  VATT_LAUNCH(launch_stage1(pl, seq_lens, workspace, st));
   if (pl.p.target == VATT_TARGET_D) {
     VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   } else {

@@ -94,6 +94,15 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// Maximum over each row of 16 lanes, left in every lane of the row.
+__device__ __forceinline__ float row_max16(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  v = fmaxf(v, dpp_f32<0x140>(v));
+  return v;
+}
+
 // Wave-wide sum of a 32-bit integer, returned as a wave-uniform value: four DPP adds leave each row of
 // 16 lanes with its row sum, four lane reads add the rows.  Every lane of the wave must be active.
 template <int CTRL>

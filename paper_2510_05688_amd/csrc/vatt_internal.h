@@ -12,9 +12,7 @@ namespace vatt {
 
 constexpr int kScoreTile = 64;        // keys per score-kernel workgroup (small tiles: many short workgroups fill and
                                       // drain the chip more evenly than few long ones; measured 64 > 128 > 256 > 32)
-constexpr int kChunkElems = 32;       // score-row elements a thread holds while a chunk's top-k is selected
-constexpr int kMergeElemsMax = 32;    // top-k candidates a thread holds while a head merges them
-constexpr int kMaxChunks = 64;         // chunks of a head's score row (LDS table of the per-head kernel)
+constexpr int kSubTile = 16;           // keys per sub-tile maximum
 constexpr int kGatherThreads = 256;
 constexpr int kDenseThreads = 256;
 
@@ -37,18 +35,19 @@ struct Plan {
   SelectParams sel;
   // sizes
   int n_pad;          // score row stride (floats)
+  int n_sub;          // sub-tiles of kSubTile keys per row (the score kernel leaves each one's largest score)
   int k_max, b0_max, b_max;
-  int stage_threads, chunk_len, n_chunks, cand_cap;  // top-k chunking (stage 1 workgroup size, chunk length)
-  int head_threads;                                   // workgroup size of the per-head kernel
-  int cand_shift;                                     // log2(cand_cap)
+  int head_threads;   // workgroup size of the per-head kernel
+  int head_resident;  // scores per thread that the per-head kernel keeps in registers (0: it streams the row)
   int gather_splits, dense_splits, vstat_splits;
   size_t idx_cap;
   int64_t seg_off[5];
   size_t head_lds_bytes;
+  int topk_general_path;          // test hook: the top-k selection always takes its general path
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
   // workspace offsets (bytes)
-  size_t off_scores, off_chunk_max, off_cand, off_cand_cnt, off_head_rec, off_gather_part,
+  size_t off_scores, off_sub_max, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };
@@ -56,7 +55,6 @@ struct Plan {
 // Every launcher returns a hipError_t from hipGetLastError() after the launch.
 hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                         const int32_t* seq_lens, void* ws, hipStream_t st);
-hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, void* ws, hipStream_t st);
 // phase 0: everything (target D); phase 1: through the base sample; phase 2: budget and final sample.
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,

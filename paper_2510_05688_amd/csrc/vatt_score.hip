@@ -24,8 +24,8 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
 template <int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
-                                                    float* __restrict__ scores, int n_pad, int n_max, int Hq,
-                                                    float sm_scale) {
+                                                    float* __restrict__ scores, float* __restrict__ sub_max,
+                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
   constexpr int ROWS_PER_WAVE = kScoreTile / 4;
@@ -92,6 +92,16 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       for (int g = 0; g < G; ++g) scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][t];
     }
   }
+  // Largest score of every 16 consecutive keys per query head: the selection kernel takes its head maximum
+  // and a lower bound of the top-k threshold from these.
+  static_assert(kScoreTile == kWave && kSubTile == 16, "one lane per key of the tile, one DPP row per sub-tile");
+  for (int g = wave; g < G; g += 4) {
+    const float v = row_max16(tile_lo + lane < n ? s_tile[g][lane] : -INFINITY);
+    if ((lane & 15) == 0) {
+      const int64_t slot = ((int64_t)b * Hq + (int64_t)kvh * G + g) * n_sub + (tile_lo + lane) / kSubTile;
+      sub_max[slot] = v;
+    }
+  }
 }
 
 template <int D, int G>
@@ -102,14 +112,15 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   KVLayout L = pl.kv_k;
   L.block_table = block_table;
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_scores);
+  float* smax = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_sub_max);
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     hipLaunchKernelGGL((score_kernel<D, G, true>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
-                       pl.sm_scale);
+                       static_cast<const uint16_t*>(k), L, seq_lens, scores, smax, pl.n_sub, pl.n_pad,
+                       p.n_max, p.n_q_heads, pl.sm_scale);
   } else {
     hipLaunchKernelGGL((score_kernel<D, G, false>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(k), L, seq_lens, scores, pl.n_pad, p.n_max, p.n_q_heads,
-                       pl.sm_scale);
+                       static_cast<const uint16_t*>(k), L, seq_lens, scores, smax, pl.n_sub, pl.n_pad,
+                       p.n_max, p.n_q_heads, pl.sm_scale);
   }
   return hipGetLastError();
 }

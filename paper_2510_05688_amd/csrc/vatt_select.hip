@@ -1,8 +1,12 @@
-// Index selection and budget: lines 1-8 of Algorithm 1 and all of Algorithm 2, per (sequence, query head).
+// Index selection and budget: lines 1-8 of Algorithm 1 and all of Algorithm 2, per (sequence, query head),
+// in one kernel with one workgroup per head.
 //
-// Top-k: every token of the middle region carries the 64-bit composite (~order_key(score) << 32) | token,
-// distinct per token, so "the k largest scores, ties to the lower token" is "the k smallest composites": a pure
-// set operation whose result does not depend on the order in which lanes, waves or workgroups contribute.
+// Top-k: the k largest scores of the middle region, ties to the lower token, i.e. the k smallest composites
+// (~order_key(score), token).  The head's score row stays in registers (or is streamed from the L2 cache when it
+// is too long); a histogram over 2048 equal-width score bins in LDS finds the bin that holds the k-th largest
+// score, the few scores of that bin are ranked exactly, and every token at or above the resulting threshold
+// is marked in an LDS bitmap.  Rows with very many scores in one bin are refined by further histograms over
+// the integer keys, and runs of equal scores by token order, so the result is exact for any data.
 //
 // Samples: sequential uniform draws from the middle region (Philox4x32-10 words, unbiased multiply-and-reject
 // mapping), skipping top-k members and tokens drawn before; the first c accepted tokens are the sample (for
@@ -11,22 +15,12 @@
 // draw order finds where the sample is complete; the result equals the sequential procedure bit for bit.
 //
 // Floating-point sums are taken in a fixed order, so the statistics and the budget are reproducible too.
-//
-// Two kernels:
-//   stage1_kernel  one workgroup per chunk of a head's score row: the chunk is kept in registers, a threshold
-//                  that keeps at least its own top-k is found by counting, and the composites under it are
-//                  written in ascending token order as candidates (any member of the global top-k is in its
-//                  chunk's top-k), plus the chunk maximum.
-//   head_kernel    one workgroup per head: selects the exact top-k among the chunk candidates, draws the base
-//                  sample, computes the statistics and the budget of Algorithm 2, draws the final sample, and
-//                  writes the index lists.
 #include "vatt_internal.h"
 
 namespace vatt {
 namespace {
 
 constexpr uint32_t kInv32 = 0xffffffffu;
-constexpr uint64_t kInvalid = ~0ull;
 
 // ---------------------------------------------------------------------------
 // Workgroup-wide exclusive scan of one uint32 per thread (DPP inside a wave, LDS across waves).
@@ -56,332 +50,13 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 }
 
 // ---------------------------------------------------------------------------
-// Workgroup select: a threshold T such that the number of valid composites <= T lies in [c, cap]
-// (exactly c when cap == c).  Composites sit in registers (hi word, lo word; E per thread; all-ones =
-// absent).  Requires 1 <= c <= number of valid composites.
-//
-// Search on the value of the high word by counting: the range [lo, hi] that holds the c-th composite
-// starts as the minimum and maximum present; each step splits it into up to eight equal bins, counts the
-// composites of every bin (byte counters in registers, DPP wave sums, eight LDS adds per wave, one barrier)
-// and keeps the bin that holds the target, so the span shrinks by four or more per step whatever the data.
-// When at most SMALL composites remain they are ranked directly by one wave.  Equal high words are resolved
-// the same way on the low word.
-// ---------------------------------------------------------------------------
-constexpr int kSelectSteps = 48;  // at most 16 steps per 32-bit word (a step divides the span by four or more)
-
-template <int NT>
-struct SelectSmem {
-  static constexpr int SMALL = 64;
-  uint32_t cnt[kSelectSteps * 8];
-  uint32_t wave_a[NT / kWave], wave_b[NT / kWave], wave_c[NT / kWave];
-  uint64_t slist[SMALL];
-  uint32_t slist_n;
-  uint64_t result;
-};
-
-template <int NT, int E>
-struct BlockSelect {
-  static constexpr int SW = NT / kWave;
-  static constexpr int SMALL = SelectSmem<NT>::SMALL;
-
-  __device__ static uint64_t run(const uint32_t (&xh)[E], const uint32_t (&xl)[E], uint32_t c, uint32_t cap,
-                                 SelectSmem<NT>& sm, unsigned long long* dbg = nullptr) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    VATT_STAMP(dbg, 10);
-    // range of the high words present, and how many composites there are
-    uint32_t mn = kInv32, mx = 0u, nv = 0u;
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-      const bool valid = (xh[e] & xl[e]) != kInv32;
-      mn = valid ? min(mn, xh[e]) : mn;
-      mx = valid ? max(mx, xh[e]) : mx;
-      nv += valid ? 1u : 0u;
-    }
-    mn = wave_min_u32(mn);
-    mx = wave_max_u32(mx);
-    nv = wave_sum_u32(nv);
-    __syncthreads();  // the caller may still be reading a previous result out of this scratch
-    if (lane == 0) {
-      sm.wave_a[wave] = mn;
-      sm.wave_b[wave] = mx;
-      sm.wave_c[wave] = nv;
-    }
-    for (int i = tid; i < kSelectSteps * 8; i += NT) sm.cnt[i] = 0;
-    if (tid < SMALL) sm.slist[tid] = kInvalid;
-    if (tid == 0) sm.slist_n = 0;
-    __syncthreads();
-    uint32_t lo = kInv32, hi = 0u, m = 0u;
-#pragma unroll
-    for (int w = 0; w < SW; ++w) {
-      lo = min(lo, sm.wave_a[w]);
-      hi = max(hi, sm.wave_b[w]);
-      m += sm.wave_c[w];
-    }
-    VATT_STAMP(dbg, 11);
-    uint32_t r = c;    // rank wanted inside [lo, hi]; c - r composites lie below the range, m inside it
-    bool low = false;  // false: searching on the high word; true: high word fixed to hv, on the low word
-    uint32_t hv = 0u;
-    // the word being searched, all-ones for slots that are empty or out of play: one unsigned compare of
-    // (w - lo) against (pivot - lo) then tells whether a slot lies in [lo, pivot]
-    uint32_t w[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) w[e] = ((xh[e] & xl[e]) != kInv32) ? min(xh[e], 0xfffffffeu) : kInv32;
-    // (a high word of all-ones is searched as 0xfffffffe; the two values are told apart again when the last
-    // few composites are ranked, so only more than SMALL composites with those two high words could be
-    // misordered, which for 32-bit hashes of distinct tokens does not happen)
-    hi = min(hi, 0xfffffffeu);
-    lo = min(lo, hi);
-    for (int step = 0; step < kSelectSteps; ++step) {
-      if ((c - r) + m <= cap) {  // everything up to hi may be taken
-        VATT_NOTE(dbg, 15, step);
-        break;
-      }
-      if (m <= (uint32_t)SMALL) {
-        uint32_t in_range = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) in_range |= ((w[e] - lo <= hi - lo) ? 1u : 0u) << e;
-        // list positions: a scan inside the wave, one LDS add per wave
-        const uint32_t mine = (uint32_t)__popc(in_range);
-        const uint32_t incl = wave_inclusive_scan_u32(mine);
-        const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-        uint32_t base = 0;
-        if (lane == 0 && wave_tot) base = atomicAdd(&sm.slist_n, wave_tot);
-        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-        if (in_range) {
-          uint32_t pos = base + incl - mine;
-#pragma unroll
-          for (int e = 0; e < E; ++e) {
-            if ((in_range >> e) & 1u) {
-              if (pos < (uint32_t)SMALL) sm.slist[pos] = ((uint64_t)xh[e] << 32) | xl[e];
-              ++pos;
-            }
-          }
-        }
-        __syncthreads();
-        if (tid < SMALL) {
-          // rank inside the range = number of listed composites below mine (the list is padded with all-ones)
-          const uint64_t mine = sm.slist[tid];
-          uint32_t below = 0;
-#pragma unroll
-          for (int j = 0; j < SMALL; ++j) below += (sm.slist[j] < mine) ? 1u : 0u;
-          if ((uint32_t)tid < m && below == r - 1u) sm.result = mine;
-        }
-        __syncthreads();
-        VATT_STAMP(dbg, 12);
-        VATT_NOTE(dbg, 13, step);
-        VATT_NOTE(dbg, 14, m);
-        return sm.result;
-      }
-      if (lo == hi) {
-        // more than SMALL composites share this high word: go on with their low words
-        low = true;
-        hv = lo;
-#pragma unroll
-        for (int e = 0; e < E; ++e) w[e] = (w[e] == hv) ? xl[e] : kInv32;
-        lo = 0u;
-        hi = 0xfffffffeu;
-      }
-      const uint32_t span = hi - lo;  // >= 1 here
-      // Equal bins of width 2^s over [lo, hi], five to eight of them (span + 1 when the span is below 4): every
-      // element adds one to a byte counter of its bin, the byte counters are widened and summed over the wave,
-      // and lanes 0..7 add the wave's counts to the step's eight LDS counters.
-      const int s = max(0, 29 - (int)__clz(span));
-      uint64_t acc = 0;
-#pragma unroll
-      for (int e = 0; e < E; ++e) {
-        const uint32_t d = w[e] - lo;
-        const uint32_t sh = ((d >> s) & 7u) << 3;
-        acc += (d <= span) ? (1ull << sh) : 0ull;
-      }
-      const uint32_t a0 = (uint32_t)acc, a1 = (uint32_t)(acc >> 32);
-      const uint32_t f0 = wave_sum_u32(a0 & 0x00ff00ffu), f1 = wave_sum_u32((a0 >> 8) & 0x00ff00ffu);
-      const uint32_t f2 = wave_sum_u32(a1 & 0x00ff00ffu), f3 = wave_sum_u32((a1 >> 8) & 0x00ff00ffu);
-      {
-        const uint32_t fa = (lane & 4) ? ((lane & 1) ? f3 : f2) : ((lane & 1) ? f1 : f0);
-        const uint32_t mine = (lane & 2) ? (fa >> 16) : (fa & 0xffffu);
-        if (lane < 8 && mine) atomicAdd(&sm.cnt[step * 8 + lane], mine);
-      }
-      __syncthreads();
-      uint32_t cum = 0, below = 0, inbin = 0, j = 0;
-      bool found = false;
-#pragma unroll
-      for (int bq = 0; bq < 8; ++bq) {
-        const uint32_t t = sm.cnt[step * 8 + bq];
-        if (!found && cum + t >= r) {
-          found = true;
-          j = (uint32_t)bq;
-          below = cum;
-          inbin = t;
-        }
-        cum += t;
-      }
-      const uint32_t lo_new = lo + (j << s);
-      hi = min(hi, lo_new + ((1u << s) - 1u));
-      lo = lo_new;
-      r -= below;
-      m = inbin;
-    }
-    VATT_STAMP(dbg, 12);
-    VATT_NOTE(dbg, 13, 1000);
-    if (!low && hi == 0xfffffffeu) return kInvalid - 1ull;
-    return low ? (((uint64_t)hv << 32) | hi) : (((uint64_t)hi << 32) | kInv32);
-  }
-};
-
-// ---------------------------------------------------------------------------
-// Positions of the taken elements of a workgroup in (element-major, thread-minor) order: element e of thread
-// t comes before element e' of thread t' when e < e', or e == e' and t < t'.  With the interleaved slot
-// layout p = e * NT + t this is ascending slot order.  pos[e] is valid where bit e of take is set.
-// ---------------------------------------------------------------------------
-template <int NT, int E>
-struct OrderedSmem {
-  uint32_t cnt[E * (NT / kWave)];
-  uint32_t total;
-};
-
-template <int NT, int E>
-__device__ __forceinline__ void ordered_positions(uint32_t take, uint32_t (&pos)[E], uint32_t* total,
-                                                  OrderedSmem<NT, E>& sm) {
-  static_assert(E <= kWave, "one lane per element publishes the wave count");
-  constexpr int SW = NT / kWave;
-  constexpr int CNT = E * SW;
-  constexpr int PER = (CNT + kWave - 1) / kWave;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t mine = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const uint64_t mask = __ballot((take >> e) & 1u);
-    pos[e] = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-    const uint32_t c = (uint32_t)__popcll(mask);
-    mine = (lane == e) ? c : mine;
-  }
-  __syncthreads();  // a previous use may still be read
-  if (lane < E) sm.cnt[lane * SW + wave] = mine;
-  __syncthreads();
-  if (wave == 0) {
-    uint32_t v[PER], s = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int q = lane * PER + i;
-      v[i] = q < CNT ? sm.cnt[q] : 0u;
-      s += v[i];
-    }
-    const uint32_t incl = wave_inclusive_scan_u32(s);
-    uint32_t run = incl - s;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int q = lane * PER + i;
-      if (q < CNT) sm.cnt[q] = run;
-      run += v[i];
-    }
-    if (lane == kWave - 1) sm.total = incl;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int e = 0; e < E; ++e) pos[e] += sm.cnt[e * SW + wave];
-  *total = sm.total;
-}
-
-// ---------------------------------------------------------------------------
-// Stage 1: top-k candidates of one chunk of a head's score row.
-// ---------------------------------------------------------------------------
-struct Stage1Args {
-  const float* scores;
-  const int32_t* seq_lens;
-  float* chunk_max;
-  uint64_t* cand;      // [B*Hq][n_chunks][cand_cap]
-  int32_t* cand_cnt;   // [B*Hq][n_chunks]
-  SelectParams sp;
-  int n_pad, n_max, Hq, chunk_len, n_chunks, cand_cap;
-  unsigned long long* dbg;
-};
-
-template <int NT, int E>
-__global__ __launch_bounds__(NT) void stage1_kernel(Stage1Args A) {
-  constexpr int SW = NT / kWave;
-  __shared__ SelectSmem<NT> sel_sm;
-  __shared__ OrderedSmem<NT, E> ord_sm;
-  __shared__ float s_wmax[SW];
-
-  const int part = blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int bh = b * A.Hq + h;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = min(max(A.seq_lens[b], 1), A.n_max);
-  const HeadSizes hs = head_sizes(n, A.sp);
-  const int lo = part * A.chunk_len;
-  const int hi = min(lo + A.chunk_len, n);
-  const float* row = A.scores + (int64_t)bh * A.n_pad;
-
-  const int slot = bh * A.n_chunks + part;
-  if (lo >= n) {
-    if (tid == 0) {
-      A.cand_cnt[slot] = 0;
-      A.chunk_max[slot] = -INFINITY;
-    }
-    return;
-  }
-  VATT_STAMP(A.dbg, 0);
-  float sc[E];
-#pragma unroll
-  for (int e = 0; e < E; ++e) sc[e] = row[min(lo + e * NT + tid, n - 1)];
-  uint32_t xh[E], xl[E];
-  float mx = -INFINITY;
-#pragma unroll
-  for (int e = 0; e < E; ++e) {
-    const int i = lo + e * NT + tid;
-    const bool in_chunk = i < hi;
-    const bool in_mid = in_chunk && i >= hs.mid_lo && i < hs.mid_hi;
-    mx = in_chunk ? fmaxf(mx, sc[e]) : mx;
-    xh[e] = in_mid ? ~float_order_key(sc[e]) : kInv32;
-    xl[e] = in_mid ? (uint32_t)i : kInv32;
-  }
-  VATT_STAMP(A.dbg, 1);
-  mx = wave_max(mx);
-  if (lane == 0) s_wmax[wave] = mx;
-  __syncthreads();
-  if (tid == 0) {
-    float t = s_wmax[0];
-    for (int w = 1; w < SW; ++w) t = fmaxf(t, s_wmax[w]);
-    A.chunk_max[slot] = t;
-  }
-  const int vlo = max(lo, hs.mid_lo), vhi = min(hi, hs.mid_hi);
-  const int nvalid = max(vhi - vlo, 0);
-  const int c = min(min(hs.k, nvalid), A.cand_cap);
-  if (c == 0) {
-    if (tid == 0) A.cand_cnt[slot] = 0;
-    return;
-  }
-  VATT_STAMP(A.dbg, 2);
-  // a superset of the chunk's top-k is as good as the exact set here: stop as soon as it fits the slot
-  const uint64_t T = (c == nvalid) ? (kInvalid - 1ull)
-                                   : BlockSelect<NT, E>::run(xh, xl, (uint32_t)c, (uint32_t)min(nvalid, A.cand_cap),
-                                                             sel_sm, A.dbg);
-  VATT_STAMP(A.dbg, 3);
-  uint32_t take = 0;
-#pragma unroll
-  for (int e = 0; e < E; ++e) take |= ((((uint64_t)xh[e] << 32) | xl[e]) <= T ? 1u : 0u) << e;
-  // element e of thread t is token lo + e * NT + t: element-major order is ascending token order
-  uint32_t pos[E], total;
-  ordered_positions<NT, E>(take, pos, &total, ord_sm);
-  uint64_t* out = A.cand + (int64_t)slot * A.cand_cap;
-#pragma unroll
-  for (int e = 0; e < E; ++e)
-    if (((take >> e) & 1u) && pos[e] < (uint32_t)A.cand_cap) out[pos[e]] = ((uint64_t)xh[e] << 32) | xl[e];
-  if (tid == 0) A.cand_cnt[slot] = (int32_t)min(total, (uint32_t)A.cand_cap);
-  VATT_STAMP(A.dbg, 4);
-}
-
-// ---------------------------------------------------------------------------
 // Per-head kernel.
 // ---------------------------------------------------------------------------
 struct HeadArgs {
   const float* scores;
+  const float* sub_max;  // [B*Hq][n_sub]: largest score of every kSubTile keys
   const int32_t* seq_lens;
   const uint64_t* seq_seeds;
-  const float* chunk_max;
-  const uint64_t* cand;
-  const int32_t* cand_cnt;
   HeadRec* head_rec;
   const double* vstat_part;  // [B*Hq][vstat_splits][2d+2] (targets N, SDPA)
   int32_t* out_idx;
@@ -392,8 +67,8 @@ struct HeadArgs {
   double z_half, z_quarter, eps, cap_frac;
   int64_t seg_topk, seg_base, seg_dyn, seg_sink, seg_win;
   int64_t idx_cap;
-  int n_pad, n_max, Hq, n_chunks, cand_cap, cand_shift;
-  int target, phase, small_batches, vstat_splits, head_dim;
+  int n_pad, n_max, Hq, n_sub;
+  int target, phase, small_batches, topk_general, vstat_splits, head_dim;
   int k_max, b0_max, b_max;
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
@@ -403,7 +78,7 @@ constexpr int kSmallBatchBlocks = 64;  // Philox blocks of a small batch (256 dr
 
 // flag bits of out_counts[7]
 constexpr int kFlagBaseComplement = 1, kFlagDynComplement = 2, kFlagBaseBatches = 4, kFlagDynBatches = 8,
-              kFlagDrawCap = 16;
+              kFlagDrawCap = 16, kFlagTopkGeneral = 32;
 
 // One batch of the draw sequence as a thread sees it: the four draws of one Philox block.
 struct DrawBatch {
@@ -422,10 +97,8 @@ struct HeadOps {
   static constexpr int SW = NT / kWave;
 
   struct HeadSmem {
-    SelectSmem<NT> sel;
     BlockScanSmem<NT> scan;
     double red[3][SW];
-    uint32_t chunk_cnt[kMaxChunks];
     uint32_t again;
   };
 
@@ -725,32 +398,347 @@ struct HeadOps {
   }
 };  // struct HeadOps
 
+// ---------------------------------------------------------------------------
+// The head's score row as the threads of the workgroup see it: thread t owns tokens t, t + NT, t + 2 NT, ...
+// EE > 0: the first EE * NT scores are loaded once and stay in registers.  EE == 0: every pass streams the
+// row again from global memory (it stays in the L2 cache), kTile scores per thread at a time.
+//
+// A pass visits the row in groups of kGroup scores per thread (kGroup * NT consecutive tokens per workgroup).
+// Groups beyond the sequence are skipped; a group that lies entirely in the middle region is handed over with
+// the tag std::true_type, so that the pass spends no instructions on the region test there.  The bodies are
+// free of per-score branches: the compiler interleaves the work of neighbouring scores only then.
+// ---------------------------------------------------------------------------
+struct InsideTag { static constexpr bool value = true; };
+struct EdgeTag { static constexpr bool value = false; };
+
+template <int NT, int EE>
+struct RowView {
+  static constexpr bool kResident = EE > 0;
+  static constexpr int kTile = 16;
+  static constexpr int kGroup = 8;
+  static_assert(!kResident || EE % kGroup == 0, "whole groups");
+  float sc[kResident ? EE : 1];
+  const float* row;
+  int n;
+
+  __device__ __forceinline__ void load(const float* r, int n_valid) {
+    row = r;
+    n = n_valid;
+    if constexpr (kResident) {
+#pragma unroll
+      for (int e = 0; e < EE; ++e) sc[e] = row[e * NT + (int)threadIdx.x];  // the workspace is padded for this
+    }
+  }
+
+  template <class G>
+  __device__ __forceinline__ void dispatch(const HeadSizes& hs, const float (&s)[kGroup], int g_lo, int t0, G&& g) {
+    if (g_lo >= hs.mid_lo && g_lo + kGroup * NT <= hs.mid_hi) g(s, g_lo + t0, InsideTag{});
+    else g(s, g_lo + t0, EdgeTag{});
+  }
+
+  // g(scores[kGroup], token of scores[0], tag): slot u of the group is token i0 + u * NT; under EdgeTag a slot
+  // may lie outside the middle region or at or beyond n (it then carries an arbitrary value).
+  template <class G>
+  __device__ __forceinline__ void for_each_group(const HeadSizes& hs, G&& g) {
+    if constexpr (kResident) {
+      // (the empty asm makes the compiler treat the registers and the thread index as new values in every
+      // pass: otherwise it keeps per-score intermediates of one pass alive for the next and runs out of
+      // registers)
+#pragma unroll
+      for (int e = 0; e < EE; ++e) asm volatile("" : "+v"(sc[e]));
+      int t0 = (int)threadIdx.x;
+      asm volatile("" : "+v"(t0));
+#pragma unroll
+      for (int e = 0; e < EE; e += kGroup) {
+        if (e * NT < n) {
+          float s[kGroup];
+#pragma unroll
+          for (int u = 0; u < kGroup; ++u) s[u] = sc[e + u];
+          dispatch(hs, s, e * NT, t0, g);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keeps the live intermediates to one group
+      }
+    } else {
+      for (int base = 0; base < n; base += NT * kTile) {
+        float v[kTile];
+#pragma unroll
+        for (int u = 0; u < kTile; ++u) v[u] = row[min(base + u * NT + (int)threadIdx.x, n - 1)];
+#pragma unroll
+        for (int q = 0; q < kTile; q += kGroup) {
+          if (base + q * NT < n) {
+            float s[kGroup];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) s[u] = v[q + u];
+            dispatch(hs, s, base + q * NT, (int)threadIdx.x, g);
+          }
+        }
+      }
+    }
+  }
+  // act(score, token) for the middle-region scores that pred(score) selects, when those are few: the test
+  // runs branch-free over a group, and only a group with a hit anywhere in the wave walks its slots.
+  template <class P, class A>
+  __device__ __forceinline__ void for_each_rare(const HeadSizes& hs, P&& pred, A&& act) {
+    for_each_group(hs, [&](const float (&s)[kGroup], int i0, auto tag) {
+      uint32_t hit = 0;
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int i = i0 + u * NT;
+        const bool mid = decltype(tag)::value || (i >= hs.mid_lo && i < hs.mid_hi);
+        hit |= ((mid && pred(s[u])) ? 1u : 0u) << u;
+      }
+      if (__ballot(hit != 0u)) {
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u)
+          if ((hit >> u) & 1u) act(s[u], i0 + u * NT);
+      }
+    });
+  }
+  // f(score, token, in the middle region) for every slot of the groups visited.
+  template <class F>
+  __device__ __forceinline__ void for_each(const HeadSizes& hs, F&& f) {
+    for_each_group(hs, [&](const float (&s)[kGroup], int i0, auto tag) {
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const int i = i0 + u * NT;
+        f(s[u], i, decltype(tag)::value || (i >= hs.mid_lo && i < hs.mid_hi));
+      }
+    });
+  }
+};
+
+// The candidates for the top-k set as a list of composites in LDS: the same interface as RowView.
+constexpr int kCandCap = 4096;
+template <int NT>
+struct CandView {
+  const uint64_t* list;
+  uint32_t count;
+  template <class F>
+  __device__ __forceinline__ void for_each(const HeadSizes&, F&& f) {
+    for (uint32_t t = threadIdx.x; t < count; t += NT) {
+      const uint64_t c = list[t];
+      f(float_from_order_key(~(uint32_t)(c >> 32)), (int)(uint32_t)c, true);
+    }
+  }
+  template <class P, class A>
+  __device__ __forceinline__ void for_each_rare(const HeadSizes&, P&& pred, A&& act) {
+    for (uint32_t t = threadIdx.x; t < count; t += NT) {
+      const uint64_t c = list[t];
+      const float sc = float_from_order_key(~(uint32_t)(c >> 32));
+      if (pred(sc)) act(sc, (int)(uint32_t)c);
+    }
+  }
+};
+
+constexpr int kBins = 2048;   // histogram bins of one pass
+constexpr int kSmall = 256;   // scores of one bin that are ranked directly
+
+struct TopkSmem {
+  uint32_t hist[kBins + 1];  // the last bin takes what is out of play
+  uint64_t slist[kSmall];
+  uint32_t slist_n;
+  uint32_t j, below, inbin;
+  uint64_t result;
+  float wf[2][16];
+  uint32_t wu[2][16];
+  uint64_t wq[16];
+  uint32_t cand_n;
+};
+
+template <int NT, class View>
+struct TopkOps {
+  static constexpr int SW = NT / kWave;
+  using Row = View;
+  using HeadSmem = typename HeadOps<NT>::HeadSmem;
+
+  // The bin that holds rank r (1-based) of the histogram: ts.j, with ts.below scores in the bins before it
+  // and ts.inbin in it.
+  static __device__ void locate(uint32_t r, TopkSmem& ts, HeadSmem& sm) {
+    constexpr int BPT = kBins / NT;
+    const int tid = threadIdx.x;
+    uint32_t v[BPT], sum = 0;
+#pragma unroll
+    for (int q = 0; q < BPT; ++q) {
+      v[q] = ts.hist[tid * BPT + q];
+      sum += v[q];
+    }
+    uint32_t total;
+    uint32_t excl = block_exclusive_scan<NT>(sum, &total, sm.scan);
+    if (excl < r && r <= excl + sum) {
+      uint32_t cum = excl;
+      bool found = false;
+#pragma unroll
+      for (int q = 0; q < BPT; ++q) {
+        if (!found && cum + v[q] >= r) {
+          found = true;
+          ts.j = (uint32_t)(tid * BPT + q);
+          ts.below = cum;
+          ts.inbin = v[q];
+        }
+        cum += v[q];
+      }
+    }
+    __syncthreads();
+  }
+
+  static __device__ void zero_hist(TopkSmem& ts) {
+    __syncthreads();  // earlier readers of the histogram are done
+    for (int q = threadIdx.x; q <= kBins; q += NT) ts.hist[q] = 0;
+    if (threadIdx.x == 0) ts.slist_n = 0;
+    __syncthreads();
+  }
+
+  // Rank r (1-based) among the composites of the middle region that pred selects (at most kSmall): ts.result.
+  template <class P>
+  static __device__ __forceinline__ void rank_small(Row& rv, const HeadSizes& hs, uint32_t r, P&& pred, TopkSmem& ts) {
+    const int tid = threadIdx.x;
+    rv.for_each_rare(hs, pred, [&](float sc, int i) {
+      const uint32_t pos = atomicAdd(&ts.slist_n, 1u);
+      if (pos < (uint32_t)kSmall) ts.slist[pos] = ((uint64_t)(~float_order_key(sc)) << 32) | (uint32_t)i;
+    });
+    __syncthreads();
+    const uint32_t cnt = min(ts.slist_n, (uint32_t)kSmall);
+    if ((uint32_t)tid < cnt) {
+      const uint64_t mine = ts.slist[tid];
+      uint32_t below = 0;
+      for (uint32_t q = 0; q < cnt; ++q) below += (ts.slist[q] < mine) ? 1u : 0u;
+      if (below == r - 1u) ts.result = mine;
+    }
+    __syncthreads();
+  }
+
+  // Threshold composite of the k smallest composites among the `count` middle-region scores of the view,
+  // 0 < k < count.  [smin, smax]: a range that holds every one of them.  scratch: all-zero bitmap, left all zero.
+  static __device__ __forceinline__ uint64_t threshold(Row& rv, const HeadSizes& hs, uint32_t k, uint32_t count,
+                                                       float smin, float smax, uint32_t* scratch, uint32_t* wpre,
+                                                       TopkSmem& ts, HeadSmem& sm, unsigned long long* dbg) {
+    const int tid = threadIdx.x;
+    uint32_t r = k;
+    uint32_t lo = ~float_order_key(smax), hi = ~float_order_key(smin);  // key range in play
+    uint32_t m = count;
+    // ---- first pass: bins of equal width in the score; (smax - s) * scale stays below kBins ----
+    const float scale = (float)(kBins - 1) / (smax - smin);
+    if (smax > smin && scale < 1e30f) {
+      zero_hist(ts);
+      rv.for_each(hs, [&](float s, int, bool mid) {
+        const uint32_t b = (uint32_t)((smax - s) * scale);
+        atomicAdd(&ts.hist[mid ? b : (uint32_t)kBins], 1u);
+      });
+      __syncthreads();
+      VATT_STAMP(dbg, 20);
+      locate(r, ts, sm);
+      const uint32_t j = ts.j;
+      r -= ts.below;
+      m = ts.inbin;
+      VATT_NOTE(dbg, 25, m);
+      auto in_bin = [&](float s) { return (uint32_t)((smax - s) * scale) == j; };
+      if (m <= (uint32_t)kSmall) {
+        rank_small(rv, hs, r, in_bin, ts);
+        VATT_STAMP(dbg, 21);
+        return ts.result;
+      }
+      // many scores in one bin: go on with the integer keys of that bin
+      uint32_t kmin = kInv32, kmax = 0u;
+      rv.for_each(hs, [&](float s, int, bool mid) {
+        const bool in = mid && in_bin(s);
+        const uint32_t key = ~float_order_key(s);
+        kmin = in ? min(kmin, key) : kmin;
+        kmax = in ? max(kmax, key) : kmax;
+      });
+      kmin = wave_min_u32(kmin);
+      kmax = wave_max_u32(kmax);
+      __syncthreads();
+      if ((tid & 63) == 0) {
+        ts.wu[0][tid >> 6] = kmin;
+        ts.wu[1][tid >> 6] = kmax;
+      }
+      __syncthreads();
+      lo = kInv32;
+      hi = 0u;
+#pragma unroll
+      for (int w = 0; w < SW; ++w) {
+        lo = min(lo, ts.wu[0][w]);
+        hi = max(hi, ts.wu[1][w]);
+      }
+    }
+    // ---- further passes: bins of equal width in the integer key ----
+    for (int pass = 0; pass < 4; ++pass) {
+      if (r == m) return ((uint64_t)hi << 32) | kInv32;  // everything up to hi
+      if (lo == hi) break;
+      const uint32_t span = hi - lo;
+      const int s = max(0, (32 - (int)__clz(span)) - 11);  // (span >> s) < kBins
+      zero_hist(ts);
+      rv.for_each(hs, [&](float sc, int, bool mid) {
+        const uint32_t d = ~float_order_key(sc) - lo;
+        atomicAdd(&ts.hist[(mid && d <= span) ? (d >> s) : (uint32_t)kBins], 1u);
+      });
+      __syncthreads();
+      locate(r, ts, sm);
+      const uint32_t lo_new = lo + (ts.j << s);
+      hi = min(hi, lo_new + ((1u << s) - 1u));
+      lo = lo_new;
+      r -= ts.below;
+      m = ts.inbin;
+      if (m <= (uint32_t)kSmall) {
+        const uint32_t lo_c = lo, span_c = hi - lo;
+        rank_small(rv, hs, r, [&](float sc) { return ~float_order_key(sc) - lo_c <= span_c; }, ts);
+        return ts.result;
+      }
+    }
+    if (r == m) return ((uint64_t)hi << 32) | kInv32;
+    // ---- more than kSmall equal scores around the threshold: the r lowest tokens among them ----
+    const int words = (hs.n + 31) >> 5;
+    const uint32_t key_eq = lo;
+    rv.for_each(hs, [&](float sc, int i, bool mid) {
+      const bool eq = mid && ~float_order_key(sc) == key_eq;
+      atomicOr(&scratch[min(i, hs.n - 1) >> 5], eq ? (1u << (i & 31)) : 0u);
+    });
+    __syncthreads();
+    HeadOps<NT>::word_prefix(scratch, words, wpre, sm);
+    for (int w = tid; w < words; w += NT) {
+      const uint32_t bits = scratch[w], before = wpre[w];
+      if (before < r && r <= before + (uint32_t)__popc(bits)) {
+        uint32_t b = bits;
+        for (uint32_t q = before + 1; q < r; ++q) b &= b - 1u;
+        ts.result = ((uint64_t)key_eq << 32) | (uint32_t)((w << 5) + (__ffs(b) - 1));
+      }
+    }
+    __syncthreads();
+    for (int w = tid; w < words; w += NT) scratch[w] = 0;
+    __syncthreads();
+    return ts.result;
+  }
+};
+
 // Philox blocks of the batch that is generated ahead, before the top-k set is known.
 template <int NT>
-__device__ __forceinline__ int ahead_blocks(uint32_t L, int small_batches) {
-  (void)L;
+__device__ __forceinline__ int ahead_blocks(int small_batches) {
   return small_batches ? kSmallBatchBlocks : min(NT, 256);
 }
 
-// NT = workgroup size; EM = top-k candidate slots a thread holds (n_chunks * cand_cap <= EM * NT).
-template <int NT, int EM>
+// NT = workgroup size; EE = scores a thread keeps in registers (the row has at most EE * NT scores), or 0 when
+// the row is streamed from global memory in every pass.
+template <int NT, int EE>
 __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   using O = HeadOps<NT>;
+  using TKR = TopkOps<NT, RowView<NT, EE>>;
+  using TKC = TopkOps<NT, CandView<NT>>;
   using HeadSmem = typename O::HeadSmem;
   using Sampler = typename O::Sampler;
   constexpr int SW = NT / kWave;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
-  __shared__ OrderedSmem<NT, EM> ord_sm;
+  __shared__ TopkSmem ts;
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
   const int n = min(max(A.seq_lens[b], 1), A.n_max);
   const HeadSizes hs = head_sizes(n, A.sp);
-  const int words_max = (A.n_max + 31) >> 5;
+  const int words_max = ((A.n_max + 63) >> 6) << 1;  // an even number of words: bitmaps are also written 64 bits at a time
   const int words = (n + 31) >> 5;
 
   HeadSmem& sm = *reinterpret_cast<HeadSmem*>(dyn_smem);
-  uint32_t* bm_f = reinterpret_cast<uint32_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
+  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
+  uint32_t* bm_f = reinterpret_cast<uint32_t*>(cand + kCandCap);
   uint32_t* taken0 = bm_f + words_max;
   uint32_t* taken1 = taken0 + words_max;
   uint32_t* scratch = taken1 + words_max;
@@ -762,19 +750,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   const uint64_t seed = A.seq_seeds[b];
 
   VATT_STAMP(A.dbg, 0);
-  // Everything the kernel needs from global memory up to the base sample is requested first, so that the
-  // latencies overlap each other and the sampler work below: the head's top-k candidate slots, the chunk
-  // counts and the chunk maxima.
-  uint64_t tcand[EM];
-  {
-    const uint64_t* src = A.cand + (int64_t)bh * A.n_chunks * A.cand_cap;
-    const int slots = A.n_chunks * A.cand_cap;
-#pragma unroll
-    for (int e = 0; e < EM; ++e) tcand[e] = (A.phase != 2) ? src[min(e * NT + tid, slots - 1)] : kInvalid;
-  }
-  static_assert(kMaxChunks <= 256, "one thread per chunk reads the chunk tables");
-  const uint32_t my_cnt = tid < A.n_chunks ? (uint32_t)A.cand_cnt[bh * A.n_chunks + tid] : 0u;
-  float m = tid < A.n_chunks ? A.chunk_max[bh * A.n_chunks + tid] : -INFINITY;
+  // The score row is requested first (when it is kept in registers), so that its latency overlaps the
+  // sampler work below.
+  RowView<NT, EE> rv;
+  rv.load(row, n);
   for (int w = tid; w < words; w += NT) {
     bm_f[w] = 0;
     taken0[w] = 0;
@@ -812,64 +791,230 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   DrawBatch spec0 = {}, spec1 = {};
   const bool want0 = hs.n_s > 0 && A.phase != 2 && hs.b0 < hs.n_s;
   const bool want1 = hs.n_s > 0 && A.phase != 1;
-  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(L, A.small_batches), false, true, sm);
-  if (want1) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(L, A.small_batches), false, false, sm);
+  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm);
+  if (want1) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
+  VATT_STAMP(A.dbg, 1);
 
-  // chunk counts, and the head maximum from the chunk maxima
-  if (tid < A.n_chunks) sm.chunk_cnt[tid] = my_cnt;
-  m = wave_max(m);
-  if ((tid & 63) == 0) sm.red[0][tid >> 6] = (double)m;
-  __syncthreads();
-  m = (float)sm.red[0][0];
+  // ---- the head maximum m, from the sub-tile maxima the score kernel left ----
+  const int n_sub = (n + kSubTile - 1) / kSubTile;
+  const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
+  float m;
+  {
+    float v_max = -INFINITY;
+    for (int t = tid; t < n_sub; t += NT) v_max = fmaxf(v_max, sub_max[t]);
+    v_max = wave_max(v_max);
+    if ((tid & 63) == 0) ts.wf[0][tid >> 6] = v_max;
+    __syncthreads();
+    m = ts.wf[0][0];
 #pragma unroll
-  for (int w = 1; w < SW; ++w) m = fmaxf(m, (float)sm.red[0][w]);
-  __syncthreads();
+    for (int w = 1; w < SW; ++w) m = fmaxf(m, ts.wf[0][w]);
+  }
   S0.m = m;
   S1.m = m;
+  VATT_STAMP(A.dbg, 2);
 
-  VATT_STAMP(A.dbg, 1);
-  double acc_f = 0.0;  // this thread's share of D_f = sum over I_f of exp(s_i - m)
+  int topk_flag = 0;
+  float acc_f32 = 0.f;  // this thread's share of D_f = sum over I_f of exp(s_i - m), kept in fp32 per thread
+  double acc_f = 0.0;
   // ---- I_t (Algorithm 1, line 3) ----
   if (A.phase != 2) {
+    const int mid_len = hs.mid_hi - hs.mid_lo;
+    bool edge_weights_done = false;
     if (hs.k > 0) {
-      // slot p = e * NT + tid of the candidate array belongs to chunk p >> cand_shift
-      uint32_t xh[EM], xl[EM];
-      const int slots = A.n_chunks * A.cand_cap;
-      uint32_t total = 0;
-      for (int c = 0; c < A.n_chunks; ++c) total += sm.chunk_cnt[c];
+      float sT = -INFINITY;
+      uint32_t Tidx = kInv32;
+      bool marked = false;
+      if (hs.k < mid_len) {
+        // Fast path.  A lower bound of the k-th largest score: the k-th largest of the sub-tile maxima (of
+        // the sub-tiles that lie entirely in the middle region) has at least k middle scores at or above it.
+        // Found to one histogram bin, it leaves a few more than k candidates, which are listed in LDS and
+        // selected among exactly.
+        const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;
+        bool have_T = false;
+        if (sub_hi - sub_lo >= hs.k && !A.topk_general) {
+          float v_min = INFINITY;
+          for (int t = sub_lo + tid; t < sub_hi; t += NT) v_min = fminf(v_min, sub_max[t]);
+          v_min = -wave_max(-v_min);
+          __syncthreads();
+          if ((tid & 63) == 0) ts.wf[1][tid >> 6] = v_min;
+          __syncthreads();
+          float lo_sub = ts.wf[1][0];
 #pragma unroll
-      for (int e = 0; e < EM; ++e) {
-        const int p = e * NT + tid;
-        const int pc = min(p, slots - 1);
-        const int ch = pc >> A.cand_shift, off = pc & (A.cand_cap - 1);
-        const bool ok = p < slots && (uint32_t)off < sm.chunk_cnt[ch];
-        xh[e] = ok ? (uint32_t)(tcand[e] >> 32) : kInv32;
-        xl[e] = ok ? (uint32_t)tcand[e] : kInv32;
-      }
-      VATT_STAMP(A.dbg, 2);
-      const uint64_t T = ((uint32_t)hs.k >= total)
-                             ? (kInvalid - 1ull)
-                             : BlockSelect<NT, EM>::run(xh, xl, (uint32_t)hs.k, (uint32_t)hs.k, sm.sel,
-                                                        A.dbg ? A.dbg + 100 : nullptr);
-      VATT_STAMP(A.dbg, 3);
-      // candidates are stored chunk by chunk in ascending token order: ascending slot order is ascending
-      // token order, and a chosen candidate carries its score in its high word
-      uint32_t take = 0;
+          for (int w = 1; w < SW; ++w) lo_sub = fminf(lo_sub, ts.wf[1][w]);
+          float bound = lo_sub;  // every middle sub-tile maximum is at or above this
+          const float scale = (float)(kBins - 1) / (m - lo_sub);
+          if (m > lo_sub && scale < 1e30f) {
+            TKR::zero_hist(ts);
+            for (int t = sub_lo + tid; t < sub_hi; t += NT) atomicAdd(&ts.hist[(uint32_t)((m - sub_max[t]) * scale)], 1u);
+            __syncthreads();
+            TKR::locate((uint32_t)hs.k, ts, sm);
+            // the lower edge of the bin of the k-th largest maximum, a little further down for rounding
+            bound = fmaxf(lo_sub, m - ((float)ts.j + 1.02f) / scale);
+          }
+          VATT_STAMP(A.dbg, 22);
+          // candidates: middle scores at or above the bound (order in the list does not matter)
+          if (tid == 0) ts.cand_n = 0;
+          __syncthreads();
+          rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
+            constexpr int G = RowView<NT, EE>::kGroup;
+            constexpr bool kInside = decltype(tag)::value;
+            uint32_t hit = 0;
 #pragma unroll
-      for (int e = 0; e < EM; ++e) {
-        const bool in = (((uint64_t)xh[e] << 32) | xl[e]) <= T;
-        take |= (in ? 1u : 0u) << e;
-        if (in) {
-          O::mark_bit(bm_f, min(xl[e], (uint32_t)(n - 1)));
-          acc_f += (double)__expf(float_from_order_key(~xh[e]) - m);
+            for (int u = 0; u < G; ++u) {
+              const int i = i0 + u * NT;
+              const bool mid = kInside || (i >= hs.mid_lo && i < hs.mid_hi);
+              hit |= ((mid && s[u] >= bound) ? 1u : 0u) << u;
+            }
+            const uint32_t mine = (uint32_t)__popc(hit);
+            const uint32_t incl = wave_inclusive_scan_u32(mine);
+            const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            if (wave_tot) {
+              uint32_t base = 0;
+              if ((tid & 63) == 0) base = atomicAdd(&ts.cand_n, wave_tot);
+              base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+              uint32_t pos = base + incl - mine;
+#pragma unroll
+              for (int u = 0; u < G; ++u) {
+                if ((hit >> u) & 1u) {
+                  if (pos < (uint32_t)kCandCap)
+                    cand[pos] = ((uint64_t)(~float_order_key(s[u])) << 32) | (uint32_t)(i0 + u * NT);
+                  ++pos;
+                }
+              }
+            }
+            if constexpr (!kInside) {
+#pragma unroll
+              for (int u = 0; u < G; ++u) {
+                const int i = i0 + u * NT;
+                if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
+              }
+            }
+          });
+          edge_weights_done = true;
+          __syncthreads();
+          const uint32_t n_cand = ts.cand_n;
+          VATT_STAMP(A.dbg, 23);
+          VATT_NOTE(A.dbg, 26, n_cand);
+          if (n_cand <= (uint32_t)kCandCap && n_cand >= (uint32_t)hs.k) {
+            CandView<NT> cv;
+            cv.list = cand;
+            cv.count = n_cand;
+            uint64_t T = ~0ull;
+            if (n_cand > (uint32_t)hs.k)
+              T = TKC::threshold(cv, hs, (uint32_t)hs.k, n_cand, bound, m, scratch, wpre, ts, sm, A.dbg);
+            // (the list order depends on scheduling: the members' weights are summed as 40-bit fixed-point
+            // integers, whose sum does not depend on the order; every weight is at most 1)
+            uint64_t fixed_sum = 0;
+            for (uint32_t t = tid; t < n_cand; t += NT) {
+              const uint64_t c = cand[t];
+              if (c <= T) {
+                const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
+                atomicOr(&bm_f[i >> 5], 1u << (i & 31));
+                fixed_sum += (uint64_t)(__expf(float_from_order_key(~(uint32_t)(c >> 32)) - m) * 1099511627776.0f);
+              }
+            }
+            fixed_sum = wave_sum(fixed_sum);
+            __syncthreads();
+            if ((tid & 63) == 0) ts.wq[tid >> 6] = fixed_sum;
+            __syncthreads();
+            if (tid == 0) {
+              uint64_t tot = 0;
+              for (int w = 0; w < SW; ++w) tot += ts.wq[w];
+              acc_f += (double)tot * (1.0 / 1099511627776.0);
+            }
+            have_T = true;
+            marked = true;
+          }
+        }
+        if (!have_T) {
+          topk_flag = kFlagTopkGeneral;
+          // General path: histogram over the whole row.  It needs the smallest score of the middle region.
+          float v_min = INFINITY, v_max = -INFINITY;
+          rv.for_each(hs, [&](float s, int, bool mid) {
+            v_min = mid ? fminf(v_min, s) : v_min;
+            v_max = mid ? fmaxf(v_max, s) : v_max;
+          });
+          v_min = -wave_max(-v_min);
+          v_max = wave_max(v_max);
+          __syncthreads();
+          if ((tid & 63) == 0) {
+            ts.wf[0][tid >> 6] = v_max;
+            ts.wf[1][tid >> 6] = v_min;
+          }
+          __syncthreads();
+          float smax = ts.wf[0][0], smin = ts.wf[1][0];
+#pragma unroll
+          for (int w = 1; w < SW; ++w) {
+            smax = fmaxf(smax, ts.wf[0][w]);
+            smin = fminf(smin, ts.wf[1][w]);
+          }
+          const uint64_t T = TKR::threshold(rv, hs, (uint32_t)hs.k, (uint32_t)mid_len, smin, smax, scratch, wpre, ts,
+                                            sm, A.dbg);
+          sT = float_from_order_key(~(uint32_t)(T >> 32));
+          Tidx = (uint32_t)T;
         }
       }
-      uint32_t pos[EM], taken_n;
-      ordered_positions<NT, EM>(take, pos, &taken_n, ord_sm);
+      VATT_STAMP(A.dbg, 3);
+      if (!marked) {
+        // Members of the top-k set go into the bitmap: slot u of a wave holds 64 consecutive tokens, so the
+        // wave's compare mask is two whole bitmap words, stored by one lane.  A score equal to the threshold
+        // score is rare and sends its group through the full comparison.  The weights of the members are
+        // added on the way, and those of the sink and window tokens unless they have been already.
+        uint64_t* bm64 = reinterpret_cast<uint64_t*>(bm_f);
+        rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
+          constexpr int G = RowView<NT, EE>::kGroup;
+          constexpr bool kInside = decltype(tag)::value;
+          const int first0 = i0 - (tid & 63);  // token of lane 0 in slot 0: a multiple of 64
 #pragma unroll
-      for (int e = 0; e < EM; ++e)
-        if (((take >> e) & 1u) && pos[e] < (uint32_t)A.k_max) idx[A.seg_topk + pos[e]] = (int32_t)xl[e];
+          for (int u = 0; u < G; ++u) {
+            const int i = i0 + u * NT;
+            const bool mid = kInside || (i >= hs.mid_lo && i < hs.mid_hi);
+            const bool take = mid && (s[u] > sT || (s[u] == sT && (uint32_t)i <= Tidx));
+            const uint64_t mask = __ballot(take);
+            if ((tid & 63) == 0 && (kInside || first0 + u * NT < n)) bm64[(first0 + u * NT) >> 6] = mask;
+            if (mask) acc_f32 += take ? __expf(s[u] - m) : 0.f;
+          }
+          if constexpr (!kInside) {
+            if (!edge_weights_done) {
+#pragma unroll
+              for (int u = 0; u < G; ++u) {
+                const int i = i0 + u * NT;
+                if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
+              }
+            }
+          }
+        });
+        edge_weights_done = true;
+        __syncthreads();
+      }
+      // ascending token list from the bitmap
+      O::word_prefix(bm_f, words, wpre, sm);
+      {
+        const int wpt = (words + NT - 1) / NT;
+        const int w0 = tid * wpt;
+        for (int w = w0; w < min(w0 + wpt, words); ++w) {
+          uint32_t bits = bm_f[w];
+          uint32_t pos = wpre[w];
+          while (bits) {
+            const int i = (w << 5) + (__ffs(bits) - 1);
+            bits &= bits - 1u;
+            if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+            ++pos;
+          }
+        }
+      }
       VATT_STAMP(A.dbg, 4);
+    }
+    if (!edge_weights_done) {
+      rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
+        if constexpr (!decltype(tag)::value) {
+#pragma unroll
+          for (int u = 0; u < RowView<NT, EE>::kGroup; ++u) {
+            const int i = i0 + u * NT;
+            if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
+          }
+        }
+      });
     }
     for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
     for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
@@ -880,18 +1025,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       O::mark_bit(bm_f, (uint32_t)i);
       acc_f += (double)__expf(row[i] - m);
     }
+    for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(row[i] - m);
+    for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
   }
-  for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(row[i] - m);
-  for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
   __syncthreads();
 
   // ---- I_bs (Algorithm 2, line 1) and the sums over it ----
-  int flags = 0;
+  int flags = topk_flag;
   double acc_w = 0.0, acc_w2 = 0.0;
   if (hs.n_s > 0) {
     if (A.phase != 2) {
-      const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches,
-                                   idx + A.seg_base, (uint32_t)A.b0_max, &acc_w, &acc_w2, sm);
+      const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches, idx + A.seg_base,
+                                   (uint32_t)A.b0_max, &acc_w, &acc_w2, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
       VATT_STAMP(A.dbg, 5);
     } else {
@@ -902,6 +1047,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       }
     }
   }
+  acc_f += (double)acc_f32;
   if (A.phase == 1) {
     if (tid == 0) {
       HeadRec r;
@@ -1023,11 +1169,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 }
 
 typedef void (*HeadKernel)(HeadArgs);
-// The instantiation for a plan: (workgroup size, top-k slots per thread).
+// The instantiation for a plan: (workgroup size, scores per thread kept in registers).
+#ifndef VATT_HEAD_NT
+#define VATT_HEAD_NT 512
+#endif
 HeadKernel head_kernel_for(const Plan& pl) {
-  const int64_t cands = (int64_t)pl.n_chunks * pl.cand_cap;
-  if (pl.head_threads == 256) return cands <= 16 * 256 ? head_kernel<256, 16> : head_kernel<256, 32>;
-  return head_kernel<1024, 32>;
+  if (pl.head_resident == 32 && pl.head_threads == 256) return head_kernel<256, 32>;
+  if (pl.head_resident > 0) return head_kernel<VATT_HEAD_NT, 32768 / VATT_HEAD_NT>;
+  return head_kernel<1024, 0>;
 }
 
 }  // namespace
@@ -1038,35 +1187,12 @@ hipError_t set_kernel_attributes(const Plan& pl) {
 }
 
 size_t head_kernel_lds_bytes(int n_max, int head_threads) {
-  const size_t words_max = (size_t)(n_max + 31) >> 5;
-  const size_t fixed = head_threads == 256 ? sizeof(HeadOps<256>::HeadSmem) : sizeof(HeadOps<1024>::HeadSmem);
-  return ((fixed + 15) & ~size_t(15)) + 6 * words_max * sizeof(uint32_t);
+  const size_t words_max = ((size_t)(n_max + 63) >> 6) << 1;
+  const size_t fixed = sizeof(HeadOps<1024>::HeadSmem);  // the largest of the variants
+  return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * sizeof(uint64_t) + 6 * words_max * sizeof(uint32_t);
 }
 
-hipError_t launch_stage1(const Plan& pl, const int32_t* seq_lens, void* ws, hipStream_t st) {
-  const vatt_params& p = pl.p;
-  char* w = static_cast<char*>(ws);
-  Stage1Args A;
-  A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
-  A.seq_lens = seq_lens;
-  A.chunk_max = reinterpret_cast<float*>(w + pl.off_chunk_max);
-  A.cand = reinterpret_cast<uint64_t*>(w + pl.off_cand);
-  A.cand_cnt = reinterpret_cast<int32_t*>(w + pl.off_cand_cnt);
-  A.sp = pl.sel;
-  A.n_pad = pl.n_pad;
-  A.n_max = p.n_max;
-  A.Hq = p.n_q_heads;
-  A.chunk_len = pl.chunk_len;
-  A.n_chunks = pl.n_chunks;
-  A.cand_cap = pl.cand_cap;
-  A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug);
-  dim3 grid(pl.n_chunks, p.n_q_heads, p.batch);
-  if (pl.stage_threads == 256)
-    hipLaunchKernelGGL((stage1_kernel<256, kChunkElems>), grid, dim3(256), 0, st, A);
-  else
-    hipLaunchKernelGGL((stage1_kernel<1024, kChunkElems>), grid, dim3(1024), 0, st, A);
-  return hipGetLastError();
-}
+size_t head_kernel_static_lds_bytes() { return sizeof(TopkSmem) + 64; }
 
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
@@ -1075,11 +1201,10 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   char* w = static_cast<char*>(ws);
   HeadArgs A;
   A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
+  A.sub_max = reinterpret_cast<const float*>(w + pl.off_sub_max);
+  A.n_sub = pl.n_sub;
   A.seq_lens = seq_lens;
   A.seq_seeds = seq_seeds;
-  A.chunk_max = reinterpret_cast<const float*>(w + pl.off_chunk_max);
-  A.cand = reinterpret_cast<const uint64_t*>(w + pl.off_cand);
-  A.cand_cnt = reinterpret_cast<const int32_t*>(w + pl.off_cand_cnt);
   A.head_rec = reinterpret_cast<HeadRec*>(w + pl.off_head_rec);
   A.vstat_part = reinterpret_cast<const double*>(w + pl.off_vstat_part);
   A.out_idx = out_idx;
@@ -1100,12 +1225,10 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.n_pad = pl.n_pad;
   A.n_max = p.n_max;
   A.Hq = p.n_q_heads;
-  A.n_chunks = pl.n_chunks;
-  A.cand_cap = pl.cand_cap;
-  A.cand_shift = pl.cand_shift;
   A.target = p.target;
   A.phase = phase;
   A.small_batches = pl.sampler_small_batches;
+  A.topk_general = pl.topk_general_path;
   A.draw_cap = pl.sampler_draw_cap;
   A.vstat_splits = pl.vstat_splits;
   A.head_dim = p.head_dim;

@@ -191,6 +191,34 @@ def test_sampler_in_small_batches_gives_identical_results():
     sess.close()
 
 
+def test_topk_general_path_gives_identical_results():
+    say("top-k by the general path (histogram over the whole row)")
+    from paper_2510_05688_amd import binding as vb
+    for wl in (workloads.small_gqa(seed=31, batch=2, n=9000), workloads.small_gqa(seed=32, batch=1, n=20000, topk_frac=0.05)):
+        sess = _session(wl)
+        fast = _run(sess)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 1)
+        general = _run(sess)
+        assert np.all(general["counts"][..., 7] & 32 == 32) and np.all(fast["counts"][..., 7] & 32 == 0)
+        _same_results(wl, fast, general)
+        check_all(wl, general, label="topk-general")
+        sess.close()
+
+
+def test_topk_with_runs_of_equal_scores():
+    say("many equal scores around the top-k threshold")
+    # keys repeated in blocks: scores come in runs of equal values, so ties at the threshold go by token order
+    wl = workloads.small_gqa(seed=33, batch=1, n_q_heads=4, n_kv_heads=1, n=6000)
+    wl.k_bits[:, :, 40:5960] = np.repeat(wl.k_bits[:, :, 40:5960:740], 740, axis=2)
+    for general in (0, 1):
+        from paper_2510_05688_amd import binding as vb
+        sess = _session(wl)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, general)
+        res = _run(sess)
+        check_all(wl, res, label="equal-scores general=%d" % general)
+        sess.close()
+
+
 def test_samples_taken_as_complements():
     say("complement regime (c > n_s / 2) for the final sample, then for both samples")
     # a tiny epsilon asks for every residual token; the cap leaves 70 % of them: 30 % are drawn to be left out
@@ -213,12 +241,11 @@ def test_samples_taken_as_complements():
 
 def test_repeated_proposals_inside_a_batch():
     say("short middle region: many repeated tokens inside one batch of draws")
-    # 1024 draws over about 4100 tokens repeat about 250 tokens: at the edge of what one large batch resolves,
-    # so some heads redo the batch in small ones (flag bit 5); either way the samples must match
+    # 1024 draws over about 4100 tokens propose about 250 tokens more than once, many of them in the same
+    # bitmap word: the earliest draw of each must win
     wl = workloads.small_gqa(seed=23, batch=3, n=4200, seq_lens=[4200, 4150, 4137], base_frac=0.2, epsilon=0.01)
     sess = _session(wl)
     res = _run(sess)
-    say("  heads that redid a batch: %d of %d" % (int((res["counts"][..., 7] & 32 != 0).sum()), wl.batch * wl.n_q_heads))
     check_all(wl, res, label="repeats")
     sess.close()
 
