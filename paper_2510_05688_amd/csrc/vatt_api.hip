@@ -100,21 +100,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
 
-  // the per-head kernel keeps rows of up to 32768 scores in registers (256 threads x 32 or 128 scores) and
-  // streams longer rows with 1024 threads
-  if (n_max <= 32 * 256) {
-    pl.head_threads = 256;
-    pl.head_resident = 32;
-  } else if (n_max <= 128 * 256) {
-#ifndef VATT_HEAD_NT
-#define VATT_HEAD_NT 512
-#endif
-    pl.head_threads = VATT_HEAD_NT;
-    pl.head_resident = 32768 / VATT_HEAD_NT;
-  } else {
-    pl.head_threads = 1024;
-    pl.head_resident = 0;
-  }
+  pl.head_threads = kHeadThreads;
 
   const int heads = p.batch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
@@ -139,9 +125,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
     off = align_up(off + bytes, 256);
     return o;
   };
-  // (the per-head kernel reads whole register tiles of a row, up to 32768 floats from the row's start,
-  // whatever the row length: the region is padded so that the last row's tile stays inside the workspace)
-  pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float) + (size_t)32768 * sizeof(float));
+  pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float));
   pl.off_sub_max = take((size_t)heads * pl.n_sub * sizeof(float));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));

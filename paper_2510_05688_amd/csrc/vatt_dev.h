@@ -94,12 +94,11 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
-// Maximum over each row of 16 lanes, left in every lane of the row.
-__device__ __forceinline__ float row_max16(float v) {
-  v = fmaxf(v, dpp_f32<0xB1>(v));
-  v = fmaxf(v, dpp_f32<0x4E>(v));
-  v = fmaxf(v, dpp_f32<0x141>(v));
-  v = fmaxf(v, dpp_f32<0x140>(v));
+// Maximum over each group of 8 adjacent lanes, left in every lane of the group.
+__device__ __forceinline__ float group_max8(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));   // partner lane ^ 1
+  v = fmaxf(v, dpp_f32<0x4E>(v));   // partner lane ^ 2
+  v = fmaxf(v, dpp_f32<0x141>(v));  // the other quad of the 8-lane half row
   return v;
 }
 

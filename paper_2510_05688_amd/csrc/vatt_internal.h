@@ -12,7 +12,8 @@ namespace vatt {
 
 constexpr int kScoreTile = 64;        // keys per score-kernel workgroup (small tiles: many short workgroups fill and
                                       // drain the chip more evenly than few long ones; measured 64 > 128 > 256 > 32)
-constexpr int kSubTile = 16;           // keys per sub-tile maximum
+constexpr int kSubTile = 8;            // keys per sub-tile maximum
+constexpr int kHeadThreads = 512;      // workgroup size of the per-head kernel
 constexpr int kGatherThreads = 256;
 constexpr int kDenseThreads = 256;
 
@@ -38,7 +39,6 @@ struct Plan {
   int n_sub;          // sub-tiles of kSubTile keys per row (the score kernel leaves each one's largest score)
   int k_max, b0_max, b_max;
   int head_threads;   // workgroup size of the per-head kernel
-  int head_resident;  // scores per thread that the per-head kernel keeps in registers (0: it streams the row)
   int gather_splits, dense_splits, vstat_splits;
   size_t idx_cap;
   int64_t seg_off[5];

@@ -92,12 +92,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       for (int g = 0; g < G; ++g) scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][t];
     }
   }
-  // Largest score of every 16 consecutive keys per query head: the selection kernel takes its head maximum
+  // Largest score of every 8 consecutive keys per query head: the selection kernel takes its head maximum
   // and a lower bound of the top-k threshold from these.
-  static_assert(kScoreTile == kWave && kSubTile == 16, "one lane per key of the tile, one DPP row per sub-tile");
+  static_assert(kScoreTile == kWave && kSubTile == 8, "one lane per key of the tile, eight lanes per sub-tile");
   for (int g = wave; g < G; g += 4) {
-    const float v = row_max16(tile_lo + lane < n ? s_tile[g][lane] : -INFINITY);
-    if ((lane & 15) == 0) {
+    const float v = group_max8(tile_lo + lane < n ? s_tile[g][lane] : -INFINITY);
+    if ((lane & 7) == 0) {
       const int64_t slot = ((int64_t)b * Hq + (int64_t)kvh * G + g) * n_sub + (tile_lo + lane) / kSubTile;
       sub_max[slot] = v;
     }

@@ -542,7 +542,7 @@ struct TopkSmem {
   float wf[2][16];
   uint32_t wu[2][16];
   uint64_t wq[16];
-  uint32_t cand_n;
+  uint32_t cand_n, qual_n;
 };
 
 template <int NT, class View>
@@ -738,7 +738,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 
   HeadSmem& sm = *reinterpret_cast<HeadSmem*>(dyn_smem);
   uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
-  uint32_t* bm_f = reinterpret_cast<uint32_t*>(cand + kCandCap);
+  uint32_t* qual = reinterpret_cast<uint32_t*>(cand + kCandCap);
+  uint32_t* bm_f = qual + kCandCap;
   uint32_t* taken0 = bm_f + words_max;
   uint32_t* taken1 = taken0 + words_max;
   uint32_t* scratch = taken1 + words_max;
@@ -754,6 +755,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // sampler work below.
   RowView<NT, EE> rv;
   rv.load(row, n);
+  const float edge0 = (A.phase != 2 && tid < hs.n_sink) ? row[tid] : -INFINITY;
+  const float edge1 = (A.phase != 2 && tid < hs.n_win) ? row[hs.mid_hi + tid] : -INFINITY;
   for (int w = tid; w < words; w += NT) {
     bm_f[w] = 0;
     taken0[w] = 0;
@@ -801,7 +804,16 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   float m;
   {
     float v_max = -INFINITY;
-    for (int t = tid; t < n_sub; t += NT) v_max = fmaxf(v_max, sub_max[t]);
+    for (int base = 0; base < n_sub; base += NT * 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t = base + u * NT + tid;
+        v[u] = t < n_sub ? sub_max[t] : -INFINITY;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v_max = fmaxf(v_max, v[u]);
+    }
     v_max = wave_max(v_max);
     if ((tid & 63) == 0) ts.wf[0][tid >> 6] = v_max;
     __syncthreads();
@@ -819,7 +831,6 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // ---- I_t (Algorithm 1, line 3) ----
   if (A.phase != 2) {
     const int mid_len = hs.mid_hi - hs.mid_lo;
-    bool edge_weights_done = false;
     if (hs.k > 0) {
       float sT = -INFINITY;
       uint32_t Tidx = kInv32;
@@ -832,8 +843,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;
         bool have_T = false;
         if (sub_hi - sub_lo >= hs.k && !A.topk_general) {
+          constexpr int U = 8;  // sub-tile maxima a thread has in flight
           float v_min = INFINITY;
-          for (int t = sub_lo + tid; t < sub_hi; t += NT) v_min = fminf(v_min, sub_max[t]);
+          for (int base = sub_lo; base < sub_hi; base += NT * U) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              const int t = base + u * NT + tid;
+              v[u] = t < sub_hi ? sub_max[t] : INFINITY;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) v_min = fminf(v_min, v[u]);
+          }
           v_min = -wave_max(-v_min);
           __syncthreads();
           if ((tid & 63) == 0) ts.wf[1][tid >> 6] = v_min;
@@ -845,55 +866,117 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
           const float scale = (float)(kBins - 1) / (m - lo_sub);
           if (m > lo_sub && scale < 1e30f) {
             TKR::zero_hist(ts);
-            for (int t = sub_lo + tid; t < sub_hi; t += NT) atomicAdd(&ts.hist[(uint32_t)((m - sub_max[t]) * scale)], 1u);
+            for (int base = sub_lo; base < sub_hi; base += NT * U) {
+              float v[U];
+#pragma unroll
+              for (int u = 0; u < U; ++u) {
+                const int t = base + u * NT + tid;
+                v[u] = t < sub_hi ? sub_max[t] : NAN;
+              }
+#pragma unroll
+              for (int u = 0; u < U; ++u) {
+                const bool in = base + u * NT + tid < sub_hi;
+                atomicAdd(&ts.hist[in ? (uint32_t)((m - v[u]) * scale) : (uint32_t)kBins], 1u);
+              }
+            }
             __syncthreads();
             TKR::locate((uint32_t)hs.k, ts, sm);
             // the lower edge of the bin of the k-th largest maximum, a little further down for rounding
             bound = fmaxf(lo_sub, m - ((float)ts.j + 1.02f) / scale);
           }
           VATT_STAMP(A.dbg, 22);
-          // candidates: middle scores at or above the bound (order in the list does not matter)
-          if (tid == 0) ts.cand_n = 0;
+          // sub-tiles that may hold a candidate: those that touch the middle region with a maximum at or
+          // above the bound (order in the list does not matter)
+          if (tid == 0) {
+            ts.cand_n = 0;
+            ts.qual_n = 0;
+          }
           __syncthreads();
-          rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
-            constexpr int G = RowView<NT, EE>::kGroup;
-            constexpr bool kInside = decltype(tag)::value;
+          const int sub_first = hs.mid_lo / kSubTile, sub_last = (hs.mid_hi + kSubTile - 1) / kSubTile;
+          for (int base = sub_first; base < sub_last; base += NT * U) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              const int t = base + u * NT + tid;
+              v[u] = t < sub_last ? sub_max[t] : -INFINITY;
+            }
             uint32_t hit = 0;
 #pragma unroll
-            for (int u = 0; u < G; ++u) {
-              const int i = i0 + u * NT;
-              const bool mid = kInside || (i >= hs.mid_lo && i < hs.mid_hi);
-              hit |= ((mid && s[u] >= bound) ? 1u : 0u) << u;
-            }
+            for (int u = 0; u < U; ++u) hit |= (v[u] >= bound ? 1u : 0u) << u;
             const uint32_t mine = (uint32_t)__popc(hit);
             const uint32_t incl = wave_inclusive_scan_u32(mine);
             const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
             if (wave_tot) {
-              uint32_t base = 0;
-              if ((tid & 63) == 0) base = atomicAdd(&ts.cand_n, wave_tot);
-              base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-              uint32_t pos = base + incl - mine;
+              uint32_t at = 0;
+              if ((tid & 63) == 0) at = atomicAdd(&ts.qual_n, wave_tot);
+              at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+              uint32_t pos = at + incl - mine;
 #pragma unroll
-              for (int u = 0; u < G; ++u) {
+              for (int u = 0; u < U; ++u) {
                 if ((hit >> u) & 1u) {
-                  if (pos < (uint32_t)kCandCap)
-                    cand[pos] = ((uint64_t)(~float_order_key(s[u])) << 32) | (uint32_t)(i0 + u * NT);
+                  if (pos < (uint32_t)kCandCap) qual[pos] = (uint32_t)(base + u * NT + tid);
                   ++pos;
                 }
               }
             }
-            if constexpr (!kInside) {
+          }
+          __syncthreads();
+          const uint32_t n_qual = ts.qual_n;
+          VATT_STAMP(A.dbg, 23);
+          VATT_NOTE(A.dbg, 27, n_qual);
+          if (n_qual <= (uint32_t)kCandCap) {
+            // candidates: the middle scores of those sub-tiles that are at or above the bound
+            static_assert(kSubTile == 8, "two 16-byte loads per sub-tile");
+            constexpr int Q = 2;  // sub-tiles a thread has in flight
+            for (uint32_t q0 = 0; q0 < n_qual; q0 += NT * Q) {
+              float sv[Q][kSubTile];
+              int tok0[Q];
 #pragma unroll
-              for (int u = 0; u < G; ++u) {
-                const int i = i0 + u * NT;
-                if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
+              for (int u = 0; u < Q; ++u) {
+                const uint32_t q = q0 + u * NT + tid;
+                const bool ok = q < n_qual;
+                tok0[u] = ok ? (int)min(qual[min(q, (uint32_t)(kCandCap - 1))], (uint32_t)(sub_last - 1)) * kSubTile : -1;
+                const float4* src = reinterpret_cast<const float4*>(row + max(tok0[u], 0));
+                const float4 x = ok ? src[0] : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float4 y = ok ? src[1] : make_float4(0.f, 0.f, 0.f, 0.f);
+                sv[u][0] = x.x; sv[u][1] = x.y; sv[u][2] = x.z; sv[u][3] = x.w;
+                sv[u][4] = y.x; sv[u][5] = y.y; sv[u][6] = y.z; sv[u][7] = y.w;
+              }
+              uint32_t hit = 0;
+#pragma unroll
+              for (int u = 0; u < Q; ++u) {
+#pragma unroll
+                for (int e = 0; e < kSubTile; ++e) {
+                  const int i = tok0[u] + e;
+                  hit |= ((tok0[u] >= 0 && i >= hs.mid_lo && i < hs.mid_hi && sv[u][e] >= bound) ? 1u : 0u)
+                         << (u * kSubTile + e);
+                }
+              }
+              const uint32_t mine = (uint32_t)__popc(hit);
+              const uint32_t incl = wave_inclusive_scan_u32(mine);
+              const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+              if (wave_tot) {
+                uint32_t at = 0;
+                if ((tid & 63) == 0) at = atomicAdd(&ts.cand_n, wave_tot);
+                at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+                uint32_t pos = at + incl - mine;
+#pragma unroll
+                for (int u = 0; u < Q; ++u) {
+#pragma unroll
+                  for (int e = 0; e < kSubTile; ++e) {
+                    if ((hit >> (u * kSubTile + e)) & 1u) {
+                      if (pos < (uint32_t)kCandCap)
+                        cand[pos] = ((uint64_t)(~float_order_key(sv[u][e])) << 32) | (uint32_t)(tok0[u] + e);
+                      ++pos;
+                    }
+                  }
+                }
               }
             }
-          });
-          edge_weights_done = true;
-          __syncthreads();
-          const uint32_t n_cand = ts.cand_n;
-          VATT_STAMP(A.dbg, 23);
+            __syncthreads();
+          }
+          const uint32_t n_cand = n_qual <= (uint32_t)kCandCap ? ts.cand_n : 0u;
+          VATT_STAMP(A.dbg, 24);
           VATT_NOTE(A.dbg, 26, n_cand);
           if (n_cand <= (uint32_t)kCandCap && n_cand >= (uint32_t)hs.k) {
             CandView<NT> cv;
@@ -959,7 +1042,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         // Members of the top-k set go into the bitmap: slot u of a wave holds 64 consecutive tokens, so the
         // wave's compare mask is two whole bitmap words, stored by one lane.  A score equal to the threshold
         // score is rare and sends its group through the full comparison.  The weights of the members are
-        // added on the way, and those of the sink and window tokens unless they have been already.
+        // added on the way.
         uint64_t* bm64 = reinterpret_cast<uint64_t*>(bm_f);
         rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
           constexpr int G = RowView<NT, EE>::kGroup;
@@ -974,17 +1057,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
             if ((tid & 63) == 0 && (kInside || first0 + u * NT < n)) bm64[(first0 + u * NT) >> 6] = mask;
             if (mask) acc_f32 += take ? __expf(s[u] - m) : 0.f;
           }
-          if constexpr (!kInside) {
-            if (!edge_weights_done) {
-#pragma unroll
-              for (int u = 0; u < G; ++u) {
-                const int i = i0 + u * NT;
-                if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
-              }
-            }
-          }
         });
-        edge_weights_done = true;
         __syncthreads();
       }
       // ascending token list from the bitmap
@@ -1005,17 +1078,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       }
       VATT_STAMP(A.dbg, 4);
     }
-    if (!edge_weights_done) {
-      rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
-        if constexpr (!decltype(tag)::value) {
-#pragma unroll
-          for (int u = 0; u < RowView<NT, EE>::kGroup; ++u) {
-            const int i = i0 + u * NT;
-            if (i < n && !(i >= hs.mid_lo && i < hs.mid_hi)) acc_f32 += __expf(s[u] - m);
-          }
-        }
-      });
-    }
+    // weights of the sink and window tokens (their scores were requested at the start)
+    acc_f32 += __expf(edge0 - m) + __expf(edge1 - m);  // exp(-inf) = 0 for threads without a token
+    for (int i = tid + NT; i < hs.n_sink; i += NT) acc_f32 += __expf(row[i] - m);
+    for (int i = tid + NT; i < hs.n_win; i += NT) acc_f32 += __expf(row[hs.mid_hi + i] - m);
     for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
     for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
   } else {
@@ -1170,13 +1236,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 
 typedef void (*HeadKernel)(HeadArgs);
 // The instantiation for a plan: (workgroup size, scores per thread kept in registers).
-#ifndef VATT_HEAD_NT
-#define VATT_HEAD_NT 512
-#endif
 HeadKernel head_kernel_for(const Plan& pl) {
-  if (pl.head_resident == 32 && pl.head_threads == 256) return head_kernel<256, 32>;
-  if (pl.head_resident > 0) return head_kernel<VATT_HEAD_NT, 32768 / VATT_HEAD_NT>;
-  return head_kernel<1024, 0>;
+  (void)pl;
+  return head_kernel<kHeadThreads, 0>;
 }
 
 }  // namespace
@@ -1188,8 +1250,9 @@ hipError_t set_kernel_attributes(const Plan& pl) {
 
 size_t head_kernel_lds_bytes(int n_max, int head_threads) {
   const size_t words_max = ((size_t)(n_max + 63) >> 6) << 1;
-  const size_t fixed = sizeof(HeadOps<1024>::HeadSmem);  // the largest of the variants
-  return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * sizeof(uint64_t) + 6 * words_max * sizeof(uint32_t);
+  const size_t fixed = sizeof(HeadOps<kHeadThreads>::HeadSmem);
+  return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * (sizeof(uint64_t) + sizeof(uint32_t)) +
+         6 * words_max * sizeof(uint32_t);
 }
 
 size_t head_kernel_static_lds_bytes() { return sizeof(TopkSmem) + 64; }
