@@ -22,11 +22,11 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 
 # HBM bytes per score-kernel launch from two rocprofv3 --pmc runs of `bench.py --only score` (FETCH_SIZE, then
 # WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for `bench.py --only copy`, a
-# 256 MiB device copy: FETCH_SIZE reads 131083.5 KiB for its 262144 KiB (factor 1.99983), WRITE_SIZE 262144
-# (factor 1).  Score kernel at config 2: FETCH_SIZE 32825.5, WRITE_SIZE 4096.0; at config 3: 524825.9 and 65536.0.  The summaries are kept under
-# profiles/.  Only the configurations that were measured have a figure.
-SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32825.5 * 262144.0 / 131083.5 + 4096.0) * 1024),
-                              "config3": int((524825.9 * 262144.0 / 131083.5 + 65536.0) * 1024)}
+# 256 MiB device copy: FETCH_SIZE reads 131084.4 KiB for its 262144 KiB (factor 1.99981), WRITE_SIZE 262144
+# (factor 1).  Score kernel at config 2: FETCH_SIZE 32827.5, WRITE_SIZE 4608.0; at config 3: 524827.5 and
+# 73728.0.  The summaries are kept under profiles/.  Only the configurations that were measured have a figure.
+SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32827.5 * 262144.0 / 131084.4 + 4608.0) * 1024),
+                              "config3": int((524827.5 * 262144.0 / 131084.4 + 73728.0) * 1024)}
 LLAMA8B_LAYERS = 32
 
 
@@ -159,12 +159,17 @@ def main():
     b_dyn = counts[:, 4]
     seq_n = np.asarray(wl.seq_lens, dtype=np.int64)
     k_scan = int(Hkv * d * 2 * seq_n.sum())
-    score_rw = int(2 * Hq * 4 * seq_n.sum())
+    score_w = int(Hq * 4 * seq_n.sum())                        # fp32 scores, written once
+    submax_w = int(Hq * 4 * ((seq_n + 63) // 64 * 8).sum())     # largest score of every 8 keys
     v_rows = int(((n_f + b_dyn) * d * 2).sum())
     if int(wl.params["target"]) != 0:
         v_rows += int(((n_f + counts[:, 3]) * d * 2).sum())
-    path_bytes = k_scan + score_rw + v_rows
-    score_kernel_bytes = k_scan + score_rw // 2 + B * Hq * d * 2
+    # the selection reads the 8-key maxima (twice) and a few thousand scores per head; the gather reads one
+    # score and one index per gathered row
+    select_r = 2 * submax_w + int(((counts[:, 2] + 2 * counts[:, 3] + b_dyn) * 32).sum())
+    gather_r = int(((n_f + b_dyn) * 8).sum())
+    path_bytes = k_scan + score_w + submax_w + select_r + gather_r + v_rows
+    score_kernel_bytes = k_scan + score_w + submax_w + B * Hq * d * 2
     dense_bytes = 2 * k_scan
 
     us_layer = ms_step * 1e3

@@ -127,7 +127,7 @@ void vatt_plan_destroy(vatt_plan* plan);
  * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that
  * the completion rule can be exercised.
  * VATT_OPT_TOPK_GENERAL_PATH = 1 makes the top-k selection skip its usual shortcut (a lower bound of the
- * threshold from the largest scores of every 16 keys) and take the general path, a histogram over the whole
+ * threshold from the largest scores of every 8 keys) and take the general path, a histogram over the whole
  * score row, which otherwise only serves short or unusual rows; results are identical.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3 };
