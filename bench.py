@@ -1,12 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the vAttention decode step (libvatt) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--no-cpu]
 
 A step is one vatt_decode call: the whole hot path (score pass, chunk top-k, per-head selection / base
 sample / statistics / budget / final sample, gather) for one layer and one batch of synthetic input that
 is already resident in HBM.  Calls cycle through `--buffers` distinct copies of the KV cache so that no
 call finds its K/V in the 256 MB last-level cache.  Prints ONE JSON line.
+--config 5 is the ragged paged decode loop (B=32, one appended token per sequence and step): it reports the step
+latency distribution and the budgets of the last step instead of the roofline of the score kernel.
 """
 import argparse
 import json
@@ -83,12 +85,70 @@ def cpu_baseline(wl, budget_s=12.0):
                        % (done, el, total_heads))
 
 
+def decode_loop(args, torch, np, workloads, DecodeSession):
+    """Config 5: ragged paged decode loop.  A step appends one token per sequence and runs vatt_decode."""
+    from paper_2510_05688_amd.session import _bf16_from_bits
+    steps, warm = args.steps, args.warmup
+    wl = workloads.config5(steps=steps + warm + 1)
+    k_pages, v_pages, table = workloads.configs.to_paged(wl, page=16, seed=3)
+    pp = plan_params(wl)
+    pp.update(kv_layout=1, page_size=16, num_blocks=int(k_pages.shape[0]))
+    sess = DecodeSession(pp)
+    sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+    new_tokens = [workloads.configs.append_tokens(5, s_, wl.batch, wl.n_kv_heads, wl.head_dim) for s_ in range(steps + warm)]
+    new_dev = [(_bf16_from_bits(kn, sess.device), _bf16_from_bits(vn, sess.device)) for kn, vn in new_tokens]
+    seeds_dev = [torch.from_numpy((wl.seeds + np.uint64(7919 * s_)).view(np.int64)).to(sess.device)
+                 for s_ in range(steps + warm)]
+
+    def step(i):
+        sess.append_device(*new_dev[i])
+        sess.seq_seeds = seeds_dev[i]
+        sess.decode()
+
+    for i in range(warm):
+        step(i)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    events[0].record()
+    for i in range(steps):
+        step(warm + i)
+        events[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = np.array([events[i].elapsed_time(events[i + 1]) for i in range(steps)]) * 1e3
+    ms_step = events[0].elapsed_time(events[steps]) / steps
+    res = sess.results_host()
+    counts = res["counts"].reshape(-1, 8).astype(np.int64)
+    b_star = res["b_star"].reshape(-1)
+    seq_n = sess.seq_lens.cpu().numpy().astype(np.int64)
+    n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
+    dens = (n_f + counts[:, 4]) / np.repeat(seq_n, wl.n_q_heads)
+    pct = lambda a, q: float(np.percentile(a, q))
+    out = {
+        "metric": "vattention_decode_us_per_layer", "value": ms_step * 1e3, "unit": "us", "n_gpus": 1,
+        "steps": steps, "warmup": warm, "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 K/V, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
+                   "head_dim": wl.head_dim, "n_start": "U[1024, 32768] per sequence", "page_size": 16,
+                   "epsilon": float(wl.params["epsilon"]), "delta": float(wl.params["delta"]),
+                   "step": "vatt_append_kv + vatt_decode"},
+        "step_latency_us": {"p10": pct(per_step, 10), "p50": pct(per_step, 50), "p90": pct(per_step, 90),
+                            "max": float(per_step.max())},
+        "sum_of_lengths_at_end": int(seq_n.sum()),
+        "budget_last_step": {"b_min": int(counts[:, 4].min()), "b_p50": pct(counts[:, 4], 50),
+                             "b_p90": pct(counts[:, 4], 90), "b_max": int(counts[:, 4].max()),
+                             "heads_above_base": int((counts[:, 4] > counts[:, 3]).sum()),
+                             "b_star_p50": pct(b_star, 50), "b_star_p90": pct(b_star, 90),
+                             "b_star_max": float(b_star.max()), "density_mean": float(dens.mean())},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4])
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
@@ -107,6 +167,9 @@ def main():
         print("bench.py needs a GPU (no CPU path exists for the product)", file=sys.stderr)
         sys.exit(2)
 
+    if args.config == 5:
+        decode_loop(args, torch, np, workloads, DecodeSession)
+        return
     wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
     sess = DecodeSession(plan_params(wl))
     sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)

@@ -232,7 +232,7 @@ struct HeadOps {
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if ((unresolved >> e) & 1u) atomicMin(&S.mail[B.tok[e] >> 5], ((uint32_t)(tid * 4 + e) << 5) | (B.tok[e] & 31));
-      if (tid == 0) sm.again = 0;
+      if (threadIdx.x == 0) sm.again = 0;
       __syncthreads();
       uint32_t won = 0;
 #pragma unroll
@@ -801,9 +801,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // ---- the head maximum m, from the sub-tile maxima the score kernel left ----
   const int n_sub = (n + kSubTile - 1) / kSubTile;
   const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
-  float m;
+  const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;  // whole middle sub-tiles
+  float m, lo_sub;  // lo_sub: the smallest maximum of a whole middle sub-tile
   {
-    float v_max = -INFINITY;
+    float v_max = -INFINITY, v_min = INFINITY;
     for (int base = 0; base < n_sub; base += NT * 8) {
       float v[8];
 #pragma unroll
@@ -812,14 +813,26 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         v[u] = t < n_sub ? sub_max[t] : -INFINITY;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v_max = fmaxf(v_max, v[u]);
+      for (int u = 0; u < 8; ++u) {
+        const int t = base + u * NT + tid;
+        v_max = fmaxf(v_max, v[u]);
+        v_min = (t >= sub_lo && t < sub_hi) ? fminf(v_min, v[u]) : v_min;
+      }
     }
     v_max = wave_max(v_max);
-    if ((tid & 63) == 0) ts.wf[0][tid >> 6] = v_max;
+    v_min = -wave_max(-v_min);
+    if ((tid & 63) == 0) {
+      ts.wf[0][tid >> 6] = v_max;
+      ts.wf[1][tid >> 6] = v_min;
+    }
     __syncthreads();
     m = ts.wf[0][0];
+    lo_sub = ts.wf[1][0];
 #pragma unroll
-    for (int w = 1; w < SW; ++w) m = fmaxf(m, ts.wf[0][w]);
+    for (int w = 1; w < SW; ++w) {
+      m = fmaxf(m, ts.wf[0][w]);
+      lo_sub = fminf(lo_sub, ts.wf[1][w]);
+    }
   }
   S0.m = m;
   S1.m = m;
@@ -840,28 +853,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         // the sub-tiles that lie entirely in the middle region) has at least k middle scores at or above it.
         // Found to one histogram bin, it leaves a few more than k candidates, which are listed in LDS and
         // selected among exactly.
-        const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;
         bool have_T = false;
         if (sub_hi - sub_lo >= hs.k && !A.topk_general) {
           constexpr int U = 8;  // sub-tile maxima a thread has in flight
-          float v_min = INFINITY;
-          for (int base = sub_lo; base < sub_hi; base += NT * U) {
-            float v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-              const int t = base + u * NT + tid;
-              v[u] = t < sub_hi ? sub_max[t] : INFINITY;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) v_min = fminf(v_min, v[u]);
-          }
-          v_min = -wave_max(-v_min);
-          __syncthreads();
-          if ((tid & 63) == 0) ts.wf[1][tid >> 6] = v_min;
-          __syncthreads();
-          float lo_sub = ts.wf[1][0];
-#pragma unroll
-          for (int w = 1; w < SW; ++w) lo_sub = fminf(lo_sub, ts.wf[1][w]);
           float bound = lo_sub;  // every middle sub-tile maximum is at or above this
           const float scale = (float)(kBins - 1) / (m - lo_sub);
           if (m > lo_sub && scale < 1e30f) {

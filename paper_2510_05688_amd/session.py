@@ -97,7 +97,11 @@ class DecodeSession:
     def append(self, k_new_bits, v_new_bits):
         kn = _bf16_from_bits(k_new_bits, self.device)
         vn = _bf16_from_bits(v_new_bits, self.device)
-        vb.vatt_append_kv(self.plan, kn, vn, self.k, self.v, self.block_table, self.seq_lens, self._stream())
+        self.append_device(kn, vn)
+
+    def append_device(self, k_new, v_new):
+        """Append one token per sequence from tensors that are already on the device (bf16 [B, Hkv, d])."""
+        vb.vatt_append_kv(self.plan, k_new, v_new, self.k, self.v, self.block_table, self.seq_lens, self._stream())
 
     # ---- read-back -----------------------------------------------------------
     def scores_host(self) -> np.ndarray:
