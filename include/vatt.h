@@ -178,6 +178,24 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v,
                 int32_t* out_counts, double* out_budget_raw, float* out_stats, void* stream);
 
 /*
+ * The same decode step with the top-k set supplied by the caller: Section 4.1 leaves the choice of I_t to any
+ * (approximate) top-k method, and without the exact score pass only the attended tokens' K and V rows are read.
+ *   topk_idx     device, int32 [B, Hq, k_max] with k_max = the length of the top-k segment of out_idx
+ *                (vatt_plan_index_segment(plan, 3) - vatt_plan_index_segment(plan, 2)); tokens in any order
+ *   topk_cnt     device, int32 [B, Hq]: entries used per head (clamped to [0, k_max])
+ * I_t is the set of supplied tokens that lie between sink and window, without repeats; everything after it
+ * follows Algorithm 1 as in vatt_decode: residual, base sample, statistics, budget, final sample, estimate.
+ * Scores exist only for I_f, I_bs and I_dyn; out_stats and out_lse use the largest score among I_f and I_bs
+ * as the shift (every quantity Algorithm 2 forms is a ratio and does not depend on it).
+ * Only the denominator target is supported (VATT_E_UNSUPPORTED_SHAPE otherwise).  Other arguments as in vatt_decode.
+ */
+int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const void* v,
+                           const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                           const int32_t* topk_idx, const int32_t* topk_cnt, void* workspace,
+                           size_t workspace_bytes, float* out_o, float* out_lse, int32_t* out_idx,
+                           int32_t* out_counts, double* out_budget_raw, float* out_stats, void* stream);
+
+/*
  * Dense decode attention (Eq. 1) on the same cache: the sparsity speed-up denominator.
  * Arguments as in vatt_decode.  out_lse may be NULL.
  */

@@ -31,7 +31,7 @@ VATT_OPT_TOPK_GENERAL_PATH = 3
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
-    "vatt_plan_index_segment", "vatt_decode", "vatt_dense_decode", "vatt_score", "vatt_append_kv",
+    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv",
     "vatt_status_string",
 ]
 
@@ -79,6 +79,8 @@ def _load():
     lib.vatt_plan_index_segment.restype = i64
     lib.vatt_decode.argtypes = [vp] * 8 + [sz] + [vp] * 7
     lib.vatt_decode.restype = ctypes.c_int
+    lib.vatt_decode_given_topk.argtypes = [vp] * 10 + [sz] + [vp] * 7
+    lib.vatt_decode_given_topk.restype = ctypes.c_int
     lib.vatt_dense_decode.argtypes = [vp] * 7 + [sz] + [vp] * 3
     lib.vatt_dense_decode.restype = ctypes.c_int
     lib.vatt_score.argtypes = [vp] * 6 + [sz, vp]
@@ -166,6 +168,16 @@ def vatt_decode(plan, q, k, v, block_table, seq_lens, seq_seeds, workspace, out_
                           _ptr(out_counts), _ptr(out_budget_raw), _ptr(out_stats), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_decode")
+
+
+def vatt_decode_given_topk(plan, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_o,
+                           out_lse, out_idx, out_counts, out_budget_raw, out_stats, stream=None) -> None:
+    rc = _lib.vatt_decode_given_topk(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(block_table), _ptr(seq_lens),
+                                     _ptr(seq_seeds), _ptr(topk_idx), _ptr(topk_cnt), _ptr(workspace),
+                                     _nbytes(workspace), _ptr(out_o), _ptr(out_lse), _ptr(out_idx),
+                                     _ptr(out_counts), _ptr(out_budget_raw), _ptr(out_stats), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_decode_given_topk")
 
 
 def vatt_dense_decode(plan, q, k, v, block_table, seq_lens, workspace, out_o, out_lse, stream=None) -> None:

@@ -127,6 +127,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
   };
   pl.off_scores = take((size_t)heads * pl.n_pad * sizeof(float));
   pl.off_sub_max = take((size_t)heads * pl.n_sub * sizeof(float));
+  pl.off_sparse = take((size_t)heads * pl.idx_cap * sizeof(float));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
   pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
@@ -269,6 +270,28 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
     VATT_LAUNCH(launch_head(pl, 2, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   }
   VATT_LAUNCH(launch_gather(pl, v, block_table, workspace, out_idx, out_o, out_lse, st));
+  return VATT_OK;
+}
+
+int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const void* v, const int32_t* block_table,
+                           const int32_t* seq_lens, const uint64_t* seq_seeds, const int32_t* topk_idx,
+                           const int32_t* topk_cnt, void* workspace, size_t workspace_bytes, float* out_o,
+                           float* out_lse, int32_t* out_idx, int32_t* out_counts, double* out_budget_raw,
+                           float* out_stats, void* stream) {
+  int rc = check_common(plan, workspace, workspace_bytes, block_table);
+  if (rc != VATT_OK) return rc;
+  if (!q || !k || !v || !seq_lens || !seq_seeds || !topk_idx || !topk_cnt || !out_o || !out_idx || !out_counts)
+    return VATT_E_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
+  const Plan& pl = plan->pl;
+  if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
+                                  out_budget_raw, out_stats, st));
+  VATT_LAUNCH(launch_sparse_score(pl, q, k, block_table, workspace, out_idx, st));
+  VATT_LAUNCH(launch_given_select(pl, 1, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
+                                  out_budget_raw, out_stats, st));
+  VATT_LAUNCH(launch_given_gather(pl, q, k, v, block_table, workspace, out_idx, out_o, out_lse, st));
   return VATT_OK;
 }
 

@@ -1,0 +1,319 @@
+// Decode step with a caller-supplied top-k set (the paper's pred-top-index hook, Section 4.1: any approximate
+// top-k method may supply I_t): no pass over the whole K cache.  Scores exist only for the tokens that are
+// attended:
+//
+//   sparse_score_kernel   s_i = sm_scale * <K[i], q> for the tokens of I_f and I_bs, written next to their
+//                         places in the index lists
+//   given_gather_kernel   the N and D sums of Section 4.1 over [I_f, I_dyn]: scores of I_f from the sparse
+//                         list, scores of I_dyn computed here from their K rows; V rows gathered as in the
+//                         dense-scored path.  No head maximum is known in advance, so every lane group keeps a
+//                         running maximum and rescales (online softmax), and the merge combines the splits'
+//                         (max, D, N) partials the same way.
+//
+// grid = (splits, query heads, sequences) for both; d/8 adjacent lanes read one K or V row with one 16-byte
+// load each.
+#include "vatt_internal.h"
+
+namespace vatt {
+namespace {
+
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc,
+                                         false);
+}
+
+struct GivenArgs {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  KVLayout Lk, Lv;
+  const HeadRec* head_rec;
+  const int32_t* idx;
+  float* sparse;      // [B*Hq][idx_cap]: score of the token at the same place of the index lists
+  float* part;        // [B*Hq][splits][d + 4]: N[d], D, running maximum
+  float* out_o;
+  float* out_lse;
+  int64_t seg_sink, seg_win, seg_topk, seg_base, seg_dyn, idx_cap;
+  int Hq, group, splits;
+  float sm_scale;
+};
+
+// Place in the index lists (offset into a head's out_idx / sparse row) of list position p of
+// [sink | window | top-k | tail), and the token there.
+__device__ __forceinline__ int64_t list_place(const GivenArgs& A, const HeadRec& r, const int32_t* idx, int64_t seg_tail,
+                                              int p, int* token, bool* in_tail) {
+  *in_tail = false;
+  if (p < r.n_sink) {
+    *token = p;
+    return A.seg_sink + p;
+  }
+  p -= r.n_sink;
+  if (p < r.n_win) {
+    *token = r.n - r.n_win + p;
+    return A.seg_win + p;
+  }
+  p -= r.n_win;
+  if (p < r.k) {
+    *token = idx[A.seg_topk + p];
+    return A.seg_topk + p;
+  }
+  p -= r.k;
+  *in_tail = true;
+  *token = idx[seg_tail + p];
+  return seg_tail + p;
+}
+
+template <int D>
+__device__ __forceinline__ void load_q(const GivenArgs& A, int bh, int sub, uint32_t (&qw)[4]) {
+  const uint4 t = *reinterpret_cast<const uint4*>(A.q + (int64_t)bh * D + sub * 8);
+  qw[0] = t.x;
+  qw[1] = t.y;
+  qw[2] = t.z;
+  qw[3] = t.w;
+}
+
+template <int LPR>
+__device__ __forceinline__ float row_score(const uint4& kv, const uint32_t (&qw)[4], float sm_scale) {
+  float a = 0.f;
+  a = dot2_bf16(kv.x, qw[0], a);
+  a = dot2_bf16(kv.y, qw[1], a);
+  a = dot2_bf16(kv.z, qw[2], a);
+  a = dot2_bf16(kv.w, qw[3], a);
+  return group_sum<LPR>(a) * sm_scale + 0.0f;
+}
+
+// Scores of the tokens of I_f and I_bs (HeadRec.b holds |I_bs| at this point).
+template <int D, bool PAGED>
+__global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs A) {
+  constexpr int LPR = D / 8;
+  constexpr int RPW = kWave / LPR;
+  constexpr int WAVES = kGatherThreads / kWave;
+  constexpr int RPB = RPW * WAVES;
+  constexpr int U = 8;
+  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int bh = b * A.Hq + h;
+  const int kvh = h / A.group;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPR, rsub = lane / LPR;
+  const HeadRec r = A.head_rec[bh];
+  const int32_t* idx = A.idx + (int64_t)bh * A.idx_cap;
+  float* sp = A.sparse + (int64_t)bh * A.idx_cap;
+  const int total = r.n_sink + r.n_win + r.k + r.b;
+  const int per = (total + A.splits - 1) / A.splits;
+  const int p_lo = split * per, p_hi = min(p_lo + per, total);
+  uint32_t qw[4];
+  load_q<D>(A, bh, sub, qw);
+  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
+    int64_t place[U];
+    uint4 kv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = p0 + u * RPB;
+      place[u] = -1;
+      kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (p < p_hi) {
+        int tok;
+        bool tail;
+        place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail);
+        tok = min(max(tok, 0), r.n - 1);
+        kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float s = row_score<LPR>(kv[u], qw, A.sm_scale);
+      if (place[u] >= 0 && sub == 0) sp[place[u]] = s;
+    }
+  }
+}
+
+template <int D, bool PAGED>
+__global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs A) {
+  constexpr int LPR = D / 8;
+  constexpr int RPW = kWave / LPR;
+  constexpr int WAVES = kGatherThreads / kWave;
+  constexpr int RPB = RPW * WAVES;
+  constexpr int GROUPS = RPB;  // lane groups of a workgroup, each with its own running maximum
+  constexpr int U = 8;
+  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int bh = b * A.Hq + h;
+  const int kvh = h / A.group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, rsub = lane / LPR;
+  const HeadRec r = A.head_rec[bh];
+  const int32_t* idx = A.idx + (int64_t)bh * A.idx_cap;
+  const float* sp = A.sparse + (int64_t)bh * A.idx_cap;
+  const int total = r.n_sink + r.n_win + r.k + r.b;
+  const int per = (total + A.splits - 1) / A.splits;
+  const int p_lo = split * per, p_hi = min(p_lo + per, total);
+  const float tail_bias = r.scale > 0.f ? __logf(r.scale) : 0.f;  // ln(n_s / b): sampled tokens weigh n_s / b
+  uint32_t qw[4];
+  load_q<D>(A, bh, sub, qw);
+
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.f;
+  float dsum = 0.f, m_run = -INFINITY;
+
+  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
+    bool have[U], tail[U];
+    float s[U];
+    uint4 kv[U], vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = p0 + u * RPB;
+      have[u] = p < p_hi;
+      tail[u] = false;
+      s[u] = 0.f;
+      kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      vv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (have[u]) {
+        int tok;
+        const int64_t place = list_place(A, r, idx, A.seg_dyn, p, &tok, &tail[u]);
+        tok = min(max(tok, 0), r.n - 1);
+        if (tail[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
+        else s[u] = sp[place];
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, tok) + sub * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      // (the lanes of a group stay together: every lane of the group computes the row's score)
+      const float sk = row_score<LPR>(kv[u], qw, A.sm_scale);
+      if (have[u]) {
+        const float e = tail[u] ? sk + tail_bias : s[u];
+        if (e > m_run) {
+          const float f = __expf(m_run - e);  // 0 when m_run is -inf
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[c] *= f;
+          dsum *= f;
+          m_run = e;
+        }
+        const float wt = __expf(e - m_run);
+        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          acc[2 * c] += wt * bf16_lo(ww[c]);
+          acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+        }
+        dsum += wt;
+      }
+    }
+  }
+
+  // every lane group has its own (maximum, D, N): bring them to the workgroup's maximum and add
+  __shared__ float s_acc[GROUPS][D];
+  __shared__ float s_d[GROUPS], s_m[GROUPS];
+  const int g = wave * RPW + rsub;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) s_acc[g][sub * 8 + c] = acc[c];
+  if (sub == 0) {
+    s_d[g] = dsum;
+    s_m[g] = m_run;
+  }
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < GROUPS; ++j) M = fmaxf(M, s_m[j]);
+  float* part = A.part + ((int64_t)bh * A.splits + split) * (D + 4);
+  if (tid < D) {
+    float a = 0.f;
+#pragma unroll
+    for (int j = 0; j < GROUPS; ++j) a += s_acc[j][tid] * (s_m[j] > -INFINITY ? __expf(s_m[j] - M) : 0.f);
+    part[tid] = a;
+  }
+  if (tid == 0) {
+    float d = 0.f;
+#pragma unroll
+    for (int j = 0; j < GROUPS; ++j) d += s_d[j] * (s_m[j] > -INFINITY ? __expf(s_m[j] - M) : 0.f);
+    part[D] = d;
+    part[D + 1] = M;
+  }
+}
+
+// Combines the per-split (maximum, D, N) partials of a head in split order: O = N / D, lse = M + ln D.
+template <int D>
+__global__ __launch_bounds__(D) void given_merge_kernel(const float* __restrict__ part, int splits, int Hq,
+                                                        float* __restrict__ out_o, float* __restrict__ out_lse) {
+  const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
+  const int c = threadIdx.x;
+  const float* p = part + (int64_t)bh * splits * (D + 4);
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, p[s * (D + 4) + D + 1]);
+  float a = 0.f, dtot = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float ms = p[s * (D + 4) + D + 1];
+    const float f = ms > -INFINITY ? __expf(ms - M) : 0.f;
+    a += p[s * (D + 4) + c] * f;
+    dtot += p[s * (D + 4) + D] * f;
+  }
+  out_o[(int64_t)bh * D + c] = a / dtot;
+  if (c == 0 && out_lse) out_lse[bh] = M + logf(dtot);
+}
+
+template <int D>
+hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* k, const void* v,
+                          const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
+                          float* out_lse, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  char* w = static_cast<char*>(ws);
+  GivenArgs A;
+  A.q = static_cast<const uint16_t*>(q);
+  A.k = static_cast<const uint16_t*>(k);
+  A.v = static_cast<const uint16_t*>(v);
+  A.Lk = pl.kv_k;
+  A.Lk.block_table = block_table;
+  A.Lv = pl.kv_v;
+  A.Lv.block_table = block_table;
+  A.head_rec = reinterpret_cast<const HeadRec*>(w + pl.off_head_rec);
+  A.idx = out_idx;
+  A.sparse = reinterpret_cast<float*>(w + pl.off_sparse);
+  A.part = reinterpret_cast<float*>(w + pl.off_gather_part);
+  A.out_o = out_o;
+  A.out_lse = out_lse;
+  A.seg_sink = pl.seg_off[0];
+  A.seg_win = pl.seg_off[1];
+  A.seg_topk = pl.seg_off[2];
+  A.seg_base = pl.seg_off[3];
+  A.seg_dyn = pl.seg_off[4];
+  A.idx_cap = (int64_t)pl.idx_cap;
+  A.Hq = p.n_q_heads;
+  A.group = pl.group;
+  A.splits = pl.gather_splits;
+  A.sm_scale = pl.sm_scale;
+  dim3 grid(A.splits, p.n_q_heads, p.batch);
+  const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
+  if (stage == 0) {
+    if (paged) hipLaunchKernelGGL((sparse_score_kernel<D, true>), grid, dim3(kGatherThreads), 0, st, A);
+    else hipLaunchKernelGGL((sparse_score_kernel<D, false>), grid, dim3(kGatherThreads), 0, st, A);
+    return hipGetLastError();
+  }
+  if (paged) hipLaunchKernelGGL((given_gather_kernel<D, true>), grid, dim3(kGatherThreads), 0, st, A);
+  else hipLaunchKernelGGL((given_gather_kernel<D, false>), grid, dim3(kGatherThreads), 0, st, A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((given_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(D), 0, st, A.part, A.splits,
+                     p.n_q_heads, out_o, out_lse);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table, void* ws,
+                               const int32_t* out_idx, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 0, q, k, nullptr, block_table, ws, out_idx, nullptr, nullptr, st);
+  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 0, q, k, nullptr, block_table, ws, out_idx, nullptr, nullptr, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
+                               const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
+                               float* out_lse, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 1, q, k, v, block_table, ws, out_idx, out_o, out_lse, st);
+  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 1, q, k, v, block_table, ws, out_idx, out_o, out_lse, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace vatt

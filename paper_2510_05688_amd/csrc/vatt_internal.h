@@ -47,7 +47,7 @@ struct Plan {
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
   // workspace offsets (bytes)
-  size_t off_scores, off_sub_max, off_head_rec, off_gather_part,
+  size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };
@@ -59,6 +59,16 @@ hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int3
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
                        hipStream_t st);
+// The path with a caller-supplied top-k set: selection phase 0 (sets, base sample) and 1 (budget, final sample),
+// scores of the listed tokens, gather with the final sample's scores computed on the way.
+hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                               const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
+                               int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st);
+hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table, void* ws,
+                               const int32_t* out_idx, hipStream_t st);
+hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
+                               const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
+                               float* out_lse, hipStream_t st);
 hipError_t launch_vstats(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
                          const int32_t* out_idx, hipStream_t st);
 hipError_t launch_gather(const Plan& pl, const void* v, const int32_t* block_table, void* ws,

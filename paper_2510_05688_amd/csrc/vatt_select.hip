@@ -55,6 +55,9 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 struct HeadArgs {
   const float* scores;
   const float* sub_max;  // [B*Hq][n_sub]: largest score of every kSubTile keys
+  const int32_t* given_idx;  // [B*Hq][k_max]: caller-supplied top-k tokens (given-top-k path)
+  const int32_t* given_cnt;  // [B*Hq]
+  const float* sparse;       // [B*Hq][idx_cap]: scores at the places of the index lists (given-top-k path)
   const int32_t* seq_lens;
   const uint64_t* seq_seeds;
   HeadRec* head_rec;
@@ -1228,6 +1231,207 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 9);
 }
 
+
+// ---------------------------------------------------------------------------
+// Selection with a caller-supplied top-k set (no score row exists).
+//   phase 0: I_t = the supplied tokens that lie in the middle region, without repeats; ascending list;
+//            sizes of Algorithm 1 from |I_t|; base sample drawn (its weights are not known yet).
+//   phase 1: with the scores of I_f and I_bs at hand (sparse list): maximum, D_f, base-sample sums, budget of
+//            Algorithm 2 for the denominator target, final sample.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int base_count_of(int n_s, const SelectParams& p) {
+  int b0 = p.base_abs > 0 ? p.base_abs : (int)floor(p.base_frac * (double)n_s);
+  b0 = b0 < 2 ? 2 : b0;
+  return b0 > n_s ? n_s : b0;
+}
+
+template <int NT>
+__global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
+  using O = HeadOps<NT>;
+  using HeadSmem = typename O::HeadSmem;
+  using Sampler = typename O::Sampler;
+  constexpr int SW = NT / kWave;
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  __shared__ float s_wf[16];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int bh = b * A.Hq + h;
+  const int tid = threadIdx.x;
+  const int n = min(max(A.seq_lens[b], 1), A.n_max);
+  HeadSizes hs = head_sizes(n, A.sp);
+  const int words_max = ((A.n_max + 63) >> 6) << 1;
+  const int words = (n + 31) >> 5;
+  HeadSmem& sm = *reinterpret_cast<HeadSmem*>(dyn_smem);
+  uint64_t* cand = reinterpret_cast<uint64_t*>(dyn_smem + ((sizeof(HeadSmem) + 15) & ~size_t(15)));
+  uint32_t* bm_f = reinterpret_cast<uint32_t*>(cand + kCandCap) + kCandCap;
+  uint32_t* taken = bm_f + words_max;
+  uint32_t* scratch = taken + 2 * words_max;
+  uint32_t* wpre = scratch + words_max;
+  uint32_t* mail = wpre + words_max;
+  int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
+  const int mid_len = hs.mid_hi - hs.mid_lo;
+
+  for (int w = tid; w < words; w += NT) {
+    bm_f[w] = 0;
+    taken[w] = 0;
+    scratch[w] = 0;
+    mail[w] = kInv32;
+  }
+  __syncthreads();
+  if (A.phase == 0) {
+    const int cnt = min(max(A.given_cnt[bh], 0), A.k_max);
+    const int32_t* given = A.given_idx + (int64_t)bh * A.k_max;
+    for (int t = tid; t < cnt; t += NT) {
+      const int i = given[t];
+      if (i >= hs.mid_lo && i < hs.mid_hi) O::mark_bit(bm_f, (uint32_t)i);
+    }
+  } else {
+    const HeadRec r = A.head_rec[bh];
+    for (int t = tid; t < r.k; t += NT) O::mark_bit(bm_f, (uint32_t)O::list_tok(idx, A.seg_topk + t, n));
+  }
+  __syncthreads();
+  const int k_eff = (int)O::word_prefix(bm_f, words, wpre, sm);
+  hs.k = k_eff;
+  hs.n_s = mid_len - k_eff;
+  hs.b0 = hs.n_s > 0 ? base_count_of(hs.n_s, A.sp) : 0;
+
+  Sampler S;
+  S.taken = taken;
+  S.scratch = scratch;
+  S.mail = mail;
+  S.bm_f = bm_f;
+  S.wpre = wpre;
+  S.row = nullptr;
+  S.seed = A.seq_seeds[b];
+  S.stream = A.phase == 0 ? 0u : 1u;
+  S.head = (uint32_t)h;
+  S.L = (uint32_t)max(mid_len, 1);
+  S.thr = (uint32_t)((0x100000000ull - (uint64_t)S.L) % (uint64_t)S.L);
+  {
+    const uint64_t dflt = 64ull * (uint64_t)S.L + 4096ull;
+    S.cap = (uint32_t)min(A.draw_cap ? (uint64_t)A.draw_cap : dflt, 0x80000000ull);
+  }
+  S.m = 0.f;
+  S.dbg = nullptr;
+  const DrawBatch none = {};
+
+  if (A.phase == 0) {
+    {
+      const int wpt = (words + NT - 1) / NT;
+      const int w0 = tid * wpt;
+      for (int w = w0; w < min(w0 + wpt, words); ++w) {
+        uint32_t bits = bm_f[w];
+        uint32_t pos = wpre[w];
+        while (bits) {
+          const int i = (w << 5) + (__ffs(bits) - 1);
+          bits &= bits - 1u;
+          if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+          ++pos;
+        }
+      }
+    }
+    for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
+    for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
+    __syncthreads();
+    int flags = 0;
+    if (hs.n_s > 0) {
+      const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches, idx + A.seg_base,
+                                   (uint32_t)A.b0_max, nullptr, nullptr, sm);
+      flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+    }
+    if (tid == 0) {
+      HeadRec r;
+      r.m = 0.f;
+      r.scale = 0.f;
+      r.n = n;
+      r.n_sink = hs.n_sink;
+      r.n_win = hs.n_win;
+      r.k = k_eff;
+      r.b = hs.b0;  // the score pass walks the base sample
+      r.n_s = hs.n_s;
+      A.head_rec[bh] = r;
+      A.out_counts[(int64_t)bh * 8 + 7] = flags;
+    }
+    return;
+  }
+
+  // ---- phase 1 ----
+  const float* sp = A.sparse + (int64_t)bh * A.idx_cap;
+  float v_max = -INFINITY;
+  for (int i = tid; i < hs.n_sink; i += NT) v_max = fmaxf(v_max, sp[A.seg_sink + i]);
+  for (int i = tid; i < hs.n_win; i += NT) v_max = fmaxf(v_max, sp[A.seg_win + i]);
+  for (int i = tid; i < k_eff; i += NT) v_max = fmaxf(v_max, sp[A.seg_topk + i]);
+  for (int i = tid; i < hs.b0; i += NT) v_max = fmaxf(v_max, sp[A.seg_base + i]);
+  v_max = wave_max(v_max);
+  if ((tid & 63) == 0) s_wf[tid >> 6] = v_max;
+  __syncthreads();
+  float m = s_wf[0];
+#pragma unroll
+  for (int w = 1; w < SW; ++w) m = fmaxf(m, s_wf[w]);
+  double acc_f = 0.0, acc_w = 0.0, acc_w2 = 0.0;
+  for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(sp[A.seg_sink + i] - m);
+  for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(sp[A.seg_win + i] - m);
+  for (int i = tid; i < k_eff; i += NT) acc_f += (double)__expf(sp[A.seg_topk + i] - m);
+  for (int i = tid; i < hs.b0; i += NT) {
+    const double w = (double)__expf(sp[A.seg_base + i] - m);
+    acc_w += w;
+    acc_w2 += w * w;
+  }
+  double sums[3] = {acc_f, acc_w, acc_w2};
+  O::block_sum(sums, sm);
+  const double D_f = sums[0];
+  double sigma2 = 0.0, b_star = 0.0, D_hat = D_f;
+  int bfin = 0;
+  if (hs.n_s > 0) {
+    const double b0d = (double)hs.b0, ns = (double)hs.n_s;
+    const double w_bar = sums[1] / b0d;
+    sigma2 = hs.b0 > 1 ? fmax(sums[2] - sums[1] * w_bar, 0.0) / (b0d - 1.0) : 0.0;
+    D_hat = D_f + ns * w_bar;
+    const double rho_D = ns * sqrt(sigma2) / D_hat;
+    const double t = A.z_half * rho_D / A.eps;
+    b_star = t * t;
+    const int cap = (int)ceil(A.cap_frac * ns);
+    int want = hs.n_s;
+    if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
+    bfin = min(hs.n_s, max(hs.b0, min(want, cap)));
+    bfin = min(bfin, A.b_max);
+  }
+  int flags = 0;
+  if (bfin > 0) {
+    const int f = O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches, idx + A.seg_dyn,
+                                 (uint32_t)A.b_max, nullptr, nullptr, sm);
+    flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+  }
+  if (tid == 0) {
+    int32_t* c = A.out_counts + (int64_t)bh * 8;
+    c[0] = hs.n_sink;
+    c[1] = hs.n_win;
+    c[2] = k_eff;
+    c[3] = hs.b0;
+    c[4] = bfin;
+    c[5] = hs.n_s;
+    c[6] = n;
+    c[7] = c[7] | flags;
+    if (A.out_budget_raw) A.out_budget_raw[bh] = b_star;
+    if (A.out_stats) {
+      float* st = A.out_stats + (int64_t)bh * 4;
+      st[0] = (float)D_hat;
+      st[1] = (float)sigma2;
+      st[2] = st[3] = 0.f;
+      // (in units of exp(-m) with m the largest score among I_f and I_bs, which is HeadRec.m and out_lse's shift)
+    }
+    HeadRec r;
+    r.m = m;
+    r.scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
+    r.n = n;
+    r.n_sink = hs.n_sink;
+    r.n_win = hs.n_win;
+    r.k = k_eff;
+    r.b = bfin;
+    r.n_s = hs.n_s;
+    A.head_rec[bh] = r;
+  }
+}
+
 typedef void (*HeadKernel)(HeadArgs);
 // The instantiation for a plan: (workgroup size, scores per thread kept in registers).
 HeadKernel head_kernel_for(const Plan& pl) {
@@ -1238,7 +1442,10 @@ HeadKernel head_kernel_for(const Plan& pl) {
 }  // namespace
 
 hipError_t set_kernel_attributes(const Plan& pl) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(head_kernel_for(pl)),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_kernel_for(pl)),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
 }
 
@@ -1251,12 +1458,37 @@ size_t head_kernel_lds_bytes(int n_max, int head_threads) {
 
 size_t head_kernel_static_lds_bytes() { return sizeof(TopkSmem) + 64; }
 
+static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                           void* ws, int32_t* out_idx, int32_t* out_counts, double* out_budget_raw,
+                           float* out_stats);
+
+hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                               const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
+                               int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st) {
+  HeadArgs A;
+  fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
+  A.given_idx = given_idx;
+  A.given_cnt = given_cnt;
+  hipLaunchKernelGGL(given_topk_kernel<kHeadThreads>, dim3(pl.p.n_q_heads, pl.p.batch), dim3(kHeadThreads),
+                     pl.head_lds_bytes, st, A);
+  return hipGetLastError();
+}
+
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
                        hipStream_t st) {
+  HeadArgs A;
+  fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
+  const vatt_params& p = pl.p;
+  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, p.batch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
+  return hipGetLastError();
+}
+
+static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                           void* ws, int32_t* out_idx, int32_t* out_counts, double* out_budget_raw,
+                           float* out_stats) {
   const vatt_params& p = pl.p;
   char* w = static_cast<char*>(ws);
-  HeadArgs A;
   A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
   A.sub_max = reinterpret_cast<const float*>(w + pl.off_sub_max);
   A.n_sub = pl.n_sub;
@@ -1293,8 +1525,9 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   A.b0_max = pl.b0_max;
   A.b_max = pl.b_max;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
-  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, p.batch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
-  return hipGetLastError();
+  A.given_idx = nullptr;
+  A.given_cnt = nullptr;
+  A.sparse = reinterpret_cast<const float*>(w + pl.off_sparse);
 }
 
 }  // namespace vatt

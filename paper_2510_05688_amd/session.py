@@ -85,6 +85,13 @@ class DecodeSession:
                        self.workspace, self.out_o, self.out_lse, self.out_idx, self.out_counts,
                        self.out_budget_raw, self.out_stats, self._stream())
 
+    def decode_given_topk(self, topk_idx, topk_cnt, k=None, v=None):
+        """vatt_decode_given_topk with int32 device tensors topk_idx [B, Hq, k_max], topk_cnt [B, Hq]."""
+        vb.vatt_decode_given_topk(self.plan, self.q, self.k if k is None else k, self.v if v is None else v,
+                                  self.block_table, self.seq_lens, self.seq_seeds, topk_idx, topk_cnt,
+                                  self.workspace, self.out_o, self.out_lse, self.out_idx, self.out_counts,
+                                  self.out_budget_raw, self.out_stats, self._stream())
+
     def dense(self, q=None, k=None, v=None):
         vb.vatt_dense_decode(self.plan, self.q if q is None else q, self.k if k is None else k,
                              self.v if v is None else v, self.block_table, self.seq_lens, self.workspace,
