@@ -151,6 +151,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
     ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--given-topk", action="store_true",
+                    help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
+                         "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -181,6 +184,16 @@ def main():
 
     def step(i):
         sess.decode(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    if args.given_topk:
+        from paper_2510_05688_amd import binding as vb
+        sess.decode()
+        seg2, seg3 = vb.vatt_plan_index_segment(sess.plan, 2), vb.vatt_plan_index_segment(sess.plan, 3)
+        topk_idx = sess.out_idx[:, :, seg2:seg3].contiguous()
+        topk_cnt = sess.out_counts[:, :, 2].contiguous()
+
+        def step(i):  # noqa: F811
+            sess.decode_given_topk(topk_idx, topk_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
 
     def score_only(i):
         sess.score(k=ks[i % nbuf])
@@ -232,12 +245,16 @@ def main():
     select_r = 2 * submax_w + int(((counts[:, 2] + 2 * counts[:, 3] + b_dyn) * 32).sum())
     gather_r = int(((n_f + b_dyn) * 8).sum())
     path_bytes = k_scan + score_w + submax_w + select_r + gather_r + v_rows
+    if args.given_topk:
+        # K rows of I_f, I_bs and I_dyn (no scan), V rows of I_f and I_dyn, the sparse scores and index lists
+        k_rows = int(((n_f + counts[:, 3] + b_dyn) * d * 2).sum())
+        path_bytes = k_rows + v_rows + int(((n_f + counts[:, 3] + b_dyn) * 12).sum())
     score_kernel_bytes = k_scan + score_w + submax_w + B * Hq * d * 2
     dense_bytes = 2 * k_scan
 
     us_layer = ms_step * 1e3
     out = {
-        "metric": "vattention_decode_us_per_layer",
+        "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else ""),
         "value": us_layer,
         "unit": "us",
         "n_gpus": 1,

@@ -241,8 +241,10 @@ __global__ __launch_bounds__(D) void given_merge_kernel(const float* __restrict_
   const int c = threadIdx.x;
   const float* p = part + (int64_t)bh * splits * (D + 4);
   float M = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < splits; ++s) M = fmaxf(M, p[s * (D + 4) + D + 1]);
   float a = 0.f, dtot = 0.f;
+#pragma unroll 8
   for (int s = 0; s < splits; ++s) {
     const float ms = p[s * (D + 4) + D + 1];
     const float f = ms > -INFINITY ? __expf(ms - M) : 0.f;
