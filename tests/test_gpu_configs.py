@@ -93,6 +93,21 @@ def test_config4_long_context():
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.timeout(600)
+def test_config4_general_topk_path_on_long_rows():
+    say("config 4 shape (n=131072), B=1, top-k by the general path (whole row streamed)")
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.config4(batch=1)
+    sess = _session(wl)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 1)
+    sess.decode()
+    res = sess.results_host()
+    assert np.all(res["counts"][..., 7] & 32 == 32)
+    _properties(wl, res)
+    check_all(wl, res, heads=[(0, 0), (0, 5), (0, 18), (0, 31)], label="config4-general")
+    sess.close()
+
+
 def test_config5_ragged_paged_decode_loop():
     say("config 5 (ragged, paged, append loop; B=8 here, 6 steps)")
     from paper_2510_05688_amd.session import DecodeSession

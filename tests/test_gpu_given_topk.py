@@ -137,6 +137,19 @@ def test_given_topk_config2_sampled_heads():
     sess.close()
 
 
+@pytest.mark.parametrize("d,hq,hkv", [(64, 8, 1), (64, 4, 4), (128, 16, 2)])
+def test_given_topk_other_head_shapes(d, hq, hkv):
+    say("given top-k, d=%d, %d/%d heads" % (d, hq, hkv))
+    wl = workloads.small_gqa(seed=45, batch=2, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n=2100, seq_lens=[2100, 517])
+    sess = _session(wl)
+    rng = np.random.default_rng(5)
+    supplied = {(b, h): _oracle_topk(wl, b, h, noise=0.2, rng=rng) for b in range(wl.batch) for h in range(hq)}
+    res = _run_given(sess, wl, supplied)
+    for (b, h), arr in supplied.items():
+        check_head_given(wl, res, b, h, arr, label="shapes")
+    sess.close()
+
+
 def test_given_topk_rejects_other_targets():
     from paper_2510_05688_amd.binding import VattError
     wl = workloads.small_gqa(seed=44, batch=1, n=1500, target=2)

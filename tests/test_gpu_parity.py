@@ -205,6 +205,24 @@ def test_topk_general_path_gives_identical_results():
         sess.close()
 
 
+def test_large_topk_sets_leave_the_shortcut():
+    say("top-k sets too large for the shortcut: more members than whole sub-tiles, more candidates than the list holds")
+    # k = 4000 of 20000: fewer whole 8-key sub-tiles (2495) than members -> general path from the start
+    wl = workloads.small_gqa(seed=34, batch=1, n_q_heads=4, n_kv_heads=2, n=20000, topk_frac=0.2)
+    sess = _session(wl)
+    res = _run(sess)
+    assert np.all(res["counts"][..., 7] & 32 == 32)
+    check_all(wl, res, label="k > sub-tiles")
+    sess.close()
+    # k = 3900 of 39000: the bound leaves more than 4096 candidates -> general path after the candidate pass
+    wl = workloads.small_gqa(seed=35, batch=1, n_q_heads=4, n_kv_heads=2, n=39000, topk_frac=0.1)
+    sess = _session(wl)
+    res = _run(sess)
+    assert np.all(res["counts"][..., 7] & 32 == 32)
+    check_all(wl, res, label="candidates > list")
+    sess.close()
+
+
 def test_topk_with_runs_of_equal_scores():
     say("many equal scores around the top-k threshold")
     # keys repeated in blocks: scores come in runs of equal values, so ties at the threshold go by token order
