@@ -1289,7 +1289,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     for (int t = tid; t < r.k; t += NT) O::mark_bit(bm_f, (uint32_t)O::list_tok(idx, A.seg_topk + t, n));
   }
   __syncthreads();
-  const int k_eff = (int)O::word_prefix(bm_f, words, wpre, sm);
+  const int k_eff = A.phase == 0 ? (int)O::word_prefix(bm_f, words, wpre, sm) : A.head_rec[bh].k;
   hs.k = k_eff;
   hs.n_s = mid_len - k_eff;
   hs.b0 = hs.n_s > 0 ? base_count_of(hs.n_s, A.sp) : 0;
@@ -1355,12 +1355,29 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   }
 
   // ---- phase 1 ----
+  // scores of [sink | window | top-k | base sample], a few per thread, requested together
   const float* sp = A.sparse + (int64_t)bh * A.idx_cap;
+  const int n_fix = hs.n_sink + hs.n_win + k_eff, n_all = n_fix + hs.b0;
+  auto place_of = [&](int p) -> int64_t {
+    if (p < hs.n_sink) return A.seg_sink + p;
+    p -= hs.n_sink;
+    if (p < hs.n_win) return A.seg_win + p;
+    p -= hs.n_win;
+    if (p < k_eff) return A.seg_topk + p;
+    return A.seg_base + (p - k_eff);
+  };
+  constexpr int U = 4;
   float v_max = -INFINITY;
-  for (int i = tid; i < hs.n_sink; i += NT) v_max = fmaxf(v_max, sp[A.seg_sink + i]);
-  for (int i = tid; i < hs.n_win; i += NT) v_max = fmaxf(v_max, sp[A.seg_win + i]);
-  for (int i = tid; i < k_eff; i += NT) v_max = fmaxf(v_max, sp[A.seg_topk + i]);
-  for (int i = tid; i < hs.b0; i += NT) v_max = fmaxf(v_max, sp[A.seg_base + i]);
+  for (int base = 0; base < n_all; base += NT * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = base + u * NT + tid;
+      v[u] = p < n_all ? sp[place_of(p)] : -INFINITY;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) v_max = fmaxf(v_max, v[u]);
+  }
   v_max = wave_max(v_max);
   if ((tid & 63) == 0) s_wf[tid >> 6] = v_max;
   __syncthreads();
@@ -1368,13 +1385,24 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
 #pragma unroll
   for (int w = 1; w < SW; ++w) m = fmaxf(m, s_wf[w]);
   double acc_f = 0.0, acc_w = 0.0, acc_w2 = 0.0;
-  for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(sp[A.seg_sink + i] - m);
-  for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(sp[A.seg_win + i] - m);
-  for (int i = tid; i < k_eff; i += NT) acc_f += (double)__expf(sp[A.seg_topk + i] - m);
-  for (int i = tid; i < hs.b0; i += NT) {
-    const double w = (double)__expf(sp[A.seg_base + i] - m);
-    acc_w += w;
-    acc_w2 += w * w;
+  for (int base = 0; base < n_all; base += NT * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = base + u * NT + tid;
+      v[u] = p < n_all ? sp[place_of(p)] : -INFINITY;  // (a second read of the same few values: cache hits)
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = base + u * NT + tid;
+      const double w = (double)__expf(v[u] - m);  // 0 for the slots beyond the list
+      if (p < n_fix) {
+        acc_f += w;
+      } else {
+        acc_w += w;
+        acc_w2 += w * w;
+      }
+    }
   }
   double sums[3] = {acc_f, acc_w, acc_w2};
   O::block_sum(sums, sm);
