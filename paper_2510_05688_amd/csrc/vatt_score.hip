@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     const int i = tile_lo + t;
     if (i < n) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i] = s_tile[g][t];
+      for (int g = 0; g < G; ++g)
+        __builtin_nontemporal_store(s_tile[g][t], &scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i]);
     }
   }
   // Largest score of every 8 consecutive keys per query head: the selection kernel takes its head maximum

@@ -511,7 +511,7 @@ struct RowView {
 };
 
 // The candidates for the top-k set as a list of composites in LDS: the same interface as RowView.
-constexpr int kCandCap = 4096;
+constexpr int kCandCap = 2048;
 template <int NT>
 struct CandView {
   const uint64_t* list;
