@@ -289,6 +289,37 @@ def test_draw_cap_completes_samples_in_index_order():
     sess2.close()
 
 
+def test_decode_inside_a_hip_graph():
+    say("vatt_decode captured in a HIP graph and replayed")
+    import torch
+    wl = workloads.small_gqa(seed=51, batch=2, n=6000)
+    sess = _session(wl)
+    eager = _run(sess)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            sess.decode()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        sess.out_o.zero_()
+        sess.out_idx.zero_()
+        sess.dense()                      # other work of the program between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        again = sess.results_host()
+        for key in ("O", "lse", "counts", "b_star", "stats"):
+            assert np.array_equal(eager[key], again[key]), key
+        for b in range(wl.batch):
+            for h in range(wl.n_q_heads):
+                ge, ga = gpu_segments(eager, b, h), gpu_segments(again, b, h)
+                for key in ("I_s", "I_l", "I_t", "I_bs", "I_dyn"):
+                    assert np.array_equal(ge[key], ga[key]), (b, h, key)
+    sess.close()
+
+
 # ---------------------------------------------------- dense, and check (a) ----
 def test_dense_decode_matches_eq1():
     say("dense decode")
