@@ -797,31 +797,51 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   DrawBatch spec0 = {}, spec1 = {};
   const bool want0 = hs.n_s > 0 && A.phase != 2 && hs.b0 < hs.n_s;
   const bool want1 = hs.n_s > 0 && A.phase != 1;
-  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm);
-  if (want1) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
-  VATT_STAMP(A.dbg, 1);
-
-  // ---- the head maximum m, from the sub-tile maxima the score kernel left ----
+  // The sub-tile maxima the score kernel left are requested before the sampler work: rows of up to 8 * NT
+  // sub-tiles keep them in registers for the three passes below, longer rows stream them in every pass.
+  constexpr int SU = 8;  // sub-tile maxima a thread has in flight
   const int n_sub = (n + kSubTile - 1) / kSubTile;
   const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
   const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;  // whole middle sub-tiles
+  const bool sub_resident = n_sub <= SU * NT;
+  float sub_reg[SU];
+#pragma unroll
+  for (int u = 0; u < SU; ++u) {
+    const int t = u * NT + tid;
+    sub_reg[u] = (sub_resident && t < n_sub) ? sub_max[t] : -INFINITY;
+  }
+  // g(maxima[SU], first sub-tile of the batch): slot u is sub-tile first + u * NT + tid, -inf beyond the row
+  auto each_sub_batch = [&](auto&& g) {
+    if (sub_resident) {
+      g(sub_reg, 0);
+    } else {
+      for (int base = 0; base < n_sub; base += NT * SU) {
+        float v[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+          const int t = base + u * NT + tid;
+          v[u] = t < n_sub ? sub_max[t] : -INFINITY;
+        }
+        g(v, base);
+      }
+    }
+  };
+  bool spec1_made = false;
+  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm);
+  VATT_STAMP(A.dbg, 1);
+
+  // ---- the head maximum m ----
   float m, lo_sub;  // lo_sub: the smallest maximum of a whole middle sub-tile
   {
     float v_max = -INFINITY, v_min = INFINITY;
-    for (int base = 0; base < n_sub; base += NT * 8) {
-      float v[8];
+    each_sub_batch([&](const float (&v)[SU], int base) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int t = base + u * NT + tid;
-        v[u] = t < n_sub ? sub_max[t] : -INFINITY;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < SU; ++u) {
         const int t = base + u * NT + tid;
         v_max = fmaxf(v_max, v[u]);
         v_min = (t >= sub_lo && t < sub_hi) ? fminf(v_min, v[u]) : v_min;
       }
-    }
+    });
     v_max = wave_max(v_max);
     v_min = -wave_max(-v_min);
     if ((tid & 63) == 0) {
@@ -858,24 +878,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         // selected among exactly.
         bool have_T = false;
         if (sub_hi - sub_lo >= hs.k && !A.topk_general) {
-          constexpr int U = 8;  // sub-tile maxima a thread has in flight
           float bound = lo_sub;  // every middle sub-tile maximum is at or above this
           const float scale = (float)(kBins - 1) / (m - lo_sub);
           if (m > lo_sub && scale < 1e30f) {
             TKR::zero_hist(ts);
-            for (int base = sub_lo; base < sub_hi; base += NT * U) {
-              float v[U];
+            each_sub_batch([&](const float (&v)[SU], int base) {
 #pragma unroll
-              for (int u = 0; u < U; ++u) {
+              for (int u = 0; u < SU; ++u) {
                 const int t = base + u * NT + tid;
-                v[u] = t < sub_hi ? sub_max[t] : NAN;
-              }
-#pragma unroll
-              for (int u = 0; u < U; ++u) {
-                const bool in = base + u * NT + tid < sub_hi;
+                const bool in = t >= sub_lo && t < sub_hi;
                 atomicAdd(&ts.hist[in ? (uint32_t)((m - v[u]) * scale) : (uint32_t)kBins], 1u);
               }
-            }
+            });
             __syncthreads();
             TKR::locate((uint32_t)hs.k, ts, sm);
             // the lower edge of the bin of the k-th largest maximum, a little further down for rounding
@@ -890,16 +904,13 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
           }
           __syncthreads();
           const int sub_first = hs.mid_lo / kSubTile, sub_last = (hs.mid_hi + kSubTile - 1) / kSubTile;
-          for (int base = sub_first; base < sub_last; base += NT * U) {
-            float v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-              const int t = base + u * NT + tid;
-              v[u] = t < sub_last ? sub_max[t] : -INFINITY;
-            }
+          each_sub_batch([&](const float (&v)[SU], int base) {
             uint32_t hit = 0;
 #pragma unroll
-            for (int u = 0; u < U; ++u) hit |= (v[u] >= bound ? 1u : 0u) << u;
+            for (int u = 0; u < SU; ++u) {
+              const int t = base + u * NT + tid;
+              hit |= ((t >= sub_first && t < sub_last && v[u] >= bound) ? 1u : 0u) << u;
+            }
             const uint32_t mine = (uint32_t)__popc(hit);
             const uint32_t incl = wave_inclusive_scan_u32(mine);
             const uint32_t wave_tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -909,14 +920,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
               at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
               uint32_t pos = at + incl - mine;
 #pragma unroll
-              for (int u = 0; u < U; ++u) {
+              for (int u = 0; u < SU; ++u) {
                 if ((hit >> u) & 1u) {
                   if (pos < (uint32_t)kCandCap) qual[pos] = (uint32_t)(base + u * NT + tid);
                   ++pos;
                 }
               }
             }
-          }
+          });
           __syncthreads();
           const uint32_t n_qual = ts.qual_n;
           VATT_STAMP(A.dbg, 23);
@@ -938,6 +949,11 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
                 const float4 y = ok ? src[1] : make_float4(0.f, 0.f, 0.f, 0.f);
                 sv[u][0] = x.x; sv[u][1] = x.y; sv[u][2] = x.z; sv[u][3] = x.w;
                 sv[u][4] = y.x; sv[u][5] = y.y; sv[u][6] = y.z; sv[u][7] = y.w;
+              }
+              if (q0 == 0 && want1) {
+                // the final sample's first batch of draws is generated while these loads are in flight
+                O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
+                spec1_made = true;
               }
               uint32_t hit = 0;
 #pragma unroll
@@ -1092,6 +1108,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
   }
   __syncthreads();
+
+  if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
 
   // ---- I_bs (Algorithm 2, line 1) and the sums over it ----
   int flags = topk_flag;
