@@ -2,11 +2,14 @@
 // in one kernel with one workgroup per head.
 //
 // Top-k: the k largest scores of the middle region, ties to the lower token, i.e. the k smallest composites
-// (~order_key(score), token).  The head's score row stays in registers (or is streamed from the L2 cache when it
-// is too long); a histogram over 2048 equal-width score bins in LDS finds the bin that holds the k-th largest
-// score, the few scores of that bin are ranked exactly, and every token at or above the resulting threshold
-// is marked in an LDS bitmap.  Rows with very many scores in one bin are refined by further histograms over
-// the integer keys, and runs of equal scores by token order, so the result is exact for any data.
+// (~order_key(score), token).  Usual path: the score kernel leaves the largest score of every 8 keys; the k-th
+// largest of those maxima is a lower bound of the k-th largest score (located to one bin of a 2048-bin LDS
+// histogram), the 8-key sub-tiles that reach it are listed, their scores loaded, and the scores at or above the
+// bound are the candidates, a few more than k.  The exact threshold among them: histogram over 2048
+// equal-width score bins, the bin that holds rank k located by a workgroup scan, its few scores ranked as
+// composites.  General path (short rows, very large k, long runs of equal scores): the same histogram selection
+// streamed over the whole row, refined by further histograms over the integer keys when a bin holds many
+// scores, and by token order inside a run of equal scores, so the result is exact for any data.
 //
 // Samples: sequential uniform draws from the middle region (Philox4x32-10 words, unbiased multiply-and-reject
 // mapping), skipping top-k members and tokens drawn before; the first c accepted tokens are the sample (for
@@ -14,7 +17,8 @@
 // a batch are generated at once, repeated tokens are resolved to their earliest draw, and a prefix count in
 // draw order finds where the sample is complete; the result equals the sequential procedure bit for bit.
 //
-// Floating-point sums are taken in a fixed order, so the statistics and the budget are reproducible too.
+// Floating-point sums are taken in a fixed order, or as fixed-point integers where the order depends on
+// scheduling, so the statistics and the budget are reproducible too.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -402,36 +406,24 @@ struct HeadOps {
 };  // struct HeadOps
 
 // ---------------------------------------------------------------------------
-// The head's score row as the threads of the workgroup see it: thread t owns tokens t, t + NT, t + 2 NT, ...
-// EE > 0: the first EE * NT scores are loaded once and stay in registers.  EE == 0: every pass streams the
-// row again from global memory (it stays in the L2 cache), kTile scores per thread at a time.
+// The head's score row as the threads of the workgroup see it (general top-k path): thread t owns tokens
+// t, t + NT, t + 2 NT, ...; every pass streams the row from global memory (it stays in the L2 cache), kTile
+// scores per thread at a time.
 //
 // A pass visits the row in groups of kGroup scores per thread (kGroup * NT consecutive tokens per workgroup).
 // Groups beyond the sequence are skipped; a group that lies entirely in the middle region is handed over with
-// the tag std::true_type, so that the pass spends no instructions on the region test there.  The bodies are
-// free of per-score branches: the compiler interleaves the work of neighbouring scores only then.
+// the tag InsideTag, so that the pass spends no instructions on the region test there.  The bodies are free of
+// per-score branches: the compiler interleaves the work of neighbouring scores only then.
 // ---------------------------------------------------------------------------
 struct InsideTag { static constexpr bool value = true; };
 struct EdgeTag { static constexpr bool value = false; };
 
-template <int NT, int EE>
+template <int NT>
 struct RowView {
-  static constexpr bool kResident = EE > 0;
   static constexpr int kTile = 16;
   static constexpr int kGroup = 8;
-  static_assert(!kResident || EE % kGroup == 0, "whole groups");
-  float sc[kResident ? EE : 1];
   const float* row;
   int n;
-
-  __device__ __forceinline__ void load(const float* r, int n_valid) {
-    row = r;
-    n = n_valid;
-    if constexpr (kResident) {
-#pragma unroll
-      for (int e = 0; e < EE; ++e) sc[e] = row[e * NT + (int)threadIdx.x];  // the workspace is padded for this
-    }
-  }
 
   template <class G>
   __device__ __forceinline__ void dispatch(const HeadSizes& hs, const float (&s)[kGroup], int g_lo, int t0, G&& g) {
@@ -440,40 +432,20 @@ struct RowView {
   }
 
   // g(scores[kGroup], token of scores[0], tag): slot u of the group is token i0 + u * NT; under EdgeTag a slot
-  // may lie outside the middle region or at or beyond n (it then carries an arbitrary value).
+  // may lie outside the middle region or at or beyond n (it then carries a copy of the last score).
   template <class G>
   __device__ __forceinline__ void for_each_group(const HeadSizes& hs, G&& g) {
-    if constexpr (kResident) {
-      // (the empty asm makes the compiler treat the registers and the thread index as new values in every
-      // pass: otherwise it keeps per-score intermediates of one pass alive for the next and runs out of
-      // registers)
+    for (int base = 0; base < n; base += NT * kTile) {
+      float v[kTile];
 #pragma unroll
-      for (int e = 0; e < EE; ++e) asm volatile("" : "+v"(sc[e]));
-      int t0 = (int)threadIdx.x;
-      asm volatile("" : "+v"(t0));
+      for (int u = 0; u < kTile; ++u) v[u] = row[min(base + u * NT + (int)threadIdx.x, n - 1)];
 #pragma unroll
-      for (int e = 0; e < EE; e += kGroup) {
-        if (e * NT < n) {
+      for (int q = 0; q < kTile; q += kGroup) {
+        if (base + q * NT < n) {
           float s[kGroup];
 #pragma unroll
-          for (int u = 0; u < kGroup; ++u) s[u] = sc[e + u];
-          dispatch(hs, s, e * NT, t0, g);
-        }
-        __builtin_amdgcn_sched_barrier(0);  // keeps the live intermediates to one group
-      }
-    } else {
-      for (int base = 0; base < n; base += NT * kTile) {
-        float v[kTile];
-#pragma unroll
-        for (int u = 0; u < kTile; ++u) v[u] = row[min(base + u * NT + (int)threadIdx.x, n - 1)];
-#pragma unroll
-        for (int q = 0; q < kTile; q += kGroup) {
-          if (base + q * NT < n) {
-            float s[kGroup];
-#pragma unroll
-            for (int u = 0; u < kGroup; ++u) s[u] = v[q + u];
-            dispatch(hs, s, base + q * NT, (int)threadIdx.x, g);
-          }
+          for (int u = 0; u < kGroup; ++u) s[u] = v[q + u];
+          dispatch(hs, s, base + q * NT, (int)threadIdx.x, g);
         }
       }
     }
@@ -719,12 +691,11 @@ __device__ __forceinline__ int ahead_blocks(int small_batches) {
   return small_batches ? kSmallBatchBlocks : min(NT, 256);
 }
 
-// NT = workgroup size; EE = scores a thread keeps in registers (the row has at most EE * NT scores), or 0 when
-// the row is streamed from global memory in every pass.
-template <int NT, int EE>
+// NT = workgroup size.
+template <int NT>
 __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   using O = HeadOps<NT>;
-  using TKR = TopkOps<NT, RowView<NT, EE>>;
+  using TKR = TopkOps<NT, RowView<NT>>;
   using TKC = TopkOps<NT, CandView<NT>>;
   using HeadSmem = typename O::HeadSmem;
   using Sampler = typename O::Sampler;
@@ -756,8 +727,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 0);
   // The score row is requested first (when it is kept in registers), so that its latency overlaps the
   // sampler work below.
-  RowView<NT, EE> rv;
-  rv.load(row, n);
+  RowView<NT> rv;
+  rv.row = row;
+  rv.n = n;
   const float edge0 = (A.phase != 2 && tid < hs.n_sink) ? row[tid] : -INFINITY;
   const float edge1 = (A.phase != 2 && tid < hs.n_win) ? row[hs.mid_hi + tid] : -INFINITY;
   for (int w = tid; w < words; w += NT) {
@@ -1057,8 +1029,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         // score is rare and sends its group through the full comparison.  The weights of the members are
         // added on the way.
         uint64_t* bm64 = reinterpret_cast<uint64_t*>(bm_f);
-        rv.for_each_group(hs, [&](const float (&s)[RowView<NT, EE>::kGroup], int i0, auto tag) {
-          constexpr int G = RowView<NT, EE>::kGroup;
+        rv.for_each_group(hs, [&](const float (&s)[RowView<NT>::kGroup], int i0, auto tag) {
+          constexpr int G = RowView<NT>::kGroup;
           constexpr bool kInside = decltype(tag)::value;
           const int first0 = i0 - (tid & 63);  // token of lane 0 in slot 0: a multiple of 64
 #pragma unroll
@@ -1482,7 +1454,7 @@ typedef void (*HeadKernel)(HeadArgs);
 // The instantiation for a plan: (workgroup size, scores per thread kept in registers).
 HeadKernel head_kernel_for(const Plan& pl) {
   (void)pl;
-  return head_kernel<kHeadThreads, 0>;
+  return head_kernel<kHeadThreads>;
 }
 
 }  // namespace
