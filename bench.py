@@ -126,8 +126,8 @@ def decode_loop(args, torch, np, workloads, DecodeSession):
     out = {
         "metric": "vattention_decode_us_per_layer", "value": ms_step * 1e3, "unit": "us", "n_gpus": 1,
         "steps": steps, "warmup": warm, "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 K/V, fp32 accumulate", "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "accumulate": "fp32", "batch": wl.batch, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
                    "head_dim": wl.head_dim, "n_start": "U[1024, 32768] per sequence", "page_size": 16,
                    "epsilon": float(wl.params["epsilon"]), "delta": float(wl.params["delta"]),
                    "step": "vatt_append_kv + vatt_decode"},
@@ -264,9 +264,9 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 K/V, fp32 accumulate",
+        "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n": n,
+        "config": {"workload": wl.name, "accumulate": "fp32", "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "n": n,
                    "sink": int(wl.params["sink"]), "window": int(wl.params["window"]),
                    "topk_frac": float(wl.params["topk_frac"]), "base_frac": float(wl.params["base_frac"]),
                    "epsilon": float(wl.params["epsilon"]), "delta": float(wl.params["delta"]),

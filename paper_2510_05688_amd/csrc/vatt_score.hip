@@ -95,11 +95,13 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   }
   // Largest score of every 8 consecutive keys per query head: the selection kernel takes its head maximum
   // and a lower bound of the top-k threshold from these.
-  static_assert(kScoreTile == kWave && kSubTile == 8, "one lane per key of the tile, eight lanes per sub-tile");
-  for (int g = wave; g < G; g += 4) {
-    const float v = group_max8(tile_lo + lane < n ? s_tile[g][lane] : -INFINITY);
+  static_assert(kScoreTile % kWave == 0 && kSubTile == 8, "whole waves of keys, eight lanes per sub-tile");
+  constexpr int CHUNKS = kScoreTile / kWave;
+  for (int c = wave; c < G * CHUNKS; c += 4) {
+    const int g = c / CHUNKS, t = (c % CHUNKS) * kWave + lane;
+    const float v = group_max8(tile_lo + t < n ? s_tile[g][t] : -INFINITY);
     if ((lane & 7) == 0) {
-      const int64_t slot = ((int64_t)b * Hq + (int64_t)kvh * G + g) * n_sub + (tile_lo + lane) / kSubTile;
+      const int64_t slot = ((int64_t)b * Hq + (int64_t)kvh * G + g) * n_sub + (tile_lo + t) / kSubTile;
       sub_max[slot] = v;
     }
   }
