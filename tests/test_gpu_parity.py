@@ -289,6 +289,25 @@ def test_draw_cap_completes_samples_in_index_order():
     sess2.close()
 
 
+def test_append_to_a_contiguous_cache_then_decode():
+    say("vatt_append_kv on a contiguous cache")
+    from workloads.configs import append_tokens
+    wl = workloads.small_gqa(seed=52, batch=3, n=2000, seq_lens=[1990, 1500, 7])
+    sess = _session(wl)
+    for step in range(3):
+        k_new, v_new = append_tokens(52, step, wl.batch, wl.n_kv_heads, wl.head_dim)
+        sess.append(k_new, v_new)
+        for b in range(wl.batch):          # mirror the append in the host copy the oracle reads
+            n = int(wl.seq_lens[b])
+            wl.k_bits[b, :, n] = k_new[b]
+            wl.v_bits[b, :, n] = v_new[b]
+        wl.seq_lens = wl.seq_lens + 1
+    assert np.array_equal(sess.seq_lens.cpu().numpy(), wl.seq_lens)
+    res = _run(sess)
+    check_all(wl, res, label="append-contiguous")
+    sess.close()
+
+
 def test_decode_inside_a_hip_graph():
     say("vatt_decode captured in a HIP graph and replayed")
     import torch
