@@ -92,7 +92,7 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
-  pl.n_sub = (int)align_up((size_t)n_max, kScoreTile) / kSubTile;
+  pl.n_sub = (int)align_up((size_t)n_max, kScoreTilePaged) / kSubTile;  // whole tiles of either tile size
   int k_max = p.topk_abs > 0 ? p.topk_abs : (int)std::floor((double)p.topk_frac * (double)n_max);
   pl.k_max = std::min(std::max(k_max, 0), n_max);
   int b0_max = p.base_abs > 0 ? p.base_abs : (int)std::floor((double)p.base_frac * (double)n_max);

@@ -12,6 +12,7 @@ namespace vatt {
 
 constexpr int kScoreTile = 64;        // keys per score-kernel workgroup (small tiles: many short workgroups fill and
                                       // drain the chip more evenly than few long ones; measured 64 > 128 > 256 > 32)
+constexpr int kScoreTilePaged = 256;  // keys per score-kernel workgroup on a paged cache
 constexpr int kSubTile = 8;            // keys per sub-tile maximum
 constexpr int kHeadThreads = 512;      // workgroup size of the per-head kernel
 constexpr int kGatherThreads = 256;

@@ -2,13 +2,13 @@
 // reading each K row from HBM once per group (first step of Algorithm 1 with exact top-k; the
 // exponent of Eq. 1).
 //
-// Work split: grid = (key tiles of 64, KV heads, sequences); a workgroup of 4 waves owns 64
-// consecutive keys.  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
+// Work split: grid = (key tiles, KV heads, sequences); a workgroup of 4 waves owns TILE consecutive keys
+// (64 on a contiguous cache, 256 on a paged one, by measurement).  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
 // segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
-// the DPP path, and the tile's G x 64 scores are staged in LDS so that they leave as whole
-// 256-byte rows.
+// the DPP path, and the tile's G x TILE scores are staged in LDS so that they leave as whole
+// 256-byte rows; the largest score of every 8 keys is written next to them.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -21,27 +21,27 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
                                          false);
 }
 
-template <int D, int G, bool PAGED>
+template <int D, int G, bool PAGED, int TILE>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ scores, float* __restrict__ sub_max,
                                                     int n_sub, int n_pad, int n_max, int Hq, float sm_scale) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
-  constexpr int ROWS_PER_WAVE = kScoreTile / 4;
+  constexpr int ROWS_PER_WAVE = TILE / 4;
   constexpr int LOADS = ROWS_PER_WAVE / RPW;
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
   const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int n = min(max(seq_lens[b], 0), n_max);
-  const int tile_lo = tile * kScoreTile;
+  const int tile_lo = tile * TILE;
   if (tile_lo >= n) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR;   // which 8-column slice of the row
   const int rsub = lane / LPR;  // which row of the wave load
 
-  __shared__ float s_tile[G][kScoreTile];
+  __shared__ float s_tile[G][TILE];
 
   uint32_t qw[G][4];
 #pragma unroll
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     }
   }
   __syncthreads();
-  for (int t = tid; t < kScoreTile; t += 256) {
+  for (int t = tid; t < TILE; t += 256) {
     const int i = tile_lo + t;
     if (i < n) {
 #pragma unroll
@@ -95,8 +95,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   }
   // Largest score of every 8 consecutive keys per query head: the selection kernel takes its head maximum
   // and a lower bound of the top-k threshold from these.
-  static_assert(kScoreTile % kWave == 0 && kSubTile == 8, "whole waves of keys, eight lanes per sub-tile");
-  constexpr int CHUNKS = kScoreTile / kWave;
+  static_assert(TILE % kWave == 0 && kSubTile == 8, "whole waves of keys, eight lanes per sub-tile");
+  constexpr int CHUNKS = TILE / kWave;
   for (int c = wave; c < G * CHUNKS; c += 4) {
     const int g = c / CHUNKS, t = (c % CHUNKS) * kWave + lane;
     const float v = group_max8(tile_lo + t < n ? s_tile[g][t] : -INFINITY);
@@ -111,19 +111,23 @@ template <int D, int G>
 hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                      const int32_t* seq_lens, void* ws, hipStream_t st) {
   const vatt_params& p = pl.p;
-  dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
+
   KVLayout L = pl.kv_k;
   L.block_table = block_table;
   float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_scores);
   float* smax = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_sub_max);
+  // (measured: 64-key tiles stream a contiguous cache best; a paged cache, whose workgroups first wait for their
+  // block-table entries, does better with 256 keys in flight per workgroup)
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
-    hipLaunchKernelGGL((score_kernel<D, G, true>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(k), L, seq_lens, scores, smax, pl.n_sub, pl.n_pad,
-                       p.n_max, p.n_q_heads, pl.sm_scale);
+    dim3 grid((p.n_max + kScoreTilePaged - 1) / kScoreTilePaged, p.n_kv_heads, p.batch);
+    hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale);
   } else {
-    hipLaunchKernelGGL((score_kernel<D, G, false>), grid, dim3(256), 0, st, static_cast<const uint16_t*>(q),
-                       static_cast<const uint16_t*>(k), L, seq_lens, scores, smax, pl.n_sub, pl.n_pad,
-                       p.n_max, p.n_q_heads, pl.sm_scale);
+    dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
+    hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale);
   }
   return hipGetLastError();
 }
