@@ -80,19 +80,20 @@ def philox4x32_10(ctr: Sequence, key: Sequence[int]) -> List[np.ndarray]:
     return [c.astype(np.uint32) for c in (c0, c1, c2, c3)]
 
 
-def draw_words(j_lo: int, j_hi: int, seed: int, head: int, stream: int) -> np.ndarray:
+def draw_words(j_lo: int, j_hi: int, seed: int, head: int, stream: int, query: int = 0) -> np.ndarray:
     """Words u_j, j in [j_lo, j_hi), of the sampler's draw sequence.
 
     Draw j reads word (j mod 4) of Philox4x32-10 applied to the counter
-    (j div 4, stream, head, 0) under the key (low 32 bits of seed, high 32 bits
-    of seed).  `head` is the query-head index, `stream` separates the base
-    sample (0) from the final sample (1).
+    (j div 4, stream, head, query) under the key (low 32 bits of seed, high 32
+    bits of seed).  `head` is the query-head index, `stream` separates the base
+    sample (0) from the final sample (1), `query` is the position of the query
+    token inside a multi-query step (0 for single-token decoding).
     """
     b_lo, b_hi = j_lo // 4, (j_hi + 3) // 4
     nblk = max(b_hi - b_lo, 0)
     blk = np.arange(b_lo, b_lo + nblk, dtype=np.uint64)
     out = philox4x32_10(
-        (blk, np.full(nblk, stream, np.uint64), np.full(nblk, head, np.uint64), np.zeros(nblk, np.uint64)),
+        (blk, np.full(nblk, stream, np.uint64), np.full(nblk, head, np.uint64), np.full(nblk, query, np.uint64)),
         (int(seed) & _MASK32, (int(seed) >> 32) & _MASK32),
     )
     return np.stack(out, axis=1).reshape(-1)[j_lo - 4 * b_lo: j_hi - 4 * b_lo]
@@ -124,7 +125,7 @@ def default_draw_cap(L: int) -> int:
 
 
 def uniform_sample(residual: np.ndarray, c: int, *, mid_lo: int, mid_len: int, seed: int, head: int,
-                   stream: int, draw_cap: Optional[int] = None) -> np.ndarray:
+                   stream: int, draw_cap: Optional[int] = None, query: int = 0) -> np.ndarray:
     """uniform-sample of Algorithms 1 and 2: c residual tokens, uniformly, without replacement.
 
     Sequential draws: draw j proposes the token mid_lo + bounded_draw(u_j,
@@ -159,7 +160,7 @@ def uniform_sample(residual: np.ndarray, c: int, *, mid_lo: int, mid_len: int, s
     j = 0
     while len(chosen) < want and j < cap:
         j_hi = min(j + 4096, cap)
-        ok, val = bounded_draw(draw_words(j, j_hi, seed, head, stream), mid_len)
+        ok, val = bounded_draw(draw_words(j, j_hi, seed, head, stream, query), mid_len)
         for a, v in zip(ok.tolist(), val.tolist()):
             if not a:
                 continue
@@ -354,7 +355,7 @@ def estimate(s: np.ndarray, V: np.ndarray, m: float, I_f: np.ndarray, I_dyn: np.
 def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head: int,
                 params: Dict[str, float], s: Optional[np.ndarray] = None,
                 forced_topk: Optional[np.ndarray] = None,
-                forced_b: Optional[int] = None) -> Dict[str, object]:
+                forced_b: Optional[int] = None, query: int = 0) -> Dict[str, object]:
     """Algorithm 1 for one (sequence, query head).
 
     q: [d], K, V: [n, d] (values already rounded to the storage precision).
@@ -392,14 +393,14 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
     mid_lo, mid_len = int(I_s.shape[0]), n - int(I_s.shape[0]) - int(I_l.shape[0])
     draw_cap = params.get("draw_cap")
     I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
-                          draw_cap=draw_cap)
+                          draw_cap=draw_cap, query=query)
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
     b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target)
     b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
     if forced_b is not None:
         b = int(forced_b)
     I_dyn = uniform_sample(residual, b, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
-                           draw_cap=draw_cap)
+                           draw_cap=draw_cap, query=query)
     N, D = estimate(s, V, m, I_f, I_dyn, n_s)
     res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st,
                O=N / D, lse=m + math.log(D), D_out=D, N_out=N)
@@ -473,4 +474,35 @@ def decode(q: np.ndarray, K: np.ndarray, V: np.ndarray, seq_lens: np.ndarray, se
         n = int(seq_lens[b])
         out[(b, h)] = decode_head(q[b, h], K[b, h // g, :n], V[b, h // g, :n],
                                   seed=int(seeds[b]), head=h, params=params)
+    return out
+
+
+def chunk_length(n: int, q_len: int, t: int) -> int:
+    """Tokens visible to query t of a step that processes the q_len newest tokens of an n-token sequence.
+
+    The queries are the tokens at positions n - q_len .. n - 1, in this order; attention is causal, so query t
+    (at position n - q_len + t) sees the tokens up to and including itself.
+    """
+    return max(int(n) - (int(q_len) - 1 - int(t)), 0)
+
+
+def decode_chunk(q: np.ndarray, K: np.ndarray, V: np.ndarray, seq_lens: np.ndarray, seeds: np.ndarray,
+                 params: Dict[str, float], items: Optional[Sequence] = None) -> Dict[tuple, Dict[str, object]]:
+    """A step with several query tokens per sequence (the question tokens of the evaluation set-up, where the
+    context is processed densely and question and generation sparsely): q [B, Q, Hq, d]; K, V [B, Hkv, n_max, d]
+    already hold the Q newest tokens; seq_lens counts them.
+
+    Every (query token, query head) is one instance of Algorithm 1 over the tokens that query may see
+    (chunk_length), with its own top-k set, samples and budget; the draw sequences of different query tokens
+    differ in the last counter word.  Returns {(b, t, h): decode_head result}; `items` restricts the triples.
+    """
+    B, Q, Hq, _ = q.shape
+    Hkv = K.shape[1]
+    g = Hq // Hkv
+    out = {}
+    todo = items if items is not None else [(b, t, h) for b in range(B) for t in range(Q) for h in range(Hq)]
+    for (b, t, h) in todo:
+        n = chunk_length(int(seq_lens[b]), Q, t)
+        out[(b, t, h)] = decode_head(q[b, t, h], K[b, h // g, :n], V[b, h // g, :n],
+                                     seed=int(seeds[b]), head=h, params=params, query=t)
     return out

@@ -523,3 +523,85 @@ def test_decode_batch_maps_gqa_heads():
     assert np.allclose(out[(1, 3)]["O"], one["O"])
     # heads of one group share K but not their samples
     assert not np.array_equal(out[(0, 0)]["I_bs"], out[(0, 1)]["I_bs"])
+
+
+# ------------------------------------------------- multi-query step (chunk) ----
+def test_draw_words_places_the_query_in_the_last_counter_word():
+    # the published vector with four different counter words fixes which argument lands in which word:
+    # counter (243f6a88, 85a308d3, 13198a2e, 03707344), key (a4093822, 299f31d0)
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) if l[0] != "#"]
+    vals = [int(x, 16) for x in rows[2]]
+    seed = (vals[5] << 32) | vals[4]
+    words = vo.draw_words(4 * vals[0], 4 * vals[0] + 4, seed, head=vals[2], stream=vals[1], query=vals[3])
+    assert [int(w) for w in words] == vals[6:10]
+    # query 0 is the single-token sequence
+    assert np.array_equal(vo.draw_words(0, 64, 77, 3, 1), vo.draw_words(0, 64, 77, 3, 1, query=0))
+    assert not np.array_equal(vo.draw_words(0, 64, 77, 3, 1), vo.draw_words(0, 64, 77, 3, 1, query=1))
+
+
+def test_chunk_lengths_are_causal():
+    # query t of Q sits at position n - Q + t and sees positions 0 .. n - Q + t
+    assert [vo.chunk_length(100, 4, t) for t in range(4)] == [97, 98, 99, 100]
+    assert vo.chunk_length(100, 1, 0) == 100
+    assert vo.chunk_length(2, 4, 0) == 0
+
+
+def test_chunk_with_full_budget_is_causal_dense_attention():
+    # b0 = n_s makes every query exact; the library's causal attention over the chunk is the reference.
+    # (is_causal aligns the mask to the top left, so the explicit lower-right mask is built here.)
+    rng = np.random.default_rng(31)
+    B, Q, Hq, Hkv, d, n = 2, 3, 4, 2, 8, 40
+    q = rng.standard_normal((B, Q, Hq, d))
+    K = rng.standard_normal((B, Hkv, n, d))
+    V = rng.standard_normal((B, Hkv, n, d))
+    lens = np.array([40, 29])
+    p = _params(sink=2, window=3, topk_abs=4, base_abs=1000, sm_scale=0.3)
+    res = vo.decode_chunk(q, K, V, lens, np.array([5, 6]), p)
+    for b in range(B):
+        nb = int(lens[b])
+        mask = torch.zeros(Q, nb, dtype=torch.bool)
+        for t in range(Q):
+            mask[t, : nb - Q + 1 + t] = True
+        for h in range(Hq):
+            ref = torch.nn.functional.scaled_dot_product_attention(
+                torch.from_numpy(q[b, :, h])[None], torch.from_numpy(K[b, h // 2, :nb])[None],
+                torch.from_numpy(V[b, h // 2, :nb])[None], attn_mask=mask[None], scale=0.3)[0].numpy()
+            for t in range(Q):
+                r = res[(b, t, h)]
+                assert r["n"] == nb - Q + 1 + t and r["b"] == r["n_s"]
+                np.testing.assert_allclose(r["O"], ref[t], rtol=1e-12, atol=1e-13)
+
+
+def test_chunk_of_one_query_is_the_single_token_step():
+    rng = np.random.default_rng(32)
+    q = rng.standard_normal((1, 1, 2, 8))
+    K = rng.standard_normal((1, 1, 300, 8))
+    V = rng.standard_normal((1, 1, 300, 8))
+    p = _params(sink=4, window=4, topk_abs=10, base_abs=20, sm_scale=0.35)
+    a = vo.decode_chunk(q, K, V, np.array([300]), np.array([9]), p)
+    b = vo.decode(q[:, 0], K, V, np.array([300]), np.array([9]), p)
+    for h in range(2):
+        assert np.array_equal(a[(0, 0, h)]["I_dyn"], b[(0, h)]["I_dyn"])
+        assert np.array_equal(a[(0, 0, h)]["O"], b[(0, h)]["O"])
+
+
+def test_chunk_queries_draw_independent_samples_from_their_own_residual():
+    rng = np.random.default_rng(33)
+    Q, n = 4, 400
+    q = rng.standard_normal((1, Q, 1, 8))
+    K = rng.standard_normal((1, 1, n, 8))
+    V = rng.standard_normal((1, 1, n, 8))
+    p = _params(sink=4, window=6, topk_abs=12, base_abs=40, sm_scale=0.35)
+    res = vo.decode_chunk(q, K, V, np.array([n]), np.array([1234]), p)
+    samples = []
+    for t in range(Q):
+        r = res[(0, t, 0)]
+        nt = n - Q + 1 + t
+        assert r["n"] == nt
+        assert np.array_equal(r["I_l"], np.arange(nt - 6, nt))          # the window ends at the query itself
+        taken = set(r["I_t"].tolist())
+        assert all(4 <= i < nt - 6 and i not in taken for i in r["I_dyn"].tolist())
+        assert len(set(r["I_dyn"].tolist())) == r["b"]
+        samples.append(set(r["I_dyn"].tolist()))
+    # different query tokens use different draw sequences
+    assert samples[0] != samples[1] and samples[1] != samples[2]
