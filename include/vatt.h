@@ -122,6 +122,25 @@ int vatt_plan_create(const vatt_params* params, int device, vatt_plan** out);
 void vatt_plan_destroy(vatt_plan* plan);
 
 /*
+ * A plan for steps with q_len query tokens per sequence (the paper evaluates with the context processed
+ * densely and the question tokens, like the generated ones, processed with sparse attention: the
+ * split-prompt set-up of its appendix on evaluation set-ups).  The queries of a sequence are its q_len
+ * newest tokens, whose K and V rows are already in the cache and counted in seq_lens; query token t
+ * (0 .. q_len - 1, oldest first) sees the sequence up to and including itself, n - (q_len - 1 - t) tokens,
+ * and runs Algorithm 1 on that prefix for every query head, with its own top-k set, samples and budget.
+ * Its draws use the Philox counter (j >> 2, stream, h, t).  All query tokens and all query heads of a KV
+ * head share one read of K in the score pass.
+ * With such a plan every "[B, ...]" shape of q and of the outputs of vatt_decode, vatt_dense_decode and
+ * vatt_score reads "[B, q_len, ...]" (seq_lens, seq_seeds, block_table and the caches stay per sequence,
+ * and every seq_lens entry should be at least q_len: a query with no visible token is treated as seeing
+ * one), and vatt_decode_given_topk returns VATT_E_UNSUPPORTED_SHAPE.  q_len = 1 is vatt_plan_create.
+ * q_len * (n_q_heads / n_kv_heads) may not exceed 64 and batch * q_len may not exceed 65535
+ * (VATT_E_UNSUPPORTED_SHAPE).
+ */
+int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vatt_plan** out);
+int vatt_plan_query_len(const vatt_plan* plan);
+
+/*
  * Options (host only), for tests.  VATT_OPT_SAMPLER_SMALL_BATCHES = 1 makes the sampler work through
  * the draw sequence in batches of 256 draws only (it normally uses up to 1024); results are identical.
  * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that

@@ -29,7 +29,7 @@ VATT_OPT_SAMPLER_DRAW_CAP = 2
 VATT_OPT_TOPK_GENERAL_PATH = 3
 
 EXPORTS = [
-    "vatt_plan_create", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
+    "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
     "vatt_plan_index_segment", "vatt_decode", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv",
     "vatt_status_string",
@@ -63,6 +63,11 @@ def _load():
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     lib.vatt_plan_create.argtypes = [ctypes.POINTER(vatt_params), ctypes.c_int, ctypes.POINTER(vp)]
     lib.vatt_plan_create.restype = ctypes.c_int
+    lib.vatt_plan_create_chunk.argtypes = [ctypes.POINTER(vatt_params), ctypes.c_int, ctypes.c_int,
+                                           ctypes.POINTER(vp)]
+    lib.vatt_plan_create_chunk.restype = ctypes.c_int
+    lib.vatt_plan_query_len.argtypes = [vp]
+    lib.vatt_plan_query_len.restype = ctypes.c_int
     lib.vatt_plan_destroy.argtypes = [vp]
     lib.vatt_plan_destroy.restype = None
     lib.vatt_plan_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
@@ -129,6 +134,21 @@ def vatt_plan_create(params, device: int) -> int:
     if rc != VATT_OK:
         raise VattError(rc, "vatt_plan_create")
     return out.value
+
+
+def vatt_plan_create_chunk(params, q_len: int, device: int) -> int:
+    """A plan for steps with q_len query tokens per sequence; otherwise as vatt_plan_create."""
+    if isinstance(params, dict):
+        params = make_params(params)
+    out = ctypes.c_void_p()
+    rc = _lib.vatt_plan_create_chunk(ctypes.byref(params), int(q_len), int(device), ctypes.byref(out))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_plan_create_chunk")
+    return out.value
+
+
+def vatt_plan_query_len(plan: int) -> int:
+    return int(_lib.vatt_plan_query_len(plan))
 
 
 def vatt_plan_destroy(plan: int) -> None:

@@ -62,8 +62,10 @@ int validate(const vatt_params& p) {
   return VATT_OK;
 }
 
-int build_plan(Plan& pl, const vatt_params& p, int device) {
+int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.p = p;
+  pl.q_len = q_len;
+  pl.vbatch = p.batch * q_len;
   pl.device = device;
   pl.num_cus = 256;
   if (device >= 0) {
@@ -102,11 +104,11 @@ int build_plan(Plan& pl, const vatt_params& p, int device) {
 
   pl.head_threads = kHeadThreads;
 
-  const int heads = p.batch * p.n_q_heads;
+  const int heads = pl.vbatch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
   pl.gather_splits = std::min(32, std::max(1, (8 * pl.num_cus + heads - 1) / heads));
   pl.vstat_splits = pl.gather_splits;
-  const int kv_heads = p.batch * p.n_kv_heads;
+  const int kv_heads = pl.vbatch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
   pl.dense_splits = std::min(std::min(128, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
 
@@ -181,14 +183,22 @@ using namespace vatt;
 extern "C" {
 
 int vatt_plan_create(const vatt_params* params, int device, vatt_plan** out) {
+  return vatt_plan_create_chunk(params, 1, device, out);
+}
+
+int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vatt_plan** out) {
   if (!params || !out) return VATT_E_INVALID_ARG;
   *out = nullptr;
   int rc = validate(*params);
   if (rc != VATT_OK) return rc;
+  if (q_len < 1) return VATT_E_INVALID_ARG;
+  // a multi-query score tile holds at most 64 (query token, group head) pairs
+  if (q_len > 1 && (int64_t)q_len * (params->n_q_heads / params->n_kv_heads) > 64) return VATT_E_UNSUPPORTED_SHAPE;
+  if ((int64_t)params->batch * q_len > 65535) return VATT_E_UNSUPPORTED_SHAPE;
   vatt_plan* plan = new (std::nothrow) vatt_plan;
   if (!plan) return VATT_E_INVALID_ARG;
   std::memset(static_cast<void*>(plan), 0, sizeof(*plan));
-  rc = build_plan(plan->pl, *params, device);
+  rc = build_plan(plan->pl, *params, q_len, device);
   if (rc == VATT_OK && device >= 0) {
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) rc = VATT_E_HIP;
@@ -216,6 +226,8 @@ size_t vatt_plan_workspace_offset(const vatt_plan* plan, int region) {
 }
 
 size_t vatt_plan_score_stride(const vatt_plan* plan) { return plan ? (size_t)plan->pl.n_pad : 0; }
+
+int vatt_plan_query_len(const vatt_plan* plan) { return plan ? plan->pl.q_len : 0; }
 
 size_t vatt_plan_index_capacity(const vatt_plan* plan) { return plan ? plan->pl.idx_cap : 0; }
 
@@ -247,7 +259,10 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
   int rc = check_common(plan, workspace, workspace_bytes, block_table);
   if (rc != VATT_OK) return rc;
   if (!q || !k || !seq_lens || !aligned16(q) || !aligned16(k)) return VATT_E_INVALID_ARG;
-  VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
+  if (plan->pl.q_len > 1)
+    VATT_LAUNCH(launch_score_chunk(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
+  else
+    VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
   return VATT_OK;
 }
 
@@ -261,7 +276,10 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
+  if (pl.q_len > 1)
+    VATT_LAUNCH(launch_score_chunk(pl, q, k, block_table, seq_lens, workspace, st));
+  else
+    VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
   if (pl.p.target == VATT_TARGET_D) {
     VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   } else {
@@ -284,7 +302,7 @@ int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const 
     return VATT_E_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
-  if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
+  if (pl.p.target != VATT_TARGET_D || pl.q_len != 1) return VATT_E_UNSUPPORTED_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
                                   out_budget_raw, out_stats, st));

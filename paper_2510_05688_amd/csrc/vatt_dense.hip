@@ -28,6 +28,7 @@ struct DenseArgs {
   float* out_o;
   float* out_lse;
   int n_max, Hq, splits;
+  int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token (each one scans the cache)
   float sm_scale;
 };
 
@@ -41,7 +42,8 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
-  const int n = min(max(A.seq_lens[b], 1), A.n_max);
+  const int seq = b / A.q_len, qtok = b - seq * A.q_len;
+  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
   // key range of this workgroup, then of this wave (multiples of RPW * U rows except at the end)
   const int step = RPW * U;
   const int per_blk = ((n + A.splits - 1) / A.splits + step * WAVES - 1) / (step * WAVES) * (step * WAVES);
@@ -76,8 +78,8 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
       ok[u] = i < hi;
       kk[u] = vv[u] = make_uint4(0u, 0u, 0u, 0u);
       if (ok[u]) {
-        kk[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, i) + sub * 8);
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, i) + sub * 8);
+        kk[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, seq, kvh, i) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, seq, kvh, i) + sub * 8);
       }
     }
     float s[G][U];
@@ -203,14 +205,14 @@ __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restr
 template <int D, int G>
 hipError_t launch_dense_dg(const Plan& pl, DenseArgs& A, hipStream_t st) {
   const vatt_params& p = pl.p;
-  dim3 grid(pl.dense_splits, p.n_kv_heads, p.batch);
+  dim3 grid(pl.dense_splits, p.n_kv_heads, pl.vbatch);
   if (p.kv_layout == VATT_LAYOUT_PAGED)
     hipLaunchKernelGGL((dense_kernel<D, G, true>), grid, dim3(kDenseThreads), 0, st, A);
   else
     hipLaunchKernelGGL((dense_kernel<D, G, false>), grid, dim3(kDenseThreads), 0, st, A);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(2 * D), 0, st, A.part, pl.dense_splits,
+  hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(2 * D), 0, st, A.part, pl.dense_splits,
                      p.n_q_heads, A.out_o, A.out_lse);
   return hipGetLastError();
 }
@@ -266,6 +268,7 @@ hipError_t launch_dense(const Plan& pl, const void* q, const void* k, const void
   A.n_max = pl.p.n_max;
   A.Hq = pl.p.n_q_heads;
   A.splits = pl.dense_splits;
+  A.q_len = pl.q_len;
   A.sm_scale = pl.sm_scale;
   if (pl.p.head_dim == 128) return launch_dense_d<128>(pl, A, st);
   if (pl.p.head_dim == 64) return launch_dense_d<64>(pl, A, st);

@@ -26,6 +26,7 @@ struct GatherArgs {
   float* out_lse;
   int64_t seg_topk, seg_base, seg_dyn, idx_cap;
   int n_pad, Hq, group, splits;
+  int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
 };
 
 // Token and weight factor of list position p for a head:
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
+  const int seq = b / A.q_len;  // the sequence whose cache this (sequence, query token) pair reads
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
 
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
       if (tok[u] >= 0) {
         const int t = min(tok[u], r.n - 1);
         w[u] = row[t];
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, b, kvh, t) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, seq, kvh, t) + sub * 8);
       }
     }
 #pragma unroll
@@ -236,14 +238,15 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   A.Hq = p.n_q_heads;
   A.group = pl.group;
   A.splits = STATS ? pl.vstat_splits : pl.gather_splits;
-  dim3 grid(A.splits, p.n_q_heads, p.batch);
+  A.q_len = pl.q_len;
+  dim3 grid(A.splits, p.n_q_heads, pl.vbatch);
   if (p.kv_layout == VATT_LAYOUT_PAGED)
     hipLaunchKernelGGL((gather_kernel<D, true, STATS>), grid, dim3(kGatherThreads), 0, st, A);
   else
     hipLaunchKernelGGL((gather_kernel<D, false, STATS>), grid, dim3(kGatherThreads), 0, st, A);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || STATS || A.splits == 1) return e;
-  hipLaunchKernelGGL((gather_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(D), 0, st, A.part, A.head_rec,
+  hipLaunchKernelGGL((gather_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(D), 0, st, A.part, A.head_rec,
                      A.splits, p.n_q_heads, out_o, out_lse);
   return hipGetLastError();
 }

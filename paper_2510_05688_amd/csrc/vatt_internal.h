@@ -30,6 +30,8 @@ struct Plan {
   int device;         // -1: geometry only
   int num_cus;
   int group;          // Hq / Hkv
+  int q_len;          // query tokens per sequence and call (1: single-token decoding)
+  int vbatch;         // batch * q_len: every (sequence, query token) pair is handled like a sequence of its own
   float sm_scale;
   double z_half;      // Phi^{-1}(1 - delta/2)
   double z_quarter;   // Phi^{-1}(1 - delta/4)
@@ -56,6 +58,9 @@ struct Plan {
 // Every launcher returns a hipError_t from hipGetLastError() after the launch.
 hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                         const int32_t* seq_lens, void* ws, hipStream_t st);
+// The score pass of a multi-query step (q_len > 1): all query tokens and group heads share one read of K.
+hipError_t launch_score_chunk(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                              const int32_t* seq_lens, void* ws, hipStream_t st);
 // phase 0: everything (target D); phase 1: through the base sample; phase 2: budget and final sample.
 hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws,
                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,

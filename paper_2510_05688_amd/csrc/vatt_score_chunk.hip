@@ -1,0 +1,164 @@
+// Score pass of a multi-query step: the q_len newest tokens of every sequence are queries (the question
+// tokens of the evaluation set-up in which only the context is processed densely), and every K row is read
+// from HBM once for all of them and for all query heads of the GQA group.
+//
+// With Q query tokens and G heads per KV head, a K tile meets Q * G query vectors: a dense contraction
+// [keys x d] . [d x (Q G)], which goes to the matrix cores.  One wave owns 16-key tiles; the MFMA
+// v_mfma_f32_16x16x32_bf16 multiplies a 16 x 32 slice of K (A operand: lane l holds row l % 16, eight
+// consecutive columns starting at 8 (l / 16)) with a 32 x 16 slice of the transposed queries (B operand: lane
+// l holds query l % 16, the same eight columns) and accumulates 16 x 16 scores in fp32 (lane l: keys
+// 4 (l / 16) .. + 3 of query l % 16).  A lane therefore reads 16 bytes of a K row per instruction and the
+// four lanes of a row read 64 contiguous bytes; d / 32 instructions cover the row.  Products of bf16 values
+// are exact in fp32, so only the order of the fp32 additions differs from the single-query kernel.
+//
+// Query token t of a sequence of n tokens sees n - (Q - 1 - t) of them; later keys are left out of its score
+// row and of its 8-key maxima (they enter as -inf), which is all the causal mask needs: the selection kernel
+// never looks beyond a row's own length.
+//
+// grid = (key tiles, KV heads, sequences), 4 waves per workgroup, TILE keys per workgroup.  Query vectors are
+// taken 16 at a time (NQT groups); the K fragments stay in registers across the groups.  Scores are staged
+// in LDS (16 queries x TILE keys) so that they leave as whole rows, with the largest of every 8 keys beside
+// them, exactly as the single-query kernel leaves them.
+#include "vatt_internal.h"
+
+namespace vatt {
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kChunkTile = 256;  // keys per workgroup
+
+template <int D, bool PAGED, int NQT, int TILE>
+__global__ __launch_bounds__(256) void score_chunk_kernel(const uint16_t* __restrict__ q,
+                                                          const uint16_t* __restrict__ k, KVLayout L,
+                                                          const int32_t* __restrict__ seq_lens,
+                                                          float* __restrict__ scores, float* __restrict__ sub_max,
+                                                          int n_sub, int n_pad, int n_max, int Hq, int G, int Q,
+                                                          float sm_scale) {
+  constexpr int S = D / 32;        // MFMA steps per row
+  constexpr int KT = TILE / 64;    // 16-key tiles per wave
+  constexpr int LD = TILE + 4;     // LDS row stride in floats: 16-byte aligned, rows 4 banks apart
+  static_assert(TILE % 64 == 0 && kSubTile == 8, "whole waves of keys, eight lanes per sub-tile");
+
+  const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int n_b = min(max(seq_lens[b], 0), n_max);  // the newest query sees all of it
+  const int tile_lo = tile * TILE;
+  if (tile_lo >= n_b) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, g4 = lane >> 4;
+  const int QG = Q * G;
+
+  __shared__ __align__(16) float s_tile[16][LD];
+
+  // B operands: query vector c = t * G + g of this KV head, for c = 16 nt + i16
+  uint4 bq[NQT][S];
+#pragma unroll
+  for (int nt = 0; nt < NQT; ++nt) {
+    const int c = nt * 16 + i16;
+    const int t = c / G, g = c - t * G;
+    const uint16_t* src = q + (((int64_t)b * Q + t) * Hq + (int64_t)kvh * G + g) * D + g4 * 8;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+      bq[nt][s] = c < QG ? *reinterpret_cast<const uint4*>(src + s * 32) : make_uint4(0u, 0u, 0u, 0u);
+  }
+
+  // A operands: this wave's KT tiles of 16 keys
+  uint4 ka[KT][S];
+#pragma unroll
+  for (int kt = 0; kt < KT; ++kt) {
+    const int i = tile_lo + wave * (KT * 16) + kt * 16 + i16;
+    if (i < n_b) {
+      const uint16_t* src = k + kv_row_offset<PAGED>(L, b, kvh, i) + g4 * 8;
+#pragma unroll
+      for (int s = 0; s < S; ++s) ka[kt][s] = load_stream_16(src + s * 32);
+    } else {
+#pragma unroll
+      for (int s = 0; s < S; ++s) ka[kt][s] = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+
+#pragma unroll
+  for (int nt = 0; nt < NQT; ++nt) {
+    if (nt * 16 >= QG) break;  // same for the whole grid
+    f32x4_t acc[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      acc[kt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < S; ++s)
+        acc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ka[kt][s]),
+                                                          __builtin_bit_cast(bf16x8_t, bq[nt][s]), acc[kt], 0, 0, 0);
+    }
+    if (nt > 0) __syncthreads();  // the previous group's rows have left the staging tile
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      // adding +0 folds a possible -0 into +0 so that the bit pattern orders like the value
+      const float4 out = make_float4(acc[kt][0] * sm_scale + 0.0f, acc[kt][1] * sm_scale + 0.0f,
+                                     acc[kt][2] * sm_scale + 0.0f, acc[kt][3] * sm_scale + 0.0f);
+      *reinterpret_cast<float4*>(&s_tile[i16][wave * (KT * 16) + kt * 16 + 4 * g4]) = out;
+    }
+    __syncthreads();
+    for (int c = 0; c < 16; ++c) {
+      const int cg = nt * 16 + c;
+      if (cg >= QG) break;
+      const int t = cg / G, g = cg - t * G;
+      const int n_t = max(n_b - (Q - 1 - t), 0);  // tokens this query sees
+      const int64_t row = ((int64_t)b * Q + t) * Hq + (int64_t)kvh * G + g;
+#pragma unroll
+      for (int x0 = 0; x0 < TILE; x0 += 256) {
+        const int x = x0 + tid;
+        const int i = tile_lo + x;
+        const float v = s_tile[c][x];
+        if (i < n_t) __builtin_nontemporal_store(v, &scores[row * n_pad + i]);
+        const float mx = group_max8(i < n_t ? v : -INFINITY);
+        if ((lane & 7) == 0) sub_max[row * n_sub + i / kSubTile] = mx;
+      }
+    }
+  }
+}
+
+template <int D, bool PAGED, int NQT>
+hipError_t launch_n(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                    const int32_t* seq_lens, void* ws, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  KVLayout L = pl.kv_k;
+  L.block_table = block_table;
+  float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_scores);
+  float* smax = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_sub_max);
+  dim3 grid((p.n_max + kChunkTile - 1) / kChunkTile, p.n_kv_heads, p.batch);
+  hipLaunchKernelGGL((score_chunk_kernel<D, PAGED, NQT, kChunkTile>), grid, dim3(256), 0, st,
+                     static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
+                     pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.group, pl.q_len, pl.sm_scale);
+  return hipGetLastError();
+}
+
+template <int D, bool PAGED>
+hipError_t launch_p(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                    const int32_t* seq_lens, void* ws, hipStream_t st) {
+  const int groups = (pl.q_len * pl.group + 15) / 16;
+  switch (groups) {
+    case 1: return launch_n<D, PAGED, 1>(pl, q, k, block_table, seq_lens, ws, st);
+    case 2: return launch_n<D, PAGED, 2>(pl, q, k, block_table, seq_lens, ws, st);
+    case 3: return launch_n<D, PAGED, 3>(pl, q, k, block_table, seq_lens, ws, st);
+    case 4: return launch_n<D, PAGED, 4>(pl, q, k, block_table, seq_lens, ws, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_score_chunk(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
+                              const int32_t* seq_lens, void* ws, hipStream_t st) {
+  const bool paged = pl.p.kv_layout == VATT_LAYOUT_PAGED;
+  if (pl.p.head_dim == 128)
+    return paged ? launch_p<128, true>(pl, q, k, block_table, seq_lens, ws, st)
+                 : launch_p<128, false>(pl, q, k, block_table, seq_lens, ws, st);
+  if (pl.p.head_dim == 64)
+    return paged ? launch_p<64, true>(pl, q, k, block_table, seq_lens, ws, st)
+                 : launch_p<64, false>(pl, q, k, block_table, seq_lens, ws, st);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace vatt

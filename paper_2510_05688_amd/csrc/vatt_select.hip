@@ -77,6 +77,7 @@ struct HeadArgs {
   int n_pad, n_max, Hq, n_sub;
   int target, phase, small_batches, topk_general, vstat_splits, head_dim;
   int k_max, b0_max, b_max;
+  int q_len;  // query tokens per sequence: blockIdx.y = sequence * q_len + query token
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
 };
@@ -170,7 +171,7 @@ struct HeadOps {
     uint32_t* wpre;       // word prefixes (LDS)
     const float* row;     // the head's scores
     uint64_t seed;
-    uint32_t stream, head;
+    uint32_t stream, head, query;
     uint32_t L, thr;      // middle-region length and 2^32 mod L
     uint32_t cap;         // draws allowed
     float m;
@@ -193,7 +194,7 @@ struct HeadOps {
     B.have_sc = load_scores;
     VATT_STAMP(S.dbg, 0);
     if (tid < blocks) {
-      const Philox4 ph = philox4x32_10(blk0 + (uint32_t)tid, S.stream, S.head, 0u, (uint32_t)S.seed,
+      const Philox4 ph = philox4x32_10(blk0 + (uint32_t)tid, S.stream, S.head, S.query, (uint32_t)S.seed,
                                        (uint32_t)(S.seed >> 32));
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -705,7 +706,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
-  const int n = min(max(A.seq_lens[b], 1), A.n_max);
+  // In a multi-query step b stands for (sequence, query token); query token t of q_len sees the sequence up to
+  // and including itself, which leaves out the q_len - 1 - t newer tokens.
+  const int seq = b / A.q_len, qtok = b - seq * A.q_len;
+  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
   const HeadSizes hs = head_sizes(n, A.sp);
   const int words_max = ((A.n_max + 63) >> 6) << 1;  // an even number of words: bitmaps are also written 64 bits at a time
   const int words = (n + 31) >> 5;
@@ -722,7 +726,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
-  const uint64_t seed = A.seq_seeds[b];
+  const uint64_t seed = A.seq_seeds[seq];
 
   VATT_STAMP(A.dbg, 0);
   // The score row is requested first (when it is kept in registers), so that its latency overlaps the
@@ -754,6 +758,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   S0.seed = seed;
   S0.stream = 0u;
   S0.head = (uint32_t)h;
+  S0.query = (uint32_t)qtok;
   S0.L = L;
   S0.thr = (uint32_t)((0x100000000ull - (uint64_t)L) % (uint64_t)L);
   {
@@ -1294,6 +1299,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   S.seed = A.seq_seeds[b];
   S.stream = A.phase == 0 ? 0u : 1u;
   S.head = (uint32_t)h;
+  S.query = 0u;
   S.L = (uint32_t)max(mid_len, 1);
   S.thr = (uint32_t)((0x100000000ull - (uint64_t)S.L) % (uint64_t)S.L);
   {
@@ -1498,7 +1504,7 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   HeadArgs A;
   fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
   const vatt_params& p = pl.p;
-  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, p.batch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
+  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, pl.vbatch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
   return hipGetLastError();
 }
 
@@ -1542,6 +1548,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.k_max = pl.k_max;
   A.b0_max = pl.b0_max;
   A.b_max = pl.b_max;
+  A.q_len = pl.q_len;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   A.given_idx = nullptr;
   A.given_cnt = nullptr;

@@ -20,15 +20,20 @@ def _bf16_from_bits(bits: np.ndarray, device) -> torch.Tensor:
 class DecodeSession:
     """Owns a plan, its workspace and output buffers on one GPU."""
 
-    def __init__(self, params: Dict, device: int = 0):
+    def __init__(self, params: Dict, device: int = 0, q_len: int = 1):
+        """q_len > 1: a plan for multi-query steps; q is then [B, q_len, Hq, d] and every output has one row per
+        (sequence, query token) pair, b * q_len + t, where the single-token shapes have one per sequence."""
         if not torch.cuda.is_available():
             raise RuntimeError("DecodeSession needs a GPU; there is no CPU path")
         self.device = torch.device("cuda", device)
         torch.cuda.set_device(self.device)
         self.params = dict(params)
-        self.plan = vb.vatt_plan_create(self.params, device)
+        self.q_len = int(q_len)
+        self.plan = (vb.vatt_plan_create(self.params, device) if self.q_len == 1
+                     else vb.vatt_plan_create_chunk(self.params, self.q_len, device))
         p = self.params
-        self.B, self.Hq, self.Hkv, self.d = p["batch"], p["n_q_heads"], p["n_kv_heads"], p["head_dim"]
+        self.Hq, self.Hkv, self.d = p["n_q_heads"], p["n_kv_heads"], p["head_dim"]
+        self.B = p["batch"] * self.q_len  # rows of every per-query buffer
         self.n_max = p["n_max"]
         self.paged = p.get("kv_layout", 0) == vb.VATT_LAYOUT_PAGED
         self.idx_cap = vb.vatt_plan_index_capacity(self.plan)

@@ -17,6 +17,7 @@ from .configs import (
     config5,
     small_gqa,
     to_paged,
+    chunk_queries,
 )
 
 __all__ = [
@@ -31,4 +32,5 @@ __all__ = [
     "config5",
     "small_gqa",
     "to_paged",
+    "chunk_queries",
 ]

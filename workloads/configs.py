@@ -268,6 +268,22 @@ def append_tokens(seed: int, step: int, batch: int, n_kv_heads: int, head_dim: i
     return f32_to_bf16_bits(k_new), f32_to_bf16_bits(v_new)
 
 
+def chunk_queries(wl: Workload, q_len: int, seed: int = 0, spread: float = 0.5) -> np.ndarray:
+    """Queries of a multi-query step over wl's cache: bf16 bits [B, q_len, Hq, d].
+
+    The newest query token (the last of the chunk) is wl's own query; the older ones are that query plus
+    N(0, spread^2) noise, so that neighbouring query tokens look at related keys (the planted keys of a spiky
+    head stay heavy for all of them) without being copies of each other.
+    """
+    rng = np.random.default_rng([seed, 4242, q_len])
+    base = wl.q_f32()  # [B, Hq, d]
+    B, Hq, d = base.shape
+    q = np.repeat(base[:, None], q_len, axis=1).astype(np.float32)
+    noise = rng.standard_normal((B, q_len, Hq, d), dtype=np.float32) * np.float32(spread)
+    noise[:, q_len - 1] = 0.0
+    return f32_to_bf16_bits(q + noise)
+
+
 def to_paged(wl: Workload, page: int = 16, seed: int = 0):
     """Re-lay a contiguous cache into shuffled pages.
 
