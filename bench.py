@@ -143,6 +143,99 @@ def decode_loop(args, torch, np, workloads, DecodeSession):
     print(json.dumps(out))
 
 
+def chunk_bench(args, torch, np, workloads, DecodeSession):
+    """A multi-query step: the q_len newest tokens of every sequence are queries in one vatt_decode call.
+
+    Compared with q_len single-token calls on the same cache (what a caller without the multi-query plan
+    would issue for those tokens, K scanned once per token) and with this build's dense attention of the
+    same queries.
+    """
+    Q = args.q_len
+    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
+    q_bits = workloads.chunk_queries(wl, Q, seed=1)
+    sess = DecodeSession(plan_params(wl), q_len=Q)
+    sess.upload(q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    single = DecodeSession(plan_params(wl))
+    single.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
+    kv_bytes = 2 * B * Hkv * n * d * 2
+    nbuf = args.buffers if args.buffers > 0 else max(2, min(32, int(60e9 // kv_bytes)))
+    ks = [sess.k] + [sess.k.clone() for _ in range(nbuf - 1)]
+    vs = [sess.v] + [sess.v.clone() for _ in range(nbuf - 1)]
+
+    def step(i):
+        sess.decode(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    def score_only(i):
+        sess.score(k=ks[i % nbuf])
+
+    def dense(i):
+        sess.dense(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    def singles(i):
+        for _ in range(Q):
+            single.decode(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    if args.only:
+        fn = dict(decode=step, score=score_only, dense=dense)[args.only]
+        for i in range(args.warmup):
+            fn(i)
+        print(json.dumps({"only": args.only, "q_len": Q, "ms_per_call": time_calls(fn, args.steps, torch),
+                          "steps": args.steps}))
+        return
+    timed = {}
+    for name, fn in (("step", step), ("score", score_only), ("dense", dense), ("singles", singles)):
+        for i in range(args.warmup):
+            fn(i)
+        timed[name] = time_calls(fn, args.steps, torch)
+    res = sess.results_host()
+    counts = res["counts"].reshape(-1, 8).astype(np.int64)
+    n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
+    b_dyn = counts[:, 4]
+    seq_n = np.asarray(wl.seq_lens, dtype=np.int64)
+    k_scan = int(Hkv * d * 2 * seq_n.sum())                       # read once for all Q query tokens
+    score_w = int(Q * Hq * 4 * seq_n.sum())
+    submax_w = int(Q * Hq * 4 * ((seq_n + 63) // 64 * 8).sum())
+    v_rows = int(((n_f + b_dyn) * d * 2).sum())
+    select_r = 2 * submax_w + int(((counts[:, 2] + 2 * counts[:, 3] + b_dyn) * 32).sum())
+    gather_r = int(((n_f + b_dyn) * 8).sum())
+    path_bytes = k_scan + score_w + submax_w + select_r + gather_r + v_rows
+    score_kernel_bytes = k_scan + score_w + submax_w + B * Q * Hq * d * 2
+    score_flops = 2.0 * Q * Hq * d * float(seq_n.sum())
+    us = timed["step"] * 1e3
+    out = {
+        "metric": "vattention_chunk_us_per_layer", "value": us, "unit": "us", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": timed["step"], "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name + "_q%d" % Q, "accumulate": "fp32", "batch": B, "q_len": Q, "n_q_heads": Hq,
+                   "n_kv_heads": Hkv, "head_dim": d, "n": n, "sink": int(wl.params["sink"]),
+                   "window": int(wl.params["window"]), "topk_frac": float(wl.params["topk_frac"]),
+                   "base_frac": float(wl.params["base_frac"]), "epsilon": float(wl.params["epsilon"]),
+                   "delta": float(wl.params["delta"]), "target": "denominator", "kv_buffers_cycled": nbuf},
+        "us_per_query_token": us / Q,
+        "path_hbm_gbps": path_bytes / (timed["step"] * 1e-3) / 1e9,
+        "path_bytes": path_bytes,
+        "q_len_single_token_calls_us": timed["singles"] * 1e3,
+        "speedup_vs_single_token_calls": timed["singles"] / timed["step"],
+        "dense_same_queries_us": timed["dense"] * 1e3,
+        "speedup_vs_dense": timed["dense"] / timed["step"],
+        "token_density": float(((n_f + b_dyn) / np.maximum(counts[:, 6], 1)).mean()),
+        "budget_b": {"min": int(b_dyn.min()), "mean": float(b_dyn.mean()), "max": int(b_dyn.max())},
+        "roofline": {
+            "kernel": "score_chunk_kernel (K scan shared by all query tokens and group heads, MFMA)",
+            "bound": "hbm",
+            "achieved": score_kernel_bytes / (timed["score"] * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": score_kernel_bytes / (timed["score"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "traffic": None,
+            "bytes_per_launch": score_kernel_bytes,
+            "us_per_launch": timed["score"] * 1e3,
+            "mfma_tflops": score_flops / (timed["score"] * 1e-3) / 1e12,
+        },
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +247,8 @@ def main():
     ap.add_argument("--given-topk", action="store_true",
                     help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -172,6 +267,9 @@ def main():
 
     if args.config == 5:
         decode_loop(args, torch, np, workloads, DecodeSession)
+        return
+    if args.q_len > 1:
+        chunk_bench(args, torch, np, workloads, DecodeSession)
         return
     wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
     sess = DecodeSession(plan_params(wl))
