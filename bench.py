@@ -29,6 +29,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 # 73728.0.  The summaries are kept under profiles/.  Only the configurations that were measured have a figure.
 SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32827.5 * 262144.0 / 131084.4 + 4608.0) * 1024),
                               "config3": int((524827.5 * 262144.0 / 131084.4 + 73728.0) * 1024)}
+# score_chunk_kernel, same two counters and scaling (config 2 with 4 query tokens)
+SCORE_CHUNK_TRAFFIC_BYTES = {("config2", 4): int((32928.6 * 262144.0 / 131084.4 + 18432.7) * 1024)}
 LLAMA8B_LAYERS = 32
 
 
@@ -227,7 +229,7 @@ def chunk_bench(args, torch, np, workloads, DecodeSession):
             "achieved": score_kernel_bytes / (timed["score"] * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": score_kernel_bytes / (timed["score"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": SCORE_CHUNK_TRAFFIC_BYTES.get(("config%d" % args.config, Q)),
             "bytes_per_launch": score_kernel_bytes,
             "us_per_launch": timed["score"] * 1e3,
             "mfma_tflops": score_flops / (timed["score"] * 1e-3) / 1e12,

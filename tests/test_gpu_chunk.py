@@ -157,3 +157,25 @@ def test_chunk_plan_limits():
     plan = vb.vatt_plan_create_chunk(p, 16, 0)
     assert vb.vatt_plan_query_len(plan) == 16
     vb.vatt_plan_destroy(plan)
+
+
+@pytest.mark.timeout(600)
+def test_chunk_at_config2_size_sampled_heads():
+    # the shape bench.py --q-len 4 times: B = 1, 32/8 heads, d = 128, n = 32768, four query tokens
+    say("chunk, config 2 shape, q_len 4")
+    wl = workloads.config2()
+    q_len = 4
+    q_bits = workloads.chunk_queries(wl, q_len, seed=1)
+    sess = _chunk_session(wl, q_bits, q_len)
+    sess.decode()
+    res = sess.results_host()
+    cv = ChunkView(wl, q_bits, q_len)
+    rng = np.random.default_rng(3)
+    heads = [(int(rng.integers(cv.batch)), int(rng.integers(32))) for _ in range(20)] + [(0, 0), (3, 31), (1, 8)]
+    check_all(cv, res, heads=heads, gpu_scores=sess.scores_host(), label="chunk config2 q4")
+    # sizes of every (query token, head): each query token sees one token more than the one before it
+    for v in range(cv.batch):
+        n_v = 32768 - (q_len - 1 - v)
+        assert np.all(res["counts"][v, :, 6] == n_v)
+        assert np.all(res["counts"][v, :, 2] == vo.topk_count(n_v, 128, 128, 0, wl.params["topk_frac"]))
+    sess.close()
