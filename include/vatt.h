@@ -149,7 +149,17 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * threshold from the largest scores of every 8 keys) and take the general path, a histogram over the whole
  * score row, which otherwise only serves short or unusual rows; results are identical.
  */
-enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3 };
+enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
+       VATT_OPT_BUDGET_BOUND = 4 };
+/*
+ * VATT_OPT_BUDGET_BOUND selects the tail bound behind the denominator budget of Algorithm 2:
+ * VATT_BOUND_CLT (default) is the corollary for D, b* = (Phi^{-1}(1 - delta/2) n_s sigma / (eps D))^2;
+ * VATT_BOUND_HOEFFDING is the conservative alternative the paper's appendix on the tightness of the bounds
+ * compares it with.  The paper prints no formula for it; the sub-Gaussian form of Hoeffding's inequality is
+ * used, b* = 2 ln(2 / delta) (n_s sigma / (eps D))^2, which reproduces the sample ratio the appendix reports
+ * (2.8 at delta = 0.2).  Denominator target only (VATT_E_UNSUPPORTED_SHAPE otherwise).
+ */
+enum { VATT_BOUND_CLT = 0, VATT_BOUND_HOEFFDING = 1 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
 
 /* Bytes of device workspace every launching call needs (256-byte aligned base). */

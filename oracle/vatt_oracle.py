@@ -31,7 +31,11 @@ proportional to the sample, not to the context); the base sample holds floor(f_b
 sample variances divide by (b0 - 1); D and ||N|| in the budget formulas are
 the full quantities D_f + residual estimate; the budget is ceil(b*), lower
 capped by the base sample size and upper capped by n_s; I_dyn is a fresh draw
-independent of I_bs.
+independent of I_bs; in a step with several query tokens every (query token,
+head) is an independent instance on the causal prefix of that token; the
+Hoeffding-type budget is the sub-Gaussian form that reproduces the sample ratio
+the paper reports (hoeffding_factor: the formula is a reading, pinned by that
+ratio and by the tail inequality it comes from).
 """
 from __future__ import annotations
 
@@ -292,7 +296,20 @@ def sample_stats(s: np.ndarray, V: Optional[np.ndarray], m: float, I_f: np.ndarr
     return out
 
 
-def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, target: int) -> float:
+def hoeffding_factor(delta: float) -> float:
+    """What takes the place of the normal quantile in the conservative (Hoeffding-type) denominator budget.
+
+    The appendix on the tightness of the bounds compares the CLT budget with a budget from Hoeffding's
+    inequality and prints no formula, only that it asks for 2.8 times the samples at delta = 0.2.  The
+    sub-Gaussian form of the inequality, P(|mean - mu| >= t) <= 2 exp(-b t^2 / (2 sigma^2)), gives
+    b >= 2 ln(2 / delta) (n_s sigma / (eps D))^2: the CLT budget with Phi^{-1}(1 - delta/2)^2 replaced by
+    2 ln(2 / delta), a ratio of 2.80 at delta = 0.2.  That reading is taken; this returns sqrt(2 ln(2 / delta)).
+    """
+    return math.sqrt(2.0 * math.log(2.0 / float(delta)))
+
+
+def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, target: int,
+               bound: str = "clt") -> float:
     """b* of Algorithm 2.
 
     Denominator (Corollary for D):  b* = (Phi^{-1}(1 - delta/2) * n_s * sigma / (eps * D))^2.
@@ -306,6 +323,12 @@ def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, 
     eps = float(np.float64(np.float32(epsilon)))
     dlt = float(np.float64(np.float32(delta)))
     rho_D = n_s * math.sqrt(stats["sigma2"]) / stats["D_hat"]
+    if bound == "hoeffding":
+        if target != TARGET_D:
+            raise ValueError("the Hoeffding-type budget is defined for the denominator target only")
+        return (hoeffding_factor(dlt) * rho_D / eps) ** 2
+    if bound != "clt":
+        raise ValueError("unknown bound")
     if target == TARGET_D:
         return (upper_tail_quantile(dlt / 2.0) * rho_D / eps) ** 2
     nn = math.sqrt(stats["N_hat_sq"])
@@ -395,7 +418,8 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
     I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
                           draw_cap=draw_cap, query=query)
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
-    b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target)
+    b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target,
+                        bound=str(params.get("bound", "clt")))
     b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
     if forced_b is not None:
         b = int(forced_b)

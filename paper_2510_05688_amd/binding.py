@@ -27,6 +27,9 @@ VATT_WS_DEBUG = 1
 VATT_OPT_SAMPLER_SMALL_BATCHES = 1
 VATT_OPT_SAMPLER_DRAW_CAP = 2
 VATT_OPT_TOPK_GENERAL_PATH = 3
+VATT_OPT_BUDGET_BOUND = 4
+VATT_BOUND_CLT = 0
+VATT_BOUND_HOEFFDING = 1
 
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",

@@ -246,6 +246,18 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     plan->pl.topk_general_path = value ? 1 : 0;
     return VATT_OK;
   }
+  if (option == VATT_OPT_BUDGET_BOUND) {
+    Plan& pl = plan->pl;
+    if (value == VATT_BOUND_CLT) {
+      pl.z_half = upper_tail_quantile((double)pl.p.delta / 2.0);
+      return VATT_OK;
+    }
+    if (value != VATT_BOUND_HOEFFDING) return VATT_E_INVALID_ARG;
+    if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
+    // sub-Gaussian tail 2 exp(-b t^2 / (2 sigma^2)) <= delta in place of the normal quantile
+    pl.z_half = std::sqrt(2.0 * std::log(2.0 / (double)pl.p.delta));
+    return VATT_OK;
+  }
   if (option == VATT_OPT_SAMPLER_DRAW_CAP) {
     if (value < 0) return VATT_E_INVALID_ARG;
     plan->pl.sampler_draw_cap = (uint32_t)value;

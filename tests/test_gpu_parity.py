@@ -400,3 +400,25 @@ def test_launch_argument_errors_are_caught_on_the_host():
                    sess.out_o, None, sess.out_idx, sess.out_counts, None, None)
     torch.cuda.synchronize()
     sess.close()
+
+
+def test_hoeffding_type_budget():
+    say("conservative (Hoeffding-type) denominator budget")
+    from paper_2510_05688_amd import binding as vb
+    # epsilon small enough that budgets rise above the base sample on most heads
+    wl = workloads.small_gqa(seed=41, batch=2, n=9000, epsilon=0.03, delta=0.2)
+    sess = _session(wl)
+    clt = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
+    hoe = _run(sess)
+    params = dict(wl.params, bound="hoeffding")
+    reps = check_all(wl, hoe, params=params, label="hoeffding")
+    assert any(r["b"] > r["b0"] for r in reps)
+    # same base sample, same statistics: b* grows by the constant 2 ln(2/delta) / z^2 (2.80 at delta = 0.2)
+    ratio = hoe["b_star"] / clt["b_star"]
+    assert np.all(np.abs(ratio - 2.8037) < 2e-3), (ratio.min(), ratio.max())
+    assert np.all(hoe["counts"][..., 4] >= clt["counts"][..., 4])
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_CLT)
+    back = _run(sess)
+    assert np.array_equal(back["counts"], clt["counts"]) and np.array_equal(back["b_star"], clt["b_star"])
+    sess.close()

@@ -106,3 +106,34 @@ def test_geometry_only_plan_cannot_launch():
         assert e.value.status == vb.VATT_E_NO_DEVICE
     finally:
         vb.vatt_plan_destroy(plan)
+
+
+def test_budget_bound_option_and_chunk_plans_on_the_host():
+    plan = vb.vatt_plan_create(_base(), -1)
+    try:
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_CLT)
+        with pytest.raises(vb.VattError):
+            vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_BOUND, 7)
+        assert vb.vatt_plan_query_len(plan) == 1
+    finally:
+        vb.vatt_plan_destroy(plan)
+    plan = vb.vatt_plan_create(_base(target=1), -1)
+    try:
+        with pytest.raises(vb.VattError):     # the conservative bound exists for the denominator target only
+            vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
+    finally:
+        vb.vatt_plan_destroy(plan)
+    # multi-query plans: buffers grow with the number of query tokens; limits are checked on the host
+    one = vb.vatt_plan_create(_base(), -1)
+    four = vb.vatt_plan_create_chunk(_base(), 4, -1)
+    try:
+        assert vb.vatt_plan_query_len(four) == 4
+        assert vb.vatt_plan_workspace_bytes(four) > 3 * vb.vatt_plan_workspace_bytes(one)
+        assert vb.vatt_plan_index_capacity(four) == vb.vatt_plan_index_capacity(one)
+    finally:
+        vb.vatt_plan_destroy(one)
+        vb.vatt_plan_destroy(four)
+    for bad in (0, -3, 17):                    # 17 * (32 / 8) query vectors exceed a score tile
+        with pytest.raises(vb.VattError):
+            vb.vatt_plan_create_chunk(_base(), bad, -1)

@@ -605,3 +605,49 @@ def test_chunk_queries_draw_independent_samples_from_their_own_residual():
         samples.append(set(r["I_dyn"].tolist()))
     # different query tokens use different draw sequences
     assert samples[0] != samples[1] and samples[1] != samples[2]
+
+
+# ------------------------------------------------ Hoeffding-type budget ----
+def test_hoeffding_budget_reproduces_the_ratio_the_paper_reports():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "hoeffding_vs_clt_ratio.txt")) if l[0] != "#"]
+    eps, delta, ratio = (float(x) for x in rows[0])
+    st = dict(D_f=3.0, w_bar=0.01, sigma2=0.0004, D_hat=3.0 + 5000 * 0.01, tr_sigma=0.0, N_hat_sq=0.0)
+    clt = vo.budget_raw(st, 5000, eps, delta, vo.TARGET_D)
+    hoe = vo.budget_raw(st, 5000, eps, delta, vo.TARGET_D, bound="hoeffding")
+    assert abs(hoe / clt - ratio) < 0.05          # the paper prints one decimal
+    # the ratio does not depend on the data, only on delta
+    st2 = dict(st, sigma2=0.09, D_hat=77.0)
+    assert abs(vo.budget_raw(st2, 900, eps, delta, vo.TARGET_D, bound="hoeffding")
+               / vo.budget_raw(st2, 900, eps, delta, vo.TARGET_D) - hoe / clt) < 1e-12
+
+
+def test_hoeffding_factor_inverts_the_subgaussian_tail_and_dominates_the_normal_quantile():
+    import scipy.stats
+    for delta in (0.01, 0.05, 0.1, 0.2, 0.5):
+        f = vo.hoeffding_factor(delta)
+        # a normal variable exceeds f standard deviations (two-sided) with probability below delta: the
+        # library's exact tail sits under the bound the factor comes from
+        assert 2.0 * scipy.stats.norm.sf(f) < delta
+        assert f > vo.upper_tail_quantile(delta / 2.0)
+    with pytest.raises(ValueError):
+        vo.budget_raw(dict(D_f=1.0, w_bar=0.1, sigma2=0.1, D_hat=2.0, tr_sigma=1.0, N_hat_sq=1.0), 10, 0.1, 0.1,
+                      vo.TARGET_N, bound="hoeffding")
+
+
+def test_hoeffding_budget_meets_the_guarantee_on_a_bounded_population():
+    # residual weights uniform on [0, 1]: with the true sigma and D in the formula, a sample of ceil(b*)
+    # tokens (without replacement) estimates D within eps in clearly more than a 1 - delta fraction of draws
+    rng = np.random.default_rng(8)
+    n_s, eps, delta = 4000, 0.02, 0.2
+    w = rng.random(n_s)
+    D_f = 50.0
+    D = D_f + w.sum()
+    st = dict(D_f=D_f, w_bar=float(w.mean()), sigma2=float(w.var(ddof=1)), D_hat=D, tr_sigma=0.0, N_hat_sq=0.0)
+    b = int(math.ceil(vo.budget_raw(st, n_s, eps, delta, vo.TARGET_D, bound="hoeffding")))
+    assert 2 <= b < n_s
+    hits = 0
+    trials = 2000
+    for _ in range(trials):
+        pick = rng.choice(n_s, size=b, replace=False)
+        hits += abs(D_f + n_s / b * w[pick].sum() - D) <= eps * D
+    assert hits / trials >= 1 - delta / 2
