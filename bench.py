@@ -249,6 +249,8 @@ def main():
     ap.add_argument("--given-topk", action="store_true",
                     help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
+    ap.add_argument("--nested", action="store_true",
+                    help="nested samples (an option beyond the paper): the final sample keeps the base sample")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
@@ -275,6 +277,9 @@ def main():
         return
     wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
     sess = DecodeSession(plan_params(wl))
+    if args.nested:
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_NESTED_SAMPLES, 1)
     sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
     B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
     kv_bytes = 2 * B * Hkv * n * d * 2
@@ -347,14 +352,15 @@ def main():
     path_bytes = k_scan + score_w + submax_w + select_r + gather_r + v_rows
     if args.given_topk:
         # K rows of I_f, I_bs and I_dyn (no scan), V rows of I_f and I_dyn, the sparse scores and index lists
-        k_rows = int(((n_f + counts[:, 3] + b_dyn) * d * 2).sum())
+        k_rows = int(((n_f + (0 if args.nested else counts[:, 3]) + b_dyn) * d * 2).sum())
         path_bytes = k_rows + v_rows + int(((n_f + counts[:, 3] + b_dyn) * 12).sum())
     score_kernel_bytes = k_scan + score_w + submax_w + B * Hq * d * 2
     dense_bytes = 2 * k_scan
 
     us_layer = ms_step * 1e3
     out = {
-        "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else ""),
+        "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else "")
+                  + ("_nested_samples" if args.nested else ""),
         "value": us_layer,
         "unit": "us",
         "n_gpus": 1,

@@ -150,7 +150,15 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * score row, which otherwise only serves short or unusual rows; results are identical.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_BUDGET_BOUND = 4 };
+       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5 };
+/*
+ * VATT_OPT_NESTED_SAMPLES = 1 departs from Algorithm 1, which draws the final sample afresh: the base sample
+ * is kept as the head of the final sample and only b - b0 further tokens are drawn (stream 1) among the
+ * residual tokens outside it.  For a fixed b the result is still a uniform b-subset of the residual; b itself
+ * was computed from the base sample, so the estimate is no longer exactly unbiased.  It saves the second
+ * sample where b = b0 (most heads) and, in vatt_decode_given_topk, the K rows of the base sample.  The final
+ * sample's segment of out_idx then starts with the base sample in its own order.  0 (default) is the paper.
+ */
 /*
  * VATT_OPT_BUDGET_BOUND selects the tail bound behind the denominator budget of Algorithm 2:
  * VATT_BOUND_CLT (default) is the corollary for D, b* = (Phi^{-1}(1 - delta/2) n_s sigma / (eps D))^2;

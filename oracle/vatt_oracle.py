@@ -423,8 +423,18 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
     b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
     if forced_b is not None:
         b = int(forced_b)
-    I_dyn = uniform_sample(residual, b, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
-                           draw_cap=draw_cap, query=query)
+    if params.get("nested"):
+        # Nested samples (not the paper's Algorithm 1, which draws I_dyn afresh): the base sample is kept and
+        # b - b0 further tokens are drawn, with the second draw sequence, from the residual tokens outside it.
+        # A uniform b0-subset plus a uniform (b - b0)-subset of the rest is a uniform b-subset for fixed b;
+        # b itself was computed from the base sample, which is where a (small) bias can enter.
+        rest = np.setdiff1d(residual, I_bs, assume_unique=True)
+        extra = uniform_sample(rest, b - b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
+                               draw_cap=draw_cap, query=query)
+        I_dyn = np.sort(np.concatenate([I_bs, extra]))
+    else:
+        I_dyn = uniform_sample(residual, b, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
+                               draw_cap=draw_cap, query=query)
     N, D = estimate(s, V, m, I_f, I_dyn, n_s)
     res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st,
                O=N / D, lse=m + math.log(D), D_out=D, N_out=N)

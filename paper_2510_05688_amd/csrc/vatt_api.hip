@@ -91,6 +91,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.sampler_small_batches = 0;
   pl.topk_general_path = 0;
   pl.sampler_draw_cap = 0;
+  pl.nested_samples = 0;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
@@ -244,6 +245,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   }
   if (option == VATT_OPT_TOPK_GENERAL_PATH) {
     plan->pl.topk_general_path = value ? 1 : 0;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_NESTED_SAMPLES) {
+    plan->pl.nested_samples = value ? 1 : 0;
     return VATT_OK;
   }
   if (option == VATT_OPT_BUDGET_BOUND) {

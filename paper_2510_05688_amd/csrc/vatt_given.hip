@@ -5,8 +5,9 @@
 //   sparse_score_kernel   s_i = sm_scale * <K[i], q> for the tokens of I_f and I_bs, written next to their
 //                         places in the index lists
 //   given_gather_kernel   the N and D sums of Section 4.1 over [I_f, I_dyn]: scores of I_f from the sparse
-//                         list, scores of I_dyn computed here from their K rows; V rows gathered as in the
-//                         dense-scored path.  No head maximum is known in advance, so every lane group keeps a
+//                         list, scores of I_dyn computed here from their K rows (with nested samples the
+//                         base-sample part of I_dyn has its scores in the list already); V rows gathered as
+//                         in the dense-scored path.  No head maximum is known in advance, so every lane group keeps a
 //                         running maximum and rescales (online softmax), and the merge combines the splits'
 //                         (max, D, N) partials the same way.
 //
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
   float dsum = 0.f, m_run = -INFINITY;
 
   for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
-    bool have[U], tail[U];
+    bool have[U], tail[U], known[U];
     float s[U];
     uint4 kv[U], vv[U];
 #pragma unroll
@@ -166,6 +167,7 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
       const int p = p0 + u * RPB;
       have[u] = p < p_hi;
       tail[u] = false;
+      known[u] = true;
       s[u] = 0.f;
       kv[u] = make_uint4(0u, 0u, 0u, 0u);
       vv[u] = make_uint4(0u, 0u, 0u, 0u);
@@ -173,8 +175,10 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
         int tok;
         const int64_t place = list_place(A, r, idx, A.seg_dyn, p, &tok, &tail[u]);
         tok = min(max(tok, 0), r.n - 1);
-        if (tail[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
-        else s[u] = sp[place];
+        // scores are at hand for I_f and, with nested samples, for the base-sample head of the final sample
+        known[u] = !tail[u] || place - A.seg_dyn < (int64_t)r.b_keep;
+        if (!known[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
+        else s[u] = sp[tail[u] ? A.seg_base + (place - A.seg_dyn) : place];
         vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, tok) + sub * 8);
       }
     }
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
       // (the lanes of a group stay together: every lane of the group computes the row's score)
       const float sk = row_score<LPR>(kv[u], qw, A.sm_scale);
       if (have[u]) {
-        const float e = tail[u] ? sk + tail_bias : s[u];
+        const float e = (known[u] ? s[u] : sk) + (tail[u] ? tail_bias : 0.f);
         if (e > m_run) {
           const float f = __expf(m_run - e);  // 0 when m_run is -inf
 #pragma unroll

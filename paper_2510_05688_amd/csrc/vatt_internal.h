@@ -23,6 +23,7 @@ struct HeadRec {
   float m;        // max score of the head
   float scale;    // n_s / b (0 when b == 0)
   int32_t n, n_sink, n_win, k, b, n_s;
+  int32_t b_keep;  // leading entries of the final sample that repeat the base sample (nested samples), else 0
 };
 
 struct Plan {
@@ -49,6 +50,7 @@ struct Plan {
   int topk_general_path;          // test hook: the top-k selection always takes its general path
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
+  int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
   // workspace offsets (bytes)
   size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;

@@ -78,6 +78,7 @@ struct HeadArgs {
   int target, phase, small_batches, topk_general, vstat_splits, head_dim;
   int k_max, b0_max, b_max;
   int q_len;  // query tokens per sequence: blockIdx.y = sequence * q_len + query token
+  int nested; // the final sample keeps the base sample and adds b - b0 tokens drawn outside it
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
 };
@@ -403,6 +404,26 @@ struct HeadOps {
       *sum_w2 += aw2;
     }
     return flags;
+  }
+
+  // Nested final sample (an option; Algorithm 1 draws the final sample afresh): the base sample, whose list
+  // of b0 tokens this workgroup wrote at `base`, is kept as the head of the final sample, and the remaining
+  // c - b0 tokens are drawn with the stream of S among the residual tokens outside the base sample.  The base
+  // tokens are added to the bitmap of excluded tokens (bm, which S.bm_f points to) for that purpose.
+  static __device__ __forceinline__ int draw_nested(const Sampler& S, HeadSizes hs, uint32_t b0, uint32_t c,
+                                                    uint32_t* bm, const int32_t* base, int32_t* dst,
+                                                    uint32_t dst_cap, int small_batches, HeadSmem& sm) {
+    __syncthreads();  // the base list is complete (global memory is coherent inside a workgroup)
+    for (uint32_t t = threadIdx.x; t < b0; t += NT) {
+      const int tok = list_tok(base, t, hs.n);
+      mark_bit(bm, (uint32_t)tok);
+      if (t < dst_cap) dst[t] = tok;
+    }
+    __syncthreads();
+    if (c <= b0 || dst_cap <= b0) return 0;
+    hs.n_s -= (int)b0;
+    const DrawBatch none = {};
+    return draw_sample(S, hs, c - b0, none, false, small_batches, dst + b0, dst_cap - b0, nullptr, nullptr, sm);
   }
 };  // struct HeadOps
 
@@ -773,7 +794,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   S1.dbg = A.dbg ? A.dbg + 300 : nullptr;
   DrawBatch spec0 = {}, spec1 = {};
   const bool want0 = hs.n_s > 0 && A.phase != 2 && hs.b0 < hs.n_s;
-  const bool want1 = hs.n_s > 0 && A.phase != 1;
+  const bool want1 = hs.n_s > 0 && A.phase != 1 && !A.nested;  // (a nested final sample rarely draws at all)
   // The sub-tile maxima the score kernel left are requested before the sampler work: rows of up to 8 * NT
   // sub-tiles keep them in registers for the three passes below, longer rows stream them in every pass.
   constexpr int SU = 8;  // sub-tile maxima a thread has in flight
@@ -1117,6 +1138,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       r.k = hs.k;
       r.b = hs.n_s > 0 ? hs.b0 : 0;  // the statistics pass walks the base sample
       r.n_s = hs.n_s;
+      r.b_keep = 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -1195,8 +1217,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 7);
   // ---- I_dyn (Algorithm 1, line 7) ----
   if (bfin > 0) {
-    const int f = O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches,
-                                 idx + A.seg_dyn, (uint32_t)A.b_max, nullptr, nullptr, sm);
+    const int f = A.nested ? O::draw_nested(S1, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
+                                            idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
+                           : O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches,
+                                            idx + A.seg_dyn, (uint32_t)A.b_max, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
     VATT_STAMP(A.dbg, 8);
   }
@@ -1221,6 +1245,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     r.k = hs.k;
     r.b = bfin;
     r.n_s = hs.n_s;
+    r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
     A.head_rec[bh] = r;
   }
   VATT_STAMP(A.dbg, 9);
@@ -1344,6 +1369,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       r.k = k_eff;
       r.b = hs.b0;  // the score pass walks the base sample
       r.n_s = hs.n_s;
+      r.b_keep = 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -1421,8 +1447,10 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   }
   int flags = 0;
   if (bfin > 0) {
-    const int f = O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches, idx + A.seg_dyn,
-                                 (uint32_t)A.b_max, nullptr, nullptr, sm);
+    const int f = A.nested ? O::draw_nested(S, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
+                                            idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
+                           : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches, idx + A.seg_dyn,
+                                            (uint32_t)A.b_max, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
   }
   if (tid == 0) {
@@ -1452,6 +1480,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     r.k = k_eff;
     r.b = bfin;
     r.n_s = hs.n_s;
+    r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
     A.head_rec[bh] = r;
   }
 }
@@ -1549,6 +1578,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.b0_max = pl.b0_max;
   A.b_max = pl.b_max;
   A.q_len = pl.q_len;
+  A.nested = pl.nested_samples;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   A.given_idx = nullptr;
   A.given_cnt = nullptr;

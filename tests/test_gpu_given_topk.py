@@ -157,3 +157,20 @@ def test_given_topk_rejects_other_targets():
     with pytest.raises(VattError):
         _run_given(sess, wl, {(0, 0): np.arange(100, 130)})
     sess.close()
+
+
+def test_given_topk_with_nested_samples():
+    say("given top-k with nested samples")
+    from paper_2510_05688_amd import binding as vb
+    for over in (dict(), dict(epsilon=0.01, delta=0.01)):
+        wl = workloads.small_gqa(seed=47, batch=2, n=3008, seq_lens=[3008, 2963], **over)
+        sess = _session(wl)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, 1)
+        supplied = {(b, h): _oracle_topk(wl, b, h) for b in range(wl.batch) for h in range(wl.n_q_heads)}
+        res = _run_given(sess, wl, supplied)
+        params = dict(wl.params, nested=True)
+        reps = [check_head_given(wl, res, b, h, supplied[(b, h)], params=params, label="nested")
+                for b in range(wl.batch) for h in range(wl.n_q_heads)]
+        if over:
+            assert any(r["b"] > r["b0"] for r in reps)
+        sess.close()

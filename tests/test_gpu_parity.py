@@ -422,3 +422,31 @@ def test_hoeffding_type_budget():
     back = _run(sess)
     assert np.array_equal(back["counts"], clt["counts"]) and np.array_equal(back["b_star"], clt["b_star"])
     sess.close()
+
+
+@pytest.mark.parametrize("name,over", [
+    ("default", dict()),                                       # budgets at the base sample: nothing more is drawn
+    ("tight_eps", dict(epsilon=0.01, delta=0.01)),             # budgets well above the base sample
+    ("complement", dict(base_frac=0.2, epsilon=0.004)),        # the added tokens are taken as a complement
+    ("target_sdpa", dict(target=2, epsilon=0.3)),
+])
+def test_nested_samples(name, over):
+    say("nested samples: %s" % name)
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=43, batch=2, n=6000, **over)
+    sess = _session(wl)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, 1)
+    res = _run(sess)
+    reps = check_all(wl, res, params=dict(wl.params, nested=True), label="nested " + name)
+    seg = res["seg"]
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            b0, bb = int(res["counts"][b, h, 3]), int(res["counts"][b, h, 4])
+            # the final sample's list starts with the base sample, in the base sample's own order
+            assert np.array_equal(res["idx"][b, h, seg[4]:seg[4] + b0], res["idx"][b, h, seg[3]:seg[3] + b0])
+            assert bb >= b0
+    if name != "default":
+        assert any(r["b"] > r["b0"] for r in reps)
+    if name == "complement":
+        assert any(r["flags"] & 2 for r in reps)
+    sess.close()
