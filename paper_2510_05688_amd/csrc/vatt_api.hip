@@ -107,8 +107,10 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
 
   const int heads = pl.vbatch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
-  pl.gather_splits = std::min(32, std::max(1, (8 * pl.num_cus + heads - 1) / heads));
+  pl.gather_splits = std::min(32, std::max(1, (32 * pl.num_cus + heads - 1) / heads));  // measured: 32 workgroups per CU beat 8, 16 and 64
   pl.vstat_splits = pl.gather_splits;
+  // (the gather with a caller-supplied top-k also reads K rows and carries running maxima: fewer, longer splits)
+  pl.given_splits = std::min(pl.gather_splits, std::max(1, (8 * pl.num_cus + heads - 1) / heads));
   const int kv_heads = pl.vbatch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
   pl.dense_splits = std::min(std::min(128, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));

@@ -287,7 +287,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.idx_cap = (int64_t)pl.idx_cap;
   A.Hq = p.n_q_heads;
   A.group = pl.group;
-  A.splits = pl.gather_splits;
+  A.splits = pl.given_splits;
   A.sm_scale = pl.sm_scale;
   dim3 grid(A.splits, p.n_q_heads, p.batch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;

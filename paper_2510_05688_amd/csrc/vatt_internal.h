@@ -43,7 +43,7 @@ struct Plan {
   int n_sub;          // sub-tiles of kSubTile keys per row (the score kernel leaves each one's largest score)
   int k_max, b0_max, b_max;
   int head_threads;   // workgroup size of the per-head kernel
-  int gather_splits, dense_splits, vstat_splits;
+  int gather_splits, dense_splits, vstat_splits, given_splits;
   size_t idx_cap;
   int64_t seg_off[5];
   size_t head_lds_bytes;
