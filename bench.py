@@ -253,7 +253,7 @@ def main():
                     help="nested samples (an option beyond the paper): the final sample keeps the base sample")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense' or 'copy' (a 256 MiB device copy) in the timed loop")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the step shards by sequence and "
@@ -311,7 +311,11 @@ def main():
             # plain device copy of known size: calibrates the HBM byte counters of the profiler
             src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
             dsts = [torch.empty_like(src) for _ in range(4)]
-        fn = dict(decode=step, score=score_only, dense=dense,
+        from paper_2510_05688_amd import binding as vb3
+        sink0 = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+        read0 = lambda i: vb3.vatt_stream_read(ks[i % nbuf], int(ks[0].numel() * ks[0].element_size()), sink0,
+                                               torch.cuda.current_stream().cuda_stream)
+        fn = dict(decode=step, score=score_only, dense=dense, read=read0,
                   copy=lambda i: dsts[i % 4].copy_(src) if args.only == "copy" else None)[args.only]
         for i in range(args.warmup):
             fn(i)
@@ -334,6 +338,17 @@ def main():
     for i in range(args.warmup):
         dense(i)
     ms_dense = time_calls(dense, args.steps, torch)
+    # what a kernel that only reads takes for the bytes of the K scan, on the same cycled buffers
+    from paper_2510_05688_amd import binding as vb2
+    sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    k_bytes_all = int(ks[0].numel() * ks[0].element_size())
+
+    def read_only(i):
+        vb2.vatt_stream_read(ks[i % nbuf], k_bytes_all, sink, torch.cuda.current_stream().cuda_stream)
+
+    for i in range(args.warmup):
+        read_only(i)
+    ms_read = time_calls(read_only, args.steps, torch)
 
     # algorithmic bytes of one layer, from the returned counts
     n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
@@ -398,6 +413,9 @@ def main():
             "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get("config%d" % args.config),
             "bytes_per_launch": score_kernel_bytes,
             "us_per_launch": ms_score * 1e3,
+            # a kernel that only reads the K cache (vatt_stream_read), same buffers: the practical floor
+            "read_only_same_k_us": ms_read * 1e3,
+            "read_only_gbps": k_bytes_all / (ms_read * 1e-3) / 1e9,
         },
     }
     if not args.no_cpu:

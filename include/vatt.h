@@ -256,6 +256,14 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
 int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
                    const int32_t* block_table, int32_t* seq_lens, void* stream);
 
+/*
+ * Measurement aid (no part of the method): one kernel that reads `bytes` bytes (a multiple of 16) from the
+ * 16-byte aligned device buffer src and discards them.  Its duration is the practical floor for any single
+ * launch that must stream that many bytes from HBM, which is what the K scan is compared with.
+ *   sink    device, at least 4 KiB, may be written (practically never is)
+ */
+int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+
 const char* vatt_status_string(int status);
 
 #ifdef __cplusplus

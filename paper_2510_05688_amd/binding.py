@@ -35,7 +35,7 @@ VATT_BOUND_HOEFFDING = 1
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
-    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv",
+    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
     "vatt_status_string",
 ]
 
@@ -96,6 +96,8 @@ def _load():
     lib.vatt_score.restype = ctypes.c_int
     lib.vatt_append_kv.argtypes = [vp] * 8
     lib.vatt_append_kv.restype = ctypes.c_int
+    lib.vatt_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.vatt_stream_read.restype = ctypes.c_int
     lib.vatt_status_string.argtypes = [ctypes.c_int]
     lib.vatt_status_string.restype = ctypes.c_char_p
     return lib
@@ -223,3 +225,10 @@ def vatt_append_kv(plan, k_new, v_new, k, v, block_table, seq_lens, stream=None)
                              _ptr(seq_lens), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_append_kv")
+
+
+def vatt_stream_read(src, nbytes: int, sink, stream=None) -> None:
+    """Measurement aid: read nbytes of the device buffer src and discard them (sink: >= 4 KiB device buffer)."""
+    rc = _lib.vatt_stream_read(_ptr(src), int(nbytes), _ptr(sink), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_stream_read")

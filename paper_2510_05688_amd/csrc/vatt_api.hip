@@ -344,6 +344,12 @@ int vatt_dense_decode(vatt_plan* plan, const void* q, const void* k, const void*
   return VATT_OK;
 }
 
+int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || !aligned16(src) || (bytes & 15u) != 0) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
 int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
                    const int32_t* block_table, int32_t* seq_lens, void* stream) {
   if (!plan) return VATT_E_INVALID_ARG;

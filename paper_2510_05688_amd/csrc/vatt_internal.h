@@ -86,6 +86,8 @@ hipError_t launch_dense(const Plan& pl, const void* q, const void* k, const void
 hipError_t launch_append(const Plan& pl, const void* k_new, const void* v_new, void* k, void* v,
                          const int32_t* block_table, int32_t* seq_lens, hipStream_t st);
 hipError_t set_kernel_attributes(const Plan& pl);
+// Reads `bytes` (a multiple of 16) from src and discards them; sink is 4 KiB of device memory.
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 
 }  // namespace vatt
 
