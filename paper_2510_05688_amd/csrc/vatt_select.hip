@@ -727,6 +727,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
+  // The sub-tile maxima the score kernel left are requested first of all, before even the sequence length is
+  // known (what lies beyond the row's own sub-tiles is masked once it is): the kernel starts with a chain of
+  // dependent loads, and this takes one link out of it.  Rows of up to 8 * NT sub-tiles keep the maxima in
+  // registers for the three passes below, longer rows stream them in every pass.
+  constexpr int SU = 8;  // sub-tile maxima a thread has in flight
+  const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
+  float sub_reg[SU];
+#pragma unroll
+  for (int u = 0; u < SU; ++u) {
+    const int t = u * NT + tid;
+    sub_reg[u] = t < A.n_sub ? sub_max[t] : -INFINITY;
+  }
   // In a multi-query step b stands for (sequence, query token); query token t of q_len sees the sequence up to
   // and including itself, which leaves out the q_len - 1 - t newer tokens.
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;
@@ -795,18 +807,13 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   DrawBatch spec0 = {}, spec1 = {};
   const bool want0 = hs.n_s > 0 && A.phase != 2 && hs.b0 < hs.n_s;
   const bool want1 = hs.n_s > 0 && A.phase != 1 && !A.nested;  // (a nested final sample rarely draws at all)
-  // The sub-tile maxima the score kernel left are requested before the sampler work: rows of up to 8 * NT
-  // sub-tiles keep them in registers for the three passes below, longer rows stream them in every pass.
-  constexpr int SU = 8;  // sub-tile maxima a thread has in flight
   const int n_sub = (n + kSubTile - 1) / kSubTile;
-  const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
   const int sub_lo = (hs.mid_lo + kSubTile - 1) / kSubTile, sub_hi = hs.mid_hi / kSubTile;  // whole middle sub-tiles
   const bool sub_resident = n_sub <= SU * NT;
-  float sub_reg[SU];
 #pragma unroll
   for (int u = 0; u < SU; ++u) {
     const int t = u * NT + tid;
-    sub_reg[u] = (sub_resident && t < n_sub) ? sub_max[t] : -INFINITY;
+    sub_reg[u] = (sub_resident && t < n_sub) ? sub_reg[u] : -INFINITY;
   }
   // g(maxima[SU], first sub-tile of the batch): slot u is sub-tile first + u * NT + tid, -inf beyond the row
   auto each_sub_batch = [&](auto&& g) {
