@@ -150,7 +150,11 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * score row, which otherwise only serves short or unusual rows; results are identical.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5 };
+       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6 };
+/*
+ * VATT_OPT_HEAD_THREADS (test hook): workgroup size of the selection kernel, 512 or 1024.  The plan picks 512
+ * for n_max <= 32768 and 1024 for longer rows; results are identical.  To be set on the plan's device.
+ */
 /*
  * VATT_OPT_NESTED_SAMPLES = 1 departs from Algorithm 1, which draws the final sample afresh: the base sample
  * is kept as the head of the final sample and only b - b0 further tokens are drawn (stream 1) among the

@@ -103,7 +103,8 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
 
-  pl.head_threads = kHeadThreads;
+  // rows of up to 8 maxima per thread keep them in registers: 32768 tokens with 512 threads, 65536 with 1024
+  pl.head_threads = n_max > 8 * kHeadThreads * kSubTile ? kHeadThreadsLong : kHeadThreads;
 
   const int heads = pl.vbatch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
@@ -247,6 +248,16 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   }
   if (option == VATT_OPT_TOPK_GENERAL_PATH) {
     plan->pl.topk_general_path = value ? 1 : 0;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_HEAD_THREADS) {
+    Plan& pl = plan->pl;
+    if (value != kHeadThreads && value != kHeadThreadsLong) return VATT_E_INVALID_ARG;
+    const size_t lds = head_kernel_lds_bytes(pl.p.n_max, value);
+    if (lds + head_kernel_static_lds_bytes() > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
+    pl.head_threads = value;
+    pl.head_lds_bytes = lds;
+    if (pl.device >= 0 && set_kernel_attributes(pl) != hipSuccess) return VATT_E_HIP;
     return VATT_OK;
   }
   if (option == VATT_OPT_NESTED_SAMPLES) {

@@ -15,6 +15,7 @@ constexpr int kScoreTile = 64;        // keys per score-kernel workgroup (small 
 constexpr int kScoreTilePaged = 256;  // keys per score-kernel workgroup on a paged cache
 constexpr int kSubTile = 8;            // keys per sub-tile maximum
 constexpr int kHeadThreads = 512;      // workgroup size of the per-head kernel
+constexpr int kHeadThreadsLong = 1024; // ... for rows whose 8-key maxima do not fit the registers of 512 threads
 constexpr int kGatherThreads = 256;
 constexpr int kDenseThreads = 256;
 

@@ -306,7 +306,8 @@ struct HeadOps {
         use_spec = false;
       } else {
         const uint32_t remaining = target - have;
-        const int blocks = (small_batches || remaining <= 128u) ? kSmallBatchBlocks : min(NT, 256);
+        const int blocks = (small_batches || remaining <= 128u) ? kSmallBatchBlocks
+                                                                  : (remaining > 1024u ? min(NT, 1024) : min(NT, 256));
         make_batch(B, S, hs, blk, blocks, blk > 0, false, sm);
       }
       ++batches;
@@ -710,7 +711,8 @@ struct TopkOps {
 // Philox blocks of the batch that is generated ahead, before the top-k set is known.
 template <int NT>
 __device__ __forceinline__ int ahead_blocks(int small_batches) {
-  return small_batches ? kSmallBatchBlocks : min(NT, 256);
+  // (a workgroup of 1024 threads serves long rows, whose samples hold thousands of tokens)
+  return small_batches ? kSmallBatchBlocks : (NT >= 1024 ? 1024 : min(NT, 256));
 }
 
 // NT = workgroup size.
@@ -731,7 +733,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // known (what lies beyond the row's own sub-tiles is masked once it is): the kernel starts with a chain of
   // dependent loads, and this takes one link out of it.  Rows of up to 8 * NT sub-tiles keep the maxima in
   // registers for the three passes below, longer rows stream them in every pass.
-  constexpr int SU = 8;  // sub-tile maxima a thread has in flight
+  constexpr int SU = NT >= 1024 ? 16 : 8;  // sub-tile maxima a thread has in flight (rows up to 131072 / 32768 tokens)
   const float* sub_max = A.sub_max + (int64_t)bh * A.n_sub;
   float sub_reg[SU];
 #pragma unroll
@@ -1496,7 +1498,7 @@ typedef void (*HeadKernel)(HeadArgs);
 // The instantiation for a plan: (workgroup size, scores per thread kept in registers).
 HeadKernel head_kernel_for(const Plan& pl) {
   (void)pl;
-  return head_kernel<kHeadThreads>;
+  return pl.head_threads == kHeadThreadsLong ? head_kernel<kHeadThreadsLong> : head_kernel<kHeadThreads>;
 }
 
 }  // namespace
@@ -1511,7 +1513,8 @@ hipError_t set_kernel_attributes(const Plan& pl) {
 
 size_t head_kernel_lds_bytes(int n_max, int head_threads) {
   const size_t words_max = ((size_t)(n_max + 63) >> 6) << 1;
-  const size_t fixed = sizeof(HeadOps<kHeadThreads>::HeadSmem);
+  const size_t fixed = head_threads == kHeadThreadsLong ? sizeof(HeadOps<kHeadThreadsLong>::HeadSmem)
+                                                        : sizeof(HeadOps<kHeadThreads>::HeadSmem);
   return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * (sizeof(uint64_t) + sizeof(uint32_t)) +
          6 * words_max * sizeof(uint32_t);
 }

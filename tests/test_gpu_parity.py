@@ -450,3 +450,24 @@ def test_nested_samples(name, over):
     if name == "complement":
         assert any(r["flags"] & 2 for r in reps)
     sess.close()
+
+
+def test_selection_kernel_with_1024_threads_gives_identical_results():
+    say("selection kernel with 1024 threads (the variant for rows longer than 32768 tokens)")
+    from paper_2510_05688_amd import binding as vb
+    cases = (workloads.small_gqa(seed=71, batch=2, n=9000, epsilon=0.02),
+             workloads.small_gqa(seed=72, batch=2, n=700, seq_lens=[700, 33], base_frac=0.3),
+             workloads.small_gqa(seed=73, batch=1, n=20000, base_frac=0.3, epsilon=0.004),     # several big batches
+             workloads.small_gqa(seed=74, batch=1, n=6000, target=2, epsilon=0.3))
+    for wl in cases:
+        sess = _session(wl)
+        narrow = _run(sess)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 1024)
+        wide = _run(sess)
+        _same_results(wl, narrow, wide)
+        check_all(wl, wide, label="1024-threads")
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 1)
+        _same_results(wl, narrow, _run(sess))
+        with pytest.raises(vb.VattError):
+            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 768)
+        sess.close()
