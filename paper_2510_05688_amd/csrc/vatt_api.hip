@@ -103,8 +103,14 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
 
-  // rows of up to 8 maxima per thread keep them in registers: 32768 tokens with 512 threads, 65536 with 1024
-  pl.head_threads = n_max > 8 * kHeadThreads * kSubTile ? kHeadThreadsLong : kHeadThreads;
+  // Rows of up to 32768 tokens keep their 8-key maxima in the registers of 512 threads, and two such workgroups
+  // share a CU.  Longer rows get 1024 threads when that costs no parallelism: when only one workgroup fits a
+  // CU's LDS anyway, or when there are no more heads than CUs.
+  pl.head_threads = kHeadThreads;
+  if (n_max > 8 * kHeadThreads * kSubTile &&
+      (2 * (head_kernel_lds_bytes(n_max, kHeadThreads) + head_kernel_static_lds_bytes()) > 160 * 1024 ||
+       pl.vbatch * p.n_q_heads <= pl.num_cus))
+    pl.head_threads = kHeadThreadsLong;
 
   const int heads = pl.vbatch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
