@@ -178,6 +178,24 @@ def chunk_bench(args, torch, np, workloads, DecodeSession):
         for _ in range(Q):
             single.decode(k=ks[i % nbuf], v=vs[i % nbuf])
 
+    if args.given_topk:
+        # the exact top-k sets of the scored path stand in for an approximate top-k method's output
+        from paper_2510_05688_amd import binding as vb
+        seg2, seg3 = vb.vatt_plan_index_segment(sess.plan, 2), vb.vatt_plan_index_segment(sess.plan, 3)
+        sess.decode()
+        topk_idx = sess.out_idx[:, :, seg2:seg3].contiguous()
+        topk_cnt = sess.out_counts[:, :, 2].contiguous()
+        single.decode()
+        s_idx = single.out_idx[:, :, seg2:seg3].contiguous()
+        s_cnt = single.out_counts[:, :, 2].contiguous()
+
+        def step(i):  # noqa: F811
+            sess.decode_given_topk(topk_idx, topk_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
+
+        def singles(i):  # noqa: F811
+            for _ in range(Q):
+                single.decode_given_topk(s_idx, s_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
+
     if args.only:
         fn = dict(decode=step, score=score_only, dense=dense)[args.only]
         for i in range(args.warmup):
@@ -202,11 +220,13 @@ def chunk_bench(args, torch, np, workloads, DecodeSession):
     select_r = 2 * submax_w + int(((counts[:, 2] + 2 * counts[:, 3] + b_dyn) * 32).sum())
     gather_r = int(((n_f + b_dyn) * 8).sum())
     path_bytes = k_scan + score_w + submax_w + select_r + gather_r + v_rows
+    if args.given_topk:
+        path_bytes = int(((n_f + counts[:, 3] + b_dyn) * d * 2).sum()) + v_rows + int(((n_f + counts[:, 3] + b_dyn) * 12).sum())
     score_kernel_bytes = k_scan + score_w + submax_w + B * Q * Hq * d * 2
     score_flops = 2.0 * Q * Hq * d * float(seq_n.sum())
     us = timed["step"] * 1e3
     out = {
-        "metric": "vattention_chunk_us_per_layer", "value": us, "unit": "us", "n_gpus": 1, "steps": args.steps,
+        "metric": "vattention_chunk_us_per_layer" + ("_given_topk" if args.given_topk else ""), "value": us, "unit": "us", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": timed["step"], "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name + "_q%d" % Q, "accumulate": "fp32", "batch": B, "q_len": Q, "n_q_heads": Hq,

@@ -133,7 +133,7 @@ void vatt_plan_destroy(vatt_plan* plan);
  * With such a plan every "[B, ...]" shape of q and of the outputs of vatt_decode, vatt_dense_decode and
  * vatt_score reads "[B, q_len, ...]" (seq_lens, seq_seeds, block_table and the caches stay per sequence,
  * and every seq_lens entry should be at least q_len: a query with no visible token is treated as seeing
- * one), and vatt_decode_given_topk returns VATT_E_UNSUPPORTED_SHAPE.  q_len = 1 is vatt_plan_create.
+ * one); the same holds for topk_idx and topk_cnt of vatt_decode_given_topk.  q_len = 1 is vatt_plan_create.
  * q_len * (n_q_heads / n_kv_heads) may not exceed 64 and batch * q_len may not exceed 65535
  * (VATT_E_UNSUPPORTED_SHAPE).
  */

@@ -338,7 +338,7 @@ int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const 
     return VATT_E_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
-  if (pl.p.target != VATT_TARGET_D || pl.q_len != 1) return VATT_E_UNSUPPORTED_SHAPE;
+  if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
                                   out_budget_raw, out_stats, st));

@@ -38,6 +38,7 @@ struct GivenArgs {
   float* out_lse;
   int64_t seg_sink, seg_win, seg_topk, seg_base, seg_dyn, idx_cap;
   int Hq, group, splits;
+  int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
   float sm_scale;
 };
 
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
         bool tail;
         place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail);
         tok = min(max(tok, 0), r.n - 1);
-        kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
+        kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok) + sub * 8);
       }
     }
 #pragma unroll
@@ -177,9 +178,9 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
         tok = min(max(tok, 0), r.n - 1);
         // scores are at hand for I_f and, with nested samples, for the base-sample head of the final sample
         known[u] = !tail[u] || place - A.seg_dyn < (int64_t)r.b_keep;
-        if (!known[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b, kvh, tok) + sub * 8);
+        if (!known[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok) + sub * 8);
         else s[u] = sp[tail[u] ? A.seg_base + (place - A.seg_dyn) : place];
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b, kvh, tok) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok) + sub * 8);
       }
     }
 #pragma unroll
@@ -288,8 +289,9 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.Hq = p.n_q_heads;
   A.group = pl.group;
   A.splits = pl.given_splits;
+  A.q_len = pl.q_len;
   A.sm_scale = pl.sm_scale;
-  dim3 grid(A.splits, p.n_q_heads, p.batch);
+  dim3 grid(A.splits, p.n_q_heads, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
   if (stage == 0) {
     if (paged) hipLaunchKernelGGL((sparse_score_kernel<D, true>), grid, dim3(kGatherThreads), 0, st, A);
@@ -300,7 +302,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   else hipLaunchKernelGGL((given_gather_kernel<D, false>), grid, dim3(kGatherThreads), 0, st, A);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((given_merge_kernel<D>), dim3(p.n_q_heads, p.batch), dim3(D), 0, st, A.part, A.splits,
+  hipLaunchKernelGGL((given_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(D), 0, st, A.part, A.splits,
                      p.n_q_heads, out_o, out_lse);
   return hipGetLastError();
 }

@@ -1285,7 +1285,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
-  const int n = min(max(A.seq_lens[b], 1), A.n_max);
+  const int seq = b / A.q_len, qtok = b - seq * A.q_len;  // (sequence, query token) of a multi-query step
+  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
   HeadSizes hs = head_sizes(n, A.sp);
   const int words_max = ((A.n_max + 63) >> 6) << 1;
   const int words = (n + 31) >> 5;
@@ -1330,10 +1331,10 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   S.bm_f = bm_f;
   S.wpre = wpre;
   S.row = nullptr;
-  S.seed = A.seq_seeds[b];
+  S.seed = A.seq_seeds[seq];
   S.stream = A.phase == 0 ? 0u : 1u;
   S.head = (uint32_t)h;
-  S.query = 0u;
+  S.query = (uint32_t)qtok;
   S.L = (uint32_t)max(mid_len, 1);
   S.thr = (uint32_t)((0x100000000ull - (uint64_t)S.L) % (uint64_t)S.L);
   {
@@ -1532,7 +1533,7 @@ hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_len
   fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
   A.given_idx = given_idx;
   A.given_cnt = given_cnt;
-  hipLaunchKernelGGL(given_topk_kernel<kHeadThreads>, dim3(pl.p.n_q_heads, pl.p.batch), dim3(kHeadThreads),
+  hipLaunchKernelGGL(given_topk_kernel<kHeadThreads>, dim3(pl.p.n_q_heads, pl.vbatch), dim3(kHeadThreads),
                      pl.head_lds_bytes, st, A);
   return hipGetLastError();
 }

@@ -179,3 +179,40 @@ def test_chunk_at_config2_size_sampled_heads():
         assert np.all(res["counts"][v, :, 6] == n_v)
         assert np.all(res["counts"][v, :, 2] == vo.topk_count(n_v, 128, 128, 0, wl.params["topk_frac"]))
     sess.close()
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_chunk_with_caller_supplied_topk(paged):
+    # multi-query step without the score pass: the caller supplies a top-k set per (query token, head); here the
+    # oracle's exact top-k of a noisy copy of the scores, as an approximate top-k method would give
+    say("chunk with caller-supplied top-k (paged=%s)" % paged)
+    from parity import check_head_given
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=27, n=3008, seq_lens=[3008, 2001], epsilon=0.02)
+    q_len = 3
+    q_bits = workloads.chunk_queries(wl, q_len, seed=9)
+    sess = _chunk_session(wl, q_bits, q_len, paged=paged)
+    cv = ChunkView(wl, q_bits, q_len)
+    k_max = vb.vatt_plan_index_segment(sess.plan, 3) - vb.vatt_plan_index_segment(sess.plan, 2)
+    rng = np.random.default_rng(12)
+    g = wl.n_q_heads // wl.n_kv_heads
+    p = wl.params
+    supplied = {}
+    idx = np.full((cv.batch, wl.n_q_heads, max(k_max, 1)), -3, dtype=np.int32)
+    cnt = np.zeros((cv.batch, wl.n_q_heads), dtype=np.int32)
+    for v in range(cv.batch):
+        n = int(cv.seq_lens[v])
+        for h in range(wl.n_q_heads):
+            s = vo.scores(cv.q_f32()[v, h].astype(np.float64), cv.k_f32(v, h // g, n).astype(np.float64), p["sm_scale"])
+            s = s + rng.normal(0.0, 0.3, size=s.shape)
+            k = vo.topk_count(n, int(p["sink"]), int(p["window"]), int(p.get("topk_abs", 0)), float(p.get("topk_frac", 0.0)))
+            top = vo.deterministic_set(s, int(p["sink"]), int(p["window"]), k)[2][:k_max]
+            supplied[(v, h)] = top
+            idx[v, h, :len(top)] = rng.permutation(top)
+            cnt[v, h] = len(top)
+    sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
+    res = sess.results_host()
+    reps = [check_head_given(cv, res, v, h, supplied[(v, h)], label="chunk given")
+            for v in range(cv.batch) for h in range(wl.n_q_heads)]
+    assert any(r["b"] > r["b0"] for r in reps)
+    sess.close()
