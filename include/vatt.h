@@ -230,7 +230,8 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v,
  * follows Algorithm 1 as in vatt_decode: residual, base sample, statistics, budget, final sample, estimate.
  * Scores exist only for I_f, I_bs and I_dyn; out_stats and out_lse use the largest score among I_f and I_bs
  * as the shift (every quantity Algorithm 2 forms is a ratio and does not depend on it).
- * Only the denominator target is supported (VATT_E_UNSUPPORTED_SHAPE otherwise).  Other arguments as in vatt_decode.
+ * With the targets N and SDPA the score kernel of the listed tokens also reads their V rows for the numerator
+ * statistics of Algorithm 2.  Other arguments as in vatt_decode.
  */
 int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const void* v,
                            const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,

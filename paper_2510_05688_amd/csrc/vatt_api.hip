@@ -338,11 +338,10 @@ int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const 
     return VATT_E_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
-  if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
                                   out_budget_raw, out_stats, st));
-  VATT_LAUNCH(launch_sparse_score(pl, q, k, block_table, workspace, out_idx, st));
+  VATT_LAUNCH(launch_sparse_score(pl, q, k, v, block_table, workspace, out_idx, st));
   VATT_LAUNCH(launch_given_select(pl, 1, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
                                   out_budget_raw, out_stats, st));
   VATT_LAUNCH(launch_given_gather(pl, q, k, v, block_table, workspace, out_idx, out_o, out_lse, st));

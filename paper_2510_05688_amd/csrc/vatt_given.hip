@@ -34,6 +34,7 @@ struct GivenArgs {
   const int32_t* idx;
   float* sparse;      // [B*Hq][idx_cap]: score of the token at the same place of the index lists
   float* part;        // [B*Hq][splits][d + 4]: N[d], D, running maximum
+  float* vstat;       // [B*Hq][splits][2d + 4]: N_f[d], R1[d], R2, maximum (numerator statistics, targets N / SDPA)
   float* out_o;
   float* out_lse;
   int64_t seg_sink, seg_win, seg_topk, seg_base, seg_dyn, idx_cap;
@@ -86,18 +87,22 @@ __device__ __forceinline__ float row_score(const uint4& kv, const uint32_t (&qw)
   return group_sum<LPR>(a) * sm_scale + 0.0f;
 }
 
-// Scores of the tokens of I_f and I_bs (HeadRec.b holds |I_bs| at this point).
-template <int D, bool PAGED>
+// Scores of the tokens of I_f and I_bs (HeadRec.b holds |I_bs| at this point).  With STATS (targets N and
+// SDPA) the V rows of the same tokens are read as well and the numerator statistics of Algorithm 2 are
+// accumulated on the way: N_f = sum_{I_f} w V, R1 = sum_{I_bs} w V, R2 = sum_{I_bs} ||w V||^2 with
+// w = exp(s - max); no maximum is known yet, so every lane group keeps a running one and rescales.
+template <int D, bool PAGED, bool STATS>
 __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs A) {
   constexpr int LPR = D / 8;
   constexpr int RPW = kWave / LPR;
   constexpr int WAVES = kGatherThreads / kWave;
   constexpr int RPB = RPW * WAVES;
+  constexpr int GROUPS = RPB;
   constexpr int U = 8;
   const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
   const HeadRec r = A.head_rec[bh];
   const int32_t* idx = A.idx + (int64_t)bh * A.idx_cap;
@@ -107,27 +112,101 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
   const int p_lo = split * per, p_hi = min(p_lo + per, total);
   uint32_t qw[4];
   load_q<D>(A, bh, sub, qw);
+  float acc_f[8], acc_b[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc_f[c] = acc_b[c] = 0.f;
+  float r2 = 0.f, m_run = -INFINITY;
   for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
     int64_t place[U];
-    uint4 kv[U];
+    bool tail[U];
+    uint4 kv[U], vv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int p = p0 + u * RPB;
       place[u] = -1;
+      tail[u] = false;
       kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      vv[u] = make_uint4(0u, 0u, 0u, 0u);
       if (p < p_hi) {
         int tok;
-        bool tail;
-        place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail);
+        place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail[u]);
         tok = min(max(tok, 0), r.n - 1);
         kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok) + sub * 8);
+        if (STATS) vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok) + sub * 8);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const float s = row_score<LPR>(kv[u], qw, A.sm_scale);
       if (place[u] >= 0 && sub == 0) sp[place[u]] = s;
+      if (STATS && place[u] >= 0) {
+        if (s > m_run) {
+          const float f = __expf(m_run - s);  // 0 when m_run is -inf
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            acc_f[c] *= f;
+            acc_b[c] *= f;
+          }
+          r2 *= f * f;
+          m_run = s;
+        }
+        const float wt = __expf(s - m_run);
+        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float x = wt * bf16_lo(ww[c]), y = wt * bf16_hi(ww[c]);
+          if (tail[u]) {
+            acc_b[2 * c] += x;
+            acc_b[2 * c + 1] += y;
+            r2 += x * x + y * y;
+          } else {
+            acc_f[2 * c] += x;
+            acc_f[2 * c + 1] += y;
+          }
+        }
+      }
     }
+  }
+  if (!STATS) return;
+  // every lane group has its own (maximum, N_f, R1, R2 share): bring them to the workgroup's maximum and add
+  __shared__ float s_f[STATS ? GROUPS : 1][STATS ? D : 1], s_b[STATS ? GROUPS : 1][STATS ? D : 1];
+  __shared__ float s_r2[GROUPS][LPR], s_m[GROUPS];
+  const int g = wave * RPW + rsub;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    s_f[g][sub * 8 + c] = acc_f[c];
+    s_b[g][sub * 8 + c] = acc_b[c];
+  }
+  s_r2[g][sub] = r2;
+  if (sub == 0) s_m[g] = m_run;
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < GROUPS; ++j) M = fmaxf(M, s_m[j]);
+  float* out = A.vstat + ((int64_t)bh * A.splits + split) * (2 * D + 4);
+  if (tid < D) {
+    float a = 0.f, c2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < GROUPS; ++j) {
+      const float f = s_m[j] > -INFINITY ? __expf(s_m[j] - M) : 0.f;
+      a += s_f[j][tid] * f;
+      c2 += s_b[j][tid] * f;
+    }
+    out[tid] = a;
+    out[D + tid] = c2;
+  }
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < GROUPS; ++j) {
+      const float f = s_m[j] > -INFINITY ? __expf(s_m[j] - M) : 0.f;
+      float q2 = 0.f;
+#pragma unroll
+      for (int c = 0; c < LPR; ++c) q2 += s_r2[j][c];
+      t += q2 * f * f;
+    }
+    out[2 * D] = t;
+    out[2 * D + 1] = M;
   }
 }
 
@@ -278,6 +357,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.idx = out_idx;
   A.sparse = reinterpret_cast<float*>(w + pl.off_sparse);
   A.part = reinterpret_cast<float*>(w + pl.off_gather_part);
+  A.vstat = reinterpret_cast<float*>(w + pl.off_vstat_part);
   A.out_o = out_o;
   A.out_lse = out_lse;
   A.seg_sink = pl.seg_off[0];
@@ -294,8 +374,11 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   dim3 grid(A.splits, p.n_q_heads, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
   if (stage == 0) {
-    if (paged) hipLaunchKernelGGL((sparse_score_kernel<D, true>), grid, dim3(kGatherThreads), 0, st, A);
-    else hipLaunchKernelGGL((sparse_score_kernel<D, false>), grid, dim3(kGatherThreads), 0, st, A);
+    const bool stats = p.target != VATT_TARGET_D;
+    if (paged && stats) hipLaunchKernelGGL((sparse_score_kernel<D, true, true>), grid, dim3(kGatherThreads), 0, st, A);
+    else if (paged) hipLaunchKernelGGL((sparse_score_kernel<D, true, false>), grid, dim3(kGatherThreads), 0, st, A);
+    else if (stats) hipLaunchKernelGGL((sparse_score_kernel<D, false, true>), grid, dim3(kGatherThreads), 0, st, A);
+    else hipLaunchKernelGGL((sparse_score_kernel<D, false, false>), grid, dim3(kGatherThreads), 0, st, A);
     return hipGetLastError();
   }
   if (paged) hipLaunchKernelGGL((given_gather_kernel<D, true>), grid, dim3(kGatherThreads), 0, st, A);
@@ -309,10 +392,10 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
 
 }  // namespace
 
-hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table, void* ws,
-                               const int32_t* out_idx, hipStream_t st) {
-  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 0, q, k, nullptr, block_table, ws, out_idx, nullptr, nullptr, st);
-  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 0, q, k, nullptr, block_table, ws, out_idx, nullptr, nullptr, st);
+hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const void* v,
+                               const int32_t* block_table, void* ws, const int32_t* out_idx, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 0, q, k, v, block_table, ws, out_idx, nullptr, nullptr, st);
+  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 0, q, k, v, block_table, ws, out_idx, nullptr, nullptr, st);
   return hipErrorInvalidValue;
 }
 

@@ -73,8 +73,9 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
 hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
                                const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
                                int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st);
-hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table, void* ws,
-                               const int32_t* out_idx, hipStream_t st);
+// (with targets N and SDPA it also reads the V rows of the listed tokens and leaves the numerator statistics)
+hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const void* v,
+                               const int32_t* block_table, void* ws, const int32_t* out_idx, hipStream_t st);
 hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
                                const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
                                float* out_lse, hipStream_t st);

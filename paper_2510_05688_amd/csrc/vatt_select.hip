@@ -66,6 +66,8 @@ struct HeadArgs {
   const uint64_t* seq_seeds;
   HeadRec* head_rec;
   const double* vstat_part;  // [B*Hq][vstat_splits][2d+2] (targets N, SDPA)
+  const float* given_vstat;  // [B*Hq][given_splits][2d+4]: N_f[d], R1[d], R2, maximum (given-top-k path)
+  int given_splits;
   int32_t* out_idx;
   int32_t* out_counts;
   double* out_budget_raw;
@@ -1439,7 +1441,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   double sums[3] = {acc_f, acc_w, acc_w2};
   O::block_sum(sums, sm);
   const double D_f = sums[0];
-  double sigma2 = 0.0, b_star = 0.0, D_hat = D_f;
+  double sigma2 = 0.0, b_star = 0.0, D_hat = D_f, tr_sigma = 0.0, nhat_sq = 0.0;
   int bfin = 0;
   if (hs.n_s > 0) {
     const double b0d = (double)hs.b0, ns = (double)hs.n_s;
@@ -1447,8 +1449,49 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     sigma2 = hs.b0 > 1 ? fmax(sums[2] - sums[1] * w_bar, 0.0) / (b0d - 1.0) : 0.0;
     D_hat = D_f + ns * w_bar;
     const double rho_D = ns * sqrt(sigma2) / D_hat;
-    const double t = A.z_half * rho_D / A.eps;
-    b_star = t * t;
+    double rho_N = 0.0;
+    if (A.target != VATT_TARGET_D) {
+      // numerator statistics left by the score kernel of the listed tokens, one partial per split, each in
+      // units of its own maximum: brought to the head's maximum m (the largest of them) and added
+      const int d = A.head_dim;
+      const int stride = 2 * d + 4;
+      const float* vp = A.given_vstat + (int64_t)bh * A.given_splits * stride;
+      double t3[3] = {0.0, 0.0, 0.0};
+      if (tid < d) {
+        double nf = 0.0, r1 = 0.0;
+        for (int s2 = 0; s2 < A.given_splits; ++s2) {
+          const float ms = vp[s2 * stride + 2 * d + 1];
+          const double f = ms > -INFINITY ? exp((double)ms - (double)m) : 0.0;
+          nf += (double)vp[s2 * stride + tid] * f;
+          r1 += (double)vp[s2 * stride + d + tid] * f;
+        }
+        const double nh = nf + ns * r1 / b0d;
+        t3[0] = nh * nh;
+        t3[1] = r1 * r1;
+      }
+      if (tid == 0) {
+        for (int s2 = 0; s2 < A.given_splits; ++s2) {
+          const float ms = vp[s2 * stride + 2 * d + 1];
+          const double f = ms > -INFINITY ? exp((double)ms - (double)m) : 0.0;
+          t3[2] += (double)vp[s2 * stride + 2 * d] * f * f;
+        }
+      }
+      O::block_sum(t3, sm);
+      nhat_sq = t3[0];
+      tr_sigma = hs.b0 > 1 ? fmax(t3[2] - t3[1] / b0d, 0.0) / (b0d - 1.0) : 0.0;
+      const double num = ns * sqrt(tr_sigma), nn = sqrt(nhat_sq);
+      rho_N = nn > 0.0 ? num / nn : (num > 0.0 ? INFINITY : 0.0);
+    }
+    if (A.target == VATT_TARGET_D) {
+      const double t = A.z_half * rho_D / A.eps;
+      b_star = t * t;
+    } else if (A.target == VATT_TARGET_N) {
+      const double t = A.z_half * rho_N / A.eps;
+      b_star = t * t;
+    } else {
+      const double t = 2.0 * A.z_quarter * (rho_D + rho_N) / A.eps;
+      b_star = t * t;
+    }
     const int cap = (int)ceil(A.cap_frac * ns);
     int want = hs.n_s;
     if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
@@ -1478,7 +1521,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       float* st = A.out_stats + (int64_t)bh * 4;
       st[0] = (float)D_hat;
       st[1] = (float)sigma2;
-      st[2] = st[3] = 0.f;
+      st[2] = (float)tr_sigma;
+      st[3] = (float)nhat_sq;
       // (in units of exp(-m) with m the largest score among I_f and I_bs, which is HeadRec.m and out_lse's shift)
     }
     HeadRec r;
@@ -1593,6 +1637,8 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   A.given_idx = nullptr;
   A.given_cnt = nullptr;
+  A.given_vstat = reinterpret_cast<const float*>(w + pl.off_vstat_part);
+  A.given_splits = pl.given_splits;
   A.sparse = reinterpret_cast<const float*>(w + pl.off_sparse);
 }
 

@@ -150,15 +150,6 @@ def test_given_topk_other_head_shapes(d, hq, hkv):
     sess.close()
 
 
-def test_given_topk_rejects_other_targets():
-    from paper_2510_05688_amd.binding import VattError
-    wl = workloads.small_gqa(seed=44, batch=1, n=1500, target=2)
-    sess = _session(wl)
-    with pytest.raises(VattError):
-        _run_given(sess, wl, {(0, 0): np.arange(100, 130)})
-    sess.close()
-
-
 def test_given_topk_with_nested_samples():
     say("given top-k with nested samples")
     from paper_2510_05688_amd import binding as vb
@@ -173,4 +164,22 @@ def test_given_topk_with_nested_samples():
                 for b in range(wl.batch) for h in range(wl.n_q_heads)]
         if over:
             assert any(r["b"] > r["b0"] for r in reps)
+        sess.close()
+
+
+@pytest.mark.parametrize("target,eps", [(1, 0.2), (2, 0.3)])
+def test_given_topk_numerator_and_sdpa_targets(target, eps):
+    # values with a mean component, so that the numerator budgets stay below the residual size
+    say("given top-k, target %d" % target)
+    from workloads.configs import default_params
+    p = default_params(128, sink=16, window=24, target=target, epsilon=eps)
+    wl = workloads.make_workload("given_mean_v", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, n_max=4096,
+                                 seq_lens=[4096, 3333], seed=53, params=p, v_mean=1.0, all_flat=True)
+    for paged in (False, True):
+        sess = _session(wl, paged=paged)
+        supplied = {(b, h): _oracle_topk(wl, b, h) for b in range(wl.batch) for h in range(wl.n_q_heads)}
+        res = _run_given(sess, wl, supplied)
+        reps = [check_head_given(wl, res, b, h, supplied[(b, h)], label="given target %d" % target)
+                for b in range(wl.batch) for h in range(wl.n_q_heads)]
+        assert any(r["b0"] < r["b"] < r["oracle"]["n_s"] for r in reps)
         sess.close()
