@@ -33,13 +33,20 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
   const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int n = min(max(seq_lens[b], 0), n_max);
   const int tile_lo = tile * TILE;
-  if (tile_lo >= n) return;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR;   // which 8-column slice of the row
   const int rsub = lane / LPR;  // which row of the wave load
+  // On a paged cache the block-table entries of the first rows are requested before the sequence length is
+  // looked at (entries beyond it are never used): one link less in the chain length -> table -> K row.
+  int64_t first_off[PAGED ? BATCH : 1];
+  if constexpr (PAGED) {
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u)
+      first_off[u] = kv_row_offset<true>(L, b, kvh, min(tile_lo + wave * ROWS_PER_WAVE + u * RPW + rsub, n_max - 1));
+  }
+  const int n = min(max(seq_lens[b], 0), n_max);
+  if (tile_lo >= n) return;
 
   __shared__ float s_tile[G][TILE];
 
@@ -61,7 +68,10 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       const int row = wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
       const int i = tile_lo + row;
       if (i < n) {
-        kv[u] = load_stream_16(k + kv_row_offset<PAGED>(L, b, kvh, i) + sub * 8);
+        int64_t off;
+        if constexpr (PAGED) off = u0 == 0 ? first_off[u] : kv_row_offset<true>(L, b, kvh, i);
+        else off = kv_row_offset<false>(L, b, kvh, i);
+        kv[u] = load_stream_16(k + off + sub * 8);
       } else {
         kv[u] = make_uint4(0u, 0u, 0u, 0u);
       }
