@@ -1,0 +1,72 @@
+"""GPU parity on seeded random configurations: shapes, lengths, layouts and every parameter of Algorithm 1
+drawn at random, small enough for the oracle to check every head."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from workloads.configs import default_params
+from parity import ChunkView, check_all, say
+from util import plan_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw_case(rng):
+    d = int(rng.choice([64, 128]))
+    g = int(rng.choice([1, 2, 4, 8]))
+    hkv = int(rng.choice([1, 2]))
+    n_max = int(rng.choice([48, 130, 517, 1000, 2048, 3100, 4500])) // 16 * 16
+    batch = int(rng.integers(1, 4))
+    lens = [int(rng.integers(1, n_max + 1)) for _ in range(batch)]
+    lens[0] = n_max
+    over = dict(
+        sink=int(rng.choice([0, 1, 4, 16, 100])), window=int(rng.choice([0, 1, 8, 24, 200])),
+        epsilon=float(rng.choice([0.3, 0.1, 0.05, 0.02, 0.008])), delta=float(rng.choice([0.3, 0.1, 0.05, 0.01])),
+        target=int(rng.choice([0, 0, 0, 1, 2])), budget_cap_frac=float(rng.choice([1.0, 1.0, 0.5, 0.1])),
+    )
+    if rng.random() < 0.5:
+        over.update(topk_abs=int(rng.choice([1, 7, 64, 300])), topk_frac=0.0)
+    else:
+        over.update(topk_frac=float(rng.choice([0.0, 0.01, 0.025, 0.1, 0.5])))
+    if rng.random() < 0.5:
+        over.update(base_abs=int(rng.choice([1, 2, 9, 64, 500])), base_frac=0.0)
+    else:
+        over.update(base_frac=float(rng.choice([0.0, 0.01, 0.025, 0.2, 0.6])))
+    return dict(d=d, g=g, hkv=hkv, n_max=n_max, batch=batch, lens=lens, over=over,
+                paged=bool(rng.random() < 0.4), q_len=int(rng.choice([1, 1, 1, 2, 3])),
+                v_mean=float(rng.choice([0.0, 1.0])), flat=bool(rng.random() < 0.5))
+
+
+@pytest.mark.timeout(900)
+def test_random_configurations_match_the_oracle():
+    from paper_2510_05688_amd.session import DecodeSession
+    rng = np.random.default_rng(20251005)
+    n_cases, heads_checked = 80, 0
+    for case in range(n_cases):
+        c = _draw_case(rng)
+        p = default_params(c["d"], **c["over"])
+        wl = workloads.make_workload("random%d" % case, batch=c["batch"], n_q_heads=c["hkv"] * c["g"],
+                                     n_kv_heads=c["hkv"], head_dim=c["d"], n_max=c["n_max"], seq_lens=c["lens"],
+                                     seed=1000 + case, params=p, v_mean=c["v_mean"], all_flat=c["flat"],
+                                     plant_frac=0.004)
+        q_len = c["q_len"]
+        if q_len > 1:
+            wl.seq_lens = np.maximum(wl.seq_lens, q_len).astype(np.int32)   # a chunk never exceeds its sequence
+        say("random case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s q_len=%d %s" % (
+            case, c["d"], c["g"], c["hkv"], c["n_max"], list(wl.seq_lens), c["paged"], q_len, c["over"]))
+        q_bits = workloads.chunk_queries(wl, q_len, seed=case) if q_len > 1 else wl.q_bits
+        if c["paged"]:
+            k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
+            sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]), q_len=q_len)
+            sess.upload(q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+        else:
+            sess = DecodeSession(plan_params(wl), q_len=q_len)
+            sess.upload(q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+        sess.decode()
+        res = sess.results_host()
+        view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
+        reps = check_all(view, res, gpu_scores=sess.scores_host(), label="random%d" % case)
+        heads_checked += len(reps)
+        sess.close()
+    say("random configurations: %d cases, %d heads checked" % (n_cases, heads_checked))
