@@ -33,7 +33,11 @@ def _draw_case(rng):
         over.update(base_abs=int(rng.choice([1, 2, 9, 64, 500])), base_frac=0.0)
     else:
         over.update(base_frac=float(rng.choice([0.0, 0.01, 0.025, 0.2, 0.6])))
-    return dict(d=d, g=g, hkv=hkv, n_max=n_max, batch=batch, lens=lens, over=over,
+    # library options (each changes how, not what, except nested samples and the budget bound, which the oracle follows)
+    opts = dict(small_batches=bool(rng.random() < 0.2), general_topk=bool(rng.random() < 0.2),
+                wide=bool(rng.random() < 0.2), nested=bool(rng.random() < 0.25),
+                hoeffding=bool(over["target"] == 0 and rng.random() < 0.25))
+    return dict(d=d, g=g, hkv=hkv, n_max=n_max, batch=batch, lens=lens, over=over, opts=opts,
                 paged=bool(rng.random() < 0.4), q_len=int(rng.choice([1, 1, 1, 2, 3])),
                 v_mean=float(rng.choice([0.0, 1.0])), flat=bool(rng.random() < 0.5))
 
@@ -41,6 +45,7 @@ def _draw_case(rng):
 @pytest.mark.timeout(900)
 def test_random_configurations_match_the_oracle():
     from paper_2510_05688_amd.session import DecodeSession
+    from paper_2510_05688_amd import binding as vb
     rng = np.random.default_rng(20251005)
     n_cases, heads_checked = 80, 0
     for case in range(n_cases):
@@ -53,8 +58,9 @@ def test_random_configurations_match_the_oracle():
         q_len = c["q_len"]
         if q_len > 1:
             wl.seq_lens = np.maximum(wl.seq_lens, q_len).astype(np.int32)   # a chunk never exceeds its sequence
-        say("random case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s q_len=%d %s" % (
-            case, c["d"], c["g"], c["hkv"], c["n_max"], list(wl.seq_lens), c["paged"], q_len, c["over"]))
+        say("random case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s q_len=%d %s %s" % (
+            case, c["d"], c["g"], c["hkv"], c["n_max"], [int(x) for x in wl.seq_lens], c["paged"], q_len, c["over"],
+            {k: v for k, v in c["opts"].items() if v}))
         q_bits = workloads.chunk_queries(wl, q_len, seed=case) if q_len > 1 else wl.q_bits
         if c["paged"]:
             k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
@@ -63,10 +69,18 @@ def test_random_configurations_match_the_oracle():
         else:
             sess = DecodeSession(plan_params(wl), q_len=q_len)
             sess.upload(q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+        o = c["opts"]
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SAMPLER_SMALL_BATCHES, int(o["small_batches"]))
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, int(o["general_topk"]))
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 1024 if o["wide"] else 512)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, int(o["nested"]))
+        if o["hoeffding"]:
+            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
+        oracle_params = dict(wl.params, nested=o["nested"], bound="hoeffding" if o["hoeffding"] else "clt")
         sess.decode()
         res = sess.results_host()
         view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
-        reps = check_all(view, res, gpu_scores=sess.scores_host(), label="random%d" % case)
+        reps = check_all(view, res, params=oracle_params, gpu_scores=sess.scores_host(), label="random%d" % case)
         heads_checked += len(reps)
         sess.close()
     say("random configurations: %d cases, %d heads checked" % (n_cases, heads_checked))
