@@ -84,3 +84,65 @@ def test_random_configurations_match_the_oracle():
         heads_checked += len(reps)
         sess.close()
     say("random configurations: %d cases, %d heads checked" % (n_cases, heads_checked))
+
+
+@pytest.mark.timeout(900)
+def test_random_configurations_with_caller_supplied_topk():
+    from parity import check_head_given
+    from oracle import vatt_oracle as vo
+    from paper_2510_05688_amd.session import DecodeSession
+    from paper_2510_05688_amd import binding as vb
+    rng = np.random.default_rng(7102510)
+    n_cases, heads_checked = 40, 0
+    for case in range(n_cases):
+        c = _draw_case(rng)
+        p = default_params(c["d"], **c["over"])
+        wl = workloads.make_workload("random_given%d" % case, batch=c["batch"], n_q_heads=c["hkv"] * c["g"],
+                                     n_kv_heads=c["hkv"], head_dim=c["d"], n_max=c["n_max"], seq_lens=c["lens"],
+                                     seed=5000 + case, params=p, v_mean=c["v_mean"], all_flat=c["flat"],
+                                     plant_frac=0.004)
+        q_len = c["q_len"]
+        if q_len > 1:
+            wl.seq_lens = np.maximum(wl.seq_lens, q_len).astype(np.int32)
+        nested = c["opts"]["nested"]
+        say("random given case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s q_len=%d nested=%s %s" % (
+            case, c["d"], c["g"], c["hkv"], c["n_max"], [int(x) for x in wl.seq_lens], c["paged"], q_len, nested,
+            c["over"]))
+        q_bits = workloads.chunk_queries(wl, q_len, seed=case) if q_len > 1 else wl.q_bits
+        if c["paged"]:
+            k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
+            sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]), q_len=q_len)
+            sess.upload(q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+        else:
+            sess = DecodeSession(plan_params(wl), q_len=q_len)
+            sess.upload(q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, int(nested))
+        view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
+        k_max = vb.vatt_plan_index_segment(sess.plan, 3) - vb.vatt_plan_index_segment(sess.plan, 2)
+        rows, Hq, g = view.batch, wl.n_q_heads, c["g"]
+        idx = rng.integers(-5, c["n_max"] + 5, size=(rows, Hq, max(k_max, 1))).astype(np.int32)   # junk beyond cnt
+        cnt = np.zeros((rows, Hq), dtype=np.int32)
+        supplied = {}
+        for v in range(rows):
+            n = int(view.seq_lens[v])
+            for h in range(Hq):
+                s = vo.scores(view.q_f32()[v, h].astype(np.float64), view.k_f32(v, h // g, n).astype(np.float64),
+                              p["sm_scale"]) + rng.normal(0.0, 0.5, size=n)
+                k = vo.topk_count(n, int(p["sink"]), int(p["window"]), int(p.get("topk_abs", 0)),
+                                  float(p.get("topk_frac", 0.0)))
+                top = vo.deterministic_set(s, int(p["sink"]), int(p["window"]), k)[2]
+                # an approximate method's list: shuffled, with a few repeats and strays, cut to the capacity
+                extra = rng.integers(-3, n + 3, size=int(rng.integers(0, 4)))
+                lst = rng.permutation(np.concatenate([top, top[:2], extra]))[:k_max].astype(np.int32)
+                supplied[(v, h)] = lst
+                idx[v, h, :len(lst)] = lst
+                cnt[v, h] = len(lst)
+        sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
+        res = sess.results_host()
+        params = dict(wl.params, nested=nested)
+        for v in range(rows):
+            for h in range(Hq):
+                check_head_given(view, res, v, h, supplied[(v, h)], params=params, label="random given %d" % case)
+                heads_checked += 1
+        sess.close()
+    say("random configurations with supplied top-k: %d cases, %d heads checked" % (n_cases, heads_checked))
