@@ -323,23 +323,23 @@ struct HeadOps {
       uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(acc), &total, sm.scan);
       const uint32_t room = target - have;
       VATT_STAMP(S.dbg, 11);
+      // (written without nested per-draw branches: a divergent branch inside an unrolled loop serialises it)
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if ((acc >> e) & 1u) {
-          if (pos < room) {
-            if (!invert) {
-              if (have + pos < dst_cap) dst[have + pos] = (int32_t)B.tok[e];
-              if (sum_w) {
-                const double w = (double)__expf((B.have_sc ? B.sc[e] : S.row[B.tok[e]]) - S.m);
-                aw += w;
-                aw2 += w * w;
-              }
-            }
-          } else if (invert) {
-            atomicAnd(&S.taken[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));  // drawn after the sample was complete
+        const bool a = (acc >> e) & 1u;
+        const bool take = a && pos < room;
+        if (!invert) {
+          if (take && have + pos < dst_cap) dst[have + pos] = (int32_t)B.tok[e];
+          if (sum_w) {
+            const float sc = B.have_sc ? B.sc[e] : (take ? S.row[B.tok[e]] : 0.f);
+            const double w = take ? (double)__expf(sc - S.m) : 0.0;
+            aw += w;
+            aw2 += w * w;
           }
-          ++pos;
+        } else if (a && !take) {
+          atomicAnd(&S.taken[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));  // drawn after the sample was complete
         }
+        pos += a ? 1u : 0u;
       }
       have += min(total, room);
       blk += (uint32_t)B.blocks;
@@ -880,6 +880,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       float sT = -INFINITY;
       uint32_t Tidx = kInv32;
       bool marked = false;
+      uint64_t T_cand = ~0ull;   // fast path: members are the candidates with composite <= T_cand
+      uint32_t n_cand_used = 0;
       if (hs.k < mid_len) {
         // Fast path.  A lower bound of the k-th largest score: the k-th largest of the sub-tile maxima (of
         // the sub-tiles that lie entirely in the middle region) has at least k middle scores at or above it.
@@ -1029,6 +1031,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
             }
             have_T = true;
             marked = true;
+            T_cand = T;
+            n_cand_used = n_cand;
           }
         }
         if (!have_T) {
@@ -1084,7 +1088,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       }
       // ascending token list from the bitmap
       O::word_prefix(bm_f, words, wpre, sm);
-      {
+      if (marked) {
+        // every member sits in the candidate list: its place in the ascending list is the number of members
+        // below it, from the word prefix and the bits below its own (no thread walks a crowded word)
+        for (uint32_t t = tid; t < n_cand_used; t += NT) {
+          const uint64_t c = cand[t];
+          if (c <= T_cand) {
+            const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
+            const uint32_t pos = wpre[i >> 5] + (uint32_t)__popc(bm_f[i >> 5] & ((1u << (i & 31)) - 1u));
+            if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)i;
+          }
+        }
+      } else {
         const int wpt = (words + NT - 1) / NT;
         const int w0 = tid * wpt;
         for (int w = w0; w < min(w0 + wpt, words); ++w) {
