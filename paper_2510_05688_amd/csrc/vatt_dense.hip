@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;
-  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
+  const int n = max(min(max(A.seq_lens[seq], 1), A.n_max) - (A.q_len - 1 - qtok), 1);  // clamp, then the causal cut
   // key range of this workgroup, then of this wave (multiples of RPW * U rows except at the end)
   const int step = RPW * U;
   const int per_blk = ((n + A.splits - 1) / A.splits + step * WAVES - 1) / (step * WAVES) * (step * WAVES);

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     for (int u = 0; u < BATCH; ++u)
       first_off[u] = kv_row_offset<true>(L, b, kvh, min(tile_lo + wave * ROWS_PER_WAVE + u * RPW + rsub, n_max - 1));
   }
-  const int n = min(max(seq_lens[b], 0), n_max);
+  const int n = min(max(seq_lens[b], 1), n_max);  // lengths outside [1, n_max] are clamped, as in every kernel
   if (tile_lo >= n) return;
 
   __shared__ float s_tile[G][TILE];

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kvh = blockIdx.y, b = blockIdx.z;
-  const int n_b = min(max(seq_lens[b], 0), n_max);  // the newest query sees all of it
+  const int n_b = min(max(seq_lens[b], 1), n_max);  // the newest query sees all of it
   const int tile_lo = (blockIdx.x * kChunkWaves + wave) * kChunkWaveKeys;
   if (tile_lo >= n_b) return;  // (no workgroup barrier below: every wave works alone)
 
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
       const int cg = nt * 16 + c;
       if (cg >= QG) break;
       const int t = cg / G, g = cg - t * G;
-      const int n_t = max(n_b - (Q - 1 - t), 0);  // tokens this query sees
+      const int n_t = max(n_b - (Q - 1 - t), 1);  // tokens this query sees (at least one, as in the other kernels)
       const int64_t row = ((int64_t)b * Q + t) * Hq + (int64_t)kvh * G + g;
       const float v = s_tile[c][lane];
       if (i < n_t) __builtin_nontemporal_store(v, &scores[row * n_pad + i]);

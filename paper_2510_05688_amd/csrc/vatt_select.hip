@@ -746,7 +746,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // In a multi-query step b stands for (sequence, query token); query token t of q_len sees the sequence up to
   // and including itself, which leaves out the q_len - 1 - t newer tokens.
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;
-  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
+  const int n = max(min(max(A.seq_lens[seq], 1), A.n_max) - (A.q_len - 1 - qtok), 1);  // clamp, then the causal cut
   const HeadSizes hs = head_sizes(n, A.sp);
   const int words_max = ((A.n_max + 63) >> 6) << 1;  // an even number of words: bitmaps are also written 64 bits at a time
   const int words = (n + 31) >> 5;
@@ -1303,7 +1303,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;  // (sequence, query token) of a multi-query step
-  const int n = min(max(A.seq_lens[seq] - (A.q_len - 1 - qtok), 1), A.n_max);
+  const int n = max(min(max(A.seq_lens[seq], 1), A.n_max) - (A.q_len - 1 - qtok), 1);  // clamp, then the causal cut
   HeadSizes hs = head_sizes(n, A.sp);
   const int words_max = ((A.n_max + 63) >> 6) << 1;
   const int words = (n + 31) >> 5;

@@ -216,3 +216,23 @@ def test_chunk_with_caller_supplied_topk(paged):
             for v in range(cv.batch) for h in range(wl.n_q_heads)]
     assert any(r["b"] > r["b0"] for r in reps)
     sess.close()
+
+
+def test_chunk_longer_than_its_sequence():
+    # a query token with nothing before it is treated as seeing one token (documented clamp): its output is V[0]
+    wl = workloads.small_gqa(seed=3, batch=2, n=64, seq_lens=[2, 64])
+    q_len = 4
+    q_bits = workloads.chunk_queries(wl, q_len, seed=4)
+    sess = _chunk_session(wl, q_bits, q_len)
+    sess.decode()
+    res = sess.results_host()
+    g = wl.n_q_heads // wl.n_kv_heads
+    assert [int(res["counts"][t, 0, 6]) for t in range(q_len)] == [1, 1, 1, 2]
+    for t in range(3):
+        for h in range(wl.n_q_heads):
+            v0 = workloads.bf16_bits_to_f32(wl.v_bits[0, h // g, 0]).astype(np.float64)
+            assert np.allclose(res["O"][t, h], v0, rtol=1e-6, atol=1e-7)
+    cv = ChunkView(wl, q_bits, q_len)
+    cv.seq_lens = np.maximum(cv.seq_lens, 1)
+    check_all(cv, res, heads=[(v, h) for v in range(3, 8) for h in range(wl.n_q_heads)], label="short chunk")
+    sess.close()

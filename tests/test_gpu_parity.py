@@ -471,3 +471,19 @@ def test_selection_kernel_with_1024_threads_gives_identical_results():
         with pytest.raises(vb.VattError):
             vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 768)
         sess.close()
+
+
+def test_lengths_outside_the_cache_are_clamped():
+    # seq_lens outside [1, n_max] are clamped by every kernel alike: 0 becomes one token, too large becomes n_max
+    wl = workloads.small_gqa(seed=81, batch=3, n=2048, seq_lens=[2048, 1, 2048])
+    sess = _session(wl)
+    sess.seq_lens = torch.tensor([0, -7, 5000], dtype=torch.int32, device=sess.device)
+    res = _run(sess)
+    assert [int(res["counts"][b, 0, 6]) for b in range(3)] == [1, 1, 2048]
+    assert np.all(np.isfinite(res["O"])) and np.all(np.isfinite(res["lse"]))
+    wl.seq_lens = np.array([1, 1, 2048], dtype=np.int32)   # what the kernels made of them
+    check_all(wl, res, label="clamped lengths")
+    sess.dense()
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(sess.dense_o.cpu().numpy()))
+    sess.close()
