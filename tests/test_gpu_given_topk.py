@@ -183,3 +183,22 @@ def test_given_topk_numerator_and_sdpa_targets(target, eps):
                 for b in range(wl.batch) for h in range(wl.n_q_heads)]
         assert any(r["b0"] < r["b"] < r["oracle"]["n_s"] for r in reps)
         sess.close()
+
+
+def test_given_topk_counts_out_of_range_are_clamped():
+    # topk_cnt below 0 means an empty list, above the capacity means the whole row of topk_idx
+    say("given top-k with out-of-range counts")
+    wl = workloads.small_gqa(seed=49, batch=1, n=2000, seq_lens=[2000])
+    sess = _session(wl)
+    k_max = _k_max(sess)
+    rng = np.random.default_rng(2)
+    idx = rng.integers(-50, 2100, size=(1, wl.n_q_heads, k_max)).astype(np.int32)
+    cnt = np.zeros((1, wl.n_q_heads), dtype=np.int32)
+    cnt[0, ::2] = -9
+    cnt[0, 1::2] = 10 ** 6
+    sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
+    res = sess.results_host()
+    for h in range(wl.n_q_heads):
+        supplied = np.empty(0, dtype=np.int64) if h % 2 == 0 else idx[0, h].astype(np.int64)
+        check_head_given(wl, res, 0, h, supplied, label="clamped counts")
+    sess.close()

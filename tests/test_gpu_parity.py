@@ -487,3 +487,24 @@ def test_lengths_outside_the_cache_are_clamped():
     torch.cuda.synchronize()
     assert np.all(np.isfinite(sess.dense_o.cpu().numpy()))
     sess.close()
+
+
+def test_block_table_entries_out_of_range_are_clamped():
+    # a corrupted block table must not make any kernel leave the cache: entries are clamped into [0, num_blocks),
+    # the sequence they belong to gets a meaningless result, the other sequences are untouched
+    wl = workloads.small_gqa(seed=83, batch=2, n=2048, seq_lens=[2048, 1777])
+    good = _paged_session(wl)
+    ref = _run(good)
+    bad = _paged_session(wl)
+    table = bad.block_table.clone()
+    table[0, 3] = -12345
+    table[0, 40] = 2 ** 30
+    bad.block_table = table
+    res = _run(bad)
+    bad.dense()
+    torch.cuda.synchronize()
+    assert np.array_equal(res["counts"][1], ref["counts"][1])
+    assert np.array_equal(res["O"][1], ref["O"][1]) and np.array_equal(res["idx"][1], ref["idx"][1])
+    assert np.all(np.isfinite(res["O"][0]))
+    good.close()
+    bad.close()
