@@ -508,3 +508,19 @@ def test_block_table_entries_out_of_range_are_clamped():
     assert np.all(np.isfinite(res["O"][0]))
     good.close()
     bad.close()
+
+
+@pytest.mark.parametrize("n_max", [1, 2, 7, 33])
+def test_tiny_caches(n_max):
+    # capacities far below one tile, one bitmap word, one batch of draws
+    say("tiny cache n_max=%d" % n_max)
+    p = default_params(128, sink=1, window=2, topk_abs=2, topk_frac=0.0, base_abs=2, base_frac=0.0, epsilon=0.02)
+    wl = workloads.make_workload("tiny_cache", batch=2, n_q_heads=4, n_kv_heads=1, head_dim=128, n_max=n_max,
+                                 seq_lens=[n_max, max(1, n_max // 2)], seed=4, params=p, all_flat=True)
+    sess = _session(wl)
+    res = _run(sess)
+    check_all(wl, res, gpu_scores=sess.scores_host(), label="tiny cache %d" % n_max)
+    sess.dense()
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(sess.dense_o.cpu().numpy()))
+    sess.close()
