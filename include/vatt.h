@@ -136,8 +136,7 @@ void vatt_plan_destroy(vatt_plan* plan);
  * vatt_score reads "[B, q_len, ...]" (seq_lens, seq_seeds, block_table and the caches stay per sequence,
  * and every seq_lens entry should be at least q_len: a query with no visible token is treated as seeing
  * one); the same holds for topk_idx and topk_cnt of vatt_decode_given_topk.  q_len = 1 is vatt_plan_create.
- * q_len * (n_q_heads / n_kv_heads) may not exceed 64 and batch * q_len may not exceed 65535
- * (VATT_E_UNSUPPORTED_SHAPE).
+ * q_len may not exceed 256 and batch * q_len may not exceed 65535 (VATT_E_UNSUPPORTED_SHAPE).
  */
 int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vatt_plan** out);
 int vatt_plan_query_len(const vatt_plan* plan);

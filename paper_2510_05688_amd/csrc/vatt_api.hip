@@ -202,8 +202,7 @@ int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vat
   int rc = validate(*params);
   if (rc != VATT_OK) return rc;
   if (q_len < 1) return VATT_E_INVALID_ARG;
-  // a multi-query score tile holds at most 64 (query token, group head) pairs
-  if (q_len > 1 && (int64_t)q_len * (params->n_q_heads / params->n_kv_heads) > 64) return VATT_E_UNSUPPORTED_SHAPE;
+  if (q_len > 256) return VATT_E_UNSUPPORTED_SHAPE;
   if ((int64_t)params->batch * q_len > 65535) return VATT_E_UNSUPPORTED_SHAPE;
   vatt_plan* plan = new (std::nothrow) vatt_plan;
   if (!plan) return VATT_E_INVALID_ARG;

@@ -20,6 +20,8 @@
 // are staged in LDS so that they leave as whole 256-byte rows, with the largest of every 8 keys beside them,
 // exactly as the single-query kernel leaves them.  The LDS executes the instructions of one wave in order, so
 // a wave's own writes and reads of its tiles need no barrier.
+#include <algorithm>
+
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -56,17 +58,21 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
   __shared__ __align__(16) float s_all[kChunkWaves][16][LD];
   float (*s_tile)[LD] = s_all[wave];
 
-  // B operands: query vector c = t * G + g of this KV head, for c = 16 nt + i16
+  // B operands: query vector c = t * G + g of this KV head, for c = c0 + 16 nt + i16.  16 NQT query vectors
+  // are held at a time; a step with more of them takes them in rounds, with the K fragments staying put.
   uint4 bq[NQT][S];
+  auto load_queries = [&](int c0) {
 #pragma unroll
-  for (int nt = 0; nt < NQT; ++nt) {
-    const int c = nt * 16 + i16;
-    const int t = c / G, g = c - t * G;
-    const uint16_t* src = q + (((int64_t)b * Q + t) * Hq + (int64_t)kvh * G + g) * D + g4 * 8;
+    for (int nt = 0; nt < NQT; ++nt) {
+      const int c = c0 + nt * 16 + i16;
+      const int t = c / G, g = c - t * G;
+      const uint16_t* src = q + (((int64_t)b * Q + t) * Hq + (int64_t)kvh * G + g) * D + g4 * 8;
 #pragma unroll
-    for (int s = 0; s < S; ++s)
-      bq[nt][s] = c < QG ? *reinterpret_cast<const uint4*>(src + s * 32) : make_uint4(0u, 0u, 0u, 0u);
-  }
+      for (int s = 0; s < S; ++s)
+        bq[nt][s] = c < QG ? *reinterpret_cast<const uint4*>(src + s * 32) : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  load_queries(0);
 
   // K rows are requested the way memory likes them: D/8 adjacent lanes read one whole row, so a wave
   // instruction covers 64 * 16 contiguous bytes (measured 12 % faster than loading the MFMA layout directly,
@@ -101,9 +107,11 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
     __builtin_amdgcn_wave_barrier();
   }
 
+  for (int c0 = 0; c0 < QG; c0 += 16 * NQT) {
+  if (c0 > 0) load_queries(c0);
 #pragma unroll
   for (int nt = 0; nt < NQT; ++nt) {
-    if (nt * 16 >= QG) break;  // same for the whole grid
+    if (c0 + nt * 16 >= QG) break;  // same for the whole grid
     f32x4_t acc[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
@@ -124,7 +132,7 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
     __builtin_amdgcn_wave_barrier();
     const int i = tile_lo + lane;
     for (int c = 0; c < 16; ++c) {
-      const int cg = nt * 16 + c;
+      const int cg = c0 + nt * 16 + c;
       if (cg >= QG) break;
       const int t = cg / G, g = cg - t * G;
       const int n_t = max(n_b - (Q - 1 - t), 1);  // tokens this query sees (at least one, as in the other kernels)
@@ -135,6 +143,7 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
       if ((lane & 7) == 0) sub_max[row * n_sub + i / kSubTile] = mx;
     }
     __builtin_amdgcn_wave_barrier();
+  }
   }
 }
 
@@ -156,7 +165,7 @@ hipError_t launch_n(const Plan& pl, const void* q, const void* k, const int32_t*
 template <int D, bool PAGED>
 hipError_t launch_p(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                     const int32_t* seq_lens, void* ws, hipStream_t st) {
-  const int groups = (pl.q_len * pl.group + 15) / 16;
+  const int groups = std::min((pl.q_len * pl.group + 15) / 16, 4);  // more query vectors go in rounds of 64
   switch (groups) {
     case 1: return launch_n<D, PAGED, 1>(pl, q, k, block_table, seq_lens, ws, st);
     case 2: return launch_n<D, PAGED, 2>(pl, q, k, block_table, seq_lens, ws, st);

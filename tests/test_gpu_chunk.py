@@ -33,6 +33,8 @@ def _chunk_session(wl, q_bits, q_len, paged=False, page=16, **over):
     (128, 4, 4, 784, [784, 9], 7),          # G = 1, a sequence barely longer than the chunk
     (128, 16, 2, 1504, [1504, 1029], 5),    # G = 8, Q = 5: three query tiles, the last half full
     (64, 8, 2, 2112, [2112, 300], 16),      # d = 64, G = 4, Q = 16: four query tiles
+    (128, 8, 2, 1008, [1008, 333], 21),     # G = 4, Q = 21: 84 query vectors, a second round of 64
+    (128, 16, 2, 528, [528, 64], 33),       # G = 8, Q = 33: 264 query vectors, five rounds
 ])
 def test_chunk_score_pass(d, hq, hkv, n, lens, q_len):
     say("chunk score pass d=%d Hq=%d Hkv=%d n=%d Q=%d" % (d, hq, hkv, n, q_len))
@@ -62,6 +64,7 @@ def test_chunk_score_pass(d, hq, hkv, n, lens, q_len):
     ("tight_eps_q3", dict(epsilon=0.01, delta=0.01), 3, False),
     ("target_sdpa_q2", dict(target=2, epsilon=0.3), 2, False),
     ("no_sink_q5", dict(sink=0, window=0), 5, True),
+    ("two_rounds_q20", dict(), 20, False),
 ])
 def test_chunk_decode_small(name, over, q_len, paged):
     say("chunk decode %s" % name)
@@ -151,7 +154,7 @@ def test_chunk_plan_limits():
     wl = workloads.small_gqa(seed=1, n=512, seq_lens=[512, 512])
     p = plan_params(wl)            # G = 4
     with pytest.raises(vb.VattError):
-        vb.vatt_plan_create_chunk(p, 17, 0)    # 17 * 4 > 64 query vectors per tile
+        vb.vatt_plan_create_chunk(p, 257, 0)   # at most 256 query tokens per sequence and call
     with pytest.raises(vb.VattError):
         vb.vatt_plan_create_chunk(p, 0, 0)
     plan = vb.vatt_plan_create_chunk(p, 16, 0)

@@ -134,6 +134,6 @@ def test_budget_bound_option_and_chunk_plans_on_the_host():
     finally:
         vb.vatt_plan_destroy(one)
         vb.vatt_plan_destroy(four)
-    for bad in (0, -3, 17):                    # 17 * (32 / 8) query vectors exceed a score tile
+    for bad in (0, -3, 257):                   # at most 256 query tokens per sequence and call
         with pytest.raises(vb.VattError):
             vb.vatt_plan_create_chunk(_base(), bad, -1)
