@@ -146,3 +146,39 @@ def test_random_configurations_with_caller_supplied_topk():
                 heads_checked += 1
         sess.close()
     say("random configurations with supplied top-k: %d cases, %d heads checked" % (n_cases, heads_checked))
+
+
+@pytest.mark.timeout(900)
+def test_random_medium_configurations_match_the_oracle():
+    # rows of 8K to 80K tokens (both workgroup sizes of the selection kernel by the plan's own choice, resident
+    # and streamed 8-key maxima, samples of several batches), a few heads each, every head checked
+    from paper_2510_05688_amd.session import DecodeSession
+    rng = np.random.default_rng(31337)
+    heads_checked = 0
+    for case in range(14):
+        n_max = int(rng.choice([8192, 16384, 32768, 40000, 65536, 80000])) // 16 * 16
+        d = int(rng.choice([64, 128]))
+        g = int(rng.choice([1, 4]))
+        batch = int(rng.integers(1, 3))
+        lens = [n_max] + [int(rng.integers(n_max // 3, n_max + 1)) for _ in range(batch - 1)]
+        over = dict(epsilon=float(rng.choice([0.05, 0.02, 0.01, 0.004])), delta=float(rng.choice([0.2, 0.05])),
+                    topk_frac=float(rng.choice([0.005, 0.025, 0.1])), base_frac=float(rng.choice([0.01, 0.025, 0.1])),
+                    sink=int(rng.choice([0, 128])), window=int(rng.choice([128, 512])))
+        paged = bool(rng.random() < 0.4)
+        p = default_params(d, **over)
+        wl = workloads.make_workload("medium%d" % case, batch=batch, n_q_heads=g, n_kv_heads=1, head_dim=d,
+                                     n_max=n_max, seq_lens=lens, seed=9000 + case, params=p,
+                                     all_flat=bool(rng.random() < 0.5), cluster=int(rng.choice([1, 64])))
+        say("medium case %d: d=%d G=%d n_max=%d lens=%s paged=%s %s" % (case, d, g, n_max, lens, paged, over))
+        if paged:
+            k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
+            sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]))
+            sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+        else:
+            sess = DecodeSession(plan_params(wl))
+            sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+        sess.decode()
+        res = sess.results_host()
+        heads_checked += len(check_all(wl, res, gpu_scores=sess.scores_host(), label="medium%d" % case))
+        sess.close()
+    say("medium random configurations: %d heads checked" % heads_checked)
