@@ -1,6 +1,5 @@
 // C ABI of libvatt: parameter validation, plan geometry, workspace layout and the launch sequences.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
