@@ -137,3 +137,21 @@ def test_budget_bound_option_and_chunk_plans_on_the_host():
     for bad in (0, -3, 257):                   # at most 256 query tokens per sequence and call
         with pytest.raises(vb.VattError):
             vb.vatt_plan_create_chunk(_base(), bad, -1)
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    import subprocess
+    src = os.path.join(ROOT, "tests", "c_abi", "plan_from_c.c")
+    exe = str(tmp_path / "plan_from_c")
+    libdir = os.path.dirname(vb.LIB_PATH)
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        src, "-o", exe, "-L", libdir, "-l:libvatt.so", "-Wl,-rpath," + libdir,
+                        "-Wl,-rpath,/opt/rocm/lib"], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stdout + out.stderr
+    lines = dict(l.split(" ", 1) for l in out.stdout.strip().splitlines() if " " in l)
+    assert int(lines["workspace_bytes"]) == vb.vatt_plan_workspace_bytes(vb.vatt_plan_create(_base(), -1))
+    assert lines["segments"] == "0 128 256 1075 1894"
+    assert "q_len 4" in out.stdout and "bad epsilon: " in out.stdout
+    assert "launch without a device: ok" not in out.stdout
