@@ -308,18 +308,33 @@ def test_append_to_a_contiguous_cache_then_decode():
     sess.close()
 
 
-def test_decode_inside_a_hip_graph():
-    say("vatt_decode captured in a HIP graph and replayed")
+@pytest.mark.parametrize("path", ["scored", "scored_sdpa_target", "given_topk", "multi_query"])
+def test_decode_inside_a_hip_graph(path):
+    say("%s step captured in a HIP graph and replayed" % path)
     import torch
-    wl = workloads.small_gqa(seed=51, batch=2, n=6000)
-    sess = _session(wl)
-    eager = _run(sess)
+    over = dict(target=2, epsilon=0.3) if path == "scored_sdpa_target" else dict()
+    wl = workloads.small_gqa(seed=51, batch=2, n=6000, **over)
+    if path == "multi_query":
+        from paper_2510_05688_amd.session import DecodeSession
+        sess = DecodeSession(plan_params(wl), q_len=3)
+        sess.upload(workloads.chunk_queries(wl, 3, seed=2), wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    else:
+        sess = _session(wl)
+    call = sess.decode
+    if path == "given_topk":
+        first = _run(sess)
+        seg = first["seg"]
+        topk_idx = sess.out_idx[:, :, seg[2]:seg[3]].contiguous()
+        topk_cnt = sess.out_counts[:, :, 2].contiguous()
+        call = lambda: sess.decode_given_topk(topk_idx, topk_cnt)  # noqa: E731
+    call()
+    eager = sess.results_host()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
-            sess.decode()
+            call()
     torch.cuda.current_stream().wait_stream(side)
     for _ in range(3):
         sess.out_o.zero_()
@@ -331,7 +346,7 @@ def test_decode_inside_a_hip_graph():
         again = sess.results_host()
         for key in ("O", "lse", "counts", "b_star", "stats"):
             assert np.array_equal(eager[key], again[key]), key
-        for b in range(wl.batch):
+        for b in range(eager["counts"].shape[0]):
             for h in range(wl.n_q_heads):
                 ge, ga = gpu_segments(eager, b, h), gpu_segments(again, b, h)
                 for key in ("I_s", "I_l", "I_t", "I_bs", "I_dyn"):
