@@ -1563,12 +1563,21 @@ HeadKernel head_kernel_for(const Plan& pl) {
 
 }  // namespace
 
+size_t head_kernel_static_lds_bytes();
+
 hipError_t set_kernel_attributes(const Plan& pl) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_kernel_for(pl)),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.head_lds_bytes);
+  // The limit on dynamic LDS belongs to the kernel, not to the plan: it is raised to all a CU has (less the
+  // kernels' static part), so that plans of different capacities can be used in any order.
+  (void)pl;
+  const int cap = 160 * 1024 - (int)head_kernel_static_lds_bytes();
+  const void* kernels[3] = {reinterpret_cast<const void*>(head_kernel<kHeadThreads>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreadsLong>),
+                            reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads>)};
+  for (const void* f : kernels) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 size_t head_kernel_lds_bytes(int n_max, int head_threads) {

@@ -543,3 +543,28 @@ def test_tiny_caches(n_max):
     torch.cuda.synchronize()
     assert np.all(np.isfinite(sess.dense_o.cpu().numpy()))
     sess.close()
+
+
+@pytest.mark.timeout(300)
+def test_plans_of_different_capacities_in_any_order():
+    # the dynamic-LDS limit is a property of a kernel, not of a plan: a long-context plan must keep working
+    # after a plan with a smaller capacity has been made (both use the 1024-thread selection kernel here)
+    say("plans of different capacities used in any order")
+    from paper_2510_05688_amd.session import DecodeSession
+    p = default_params(128, sink=128, window=128)
+    big = workloads.make_workload("cap_big", batch=1, n_q_heads=2, n_kv_heads=1, head_dim=128, n_max=120000,
+                                  seq_lens=[120000], seed=91, params=p)
+    small = workloads.make_workload("cap_small", batch=1, n_q_heads=2, n_kv_heads=1, head_dim=128, n_max=70000,
+                                    seq_lens=[70000], seed=92, params=p)
+    s_big = DecodeSession(plan_params(big))
+    s_big.upload(big.q_bits, big.k_bits, big.v_bits, big.seq_lens, big.seeds)
+    s_small = DecodeSession(plan_params(small))          # made after the big one
+    s_small.upload(small.q_bits, small.k_bits, small.v_bits, small.seq_lens, small.seeds)
+    check_all(big, _run(s_big), label="big plan after a smaller one was made")
+    check_all(small, _run(s_small), label="small plan")
+    seg = s_big.seg
+    s_big.decode_given_topk(s_big.out_idx[:, :, seg[2]:seg[3]].contiguous(), s_big.out_counts[:, :, 2].contiguous())
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(s_big.out_o.cpu().numpy()))
+    s_big.close()
+    s_small.close()
