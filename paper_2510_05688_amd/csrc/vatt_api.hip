@@ -119,7 +119,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.given_splits = std::min(pl.gather_splits, std::max(1, (8 * pl.num_cus + heads - 1) / heads));
   const int kv_heads = pl.vbatch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
-  pl.dense_splits = std::min(std::min(128, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
+  pl.dense_splits = std::min(std::min(64, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
 
   pl.seg_off[0] = 0;
   pl.seg_off[1] = p.sink;
