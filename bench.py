@@ -351,6 +351,17 @@ def main():
     t_wall = time.perf_counter() - t_wall
     res = sess.results_host()
     counts = res["counts"].reshape(-1, 8).astype(np.int64)
+    # spread of single calls: a second pass with an event after every call (the events cost a little, so the
+    # headline figure above comes from the undisturbed loop)
+    n_spread = min(args.steps, 200)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+    torch.cuda.synchronize()
+    marks[0].record()
+    for i in range(n_spread):
+        step(i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_call = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]) * 1e3
 
     for i in range(args.warmup):
         score_only(i)
@@ -423,6 +434,9 @@ def main():
         "budget_b": {"min": int(b_dyn.min()), "mean": float(b_dyn.mean()), "max": int(b_dyn.max()),
                      "base_b0_mean": float(counts[:, 3].mean())},
         "wall_s_timed_region": t_wall,
+        "step_latency_us": {"p10": float(np.percentile(per_call, 10)), "p50": float(np.percentile(per_call, 50)),
+                            "p90": float(np.percentile(per_call, 90)), "calls": int(n_spread),
+                            "note": "one event per call; the events add about a microsecond"},
         "roofline": {
             "kernel": "score_kernel (K scan, shared across the GQA group)",
             "bound": "hbm",
