@@ -436,7 +436,7 @@ def main():
         "wall_s_timed_region": t_wall,
         "step_latency_us": {"p10": float(np.percentile(per_call, 10)), "p50": float(np.percentile(per_call, 50)),
                             "p90": float(np.percentile(per_call, 90)), "calls": int(n_spread),
-                            "note": "one event per call; the events add about a microsecond"},
+                            "note": "one event per call; the events add two to three microseconds per call"},
         "roofline": {
             "kernel": "score_kernel (K scan, shared across the GQA group)",
             "bound": "hbm",
