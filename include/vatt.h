@@ -143,7 +143,8 @@ int vatt_plan_query_len(const vatt_plan* plan);
 
 /*
  * Options (host only), for tests.  VATT_OPT_SAMPLER_SMALL_BATCHES = 1 makes the sampler work through
- * the draw sequence in batches of 256 draws only (it normally uses up to 1024); results are identical.
+ * the draw sequence in batches of 256 draws only (it normally uses up to 1024, or 4096 with 1024 threads);
+ * results are identical.
  * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that
  * the completion rule can be exercised.
  * VATT_OPT_TOPK_GENERAL_PATH = 1 makes the top-k selection skip its usual shortcut (a lower bound of the
@@ -154,7 +155,8 @@ enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_O
        VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6 };
 /*
  * VATT_OPT_HEAD_THREADS (test hook): workgroup size of the selection kernel, 512 or 1024.  The plan picks 512
- * for n_max <= 32768 and 1024 for longer rows; results are identical.  To be set on the plan's device.
+ * for n_max <= 32768, and 1024 for longer rows when that costs no parallelism (the LDS of a CU holds one such
+ * workgroup only, or there are no more heads than CUs); results are identical.  To be set on the plan's device.
  */
 /*
  * VATT_OPT_NESTED_SAMPLES = 1 departs from Algorithm 1, which draws the final sample afresh: the base sample
