@@ -568,3 +568,19 @@ def test_plans_of_different_capacities_in_any_order():
     assert np.all(np.isfinite(s_big.out_o.cpu().numpy()))
     s_big.close()
     s_small.close()
+
+
+@pytest.mark.timeout(300)
+def test_many_short_sequences():
+    # a large batch of short sequences: grid dimensions grow with the batch, every head is still checked
+    say("1200 short sequences")
+    p = default_params(64, sink=4, window=8, topk_abs=6, topk_frac=0.0, base_abs=8, base_frac=0.0, epsilon=0.1)
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(1, 257, size=1200)]
+    wl = workloads.make_workload("many_short", batch=1200, n_q_heads=2, n_kv_heads=1, head_dim=64, n_max=256,
+                                 seq_lens=lens, seed=6, params=p, all_flat=True)
+    for paged in (False, True):
+        sess = _paged_session(wl) if paged else _session(wl)
+        res = _run(sess)
+        check_all(wl, res, label="many short sequences, paged=%s" % paged)
+        sess.close()
