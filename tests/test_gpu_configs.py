@@ -73,7 +73,7 @@ def test_config3_batch16_sampled_heads():
     res = sess.results_host()
     _properties(wl, res)
     rng = np.random.default_rng(0)
-    heads = [(int(rng.integers(16)), int(rng.integers(32))) for _ in range(48)] + [(0, 0), (15, 31)]
+    heads = [(int(rng.integers(16)), int(rng.integers(32))) for _ in range(94)] + [(0, 0), (15, 31)]
     check_all(wl, res, heads=heads, label="config3")
     sess.close()
 
@@ -92,7 +92,6 @@ def test_config4_long_context():
     sess.close()
 
 
-@pytest.mark.timeout(600)
 @pytest.mark.timeout(600)
 def test_config4_general_topk_path_on_long_rows():
     say("config 4 shape (n=131072), B=1, top-k by the general path (whole row streamed)")
@@ -136,6 +135,37 @@ def test_config5_ragged_paged_decode_loop():
             rng = np.random.default_rng(step)
             heads = [(int(rng.integers(wl.batch)), int(rng.integers(32))) for _ in range(10)]
             check_all(wl, res, heads=heads, label="config5/step%d" % step)
+    sess.close()
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_batch_two_steps():
+    # the shape bench.py --config 5 times: B = 32, lengths 1K-33K, 16-token pages, append then decode
+    say("config 5 at full batch (B=32), two steps")
+    from paper_2510_05688_amd.session import DecodeSession
+    wl = workloads.config5(steps=256)
+    k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=3)
+    sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]))
+    sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
+    del k_pages, v_pages
+    base_seeds = wl.seeds.copy()
+    for step in range(2):
+        k_new, v_new = append_tokens(5, step, wl.batch, wl.n_kv_heads, wl.head_dim)
+        sess.append(k_new, v_new)
+        for b in range(wl.batch):
+            n = int(wl.seq_lens[b])
+            wl.k_bits[b, :, n] = k_new[b]
+            wl.v_bits[b, :, n] = v_new[b]
+        wl.seq_lens = wl.seq_lens + 1
+        wl.seeds = base_seeds + np.uint64(7919 * step)
+        sess.set_seeds(wl.seeds)
+        sess.decode()
+        res = sess.results_host()
+        assert np.array_equal(sess.seq_lens.cpu().numpy(), wl.seq_lens)
+        _properties(wl, res)
+        rng = np.random.default_rng(100 + step)
+        heads = [(int(rng.integers(wl.batch)), int(rng.integers(32))) for _ in range(20)]
+        check_all(wl, res, heads=heads, label="config5 full batch/step%d" % step)
     sess.close()
 
 
