@@ -11,6 +11,10 @@ from util import plan_params
 
 pytestmark = pytest.mark.gpu
 
+# The committed runs use the seeds below; VATT_TEST_SEED=k shifts all of them (a way to try other draws by hand).
+import os  # noqa: E402
+SEED_SHIFT = int(os.environ.get("VATT_TEST_SEED", "0"))
+
 
 def _draw_case(rng):
     d = int(rng.choice([64, 128]))
@@ -46,7 +50,7 @@ def _draw_case(rng):
 def test_random_configurations_match_the_oracle():
     from paper_2510_05688_amd.session import DecodeSession
     from paper_2510_05688_amd import binding as vb
-    rng = np.random.default_rng(20251005)
+    rng = np.random.default_rng(20251005 + SEED_SHIFT)
     n_cases, heads_checked = 80, 0
     for case in range(n_cases):
         c = _draw_case(rng)
@@ -92,7 +96,7 @@ def test_random_configurations_with_caller_supplied_topk():
     from oracle import vatt_oracle as vo
     from paper_2510_05688_amd.session import DecodeSession
     from paper_2510_05688_amd import binding as vb
-    rng = np.random.default_rng(7102510)
+    rng = np.random.default_rng(7102510 + SEED_SHIFT)
     n_cases, heads_checked = 40, 0
     for case in range(n_cases):
         c = _draw_case(rng)
@@ -153,7 +157,7 @@ def test_random_medium_configurations_match_the_oracle():
     # rows of 8K to 80K tokens (both workgroup sizes of the selection kernel by the plan's own choice, resident
     # and streamed 8-key maxima, samples of several batches), a few heads each, every head checked
     from paper_2510_05688_amd.session import DecodeSession
-    rng = np.random.default_rng(31337)
+    rng = np.random.default_rng(31337 + SEED_SHIFT)
     heads_checked = 0
     for case in range(14):
         n_max = int(rng.choice([8192, 16384, 32768, 40000, 65536, 80000])) // 16 * 16
