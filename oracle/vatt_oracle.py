@@ -480,13 +480,14 @@ def topk_alternatives(s: np.ndarray, sink: int, window: int, k: int, rel_tol: fl
 
 
 def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-4) -> List[int]:
-    """Budgets a correct fp32-statistics implementation may reach: b for b*(1 +- rel_tol)."""
-    outs = []
-    for f in (1.0, 1.0 - rel_tol, 1.0 + rel_tol):
-        v = clamp_budget(b_star * f, b0, n_s, cap_frac)
-        if v not in outs:
-            outs.append(v)
-    return outs
+    """Budgets a correct fp32-statistics implementation may reach: the clamped ceil(b') of every b' within
+    rel_tol (relative) of b*, the oracle's own budget first."""
+    own = clamp_budget(b_star, b0, n_s, cap_frac)
+    if not math.isfinite(b_star):
+        return [own]
+    lo = clamp_budget(b_star * (1.0 - rel_tol), b0, n_s, cap_frac)
+    hi = clamp_budget(b_star * (1.0 + rel_tol), b0, n_s, cap_frac)
+    return [own] + [v for v in range(min(lo, hi), max(lo, hi) + 1) if v != own]
 
 
 # --------------------------------------------------------------------------
