@@ -20,7 +20,8 @@ def _draw_case(rng):
     d = int(rng.choice([64, 128]))
     g = int(rng.choice([1, 2, 4, 8]))
     hkv = int(rng.choice([1, 2]))
-    n_max = int(rng.choice([48, 130, 517, 1000, 2048, 3100, 4500])) // 16 * 16
+    page = int(rng.choice([8, 16, 16, 64, 256]))
+    n_max = max(int(rng.choice([48, 130, 517, 1000, 2048, 3100, 4500])) // page * page, page)
     batch = int(rng.integers(1, 4))
     lens = [int(rng.integers(1, n_max + 1)) for _ in range(batch)]
     lens[0] = n_max
@@ -41,7 +42,7 @@ def _draw_case(rng):
     opts = dict(small_batches=bool(rng.random() < 0.2), general_topk=bool(rng.random() < 0.2),
                 wide=bool(rng.random() < 0.2), nested=bool(rng.random() < 0.25),
                 hoeffding=bool(over["target"] == 0 and rng.random() < 0.25))
-    return dict(d=d, g=g, hkv=hkv, n_max=n_max, batch=batch, lens=lens, over=over, opts=opts,
+    return dict(d=d, g=g, hkv=hkv, n_max=n_max, batch=batch, lens=lens, over=over, opts=opts, page=page,
                 paged=bool(rng.random() < 0.4), q_len=int(rng.choice([1, 1, 1, 2, 3])),
                 v_mean=float(rng.choice([0.0, 1.0])), flat=bool(rng.random() < 0.5))
 
@@ -62,13 +63,13 @@ def test_random_configurations_match_the_oracle():
         q_len = c["q_len"]
         if q_len > 1:
             wl.seq_lens = np.maximum(wl.seq_lens, q_len).astype(np.int32)   # a chunk never exceeds its sequence
-        say("random case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s q_len=%d %s %s" % (
-            case, c["d"], c["g"], c["hkv"], c["n_max"], [int(x) for x in wl.seq_lens], c["paged"], q_len, c["over"],
+        say("random case %d: d=%d G=%d Hkv=%d n_max=%d lens=%s paged=%s/%d q_len=%d %s %s" % (
+            case, c["d"], c["g"], c["hkv"], c["n_max"], [int(x) for x in wl.seq_lens], c["paged"], c["page"], q_len, c["over"],
             {k: v for k, v in c["opts"].items() if v}))
         q_bits = workloads.chunk_queries(wl, q_len, seed=case) if q_len > 1 else wl.q_bits
         if c["paged"]:
-            k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
-            sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]), q_len=q_len)
+            k_pages, v_pages, table = workloads.to_paged(wl, page=c["page"], seed=case)
+            sess = DecodeSession(plan_params(wl, paged=True, page=c["page"], num_blocks=k_pages.shape[0]), q_len=q_len)
             sess.upload(q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
         else:
             sess = DecodeSession(plan_params(wl), q_len=q_len)
@@ -114,8 +115,8 @@ def test_random_configurations_with_caller_supplied_topk():
             c["over"]))
         q_bits = workloads.chunk_queries(wl, q_len, seed=case) if q_len > 1 else wl.q_bits
         if c["paged"]:
-            k_pages, v_pages, table = workloads.to_paged(wl, page=16, seed=case)
-            sess = DecodeSession(plan_params(wl, paged=True, page=16, num_blocks=k_pages.shape[0]), q_len=q_len)
+            k_pages, v_pages, table = workloads.to_paged(wl, page=c["page"], seed=case)
+            sess = DecodeSession(plan_params(wl, paged=True, page=c["page"], num_blocks=k_pages.shape[0]), q_len=q_len)
             sess.upload(q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
         else:
             sess = DecodeSession(plan_params(wl), q_len=q_len)
