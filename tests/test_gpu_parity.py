@@ -584,3 +584,17 @@ def test_many_short_sequences():
         res = _run(sess)
         check_all(wl, res, label="many short sequences, paged=%s" % paged)
         sess.close()
+
+
+def test_seeds_use_all_64_bits():
+    # the sampler's Philox key is (low word, high word) of the 64-bit seed: seeds that differ only in the high word,
+    # or have the top bit set, must reach the kernels intact
+    say("64-bit seeds")
+    wl = workloads.small_gqa(seed=85, batch=4, n=3000, seq_lens=[3000, 3000, 2500, 2500])
+    wl.seeds = np.array([0xFFFFFFFFFFFFFFFF, 1 << 63, (7 << 32) | 5, 5], dtype=np.uint64)
+    sess = _session(wl)
+    res = _run(sess)
+    check_all(wl, res, label="64-bit seeds")
+    a, b = gpu_segments(res, 2, 0), gpu_segments(res, 3, 0)   # same low word, different high word
+    assert not np.array_equal(a["I_bs"], b["I_bs"])
+    sess.close()
