@@ -204,6 +204,31 @@ def test_uniform_sample_worked_example_from_the_published_vector():
     assert _sample(residual, 0, 0, lo=5, L=10).tolist() == []
 
 
+def test_decode_head_draws_over_the_middle_region_worked_example():
+    # The same published vector, now through decode_head: 20 tokens, sink 5, window 5 -> the middle region is
+    # tokens 5 .. 14 (10 tokens), so with seed 0 and head 0 the base sample's draws propose tokens 8, 13, 12, 11
+    # whatever the scores are.  (Drawing over a longer or shifted range, e.g. including the window, would
+    # propose other tokens: floor(0x6627e8d5 * 15 / 2^32) = 5.)
+    rng = np.random.default_rng(3)
+    q, K, V = rng.standard_normal(8), rng.standard_normal((20, 8)), rng.standard_normal((20, 8))
+    params = dict(sm_scale=0.3, sink=5, window=5, topk_abs=0, topk_frac=0.0, base_abs=3, base_frac=0.0,
+                  epsilon=0.9, delta=0.9, target=vo.TARGET_D, budget_cap_frac=1.0)
+    r = vo.decode_head(q, K, V, seed=0, head=0, params=params)
+    assert r["n_s"] == 10 and r["I_bs"].tolist() == [8, 12, 13]
+    # token 13 made the largest score of the middle region and k = 1: it is in I_t, its draw is skipped
+    K2 = K.copy()
+    K2[13] = 50.0 * q / np.linalg.norm(q)
+    r = vo.decode_head(q, K2, V, seed=0, head=0, params=dict(params, topk_abs=1))
+    assert r["I_t"].tolist() == [13] and r["n_s"] == 9 and r["I_bs"].tolist() == [8, 11, 12]
+    # nested samples: the base sample is kept and the extension comes from the second draw sequence (stream 1),
+    # skipping the base sample; the first sequence would continue with token 11
+    ok, val = vo.bounded_draw(vo.draw_words(0, 64, 0, 0, 1), 10)
+    second = [5 + int(v) for a, v in zip(ok, val) if a and 5 + int(v) not in (8, 12, 13)]
+    r = vo.decode_head(q, K, V, seed=0, head=0, params=dict(params, nested=True), forced_b=4)
+    assert r["I_bs"].tolist() == [8, 12, 13] and r["I_dyn"].tolist() == sorted([8, 12, 13, second[0]])
+    assert second[0] != 11
+
+
 def test_uniform_sample_invariants():
     residual = np.setdiff1d(np.arange(10, 480), np.arange(50, 400, 7))
     n_s = len(residual)
@@ -223,6 +248,18 @@ def test_uniform_sample_invariants():
         prev = smp
     assert np.array_equal(_sample(residual, 60, 42, head=2, lo=10, L=470), _sample(residual, 60, 42, head=2, lo=10, L=470))
     assert not np.array_equal(_sample(residual, 60, 42, head=2, lo=10, L=470), _sample(residual, 60, 42, head=2, stream=1, lo=10, L=470))
+
+
+def test_default_draw_cap_does_not_disturb_uniformity_of_a_sparse_residual():
+    # two residual tokens in a middle region of 1000 (everything else is in the top-k set): a draw hits one of
+    # them with probability 1/500, so a sample needs about 500 draws and sometimes several thousand.  The draw
+    # limit must be far beyond that, or the fall-back (lowest index first) would favour token 300: with a limit
+    # of 1000 draws it would be chosen in 57 % of the seeds.
+    residual = np.array([300, 700])
+    first = sum(int(vo.uniform_sample(residual, 1, mid_lo=100, mid_len=1000, seed=s, head=0, stream=0)[0] == 300)
+                for s in range(1500))
+    assert abs(first / 1500.0 - 0.5) < 4.0 * math.sqrt(0.25 / 1500.0)
+    assert vo.default_draw_cap(1000) >= 64 * 1000
 
 
 def test_uniform_sample_draw_cap_completes_in_index_order():
@@ -500,6 +537,9 @@ def test_alternatives_enumerate_near_ties():
     alts = vo.topk_alternatives(s, 0, 0, 3, rel_tol=1e-5)
     assert [a.tolist() for a in alts] == [[0, 1, 3], [0, 1, 2]]
     assert len(vo.topk_alternatives(s, 0, 0, 2, rel_tol=1e-5)) == 1
+    # the tolerance is relative: at scores near 300 a gap of 1e-3 is a tie (3e-6 relative), a gap of 1e-2 is not
+    big = np.array([500.0, 300.0, 300.0 + 1e-3, 300.0 - 1e-2, 10.0])
+    assert [a.tolist() for a in vo.topk_alternatives(big, 0, 0, 2, rel_tol=1e-5)] == [[0, 2], [0, 1]]
     assert vo.budget_alternatives(100.000001, 10, 1000, 1.0) == [101, 100]
     assert vo.budget_alternatives(100.5, 10, 1000, 1.0) == [101]
     r = vo.decode_head(*_scalar_head(s), seed=1, head=0,
@@ -508,21 +548,33 @@ def test_alternatives_enumerate_near_ties():
 
 
 def test_decode_batch_maps_gqa_heads():
+    # the batch driver against Algorithm 1 called by hand on hand-sliced inputs, for every (sequence, head):
+    # query head h reads KV head h // 4, draws with its own index h and the seed of its sequence, and sees
+    # seq_lens[b] tokens
     rng = np.random.default_rng(10)
-    B, Hq, Hkv, n, d = 2, 4, 2, 64, 8
+    B, Hq, Hkv, n, d = 2, 8, 2, 200, 8
     q = rng.standard_normal((B, Hq, d))
     K = rng.standard_normal((B, Hkv, n, d))
     V = rng.standard_normal((B, Hkv, n, d))
-    lens = np.array([64, 40])
+    lens = np.array([200, 140])
     seeds = np.array([7, 8], dtype=np.uint64)
-    p = _params(sink=2, window=2, topk_abs=4, base_abs=6, sm_scale=0.3)
+    p = _params(sink=2, window=2, topk_abs=4, base_abs=16, sm_scale=0.3, epsilon=0.5, delta=0.5)
     out = vo.decode(q, K, V, lens, seeds, p)
     assert set(out) == {(b, h) for b in range(B) for h in range(Hq)}
-    one = vo.decode_head(q[1, 3], K[1, 1, :40], V[1, 1, :40], seed=8, head=3, params=p)
-    assert np.array_equal(out[(1, 3)]["I_dyn"], one["I_dyn"])
-    assert np.allclose(out[(1, 3)]["O"], one["O"])
-    # heads of one group share K but not their samples
-    assert not np.array_equal(out[(0, 0)]["I_bs"], out[(0, 1)]["I_bs"])
+    for b in range(B):
+        for h in range(Hq):
+            kv = [0, 0, 0, 0, 1, 1, 1, 1][h]
+            one = vo.decode_head(q[b, h], K[b, kv, :lens[b]], V[b, kv, :lens[b]], seed=int(seeds[b]), head=h, params=p)
+            assert out[(b, h)]["n"] == lens[b]
+            for key in ("I_t", "I_bs", "I_dyn"):
+                assert np.array_equal(out[(b, h)][key], one[key]), (b, h, key)
+            assert np.allclose(out[(b, h)]["O"], one["O"], rtol=0, atol=0)
+    assert any(out[(b, h)]["b"] < out[(b, h)]["n_s"] for b in range(B) for h in range(Hq))   # real samples
+    # the draws do depend on the head index and on the sequence's seed
+    other_head = vo.decode_head(q[1, 3], K[1, 0, :140], V[1, 0, :140], seed=8, head=0, params=p)
+    other_seed = vo.decode_head(q[1, 3], K[1, 0, :140], V[1, 0, :140], seed=7, head=3, params=p)
+    assert not np.array_equal(out[(1, 3)]["I_bs"], other_head["I_bs"])
+    assert not np.array_equal(out[(1, 3)]["I_bs"], other_seed["I_bs"])
 
 
 # ------------------------------------------------- multi-query step (chunk) ----
@@ -605,6 +657,30 @@ def test_chunk_queries_draw_independent_samples_from_their_own_residual():
         samples.append(set(r["I_dyn"].tolist()))
     # different query tokens use different draw sequences
     assert samples[0] != samples[1] and samples[1] != samples[2]
+
+
+def test_chunk_driver_passes_prefix_query_position_head_and_seed():
+    # every (sequence, query token, head) of the chunk driver against Algorithm 1 called by hand on the causal
+    # prefix, with the query's position as the last counter word
+    rng = np.random.default_rng(34)
+    B, Q, Hq, Hkv, n, d = 2, 3, 4, 2, 300, 8
+    q = rng.standard_normal((B, Q, Hq, d))
+    K = rng.standard_normal((B, Hkv, n, d))
+    V = rng.standard_normal((B, Hkv, n, d))
+    lens, seeds = np.array([300, 170]), np.array([21, 22], dtype=np.uint64)
+    p = _params(sink=3, window=5, topk_abs=8, base_abs=24, sm_scale=0.35, epsilon=0.5, delta=0.5)
+    res = vo.decode_chunk(q, K, V, lens, seeds, p)
+    assert set(res) == {(b, t, h) for b in range(B) for t in range(Q) for h in range(Hq)}
+    for (b, t, h), r in res.items():
+        nt = int(lens[b]) - (Q - 1 - t)
+        kv = [0, 0, 1, 1][h]
+        one = vo.decode_head(q[b, t, h], K[b, kv, :nt], V[b, kv, :nt], seed=int(seeds[b]), head=h, params=p, query=t)
+        for key in ("I_t", "I_bs", "I_dyn"):
+            assert np.array_equal(r[key], one[key]), (b, t, h, key)
+        assert np.array_equal(r["O"], one["O"])
+        if t > 0:   # the position does change the draws
+            zero = vo.decode_head(q[b, t, h], K[b, kv, :nt], V[b, kv, :nt], seed=int(seeds[b]), head=h, params=p)
+            assert not np.array_equal(r["I_bs"], zero["I_bs"])
 
 
 # ------------------------------------------------ Hoeffding-type budget ----
