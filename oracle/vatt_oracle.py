@@ -341,19 +341,29 @@ def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, 
     raise ValueError("unknown target")
 
 
-def clamp_budget(b_star: float, b0: int, n_s: int, cap_frac: float) -> int:
+def clamp_budget(b_star: float, b0: int, n_s: int, cap_frac: float, multiple: int = 1) -> int:
     """b = min(n_s, max(b0', min(ceil(b*), ceil(cap_frac * n_s)))).
 
     The budget is lower capped by the base sample size (as the paper does in
     its experiments) and cannot exceed the residual count when sampling
     without replacement.  cap_frac = 1 leaves it uncapped.
+
+    multiple > 1 (an option beyond the paper, for hardware that reads rows in
+    groups): b is then rounded up to the next multiple of `multiple`, but not
+    beyond min(n_s, max(b0', ceil(cap_frac * n_s))), the largest value the rule
+    above can give.  Rounding up only adds samples, so the guarantee stands.
     """
     cap = int(math.ceil(np.float64(np.float32(cap_frac)) * n_s))
     if not math.isfinite(b_star) or b_star >= n_s:
         want = n_s
     else:
         want = int(math.ceil(b_star))
-    return int(min(n_s, max(b0, min(want, cap))))
+    b = int(min(n_s, max(b0, min(want, cap))))
+    q = int(multiple)
+    if q > 1:
+        top = int(min(n_s, max(b0, cap)))
+        b = min(top, (b + q - 1) // q * q)
+    return b
 
 
 def estimate(s: np.ndarray, V: np.ndarray, m: float, I_f: np.ndarray, I_dyn: np.ndarray, n_s: int):
@@ -420,7 +430,8 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
     b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target,
                         bound=str(params.get("bound", "clt")))
-    b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)))
+    b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)),
+                     int(params.get("budget_multiple", 1)))
     if forced_b is not None:
         b = int(forced_b)
     if params.get("nested"):
@@ -479,15 +490,21 @@ def topk_alternatives(s: np.ndarray, sink: int, window: int, k: int, rel_tol: fl
     return alts
 
 
-def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-4) -> List[int]:
+def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-4,
+                        multiple: int = 1) -> List[int]:
     """Budgets a correct fp32-statistics implementation may reach: the clamped ceil(b') of every b' within
     rel_tol (relative) of b*, the oracle's own budget first."""
-    own = clamp_budget(b_star, b0, n_s, cap_frac)
+    own = clamp_budget(b_star, b0, n_s, cap_frac, multiple)
     if not math.isfinite(b_star):
         return [own]
     lo = clamp_budget(b_star * (1.0 - rel_tol), b0, n_s, cap_frac)
     hi = clamp_budget(b_star * (1.0 + rel_tol), b0, n_s, cap_frac)
-    return [own] + [v for v in range(min(lo, hi), max(lo, hi) + 1) if v != own]
+    out = [own]
+    for v in range(min(lo, hi), max(lo, hi) + 1):        # every ceil(b') in the range, then the same rounding
+        w = clamp_budget(float(v), b0, n_s, cap_frac, multiple)
+        if w not in out:
+            out.append(w)
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -532,6 +532,34 @@ def test_clamp_budget_cases():
     assert vo.clamp_budget(3.0, 2, 2, 1.0) == 2
 
 
+def test_clamp_budget_rounds_up_to_a_multiple_when_asked():
+    # an option beyond the paper: b goes up to the next multiple of 64, never beyond what the plain rule can reach
+    assert vo.clamp_budget(100.2, 32, 1000, 1.0, 64) == 128
+    assert vo.clamp_budget(128.0, 32, 1000, 1.0, 64) == 128       # a multiple stays
+    assert vo.clamp_budget(128.5, 32, 1000, 1.0, 64) == 192
+    assert vo.clamp_budget(0.0, 32, 1000, 1.0, 64) == 64          # the lower cap first, then the rounding
+    assert vo.clamp_budget(990.0, 32, 1000, 1.0, 64) == 1000      # 1024 would exceed the residual
+    assert vo.clamp_budget(800.0, 32, 1000, 0.5, 64) == 500       # ... or the explicit cap
+    assert vo.clamp_budget(200.0, 32, 1000, 0.5, 64) == 256
+    assert vo.clamp_budget(3.0, 600, 1000, 0.5, 64) == 600        # lower cap above the explicit cap: nothing above it
+    assert vo.clamp_budget(100.2, 32, 1000, 1.0, 1) == 101
+    for b_star in (0.0, 17.3, 64.0, 65.0, 400.0, 5000.0):         # never fewer samples than the paper's rule
+        for q in (2, 16, 64, 100):
+            plain, rounded = vo.clamp_budget(b_star, 8, 777, 1.0), vo.clamp_budget(b_star, 8, 777, 1.0, q)
+            assert plain <= rounded <= 777 and (rounded % q == 0 or rounded == 777) and rounded - plain < q
+    # the legal budgets near an integer b* follow the same rounding
+    assert vo.budget_alternatives(128.000001, 10, 1000, 1.0, multiple=64) == [192, 128]
+    assert vo.budget_alternatives(100.5, 10, 1000, 1.0, multiple=64) == [128]
+    # through Algorithm 1: the final sample has the rounded size and the estimate stays exact over all samples
+    rng = np.random.default_rng(5)
+    q, K, V = _rand_head(rng, 400, 8)
+    p = _params(sink=4, window=4, topk_abs=8, base_abs=20, sm_scale=0.4, epsilon=0.2, delta=0.2)
+    plain = vo.decode_head(q, K, V, seed=3, head=1, params=p)
+    rounded = vo.decode_head(q, K, V, seed=3, head=1, params=dict(p, budget_multiple=64))
+    assert plain["b_star"] == rounded["b_star"] and np.array_equal(plain["I_bs"], rounded["I_bs"])
+    assert plain["b"] % 64 != 0 and rounded["b"] == (plain["b"] + 63) // 64 * 64 == len(rounded["I_dyn"])
+
+
 def test_alternatives_enumerate_near_ties():
     s = np.array([5.0, 4.0, 3.0, 3.0 + 1e-7, 2.0, 1.0, 0.0])
     alts = vo.topk_alternatives(s, 0, 0, 3, rel_tol=1e-5)
