@@ -271,6 +271,8 @@ def main():
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
     ap.add_argument("--nested", action="store_true",
                     help="nested samples (an option beyond the paper): the final sample keeps the base sample")
+    ap.add_argument("--budget-multiple", type=int, default=1,
+                    help="round every budget up to a multiple of this (an option beyond the paper; 1 = the paper's rule)")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
@@ -297,6 +299,9 @@ def main():
         return
     wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
     sess = DecodeSession(plan_params(wl))
+    if args.budget_multiple != 1:
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_BUDGET_MULTIPLE, args.budget_multiple)
     if args.nested:
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_NESTED_SAMPLES, 1)
@@ -406,7 +411,8 @@ def main():
     us_layer = ms_step * 1e3
     out = {
         "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else "")
-                  + ("_nested_samples" if args.nested else ""),
+                  + ("_nested_samples" if args.nested else "")
+                  + ("_budget_multiple_%d" % args.budget_multiple if args.budget_multiple != 1 else ""),
         "value": us_layer,
         "unit": "us",
         "n_gpus": 1,

@@ -152,7 +152,15 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * score row, which otherwise only serves short or unusual rows; results are identical.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6 };
+       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6,
+       VATT_OPT_BUDGET_MULTIPLE = 7 };
+/*
+ * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up
+ * to the next multiple of q, e.g. 16, the V rows one wave of the gather reads per instruction at d = 128, or 64.
+ * It never goes beyond min(n_s, max(b0, ceil(budget_cap_frac * n_s))), the largest value the plain rule can
+ * give, so the index buffer needs no more room.  More samples than Algorithm 2 asks for keep its guarantee.
+ * out_budget_raw still reports b* itself.
+ */
 /*
  * VATT_OPT_HEAD_THREADS (test hook): workgroup size of the selection kernel, 512 or 1024.  The plan picks 512
  * for n_max <= 32768, and 1024 for longer rows when that costs no parallelism (the LDS of a CU holds one such

@@ -35,7 +35,9 @@ independent of I_bs; in a step with several query tokens every (query token,
 head) is an independent instance on the causal prefix of that token; the
 Hoeffding-type budget is the sub-Gaussian form that reproduces the sample ratio
 the paper reports (hoeffding_factor: the formula is a reading, pinned by that
-ratio and by the tail inequality it comes from).
+ratio and by the tail inequality it comes from).  Two options go beyond the
+paper and are off unless asked for: nested samples (the final sample extends
+the base sample) and a budget rounded up to a multiple (clamp_budget).
 """
 from __future__ import annotations
 

@@ -91,6 +91,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.topk_general_path = 0;
   pl.sampler_draw_cap = 0;
   pl.nested_samples = 0;
+  pl.budget_multiple = 1;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
@@ -278,6 +279,11 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
     // sub-Gaussian tail 2 exp(-b t^2 / (2 sigma^2)) <= delta in place of the normal quantile
     pl.z_half = std::sqrt(2.0 * std::log(2.0 / (double)pl.p.delta));
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_BUDGET_MULTIPLE) {
+    if (value < 1 || value > 65536) return VATT_E_INVALID_ARG;
+    plan->pl.budget_multiple = value;
     return VATT_OK;
   }
   if (option == VATT_OPT_SAMPLER_DRAW_CAP) {

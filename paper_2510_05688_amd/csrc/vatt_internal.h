@@ -52,6 +52,7 @@ struct Plan {
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
+  int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
   // workspace offsets (bytes)
   size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;

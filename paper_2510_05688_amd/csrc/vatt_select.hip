@@ -81,6 +81,7 @@ struct HeadArgs {
   int k_max, b0_max, b_max;
   int q_len;  // query tokens per sequence: blockIdx.y = sequence * q_len + query token
   int nested; // the final sample keeps the base sample and adds b - b0 tokens drawn outside it
+  int b_multiple;  // b is rounded up to a multiple of this (1: the paper's rule)
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
 };
@@ -1226,6 +1227,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     int want = hs.n_s;
     if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
     bfin = min(hs.n_s, max(hs.b0, min(want, cap)));
+    // (optional) rounded up to a multiple, not beyond the largest value the rule above can give
+    if (A.b_multiple > 1)
+      bfin = min(min(hs.n_s, max(hs.b0, cap)), (bfin + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
     bfin = min(bfin, A.b_max);
     if (tid == 0 && A.out_stats) {
       float* st = A.out_stats + (int64_t)bh * 4;
@@ -1511,6 +1515,9 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     int want = hs.n_s;
     if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
     bfin = min(hs.n_s, max(hs.b0, min(want, cap)));
+    // (optional) rounded up to a multiple, not beyond the largest value the rule above can give
+    if (A.b_multiple > 1)
+      bfin = min(min(hs.n_s, max(hs.b0, cap)), (bfin + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
     bfin = min(bfin, A.b_max);
   }
   int flags = 0;
@@ -1658,6 +1665,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.b_max = pl.b_max;
   A.q_len = pl.q_len;
   A.nested = pl.nested_samples;
+  A.b_multiple = pl.budget_multiple;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   A.given_idx = nullptr;
   A.given_cnt = nullptr;

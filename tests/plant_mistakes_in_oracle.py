@@ -59,6 +59,9 @@ M = [
  ("clamp floor", "want = int(math.ceil(b_star))", "want = int(math.floor(b_star))"),
  ("clamp no lower cap", "return int(min(n_s, max(b0, min(want, cap))))", "return int(min(n_s, min(want, cap)))"),
  ("clamp no upper", "return int(min(n_s, max(b0, min(want, cap))))", "return int(max(b0, min(want, cap)))"),
+ ("multiple rounds down", "b = min(top, (b + q - 1) // q * q)", "b = min(top, b // q * q)"),
+ ("multiple beyond the residual", "b = min(top, (b + q - 1) // q * q)", "b = (b + q - 1) // q * q"),
+ ("multiple ignores the lower cap", "top = int(min(n_s, max(b0, cap)))", "top = int(min(n_s, cap))"),
  ("estimate scale b/n_s", "scale = n_s / b\n", "scale = b / n_s\n"),
  ("estimate scale missing in N", "N = N + scale * (w_d @ V64[I_dyn])", "N = N + (w_d @ V64[I_dyn])"),
  ("estimate scale missing in D", "D = D + scale * float(w_d.sum())", "D = D + float(w_d.sum())"),

@@ -467,6 +467,48 @@ def test_nested_samples(name, over):
     sess.close()
 
 
+@pytest.mark.parametrize("name,over,q", [
+    ("d_target_64", dict(epsilon=0.02, delta=0.1), 64),          # budgets above the base sample, rounded to 64
+    ("d_target_16", dict(epsilon=0.02, delta=0.1), 16),
+    ("at_base_7", dict(), 7),                                    # budgets at the base sample: b0 rounded up
+    ("capped_64", dict(epsilon=0.004, budget_cap_frac=0.3), 64), # the rounding stops at the explicit cap
+    ("near_all_64", dict(base_frac=0.2, epsilon=0.002), 64),     # ... and at the residual count
+    ("target_sdpa_16", dict(target=2, epsilon=0.3), 16),
+])
+def test_budget_rounded_up_to_a_multiple(name, over, q):
+    say("budget rounded up to a multiple of %d: %s" % (q, name))
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=47, batch=2, n=6000, seq_lens=[6000, 3301], **over)
+    sess = _session(wl)
+    plain = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, q)
+    res = _run(sess)
+    params = dict(wl.params, budget_multiple=q)
+    reps = check_all(wl, res, params=params, label="multiple " + name)
+    b_plain, b_round = plain["counts"][..., 4].astype(np.int64), res["counts"][..., 4].astype(np.int64)
+    n_s, b0 = res["counts"][..., 5].astype(np.int64), res["counts"][..., 3].astype(np.int64)
+    cap = np.ceil(np.float64(np.float32(wl.params["budget_cap_frac"])) * n_s).astype(np.int64)
+    top = np.minimum(n_s, np.maximum(b0, cap))
+    assert np.array_equal(b_round, np.minimum(top, (b_plain + q - 1) // q * q))
+    assert np.array_equal(res["b_star"], plain["b_star"])           # b* itself is not touched
+    assert np.any(b_round > b_plain)
+    if name == "capped_64":
+        assert np.any((b_round == top) & (b_round % q != 0))
+    # the same option on the path with a caller-supplied top-k set
+    if name == "d_target_64":
+        seg = res["seg"]
+        topk_idx = sess.out_idx[:, :, seg[2]:seg[3]].contiguous()
+        topk_cnt = sess.out_counts[:, :, 2].contiguous()
+        sess.decode_given_topk(topk_idx, topk_cnt)
+        given = sess.results_host()
+        bg = given["counts"][..., 4].astype(np.int64)
+        assert np.all((bg % q == 0) | (bg == top)) and np.array_equal(given["counts"][..., 2], res["counts"][..., 2])
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, 1)
+    back = _run(sess)
+    assert np.array_equal(back["counts"], plain["counts"])
+    sess.close()
+
+
 def test_selection_kernel_with_1024_threads_gives_identical_results():
     say("selection kernel with 1024 threads (the variant for rows longer than 32768 tokens)")
     from paper_2510_05688_amd import binding as vb

@@ -47,6 +47,11 @@ def _draw_case(rng):
                 v_mean=float(rng.choice([0.0, 1.0])), flat=bool(rng.random() < 0.5))
 
 
+def _budget_multiple(c):
+    """The budget rounding of a case, derived from what was drawn (so that adding it left the cases as they were)."""
+    return (1, 1, 16, 64, 7)[(c["n_max"] + c["batch"]) % 5]
+
+
 @pytest.mark.timeout(900)
 def test_random_configurations_match_the_oracle():
     from paper_2510_05688_amd.session import DecodeSession
@@ -81,7 +86,10 @@ def test_random_configurations_match_the_oracle():
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, int(o["nested"]))
         if o["hoeffding"]:
             vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
-        oracle_params = dict(wl.params, nested=o["nested"], bound="hoeffding" if o["hoeffding"] else "clt")
+        multiple = _budget_multiple(c)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, multiple)
+        oracle_params = dict(wl.params, nested=o["nested"], bound="hoeffding" if o["hoeffding"] else "clt",
+                             budget_multiple=multiple)
         sess.decode()
         res = sess.results_host()
         view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
@@ -122,6 +130,8 @@ def test_random_configurations_with_caller_supplied_topk():
             sess = DecodeSession(plan_params(wl), q_len=q_len)
             sess.upload(q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, int(nested))
+        multiple = _budget_multiple(c)
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, multiple)
         view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
         k_max = vb.vatt_plan_index_segment(sess.plan, 3) - vb.vatt_plan_index_segment(sess.plan, 2)
         rows, Hq, g = view.batch, wl.n_q_heads, c["g"]
@@ -144,7 +154,7 @@ def test_random_configurations_with_caller_supplied_topk():
                 cnt[v, h] = len(lst)
         sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
         res = sess.results_host()
-        params = dict(wl.params, nested=nested)
+        params = dict(wl.params, nested=nested, budget_multiple=multiple)
         for v in range(rows):
             for h in range(Hq):
                 check_head_given(view, res, v, h, supplied[(v, h)], params=params, label="random given %d" % case)

@@ -139,6 +139,22 @@ def test_budget_bound_option_and_chunk_plans_on_the_host():
             vb.vatt_plan_create_chunk(_base(), bad, -1)
 
 
+def test_budget_multiple_option_is_checked_on_the_host():
+    plan = vb.vatt_plan_create(_base(), -1)
+    try:
+        for q in (1, 2, 16, 64, 65536):
+            vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_MULTIPLE, q)
+        for bad in (0, -4, 65537):
+            with pytest.raises(vb.VattError) as e:
+                vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_MULTIPLE, bad)
+            assert e.value.status == vb.VATT_E_INVALID_ARG
+        cap = vb.vatt_plan_index_capacity(plan)
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_BUDGET_MULTIPLE, 64)
+        assert vb.vatt_plan_index_capacity(plan) == cap      # the rounding never needs a longer index buffer
+    finally:
+        vb.vatt_plan_destroy(plan)
+
+
 def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
     import subprocess
     src = os.path.join(ROOT, "tests", "c_abi", "plan_from_c.c")
