@@ -137,6 +137,21 @@ def test_given_topk_config2_sampled_heads():
     sess.close()
 
 
+@pytest.mark.timeout(300)
+def test_given_topk_config4_size_sampled_heads():
+    say("config 4 shape (n = 131072, B = 1), given top-k from noisy scores, 5 heads checked")
+    wl = workloads.config4(batch=1)
+    sess = _session(wl)
+    rng = np.random.default_rng(5)
+    heads = [0, 3, 14, 21, 31]
+    supplied = {(0, h): (_oracle_topk(wl, 0, h, noise=0.3, rng=rng) if h in heads else np.empty(0, np.int64))
+                for h in range(wl.n_q_heads)}
+    res = _run_given(sess, wl, supplied)
+    for h in heads:
+        check_head_given(wl, res, 0, h, supplied[(0, h)], label="config4")
+    sess.close()
+
+
 @pytest.mark.parametrize("d,hq,hkv", [(64, 8, 1), (64, 4, 4), (128, 16, 2)])
 def test_given_topk_other_head_shapes(d, hq, hkv):
     say("given top-k, d=%d, %d/%d heads" % (d, hq, hkv))
