@@ -1,6 +1,7 @@
 // Dense decode attention (Eq. 1) on the same cache, and the KV append.
 //
-// dense_kernel: grid = (splits, KV heads, sequences).  A workgroup owns a contiguous key range; each
+// dense_kernel: grid = (KV heads, splits, sequences), KV head fastest so that the partials of a KV head stay in
+// the L2 of one XCD, where the merge of its heads runs.  A workgroup owns a contiguous key range; each
 // wave walks its quarter of it, 4 (d = 128) rows per load, computing the G scores of a row with
 // the same lane layout as the score pass and keeping a running (max, sum, accumulator) per lane
 // group -- no LDS traffic inside the loop.  Lane groups, waves and finally splits are merged by
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   constexpr int WAVES = kDenseThreads / kWave;
   constexpr int U = 4;
 
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;
@@ -177,8 +178,12 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
 // that their loads are independent and can be in flight together.
 template <int D>
 __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restrict__ part, int splits, int Hq,
-                                                            float* __restrict__ out_o, float* __restrict__ out_lse) {
-  const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
+                                                            int Hkv, float* __restrict__ out_o,
+                                                            float* __restrict__ out_lse) {
+  // blockIdx.x runs over the KV heads first, then over the heads of a group: a head's merge then sits on the XCD
+  // (workgroups go to the XCDs round-robin in launch order) whose L2 holds the partials of its KV head
+  const int kvh = blockIdx.x % Hkv, g = blockIdx.x / Hkv;
+  const int h = kvh * (Hq / Hkv) + g, b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x % D, half = threadIdx.x / D;
   const float* p = part + (int64_t)bh * splits * (D + 4);
   __shared__ float s_m[128], s_l[128], s_a[D];
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restr
 template <int D, int G>
 hipError_t launch_dense_dg(const Plan& pl, DenseArgs& A, hipStream_t st) {
   const vatt_params& p = pl.p;
-  dim3 grid(pl.dense_splits, p.n_kv_heads, pl.vbatch);
+  dim3 grid(p.n_kv_heads, pl.dense_splits, pl.vbatch);
   if (p.kv_layout == VATT_LAYOUT_PAGED)
     hipLaunchKernelGGL((dense_kernel<D, G, true>), grid, dim3(kDenseThreads), 0, st, A);
   else
@@ -213,7 +218,7 @@ hipError_t launch_dense_dg(const Plan& pl, DenseArgs& A, hipStream_t st) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(2 * D), 0, st, A.part, pl.dense_splits,
-                     p.n_q_heads, A.out_o, A.out_lse);
+                     p.n_q_heads, p.n_kv_heads, A.out_o, A.out_lse);
   return hipGetLastError();
 }
 

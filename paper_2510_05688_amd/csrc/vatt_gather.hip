@@ -5,10 +5,15 @@
 // different workgroups add directly).  Also the V-side statistics of Algorithm 2 for the numerator and
 // SDPA targets (N_f, sum r_i and sum ||r_i||^2 over the base sample, r_i = w_i V[i]).
 //
-// grid = (splits, query heads, sequences).  A workgroup walks its slice of the head's token list 16 rows
+// grid = (query heads, splits, sequences).  A workgroup walks its slice of the head's token list 16 rows
 // (d = 128) at a time: d/8 adjacent lanes read one 256-byte V row with one 16-byte load each.  With more
 // than one split per head a small second kernel adds the per-split partials in split order and writes
 // O and ln D (a kernel boundary is the cheapest device-wide ordering point on this chip).
+// The head index is the fastest grid dimension on purpose: workgroups go to the chip's eight XCDs round-robin
+// in launch order, so with a head count that is a multiple of eight all workgroups of head h, in the selection
+// kernel, here and in the merge kernel, run on XCD h mod 8, and the index list, the head record and the
+// partial sums are found in that XCD's L2 instead of being fetched from memory (measured: 46.4 -> 45.1 us per
+// call at batch 1).
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -53,7 +58,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   constexpr int RPB = RPW * WAVES;  // rows per workgroup step
   constexpr int U = 8;              // independent rows in flight per lane
 
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int seq = b / A.q_len;  // the sequence whose cache this (sequence, query token) pair reads
@@ -239,7 +244,7 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   A.group = pl.group;
   A.splits = STATS ? pl.vstat_splits : pl.gather_splits;
   A.q_len = pl.q_len;
-  dim3 grid(A.splits, p.n_q_heads, pl.vbatch);
+  dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   if (p.kv_layout == VATT_LAYOUT_PAGED)
     hipLaunchKernelGGL((gather_kernel<D, true, STATS>), grid, dim3(kGatherThreads), 0, st, A);
   else

@@ -11,8 +11,9 @@
 //                         running maximum and rescales (online softmax), and the merge combines the splits'
 //                         (max, D, N) partials the same way.
 //
-// grid = (splits, query heads, sequences) for both; d/8 adjacent lanes read one K or V row with one 16-byte
-// load each.
+// grid = (query heads, splits, sequences) for both (head fastest: all workgroups of a head then share an XCD and
+// its L2 with the selection and merge kernels of that head); d/8 adjacent lanes read one K or V row with one
+// 16-byte load each.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
   constexpr int RPB = RPW * WAVES;
   constexpr int GROUPS = RPB;
   constexpr int U = 8;
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
   constexpr int RPB = RPW * WAVES;
   constexpr int GROUPS = RPB;  // lane groups of a workgroup, each with its own running maximum
   constexpr int U = 8;
-  const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -371,7 +372,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.splits = pl.given_splits;
   A.q_len = pl.q_len;
   A.sm_scale = pl.sm_scale;
-  dim3 grid(A.splits, p.n_q_heads, pl.vbatch);
+  dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
   if (stage == 0) {
     const bool stats = p.target != VATT_TARGET_D;
