@@ -93,6 +93,11 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.nested_samples = 0;
   pl.budget_multiple = 1;
 
+  // All tiles of a KV head on one XCD, with the workgroups of its query heads in the later kernels on the same
+  // one (see the score kernel): pays up to 64K tokens, costs the K stream 5 % at 128K.  Single-query plans only
+  // (the multi-query score kernel has its own launch order).
+  pl.kv_major = (p.n_kv_heads % 8 == 0 && p.n_max <= 65536 && q_len == 1) ? 1 : 0;
+
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
   pl.n_sub = (int)align_up((size_t)n_max, kScoreTilePaged) / kSubTile;  // whole tiles of either tile size
@@ -284,6 +289,11 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   if (option == VATT_OPT_BUDGET_MULTIPLE) {
     if (value < 1 || value > 65536) return VATT_E_INVALID_ARG;
     plan->pl.budget_multiple = value;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_KV_HEAD_MAJOR) {
+    if (plan->pl.q_len != 1 && value) return VATT_E_UNSUPPORTED_SHAPE;
+    plan->pl.kv_major = value ? 1 : 0;
     return VATT_OK;
   }
   if (option == VATT_OPT_SAMPLER_DRAW_CAP) {

@@ -182,8 +182,7 @@ __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restr
                                                             float* __restrict__ out_lse) {
   // blockIdx.x runs over the KV heads first, then over the heads of a group: a head's merge then sits on the XCD
   // (workgroups go to the XCDs round-robin in launch order) whose L2 holds the partials of its KV head
-  const int kvh = blockIdx.x % Hkv, g = blockIdx.x / Hkv;
-  const int h = kvh * (Hq / Hkv) + g, b = blockIdx.y, bh = b * Hq + h;
+  const int h = head_of_block((int)blockIdx.x, Hq, Hkv, 1), b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x % D, half = threadIdx.x / D;
   const float* p = part + (int64_t)bh * splits * (D + 4);
   __shared__ float s_m[128], s_l[128], s_a[D];

@@ -8,6 +8,14 @@ namespace vatt {
 
 constexpr int kWave = 64;
 
+// Query head of a workgroup whose blockIdx.x runs over the heads.  Plain order: the head is blockIdx.x.
+// KV-head-major order: blockIdx.x runs over the KV heads first and over the heads of a group second, so that
+// (workgroups go to the XCDs round-robin in launch order, and with a KV head count that is a multiple of 8)
+// the workgroups of KV head j's query heads run on XCD j mod 8, where the score kernel left their rows.
+__device__ __forceinline__ int head_of_block(int x, int Hq, int Hkv, int kv_major) {
+  return kv_major ? (x % Hkv) * (Hq / Hkv) + x / Hkv : x;
+}
+
 // Optional phase timing for kernel development: built with -DVATT_TIMING, thread 0 of workgroup 0 stores
 // the shader clock at numbered points into the VATT_WS_DEBUG region of the workspace.  Compiled out
 // otherwise.

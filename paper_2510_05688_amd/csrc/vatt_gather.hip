@@ -31,6 +31,7 @@ struct GatherArgs {
   float* out_lse;
   int64_t seg_topk, seg_base, seg_dyn, idx_cap;
   int n_pad, Hq, group, splits;
+  int kv_major, Hkv;  // see head_of_block
   int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
 };
 
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   constexpr int RPB = RPW * WAVES;  // rows per workgroup step
   constexpr int U = 8;              // independent rows in flight per lane
 
-  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.kv_major), split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int seq = b / A.q_len;  // the sequence whose cache this (sequence, query token) pair reads
@@ -205,8 +206,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
 template <int D>
 __global__ __launch_bounds__(D) void gather_merge_kernel(const float* __restrict__ part,
                                                          const HeadRec* __restrict__ head_rec, int splits, int Hq,
-                                                         float* __restrict__ out_o, float* __restrict__ out_lse) {
-  const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
+                                                         float* __restrict__ out_o, float* __restrict__ out_lse, int kv_major, int Hkv) {
+  const int h = head_of_block((int)blockIdx.x, Hq, Hkv, kv_major), b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x;
   const float* p = part + (int64_t)bh * splits * (D + 4);
   float a = 0.f, dtot = 0.f;
@@ -244,6 +245,8 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   A.group = pl.group;
   A.splits = STATS ? pl.vstat_splits : pl.gather_splits;
   A.q_len = pl.q_len;
+  A.kv_major = pl.kv_major;
+  A.Hkv = p.n_kv_heads;
   dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   if (p.kv_layout == VATT_LAYOUT_PAGED)
     hipLaunchKernelGGL((gather_kernel<D, true, STATS>), grid, dim3(kGatherThreads), 0, st, A);
@@ -252,7 +255,7 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || STATS || A.splits == 1) return e;
   hipLaunchKernelGGL((gather_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(D), 0, st, A.part, A.head_rec,
-                     A.splits, p.n_q_heads, out_o, out_lse);
+                     A.splits, p.n_q_heads, out_o, out_lse, pl.kv_major, p.n_kv_heads);
   return hipGetLastError();
 }
 

@@ -2,13 +2,22 @@
 // reading each K row from HBM once per group (first step of Algorithm 1 with exact top-k; the
 // exponent of Eq. 1).
 //
-// Work split: grid = (key tiles, KV heads, sequences); a workgroup of 4 waves owns TILE consecutive keys
-// (64 on a contiguous cache, 256 on a paged one, by measurement).  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
+// Work split: a workgroup of 4 waves owns TILE consecutive keys of one KV head (64 on a contiguous cache, 256 on
+// a paged one, by measurement).  Two launch orders.  Tile-major, grid = (key tiles, KV heads, sequences):
+// neighbouring workgroups stream neighbouring memory, and the eight XCDs (workgroups go to them round-robin in
+// launch order) share every row.  KV-head-major, grid = (KV heads, key tiles, sequences), for plans whose KV
+// head count is a multiple of 8: all tiles of KV head j run on XCD j mod 8, each XCD streams its own heads'
+// rows, and the scores and 8-key maxima it writes stay in its L2, where the selection, gather and merge
+// workgroups of those heads (placed on the same XCD by their own grids) find them.  Measured: 3 % off the
+// whole call at 32K tokens, 6 % at 64K and batch 1, nothing at 8K, and a K stream 5 % slower at 128K tokens,
+// so the plan takes this order up to 65536 tokens.  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
 // segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
 // the DPP path, and the tile's G x TILE scores are staged in LDS so that they leave as whole
 // 256-byte rows; the largest score of every 8 keys is written next to them.
+#include <utility>
+
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -25,14 +34,15 @@ template <int D, int G, bool PAGED, int TILE>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ scores, float* __restrict__ sub_max,
-                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale) {
+                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale, int kv_major) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
   constexpr int ROWS_PER_WAVE = TILE / 4;
   constexpr int LOADS = ROWS_PER_WAVE / RPW;
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
-  const int tile = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // grid = (tiles, KV heads, sequences), or (KV heads, tiles, sequences) in the KV-head-major order
+  const int tile = kv_major ? blockIdx.y : blockIdx.x, kvh = kv_major ? blockIdx.x : blockIdx.y, b = blockIdx.z;
   const int tile_lo = tile * TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR;   // which 8-column slice of the row
@@ -100,7 +110,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
     if (i < n) {
 #pragma unroll
       for (int g = 0; g < G; ++g)
-        __builtin_nontemporal_store(s_tile[g][t], &scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i]);
+      {
+        // tile-major order: only a few thousand of the scores are read again, and from other XCDs, so they
+        // leave as non-temporal stores; KV-head-major order: the readers run on this XCD, the scores stay in L2
+        float* dst = &scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i];
+        if (kv_major) *dst = s_tile[g][t]; else __builtin_nontemporal_store(s_tile[g][t], dst);
+      }
     }
   }
   // Largest score of every 8 consecutive keys per query head: the selection kernel takes its head maximum
@@ -130,14 +145,16 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   // block-table entries, does better with 256 keys in flight per workgroup)
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     dim3 grid((p.n_max + kScoreTilePaged - 1) / kScoreTilePaged, p.n_kv_heads, p.batch);
+    if (pl.kv_major) std::swap(grid.x, grid.y);
     hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.kv_major);
   } else {
     dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
+    if (pl.kv_major) std::swap(grid.x, grid.y);
     hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.kv_major);
   }
   return hipGetLastError();
 }

@@ -139,6 +139,23 @@ def test_budget_bound_option_and_chunk_plans_on_the_host():
             vb.vatt_plan_create_chunk(_base(), bad, -1)
 
 
+def test_score_order_option_on_the_host():
+    plan = vb.vatt_plan_create(_base(), -1)
+    try:
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_KV_HEAD_MAJOR, 1)
+        vb.vatt_plan_set_option(plan, vb.VATT_OPT_KV_HEAD_MAJOR, 0)
+    finally:
+        vb.vatt_plan_destroy(plan)
+    chunk = vb.vatt_plan_create_chunk(_base(), 4, -1)
+    try:
+        vb.vatt_plan_set_option(chunk, vb.VATT_OPT_KV_HEAD_MAJOR, 0)
+        with pytest.raises(vb.VattError) as e:       # the multi-query score kernel has one launch order
+            vb.vatt_plan_set_option(chunk, vb.VATT_OPT_KV_HEAD_MAJOR, 1)
+        assert e.value.status == vb.VATT_E_UNSUPPORTED_SHAPE
+    finally:
+        vb.vatt_plan_destroy(chunk)
+
+
 def test_budget_multiple_option_is_checked_on_the_host():
     plan = vb.vatt_plan_create(_base(), -1)
     try:
