@@ -155,10 +155,9 @@ enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_O
        VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6,
        VATT_OPT_BUDGET_MULTIPLE = 7, VATT_OPT_KV_HEAD_MAJOR = 8 };
 /*
- * VATT_OPT_KV_HEAD_MAJOR (test hook) = 1 / 0: launch order of the score pass and placement of the later kernels'
- * workgroups: all tiles of a KV head on one XCD, with the workgroups of its query heads on the same one, or
- * tile by tile across the XCDs.  The plan picks 1 when the KV head count is a multiple of 8 and n_max <= 65536;
- * results are identical.  Not for multi-query plans (VATT_E_UNSUPPORTED_SHAPE).
+ * VATT_OPT_KV_HEAD_MAJOR (test hook) = 1 / 0: launch order of the score pass: all tiles of a KV head on one XCD,
+ * or tile by tile across the XCDs.  The plan picks 1 when the KV head count is a multiple of 8 and
+ * n_max <= 65536; results are identical.  Not for multi-query plans (VATT_E_UNSUPPORTED_SHAPE).
  */
 /*
  * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up

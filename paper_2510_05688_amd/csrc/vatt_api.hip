@@ -93,10 +93,12 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.nested_samples = 0;
   pl.budget_multiple = 1;
 
-  // All tiles of a KV head on one XCD, with the workgroups of its query heads in the later kernels on the same
-  // one (see the score kernel): pays up to 64K tokens, costs the K stream 5 % at 128K.  Single-query plans only
-  // (the multi-query score kernel has its own launch order).
-  pl.kv_major = (p.n_kv_heads % 8 == 0 && p.n_max <= 65536 && q_len == 1) ? 1 : 0;
+  // Workgroups go to the eight XCDs round-robin in launch order.  With a multiple of 8 KV heads the selection,
+  // gather and merge kernels launch the query heads of a KV head on one XCD (they read the same sink, window and
+  // heavy V rows), and up to 64K tokens the score pass launches all tiles of a KV head on one XCD too (at 128K
+  // that order costs the K stream 5 %).  The multi-query score kernel has its own launch order.
+  pl.group_major = (p.n_kv_heads % 8 == 0) ? 1 : 0;
+  pl.kv_major = (pl.group_major && p.n_max <= 65536 && q_len == 1) ? 1 : 0;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);

@@ -1,7 +1,8 @@
 // Dense decode attention (Eq. 1) on the same cache, and the KV append.
 //
-// dense_kernel: grid = (KV heads, splits, sequences), KV head fastest so that the partials of a KV head stay in
-// the L2 of one XCD, where the merge of its heads runs.  A workgroup owns a contiguous key range; each
+// dense_kernel: grid = (KV heads, splits, sequences), KV head fastest: with 8 KV heads every XCD then streams
+// the K and V rows of one KV head front to back (measured 3 % faster at batch 4 and 16 than with the splits
+// fastest, the same at batch 1).  A workgroup owns a contiguous key range; each
 // wave walks its quarter of it, 4 (d = 128) rows per load, computing the G scores of a row with
 // the same lane layout as the score pass and keeping a running (max, sum, accumulator) per lane
 // group -- no LDS traffic inside the loop.  Lane groups, waves and finally splits are merged by
@@ -180,8 +181,7 @@ template <int D>
 __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restrict__ part, int splits, int Hq,
                                                             int Hkv, float* __restrict__ out_o,
                                                             float* __restrict__ out_lse) {
-  // blockIdx.x runs over the KV heads first, then over the heads of a group: a head's merge then sits on the XCD
-  // (workgroups go to the XCDs round-robin in launch order) whose L2 holds the partials of its KV head
+  // blockIdx.x runs over the KV heads first, then over the heads of a group (as in the dense kernel's grid)
   const int h = head_of_block((int)blockIdx.x, Hq, Hkv, 1), b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x % D, half = threadIdx.x / D;
   const float* p = part + (int64_t)bh * splits * (D + 4);

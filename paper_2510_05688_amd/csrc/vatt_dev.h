@@ -9,11 +9,12 @@ namespace vatt {
 constexpr int kWave = 64;
 
 // Query head of a workgroup whose blockIdx.x runs over the heads.  Plain order: the head is blockIdx.x.
-// KV-head-major order: blockIdx.x runs over the KV heads first and over the heads of a group second, so that
+// Group-major order: blockIdx.x runs over the KV heads first and over the heads of a group second, so that
 // (workgroups go to the XCDs round-robin in launch order, and with a KV head count that is a multiple of 8)
-// the workgroups of KV head j's query heads run on XCD j mod 8, where the score kernel left their rows.
-__device__ __forceinline__ int head_of_block(int x, int Hq, int Hkv, int kv_major) {
-  return kv_major ? (x % Hkv) * (Hq / Hkv) + x / Hkv : x;
+// the workgroups of all query heads of KV head j run on XCD j mod 8 and share its L2 while the kernel runs:
+// they read the same sink and window rows of V and many of the same heavy tokens.
+__device__ __forceinline__ int head_of_block(int x, int Hq, int Hkv, int group_major) {
+  return group_major ? (x % Hkv) * (Hq / Hkv) + x / Hkv : x;
 }
 
 // Optional phase timing for kernel development: built with -DVATT_TIMING, thread 0 of workgroup 0 stores

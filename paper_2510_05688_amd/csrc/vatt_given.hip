@@ -11,9 +11,9 @@
 //                         running maximum and rescales (online softmax), and the merge combines the splits'
 //                         (max, D, N) partials the same way.
 //
-// grid = (query heads, splits, sequences) for both (head fastest: all workgroups of a head then share an XCD and
-// its L2 with the selection and merge kernels of that head); d/8 adjacent lanes read one K or V row with one
-// 16-byte load each.
+// grid = (query heads, splits, sequences) for both, head fastest and in head_of_block order: the splits of a
+// head, and the heads of a KV head, then share an XCD and its L2 (index lists, and the K and V rows they have in
+// common); d/8 adjacent lanes read one K or V row with one 16-byte load each.
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -40,6 +40,7 @@ struct GivenArgs {
   float* out_lse;
   int64_t seg_sink, seg_win, seg_topk, seg_base, seg_dyn, idx_cap;
   int Hq, group, splits;
+  int group_major;  // see head_of_block (the KV head count is Hq / group)
   int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
   float sm_scale;
 };
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
   constexpr int RPB = RPW * WAVES;
   constexpr int GROUPS = RPB;
   constexpr int U = 8;
-  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hq / A.group, A.group_major), split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
   constexpr int RPB = RPW * WAVES;
   constexpr int GROUPS = RPB;  // lane groups of a workgroup, each with its own running maximum
   constexpr int U = 8;
-  const int h = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hq / A.group, A.group_major), split = blockIdx.y, b = blockIdx.z;
   const int bh = b * A.Hq + h;
   const int kvh = h / A.group;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -321,8 +322,9 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
 // Combines the per-split (maximum, D, N) partials of a head in split order: O = N / D, lse = M + ln D.
 template <int D>
 __global__ __launch_bounds__(D) void given_merge_kernel(const float* __restrict__ part, int splits, int Hq,
-                                                        float* __restrict__ out_o, float* __restrict__ out_lse) {
-  const int h = blockIdx.x, b = blockIdx.y, bh = b * Hq + h;
+                                                        float* __restrict__ out_o, float* __restrict__ out_lse,
+                                                        int group_major, int Hkv) {
+  const int h = head_of_block((int)blockIdx.x, Hq, Hkv, group_major), b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x;
   const float* p = part + (int64_t)bh * splits * (D + 4);
   float M = -INFINITY;
@@ -371,6 +373,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.group = pl.group;
   A.splits = pl.given_splits;
   A.q_len = pl.q_len;
+  A.group_major = pl.group_major;
   A.sm_scale = pl.sm_scale;
   dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
@@ -387,7 +390,7 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((given_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(D), 0, st, A.part, A.splits,
-                     p.n_q_heads, out_o, out_lse);
+                     p.n_q_heads, out_o, out_lse, pl.group_major, p.n_kv_heads);
   return hipGetLastError();
 }
 

@@ -51,7 +51,8 @@ struct Plan {
   int topk_general_path;          // test hook: the top-k selection always takes its general path
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
-  int kv_major;                   // score launch in KV-head-major order, heads of the later kernels placed to match
+  int group_major;                // the later kernels launch the query heads of a KV head on one XCD (head_of_block)
+  int kv_major;                   // score launch in KV-head-major order (all tiles of a KV head on one XCD)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
   // workspace offsets (bytes)

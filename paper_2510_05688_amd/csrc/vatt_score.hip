@@ -6,11 +6,11 @@
 // a paged one, by measurement).  Two launch orders.  Tile-major, grid = (key tiles, KV heads, sequences):
 // neighbouring workgroups stream neighbouring memory, and the eight XCDs (workgroups go to them round-robin in
 // launch order) share every row.  KV-head-major, grid = (KV heads, key tiles, sequences), for plans whose KV
-// head count is a multiple of 8: all tiles of KV head j run on XCD j mod 8, each XCD streams its own heads'
-// rows, and the scores and 8-key maxima it writes stay in its L2, where the selection, gather and merge
-// workgroups of those heads (placed on the same XCD by their own grids) find them.  Measured: 3 % off the
-// whole call at 32K tokens, 6 % at 64K and batch 1, nothing at 8K, and a K stream 5 % slower at 128K tokens,
-// so the plan takes this order up to 65536 tokens.  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
+// head count is a multiple of 8: all tiles of KV head j run on XCD j mod 8, so each XCD streams its own heads'
+// K rows front to back and writes whole score rows (with plain stores, which its L2 gathers into full lines).
+// Measured: the pass itself 1.5 - 2 % faster at 32K tokens, the same at 64K, 5 % slower at 128K tokens, so the
+// plan takes this order up to 65536 tokens.  (The L2 counters show that nothing written here is still in L2
+// when the next kernel reads it: the selection kernel's hits and misses are the same in both orders.)  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
 // segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
@@ -111,8 +111,8 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 #pragma unroll
       for (int g = 0; g < G; ++g)
       {
-        // tile-major order: only a few thousand of the scores are read again, and from other XCDs, so they
-        // leave as non-temporal stores; KV-head-major order: the readers run on this XCD, the scores stay in L2
+        // tile-major order: a row's neighbouring tiles are written by other XCDs, non-temporal stores are best;
+        // KV-head-major order: this XCD writes the whole row, plain stores measured up to 3 % faster
         float* dst = &scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i];
         if (kv_major) *dst = s_tile[g][t]; else __builtin_nontemporal_store(s_tile[g][t], dst);
       }

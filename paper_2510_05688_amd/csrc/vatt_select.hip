@@ -80,7 +80,7 @@ struct HeadArgs {
   int target, phase, small_batches, topk_general, vstat_splits, head_dim;
   int k_max, b0_max, b_max;
   int q_len;  // query tokens per sequence: blockIdx.y = sequence * q_len + query token
-  int kv_major, Hkv;  // see head_of_block
+  int group_major, Hkv;  // see head_of_block
   int nested; // the final sample keeps the base sample and adds b - b0 tokens drawn outside it
   int b_multiple;  // b is rounded up to a multiple of this (1: the paper's rule)
   uint32_t draw_cap;  // 0: the default 64 L + 4096
@@ -730,7 +730,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   constexpr int SW = NT / kWave;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   __shared__ TopkSmem ts;
-  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.kv_major), b = blockIdx.y;
+  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.group_major), b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
   // The sub-tile maxima the score kernel left are requested first of all, before even the sequence length is
@@ -1304,7 +1304,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   constexpr int SW = NT / kWave;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   __shared__ float s_wf[16];
-  const int h = blockIdx.x, b = blockIdx.y;
+  const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.group_major), b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;  // (sequence, query token) of a multi-query step
@@ -1666,7 +1666,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.b_max = pl.b_max;
   A.q_len = pl.q_len;
   A.nested = pl.nested_samples;
-  A.kv_major = pl.kv_major;
+  A.group_major = pl.group_major;
   A.Hkv = p.n_kv_heads;
   A.b_multiple = pl.budget_multiple;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
