@@ -8,12 +8,12 @@
  *
  *   score     s_i = sm_scale * <K[i], q>                       (exponent of Eq. 1)
  *   I_f       sink tokens + local window + exact top-k of the tokens in
- *             between                                          (Alg. 1, lines 1-5)
- *   I_bs      base sample of the residual tokens               (Alg. 2, line 1)
+ *             between                                          (Alg. 1, index sets)
+ *   I_bs      base sample of the residual tokens               (Alg. 2, sampling)
  *   stats     sigma^2, D (and Tr Sigma, ||N||) from I_f, I_bs  (Alg. 2, get-stats)
  *   b         CLT budget for the verified quantity X           (Corollaries for N and D,
  *                                                               Theorem 4.3)
- *   I_dyn     b residual tokens, uniform without replacement   (Alg. 1, line 7)
+ *   I_dyn     b residual tokens, uniform without replacement   (Alg. 1, sampling)
  *   O         N/D with N = N_f + (n_s/b) sum_{I_dyn} w_i V[i],
  *             D = D_f + (n_s/b) sum_{I_dyn} w_i                 (Section 4.1; Eq. 3)
  *
@@ -41,8 +41,8 @@
  *               (the result for that sequence is then meaningless, but no
  *               access leaves the allocation).
  *
- * Sampler (the paper asks for a uniform sample of the residual tokens, Alg. 1
- * line 7 and Alg. 2 line 1, and leaves the procedure open)
+ * Sampler (the paper asks for a uniform sample of the residual tokens in Alg. 1
+ * and in Alg. 2, and leaves the procedure open)
  *   Stream 0 is the base sample, stream 1 the final sample.  Draw j of
  *   (sequence, query head h, stream) is the 32-bit word
  *       u_j = Philox4x32-10(counter = (j >> 2, stream, h, 0),

@@ -233,7 +233,7 @@ def dense_sdpa(q: np.ndarray, K: np.ndarray, V: np.ndarray, sm_scale: float):
 
 
 def deterministic_set(s: np.ndarray, sink: int, window: int, k: int):
-    """Lines 1-5 of Algorithm 1 with oracle top-k.
+    """The deterministic index sets of Algorithm 1 (sink, local window, top-k) with oracle top-k.
 
     I_s = first `sink` tokens, I_l = last `window` tokens (not overlapping
     I_s), I_t = the k largest scores among the tokens in between (ties go to

@@ -257,7 +257,7 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 // ---------------------------------------------------------------------------
-// Per-head sizes of Algorithm 1, lines 1-5, derived from the sequence length alone.
+// Per-head sizes of Algorithm 1's index sets, derived from the sequence length alone.
 // ---------------------------------------------------------------------------
 struct HeadSizes {
   int n, n_sink, n_win, mid_lo, mid_hi, k, n_s, b0;

@@ -1,4 +1,4 @@
-// Index selection and budget: lines 1-8 of Algorithm 1 and all of Algorithm 2, per (sequence, query head),
+// Index selection and budget: Algorithm 1 up to the final sample and all of Algorithm 2, per (sequence, query head),
 // in one kernel with one workgroup per head.
 //
 // Top-k: the k largest scores of the middle region, ties to the lower token, i.e. the k smallest composites
@@ -875,7 +875,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   int topk_flag = 0;
   float acc_f32 = 0.f;  // this thread's share of D_f = sum over I_f of exp(s_i - m), kept in fp32 per thread
   double acc_f = 0.0;
-  // ---- I_t (Algorithm 1, line 3) ----
+  // ---- I_t (Algorithm 1, top-k step) ----
   if (A.phase != 2) {
     const int mid_len = hs.mid_hi - hs.mid_lo;
     if (hs.k > 0) {
@@ -1137,7 +1137,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 
   if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
 
-  // ---- I_bs (Algorithm 2, line 1) and the sums over it ----
+  // ---- I_bs (Algorithm 2, base sample) and the sums over it ----
   int flags = topk_flag;
   double acc_w = 0.0, acc_w2 = 0.0;
   if (hs.n_s > 0) {
@@ -1246,7 +1246,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   }
 
   VATT_STAMP(A.dbg, 7);
-  // ---- I_dyn (Algorithm 1, line 7) ----
+  // ---- I_dyn (Algorithm 1, final sample) ----
   if (bfin > 0) {
     const int f = A.nested ? O::draw_nested(S1, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
                                             idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
