@@ -25,6 +25,8 @@ def _draw_case(rng):
     batch = int(rng.integers(1, 4))
     lens = [int(rng.integers(1, n_max + 1)) for _ in range(batch)]
     lens[0] = n_max
+    if (n_max // page + batch) % 4 == 0:
+        hkv = 8        # (no draw of its own: the other cases stay as they were) 8 KV heads: heads placed by KV head
     over = dict(
         sink=int(rng.choice([0, 1, 4, 16, 100])), window=int(rng.choice([0, 1, 8, 24, 200])),
         epsilon=float(rng.choice([0.3, 0.1, 0.05, 0.02, 0.008])), delta=float(rng.choice([0.3, 0.1, 0.05, 0.01])),
