@@ -153,11 +153,12 @@ int vatt_plan_query_len(const vatt_plan* plan);
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
        VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6,
-       VATT_OPT_BUDGET_MULTIPLE = 7, VATT_OPT_KV_HEAD_MAJOR = 8 };
+       VATT_OPT_BUDGET_MULTIPLE = 7, VATT_OPT_SCORE_ORDER = 8 };
 /*
- * VATT_OPT_KV_HEAD_MAJOR (test hook) = 1 / 0: launch order of the score pass: all tiles of a KV head on one XCD,
- * or tile by tile across the XCDs.  The plan picks 1 when the KV head count is a multiple of 8 and
- * n_max <= 65536; results are identical.  Not for multi-query plans (VATT_E_UNSUPPORTED_SHAPE).
+ * VATT_OPT_SCORE_ORDER (test hook) = 0 / 1 / 2: launch order of the score pass, i.e. which of the chip's XCDs
+ * reads which tile: 0 tile by tile across the XCDs, 1 all tiles of a KV head on one XCD, 2 every XCD an eighth
+ * of each row.  The plan picks 1 up to n_max = 65536 when the KV head count is a multiple of 8 (else 0) and 2
+ * beyond; results are identical.  Multi-query plans have order 0 only (VATT_E_UNSUPPORTED_SHAPE otherwise).
  */
 /*
  * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up

@@ -95,10 +95,13 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
 
   // Workgroups go to the eight XCDs round-robin in launch order.  With a multiple of 8 KV heads the selection,
   // gather and merge kernels launch the query heads of a KV head on one XCD (they read the same sink, window and
-  // heavy V rows), and up to 64K tokens the score pass launches all tiles of a KV head on one XCD too (at 128K
-  // that order costs the K stream 5 %).  The multi-query score kernel has its own launch order.
+  // heavy V rows).  The score pass has three launch orders (see its kernel): by measurement the KV-head-major
+  // one up to 64K tokens when the KV heads can be dealt out to the XCDs evenly, the one that gives every XCD an
+  // eighth of each row beyond 64K tokens, the tile-major one otherwise.  (The multi-query score kernel has one
+  // order of its own.)
   pl.group_major = (p.n_kv_heads % 8 == 0) ? 1 : 0;
-  pl.kv_major = (pl.group_major && p.n_max <= 65536 && q_len == 1) ? 1 : 0;
+  pl.score_order = p.n_max > 65536 ? kScoreOrderEighths : (pl.group_major ? kScoreOrderKvHead : kScoreOrderTile);
+  if (q_len != 1) pl.score_order = kScoreOrderTile;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
@@ -293,9 +296,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     plan->pl.budget_multiple = value;
     return VATT_OK;
   }
-  if (option == VATT_OPT_KV_HEAD_MAJOR) {
-    if (plan->pl.q_len != 1 && value) return VATT_E_UNSUPPORTED_SHAPE;
-    plan->pl.kv_major = value ? 1 : 0;
+  if (option == VATT_OPT_SCORE_ORDER) {
+    if (value != kScoreOrderTile && value != kScoreOrderKvHead && value != kScoreOrderEighths) return VATT_E_INVALID_ARG;
+    if (plan->pl.q_len != 1 && value != kScoreOrderTile) return VATT_E_UNSUPPORTED_SHAPE;
+    plan->pl.score_order = value;
     return VATT_OK;
   }
   if (option == VATT_OPT_SAMPLER_DRAW_CAP) {

@@ -17,6 +17,8 @@ constexpr int kSubTile = 8;            // keys per sub-tile maximum
 constexpr int kHeadThreads = 512;      // workgroup size of the per-head kernel
 constexpr int kHeadThreadsLong = 1024; // ... for rows whose 8-key maxima do not fit the registers of 512 threads
 constexpr int kGatherThreads = 256;
+// Launch orders of the score pass (see the score kernel); the values of VATT_OPT_SCORE_ORDER.
+constexpr int kScoreOrderTile = 0, kScoreOrderKvHead = 1, kScoreOrderEighths = 2;
 constexpr int kDenseThreads = 256;
 
 // What the per-head kernel leaves for the gather kernel.
@@ -52,7 +54,7 @@ struct Plan {
   int sampler_small_batches;      // test hook: the sampler works in batches of 256 draws only
   uint32_t sampler_draw_cap;      // draws after which a sample is completed in index order (0: 64 L + 4096)
   int group_major;                // the later kernels launch the query heads of a KV head on one XCD (head_of_block)
-  int kv_major;                   // score launch in KV-head-major order (all tiles of a KV head on one XCD)
+  int score_order;                // launch order of the score pass (kScoreOrder*)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
   // workspace offsets (bytes)

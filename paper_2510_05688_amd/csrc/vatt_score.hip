@@ -3,14 +3,21 @@
 // exponent of Eq. 1).
 //
 // Work split: a workgroup of 4 waves owns TILE consecutive keys of one KV head (64 on a contiguous cache, 256 on
-// a paged one, by measurement).  Two launch orders.  Tile-major, grid = (key tiles, KV heads, sequences):
-// neighbouring workgroups stream neighbouring memory, and the eight XCDs (workgroups go to them round-robin in
-// launch order) share every row.  KV-head-major, grid = (KV heads, key tiles, sequences), for plans whose KV
-// head count is a multiple of 8: all tiles of KV head j run on XCD j mod 8, so each XCD streams its own heads'
-// K rows front to back and writes whole score rows (with plain stores, which its L2 gathers into full lines).
-// Measured: the pass itself 1.5 - 2 % faster at 32K tokens, the same at 64K, 5 % slower at 128K tokens, so the
-// plan takes this order up to 65536 tokens.  (The L2 counters show that nothing written here is still in L2
-// when the next kernel reads it: the selection kernel's hits and misses are the same in both orders.)  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
+// a paged one, by measurement).  Workgroups go to the chip's eight XCDs round-robin in launch order, so the
+// launch order decides which XCD reads which tile and writes which piece of a score row.  Three orders:
+//   tile-major, grid = (key tiles, KV heads, sequences): neighbouring workgroups stream neighbouring memory and
+//     the eight XCDs take turns along every row;
+//   KV-head-major, grid = (KV heads, key tiles, sequences), for plans whose KV head count is a multiple of 8:
+//     all tiles of KV head j run on XCD j mod 8, which streams that head's K rows front to back and writes
+//     whole score rows;
+//   eighths: tile-major, but XCD x takes the x-th eighth of a row's tiles, so it writes one long run of every
+//     score row while all XCDs still work on the same KV head.
+// Measured (whole call): KV-head-major is the best order up to 64K tokens (2 - 4 % under tile-major at 8K - 32K,
+// 7 % at 64K and batch 1), and 3 % behind it at 128K, where eighths is the best one (1.4 % under tile-major at
+// 128K and batch 4; equal to KV-head-major at 32K and batch 16, behind it at batch 1).  The plan picks
+// accordingly.  (A read-only kernel loses 5 - 8 % in the KV-head-major pattern: the gain is on the write side.
+// And nothing written here is still in an L2 when the next kernel reads it: the selection kernel's L2 hits and
+// misses are the same in every order.)  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
 // segment.  Each lane multiplies its 8 columns with the matching 8 columns of the G queries
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
@@ -34,15 +41,19 @@ template <int D, int G, bool PAGED, int TILE>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ scores, float* __restrict__ sub_max,
-                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale, int kv_major) {
+                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale, int order) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
   constexpr int ROWS_PER_WAVE = TILE / 4;
   constexpr int LOADS = ROWS_PER_WAVE / RPW;
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
-  // grid = (tiles, KV heads, sequences), or (KV heads, tiles, sequences) in the KV-head-major order
-  const int tile = kv_major ? blockIdx.y : blockIdx.x, kvh = kv_major ? blockIdx.x : blockIdx.y, b = blockIdx.z;
+  // grid = (tiles, KV heads, sequences); (KV heads, tiles, sequences) in the KV-head-major order; in the third
+  // order blockIdx.x = 8 j + x stands for tile x * (gridDim.x / 8) + j (gridDim.x is then a multiple of 8)
+  const int kvh = order == kScoreOrderKvHead ? blockIdx.x : blockIdx.y, b = blockIdx.z;
+  const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y
+                   : order == kScoreOrderEighths ? (int)((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8)
+                                                 : (int)blockIdx.x;
   const int tile_lo = tile * TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR;   // which 8-column slice of the row
@@ -112,9 +123,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
       for (int g = 0; g < G; ++g)
       {
         // tile-major order: a row's neighbouring tiles are written by other XCDs, non-temporal stores are best;
-        // KV-head-major order: this XCD writes the whole row, plain stores measured up to 3 % faster
+        // the other orders: this XCD writes long runs of the row, plain stores measured up to 3 % faster
         float* dst = &scores[((int64_t)b * Hq + (int64_t)kvh * G + g) * n_pad + i];
-        if (kv_major) *dst = s_tile[g][t]; else __builtin_nontemporal_store(s_tile[g][t], dst);
+        if (order != kScoreOrderTile) *dst = s_tile[g][t]; else __builtin_nontemporal_store(s_tile[g][t], dst);
       }
     }
   }
@@ -132,6 +143,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   }
 }
 
+// The launch grid of an order, from the tile-major one (tiles, KV heads, sequences).
+inline void shape_grid(dim3& grid, int order) {
+  if (order == kScoreOrderKvHead) std::swap(grid.x, grid.y);
+  if (order == kScoreOrderEighths) grid.x = (grid.x + 7) / 8 * 8;  // tiles beyond the last one exit at once
+}
+
 template <int D, int G>
 hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                      const int32_t* seq_lens, void* ws, hipStream_t st) {
@@ -145,16 +162,16 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   // block-table entries, does better with 256 keys in flight per workgroup)
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     dim3 grid((p.n_max + kScoreTilePaged - 1) / kScoreTilePaged, p.n_kv_heads, p.batch);
-    if (pl.kv_major) std::swap(grid.x, grid.y);
+    shape_grid(grid, pl.score_order);
     hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.kv_major);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
   } else {
     dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
-    if (pl.kv_major) std::swap(grid.x, grid.y);
+    shape_grid(grid, pl.score_order);
     hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.kv_major);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
   }
   return hipGetLastError();
 }

@@ -511,26 +511,27 @@ def test_budget_rounded_up_to_a_multiple(name, over, q):
 
 @pytest.mark.parametrize("hq,hkv,paged", [(16, 8, False), (8, 8, True), (8, 2, False), (4, 1, True)])
 def test_score_launch_orders_give_identical_results(hq, hkv, paged):
-    say("score pass launched tile by tile and KV head by KV head: Hq=%d Hkv=%d paged=%s" % (hq, hkv, paged))
+    say("score pass launched in each of its three orders: Hq=%d Hkv=%d paged=%s" % (hq, hkv, paged))
     from paper_2510_05688_amd import binding as vb
     wl = workloads.small_gqa(seed=71, batch=3, n_q_heads=hq, n_kv_heads=hkv, n=4096, seq_lens=[4096, 1500, 33],
                              epsilon=0.03)
     sess = _paged_session(wl) if paged else _session(wl)
     runs = []
-    for order in (0, 1):
-        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_KV_HEAD_MAJOR, order)
+    for order in (0, 1, 2):
+        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SCORE_ORDER, order)
         sess.out_o.zero_()
         sess.out_idx.zero_()
         sess.workspace.zero_()
         runs.append(_run(sess))
         check_all(wl, runs[-1], gpu_scores=sess.scores_host(), label="order %d" % order)
-    for key in ("O", "lse", "counts", "b_star", "stats"):
-        assert np.array_equal(runs[0][key], runs[1][key]), key
-    for b in range(wl.batch):
-        for h in range(hq):
-            g0, g1 = gpu_segments(runs[0], b, h), gpu_segments(runs[1], b, h)
-            for key in ("I_s", "I_l", "I_t", "I_bs", "I_dyn"):
-                assert np.array_equal(g0[key], g1[key]), (b, h, key)
+    for other in runs[1:]:
+        for key in ("O", "lse", "counts", "b_star", "stats"):
+            assert np.array_equal(runs[0][key], other[key]), key
+        for b in range(wl.batch):
+            for h in range(hq):
+                g0, g1 = gpu_segments(runs[0], b, h), gpu_segments(other, b, h)
+                for key in ("I_s", "I_l", "I_t", "I_bs", "I_dyn"):
+                    assert np.array_equal(g0[key], g1[key]), (b, h, key)
     sess.close()
 
 

@@ -91,7 +91,7 @@ def test_random_configurations_match_the_oracle():
         multiple = _budget_multiple(c)
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, multiple)
         if q_len == 1:
-            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_KV_HEAD_MAJOR, (c["n_max"] // 7 + c["hkv"]) % 2)
+            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SCORE_ORDER, (c["n_max"] // 7 + c["hkv"]) % 3)
         oracle_params = dict(wl.params, nested=o["nested"], bound="hoeffding" if o["hoeffding"] else "clt",
                              budget_multiple=multiple)
         sess.decode()

@@ -142,15 +142,18 @@ def test_budget_bound_option_and_chunk_plans_on_the_host():
 def test_score_order_option_on_the_host():
     plan = vb.vatt_plan_create(_base(), -1)
     try:
-        vb.vatt_plan_set_option(plan, vb.VATT_OPT_KV_HEAD_MAJOR, 1)
-        vb.vatt_plan_set_option(plan, vb.VATT_OPT_KV_HEAD_MAJOR, 0)
+        for order in (0, 1, 2):
+            vb.vatt_plan_set_option(plan, vb.VATT_OPT_SCORE_ORDER, order)
+        for bad in (-1, 3):
+            with pytest.raises(vb.VattError):
+                vb.vatt_plan_set_option(plan, vb.VATT_OPT_SCORE_ORDER, bad)
     finally:
         vb.vatt_plan_destroy(plan)
     chunk = vb.vatt_plan_create_chunk(_base(), 4, -1)
     try:
-        vb.vatt_plan_set_option(chunk, vb.VATT_OPT_KV_HEAD_MAJOR, 0)
+        vb.vatt_plan_set_option(chunk, vb.VATT_OPT_SCORE_ORDER, 0)
         with pytest.raises(vb.VattError) as e:       # the multi-query score kernel has one launch order
-            vb.vatt_plan_set_option(chunk, vb.VATT_OPT_KV_HEAD_MAJOR, 1)
+            vb.vatt_plan_set_option(chunk, vb.VATT_OPT_SCORE_ORDER, 2)
         assert e.value.status == vb.VATT_E_UNSUPPORTED_SHAPE
     finally:
         vb.vatt_plan_destroy(chunk)
