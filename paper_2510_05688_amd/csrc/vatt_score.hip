@@ -13,9 +13,11 @@
 //   eighths: tile-major, but XCD x takes the x-th eighth of a row's tiles, so it writes one long run of every
 //     score row while all XCDs still work on the same KV head.
 // Measured (whole call): KV-head-major is the best order up to 64K tokens (2 - 4 % under tile-major at 8K - 32K,
-// 7 % at 64K and batch 1), and 3 % behind it at 128K, where eighths is the best one (1.4 % under tile-major at
-// 128K and batch 4; equal to KV-head-major at 32K and batch 16, behind it at batch 1).  The plan picks
-// accordingly.  (A read-only kernel loses 5 - 8 % in the KV-head-major pattern: the gain is on the write side.
+// 7 % at 64K and batch 1), and 3 % behind it at 128K, where eighths is the best one on sequences of equal
+// length (1.4 % under tile-major at 128K and batch 4; equal to KV-head-major at 32K and batch 16, behind it at
+// batch 1).  But on a ragged batch eighths leaves the short sequences to one XCD (one 128K and three 8K - 20K
+// sequences: the pass 63 % slower), and rotating the eighths over the XCDs per head and sequence takes its gain
+// away; so the plan picks KV-head-major up to 64K tokens and tile-major beyond, and eighths is there on request.  (A read-only kernel loses 5 - 8 % in the KV-head-major pattern: the gain is on the write side.
 // And nothing written here is still in an L2 when the next kernel reads it: the selection kernel's L2 hits and
 // misses are the same in every order.)  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
