@@ -273,9 +273,9 @@ def main():
                     help="nested samples (an option beyond the paper): the final sample keeps the base sample")
     ap.add_argument("--budget-multiple", type=int, default=1,
                     help="round every budget up to a multiple of this (an option beyond the paper; 1 = the paper's rule)")
-    ap.add_argument("--score-order", default="plan", choices=["plan", "tile", "kvhead", "eighths"],
+    ap.add_argument("--score-order", default="plan", choices=["plan", "tile", "kvhead", "blocks"],
                     help="launch order of the score pass (VATT_OPT_SCORE_ORDER): the plan's choice, tile-major, "
-                         "KV-head-major, or every XCD an eighth of each row; results are identical")
+                         "KV-head-major, or tile-major in blocks of 256 KiB; results are identical")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
@@ -308,7 +308,7 @@ def main():
     if args.score_order != "plan":
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_SCORE_ORDER,
-                                 dict(tile=0, kvhead=1, eighths=2)[args.score_order])
+                                 dict(tile=0, kvhead=1, blocks=2)[args.score_order])
     if args.nested:
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_NESTED_SAMPLES, 1)

@@ -156,10 +156,9 @@ enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_O
        VATT_OPT_BUDGET_MULTIPLE = 7, VATT_OPT_SCORE_ORDER = 8 };
 /*
  * VATT_OPT_SCORE_ORDER (test hook) = 0 / 1 / 2: launch order of the score pass, i.e. which of the chip's XCDs
- * reads which tile: 0 tile by tile across the XCDs, 1 all tiles of a KV head on one XCD, 2 every XCD an eighth
- * of each row.  The plan picks 1 up to n_max = 65536 when the KV head count is a multiple of 8, else 0; 2 is
- * 1 - 2 % faster than 0 on long sequences of equal length and much slower on ragged batches.  Results are
- * identical.  Multi-query plans have order 0 only (VATT_E_UNSUPPORTED_SHAPE otherwise).
+ * reads which tile: 0 tile by tile across the XCDs, 1 all tiles of a KV head on one XCD, 2 like 0 in blocks of
+ * 256 KiB of K.  The plan picks 1 up to n_max = 65536 when the KV head count is a multiple of 8, else 2.
+ * Results are identical.  Multi-query plans have order 0 only (VATT_E_UNSUPPORTED_SHAPE otherwise).
  */
 /*
  * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up

@@ -96,11 +96,12 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   // Workgroups go to the eight XCDs round-robin in launch order.  With a multiple of 8 KV heads the selection,
   // gather and merge kernels launch the query heads of a KV head on one XCD (they read the same sink, window and
   // heavy V rows).  The score pass has three launch orders (see its kernel): by measurement the KV-head-major
-  // one up to 64K tokens when the KV heads can be dealt out to the XCDs evenly, the tile-major one otherwise.
-  // (The third one pays 1.4 % on long sequences of equal length and costs 30 % on a ragged batch, whose lengths
-  // the host does not know: only on request.  The multi-query score kernel has one order of its own.)
+  // one up to 64K tokens when the KV heads can be dealt out to the XCDs evenly, the blocks order otherwise (the
+  // tile-major one is 1 - 2 % behind it and stays for tests).  The multi-query score kernel has one order of
+  // its own.
   pl.group_major = (p.n_kv_heads % 8 == 0) ? 1 : 0;
-  pl.score_order = (pl.group_major && p.n_max <= 65536 && q_len == 1) ? kScoreOrderKvHead : kScoreOrderTile;
+  pl.score_order = (pl.group_major && p.n_max <= 65536) ? kScoreOrderKvHead : kScoreOrderBlocks;
+  if (q_len != 1) pl.score_order = kScoreOrderTile;
 
   const int n_max = p.n_max;
   pl.n_pad = (int)align_up((size_t)n_max, 256);
@@ -296,7 +297,7 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     return VATT_OK;
   }
   if (option == VATT_OPT_SCORE_ORDER) {
-    if (value != kScoreOrderTile && value != kScoreOrderKvHead && value != kScoreOrderEighths) return VATT_E_INVALID_ARG;
+    if (value != kScoreOrderTile && value != kScoreOrderKvHead && value != kScoreOrderBlocks) return VATT_E_INVALID_ARG;
     if (plan->pl.q_len != 1 && value != kScoreOrderTile) return VATT_E_UNSUPPORTED_SHAPE;
     plan->pl.score_order = value;
     return VATT_OK;

@@ -18,7 +18,7 @@ constexpr int kHeadThreads = 512;      // workgroup size of the per-head kernel
 constexpr int kHeadThreadsLong = 1024; // ... for rows whose 8-key maxima do not fit the registers of 512 threads
 constexpr int kGatherThreads = 256;
 // Launch orders of the score pass (see the score kernel); the values of VATT_OPT_SCORE_ORDER.
-constexpr int kScoreOrderTile = 0, kScoreOrderKvHead = 1, kScoreOrderEighths = 2;
+constexpr int kScoreOrderTile = 0, kScoreOrderKvHead = 1, kScoreOrderBlocks = 2;
 constexpr int kDenseThreads = 256;
 
 // What the per-head kernel leaves for the gather kernel.

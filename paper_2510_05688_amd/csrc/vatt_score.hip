@@ -10,14 +10,16 @@
 //   KV-head-major, grid = (KV heads, key tiles, sequences), for plans whose KV head count is a multiple of 8:
 //     all tiles of KV head j run on XCD j mod 8, which streams that head's K rows front to back and writes
 //     whole score rows;
-//   eighths: tile-major, but XCD x takes the x-th eighth of a row's tiles, so it writes one long run of every
-//     score row while all XCDs still work on the same KV head.
+//   blocks: tile-major, but the XCDs take turns in blocks of 256 KiB of K (16 tiles of 64 keys at d = 128)
+//     instead of single tiles, so each writes runs of 4 KiB of every score row while all XCDs still work on
+//     the same KV head.  (A read-only probe reads such blocks as fast as single tiles; blocks of 64 KiB, or of
+//     4 MiB and more, read 6 - 8 % slower.)
 // Measured (whole call): KV-head-major is the best order up to 64K tokens (2 - 4 % under tile-major at 8K - 32K,
-// 7 % at 64K and batch 1), and 3 % behind it at 128K, where eighths is the best one on sequences of equal
-// length (1.4 % under tile-major at 128K and batch 4; equal to KV-head-major at 32K and batch 16, behind it at
-// batch 1).  But on a ragged batch eighths leaves the short sequences to one XCD (one 128K and three 8K - 20K
-// sequences: the pass 63 % slower), and rotating the eighths over the XCDs per head and sequence takes its gain
-// away; so the plan picks KV-head-major up to 64K tokens and tile-major beyond, and eighths is there on request.  (A read-only kernel loses 5 - 8 % in the KV-head-major pattern: the gain is on the write side.
+// 7 % at 64K and batch 1), and 3 % behind it at 128K; blocks is 1 - 2 % under tile-major at every size tried,
+// equal to KV-head-major at 32K and batch 16 and behind it at batch 1, and as good as tile-major on a ragged
+// batch (an earlier form that gave every XCD one eighth of a row left the short sequences of a ragged batch to
+// one XCD: 63 % slower).  The plan picks KV-head-major up to 64K tokens when it can deal the KV heads out to
+// the XCDs evenly, and blocks otherwise.  (A read-only kernel loses 5 - 8 % in the KV-head-major pattern: the gain is on the write side.
 // And nothing written here is still in an L2 when the next kernel reads it: the selection kernel's L2 hits and
 // misses are the same in every order.)  A K row of d bf16 values is read by d/8 adjacent lanes with one 16-byte load
 // each, so a wave instruction covers 4 (d = 128) or 8 (d = 64) whole rows as one contiguous 1 KiB
@@ -31,6 +33,9 @@
 
 namespace vatt {
 namespace {
+
+// Tiles per block of the blocks order: 256 KiB of K rows.
+constexpr int score_block_tiles(int d, int tile) { return (256 * 1024) / (tile * d * 2) > 0 ? (256 * 1024) / (tile * d * 2) : 1; }
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
@@ -50,11 +55,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   constexpr int LOADS = ROWS_PER_WAVE / RPW;
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
-  // grid = (tiles, KV heads, sequences); (KV heads, tiles, sequences) in the KV-head-major order; in the third
-  // order blockIdx.x = 8 j + x stands for tile x * (gridDim.x / 8) + j (gridDim.x is then a multiple of 8)
+  // grid = (tiles, KV heads, sequences); (KV heads, tiles, sequences) in the KV-head-major order; in the blocks
+  // order blockIdx.x = 8 k + x stands for tile k mod BL of block 8 (k / BL) + x (gridDim.x: a multiple of 8 BL)
+  constexpr int BL = score_block_tiles(D, TILE);
   const int kvh = order == kScoreOrderKvHead ? blockIdx.x : blockIdx.y, b = blockIdx.z;
   const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y
-                   : order == kScoreOrderEighths ? (int)((blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8)
+                   : order == kScoreOrderBlocks ? (int)((((blockIdx.x / 8) / BL) * 8 + blockIdx.x % 8) * BL + (blockIdx.x / 8) % BL)
                                                  : (int)blockIdx.x;
   const int tile_lo = tile * TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -146,9 +152,12 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 }
 
 // The launch grid of an order, from the tile-major one (tiles, KV heads, sequences).
-inline void shape_grid(dim3& grid, int order) {
+inline void shape_grid(dim3& grid, int order, int block_tiles) {
   if (order == kScoreOrderKvHead) std::swap(grid.x, grid.y);
-  if (order == kScoreOrderEighths) grid.x = (grid.x + 7) / 8 * 8;  // tiles beyond the last one exit at once
+  if (order == kScoreOrderBlocks) {  // whole groups of eight blocks; tiles beyond the last one exit at once
+    const unsigned g = 8u * (unsigned)block_tiles;
+    grid.x = (grid.x + g - 1) / g * g;
+  }
 }
 
 template <int D, int G>
@@ -164,13 +173,13 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   // block-table entries, does better with 256 keys in flight per workgroup)
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     dim3 grid((p.n_max + kScoreTilePaged - 1) / kScoreTilePaged, p.n_kv_heads, p.batch);
-    shape_grid(grid, pl.score_order);
+    shape_grid(grid, pl.score_order, score_block_tiles(D, kScoreTilePaged));
     hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
                        pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
   } else {
     dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
-    shape_grid(grid, pl.score_order);
+    shape_grid(grid, pl.score_order, score_block_tiles(D, kScoreTile));
     hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
                        pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
