@@ -207,7 +207,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
 template <int D>
 __global__ __launch_bounds__(D) void gather_merge_kernel(const float* __restrict__ part,
                                                          const HeadRec* __restrict__ head_rec, int splits, int Hq,
-                                                         float* __restrict__ out_o, float* __restrict__ out_lse, int group_major, int Hkv) {
+                                                         float* __restrict__ out_o, float* __restrict__ out_lse,
+                                                         int group_major, int Hkv) {
   const int h = head_of_block((int)blockIdx.x, Hq, Hkv, group_major), b = blockIdx.y, bh = b * Hq + h;
   const int c = threadIdx.x;
   const float* p = part + (int64_t)bh * splits * (D + 4);

@@ -35,7 +35,10 @@ namespace vatt {
 namespace {
 
 // Tiles per block of the blocks order: 256 KiB of K rows.
-constexpr int score_block_tiles(int d, int tile) { return (256 * 1024) / (tile * d * 2) > 0 ? (256 * 1024) / (tile * d * 2) : 1; }
+constexpr int score_block_tiles(int d, int tile) {
+  const int t = (256 * 1024) / (tile * d * 2);
+  return t > 0 ? t : 1;
+}
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
@@ -60,8 +63,9 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   constexpr int BL = score_block_tiles(D, TILE);
   const int kvh = order == kScoreOrderKvHead ? blockIdx.x : blockIdx.y, b = blockIdx.z;
   const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y
-                   : order == kScoreOrderBlocks ? (int)((((blockIdx.x / 8) / BL) * 8 + blockIdx.x % 8) * BL + (blockIdx.x / 8) % BL)
-                                                 : (int)blockIdx.x;
+                   : order == kScoreOrderBlocks
+                       ? (int)((((blockIdx.x / 8) / BL) * 8 + blockIdx.x % 8) * BL + (blockIdx.x / 8) % BL)
+                       : (int)blockIdx.x;
   const int tile_lo = tile * TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR;   // which 8-column slice of the row
