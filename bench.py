@@ -96,6 +96,10 @@ def decode_loop(args, torch, np, workloads, DecodeSession):
     pp = plan_params(wl)
     pp.update(kv_layout=1, page_size=16, num_blocks=int(k_pages.shape[0]))
     sess = DecodeSession(pp)
+    if args.score_order != "plan":
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_SCORE_ORDER,
+                                 dict(tile=0, kvhead=1, blocks=2)[args.score_order])
     sess.upload(wl.q_bits, k_pages, v_pages, wl.seq_lens, wl.seeds, block_table=table)
     new_tokens = [workloads.configs.append_tokens(5, s_, wl.batch, wl.n_kv_heads, wl.head_dim) for s_ in range(steps + warm)]
     new_dev = [(_bf16_from_bits(kn, sess.device), _bf16_from_bits(vn, sess.device)) for kn, vn in new_tokens]

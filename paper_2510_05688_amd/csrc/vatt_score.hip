@@ -12,7 +12,8 @@
 //     whole score rows;
 //   blocks: tile-major, but the XCDs take turns in blocks of 256 KiB of K (16 tiles of 64 keys at d = 128)
 //     instead of single tiles, so each writes runs of 4 KiB of every score row while all XCDs still work on
-//     the same KV head.  (A read-only probe reads such blocks as fast as single tiles; blocks of 64 KiB, or of
+//     the same KV head; which XCD starts a row rotates with the KV head and the sequence (short sequences have
+//     first blocks only: without the rotation a ragged paged batch ran 3.7 % slower than tile by tile).  (A read-only probe reads such blocks as fast as single tiles; blocks of 64 KiB, or of
 //     4 MiB and more, read 6 - 8 % slower.)
 // Measured (whole call): KV-head-major is the best order up to 64K tokens (2 - 4 % under tile-major at 8K - 32K,
 // 7 % at 64K and batch 1), and 3 % behind it at 128K; blocks is 1 - 2 % under tile-major at every size tried,
@@ -59,12 +60,15 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   constexpr int BATCH = LOADS < 8 ? LOADS : 8;
 
   // grid = (tiles, KV heads, sequences); (KV heads, tiles, sequences) in the KV-head-major order; in the blocks
-  // order blockIdx.x = 8 k + x stands for tile k mod BL of block 8 (k / BL) + x (gridDim.x: a multiple of 8 BL)
+  // order blockIdx.x = 8 k + x stands for tile k mod BL of block 8 (k / BL) + (x + KV head + sequence) mod 8
+  // (gridDim.x: a multiple of 8 BL; the rotation spreads the first blocks, all that a short sequence has, over
+  // the XCDs)
   constexpr int BL = score_block_tiles(D, TILE);
   const int kvh = order == kScoreOrderKvHead ? blockIdx.x : blockIdx.y, b = blockIdx.z;
   const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y
                    : order == kScoreOrderBlocks
-                       ? (int)((((blockIdx.x / 8) / BL) * 8 + blockIdx.x % 8) * BL + (blockIdx.x / 8) % BL)
+                       ? (int)((((blockIdx.x / 8) / BL) * 8 + (blockIdx.x + blockIdx.y + blockIdx.z) % 8) * BL +
+                               (blockIdx.x / 8) % BL)
                        : (int)blockIdx.x;
   const int tile_lo = tile * TILE;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
