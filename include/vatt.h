@@ -108,10 +108,9 @@ typedef struct vatt_params {
 
 typedef struct vatt_plan vatt_plan;
 
-/* Regions of the workspace that tests and tools may want to read (see vatt_plan_workspace_offset). */
+/* Regions of the workspace a caller may read (see vatt_plan_workspace_offset). */
 enum {
-  VATT_WS_SCORES = 0, /* float [B, Hq, n_max_padded]: s_i of the last vatt_decode call                  */
-  VATT_WS_DEBUG = 1   /* uint64 [512]: phase clock stamps, written only by builds made with -DVATT_TIMING */
+  VATT_WS_SCORES = 0 /* float [B, Hq, n_max_padded]: s_i of the last vatt_decode or vatt_score call */
 };
 
 /*
@@ -142,35 +141,17 @@ int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vat
 int vatt_plan_query_len(const vatt_plan* plan);
 
 /*
- * Options (host only), for tests.  VATT_OPT_SAMPLER_SMALL_BATCHES = 1 makes the sampler work through
- * the draw sequence in batches of 256 draws only (it normally uses up to 1024, or 4096 with 1024 threads);
- * results are identical.
- * VATT_OPT_SAMPLER_DRAW_CAP = c > 0 replaces the 64 L + 4096 draw limit by c draws (0 restores it), so that
- * the completion rule can be exercised.
- * VATT_OPT_TOPK_GENERAL_PATH = 1 makes the top-k selection skip its usual shortcut (a lower bound of the
- * threshold from the largest scores of every 8 keys) and take the general path, a histogram over the whole
- * score row, which otherwise only serves short or unusual rows; results are identical.
+ * Options of the method (host only; vatt_plan_set_option).  All are off by default, which is the paper's
+ * algorithm.  (include/vatt_testing.h declares further option numbers that only change how the same results
+ * are computed; they exist for the test suite.)
  */
-enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_HEAD_THREADS = 6,
-       VATT_OPT_BUDGET_MULTIPLE = 7, VATT_OPT_SCORE_ORDER = 8 };
-/*
- * VATT_OPT_SCORE_ORDER (test hook) = 0 / 1 / 2: launch order of the score pass, i.e. which of the chip's XCDs
- * reads which tile: 0 tile by tile across the XCDs, 1 all tiles of a KV head on one XCD, 2 like 0 in blocks of
- * 256 KiB of K.  The plan picks 1 up to n_max = 65536 when the KV head count is a multiple of 8, else 2.
- * Results are identical.  Multi-query plans have order 0 only (VATT_E_UNSUPPORTED_SHAPE otherwise).
- */
+enum { VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_BUDGET_MULTIPLE = 7 };
 /*
  * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up
  * to the next multiple of q, e.g. 16, the V rows one wave of the gather reads per instruction at d = 128, or 64.
  * It never goes beyond min(n_s, max(b0, ceil(budget_cap_frac * n_s))), the largest value the plain rule can
  * give, so the index buffer needs no more room.  More samples than Algorithm 2 asks for keep its guarantee.
  * out_budget_raw still reports b* itself.
- */
-/*
- * VATT_OPT_HEAD_THREADS (test hook): workgroup size of the selection kernel, 512 or 1024.  The plan picks 512
- * for n_max <= 32768, and 1024 for longer rows when that costs no parallelism (the LDS of a CU holds one such
- * workgroup only, or there are no more heads than CUs); results are identical.  To be set on the plan's device.
  */
 /*
  * VATT_OPT_NESTED_SAMPLES = 1 departs from Algorithm 1, which draws the final sample afresh: the base sample
@@ -183,10 +164,14 @@ enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_O
 /*
  * VATT_OPT_BUDGET_BOUND selects the tail bound behind the denominator budget of Algorithm 2:
  * VATT_BOUND_CLT (default) is the corollary for D, b* = (Phi^{-1}(1 - delta/2) n_s sigma / (eps D))^2;
- * VATT_BOUND_HOEFFDING is the conservative alternative the paper's appendix on the tightness of the bounds
- * compares it with.  The paper prints no formula for it; the sub-Gaussian form of Hoeffding's inequality is
- * used, b* = 2 ln(2 / delta) (n_s sigma / (eps D))^2, which reproduces the sample ratio the appendix reports
- * (2.8 at delta = 0.2).  Denominator target only (VATT_E_UNSUPPORTED_SHAPE otherwise).
+ * VATT_BOUND_HOEFFDING is the more conservative alternative the paper's appendix on the tightness of the
+ * bounds compares it with.  The paper prints no formula for it.  What is built is a reading fitted to the one
+ * number the appendix reports (2.8 times the samples at delta = 0.2): the sub-Gaussian tail form
+ * b* = 2 ln(2 / delta) (n_s sigma / (eps D))^2, i.e. the CLT budget with z^2 replaced by 2 ln(2 / delta).  It
+ * uses the sample variance where Hoeffding's inequality proper uses the range of the weights, so it carries
+ * no distribution-free finite-sample guarantee (the range-based form, (ln(2 / delta) / 2) (n_s R / (eps D))^2
+ * with R <= 1 the weight range, would, and asks for far more samples than the appendix reports).
+ * Denominator target only (VATT_E_UNSUPPORTED_SHAPE otherwise).
  */
 enum { VATT_BOUND_CLT = 0, VATT_BOUND_HOEFFDING = 1 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
@@ -277,14 +262,6 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
  */
 int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
                    const int32_t* block_table, int32_t* seq_lens, void* stream);
-
-/*
- * Measurement aid (no part of the method): one kernel that reads `bytes` bytes (a multiple of 16) from the
- * 16-byte aligned device buffer src and discards them.  Its duration is the practical floor for any single
- * launch that must stream that many bytes from HBM, which is what the K scan is compared with.
- *   sink    device, at least 4 KiB, may be written (practically never is)
- */
-int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 const char* vatt_status_string(int status);
 

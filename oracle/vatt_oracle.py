@@ -492,10 +492,13 @@ def topk_alternatives(s: np.ndarray, sink: int, window: int, k: int, rel_tol: fl
     return alts
 
 
-def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-4,
+def budget_alternatives(b_star: float, b0: int, n_s: int, cap_frac: float, rel_tol: float = 1e-6,
                         multiple: int = 1) -> List[int]:
     """Budgets a correct fp32-statistics implementation may reach: the clamped ceil(b') of every b' within
-    rel_tol (relative) of b*, the oracle's own budget first."""
+    rel_tol (relative) of b*, the oracle's own budget first.  The window is 1e-6: b* is a ratio of sums of
+    some hundreds of fp32 weights whose individual relative errors (about 1e-6 from the fp32 score and the
+    fp32 exponential) are independent, so the sums agree with the fp64 ones to well under 1e-6; a budget is
+    bit-exact unless b* lies that close to an integer."""
     own = clamp_budget(b_star, b0, n_s, cap_frac, multiple)
     if not math.isfinite(b_star):
         return [own]

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/vatt.h"
+#include "../../include/vatt_testing.h"
 #include "vatt_dev.h"
 
 namespace vatt {

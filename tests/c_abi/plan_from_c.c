@@ -40,10 +40,12 @@ int main(void) {
   printf("hoeffding option %s\n", vatt_status_string(rc));
   rc = vatt_plan_create_chunk(&p, 4, -1, &chunk);
   printf("chunk plan %s q_len %d\n", vatt_status_string(rc), vatt_plan_query_len(chunk));
-  p.epsilon = 2.0f;
-  rc = vatt_plan_create(&p, -1, &plan);
-  printf("bad epsilon: %s\n", vatt_status_string(rc));
   vatt_plan_destroy(chunk);
+  vatt_plan_destroy(plan);
+  plan = NULL;
+  p.epsilon = 2.0f;
+  rc = vatt_plan_create(&p, -1, &plan); /* fails and leaves *out NULL: nothing to destroy */
+  printf("bad epsilon: %s (plan %s)\n", vatt_status_string(rc), plan ? "set" : "null");
   /* a plan made without a device cannot launch */
   p.epsilon = 0.05f;
   rc = vatt_plan_create(&p, -1, &plan);

@@ -6,7 +6,8 @@ Every entry of M replaces one piece of oracle/vatt_oracle.py by a plausible mist
 sign or index, swapped arguments, a wrong constant).  The copy, with tests/ and workloads/, goes to a temporary
 directory, and tests/test_oracle_pins.py and tests/test_oracle_statistics.py run there: a mistake is caught when
 they fail.  Prints one line per mistake and exits with status 1 if one is not caught (entries in EQUIVALENT
-change nothing that can be observed and are expected to pass).  CPU only; about five minutes on eight cores.
+change nothing that can be observed and are expected to pass); an entry whose text no longer occurs in the
+oracle stops the run (tests/test_oracle_pins.py checks the list against the oracle on every CPU run).  CPU only; about five minutes on eight cores.
 Not collected by pytest (it would multiply the suite's run time); run by hand after changing the oracle or
 its pins.
 """
@@ -57,8 +58,8 @@ M = [
  ("sdpa max instead of sum", "(rho_D + rho_N) / eps) ** 2", "max(rho_D, rho_N) / eps) ** 2"),
  ("hoeffding ln(1/delta)", "return math.sqrt(2.0 * math.log(2.0 / float(delta)))", "return math.sqrt(2.0 * math.log(1.0 / float(delta)))"),
  ("clamp floor", "want = int(math.ceil(b_star))", "want = int(math.floor(b_star))"),
- ("clamp no lower cap", "return int(min(n_s, max(b0, min(want, cap))))", "return int(min(n_s, min(want, cap)))"),
- ("clamp no upper", "return int(min(n_s, max(b0, min(want, cap))))", "return int(max(b0, min(want, cap)))"),
+ ("clamp no lower cap", "b = int(min(n_s, max(b0, min(want, cap))))", "b = int(min(n_s, min(want, cap)))"),
+ ("clamp no upper", "b = int(min(n_s, max(b0, min(want, cap))))", "b = int(max(b0, min(want, cap)))"),
  ("multiple rounds down", "b = min(top, (b + q - 1) // q * q)", "b = min(top, b // q * q)"),
  ("multiple beyond the residual", "b = min(top, (b + q - 1) // q * q)", "b = (b + q - 1) // q * q"),
  ("multiple ignores the lower cap", "top = int(min(n_s, max(b0, cap)))", "top = int(min(n_s, cap))"),
@@ -88,7 +89,8 @@ M = [
  ("m over I_f only", "    m = float(s.max())\n    k = topk_count", "    m = float(s[:1].max())\n    k = topk_count"),
  ("n_s counts top-k", "n_s = int(residual.shape[0])\n    res: Dict", "n_s = int(residual.shape[0]) + int(I_t.shape[0])\n    res: Dict"),
  ("cap frac ignored", "cap = int(math.ceil(np.float64(np.float32(cap_frac)) * n_s))", "cap = n_s"),
- ("budget alt only own", "return [own] + [v for v in range(min(lo, hi), max(lo, hi) + 1) if v != own]", "return [own]"),
+ ("budget alt only own", "for v in range(min(lo, hi), max(lo, hi) + 1):        # every ceil(b')", "for v in range(0):        # every ceil(b')"),
+ ("budget alt window 1e-4", "rel_tol: float = 1e-6,\n                        multiple: int = 1) -> List[int]:", "rel_tol: float = 1e-4,\n                        multiple: int = 1) -> List[int]:"),
  ("topk alt tolerance abs", "near = np.abs(s[mid] - tau) <= rel_tol * np.maximum(np.abs(s[mid]), abs(tau))", "near = np.abs(s[mid] - tau) <= rel_tol"),
  ("dense lse base", "return N / D, m + math.log(D)", "return N / D, math.log(D)"),
  ("draw cap tiny", "return 64 * int(L) + 4096", "return int(L)"),
@@ -100,7 +102,7 @@ def run(i):
     if old is None:
         return name, "skipped"
     if SRC.count(old) < 1:
-        return name, "PATTERN NOT FOUND"
+        raise SystemExit("pattern of mistake %r no longer occurs in the oracle: update the list" % name)
     d = tempfile.mkdtemp(prefix="oracle_mistake_%02d_" % i)
     for sub in ("oracle", "tests", "workloads"):
         shutil.copytree(os.path.join(ROOT, sub), os.path.join(d, sub), ignore=shutil.ignore_patterns("__pycache__", "test_gpu_*"))
@@ -112,14 +114,25 @@ def run(i):
     shutil.rmtree(d, ignore_errors=True)
     return name, ("caught: " + (tail[0][:150] if tail else "?")) if r.returncode != 0 else "NOT CAUGHT " + (tail[-1] if tail else "")
 
-sel = [i for i in range(len(M)) if len(sys.argv) < 2 or sys.argv[1] in M[i][0]]
-missed = 0
-with ThreadPoolExecutor(max(1, min(6, (os.cpu_count() or 2) - 2))) as ex:
-    for name, res in ex.map(run, sel):
-        if res.startswith("NOT CAUGHT") and name in EQUIVALENT:
-            res = "passes, as expected of an equivalent change"
-        elif not res.startswith("caught"):
-            missed += 1
-        print("%-32s %s" % (name, res), flush=True)
-print("%d mistakes planted, %d not caught" % (len(sel), missed))
-sys.exit(1 if missed else 0)
+
+def stale_patterns():
+    """Names of the entries whose text no longer occurs in the oracle (the list has to follow the oracle)."""
+    return [name for name, old, _ in M if old is not None and SRC.count(old) < 1]
+
+
+def main():
+    sel = [i for i in range(len(M)) if len(sys.argv) < 2 or sys.argv[1] in M[i][0]]
+    missed = 0
+    with ThreadPoolExecutor(max(1, min(6, (os.cpu_count() or 2) - 2))) as ex:
+        for name, res in ex.map(run, sel):
+            if res.startswith("NOT CAUGHT") and name in EQUIVALENT:
+                res = "passes, as expected of an equivalent change"
+            elif not res.startswith("caught"):
+                missed += 1
+            print("%-32s %s" % (name, res), flush=True)
+    print("%d mistakes planted, %d not caught" % (len(sel), missed))
+    sys.exit(1 if missed else 0)
+
+
+if __name__ == "__main__":
+    main()

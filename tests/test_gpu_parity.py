@@ -6,7 +6,7 @@ import torch
 import workloads
 from workloads.configs import default_params, append_tokens
 from oracle import vatt_oracle as vo
-from parity import check_all, check_head, gpu_segments, head_inputs, say, score_tolerance
+from parity import alternatives_used, check_all, check_head, gpu_segments, head_inputs, say, score_tolerance
 from util import plan_params
 
 pytestmark = pytest.mark.gpu
@@ -125,6 +125,7 @@ def test_config1_tiny_single_head():
     res = _run(sess)
     reps = check_all(wl, res, gpu_scores=sess.scores_host(), label="config1")
     assert reps[0]["b"] == 32 and reps[0]["n_s"] == 1024 - 4 - 32 - 32
+    assert alternatives_used(reps) == (0, 0)      # sets and budget bit-exact, no tie or boundary alternative
     sess.close()
 
 

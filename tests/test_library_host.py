@@ -18,9 +18,12 @@ def _base(**over):
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "vatt.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(vatt_[a-z_]+)\s*\(", header))
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if name.endswith(".h"):
+            header = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", name)).read(), flags=re.S)
+            declared |= set(re.findall(r"\b(vatt_[a-z_]+)\s*\(", header))
+    assert "vatt_decode" in declared and "vatt_stream_read" in declared
     assert declared == set(vb.EXPORTS), declared ^ set(vb.EXPORTS)
     lib = ctypes.CDLL(vb.LIB_PATH)
     for name in sorted(declared):

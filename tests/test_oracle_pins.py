@@ -570,6 +570,10 @@ def test_alternatives_enumerate_near_ties():
     assert [a.tolist() for a in vo.topk_alternatives(big, 0, 0, 2, rel_tol=1e-5)] == [[0, 2], [0, 1]]
     assert vo.budget_alternatives(100.000001, 10, 1000, 1.0) == [101, 100]
     assert vo.budget_alternatives(100.5, 10, 1000, 1.0) == [101]
+    # the window around b* is 1e-6 relative: 100.001 (1e-5 above an integer) has one legal budget only,
+    # 99.99999995 (5e-10 below one) has the next integer as well
+    assert vo.budget_alternatives(100.001, 10, 1000, 1.0) == [101]
+    assert vo.budget_alternatives(99.99999995, 10, 1000, 1.0) == [100, 101]
     r = vo.decode_head(*_scalar_head(s), seed=1, head=0,
                        params=_params(sink=0, window=0, topk_abs=3, base_abs=2), forced_topk=alts[1])
     assert r["I_t"].tolist() == [0, 1, 2] and 3 not in r["I_t"] and r["n_s"] == 4
@@ -755,3 +759,11 @@ def test_hoeffding_budget_meets_the_guarantee_on_a_bounded_population():
         pick = rng.choice(n_s, size=b, replace=False)
         hits += abs(D_f + n_s / b * w[pick].sum() - D) <= eps * D
     assert hits / trials >= 1 - delta / 2
+
+
+def test_planted_mistakes_list_follows_the_oracle():
+    # tests/plant_mistakes_in_oracle.py (run by hand) replaces pieces of the oracle's text by mistakes; every
+    # piece it names has to occur in the oracle as it stands, or the check silently shrinks
+    import plant_mistakes_in_oracle as pm
+    assert pm.stale_patterns() == []
+    assert len(pm.M) >= 77

@@ -144,11 +144,14 @@ def test_epsilon_delta_coverage(target, v_mean, eps):
                                                                          base_abs=48, base_frac=0.0,
                                                                          epsilon=eps, delta=delta))
     frac, density, unclamped = _coverage(target, wl, n_queries=24, seeds_per_query=50, rng_seed=5)
-    # the CLT budget is an approximation ("optimistic" in the paper's words), the base-sample
-    # variance estimate is noisy, and 1200 trials give a standard error of ~0.009 on the fraction
+    # Definition 4.1 asks for a fraction of at least 1 - delta; an observed fraction over N = 1200 trials has
+    # a binomial standard error of sqrt(delta (1 - delta) / N), and three of them are allowed below 1 - delta
+    n_trials = 24 * 50
+    margin = 3.0 * np.sqrt(delta * (1.0 - delta) / n_trials)
+    print("coverage %.4f (required %.4f - %.4f), density %.3f, unclamped %.3f" % (frac, 1 - delta, margin, density, unclamped))
     assert unclamped > 0.5, "budgets must come from the formula, not the lower cap"
     assert density < 0.5
-    assert frac >= 1.0 - delta - 0.03, (frac, density, unclamped)
+    assert frac >= 1.0 - delta - margin, (frac, density, unclamped)
 
 
 # ------------------------------------------------------------ nested samples ----
