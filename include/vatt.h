@@ -221,6 +221,24 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v,
                 int32_t* out_counts, double* out_budget_raw, float* out_stats, void* stream);
 
 /*
+ * vatt_decode without a workspace argument, for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The kernels are those of vatt_decode;
+ * their scratch memory (scores, partial sums, per-head records) is an array inside the library,
+ * vatt_static_scratch_bytes() = 16 MiB per GPU, which every GPU the library runs on holds until the process
+ * ends.  The call allocates nothing, frees nothing and calls no allocating routine; the array's address on the
+ * plan's device was looked up by vatt_plan_create.  A plan whose vatt_plan_workspace_bytes exceeds the array is
+ * refused with VATT_E_WORKSPACE_TOO_SMALL (the 32K-token, batch-1 layer of 32 / 8 heads needs 12.3 MiB).
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (nothing in it has to
+ * start at zero: every region is written before it is read within a call): calls that overlap on one GPU,
+ * from any streams or plans, race.  Other arguments, results and errors as in vatt_decode.
+ */
+size_t vatt_static_scratch_bytes(void);
+int vatt_decode_static(vatt_plan* plan, const void* q, const void* k, const void* v,
+                       const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                       float* out_o, float* out_lse, int32_t* out_idx, int32_t* out_counts,
+                       double* out_budget_raw, float* out_stats, void* stream);
+
+/*
  * The same decode step with the top-k set supplied by the caller: Section 4.1 leaves the choice of I_t to any
  * (approximate) top-k method, and without the exact score pass only the attended tokens' K and V rows are read.
  *   topk_idx     device, int32 [B, Hq, k_max] with k_max = the length of the top-k segment of out_idx

@@ -38,7 +38,7 @@ VATT_BOUND_HOEFFDING = 1
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
-    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
+    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_static", "vatt_static_scratch_bytes", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
     "vatt_status_string",
 ]
 
@@ -91,6 +91,10 @@ def _load():
     lib.vatt_plan_index_segment.restype = i64
     lib.vatt_decode.argtypes = [vp] * 8 + [sz] + [vp] * 7
     lib.vatt_decode.restype = ctypes.c_int
+    lib.vatt_decode_static.argtypes = [vp] * 14
+    lib.vatt_decode_static.restype = ctypes.c_int
+    lib.vatt_static_scratch_bytes.argtypes = []
+    lib.vatt_static_scratch_bytes.restype = sz
     lib.vatt_decode_given_topk.argtypes = [vp] * 10 + [sz] + [vp] * 7
     lib.vatt_decode_given_topk.restype = ctypes.c_int
     lib.vatt_dense_decode.argtypes = [vp] * 7 + [sz] + [vp] * 3
@@ -197,6 +201,20 @@ def vatt_decode(plan, q, k, v, block_table, seq_lens, seq_seeds, workspace, out_
                           _ptr(out_counts), _ptr(out_budget_raw), _ptr(out_stats), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_decode")
+
+
+def vatt_static_scratch_bytes() -> int:
+    return int(_lib.vatt_static_scratch_bytes())
+
+
+def vatt_decode_static(plan, q, k, v, block_table, seq_lens, seq_seeds, out_o, out_lse, out_idx, out_counts,
+                       out_budget_raw, out_stats, stream=None) -> None:
+    """vatt_decode on the library's own scratch array (no workspace argument, nothing allocated)."""
+    rc = _lib.vatt_decode_static(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(block_table), _ptr(seq_lens),
+                                 _ptr(seq_seeds), _ptr(out_o), _ptr(out_lse), _ptr(out_idx), _ptr(out_counts),
+                                 _ptr(out_budget_raw), _ptr(out_stats), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_decode_static")
 
 
 def vatt_decode_given_topk(plan, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_o,

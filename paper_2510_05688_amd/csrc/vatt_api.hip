@@ -1,6 +1,7 @@
 // C ABI of libvatt: parameter validation, plan geometry, workspace layout and the launch sequences.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "vatt_internal.h"
@@ -178,6 +179,37 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ---------------------------------------------------------------------------
+// Scratch memory of vatt_decode_static: a device array owned by the library, so that the call needs no
+// workspace from the caller and nothing is ever allocated.  Every GPU the library runs on holds its own copy
+// at its own address; `scratch` itself is only the host-side handle of the symbol, never a device address:
+// resolve_scratch looks the address up once per device and everything else uses that pointer.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on device i, or null before resolve_scratch(i)
+std::mutex g_scratch_mutex;
+
+// To be called with `device` current.
+hipError_t resolve_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void* ptr = nullptr;
+  const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u) != 0) return hipErrorInvalidSymbol;
+  g_scratch_ptr[device] = ptr;
+  return hipSuccess;
+}
+
+void* scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  return g_scratch_ptr[device];
+}
+
 int check_common(const vatt_plan* plan, const void* ws, size_t ws_bytes, const int32_t* block_table) {
   if (!plan || !ws) return VATT_E_INVALID_ARG;
   if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
@@ -223,6 +255,7 @@ int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vat
     if (hipGetDevice(&cur) != hipSuccess) rc = VATT_E_HIP;
     if (rc == VATT_OK && cur != device && hipSetDevice(device) != hipSuccess) rc = VATT_E_HIP;
     if (rc == VATT_OK && set_kernel_attributes(plan->pl) != hipSuccess) rc = VATT_E_HIP;
+    if (rc == VATT_OK && resolve_scratch(device) != hipSuccess) rc = VATT_E_HIP;  // for vatt_decode_static
     if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
   }
   if (rc != VATT_OK) {
@@ -320,6 +353,21 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
   else
     VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
   return VATT_OK;
+}
+
+size_t vatt_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int vatt_decode_static(vatt_plan* plan, const void* q, const void* k, const void* v, const int32_t* block_table,
+                       const int32_t* seq_lens, const uint64_t* seq_seeds, float* out_o, float* out_lse,
+                       int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                       void* stream) {
+  if (!plan) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  if (plan->pl.ws_bytes > kStaticScratchBytes) return VATT_E_WORKSPACE_TOO_SMALL;
+  void* ws = scratch_of(plan->pl.device);  // found by vatt_plan_create for this device
+  if (!ws) return VATT_E_HIP;
+  return vatt_decode(plan, q, k, v, block_table, seq_lens, seq_seeds, ws, kStaticScratchBytes, out_o, out_lse,
+                     out_idx, out_counts, out_budget_raw, out_stats, stream);
 }
 
 int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, const int32_t* block_table,
