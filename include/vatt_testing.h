@@ -29,9 +29,14 @@ extern "C" {
  *     tile: 0 tile by tile across the XCDs, 1 all tiles of a KV head on one XCD, 2 like 0 in blocks of 256 KiB
  *     of K.  The plan picks 1 up to n_max = 65536 when the KV head count is a multiple of 8, else 2.
  *     Multi-query plans have order 0 only (VATT_E_UNSUPPORTED_SHAPE otherwise).
+ *   VATT_OPT_FUSED_GATHER = 0, 1, 2, 4, 8 or 16: 0 keeps selection and gather in kernels of their own; S > 0
+ *     runs them as one kernel with S workgroups per head (denominator target, 512-thread selection and fresh
+ *     final samples only; VATT_E_UNSUPPORTED_SHAPE when the kernel's LDS does not hold that split).  The plan
+ *     picks S > 0 for batches with fewer heads than half the chip's compute units.  The index sets, budgets
+ *     and statistics are identical; the output sums run in another order.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8 };
+       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9 };
 
 /* Workspace region (vatt_plan_workspace_offset): uint64 [512] of phase clock stamps, written only by builds
  * of the library made with -DVATT_TIMING. */

@@ -1,4 +1,5 @@
 // C ABI of libvatt: parameter validation, plan geometry, workspace layout and the launch sequences.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -133,6 +134,8 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   const int max_dense = std::max(1, (n_max + 255) / 256);
   pl.dense_splits = std::min(std::min(64, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
 
+  pl.fuse_splits = fused_splits_for(pl);
+
   pl.seg_off[0] = 0;
   pl.seg_off[1] = p.sink;
   pl.seg_off[2] = (int64_t)p.sink + p.window;
@@ -152,7 +155,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.off_sub_max = take((size_t)heads * pl.n_sub * sizeof(float));
   pl.off_sparse = take((size_t)heads * pl.idx_cap * sizeof(float));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
-  pl.off_gather_part = take((size_t)heads * pl.gather_splits * (p.head_dim + 4) * sizeof(float));
+  pl.off_gather_part = take((size_t)heads * std::max(pl.gather_splits, 16) * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
   pl.off_vstat_part = take((size_t)heads * pl.vstat_splits * (2 * p.head_dim + 2) * sizeof(double));
   pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
@@ -305,7 +308,13 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     if (lds + head_kernel_static_lds_bytes() > 160 * 1024) return VATT_E_UNSUPPORTED_SHAPE;
     pl.head_threads = value;
     pl.head_lds_bytes = lds;
+    if (value != kHeadThreads) pl.fuse_splits = 0;
     if (pl.device >= 0 && set_kernel_attributes(pl) != hipSuccess) return VATT_E_HIP;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_FUSED_GATHER) {
+    if (value != 0 && !fused_splits_fit(plan->pl, value)) return VATT_E_UNSUPPORTED_SHAPE;
+    plan->pl.fuse_splits = value;
     return VATT_OK;
   }
   if (option == VATT_OPT_NESTED_SAMPLES) {
@@ -384,6 +393,13 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
     VATT_LAUNCH(launch_score_chunk(pl, q, k, block_table, seq_lens, workspace, st));
   else
     VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
+  if (pl.p.target == VATT_TARGET_D && pl.fuse_splits > 0 && !pl.nested_samples) {
+    // small batch: selection and gather in one kernel, several workgroups per head
+    VATT_LAUNCH(launch_head_fused(pl, v, block_table, seq_lens, seq_seeds, workspace, out_idx, out_counts,
+                                  out_budget_raw, out_stats, st));
+    VATT_LAUNCH(launch_gather_merge(pl, workspace, pl.fuse_splits, out_o, out_lse, st));
+    return VATT_OK;
+  }
   if (pl.p.target == VATT_TARGET_D) {
     VATT_LAUNCH(launch_head(pl, 0, seq_lens, seq_seeds, workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
   } else {

@@ -270,6 +270,22 @@ hipError_t launch_gather(const Plan& pl, const void* v, const int32_t* block_tab
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_gather_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  char* w = static_cast<char*>(ws);
+  const float* part = reinterpret_cast<const float*>(w + pl.off_gather_part);
+  const HeadRec* rec = reinterpret_cast<const HeadRec*>(w + pl.off_head_rec);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL((gather_merge_kernel<128>), dim3(p.n_q_heads, pl.vbatch), dim3(128), 0, st, part, rec, splits,
+                       p.n_q_heads, out_o, out_lse, pl.group_major, p.n_kv_heads);
+  else if (p.head_dim == 64)
+    hipLaunchKernelGGL((gather_merge_kernel<64>), dim3(p.n_q_heads, pl.vbatch), dim3(64), 0, st, part, rec, splits,
+                       p.n_q_heads, out_o, out_lse, pl.group_major, p.n_kv_heads);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 hipError_t launch_vstats(const Plan& pl, const void* v, const int32_t* block_table, void* ws,
                          const int32_t* out_idx, hipStream_t st) {
   if (pl.p.head_dim == 128) return launch_gather_d<128, true>(pl, v, block_table, ws, out_idx, nullptr, nullptr, st);

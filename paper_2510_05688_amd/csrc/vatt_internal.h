@@ -58,6 +58,7 @@ struct Plan {
   int score_order;                // launch order of the score pass (kScoreOrder*)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
+  int fuse_splits;                // > 0: the selection kernel also gathers, with this many workgroups per head
   // workspace offsets (bytes)
   size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
       off_debug, off_vstat_part, off_dense_part, ws_bytes;
@@ -76,6 +77,14 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
                        hipStream_t st);
 // The path with a caller-supplied top-k set: selection phase 0 (sets, base sample) and 1 (budget, final sample),
 // scores of the listed tokens, gather with the final sample's scores computed on the way.
+// Selection and gather in one kernel for small batches (denominator target, fresh final sample), then the merge
+// of the per-workgroup partial sums.
+hipError_t launch_head_fused(const Plan& pl, const void* v, const int32_t* block_table, const int32_t* seq_lens,
+                             const uint64_t* seq_seeds, void* ws, int32_t* out_idx, int32_t* out_counts,
+                             double* out_budget_raw, float* out_stats, hipStream_t st);
+hipError_t launch_gather_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st);
+int fused_splits_for(const Plan& pl);           // the plan's own choice (0: separate kernels)
+bool fused_splits_fit(const Plan& pl, int splits);  // whether the fused kernel can run with that many
 hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
                                const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
                                int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st);

@@ -85,7 +85,41 @@ struct HeadArgs {
   int b_multiple;  // b is rounded up to a multiple of this (1: the paper's rule)
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
+  // fused gather (head_kernel with FD > 0): every head has `splits` workgroups, each of which repeats the
+  // selection and then gathers every splits-th row of the head's token list
+  const uint16_t* v;
+  KVLayout L;
+  float* part;       // [B*Hq][splits][d + 4]: partial (sum w V, sum w) of every workgroup
+  int splits, split_shift, group;
+  int glist_cap, dlist_cap;  // LDS entries for a workgroup's share of I_f and of the final sample
 };
+
+// Where an accepted token goes: into the index list in global memory (dst, for the workgroup that writes the
+// outputs) and, when a workgroup gathers its own share of the list (fused gather), every 2^shift-th entry into
+// an LDS list.
+struct Emit {
+  int32_t* dst;
+  uint32_t dst_cap;
+  uint32_t* lds;      // nullptr: no LDS list
+  uint32_t lds_cap;
+  uint32_t shift, split;
+  bool global;
+};
+__device__ __forceinline__ void emit_tok(const Emit& E, uint32_t p, int32_t tok) {
+  if (E.global && p < E.dst_cap) E.dst[p] = tok;
+  if (E.lds && (p & ((1u << E.shift) - 1u)) == E.split && (p >> E.shift) < E.lds_cap) E.lds[p >> E.shift] = (uint32_t)tok;
+}
+__device__ __forceinline__ Emit emit_to(int32_t* dst, uint32_t dst_cap) {
+  Emit E;
+  E.dst = dst;
+  E.dst_cap = dst_cap;
+  E.lds = nullptr;
+  E.lds_cap = 0;
+  E.shift = 0;
+  E.split = 0;
+  E.global = true;
+  return E;
+}
 
 constexpr int kSmallBatchBlocks = 64;  // Philox blocks of a small batch (256 draws)
 
@@ -282,7 +316,7 @@ struct HeadOps {
   // sum_w is given, adds exp(s_i - m) and its square over the sample to this thread's partial sums.
   // Returns flag bits: 1 complement regime, 2 more than one batch, 4 draw cap reached.
   static __device__ __forceinline__ int draw_sample(const Sampler& S, const HeadSizes& hs, uint32_t c, const DrawBatch& spec, bool have_spec,
-                                    int small_batches, int32_t* dst, uint32_t dst_cap, double* sum_w,
+                                    int small_batches, const Emit& E, double* sum_w,
                                     double* sum_w2, HeadSmem& sm) {
     const int tid = threadIdx.x;
     const int words = (hs.n + 31) >> 5;
@@ -331,7 +365,7 @@ struct HeadOps {
         const bool a = (acc >> e) & 1u;
         const bool take = a && pos < room;
         if (!invert) {
-          if (take && have + pos < dst_cap) dst[have + pos] = (int32_t)B.tok[e];
+          if (take) emit_tok(E, have + pos, (int32_t)B.tok[e]);
           if (sum_w) {
             const float sc = B.have_sc ? B.sc[e] : (take ? S.row[B.tok[e]] : 0.f);
             const double w = take ? (double)__expf(sc - S.m) : 0.0;
@@ -365,7 +399,7 @@ struct HeadOps {
           if (invert) {
             atomicOr(&S.taken[i >> 5], 1u << (i & 31));
           } else {
-            if (have + pos < dst_cap) dst[have + pos] = (int32_t)i;
+            emit_tok(E, have + pos, (int32_t)i);
             if (sum_w) {
               const double wt = (double)__expf(S.row[i] - S.m);
               aw += wt;
@@ -391,7 +425,7 @@ struct HeadOps {
         while (bits) {
           const int i = (w << 5) + (__ffs(bits) - 1);
           bits &= bits - 1u;
-          if (pos < dst_cap) dst[pos] = i;
+          emit_tok(E, pos, i);
           if (sum_w) {
             const double wt = (double)__expf(S.row[i] - S.m);
             aw += wt;
@@ -428,7 +462,7 @@ struct HeadOps {
     if (c <= b0 || dst_cap <= b0) return 0;
     hs.n_s -= (int)b0;
     const DrawBatch none = {};
-    return draw_sample(S, hs, c - b0, none, false, small_batches, dst + b0, dst_cap - b0, nullptr, nullptr, sm);
+    return draw_sample(S, hs, c - b0, none, false, small_batches, emit_to(dst + b0, dst_cap - b0), nullptr, nullptr, sm);
   }
 };  // struct HeadOps
 
@@ -719,9 +753,26 @@ __device__ __forceinline__ int ahead_blocks(int small_batches) {
   return small_batches ? kSmallBatchBlocks : (NT >= 1024 ? 1024 : min(NT, 256));
 }
 
-// NT = workgroup size.
-template <int NT>
+// Accumulates weight * (8 bf16 values of a V row) into acc.
+__device__ __forceinline__ void add_weighted_row(float (&acc)[8], float wt, const uint4& vv) {
+  const uint32_t ww[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    acc[2 * c] += wt * bf16_lo(ww[c]);
+    acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+  }
+}
+
+// NT = workgroup size.  FD = 0: selection only (the gather is a kernel of its own).  FD = head dimension: fused
+// gather for small batches, where one workgroup per head would leave most of the chip idle and every kernel
+// boundary is a visible part of the step: every head gets A.splits workgroups (blockIdx.z), each of which runs
+// the whole selection (identical results in all of them: nothing is exchanged), keeps every A.splits-th token
+// of the head's list in LDS, gathers those V rows and leaves a partial (sum w V, sum w) for the merge kernel.
+// Only workgroup 0 of a head writes the index lists, counts, statistics and budget.  The rows of I_f are
+// requested as soon as the top-k set is known and are added after the samplers have run.
+template <int NT, int FD, bool PAGED>
 __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
+  constexpr bool kFused = FD > 0;
   using O = HeadOps<NT>;
   using TKR = TopkOps<NT, RowView<NT>>;
   using TKC = TopkOps<NT, CandView<NT>>;
@@ -733,6 +784,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.group_major), b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
+  const uint32_t split = kFused ? blockIdx.z : 0u, shift = kFused ? (uint32_t)A.split_shift : 0u;
+  const uint32_t smask = (1u << shift) - 1u;
+  const bool writer = split == 0u;  // this workgroup writes the head's outputs
   // The sub-tile maxima the score kernel left are requested first of all, before even the sequence length is
   // known (what lies beyond the row's own sub-tiles is masked once it is): the kernel starts with a chain of
   // dependent loads, and this takes one link out of it.  Rows of up to 8 * NT sub-tiles keep the maxima in
@@ -762,6 +816,13 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   uint32_t* scratch = taken1 + words_max;
   uint32_t* wpre = scratch + words_max;
   uint32_t* mail = wpre + words_max;
+  // fused gather: this workgroup's share of I_f and of the final sample, and the cross-wave sums
+  uint32_t* glist = mail + words_max;
+  uint32_t* dlist = glist + (kFused ? A.glist_cap : 0);
+  float* g_red = reinterpret_cast<float*>(dlist + (kFused ? A.dlist_cap : 0));
+  auto to_glist = [&](uint32_t p, uint32_t tok) {
+    if (kFused && (p & smask) == split && (p >> shift) < (uint32_t)A.glist_cap) glist[p >> shift] = tok;
+  };
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
@@ -1098,7 +1159,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
           if (c <= T_cand) {
             const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
             const uint32_t pos = wpre[i >> 5] + (uint32_t)__popc(bm_f[i >> 5] & ((1u << (i & 31)) - 1u));
-            if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)i;
+            if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)i;
+            to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, i);
           }
         }
       } else {
@@ -1110,7 +1172,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
           while (bits) {
             const int i = (w << 5) + (__ffs(bits) - 1);
             bits &= bits - 1u;
-            if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+            if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+            to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, (uint32_t)i);
             ++pos;
           }
         }
@@ -1121,8 +1184,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     acc_f32 += __expf(edge0 - m) + __expf(edge1 - m);  // exp(-inf) = 0 for threads without a token
     for (int i = tid + NT; i < hs.n_sink; i += NT) acc_f32 += __expf(row[i] - m);
     for (int i = tid + NT; i < hs.n_win; i += NT) acc_f32 += __expf(row[hs.mid_hi + i] - m);
-    for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
-    for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
+    for (int i = tid; i < hs.n_sink; i += NT) {
+      if (writer) idx[A.seg_sink + i] = i;
+      to_glist((uint32_t)i, (uint32_t)i);
+    }
+    for (int i = tid; i < hs.n_win; i += NT) {
+      if (writer) idx[A.seg_win + i] = hs.mid_hi + i;
+      to_glist((uint32_t)(hs.n_sink + i), (uint32_t)(hs.mid_hi + i));
+    }
   } else {
     // phase 2: rebuild the top-k bitmap from the list written in phase 1
     for (int t = tid; t < hs.k; t += NT) {
@@ -1135,6 +1204,35 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   }
   __syncthreads();
 
+  // Fused gather, first part: the V rows (and scores) of this workgroup's share of I_f are requested now and
+  // added after the samplers have run.  LPR adjacent lanes read one row; NG rows per round, UF rounds in flight.
+  constexpr int LPR = kFused ? FD / 8 : 16;
+  constexpr int NG = NT / LPR;
+  constexpr int UF = 8;
+  const int g_sub = tid % LPR, g_grp = tid / LPR;
+  const int kvh = kFused ? h / A.group : 0;
+  float gacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float gdsum = 0.f;
+  uint4 fv[UF];
+  float fs[UF];
+  int my_nf = 0;
+  auto load_row = [&](const uint32_t* list, int j, int count, float& sc, uint4& vv) {
+    sc = -INFINITY;  // weight exp(-inf - m) = 0
+    vv = make_uint4(0u, 0u, 0u, 0u);
+    if (j < count) {
+      const int t = min((int)list[j], n - 1);
+      sc = row[t];
+      vv = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, seq, kvh, t) + g_sub * 8);
+    }
+  };
+  if constexpr (kFused) {
+    const int n_f = hs.n_sink + hs.n_win + hs.k;
+    my_nf = n_f > (int)split ? (int)(((uint32_t)n_f - split + smask) >> shift) : 0;
+    my_nf = min(my_nf, A.glist_cap);
+#pragma unroll
+    for (int u = 0; u < UF; ++u) load_row(glist, u * NG + g_grp, my_nf, fs[u], fv[u]);
+  }
+
   if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
 
   // ---- I_bs (Algorithm 2, base sample) and the sums over it ----
@@ -1142,8 +1240,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   double acc_w = 0.0, acc_w2 = 0.0;
   if (hs.n_s > 0) {
     if (A.phase != 2) {
-      const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches, idx + A.seg_base,
-                                   (uint32_t)A.b0_max, &acc_w, &acc_w2, sm);
+      Emit E0 = emit_to(idx + A.seg_base, (uint32_t)A.b0_max);
+      E0.global = writer;
+      const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches, E0, &acc_w, &acc_w2, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
       VATT_STAMP(A.dbg, 5);
     } else {
@@ -1232,14 +1331,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     if (A.b_multiple > 1)
       bfin = min(min(hs.n_s, max(hs.b0, cap)), (bfin + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
     bfin = min(bfin, A.b_max);
-    if (tid == 0 && A.out_stats) {
+    if (tid == 0 && writer && A.out_stats) {
       float* st = A.out_stats + (int64_t)bh * 4;
       st[0] = (float)D_hat;
       st[1] = (float)sigma2;
       st[2] = (float)tr_sigma;
       st[3] = (float)nhat_sq;
     }
-  } else if (tid == 0 && A.out_stats) {
+  } else if (tid == 0 && writer && A.out_stats) {
     float* st = A.out_stats + (int64_t)bh * 4;
     st[0] = (float)D_f;
     st[1] = st[2] = st[3] = 0.f;
@@ -1248,14 +1347,22 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 7);
   // ---- I_dyn (Algorithm 1, final sample) ----
   if (bfin > 0) {
-    const int f = A.nested ? O::draw_nested(S1, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
-                                            idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
-                           : O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches,
-                                            idx + A.seg_dyn, (uint32_t)A.b_max, nullptr, nullptr, sm);
+    Emit E1 = emit_to(idx + A.seg_dyn, (uint32_t)A.b_max);
+    E1.global = writer;
+    if (kFused) {
+      E1.lds = dlist;
+      E1.lds_cap = (uint32_t)A.dlist_cap;
+      E1.shift = shift;
+      E1.split = split;
+    }
+    const int f = (!kFused && A.nested)
+                      ? O::draw_nested(S1, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
+                                       idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
+                      : O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches, E1, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
     VATT_STAMP(A.dbg, 8);
   }
-  if (tid == 0) {
+  if (tid == 0 && writer) {
     int32_t* c = A.out_counts + (int64_t)bh * 8;
     const int prev = (A.phase == 2) ? c[7] : 0;
     c[0] = hs.n_sink;
@@ -1280,6 +1387,62 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     A.head_rec[bh] = r;
   }
   VATT_STAMP(A.dbg, 9);
+
+  // Fused gather, second part: add the rows of I_f that were requested above, then the rest of I_f (only long
+  // lists have one), then this workgroup's share of the final sample with the weight factor n_s / b.
+  if constexpr (kFused) {
+    auto add_rows = [&](const float (&sc)[UF], const uint4 (&vv)[UF], float factor) {
+#pragma unroll
+      for (int u = 0; u < UF; ++u) {
+        const float wt = __expf(sc[u] - m) * factor;
+        add_weighted_row(gacc, wt, vv[u]);
+        gdsum += g_sub == 0 ? wt : 0.f;
+      }
+    };
+    add_rows(fs, fv, 1.0f);
+    for (int j0 = UF * NG; j0 < my_nf; j0 += UF * NG) {
+#pragma unroll
+      for (int u = 0; u < UF; ++u) load_row(glist, j0 + u * NG + g_grp, my_nf, fs[u], fv[u]);
+      add_rows(fs, fv, 1.0f);
+    }
+    int my_nd = bfin > (int)split ? (int)(((uint32_t)bfin - split + smask) >> shift) : 0;
+    my_nd = min(my_nd, A.dlist_cap);
+    const float tail_scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
+    for (int j0 = 0; j0 < my_nd; j0 += UF * NG) {
+#pragma unroll
+      for (int u = 0; u < UF; ++u) load_row(dlist, j0 + u * NG + g_grp, my_nd, fs[u], fv[u]);
+      add_rows(fs, fv, tail_scale);
+    }
+    VATT_STAMP(A.dbg, 10);
+    // lane groups of a wave hold different rows: add them, then the waves through LDS
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) gacc[c] += __shfl_xor(gacc[c], o);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) gdsum += __shfl_xor(gdsum, o);
+    const int lane = tid & 63, wave = tid >> 6;
+    float* g_d = g_red + SW * FD;
+    if (lane < LPR) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) g_red[wave * FD + lane * 8 + c] = gacc[c];
+    }
+    if (lane == 0) g_d[wave] = gdsum;
+    __syncthreads();
+    float dtot = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < SW; ++w2) dtot += g_d[w2];
+    float* part = A.part + ((int64_t)bh * A.splits + split) * (FD + 4);
+    if (tid < FD) {
+      float a = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < SW; ++w2) a += g_red[w2 * FD + tid];
+      part[tid] = a;
+    }
+    if (tid == 0) part[FD] = dtot;
+    VATT_STAMP(A.dbg, 11);
+  }
 }
 
 
@@ -1387,8 +1550,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     __syncthreads();
     int flags = 0;
     if (hs.n_s > 0) {
-      const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches, idx + A.seg_base,
-                                   (uint32_t)A.b0_max, nullptr, nullptr, sm);
+      const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches,
+                                   emit_to(idx + A.seg_base, (uint32_t)A.b0_max), nullptr, nullptr, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
     }
     if (tid == 0) {
@@ -1525,8 +1688,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   if (bfin > 0) {
     const int f = A.nested ? O::draw_nested(S, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
                                             idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
-                           : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches, idx + A.seg_dyn,
-                                            (uint32_t)A.b_max, nullptr, nullptr, sm);
+                           : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches,
+                                            emit_to(idx + A.seg_dyn, (uint32_t)A.b_max), nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
   }
   if (tid == 0) {
@@ -1563,10 +1726,14 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
 }
 
 typedef void (*HeadKernel)(HeadArgs);
-// The instantiation for a plan: (workgroup size, scores per thread kept in registers).
-HeadKernel head_kernel_for(const Plan& pl) {
-  (void)pl;
-  return pl.head_threads == kHeadThreadsLong ? head_kernel<kHeadThreadsLong> : head_kernel<kHeadThreads>;
+// The instantiation for a plan: workgroup size; with the fused gather also head dimension and cache layout.
+HeadKernel head_kernel_for(const Plan& pl, bool fused) {
+  if (fused) {
+    const bool paged = pl.p.kv_layout == VATT_LAYOUT_PAGED;
+    if (pl.p.head_dim == 128) return paged ? head_kernel<kHeadThreads, 128, true> : head_kernel<kHeadThreads, 128, false>;
+    return paged ? head_kernel<kHeadThreads, 64, true> : head_kernel<kHeadThreads, 64, false>;
+  }
+  return pl.head_threads == kHeadThreadsLong ? head_kernel<kHeadThreadsLong, 0, false> : head_kernel<kHeadThreads, 0, false>;
 }
 
 }  // namespace
@@ -1578,8 +1745,12 @@ hipError_t set_kernel_attributes(const Plan& pl) {
   // kernels' static part), so that plans of different capacities can be used in any order.
   (void)pl;
   const int cap = 160 * 1024 - (int)head_kernel_static_lds_bytes();
-  const void* kernels[3] = {reinterpret_cast<const void*>(head_kernel<kHeadThreads>),
-                            reinterpret_cast<const void*>(head_kernel<kHeadThreadsLong>),
+  const void* kernels[7] = {reinterpret_cast<const void*>(head_kernel<kHeadThreads, 0, false>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreadsLong, 0, false>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreads, 128, false>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreads, 128, true>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreads, 64, false>),
+                            reinterpret_cast<const void*>(head_kernel<kHeadThreads, 64, true>),
                             reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads>)};
   for (const void* f : kernels) {
     const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
@@ -1594,6 +1765,16 @@ size_t head_kernel_lds_bytes(int n_max, int head_threads) {
                                                         : sizeof(HeadOps<kHeadThreads>::HeadSmem);
   return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * (sizeof(uint64_t) + sizeof(uint32_t)) +
          6 * words_max * sizeof(uint32_t);
+}
+
+// LDS entries of a workgroup's share of I_f and of the final sample when `splits` workgroups share a head.
+int fused_glist_cap(const Plan& pl, int splits) { return (pl.p.sink + pl.p.window + pl.k_max) / splits + 2; }
+int fused_dlist_cap(const Plan& pl, int splits) { return pl.b_max / splits + 2; }
+// Dynamic LDS of the selection kernel with the fused gather (512 threads).
+size_t fused_head_lds_bytes(const Plan& pl, int splits) {
+  return head_kernel_lds_bytes(pl.p.n_max, kHeadThreads) +
+         ((size_t)fused_glist_cap(pl, splits) + (size_t)fused_dlist_cap(pl, splits)) * sizeof(uint32_t) +
+         (size_t)(kHeadThreads / kWave) * (pl.p.head_dim + 1) * sizeof(float) + 64;
 }
 
 size_t head_kernel_static_lds_bytes() { return sizeof(TopkSmem) + 64; }
@@ -1620,7 +1801,46 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
   HeadArgs A;
   fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
   const vatt_params& p = pl.p;
-  hipLaunchKernelGGL(head_kernel_for(pl), dim3(p.n_q_heads, pl.vbatch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
+  hipLaunchKernelGGL(head_kernel_for(pl, false), dim3(p.n_q_heads, pl.vbatch), dim3(pl.head_threads), pl.head_lds_bytes, st, A);
+  return hipGetLastError();
+}
+
+bool fused_splits_fit(const Plan& pl, int splits) {
+  if (splits < 1 || splits > 16 || (splits & (splits - 1)) != 0) return false;
+  if (pl.head_threads != kHeadThreads || pl.p.target != VATT_TARGET_D) return false;
+  return fused_head_lds_bytes(pl, splits) + head_kernel_static_lds_bytes() <= 160 * 1024;
+}
+
+// Small batches only: with fewer heads than half the compute units, every head gets the largest power of two
+// of workgroups (at most 16) that the chip can run at once, one per compute unit.
+int fused_splits_for(const Plan& pl) {
+  const int heads = pl.vbatch * pl.p.n_q_heads;
+  if (2 * heads > pl.num_cus) return 0;
+  int s = 1;
+  while (2 * s * heads <= pl.num_cus && s < 16) s *= 2;
+  while (s >= 2 && !fused_splits_fit(pl, s)) s /= 2;
+  return s >= 2 ? s : 0;
+}
+
+// Selection with the fused gather (denominator target, fresh final sample): pl.fuse_splits workgroups per head.
+hipError_t launch_head_fused(const Plan& pl, const void* v, const int32_t* block_table, const int32_t* seq_lens,
+                             const uint64_t* seq_seeds, void* ws, int32_t* out_idx, int32_t* out_counts,
+                             double* out_budget_raw, float* out_stats, hipStream_t st) {
+  HeadArgs A;
+  fill_head_args(A, pl, 0, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
+  const vatt_params& p = pl.p;
+  A.v = static_cast<const uint16_t*>(v);
+  A.L = pl.kv_v;
+  A.L.block_table = block_table;
+  A.part = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_gather_part);
+  A.splits = pl.fuse_splits;
+  A.split_shift = 0;
+  while ((1 << A.split_shift) < pl.fuse_splits) ++A.split_shift;
+  A.group = pl.group;
+  A.glist_cap = fused_glist_cap(pl, pl.fuse_splits);
+  A.dlist_cap = fused_dlist_cap(pl, pl.fuse_splits);
+  hipLaunchKernelGGL(head_kernel_for(pl, true), dim3(p.n_q_heads, pl.vbatch, pl.fuse_splits), dim3(kHeadThreads),
+                     fused_head_lds_bytes(pl, pl.fuse_splits), st, A);
   return hipGetLastError();
 }
 
@@ -1675,6 +1895,14 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.given_vstat = reinterpret_cast<const float*>(w + pl.off_vstat_part);
   A.given_splits = pl.given_splits;
   A.sparse = reinterpret_cast<const float*>(w + pl.off_sparse);
+  A.v = nullptr;
+  A.L = pl.kv_v;
+  A.part = nullptr;
+  A.splits = 1;
+  A.split_shift = 0;
+  A.group = pl.group;
+  A.glist_cap = 0;
+  A.dlist_cap = 0;
 }
 
 }  // namespace vatt
