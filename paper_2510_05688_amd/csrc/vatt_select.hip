@@ -224,15 +224,20 @@ struct HeadOps {
   // the token is repeated and says so in `scratch`.  The draws of repeated tokens then post (draw number,
   // bit position) with an atomic minimum into the mail slot of their bitmap word; the smallest draw number
   // of a token wins its slot.  Two repeated tokens that share a word take turns (one more round per token).
+  //
+  // lt: the Philox block (relative to blk0) this thread generates, normally its thread index.  Two streams can
+  // share one call, each thread working for one of them (its own S, with bitmaps, scratch and mail of that
+  // stream, and lt counted inside the stream's group of threads): the barriers are common, the rest is per
+  // thread.
   static __device__ __forceinline__ void make_batch(DrawBatch& B, const Sampler& S, const HeadSizes& hs, uint32_t blk0, int blocks,
-                                    bool check_prev, bool load_scores, HeadSmem& sm) {
-    const int tid = threadIdx.x;
+                                    bool check_prev, bool load_scores, HeadSmem& sm, int lt) {
+    const int tid = lt;
     B.blocks = blocks;
     B.ok = 0;
     B.first = 0;
     B.have_sc = load_scores;
     VATT_STAMP(S.dbg, 0);
-    if (tid < blocks) {
+    if (tid >= 0 && tid < blocks) {
       const Philox4 ph = philox4x32_10(blk0 + (uint32_t)tid, S.stream, S.head, S.query, (uint32_t)S.seed,
                                        (uint32_t)(S.seed >> 32));
 #pragma unroll
@@ -346,7 +351,7 @@ struct HeadOps {
         const uint32_t remaining = target - have;
         const int blocks = (small_batches || remaining <= 128u) ? kSmallBatchBlocks
                                                                   : (remaining > 1024u ? min(NT, 1024) : min(NT, 256));
-        make_batch(B, S, hs, blk, blocks, blk > 0, false, sm);
+        make_batch(B, S, hs, blk, blocks, blk > 0, false, sm, (int)threadIdx.x);
       }
       ++batches;
       VATT_STAMP(S.dbg, 10);
@@ -816,8 +821,13 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   uint32_t* scratch = taken1 + words_max;
   uint32_t* wpre = scratch + words_max;
   uint32_t* mail = wpre + words_max;
+  // (the 512-thread kernel can generate the first batches of both streams at once: the final sample's stream
+  // then needs a scratch bitmap and mail slots of its own)
+  constexpr bool kTwoStreams = NT == kHeadThreads;
+  uint32_t* scratch1 = kTwoStreams ? mail + words_max : scratch;
+  uint32_t* mail1 = kTwoStreams ? scratch1 + words_max : mail;
   // fused gather: this workgroup's share of I_f and of the final sample, and the cross-wave sums
-  uint32_t* glist = mail + words_max;
+  uint32_t* glist = mail1 + words_max;
   uint32_t* dlist = glist + (kFused ? A.glist_cap : 0);
   float* g_red = reinterpret_cast<float*>(dlist + (kFused ? A.dlist_cap : 0));
   auto to_glist = [&](uint32_t p, uint32_t tok) {
@@ -842,6 +852,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     taken1[w] = 0;
     scratch[w] = 0;
     mail[w] = kInv32;
+    if (kTwoStreams) {
+      scratch1[w] = 0;
+      mail1[w] = kInv32;
+    }
   }
   __syncthreads();
 
@@ -869,6 +883,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   S0.dbg = A.dbg ? A.dbg + 200 : nullptr;
   S1 = S0;
   S1.taken = taken1;
+  S1.scratch = scratch1;
+  S1.mail = mail1;
   S1.stream = 1u;
   S1.dbg = A.dbg ? A.dbg + 300 : nullptr;
   DrawBatch spec0 = {}, spec1 = {};
@@ -899,7 +915,20 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     }
   };
   bool spec1_made = false;
-  if (want0) O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm);
+  if (kTwoStreams && want0 && want1 && 2 * ahead_blocks<NT>(A.small_batches) <= NT) {
+    // both streams at once: the lower half of the workgroup generates the first batch of the base sample,
+    // the upper half that of the final sample
+    const int half = tid >= NT / 2 ? 1 : 0;
+    const int blocks = ahead_blocks<NT>(A.small_batches);
+    DrawBatch mine = {};
+    O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, half == 0, sm, tid - half * (NT / 2));
+    spec0.blocks = spec1.blocks = blocks;
+    spec0.have_sc = true;
+    if (half) spec1 = mine; else spec0 = mine;
+    spec1_made = true;
+  } else if (want0) {
+    O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm, tid);
+  }
   VATT_STAMP(A.dbg, 1);
 
   // ---- the head maximum m ----
@@ -1024,9 +1053,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
                 sv[u][0] = x.x; sv[u][1] = x.y; sv[u][2] = x.z; sv[u][3] = x.w;
                 sv[u][4] = y.x; sv[u][5] = y.y; sv[u][6] = y.z; sv[u][7] = y.w;
               }
-              if (q0 == 0 && want1) {
+              if (q0 == 0 && want1 && !spec1_made) {
                 // the final sample's first batch of draws is generated while these loads are in flight
-                O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
+                O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm, tid);
                 spec1_made = true;
               }
               uint32_t hit = 0;
@@ -1202,7 +1231,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(row[i] - m);
     for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
   }
+  VATT_STAMP(A.dbg, 30);
   __syncthreads();
+  VATT_STAMP(A.dbg, 31);
 
   // Fused gather, first part: the V rows (and scores) of this workgroup's share of I_f are requested now and
   // added after the samplers have run.  LPR adjacent lanes read one row; NG rows per round, UF rounds in flight.
@@ -1216,24 +1247,37 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   uint4 fv[UF];
   float fs[UF];
   int my_nf = 0;
-  auto load_row = [&](const uint32_t* list, int j, int count, float& sc, uint4& vv) {
-    sc = -INFINITY;  // weight exp(-inf - m) = 0
-    vv = make_uint4(0u, 0u, 0u, 0u);
-    if (j < count) {
-      const int t = min((int)list[j], n - 1);
-      sc = row[t];
-      vv = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, seq, kvh, t) + g_sub * 8);
+  // contiguous cache: this lane's 8 columns of row 0 of the head's V slice
+  const uint16_t* v_head = (kFused && !PAGED)
+                               ? A.v + (int64_t)seq * A.L.seq_stride + (int64_t)kvh * A.L.head_stride + g_sub * 8
+                               : nullptr;
+  // UF rows of a list at once, without branches: the list entries are read first, then all scores and rows
+  // are requested; slots beyond the list read token 0 and get the score -inf (weight exp(-inf - m) = 0).
+  auto load_rows = [&](const uint32_t* list, int j0, int count, int cap, float (&sc)[UF], uint4 (&vv)[UF]) {
+    int t[UF];
+#pragma unroll
+    for (int u = 0; u < UF; ++u) {
+      const int j = j0 + u * NG + g_grp;
+      t[u] = j < count ? min((int)list[min(j, cap - 1)], n - 1) : -1;
     }
+#pragma unroll
+    for (int u = 0; u < UF; ++u) {
+      const int tt = max(t[u], 0);
+      sc[u] = row[tt];
+      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, tt) + g_sub * 8);
+      else vv[u] = load_stream_16(v_head + (uint32_t)tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
+    }
+#pragma unroll
+    for (int u = 0; u < UF; ++u) sc[u] = t[u] >= 0 ? sc[u] : -INFINITY;
   };
   if constexpr (kFused) {
     const int n_f = hs.n_sink + hs.n_win + hs.k;
     my_nf = n_f > (int)split ? (int)(((uint32_t)n_f - split + smask) >> shift) : 0;
     my_nf = min(my_nf, A.glist_cap);
-#pragma unroll
-    for (int u = 0; u < UF; ++u) load_row(glist, u * NG + g_grp, my_nf, fs[u], fv[u]);
   }
 
-  if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm);
+  VATT_STAMP(A.dbg, 32);
+  if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm, tid);
 
   // ---- I_bs (Algorithm 2, base sample) and the sums over it ----
   int flags = topk_flag;
@@ -1345,6 +1389,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   }
 
   VATT_STAMP(A.dbg, 7);
+  if constexpr (kFused) {
+    load_rows(glist, 0, my_nf, A.glist_cap, fs, fv);
+  }
   // ---- I_dyn (Algorithm 1, final sample) ----
   if (bfin > 0) {
     Emit E1 = emit_to(idx + A.seg_dyn, (uint32_t)A.b_max);
@@ -1401,16 +1448,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     };
     add_rows(fs, fv, 1.0f);
     for (int j0 = UF * NG; j0 < my_nf; j0 += UF * NG) {
-#pragma unroll
-      for (int u = 0; u < UF; ++u) load_row(glist, j0 + u * NG + g_grp, my_nf, fs[u], fv[u]);
+      load_rows(glist, j0, my_nf, A.glist_cap, fs, fv);
       add_rows(fs, fv, 1.0f);
     }
     int my_nd = bfin > (int)split ? (int)(((uint32_t)bfin - split + smask) >> shift) : 0;
     my_nd = min(my_nd, A.dlist_cap);
     const float tail_scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
     for (int j0 = 0; j0 < my_nd; j0 += UF * NG) {
-#pragma unroll
-      for (int u = 0; u < UF; ++u) load_row(dlist, j0 + u * NG + g_grp, my_nd, fs[u], fv[u]);
+      load_rows(dlist, j0, my_nd, A.dlist_cap, fs, fv);
       add_rows(fs, fv, tail_scale);
     }
     VATT_STAMP(A.dbg, 10);
@@ -1420,8 +1465,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) gacc[c] += __shfl_xor(gacc[c], o);
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) gdsum += __shfl_xor(gdsum, o);
+    gdsum = wave_sum_f32(gdsum);
     const int lane = tid & 63, wave = tid >> 6;
     float* g_d = g_red + SW * FD;
     if (lane < LPR) {
@@ -1764,7 +1808,7 @@ size_t head_kernel_lds_bytes(int n_max, int head_threads) {
   const size_t fixed = head_threads == kHeadThreadsLong ? sizeof(HeadOps<kHeadThreadsLong>::HeadSmem)
                                                         : sizeof(HeadOps<kHeadThreads>::HeadSmem);
   return ((fixed + 15) & ~size_t(15)) + (size_t)kCandCap * (sizeof(uint64_t) + sizeof(uint32_t)) +
-         6 * words_max * sizeof(uint32_t);
+         (head_threads == kHeadThreads ? 8 : 6) * words_max * sizeof(uint32_t);
 }
 
 // LDS entries of a workgroup's share of I_f and of the final sample when `splits` workgroups share a head.

@@ -552,10 +552,10 @@ def test_selection_kernel_with_1024_threads_gives_identical_results():
         narrow = _run(sess)
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 1024)
         wide = _run(sess)
-        _same_results(wl, narrow, wide)
+        _same_results(wl, narrow, wide, output_by_norm=True)   # (narrow may run with the gather fused in)
         check_all(wl, wide, label="1024-threads")
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 1)
-        _same_results(wl, narrow, _run(sess))
+        _same_results(wl, narrow, _run(sess), output_by_norm=True)
         with pytest.raises(vb.VattError):
             vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 768)
         sess.close()
