@@ -34,9 +34,12 @@ extern "C" {
  *     final samples only; VATT_E_UNSUPPORTED_SHAPE when the kernel's LDS does not hold that split).  The plan
  *     picks S > 0 for batches with fewer heads than half the chip's compute units.  The index sets, budgets
  *     and statistics are identical; the output sums run in another order.
+ *   VATT_OPT_SCORE_PREWORK = 0 / 1: with the fused gather, whether the first batches of the sampler's draw
+ *     sequences are made by the first workgroups of the score launch while the rest of it streams K (1, the
+ *     default for such plans in the KV-head-major launch order) or by the selection kernel itself (0).
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9 };
+       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9, VATT_OPT_SCORE_PREWORK = 10 };
 
 /* Workspace region (vatt_plan_workspace_offset): uint64 [512] of phase clock stamps, written only by builds
  * of the library made with -DVATT_TIMING. */

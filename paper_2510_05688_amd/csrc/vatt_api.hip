@@ -135,6 +135,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.dense_splits = std::min(std::min(64, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
 
   pl.fuse_splits = fused_splits_for(pl);
+  pl.prework = pl.fuse_splits > 0 ? 1 : 0;
 
   pl.seg_off[0] = 0;
   pl.seg_off[1] = p.sink;
@@ -159,6 +160,8 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.off_debug = take(512 * sizeof(uint64_t));
   pl.off_vstat_part = take((size_t)heads * pl.vstat_splits * (2 * p.head_dim + 2) * sizeof(double));
   pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
+  pl.off_pre_tok = take((size_t)heads * kHeadThreads * sizeof(uint4));
+  pl.off_pre_flags = take((size_t)heads * kHeadThreads * sizeof(uint32_t));
   pl.ws_bytes = off;
 
   KVLayout L;
@@ -262,7 +265,7 @@ int vatt_plan_create_chunk(const vatt_params* params, int q_len, int device, vat
     if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
   }
   if (rc != VATT_OK) {
-    delete plan;
+    vatt_plan_destroy(plan);
     return rc;
   }
   *out = plan;
@@ -310,6 +313,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     pl.head_lds_bytes = lds;
     if (value != kHeadThreads) pl.fuse_splits = 0;
     if (pl.device >= 0 && set_kernel_attributes(pl) != hipSuccess) return VATT_E_HIP;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_SCORE_PREWORK) {
+    plan->pl.prework = value ? 1 : 0;
     return VATT_OK;
   }
   if (option == VATT_OPT_FUSED_GATHER) {
@@ -360,7 +367,7 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
   if (plan->pl.q_len > 1)
     VATT_LAUNCH(launch_score_chunk(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
   else
-    VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, workspace, static_cast<hipStream_t>(stream)));
+    VATT_LAUNCH(launch_score(plan->pl, q, k, block_table, seq_lens, nullptr, workspace, static_cast<hipStream_t>(stream)));
   return VATT_OK;
 }
 
@@ -389,14 +396,15 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool fused = pl.p.target == VATT_TARGET_D && pl.fuse_splits > 0 && !pl.nested_samples;
   if (pl.q_len > 1)
     VATT_LAUNCH(launch_score_chunk(pl, q, k, block_table, seq_lens, workspace, st));
   else
-    VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, workspace, st));
-  if (pl.p.target == VATT_TARGET_D && pl.fuse_splits > 0 && !pl.nested_samples) {
+    VATT_LAUNCH(launch_score(pl, q, k, block_table, seq_lens, seq_seeds, workspace, st));
+  if (fused) {
     // small batch: selection and gather in one kernel, several workgroups per head
     VATT_LAUNCH(launch_head_fused(pl, v, block_table, seq_lens, seq_seeds, workspace, out_idx, out_counts,
-                                  out_budget_raw, out_stats, st));
+                                  out_budget_raw, out_stats, score_prework(pl), st));
     VATT_LAUNCH(launch_gather_merge(pl, workspace, pl.fuse_splits, out_o, out_lse, st));
     return VATT_OK;
   }

@@ -58,16 +58,18 @@ struct Plan {
   int score_order;                // launch order of the score pass (kScoreOrder*)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
+  int prework;                    // the sampler streams' first batches are made by workgroups of the score launch
   int fuse_splits;                // > 0: the selection kernel also gathers, with this many workgroups per head
   // workspace offsets (bytes)
   size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
-      off_debug, off_vstat_part, off_dense_part, ws_bytes;
+      off_debug, off_vstat_part, off_dense_part, off_pre_tok, off_pre_flags, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };
 
 // Every launcher returns a hipError_t from hipGetLastError() after the launch.
+// seq_seeds: needed (may be nullptr otherwise) when score_prework(pl)
 hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
-                        const int32_t* seq_lens, void* ws, hipStream_t st);
+                        const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws, hipStream_t st);
 // The score pass of a multi-query step (q_len > 1): all query tokens and group heads share one read of K.
 hipError_t launch_score_chunk(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
                               const int32_t* seq_lens, void* ws, hipStream_t st);
@@ -81,7 +83,13 @@ hipError_t launch_head(const Plan& pl, int phase, const int32_t* seq_lens, const
 // of the per-workgroup partial sums.
 hipError_t launch_head_fused(const Plan& pl, const void* v, const int32_t* block_table, const int32_t* seq_lens,
                              const uint64_t* seq_seeds, void* ws, int32_t* out_idx, int32_t* out_counts,
-                             double* out_budget_raw, float* out_stats, hipStream_t st);
+                             double* out_budget_raw, float* out_stats, bool pre_made, hipStream_t st);
+// Whether workgroups of the score launch make the sampler streams' first batches for the fused selection kernel
+// (single-token steps in the KV-head-major launch order only).
+inline bool score_prework(const Plan& pl) {
+  return pl.prework && pl.fuse_splits > 0 && !pl.nested_samples && pl.q_len == 1 &&
+         pl.p.target == VATT_TARGET_D && pl.score_order == kScoreOrderKvHead;
+}
 hipError_t launch_gather_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st);
 int fused_splits_for(const Plan& pl);           // the plan's own choice (0: separate kernels)
 bool fused_splits_fit(const Plan& pl, int splits);  // whether the fused kernel can run with that many

@@ -28,9 +28,11 @@
 // (bf16 pair dot-products accumulating in fp32), the partial sums are added across the d/8 lanes on
 // the DPP path, and the tile's G x TILE scores are staged in LDS so that they leave as whole
 // 256-byte rows; the largest score of every 8 keys is written next to them.
+#include <cstring>
 #include <utility>
 
 #include "vatt_internal.h"
+#include "vatt_sampler.h"
 
 namespace vatt {
 namespace {
@@ -52,7 +54,8 @@ template <int D, int G, bool PAGED, int TILE>
 __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     KVLayout L, const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ scores, float* __restrict__ sub_max,
-                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale, int order) {
+                                                    int n_sub, int n_pad, int n_max, int Hq, float sm_scale, int order,
+                                                    PreArgs pre) {
   constexpr int LPR = D / 8;             // lanes per K row
   constexpr int RPW = kWave / LPR;       // rows per wave load
   constexpr int ROWS_PER_WAVE = TILE / 4;
@@ -64,8 +67,16 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
   // (gridDim.x: a multiple of 8 BL; the rotation spreads the first blocks, all that a short sequence has, over
   // the XCDs)
   constexpr int BL = score_block_tiles(D, TILE);
+  // KV-head-major order with sampler pre-work: the first pre.job_rows rows of the grid (the workgroups that
+  // start first) each make the first batch of draws of one (head, stream) and are done
+  if (pre.job_rows > 0 && (int)blockIdx.y < pre.job_rows) {
+    extern __shared__ __align__(16) unsigned char pre_smem[];
+    const int job = (int)blockIdx.y * (int)gridDim.x + (int)blockIdx.x;
+    if (job < 2 * Hq) prework_job(pre, (int)blockIdx.z, job >> 1, job & 1, pre_smem);
+    return;
+  }
   const int kvh = order == kScoreOrderKvHead ? blockIdx.x : blockIdx.y, b = blockIdx.z;
-  const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y
+  const int tile = order == kScoreOrderKvHead ? (int)blockIdx.y - pre.job_rows
                    : order == kScoreOrderBlocks
                        ? (int)((((blockIdx.x / 8) / BL) * 8 + (blockIdx.x + blockIdx.y + blockIdx.z) % 8) * BL +
                                (blockIdx.x / 8) % BL)
@@ -170,8 +181,27 @@ inline void shape_grid(dim3& grid, int order, int block_tiles) {
 
 template <int D, int G>
 hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
-                     const int32_t* seq_lens, void* ws, hipStream_t st) {
+                     const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws, hipStream_t st) {
   const vatt_params& p = pl.p;
+  PreArgs pre;
+  memset(&pre, 0, sizeof(pre));
+  size_t lds = 0;
+  int job_rows = 0;
+  if (score_prework(pl) && seq_seeds) {
+    char* w = static_cast<char*>(ws);
+    pre.seq_lens = seq_lens;
+    pre.seq_seeds = seq_seeds;
+    pre.pre_tok = reinterpret_cast<uint4*>(w + pl.off_pre_tok);
+    pre.pre_flags = reinterpret_cast<uint32_t*>(w + pl.off_pre_flags);
+    pre.sp = pl.sel;
+    pre.n_max = p.n_max;
+    pre.Hq = p.n_q_heads;
+    pre.small_batches = pl.sampler_small_batches;
+    pre.draw_cap = pl.sampler_draw_cap;
+    job_rows = (2 * p.n_q_heads + p.n_kv_heads - 1) / p.n_kv_heads;  // grid rows of n_kv_heads workgroups
+    pre.job_rows = job_rows;
+    lds = prework_lds_bytes(p.n_max);
+  }
 
   KVLayout L = pl.kv_k;
   L.block_table = block_table;
@@ -182,27 +212,29 @@ hipError_t launch_dg(const Plan& pl, const void* q, const void* k, const int32_t
   if (p.kv_layout == VATT_LAYOUT_PAGED) {
     dim3 grid((p.n_max + kScoreTilePaged - 1) / kScoreTilePaged, p.n_kv_heads, p.batch);
     shape_grid(grid, pl.score_order, score_block_tiles(D, kScoreTilePaged));
-    hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), 0, st,
+    grid.y += job_rows;  // (only set in the KV-head-major order, where y runs over the tiles)
+    hipLaunchKernelGGL((score_kernel<D, G, true, kScoreTilePaged>), grid, dim3(256), lds, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order, pre);
   } else {
     dim3 grid((p.n_max + kScoreTile - 1) / kScoreTile, p.n_kv_heads, p.batch);
     shape_grid(grid, pl.score_order, score_block_tiles(D, kScoreTile));
-    hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), 0, st,
+    grid.y += job_rows;
+    hipLaunchKernelGGL((score_kernel<D, G, false, kScoreTile>), grid, dim3(256), lds, st,
                        static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k), L, seq_lens, scores, smax,
-                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order);
+                       pl.n_sub, pl.n_pad, p.n_max, p.n_q_heads, pl.sm_scale, pl.score_order, pre);
   }
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_d(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
-                    const int32_t* seq_lens, void* ws, hipStream_t st) {
+                    const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws, hipStream_t st) {
   switch (pl.group) {
-    case 1: return launch_dg<D, 1>(pl, q, k, block_table, seq_lens, ws, st);
-    case 2: return launch_dg<D, 2>(pl, q, k, block_table, seq_lens, ws, st);
-    case 4: return launch_dg<D, 4>(pl, q, k, block_table, seq_lens, ws, st);
-    case 8: return launch_dg<D, 8>(pl, q, k, block_table, seq_lens, ws, st);
+    case 1: return launch_dg<D, 1>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
+    case 2: return launch_dg<D, 2>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
+    case 4: return launch_dg<D, 4>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
+    case 8: return launch_dg<D, 8>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -210,9 +242,9 @@ hipError_t launch_d(const Plan& pl, const void* q, const void* k, const int32_t*
 }  // namespace
 
 hipError_t launch_score(const Plan& pl, const void* q, const void* k, const int32_t* block_table,
-                        const int32_t* seq_lens, void* ws, hipStream_t st) {
-  if (pl.p.head_dim == 128) return launch_d<128>(pl, q, k, block_table, seq_lens, ws, st);
-  if (pl.p.head_dim == 64) return launch_d<64>(pl, q, k, block_table, seq_lens, ws, st);
+                        const int32_t* seq_lens, const uint64_t* seq_seeds, void* ws, hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_d<128>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
+  if (pl.p.head_dim == 64) return launch_d<64>(pl, q, k, block_table, seq_lens, seq_seeds, ws, st);
   return hipErrorInvalidValue;
 }
 

@@ -20,38 +20,10 @@
 // Floating-point sums are taken in a fixed order, or as fixed-point integers where the order depends on
 // scheduling, so the statistics and the budget are reproducible too.
 #include "vatt_internal.h"
+#include "vatt_sampler.h"
 
 namespace vatt {
 namespace {
-
-constexpr uint32_t kInv32 = 0xffffffffu;
-
-// ---------------------------------------------------------------------------
-// Workgroup-wide exclusive scan of one uint32 per thread (DPP inside a wave, LDS across waves).
-// ---------------------------------------------------------------------------
-template <int NT>
-struct BlockScanSmem {
-  uint32_t wave_total[NT / kWave];
-};
-// Returns the exclusive prefix of v; *total gets the workgroup sum.
-template <int NT>
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* total, BlockScanSmem<NT>& sm) {
-  constexpr int SW = NT / kWave;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t incl = wave_inclusive_scan_u32(v);
-  __syncthreads();  // protects wave_total against a previous use
-  if (lane == kWave - 1) sm.wave_total[wave] = incl;
-  __syncthreads();
-  uint32_t base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < SW; ++w) {
-    const uint32_t t = sm.wave_total[w];
-    base += (w < wave) ? t : 0u;
-    tot += t;
-  }
-  *total = tot;
-  return base + incl - v;
-}
 
 // ---------------------------------------------------------------------------
 // Per-head kernel.
@@ -92,384 +64,11 @@ struct HeadArgs {
   float* part;       // [B*Hq][splits][d + 4]: partial (sum w V, sum w) of every workgroup
   int splits, split_shift, group;
   int glist_cap, dlist_cap;  // LDS entries for a workgroup's share of I_f and of the final sample
+  // first batches of both sampler streams made ahead by prework_kernel (nullptr: made here)
+  const uint4* pre_tok;       // [B*Hq][kHeadThreads]: the four proposed tokens of every thread
+  const uint32_t* pre_flags;  // [B*Hq][kHeadThreads]: ok | first << 4 | (made ? 256 : 0)
 };
 
-// Where an accepted token goes: into the index list in global memory (dst, for the workgroup that writes the
-// outputs) and, when a workgroup gathers its own share of the list (fused gather), every 2^shift-th entry into
-// an LDS list.
-struct Emit {
-  int32_t* dst;
-  uint32_t dst_cap;
-  uint32_t* lds;      // nullptr: no LDS list
-  uint32_t lds_cap;
-  uint32_t shift, split;
-  bool global;
-};
-__device__ __forceinline__ void emit_tok(const Emit& E, uint32_t p, int32_t tok) {
-  if (E.global && p < E.dst_cap) E.dst[p] = tok;
-  if (E.lds && (p & ((1u << E.shift) - 1u)) == E.split && (p >> E.shift) < E.lds_cap) E.lds[p >> E.shift] = (uint32_t)tok;
-}
-__device__ __forceinline__ Emit emit_to(int32_t* dst, uint32_t dst_cap) {
-  Emit E;
-  E.dst = dst;
-  E.dst_cap = dst_cap;
-  E.lds = nullptr;
-  E.lds_cap = 0;
-  E.shift = 0;
-  E.split = 0;
-  E.global = true;
-  return E;
-}
-
-constexpr int kSmallBatchBlocks = 64;  // Philox blocks of a small batch (256 draws)
-
-// flag bits of out_counts[7]
-constexpr int kFlagBaseComplement = 1, kFlagDynComplement = 2, kFlagBaseBatches = 4, kFlagDynBatches = 8,
-              kFlagDrawCap = 16, kFlagTopkGeneral = 32;
-
-// One batch of the draw sequence as a thread sees it: the four draws of one Philox block.
-struct DrawBatch {
-  uint32_t tok[4];  // proposed tokens
-  float sc[4];      // their scores, when loaded ahead
-  uint32_t ok;      // bit e: the draw counts (inside the batch and the draw cap, word not rejected, token not
-                    // drawn in an earlier batch)
-  uint32_t first;   // bit e: ok and no earlier draw of the batch proposes the same token
-  int blocks;       // Philox blocks in the batch
-  bool have_sc;
-};
-
-// Device functions of the per-head kernel for a workgroup of NT threads.
-template <int NT>
-struct HeadOps {
-  static constexpr int SW = NT / kWave;
-
-  struct HeadSmem {
-    BlockScanSmem<NT> scan;
-    double red[3][SW];
-    uint32_t again;
-  };
-
-  // Workgroup sums of up to three doubles at once; every thread gets all of them.
-  template <int N>
-  static __device__ __forceinline__ void block_sum(double (&v)[N], HeadSmem& sm) {
-#pragma unroll
-    for (int j = 0; j < N; ++j) v[j] = wave_sum(v[j]);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-      for (int j = 0; j < N; ++j) sm.red[j][threadIdx.x >> 6] = v[j];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-      double t = 0.0;
-#pragma unroll
-      for (int w = 0; w < SW; ++w) t += sm.red[j][w];
-      v[j] = t;
-    }
-  }
-
-  // Token read back from an index list, forced into [0, n): a list entry can never address outside the row.
-  static __device__ __forceinline__ int list_tok(const int32_t* idx, int64_t pos, int n) {
-    return min(max(idx[pos], 0), n - 1);
-  }
-
-  static __device__ __forceinline__ void mark_bit(uint32_t* bm, uint32_t i) { atomicOr(&bm[i >> 5], 1u << (i & 31)); }
-  static __device__ __forceinline__ bool test_bit(const uint32_t* bm, uint32_t i) { return (bm[i >> 5] >> (i & 31)) & 1u; }
-
-  // Exclusive prefix of the set-bit counts of bm[0, words) into wpre; returns the number of set bits.
-  static __device__ uint32_t word_prefix(const uint32_t* bm, int words, uint32_t* wpre, HeadSmem& sm) {
-    const int wpt = (words + NT - 1) / NT;
-    const int w0 = threadIdx.x * wpt;
-    uint32_t cnt = 0;
-    for (int w = w0; w < min(w0 + wpt, words); ++w) cnt += __popc(bm[w]);
-    uint32_t total;
-    uint32_t pos = block_exclusive_scan<NT>(cnt, &total, sm.scan);
-    for (int w = w0; w < min(w0 + wpt, words); ++w) {
-      wpre[w] = pos;
-      pos += __popc(bm[w]);
-    }
-    __syncthreads();
-    return total;
-  }
-
-  // Bits of word w that lie in the middle region [mid_lo, mid_hi).
-  static __device__ __forceinline__ uint32_t mid_mask(const HeadSizes& hs, int w) {
-    const int i0 = w << 5;
-    if (i0 + 31 < hs.mid_lo || i0 >= hs.mid_hi) return 0u;
-    const int a = max(hs.mid_lo - i0, 0), bnd = min(hs.mid_hi - i0, 32);
-    return (bnd >= 32 ? 0xffffffffu : ((1u << bnd) - 1u)) & ~((1u << a) - 1u);
-  }
-
-  // What one sample needs to know.
-  struct Sampler {
-    uint32_t* taken;      // tokens proposed so far (bitmap, LDS)
-    uint32_t* scratch;    // all-zero bitmap between uses (LDS)
-    uint32_t* mail;       // one slot per bitmap word, all-ones between uses (LDS)
-    const uint32_t* bm_f; // top-k members (bitmap, LDS)
-    uint32_t* wpre;       // word prefixes (LDS)
-    const float* row;     // the head's scores
-    uint64_t seed;
-    uint32_t stream, head, query;
-    uint32_t L, thr;      // middle-region length and 2^32 mod L
-    uint32_t cap;         // draws allowed
-    float m;
-    unsigned long long* dbg;
-  };
-
-  // Generate the draws of Philox blocks [blk0, blk0 + blocks) of the stream and find, for every token that is
-  // proposed more than once in the batch, its earliest draw.
-  //
-  // Every draw that counts sets its token's bit in `taken`; a draw that finds the bit already set knows that
-  // the token is repeated and says so in `scratch`.  The draws of repeated tokens then post (draw number,
-  // bit position) with an atomic minimum into the mail slot of their bitmap word; the smallest draw number
-  // of a token wins its slot.  Two repeated tokens that share a word take turns (one more round per token).
-  //
-  // lt: the Philox block (relative to blk0) this thread generates, normally its thread index.  Two streams can
-  // share one call, each thread working for one of them (its own S, with bitmaps, scratch and mail of that
-  // stream, and lt counted inside the stream's group of threads): the barriers are common, the rest is per
-  // thread.
-  static __device__ __forceinline__ void make_batch(DrawBatch& B, const Sampler& S, const HeadSizes& hs, uint32_t blk0, int blocks,
-                                    bool check_prev, bool load_scores, HeadSmem& sm, int lt) {
-    const int tid = lt;
-    B.blocks = blocks;
-    B.ok = 0;
-    B.first = 0;
-    B.have_sc = load_scores;
-    VATT_STAMP(S.dbg, 0);
-    if (tid >= 0 && tid < blocks) {
-      const Philox4 ph = philox4x32_10(blk0 + (uint32_t)tid, S.stream, S.head, S.query, (uint32_t)S.seed,
-                                       (uint32_t)(S.seed >> 32));
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t j = ((blk0 + (uint32_t)tid) << 2) + (uint32_t)e;
-        const uint64_t x = (uint64_t)ph.v[e] * (uint64_t)S.L;
-        const uint32_t t = (uint32_t)hs.mid_lo + (uint32_t)(x >> 32);
-        bool v = j < S.cap && (uint32_t)x >= S.thr;
-        if (check_prev) v = v && !test_bit(S.taken, t);
-        B.tok[e] = t;
-        B.ok |= (v ? 1u : 0u) << e;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) B.tok[e] = (uint32_t)hs.mid_lo;
-    }
-    if (load_scores) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) B.sc[e] = S.row[B.tok[e]];
-    }
-    VATT_STAMP(S.dbg, 1);
-    if (check_prev) __syncthreads();  // every test of `taken` comes before the marks of this batch
-    uint32_t lose = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      if ((B.ok >> e) & 1u) {
-        const uint32_t bit = 1u << (B.tok[e] & 31);
-        const uint32_t old = atomicOr(&S.taken[B.tok[e] >> 5], bit);
-        if (old & bit) {
-          lose |= 1u << e;
-          atomicOr(&S.scratch[B.tok[e] >> 5], bit);
-        }
-      }
-    }
-    __syncthreads();
-    VATT_STAMP(S.dbg, 2);
-    // draws whose token is proposed more than once in this batch
-    uint32_t unresolved = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (((B.ok >> e) & 1u) && test_bit(S.scratch, B.tok[e])) unresolved |= 1u << e;
-    uint32_t later = 0;
-    for (;;) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if ((unresolved >> e) & 1u) atomicMin(&S.mail[B.tok[e] >> 5], ((uint32_t)(tid * 4 + e) << 5) | (B.tok[e] & 31));
-      if (threadIdx.x == 0) sm.again = 0;
-      __syncthreads();
-      uint32_t won = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if ((unresolved >> e) & 1u) {
-          const uint32_t v = S.mail[B.tok[e] >> 5];
-          if ((v & 31u) == (B.tok[e] & 31u)) {
-            if ((v >> 5) == (uint32_t)(tid * 4 + e)) won |= 1u << e; else later |= 1u << e;
-            unresolved &= ~(1u << e);
-          }
-        }
-      }
-      if (unresolved) sm.again = 1;
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if ((won >> e) & 1u) S.mail[B.tok[e] >> 5] = kInv32;
-      const bool again = sm.again != 0;
-      __syncthreads();
-      if (!again) break;
-    }
-    B.first = B.ok & ~later;
-    VATT_STAMP(S.dbg, 3);
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if ((lose >> e) & 1u) atomicAnd(&S.scratch[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));
-    __syncthreads();
-    VATT_STAMP(S.dbg, 4);
-  }
-
-  // Draw a sample of c residual tokens for the stream described by S.  `taken` must be all zero on entry
-  // unless `spec` carries the first batch (have_spec; made from block 0 with make_batch), `scratch` all zero.
-  // Writes the token list to dst (acceptance order, or ascending when the sample is a complement) and, when
-  // sum_w is given, adds exp(s_i - m) and its square over the sample to this thread's partial sums.
-  // Returns flag bits: 1 complement regime, 2 more than one batch, 4 draw cap reached.
-  static __device__ __forceinline__ int draw_sample(const Sampler& S, const HeadSizes& hs, uint32_t c, const DrawBatch& spec, bool have_spec,
-                                    int small_batches, const Emit& E, double* sum_w,
-                                    double* sum_w2, HeadSmem& sm) {
-    const int tid = threadIdx.x;
-    const int words = (hs.n + 31) >> 5;
-    const uint32_t ns = (uint32_t)hs.n_s;
-    if (c == 0) return 0;
-    int flags = 0;
-    const bool all = c >= ns;
-    const bool invert = all || 2u * c > ns;
-    const uint32_t target = all ? 0u : (invert ? ns - c : c);
-    if (all) {
-      // the whole residual: no draws; forget a batch that was generated ahead
-      __syncthreads();
-      for (int w = tid; w < words; w += NT) S.taken[w] = 0;
-      __syncthreads();
-    }
-    uint32_t have = 0, blk = 0;
-    int batches = 0;
-    bool use_spec = have_spec;
-    double aw = 0.0, aw2 = 0.0;
-    while (have < target) {
-      if ((uint64_t)blk * 4ull >= (uint64_t)S.cap) break;
-      DrawBatch B;
-      if (use_spec) {
-        B = spec;
-        use_spec = false;
-      } else {
-        const uint32_t remaining = target - have;
-        const int blocks = (small_batches || remaining <= 128u) ? kSmallBatchBlocks
-                                                                  : (remaining > 1024u ? min(NT, 1024) : min(NT, 256));
-        make_batch(B, S, hs, blk, blocks, blk > 0, false, sm, (int)threadIdx.x);
-      }
-      ++batches;
-      VATT_STAMP(S.dbg, 10);
-      // accept in draw order: first proposals of residual tokens, until the target is reached
-      uint32_t acc = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (((B.first >> e) & 1u) && !test_bit(S.bm_f, B.tok[e])) acc |= 1u << e;
-      uint32_t total;
-      uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(acc), &total, sm.scan);
-      const uint32_t room = target - have;
-      VATT_STAMP(S.dbg, 11);
-      // (written without nested per-draw branches: a divergent branch inside an unrolled loop serialises it)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const bool a = (acc >> e) & 1u;
-        const bool take = a && pos < room;
-        if (!invert) {
-          if (take) emit_tok(E, have + pos, (int32_t)B.tok[e]);
-          if (sum_w) {
-            const float sc = B.have_sc ? B.sc[e] : (take ? S.row[B.tok[e]] : 0.f);
-            const double w = take ? (double)__expf(sc - S.m) : 0.0;
-            aw += w;
-            aw2 += w * w;
-          }
-        } else if (a && !take) {
-          atomicAnd(&S.taken[B.tok[e] >> 5], ~(1u << (B.tok[e] & 31)));  // drawn after the sample was complete
-        }
-        pos += a ? 1u : 0u;
-      }
-      have += min(total, room);
-      blk += (uint32_t)B.blocks;
-      VATT_STAMP(S.dbg, 12);
-    }
-    if (batches > 1) flags |= 2;
-    __syncthreads();
-    if (have < target) {
-      // draw cap reached: complete with the lowest-index residual tokens not yet accepted
-      flags |= 4;
-      const uint32_t need = target - have;
-      for (int w = tid; w < words; w += NT) S.scratch[w] = mid_mask(hs, w) & ~S.bm_f[w] & ~S.taken[w];
-      __syncthreads();
-      word_prefix(S.scratch, words, S.wpre, sm);
-      for (int w = tid; w < words; w += NT) {
-        uint32_t bits = S.scratch[w];
-        uint32_t pos = S.wpre[w];
-        while (bits && pos < need) {
-          const uint32_t i = (uint32_t)(w << 5) + (uint32_t)(__ffs(bits) - 1);
-          bits &= bits - 1u;
-          if (invert) {
-            atomicOr(&S.taken[i >> 5], 1u << (i & 31));
-          } else {
-            emit_tok(E, have + pos, (int32_t)i);
-            if (sum_w) {
-              const double wt = (double)__expf(S.row[i] - S.m);
-              aw += wt;
-              aw2 += wt * wt;
-            }
-          }
-          ++pos;
-        }
-      }
-      __syncthreads();
-      for (int w = tid; w < words; w += NT) S.scratch[w] = 0;
-      __syncthreads();
-    }
-    if (invert) {
-      // the sample is the residual minus the accepted tokens, in ascending order
-      flags |= 1;
-      for (int w = tid; w < words; w += NT) S.scratch[w] = mid_mask(hs, w) & ~S.bm_f[w] & ~S.taken[w];
-      __syncthreads();
-      word_prefix(S.scratch, words, S.wpre, sm);
-      for (int w = tid; w < words; w += NT) {
-        uint32_t bits = S.scratch[w];
-        uint32_t pos = S.wpre[w];
-        while (bits) {
-          const int i = (w << 5) + (__ffs(bits) - 1);
-          bits &= bits - 1u;
-          emit_tok(E, pos, i);
-          if (sum_w) {
-            const double wt = (double)__expf(S.row[i] - S.m);
-            aw += wt;
-            aw2 += wt * wt;
-          }
-          ++pos;
-        }
-      }
-      __syncthreads();
-      for (int w = tid; w < words; w += NT) S.scratch[w] = 0;
-      __syncthreads();
-    }
-    if (sum_w) {
-      *sum_w += aw;
-      *sum_w2 += aw2;
-    }
-    return flags;
-  }
-
-  // Nested final sample (an option; Algorithm 1 draws the final sample afresh): the base sample, whose list
-  // of b0 tokens this workgroup wrote at `base`, is kept as the head of the final sample, and the remaining
-  // c - b0 tokens are drawn with the stream of S among the residual tokens outside the base sample.  The base
-  // tokens are added to the bitmap of excluded tokens (bm, which S.bm_f points to) for that purpose.
-  static __device__ __forceinline__ int draw_nested(const Sampler& S, HeadSizes hs, uint32_t b0, uint32_t c,
-                                                    uint32_t* bm, const int32_t* base, int32_t* dst,
-                                                    uint32_t dst_cap, int small_batches, HeadSmem& sm) {
-    __syncthreads();  // the base list is complete (global memory is coherent inside a workgroup)
-    for (uint32_t t = threadIdx.x; t < b0; t += NT) {
-      const int tok = list_tok(base, t, hs.n);
-      mark_bit(bm, (uint32_t)tok);
-      if (t < dst_cap) dst[t] = tok;
-    }
-    __syncthreads();
-    if (c <= b0 || dst_cap <= b0) return 0;
-    hs.n_s -= (int)b0;
-    const DrawBatch none = {};
-    return draw_sample(S, hs, c - b0, none, false, small_batches, emit_to(dst + b0, dst_cap - b0), nullptr, nullptr, sm);
-  }
-};  // struct HeadOps
 
 // ---------------------------------------------------------------------------
 // The head's score row as the threads of the workgroup see it (general top-k path): thread t owns tokens
@@ -751,12 +350,6 @@ struct TopkOps {
   }
 };
 
-// Philox blocks of the batch that is generated ahead, before the top-k set is known.
-template <int NT>
-__device__ __forceinline__ int ahead_blocks(int small_batches) {
-  // (a workgroup of 1024 threads serves long rows, whose samples hold thousands of tokens)
-  return small_batches ? kSmallBatchBlocks : (NT >= 1024 ? 1024 : min(NT, 256));
-}
 
 // Accumulates weight * (8 bf16 values of a V row) into acc.
 __device__ __forceinline__ void add_weighted_row(float (&acc)[8], float wt, const uint4& vv) {
@@ -803,6 +396,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   for (int u = 0; u < SU; ++u) {
     const int t = u * NT + tid;
     sub_reg[u] = t < A.n_sub ? sub_max[t] : -INFINITY;
+  }
+  uint4 pre_t = make_uint4(0u, 0u, 0u, 0u);
+  uint32_t pre_f = 0u;
+  bool pre_made = false;
+  if (NT == kHeadThreads && A.pre_tok) {
+    pre_t = A.pre_tok[(int64_t)bh * NT + tid];
+    pre_f = A.pre_flags[(int64_t)bh * NT + tid];
+    pre_made = (A.pre_flags[(int64_t)bh * NT] & 256u) != 0u;  // one word for the whole workgroup: uniform
   }
   // In a multi-query step b stands for (sequence, query token); query token t of q_len sees the sequence up to
   // and including itself, which leaves out the q_len - 1 - t newer tokens.
@@ -921,7 +522,24 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     const int half = tid >= NT / 2 ? 1 : 0;
     const int blocks = ahead_blocks<NT>(A.small_batches);
     DrawBatch mine = {};
-    O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, half == 0, sm, tid - half * (NT / 2));
+    if (pre_made) {
+      // made ahead, while the scores were computed: the proposals are marked as drawn, and the scores of the
+      // base sample's proposals are requested
+      const uint32_t tk[4] = {pre_t.x, pre_t.y, pre_t.z, pre_t.w};
+      uint32_t* tk_bm = half ? taken1 : taken0;
+      mine.ok = pre_f & 15u;
+      mine.first = (pre_f >> 4) & 15u;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        mine.tok[e] = min(max(tk[e], (uint32_t)hs.mid_lo), (uint32_t)max(hs.mid_hi - 1, hs.mid_lo));
+        if (half == 0) mine.sc[e] = row[mine.tok[e]];
+        if ((mine.ok >> e) & 1u) atomicOr(&tk_bm[mine.tok[e] >> 5], 1u << (mine.tok[e] & 31));
+      }
+      mine.blocks = blocks;
+      mine.have_sc = half == 0;
+    } else {
+      O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, half == 0, sm, tid - half * (NT / 2));
+    }
     spec0.blocks = spec1.blocks = blocks;
     spec0.have_sc = true;
     if (half) spec1 = mine; else spec0 = mine;
@@ -1869,10 +1487,14 @@ int fused_splits_for(const Plan& pl) {
 // Selection with the fused gather (denominator target, fresh final sample): pl.fuse_splits workgroups per head.
 hipError_t launch_head_fused(const Plan& pl, const void* v, const int32_t* block_table, const int32_t* seq_lens,
                              const uint64_t* seq_seeds, void* ws, int32_t* out_idx, int32_t* out_counts,
-                             double* out_budget_raw, float* out_stats, hipStream_t st) {
+                             double* out_budget_raw, float* out_stats, bool pre_made, hipStream_t st) {
   HeadArgs A;
   fill_head_args(A, pl, 0, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
   const vatt_params& p = pl.p;
+  if (pre_made) {  // launch_prework ran for this call
+    A.pre_tok = reinterpret_cast<const uint4*>(static_cast<char*>(ws) + pl.off_pre_tok);
+    A.pre_flags = reinterpret_cast<const uint32_t*>(static_cast<char*>(ws) + pl.off_pre_flags);
+  }
   A.v = static_cast<const uint16_t*>(v);
   A.L = pl.kv_v;
   A.L.block_table = block_table;
@@ -1947,6 +1569,8 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.group = pl.group;
   A.glist_cap = 0;
   A.dlist_cap = 0;
+  A.pre_tok = nullptr;
+  A.pre_flags = nullptr;
 }
 
 }  // namespace vatt

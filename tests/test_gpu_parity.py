@@ -590,6 +590,11 @@ def test_fused_gather_matches_the_separate_kernels(case):
         fused = _run(sess)
         _same_results(wl, apart, fused, output_by_norm=True)
         check_all(wl, fused, label="fused, %d workgroups per head / %s" % (splits, case))
+    # the sampler's first batches made by the selection kernel itself instead of workgroups of the score launch
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SCORE_PREWORK, 0)
+    own = _run(sess)
+    for key in ("O", "lse", "b_star", "stats", "idx", "counts"):
+        assert np.array_equal(own[key], fused[key]), key
     with pytest.raises(vb.VattError):
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, 3)
     sess.close()
