@@ -430,9 +430,24 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // fused gather: this workgroup's share of I_f and of the final sample, and the cross-wave sums
   uint32_t* glist = mail1 + words_max;
   uint32_t* dlist = glist + (kFused ? A.glist_cap : 0);
-  float* g_red = reinterpret_cast<float*>(dlist + (kFused ? A.dlist_cap : 0));
-  auto to_glist = [&](uint32_t p, uint32_t tok) {
-    if (kFused && (p & smask) == split && (p >> shift) < (uint32_t)A.glist_cap) glist[p >> shift] = tok;
+  // (the scores of the listed tokens, so that the gather requests V rows only)
+  float* glist_sc = reinterpret_cast<float*>(dlist + (kFused ? A.dlist_cap : 0));
+  float* dlist_sc = glist_sc + (kFused ? A.glist_cap : 0);
+  float* g_red = dlist_sc + (kFused ? A.dlist_cap : 0);
+  // (I_f is dealt out in runs of consecutive list places: its top-k part is in ascending token order, so a
+  // workgroup's rows then lie close together in the cache)
+  uint32_t g_lo = 0, g_hi = 0;
+  if (kFused) {
+    const uint32_t n_f = (uint32_t)(hs.n_sink + hs.n_win + hs.k);
+    const uint32_t run = min((n_f + smask) >> shift, (uint32_t)A.glist_cap);  // ceil(n_f / splits)
+    g_lo = min(split * run, n_f);
+    g_hi = min(g_lo + run, n_f);
+  }
+  auto to_glist = [&](uint32_t p, uint32_t tok, float sc) {
+    if (kFused && p >= g_lo && p < g_hi) {
+      glist[p - g_lo] = tok;
+      glist_sc[p - g_lo] = sc;
+    }
   };
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
@@ -515,7 +530,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       }
     }
   };
-  bool spec1_made = false;
+  bool spec1_made = false, pair_made = false;
   if (kTwoStreams && want0 && want1 && 2 * ahead_blocks<NT>(A.small_batches) <= NT) {
     // both streams at once: the lower half of the workgroup generates the first batch of the base sample,
     // the upper half that of the final sample
@@ -532,18 +547,19 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         mine.tok[e] = min(max(tk[e], (uint32_t)hs.mid_lo), (uint32_t)max(hs.mid_hi - 1, hs.mid_lo));
-        if (half == 0) mine.sc[e] = row[mine.tok[e]];
+        mine.sc[e] = row[mine.tok[e]];
         if ((mine.ok >> e) & 1u) atomicOr(&tk_bm[mine.tok[e] >> 5], 1u << (mine.tok[e] & 31));
       }
       mine.blocks = blocks;
-      mine.have_sc = half == 0;
+      mine.have_sc = true;
     } else {
-      O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, half == 0, sm, tid - half * (NT / 2));
+      O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, true, sm, tid - half * (NT / 2));
     }
     spec0.blocks = spec1.blocks = blocks;
     spec0.have_sc = true;
     if (half) spec1 = mine; else spec0 = mine;
     spec1_made = true;
+    pair_made = true;
   } else if (want0) {
     O::make_batch(spec0, S0, hs, 0u, ahead_blocks<NT>(A.small_batches), false, true, sm, tid);
   }
@@ -807,7 +823,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
             const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
             const uint32_t pos = wpre[i >> 5] + (uint32_t)__popc(bm_f[i >> 5] & ((1u << (i & 31)) - 1u));
             if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)i;
-            to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, i);
+            to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, i, float_from_order_key(~(uint32_t)(c >> 32)));
           }
         }
       } else {
@@ -820,7 +836,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
             const int i = (w << 5) + (__ffs(bits) - 1);
             bits &= bits - 1u;
             if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
-            to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, (uint32_t)i);
+            if (kFused) to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, (uint32_t)i, row[i]);
             ++pos;
           }
         }
@@ -833,11 +849,11 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     for (int i = tid + NT; i < hs.n_win; i += NT) acc_f32 += __expf(row[hs.mid_hi + i] - m);
     for (int i = tid; i < hs.n_sink; i += NT) {
       if (writer) idx[A.seg_sink + i] = i;
-      to_glist((uint32_t)i, (uint32_t)i);
+      if (kFused) to_glist((uint32_t)i, (uint32_t)i, i == tid ? edge0 : row[i]);
     }
     for (int i = tid; i < hs.n_win; i += NT) {
       if (writer) idx[A.seg_win + i] = hs.mid_hi + i;
-      to_glist((uint32_t)(hs.n_sink + i), (uint32_t)(hs.mid_hi + i));
+      if (kFused) to_glist((uint32_t)(hs.n_sink + i), (uint32_t)(hs.mid_hi + i), i == tid ? edge1 : row[hs.mid_hi + i]);
     }
   } else {
     // phase 2: rebuild the top-k bitmap from the list written in phase 1
@@ -871,27 +887,38 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
                                : nullptr;
   // UF rows of a list at once, without branches: the list entries are read first, then all scores and rows
   // are requested; slots beyond the list read token 0 and get the score -inf (weight exp(-inf - m) = 0).
-  auto load_rows = [&](const uint32_t* list, int j0, int count, int cap, float (&sc)[UF], uint4 (&vv)[UF]) {
+  // (rounds that lie entirely beyond the list are skipped: the test is the same for the whole workgroup)
+  // list_sc: the scores of the listed tokens (LDS), or nullptr: read from the score row
+  auto load_rows = [&](const uint32_t* list, const float* list_sc, int j0, int count, int cap, float (&sc)[UF],
+                       uint4 (&vv)[UF]) {
     int t[UF];
 #pragma unroll
     for (int u = 0; u < UF; ++u) {
       const int j = j0 + u * NG + g_grp;
-      t[u] = j < count ? min((int)list[min(j, cap - 1)], n - 1) : -1;
+      t[u] = -1;
+      sc[u] = -INFINITY;
+      if (j0 + u * NG < count) {
+        t[u] = j < count ? min((int)list[min(j, cap - 1)], n - 1) : -1;
+        if (list_sc) sc[u] = list_sc[min(j, cap - 1)];
+      }
     }
 #pragma unroll
     for (int u = 0; u < UF; ++u) {
-      const int tt = max(t[u], 0);
-      sc[u] = row[tt];
-      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, tt) + g_sub * 8);
-      else vv[u] = load_stream_16(v_head + (uint32_t)tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
+      vv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (j0 + u * NG < count) {
+        const int tt = max(t[u], 0);
+        if (!list_sc) sc[u] = row[tt];
+        if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, tt) + g_sub * 8);
+        else vv[u] = load_stream_16(v_head + (uint32_t)tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
+      }
     }
 #pragma unroll
     for (int u = 0; u < UF; ++u) sc[u] = t[u] >= 0 ? sc[u] : -INFINITY;
   };
   if constexpr (kFused) {
     const int n_f = hs.n_sink + hs.n_win + hs.k;
-    my_nf = n_f > (int)split ? (int)(((uint32_t)n_f - split + smask) >> shift) : 0;
-    my_nf = min(my_nf, A.glist_cap);
+    (void)n_f;
+    my_nf = (int)(g_hi - g_lo);
   }
 
   VATT_STAMP(A.dbg, 32);
@@ -900,7 +927,65 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // ---- I_bs (Algorithm 2, base sample) and the sums over it ----
   int flags = topk_flag;
   double acc_w = 0.0, acc_w2 = 0.0;
-  if (hs.n_s > 0) {
+  // Fused gather, usual case (both first batches at hand, base sample neither the whole residual nor taken as a
+  // complement): the draws of both streams are tested against the top-k set and counted in draw order by ONE
+  // workgroup scan (the lower half of the workgroup holds the base sample's stream, the upper half the final
+  // sample's; the two counts travel in the halves of one word).  The base sample is complete if its first
+  // batch holds b0 accepted draws.  And since the budget is never below b0, the first b0 accepted draws of the
+  // other stream belong to the final sample whatever the budget turns out to be (unless it asks for so much
+  // that the sample is taken as a complement): their V rows are requested now, with those of I_f, and
+  // are in when the budget is known.
+  bool fast_base = false, spec_dyn = false;
+  uint32_t acc_bits = 0, acc_pos = 0, tot1 = 0;
+  const int half = tid >= NT / 2 ? 1 : 0;
+  float dacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // final-sample rows, before the factor n_s / b
+  float ddsum = 0.f;
+  uint4 dv[UF];
+  float ds[UF];
+  int my_spec = 0;
+  if constexpr (kFused) {
+    const uint32_t ns = (uint32_t)hs.n_s, c0 = (uint32_t)hs.b0;
+    if (pair_made && hs.n_s > 0 && c0 < ns && 2u * c0 <= ns) {
+      const DrawBatch& B = half ? spec1 : spec0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (((B.first >> e) & 1u) && !O::test_bit(bm_f, B.tok[e])) acc_bits |= 1u << e;
+      uint32_t total;
+      const uint32_t excl = block_exclusive_scan<NT>((uint32_t)__popc(acc_bits) << (half ? 16 : 0), &total, sm.scan);
+      const uint32_t tot0 = total & 0xffffu;
+      tot1 = total >> 16;
+      acc_pos = half ? excl >> 16 : excl & 0xffffu;
+      fast_base = tot0 >= c0;
+      spec_dyn = fast_base && tot1 >= c0;
+    }
+    if (fast_base) {
+      uint32_t pos = acc_pos;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool a = (acc_bits >> e) & 1u;
+        const bool take = a && pos < (uint32_t)hs.b0;
+        if (!half) {
+          if (take && writer && pos < (uint32_t)A.b0_max) idx[A.seg_base + pos] = (int32_t)spec0.tok[e];
+          const double w = take ? (double)__expf(spec0.sc[e] - m) : 0.0;
+          acc_w += w;
+          acc_w2 += w * w;
+        } else if (spec_dyn && take && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
+          dlist[pos >> shift] = spec1.tok[e];
+          dlist_sc[pos >> shift] = spec1.sc[e];
+        }
+        pos += a ? 1u : 0u;
+      }
+      __syncthreads();
+      VATT_STAMP(A.dbg, 5);
+      load_rows(glist, glist_sc, 0, my_nf, A.glist_cap, fs, fv);
+      if (spec_dyn) {
+        my_spec = hs.b0 > (int)split ? (int)(((uint32_t)hs.b0 - split + smask) >> shift) : 0;
+        my_spec = min(my_spec, A.dlist_cap);
+        load_rows(dlist, dlist_sc, 0, my_spec, A.dlist_cap, ds, dv);
+      }
+    }
+  }
+  if (hs.n_s > 0 && !fast_base) {
     if (A.phase != 2) {
       Emit E0 = emit_to(idx + A.seg_base, (uint32_t)A.b0_max);
       E0.global = writer;
@@ -1007,11 +1092,31 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   }
 
   VATT_STAMP(A.dbg, 7);
-  if constexpr (kFused) {
-    load_rows(glist, 0, my_nf, A.glist_cap, fs, fv);
-  }
   // ---- I_dyn (Algorithm 1, final sample) ----
-  if (bfin > 0) {
+  bool fast_dyn = false;
+  if constexpr (kFused) {
+    if (!fast_base) load_rows(glist, glist_sc, 0, my_nf, A.glist_cap, fs, fv);
+    // the first batch of draws holds the whole final sample, and it is not taken as a complement: its members
+    // are the accepted draws counted above, up to the budget
+    fast_dyn = spec_dyn && (uint32_t)bfin <= tot1 && 2u * (uint32_t)bfin <= (uint32_t)hs.n_s;
+    if (fast_dyn) {
+      uint32_t pos = acc_pos;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool a = (acc_bits >> e) & 1u;
+        if (half && a && pos < (uint32_t)bfin) {
+          if (writer && pos < (uint32_t)A.b_max) idx[A.seg_dyn + pos] = (int32_t)spec1.tok[e];
+          if (pos >= (uint32_t)hs.b0 && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
+            dlist[pos >> shift] = spec1.tok[e];
+            dlist_sc[pos >> shift] = spec1.sc[e];
+          }
+        }
+        pos += a ? 1u : 0u;
+      }
+      __syncthreads();
+    }
+  }
+  if (bfin > 0 && !fast_dyn) {
     Emit E1 = emit_to(idx + A.seg_dyn, (uint32_t)A.b_max);
     E1.global = writer;
     if (kFused) {
@@ -1056,26 +1161,35 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // Fused gather, second part: add the rows of I_f that were requested above, then the rest of I_f (only long
   // lists have one), then this workgroup's share of the final sample with the weight factor n_s / b.
   if constexpr (kFused) {
-    auto add_rows = [&](const float (&sc)[UF], const uint4 (&vv)[UF], float factor) {
+    auto add_rows = [&](float (&acc)[8], float& dsum, const float (&sc)[UF], const uint4 (&vv)[UF]) {
 #pragma unroll
       for (int u = 0; u < UF; ++u) {
-        const float wt = __expf(sc[u] - m) * factor;
-        add_weighted_row(gacc, wt, vv[u]);
-        gdsum += g_sub == 0 ? wt : 0.f;
+        const float wt = __expf(sc[u] - m);
+        add_weighted_row(acc, wt, vv[u]);
+        dsum += g_sub == 0 ? wt : 0.f;
       }
     };
-    add_rows(fs, fv, 1.0f);
+    add_rows(gacc, gdsum, fs, fv);
     for (int j0 = UF * NG; j0 < my_nf; j0 += UF * NG) {
-      load_rows(glist, j0, my_nf, A.glist_cap, fs, fv);
-      add_rows(fs, fv, 1.0f);
+      load_rows(glist, glist_sc, j0, my_nf, A.glist_cap, fs, fv);
+      add_rows(gacc, gdsum, fs, fv);
     }
     int my_nd = bfin > (int)split ? (int)(((uint32_t)bfin - split + smask) >> shift) : 0;
     my_nd = min(my_nd, A.dlist_cap);
-    const float tail_scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
-    for (int j0 = 0; j0 < my_nd; j0 += UF * NG) {
-      load_rows(dlist, j0, my_nd, A.dlist_cap, fs, fv);
-      add_rows(fs, fv, tail_scale);
+    int j_done = 0;  // entries of this workgroup's share of the final sample that are already requested
+    if (fast_dyn) {
+      add_rows(dacc, ddsum, ds, dv);  // (slots beyond the list carry weight 0)
+      j_done = min(UF * NG, my_spec);
+      // rows requested ahead cover the first b0 tokens; what the budget adds comes after them in the list
     }
+    for (int j0 = j_done; j0 < my_nd; j0 += UF * NG) {
+      load_rows(dlist, fast_dyn ? dlist_sc : nullptr, j0, my_nd, A.dlist_cap, ds, dv);
+      add_rows(dacc, ddsum, ds, dv);
+    }
+    const float tail_scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) gacc[c] += tail_scale * dacc[c];
+    gdsum += tail_scale * ddsum;
     VATT_STAMP(A.dbg, 10);
     // lane groups of a wave hold different rows: add them, then the waves through LDS
 #pragma unroll
@@ -1435,7 +1549,7 @@ int fused_dlist_cap(const Plan& pl, int splits) { return pl.b_max / splits + 2; 
 // Dynamic LDS of the selection kernel with the fused gather (512 threads).
 size_t fused_head_lds_bytes(const Plan& pl, int splits) {
   return head_kernel_lds_bytes(pl.p.n_max, kHeadThreads) +
-         ((size_t)fused_glist_cap(pl, splits) + (size_t)fused_dlist_cap(pl, splits)) * sizeof(uint32_t) +
+         ((size_t)fused_glist_cap(pl, splits) + (size_t)fused_dlist_cap(pl, splits)) * (sizeof(uint32_t) + sizeof(float)) +
          (size_t)(kHeadThreads / kWave) * (pl.p.head_dim + 1) * sizeof(float) + 64;
 }
 

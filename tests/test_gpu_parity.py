@@ -582,14 +582,21 @@ def test_fused_gather_matches_the_separate_kernels(case):
     vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, 0)
     apart = _run(sess)
     check_all(wl, apart, label="kernels apart / " + case)
+    tried = 0
     for splits in (1, 2, 4, 8, 16):
-        vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, splits)
+        try:
+            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, splits)
+        except vb.VattError as e:       # the kernel's LDS does not hold a workgroup's share of the lists
+            assert e.status == vb.VATT_E_UNSUPPORTED_SHAPE and splits < 4
+            continue
+        tried += 1
         sess.out_o.fill_(float("nan"))
         sess.out_idx.fill_(-3)
         sess.out_counts.fill_(-3)
         fused = _run(sess)
         _same_results(wl, apart, fused, output_by_norm=True)
         check_all(wl, fused, label="fused, %d workgroups per head / %s" % (splits, case))
+    assert tried >= 3
     # the sampler's first batches made by the selection kernel itself instead of workgroups of the score launch
     vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SCORE_PREWORK, 0)
     own = _run(sess)
