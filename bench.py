@@ -3,10 +3,13 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--no-cpu]
 
-A step is one vatt_decode call: the whole hot path (score pass, chunk top-k, per-head selection / base
-sample / statistics / budget / final sample, gather) for one layer and one batch of synthetic input that
+A step is one vatt_decode call: the whole hot path (score pass, per-head selection / base sample /
+statistics / budget / final sample, gather and merge) for one layer and one batch of synthetic input that
 is already resident in HBM.  Calls cycle through `--buffers` distinct copies of the KV cache so that no
-call finds its K/V in the 256 MB last-level cache.  Prints ONE JSON line.
+call finds its K/V in the 256 MB last-level cache.  Prints ONE JSON line.  The default run times config 2
+(the headline: B = 1, 32K tokens), and adds two sub-objects: `batched` (config 3, B = 16, where the path is
+bound by HBM bandwidth rather than by latency) and `adaptive_budget` (config 2 with a 32-token base sample,
+where the budget rule sets the sample sizes).
 --config 5 is the ragged paged decode loop (B=32, one appended token per sequence and step): it reports the step
 latency distribution and the budgets of the last step instead of the roofline of the score kernel.
 """
@@ -31,6 +34,11 @@ SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32827.5 * 262144.0 / 131084.4 + 46
                               "config3": int((524827.5 * 262144.0 / 131084.4 + 73728.0) * 1024)}
 # score_chunk_kernel, same two counters and scaling (config 2 with 4 query tokens)
 SCORE_CHUNK_TRAFFIC_BYTES = {("config2", 4): int((32928.6 * 262144.0 / 131084.4 + 18432.7) * 1024)}
+# HBM bytes of all kernels of one vatt_decode step, same two counters and scaling (profiles/decode_step_hbm_traffic.md)
+STEP_TRAFFIC_BYTES = {}
+# rocprofv3 --kernel-trace --stats averages (us) of the kernels of one step, `python3 bench.py --no-cpu` under the
+# profiler (profiles/decode_config2_kernel_stats.md, profiles/decode_config3_kernel_stats.md)
+PROFILE_KERNEL_US = {}
 LLAMA8B_LAYERS = 32
 
 
@@ -85,6 +93,91 @@ def cpu_baseline(wl, budget_s=12.0):
     return dict(value=us_per_layer, unit="us/layer", cores=1, kind="oracle",
                 sample="%d (sequence, head) units of the same workload in %.1f s, scaled to the %d units of one layer"
                        % (done, el, total_heads))
+
+
+def _cpu_worker(job):
+    """One worker of the all-core oracle timing: whole heads of the workload, round robin, for budget_s."""
+    config, rank, world, budget_s = job
+    import numpy as np
+    import workloads
+    from oracle import vatt_oracle as vo
+    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[config]()
+    g = wl.n_q_heads // wl.n_kv_heads
+    q_all = wl.q_f32()
+    total = wl.batch * wl.n_q_heads
+    t0 = time.perf_counter()
+    done, unit = 0, rank
+    while True:
+        b, h = divmod(unit % total, wl.n_q_heads)
+        n = int(wl.seq_lens[b])
+        vo.decode_head(q_all[b, h].astype(np.float64), wl.k_f32(b, h // g, n).astype(np.float64),
+                       wl.v_f32(b, h // g, n).astype(np.float64), seed=int(wl.seeds[b]), head=h, params=wl.params)
+        done += 1
+        unit += world
+        el = time.perf_counter() - t0
+        if el >= budget_s:
+            return done, el
+
+
+def cpu_baseline_all_cores(config, budget_s=8.0):
+    """The same oracle in one process per host core the job may use (fresh processes that never touch the GPU),
+    each on whole heads for about budget_s; the aggregate rate scaled to one layer."""
+    import multiprocessing as mp
+    import workloads
+    cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16"))))
+    if config != 2:
+        cores = min(cores, 4)       # (every worker generates the workload for itself: bound the host memory)
+    keep = {k: os.environ.get(k) for k in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS")}
+    try:
+        for k in keep:
+            os.environ[k] = "1"
+        with mp.get_context("spawn").Pool(cores) as pool:
+            res = pool.map(_cpu_worker, [(config, r, cores, budget_s) for r in range(cores)])
+    finally:
+        for k, v in keep.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    wl_heads = {2: 32, 3: 512, 4: 128}[config]
+    rate = sum(d / el for d, el in res)          # heads per second over all workers
+    return dict(value=wl_heads / rate * 1e6, unit="us/layer", cores=cores,
+                sample="%d (sequence, head) units in %d processes of about %.0f s each" % (sum(d for d, _ in res), cores, budget_s))
+
+
+def measure_adaptive(args, torch, np, workloads, DecodeSession):
+    """Config 2's tensors with a base sample of 32 tokens per head and epsilon = 0.02: the budget rule of
+    Algorithm 2, not the lower cap, then sets the size of the final sample on most heads (final samples of a
+    few hundred to a few thousand tokens, several batches of draws, more gathered V rows)."""
+    wl = workloads.config2()
+    pp = plan_params(wl)
+    pp.update(base_abs=32, base_frac=0.0, epsilon=0.02)
+    sess = DecodeSession(pp)
+    sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    nbuf = 16
+    ks = [sess.k] + [sess.k.clone() for _ in range(nbuf - 1)]
+    vs = [sess.v] + [sess.v.clone() for _ in range(nbuf - 1)]
+
+    def step(i):
+        sess.decode(k=ks[i % nbuf], v=vs[i % nbuf])
+
+    for i in range(args.warmup):
+        step(i)
+    ms = time_calls(step, args.steps, torch)
+    res = sess.results_host()
+    counts = res["counts"].reshape(-1, 8).astype(np.int64)
+    b_star = res["b_star"].reshape(-1)
+    b_dyn = counts[:, 4]
+    out = {"workload": wl.name + " with base_abs = 32, epsilon = 0.02", "us_per_layer": ms * 1e3,
+           "heads_above_base": int((b_dyn > counts[:, 3]).sum()), "heads": int(b_dyn.size),
+           "budget_b": {"min": int(b_dyn.min()), "p50": float(np.percentile(b_dyn, 50)),
+                        "p90": float(np.percentile(b_dyn, 90)), "max": int(b_dyn.max())},
+           "b_star": {"p50": float(np.percentile(b_star, 50)), "p90": float(np.percentile(b_star, 90)),
+                      "max": float(b_star.max())}}
+    sess.close()
+    del ks, vs, sess
+    torch.cuda.empty_cache()
+    return out
 
 
 def decode_loop(args, torch, np, workloads, DecodeSession):
@@ -262,49 +355,12 @@ def chunk_bench(args, torch, np, workloads, DecodeSession):
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
-    ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--given-topk", action="store_true",
-                    help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
-                         "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
-    ap.add_argument("--nested", action="store_true",
-                    help="nested samples (an option beyond the paper): the final sample keeps the base sample")
-    ap.add_argument("--budget-multiple", type=int, default=1,
-                    help="round every budget up to a multiple of this (an option beyond the paper; 1 = the paper's rule)")
-    ap.add_argument("--score-order", default="plan", choices=["plan", "tile", "kvhead", "blocks"],
-                    help="launch order of the score pass (VATT_OPT_SCORE_ORDER): the plan's choice, tile-major, "
-                         "KV-head-major, or tile-major in blocks of 256 KiB; results are identical")
-    ap.add_argument("--q-len", type=int, default=1,
-                    help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (the step shards by sequence and "
-              "KV head without communication). Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-    import workloads
-    from paper_2510_05688_amd.session import DecodeSession
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU (no CPU path exists for the product)", file=sys.stderr)
-        sys.exit(2)
-
-    if args.config == 5:
-        decode_loop(args, torch, np, workloads, DecodeSession)
-        return
-    if args.q_len > 1:
-        chunk_bench(args, torch, np, workloads, DecodeSession)
-        return
-    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
+def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
+    """Times vatt_decode, vatt_score, vatt_dense_decode and the read-only kernel on one configuration and
+    returns the result object (the headline line for `headline`, else a sub-object with fewer steps)."""
+    steps = args.steps if headline else max(20, min(args.steps, 60))
+    warmup = args.warmup if headline else max(5, min(args.warmup, 10))
+    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[config]()
     sess = DecodeSession(plan_params(wl))
     if args.budget_multiple != 1:
         from paper_2510_05688_amd import binding as vb_
@@ -353,23 +409,23 @@ def main():
                                                torch.cuda.current_stream().cuda_stream)
         fn = dict(decode=step, score=score_only, dense=dense, read=read0,
                   copy=lambda i: dsts[i % 4].copy_(src) if args.only == "copy" else None)[args.only]
-        for i in range(args.warmup):
+        for i in range(warmup):
             fn(i)
-        ms = time_calls(fn, args.steps, torch)
-        print(json.dumps({"only": args.only, "ms_per_call": ms, "steps": args.steps}))
-        return
+        ms = time_calls(fn, steps, torch)
+        print(json.dumps({"only": args.only, "ms_per_call": ms, "steps": steps}))
+        return None
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t_wall = time.perf_counter()
-    ms_step = time_calls(step, args.steps, torch)
+    ms_step = time_calls(step, steps, torch)
     t_wall = time.perf_counter() - t_wall
     res = sess.results_host()
     counts = res["counts"].reshape(-1, 8).astype(np.int64)
     # spread of single calls: a second pass with an event after every call (the events cost a little, so the
     # headline figure above comes from the undisturbed loop)
-    n_spread = min(args.steps, 200)
+    n_spread = min(steps, 200)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
     torch.cuda.synchronize()
     marks[0].record()
@@ -379,12 +435,12 @@ def main():
     torch.cuda.synchronize()
     per_call = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(n_spread)]) * 1e3
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         score_only(i)
-    ms_score = time_calls(score_only, args.steps, torch)
-    for i in range(args.warmup):
+    ms_score = time_calls(score_only, steps, torch)
+    for i in range(warmup):
         dense(i)
-    ms_dense = time_calls(dense, args.steps, torch)
+    ms_dense = time_calls(dense, steps, torch)
     # what a kernel that only reads takes for the bytes of the K scan, on the same cycled buffers
     from paper_2510_05688_amd import binding as vb2
     sink = torch.zeros(4096, dtype=torch.uint8, device="cuda")
@@ -393,9 +449,9 @@ def main():
     def read_only(i):
         vb2.vatt_stream_read(ks[i % nbuf], k_bytes_all, sink, torch.cuda.current_stream().cuda_stream)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         read_only(i)
-    ms_read = time_calls(read_only, args.steps, torch)
+    ms_read = time_calls(read_only, steps, torch)
 
     # algorithmic bytes of one layer, from the returned counts
     n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
@@ -427,8 +483,8 @@ def main():
         "value": us_layer,
         "unit": "us",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_step,
         "higher_is_better": False,
         "scaling": "weak",
@@ -454,23 +510,106 @@ def main():
         "step_latency_us": {"p10": float(np.percentile(per_call, 10)), "p50": float(np.percentile(per_call, 50)),
                             "p90": float(np.percentile(per_call, 90)), "calls": int(n_spread),
                             "note": "one event per call; the events add two to three microseconds per call"},
+        # The roofline of the target's quantity: the whole score-plus-gather path (every kernel of one step),
+        # algorithmic bytes from the returned counts over the step time; `kernels` splits it.  The score kernel
+        # is timed live (vatt_score launches back to back on the same cycled buffers); the rest of the step is
+        # the difference; `profile_us` are the rocprofv3 averages kept under profiles/ for the same command.
         "roofline": {
-            "kernel": "score_kernel (K scan, shared across the GQA group)",
+            "scope": "one vatt_decode step: score kernel, selection (with the gather fused in at small batch), gather, merge",
             "bound": "hbm",
-            "achieved": score_kernel_bytes / (ms_score * 1e-3) / 1e9,
+            "achieved": path_bytes / (ms_step * 1e-3) / 1e9,
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
-            "frac": score_kernel_bytes / (ms_score * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get("config%d" % args.config),
-            "bytes_per_launch": score_kernel_bytes,
-            "us_per_launch": ms_score * 1e3,
-            # a kernel that only reads the K cache (vatt_stream_read), same buffers: the practical floor
-            "read_only_same_k_us": ms_read * 1e3,
-            "read_only_gbps": k_bytes_all / (ms_read * 1e-3) / 1e9,
+            "frac": path_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "traffic": STEP_TRAFFIC_BYTES.get("config%d" % config),
+            "bytes_per_step": path_bytes,
+            "us_per_step": us_layer,
+            "kernels": [
+                {"name": "score_kernel (K scan, q.K for the GQA group; the dominant kernel)",
+                 "us": ms_score * 1e3, "us_source": "HIP events on the launch stream, vatt_score back to back",
+                 "bytes": score_kernel_bytes,
+                 "achieved": score_kernel_bytes / (ms_score * 1e-3) / 1e9,
+                 "frac": score_kernel_bytes / (ms_score * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                 "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get("config%d" % config),
+                 # a kernel that only reads the K cache (vatt_stream_read), same buffers: the practical floor
+                 "read_only_same_k_us": ms_read * 1e3,
+                 "read_only_gbps": k_bytes_all / (ms_read * 1e-3) / 1e9},
+                {"name": "selection, gather and merge kernels (the rest of the step)",
+                 "us": (ms_step - ms_score) * 1e3, "us_source": "step time minus the score kernel's",
+                 "bytes": path_bytes - score_kernel_bytes,
+                 "achieved": (path_bytes - score_kernel_bytes) / max((ms_step - ms_score) * 1e-3, 1e-9) / 1e9,
+                 "frac": (path_bytes - score_kernel_bytes) / max((ms_step - ms_score) * 1e-3, 1e-9) / 1e9 / HBM_PEAK_GBPS},
+            ],
+            "profile_us": PROFILE_KERNEL_US.get("config%d" % config),
         },
     }
+    sess.close()
+    del ks, vs, sess
+    torch.cuda.empty_cache()
+    return out
+
+
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5])
+    ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="config 2 only: skip the batched (config 3) and adaptive-budget legs of the default run")
+    ap.add_argument("--given-topk", action="store_true",
+                    help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
+                         "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
+    ap.add_argument("--nested", action="store_true",
+                    help="nested samples (an option beyond the paper): the final sample keeps the base sample")
+    ap.add_argument("--budget-multiple", type=int, default=1,
+                    help="round every budget up to a multiple of this (an option beyond the paper; 1 = the paper's rule)")
+    ap.add_argument("--score-order", default="plan", choices=["plan", "tile", "kvhead", "blocks"],
+                    help="launch order of the score pass (VATT_OPT_SCORE_ORDER): the plan's choice, tile-major, "
+                         "KV-head-major, or tile-major in blocks of 256 KiB; results are identical")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the step shards by sequence and "
+              "KV head without communication). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    from paper_2510_05688_amd.session import DecodeSession
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU path exists for the product)", file=sys.stderr)
+        sys.exit(2)
+
+    if args.config == 5:
+        decode_loop(args, torch, np, workloads, DecodeSession)
+        return
+    if args.q_len > 1:
+        chunk_bench(args, torch, np, workloads, DecodeSession)
+        return
+    out = measure_config(args.config, args, torch, np, workloads, DecodeSession, headline=True)
+    if args.only:
+        return
+    if args.config == 2 and not args.given_topk and not args.nested and args.budget_multiple == 1 and not args.no_extra:
+        # the same step where the budget rule, not the lower cap, sets the sample size on most heads
+        out["adaptive_budget"] = measure_adaptive(args, torch, np, workloads, DecodeSession)
+        # the batched configuration (config 3, B = 16), where the path is bound by HBM rather than by latency
+        b3 = measure_config(3, args, torch, np, workloads, DecodeSession, headline=False)
+        out["batched"] = {k: b3[k] for k in ("config", "value", "unit", "ms_per_step", "steps", "tokens_per_s_attention_only",
+                                              "path_bytes", "dense_decode_us_per_layer", "speedup_vs_dense",
+                                              "token_density", "budget_b", "roofline")}
     if not args.no_cpu:
+        wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
         out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"]["all_cores"] = cpu_baseline_all_cores(args.config)
     print(json.dumps(out))
 
 
