@@ -351,6 +351,53 @@ struct TopkOps {
 };
 
 
+// ---------------------------------------------------------------------------
+// Algorithm 2 from the sums over I_f and the base sample (shared by the scored path and the path with a
+// caller-supplied top-k set): unbiased variance, D^, rho_D = n_s sigma / D^; the numerator's
+// rho_N = n_s sqrt(Tr Sigma) / ||N^|| from its own sums; b* of the target (Corollaries for D and N, Theorem 4.3
+// with delta' = delta / 2); then b = min(n_s, max(b0, min(ceil(b*), ceil(cap n_s)))), optionally rounded up to
+// a multiple.  Everything in double; every thread of the workgroup computes the same values.
+// ---------------------------------------------------------------------------
+struct Budget {
+  double sigma2, D_hat, b_star;
+  int b;
+};
+__device__ __forceinline__ double numerator_rho(int n_s, int b0, double sum_r_sq, double sum_r2, double nhat_sq,
+                                                double* tr_sigma) {
+  const double b0d = (double)b0, ns = (double)n_s;
+  *tr_sigma = b0 > 1 ? fmax(sum_r2 - sum_r_sq / b0d, 0.0) / (b0d - 1.0) : 0.0;
+  const double num = ns * sqrt(*tr_sigma), nn = sqrt(nhat_sq);
+  return nn > 0.0 ? num / nn : (num > 0.0 ? INFINITY : 0.0);
+}
+__device__ __forceinline__ Budget algorithm2_budget(const HeadArgs& A, int n_s, int b0, double D_f, double sum_w,
+                                                    double sum_w2, double rho_N) {
+  Budget B;
+  const double b0d = (double)b0, ns = (double)n_s;
+  const double w_bar = sum_w / b0d;
+  // unbiased variance from the two sums; the scores are shifted so that the largest weight is 1
+  B.sigma2 = b0 > 1 ? fmax(sum_w2 - sum_w * w_bar, 0.0) / (b0d - 1.0) : 0.0;
+  B.D_hat = D_f + ns * w_bar;
+  const double rho_D = ns * sqrt(B.sigma2) / B.D_hat;
+  if (A.target == VATT_TARGET_D) {
+    const double t = A.z_half * rho_D / A.eps;
+    B.b_star = t * t;
+  } else if (A.target == VATT_TARGET_N) {
+    const double t = A.z_half * rho_N / A.eps;
+    B.b_star = t * t;
+  } else {
+    const double t = 2.0 * A.z_quarter * (rho_D + rho_N) / A.eps;
+    B.b_star = t * t;
+  }
+  const int cap = (int)ceil(A.cap_frac * ns);
+  int want = n_s;
+  if (B.b_star == B.b_star && B.b_star < ns) want = (int)ceil(B.b_star);
+  int b = min(n_s, max(b0, min(want, cap)));
+  // (optional) rounded up to a multiple, not beyond the largest value the rule above can give
+  if (A.b_multiple > 1) b = min(min(n_s, max(b0, cap)), (b + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
+  B.b = min(b, A.b_max);
+  return B;
+}
+
 // Accumulates weight * (8 bf16 values of a V row) into acc.
 __device__ __forceinline__ void add_weighted_row(float (&acc)[8], float wt, const uint4& vv) {
   const uint32_t ww[4] = {vv.x, vv.y, vv.z, vv.w};
@@ -1027,13 +1074,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   double sigma2 = 0.0, b_star = 0.0, tr_sigma = 0.0, nhat_sq = 0.0;
   int bfin = 0;
   if (hs.n_s > 0) {
-    const double b0d = (double)hs.b0;
-    const double w_bar = sums[1] / b0d;
-    // unbiased variance from the two sums; the scores are shifted so that the largest weight is 1
-    sigma2 = hs.b0 > 1 ? fmax(sums[2] - sums[1] * w_bar, 0.0) / (b0d - 1.0) : 0.0;
-    const double ns = (double)hs.n_s;
-    const double D_hat = D_f + ns * w_bar;
-    const double rho_D = ns * sqrt(sigma2) / D_hat;
+    const double b0d = (double)hs.b0, ns = (double)hs.n_s;
     double rho_N = 0.0;
     if (A.target != VATT_TARGET_D) {
       // numerator statistics from the V pass: per split {N_f[d], R1[d], R2, pad}
@@ -1055,29 +1096,13 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         for (int s = 0; s < A.vstat_splits; ++s) t3[2] += vp[s * stride + 2 * d];
       O::block_sum(t3, sm);
       nhat_sq = t3[0];
-      tr_sigma = hs.b0 > 1 ? fmax(t3[2] - t3[1] / b0d, 0.0) / (b0d - 1.0) : 0.0;
-      const double num = ns * sqrt(tr_sigma), nn = sqrt(nhat_sq);
-      rho_N = nn > 0.0 ? num / nn : (num > 0.0 ? INFINITY : 0.0);
+      rho_N = numerator_rho(hs.n_s, hs.b0, t3[1], t3[2], nhat_sq, &tr_sigma);
     }
-    if (A.target == VATT_TARGET_D) {
-      const double t = A.z_half * rho_D / A.eps;
-      b_star = t * t;
-    } else if (A.target == VATT_TARGET_N) {
-      const double t = A.z_half * rho_N / A.eps;
-      b_star = t * t;
-    } else {
-      const double t = 2.0 * A.z_quarter * (rho_D + rho_N) / A.eps;
-      b_star = t * t;
-    }
-    // b = min(n_s, max(b0, min(ceil(b*), ceil(cap * n_s))))
-    const int cap = (int)ceil(A.cap_frac * ns);
-    int want = hs.n_s;
-    if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
-    bfin = min(hs.n_s, max(hs.b0, min(want, cap)));
-    // (optional) rounded up to a multiple, not beyond the largest value the rule above can give
-    if (A.b_multiple > 1)
-      bfin = min(min(hs.n_s, max(hs.b0, cap)), (bfin + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
-    bfin = min(bfin, A.b_max);
+    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N);
+    sigma2 = bud.sigma2;
+    b_star = bud.b_star;
+    bfin = bud.b;
+    const double D_hat = bud.D_hat;
     if (tid == 0 && writer && A.out_stats) {
       float* st = A.out_stats + (int64_t)bh * 4;
       st[0] = (float)D_hat;
@@ -1404,10 +1429,6 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   int bfin = 0;
   if (hs.n_s > 0) {
     const double b0d = (double)hs.b0, ns = (double)hs.n_s;
-    const double w_bar = sums[1] / b0d;
-    sigma2 = hs.b0 > 1 ? fmax(sums[2] - sums[1] * w_bar, 0.0) / (b0d - 1.0) : 0.0;
-    D_hat = D_f + ns * w_bar;
-    const double rho_D = ns * sqrt(sigma2) / D_hat;
     double rho_N = 0.0;
     if (A.target != VATT_TARGET_D) {
       // numerator statistics left by the score kernel of the listed tokens, one partial per split, each in
@@ -1437,28 +1458,13 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       }
       O::block_sum(t3, sm);
       nhat_sq = t3[0];
-      tr_sigma = hs.b0 > 1 ? fmax(t3[2] - t3[1] / b0d, 0.0) / (b0d - 1.0) : 0.0;
-      const double num = ns * sqrt(tr_sigma), nn = sqrt(nhat_sq);
-      rho_N = nn > 0.0 ? num / nn : (num > 0.0 ? INFINITY : 0.0);
+      rho_N = numerator_rho(hs.n_s, hs.b0, t3[1], t3[2], nhat_sq, &tr_sigma);
     }
-    if (A.target == VATT_TARGET_D) {
-      const double t = A.z_half * rho_D / A.eps;
-      b_star = t * t;
-    } else if (A.target == VATT_TARGET_N) {
-      const double t = A.z_half * rho_N / A.eps;
-      b_star = t * t;
-    } else {
-      const double t = 2.0 * A.z_quarter * (rho_D + rho_N) / A.eps;
-      b_star = t * t;
-    }
-    const int cap = (int)ceil(A.cap_frac * ns);
-    int want = hs.n_s;
-    if (b_star == b_star && b_star < ns) want = (int)ceil(b_star);
-    bfin = min(hs.n_s, max(hs.b0, min(want, cap)));
-    // (optional) rounded up to a multiple, not beyond the largest value the rule above can give
-    if (A.b_multiple > 1)
-      bfin = min(min(hs.n_s, max(hs.b0, cap)), (bfin + A.b_multiple - 1) / A.b_multiple * A.b_multiple);
-    bfin = min(bfin, A.b_max);
+    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N);
+    sigma2 = bud.sigma2;
+    b_star = bud.b_star;
+    bfin = bud.b;
+    D_hat = bud.D_hat;
   }
   int flags = 0;
   if (bfin > 0) {
