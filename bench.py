@@ -372,6 +372,9 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     if args.nested:
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_NESTED_SAMPLES, 1)
+    if args.ascending:
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_ASCENDING_SAMPLES, 1)
     sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
     B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
     kv_bytes = 2 * B * Hkv * n * d * 2
@@ -478,7 +481,7 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     us_layer = ms_step * 1e3
     out = {
         "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else "")
-                  + ("_nested_samples" if args.nested else "")
+                  + ("_nested_samples" if args.nested else "") + ("_ascending_samples" if args.ascending else "")
                   + ("_budget_multiple_%d" % args.budget_multiple if args.budget_multiple != 1 else ""),
         "value": us_layer,
         "unit": "us",
@@ -564,6 +567,8 @@ def main():
     ap.add_argument("--given-topk", action="store_true",
                     help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
+    ap.add_argument("--ascending", action="store_true",
+                    help="sample lists in ascending token order (VATT_OPT_ASCENDING_SAMPLES)")
     ap.add_argument("--nested", action="store_true",
                     help="nested samples (an option beyond the paper): the final sample keeps the base sample")
     ap.add_argument("--budget-multiple", type=int, default=1,
@@ -598,7 +603,8 @@ def main():
     out = measure_config(args.config, args, torch, np, workloads, DecodeSession, headline=True)
     if args.only:
         return
-    if args.config == 2 and not args.given_topk and not args.nested and args.budget_multiple == 1 and not args.no_extra:
+    if (args.config == 2 and not args.given_topk and not args.nested and not args.ascending
+            and args.budget_multiple == 1 and not args.no_extra):
         # the same step where the budget rule, not the lower cap, sets the sample size on most heads
         out["adaptive_budget"] = measure_adaptive(args, torch, np, workloads, DecodeSession)
         # the batched configuration (config 3, B = 16), where the path is bound by HBM rather than by latency

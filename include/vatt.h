@@ -145,7 +145,14 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * algorithm.  (include/vatt_testing.h declares further option numbers that only change how the same results
  * are computed; they exist for the test suite.)
  */
-enum { VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_BUDGET_MULTIPLE = 7 };
+enum { VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_BUDGET_MULTIPLE = 7,
+       VATT_OPT_ASCENDING_SAMPLES = 12 };
+/*
+ * VATT_OPT_ASCENDING_SAMPLES = 1: the base and final samples' segments of out_idx are written in ascending token
+ * order (they are the same sets; by default they come in the order in which the sampler accepted the tokens).
+ * The gather then walks every head's rows in address order.  Plans with this option keep selection and gather
+ * in kernels of their own.
+ */
 /*
  * VATT_OPT_BUDGET_MULTIPLE = q (1 .. 65536; 1, the default, is Algorithm 2's rule): the budget b is rounded up
  * to the next multiple of q, e.g. 16, the V rows one wave of the gather reads per instruction at d = 128, or 64.

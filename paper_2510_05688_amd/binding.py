@@ -34,6 +34,7 @@ VATT_OPT_BUDGET_MULTIPLE = 7
 VATT_OPT_SCORE_ORDER = 8
 VATT_OPT_FUSED_GATHER = 9
 VATT_OPT_SCORE_PREWORK = 10
+VATT_OPT_ASCENDING_SAMPLES = 12
 VATT_BOUND_CLT = 0
 VATT_BOUND_HOEFFDING = 1
 

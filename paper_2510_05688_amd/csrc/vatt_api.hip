@@ -94,6 +94,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.sampler_draw_cap = 0;
   pl.nested_samples = 0;
   pl.budget_multiple = 1;
+  pl.ascending_samples = 0;
 
   // Workgroups go to the eight XCDs round-robin in launch order.  With a multiple of 8 KV heads the selection,
   // gather and merge kernels launch the query heads of a KV head on one XCD (they read the same sink, window and
@@ -324,6 +325,10 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     plan->pl.fuse_splits = value;
     return VATT_OK;
   }
+  if (option == VATT_OPT_ASCENDING_SAMPLES) {
+    plan->pl.ascending_samples = value ? 1 : 0;
+    return VATT_OK;
+  }
   if (option == VATT_OPT_NESTED_SAMPLES) {
     plan->pl.nested_samples = value ? 1 : 0;
     return VATT_OK;
@@ -396,7 +401,7 @@ int vatt_decode(vatt_plan* plan, const void* q, const void* k, const void* v, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
   const Plan& pl = plan->pl;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool fused = pl.p.target == VATT_TARGET_D && pl.fuse_splits > 0 && !pl.nested_samples;
+  const bool fused = pl.p.target == VATT_TARGET_D && pl.fuse_splits > 0 && !pl.nested_samples && !pl.ascending_samples;
   if (pl.q_len > 1)
     VATT_LAUNCH(launch_score_chunk(pl, q, k, block_table, seq_lens, workspace, st));
   else

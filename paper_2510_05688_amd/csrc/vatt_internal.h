@@ -57,6 +57,7 @@ struct Plan {
   int group_major;                // the later kernels launch the query heads of a KV head on one XCD (head_of_block)
   int score_order;                // launch order of the score pass (kScoreOrder*)
   int nested_samples;             // the final sample keeps the base sample and extends it (not the paper's fresh draw)
+  int ascending_samples;          // the samples' index lists are written in ascending token order
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
   int prework;                    // the sampler streams' first batches are made by workgroups of the score launch
   int fuse_splits;                // > 0: the selection kernel also gathers, with this many workgroups per head
@@ -87,7 +88,7 @@ hipError_t launch_head_fused(const Plan& pl, const void* v, const int32_t* block
 // Whether workgroups of the score launch make the sampler streams' first batches for the fused selection kernel
 // (single-token steps in the KV-head-major launch order only).
 inline bool score_prework(const Plan& pl) {
-  return pl.prework && pl.fuse_splits > 0 && !pl.nested_samples && pl.q_len == 1 &&
+  return pl.prework && pl.fuse_splits > 0 && !pl.nested_samples && !pl.ascending_samples && pl.q_len == 1 &&
          pl.p.target == VATT_TARGET_D && pl.score_order == kScoreOrderKvHead;
 }
 hipError_t launch_gather_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st);

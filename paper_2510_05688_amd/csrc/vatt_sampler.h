@@ -396,6 +396,32 @@ struct HeadOps {
     return flags;
   }
 
+  // Rewrites a token list this workgroup wrote at dst (count distinct tokens below n) in ascending order:
+  // the tokens are marked in the all-zero bitmap `scratch`, counted by bitmap word, and written back by
+  // position; `scratch` is left all zero.  (An option of the plans: rows gathered in ascending order.)
+  static __device__ void sort_ascending(int32_t* dst, uint32_t count, uint32_t* scratch, uint32_t* wpre, int n,
+                                        HeadSmem& sm) {
+    const int tid = threadIdx.x;
+    const int words = (n + 31) >> 5;
+    __syncthreads();  // the list is complete (global memory is coherent inside a workgroup)
+    for (uint32_t t = tid; t < count; t += NT) mark_bit(scratch, (uint32_t)list_tok(dst, t, n));
+    __syncthreads();
+    word_prefix(scratch, words, wpre, sm);
+    for (int w = tid; w < words; w += NT) {
+      uint32_t bits = scratch[w];
+      uint32_t pos = wpre[w];
+      while (bits) {
+        const int i = (w << 5) + (__ffs(bits) - 1);
+        bits &= bits - 1u;
+        if (pos < count) dst[pos] = i;
+        ++pos;
+      }
+    }
+    __syncthreads();
+    for (int w = tid; w < words; w += NT) scratch[w] = 0;
+    __syncthreads();
+  }
+
   // Nested final sample (an option; Algorithm 1 draws the final sample afresh): the base sample, whose list
   // of b0 tokens this workgroup wrote at `base`, is kept as the head of the final sample, and the remaining
   // c - b0 tokens are drawn with the stream of S among the residual tokens outside the base sample.  The base

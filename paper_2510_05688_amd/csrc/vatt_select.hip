@@ -55,6 +55,7 @@ struct HeadArgs {
   int group_major, Hkv;  // see head_of_block
   int nested; // the final sample keeps the base sample and adds b - b0 tokens drawn outside it
   int b_multiple;  // b is rounded up to a multiple of this (1: the paper's rule)
+  int ascending;   // the two samples' lists are written in ascending token order (else in acceptance order)
   uint32_t draw_cap;  // 0: the default 64 L + 4096
   unsigned long long* dbg;
   // fused gather (head_kernel with FD > 0): every head has `splits` workgroups, each of which repeats the
@@ -1038,6 +1039,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       E0.global = writer;
       const int f = O::draw_sample(S0, hs, (uint32_t)hs.b0, spec0, want0, A.small_batches, E0, &acc_w, &acc_w2, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+      if (A.ascending && !(f & 1))
+        O::sort_ascending(idx + A.seg_base, (uint32_t)min(hs.b0, A.b0_max), scratch, wpre, n, sm);
       VATT_STAMP(A.dbg, 5);
     } else {
       for (int t = tid; t < hs.b0; t += NT) {
@@ -1155,6 +1158,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
                                        idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
                       : O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches, E1, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+    if (!kFused && A.ascending && !A.nested && !(f & 1))
+      O::sort_ascending(idx + A.seg_dyn, (uint32_t)min(bfin, A.b_max), scratch, wpre, n, sm);
     VATT_STAMP(A.dbg, 8);
   }
   if (tid == 0 && writer) {
@@ -1354,6 +1359,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches,
                                    emit_to(idx + A.seg_base, (uint32_t)A.b0_max), nullptr, nullptr, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+      if (A.ascending && !(f & 1))
+        O::sort_ascending(idx + A.seg_base, (uint32_t)min(hs.b0, A.b0_max), scratch, wpre, n, sm);
     }
     if (tid == 0) {
       HeadRec r;
@@ -1473,6 +1480,8 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
                            : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches,
                                             emit_to(idx + A.seg_dyn, (uint32_t)A.b_max), nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+    if (A.ascending && !A.nested && !(f & 1))
+      O::sort_ascending(idx + A.seg_dyn, (uint32_t)min(bfin, A.b_max), scratch, wpre, n, sm);
   }
   if (tid == 0) {
     int32_t* c = A.out_counts + (int64_t)bh * 8;
@@ -1675,6 +1684,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.group_major = pl.group_major;
   A.Hkv = p.n_kv_heads;
   A.b_multiple = pl.budget_multiple;
+  A.ascending = pl.ascending_samples;
   A.dbg = reinterpret_cast<unsigned long long*>(w + pl.off_debug) + 64;
   A.given_idx = nullptr;
   A.given_cnt = nullptr;

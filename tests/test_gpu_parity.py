@@ -607,6 +607,33 @@ def test_fused_gather_matches_the_separate_kernels(case):
     sess.close()
 
 
+@pytest.mark.parametrize("target", [0, 2])
+def test_sample_lists_in_ascending_order(target):
+    say("samples written in ascending token order, target %d" % target)
+    from paper_2510_05688_amd import binding as vb
+    wl = workloads.small_gqa(seed=91, batch=2, n=6000, seq_lens=[6000, 911], epsilon=0.02 if target == 0 else 0.3,
+                             target=target)
+    sess = _session(wl)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, 0)
+    plain = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_ASCENDING_SAMPLES, 1)
+    asc = _run(sess)
+    seg = asc["seg"]
+    assert np.array_equal(plain["counts"][..., :7], asc["counts"][..., :7])
+    some_unsorted = False
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            c = asc["counts"][b, h]
+            for s_, cnt in ((3, c[3]), (4, c[4])):
+                a, p_ = asc["idx"][b, h, seg[s_]:seg[s_] + cnt], plain["idx"][b, h, seg[s_]:seg[s_] + cnt]
+                assert np.all(np.diff(a) > 0) and np.array_equal(a, np.sort(p_))
+                some_unsorted |= bool(np.any(np.diff(p_) < 0))
+    assert some_unsorted      # (the default order is the sampler's acceptance order)
+    _same_results(wl, plain, asc, output_by_norm=True)
+    check_all(wl, asc, label="ascending samples, target %d" % target)
+    sess.close()
+
+
 def test_lengths_outside_the_cache_are_clamped():
     # seq_lens outside [1, n_max] are clamped by every kernel alike: 0 becomes one token, too large becomes n_max
     wl = workloads.small_gqa(seed=81, batch=3, n=2048, seq_lens=[2048, 1, 2048])
