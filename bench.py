@@ -401,6 +401,31 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     def dense(i):
         sess.dense(k=ks[i % nbuf], v=vs[i % nbuf])
 
+    if args.graph_steps > 0:
+        # the same launches captured in HIP graphs of `graph_steps` consecutive steps each (one graph per group
+        # of KV buffers, since a graph fixes its pointers) and replayed
+        per = args.graph_steps
+        n_graphs = max(1, nbuf // per)
+        side = torch.cuda.Stream()
+        graphs = []
+        for j in range(n_graphs):
+            side.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    for u in range(per):
+                        step(j * per + u)
+            torch.cuda.current_stream().wait_stream(side)
+            graphs.append(g)
+        for i in range(warmup):
+            step(i)
+        ms_plain = time_calls(step, steps, torch)
+        for i in range(max(2, warmup // per)):
+            graphs[i % n_graphs].replay()
+        ms_graph = time_calls(lambda i: graphs[i % n_graphs].replay(), max(4, steps // per), torch) / per
+        print(json.dumps({"only": "graph", "steps_per_graph": per, "plain_us_per_step": ms_plain * 1e3,
+                          "graph_us_per_step": ms_graph * 1e3, "steps": steps}))
+        return None
     if args.only:
         if args.only == "copy":
             # plain device copy of known size: calibrates the HBM byte counters of the profiler
@@ -578,6 +603,8 @@ def main():
                          "KV-head-major, or tile-major in blocks of 256 KiB; results are identical")
     ap.add_argument("--q-len", type=int, default=1,
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
+    ap.add_argument("--graph-steps", type=int, default=0,
+                    help="time plain launches against replays of HIP graphs that hold this many steps each")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -601,7 +628,7 @@ def main():
         chunk_bench(args, torch, np, workloads, DecodeSession)
         return
     out = measure_config(args.config, args, torch, np, workloads, DecodeSession, headline=True)
-    if args.only:
+    if args.only or out is None:
         return
     if (args.config == 2 and not args.given_topk and not args.nested and not args.ascending
             and args.budget_multiple == 1 and not args.no_extra):
