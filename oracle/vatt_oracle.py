@@ -390,8 +390,12 @@ def estimate(s: np.ndarray, V: np.ndarray, m: float, I_f: np.ndarray, I_dyn: np.
 def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head: int,
                 params: Dict[str, float], s: Optional[np.ndarray] = None,
                 forced_topk: Optional[np.ndarray] = None,
-                forced_b: Optional[int] = None, query: int = 0) -> Dict[str, object]:
+                forced_b: Optional[int] = None, query: int = 0,
+                cache_tokens: Optional[Sequence[int]] = None) -> Dict[str, object]:
     """Algorithm 1 for one (sequence, query head).
+
+    cache_tokens: the random cache of the head's (sequence, KV head) in slot order; the base sample is then
+    taken from it (base_sample_from_cache) when it holds enough residual tokens.
 
     q: [d], K, V: [n, d] (values already rounded to the storage precision).
     `s` may carry precomputed scores of the same inputs.  forced_topk /
@@ -427,8 +431,11 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
     b0 = base_count(n_s, int(params.get("base_abs", 0)), float(params.get("base_frac", 0.0)))
     mid_lo, mid_len = int(I_s.shape[0]), n - int(I_s.shape[0]) - int(I_l.shape[0])
     draw_cap = params.get("draw_cap")
-    I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
-                          draw_cap=draw_cap, query=query)
+    I_bs = base_sample_from_cache(cache_tokens, residual, b0) if cache_tokens is not None else None
+    base_from_cache = I_bs is not None
+    if I_bs is None:
+        I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
+                              draw_cap=draw_cap, query=query)
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
     b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target,
                         bound=str(params.get("bound", "clt")))
@@ -449,9 +456,86 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
         I_dyn = uniform_sample(residual, b, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,
                                draw_cap=draw_cap, query=query)
     N, D = estimate(s, V, m, I_f, I_dyn, n_s)
-    res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st,
+    res.update(I_bs=I_bs, I_dyn=I_dyn, b0=b0, b=b, b_star=b_star, stats=st, base_from_cache=base_from_cache,
                O=N / D, lse=m + math.log(D), D_out=D, N_out=N)
     return res
+
+
+# --------------------------------------------------------------------------
+# Random cache of base-sample tokens.  The paper's implementation note after Theorem 4.3 says that the base
+# sample can be served from a small random cache that is populated and updated during generation; it gives
+# no procedure.  Reading taken here: per (sequence, KV head) a cache of C slots holds a uniform random C-subset
+# of the tokens seen so far, in uniformly random slot order, maintained by reservoir sampling as tokens
+# arrive; the base sample of a query head is then the first b0 cached tokens, in slot order, that are
+# residual tokens of that head (not in I_s, I_l, I_t).  A uniform random subset in random order, filtered by
+# a condition that does not depend on the order, yields a uniform b0-subset of the residual.  When the
+# cache holds fewer than b0 residual tokens the base sample is drawn by the sampler as without a cache.
+# --------------------------------------------------------------------------
+CACHE_STREAM = 2
+
+
+def cache_words(t_lo: int, t_hi: int, seed: int, kv_head: int) -> np.ndarray:
+    """Rows t_lo .. t_hi-1: the four words of Philox4x32-10(counter = (t, CACHE_STREAM, kv_head, 0), key = halves of seed)."""
+    t = np.arange(int(t_lo), int(t_hi), dtype=np.uint64) & np.uint64(_MASK32)
+    w = philox4x32_10((t, np.full(t.size, CACHE_STREAM, np.uint64), np.full(t.size, kv_head, np.uint64),
+                       np.full(t.size, 0, np.uint64)),
+                      (int(seed) & _MASK32, (int(seed) >> 32) & _MASK32))
+    return np.stack([np.asarray(x, dtype=np.uint64) for x in w], axis=1)
+
+
+def cache_draw(words4, R: int) -> int:
+    """Uniform integer in [0, R) from the four words of one token's arrival.
+
+    Each word is mapped by the unbiased multiply-and-reject rule; the first accepted one counts, and the
+    fourth is taken whether accepted or not (probability below (R / 2^32)^3 per draw).
+    """
+    ok, val = bounded_draw(np.asarray(words4, dtype=np.uint64), int(R))
+    for a, v in zip(ok, val):
+        if bool(a):
+            return int(v)
+    return int(val[-1])
+
+
+def random_cache_append(slots: List[int], C: int, t: int, seed: int, kv_head: int, words4=None) -> None:
+    """Token t (the t-th token of the sequence, counted from 0) arrives; `slots` is the cache in slot order.
+
+    While the cache is not full, t is inserted at a uniformly random place of the t + 1 entries (the entry
+    that was there moves to the end): the entries stay in uniformly random order.  Once it is full, t
+    replaces slot r when r, uniform in [0, t], falls below C (reservoir sampling: every C-subset of the
+    t + 1 tokens is then equally likely, and the slot order stays exchangeable).
+    """
+    if words4 is None:
+        words4 = cache_words(t, t + 1, seed, kv_head)[0]
+    c = len(slots)
+    if c < C:
+        j = cache_draw(words4, c + 1)
+        if j == c:
+            slots.append(int(t))
+        else:
+            slots.append(slots[j])
+            slots[j] = int(t)
+    else:
+        r = cache_draw(words4, t + 1)
+        if r < C:
+            slots[r] = int(t)
+
+
+def random_cache_fill(n: int, C: int, seed: int, kv_head: int) -> List[int]:
+    """The cache after tokens 0 .. n-1 have arrived one by one."""
+    slots: List[int] = []
+    words = cache_words(0, n, seed, kv_head)
+    for t in range(int(n)):
+        random_cache_append(slots, C, t, seed, kv_head, words[t])
+    return slots
+
+
+def base_sample_from_cache(cache_tokens: Sequence[int], residual: np.ndarray, b0: int) -> Optional[np.ndarray]:
+    """First b0 cached tokens, in slot order, that are residual tokens; None when the cache has fewer."""
+    is_res = set(int(x) for x in residual)
+    got = [int(t) for t in cache_tokens if int(t) in is_res][:int(b0)]
+    if len(got) < int(b0):
+        return None
+    return np.sort(np.asarray(got, dtype=np.int64))
 
 
 # --------------------------------------------------------------------------

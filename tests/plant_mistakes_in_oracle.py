@@ -84,6 +84,17 @@ M = [
  ("nested from whole residual", "rest = np.setdiff1d(residual, I_bs, assume_unique=True)", "rest = residual"),
  ("nested stream 0", "extra = uniform_sample(rest, b - b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,", "extra = uniform_sample(rest, b - b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,"),
  ("nested size b", "extra = uniform_sample(rest, b - b0, mid_lo", "extra = uniform_sample(rest, b, mid_lo"),
+ ("cache replace range t", "r = cache_draw(words4, t + 1)", "r = cache_draw(words4, t)"),
+ ("cache replace always", "        if r < C:\n            slots[r] = int(t)", "        slots[r % C] = int(t)"),
+ ("cache fills in arrival order", "j = cache_draw(words4, c + 1)", "j = c"),
+ ("cache fill swaps wrong range", "j = cache_draw(words4, c + 1)", "j = cache_draw(words4, max(c, 1))"),
+ ("cache kv head dropped", "np.full(t.size, kv_head, np.uint64)", "np.full(t.size, 0, np.uint64)"),
+ ("cache seed low half only", "                      (int(seed) & _MASK32, (int(seed) >> 32) & _MASK32))\n    return np.stack([np.asarray(x", "                      (int(seed) & _MASK32, 0))\n    return np.stack([np.asarray(x"),
+ ("cache token counter dropped", "t = np.arange(int(t_lo), int(t_hi), dtype=np.uint64) & np.uint64(_MASK32)\n    w = philox", "t = np.arange(int(t_lo), int(t_hi), dtype=np.uint64) * np.uint64(0)\n    w = philox"),
+ ("base from cache not filtered", "got = [int(t) for t in cache_tokens if int(t) in is_res][:int(b0)]", "got = [int(t) for t in cache_tokens][:int(b0)]"),
+ ("base from cache lowest tokens", "got = [int(t) for t in cache_tokens if int(t) in is_res][:int(b0)]", "got = sorted(int(t) for t in cache_tokens if int(t) in is_res)[:int(b0)]"),
+ ("base from cache short sample", "    if len(got) < int(b0):\n        return None", "    if len(got) < 1:\n        return None"),
+ ("cache never used", "I_bs = base_sample_from_cache(cache_tokens, residual, b0) if cache_tokens is not None else None", "I_bs = None"),
  ("base sample stream 1", "I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,", "I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,"),
  ("stats over I_dyn scale", "st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))", "st = sample_stats(s, V, m, I_f, I_bs, n_s - 1, need_num=(target != TARGET_D))"),
  ("m over I_f only", "    m = float(s.max())\n    k = topk_count", "    m = float(s[:1].max())\n    k = topk_count"),
@@ -108,7 +119,9 @@ def run(i):
         shutil.copytree(os.path.join(ROOT, sub), os.path.join(d, sub), ignore=shutil.ignore_patterns("__pycache__", "test_gpu_*"))
     open(os.path.join(d, "oracle/vatt_oracle.py"), "w").write(SRC.replace(old, new, 1))
     env = dict(os.environ, PYTHONDONTWRITEBYTECODE="1", OMP_NUM_THREADS="1")
-    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "tests/test_oracle_statistics.py", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider"],
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_oracle_pins.py", "tests/test_oracle_statistics.py", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+                        # that test compares this list with the oracle's text, which the planted mistake has just changed
+                        "--deselect", "tests/test_oracle_pins.py::test_planted_mistakes_list_follows_the_oracle"],
                        cwd=d, env=env, capture_output=True, text=True)
     tail = [l for l in r.stdout.splitlines() if l.startswith("FAILED") or "passed" in l or "failed" in l]
     shutil.rmtree(d, ignore_errors=True)

@@ -239,3 +239,123 @@ def test_nested_samples_bias_with_adaptive_budget():
     assert -0.05 < rel < -0.005 and abs(rel) < 0.3 * sd
     rel, sd = run(128, 0.05, 2500)
     assert abs(rel) < 0.005 and abs(rel) < 0.2 * sd
+
+
+# ---- random cache of base-sample tokens (implementation note after Theorem 4.3) ----
+def test_random_cache_is_a_uniform_subset_in_uniform_order_by_enumeration():
+    # n = 6 tokens, C = 3 slots: each of the 6*5*4 ordered arrangements is (about) equally likely over seeds,
+    # hence every 3-subset too; a wrong range of the replacement draw or a filling phase that keeps arrival
+    # order breaks this
+    trials = 24000
+    counts = {}
+    for t in range(trials):
+        c = tuple(vo.random_cache_fill(6, 3, 0x9000_0000_0000 + 77 * t, 1))
+        assert len(set(c)) == 3 and all(0 <= x < 6 for x in c)
+        counts[c] = counts.get(c, 0) + 1
+    assert len(counts) == 120
+    expect = trials / 120
+    chi2 = sum((v - expect) ** 2 / expect for v in counts.values())
+    assert chi2 < 180.0     # chi2(119): 99.97 % point is about 178
+    # while the cache is not full it holds every token, still in random order
+    orders = {tuple(vo.random_cache_fill(3, 4, 5000 + t, 0)) for t in range(200)}
+    assert orders == {(0, 1, 2), (0, 2, 1), (1, 0, 2), (1, 2, 0), (2, 0, 1), (2, 1, 0)}
+
+
+def test_random_cache_inclusion_is_flat_over_the_sequence():
+    # n = 400, C = 32: every token, early or late, is cached with probability C / n, and sits in slot 0 equally often
+    n, C, trials = 400, 32, 4000
+    inc = np.zeros(n)
+    first = np.zeros(n)
+    for t in range(trials):
+        c = vo.random_cache_fill(n, C, 123456789 + 1000003 * t, 2)
+        assert len(c) == C and len(set(c)) == C
+        inc[c] += 1
+        first[c[0]] += 1
+    p = C / n
+    # counts are negatively correlated draws of a fixed-size subset: variance trials * p * (1 - p) each
+    chi2 = ((inc - trials * p) ** 2 / (trials * p * (1 - p))).sum()
+    assert chi2 < n + 4 * math.sqrt(2 * n)
+    thirds = inc.reshape(4, -1).sum(axis=1)
+    assert np.all(np.abs(thirds - trials * C / 4) < 4 * math.sqrt(trials * C / 4))
+    chi2_first = ((first - trials / n) ** 2 / (trials / n)).sum()
+    assert chi2_first < n + 4 * math.sqrt(2 * n)
+
+
+def test_random_cache_depends_on_seed_and_kv_head_only_and_grows_by_appends():
+    a = vo.random_cache_fill(300, 16, 42, 0)
+    assert a == vo.random_cache_fill(300, 16, 42, 0)
+    assert a != vo.random_cache_fill(300, 16, 42, 1) and a != vo.random_cache_fill(300, 16, 43, 0)
+    assert a != vo.random_cache_fill(300, 16, 42 << 32, 0) and a != vo.random_cache_fill(300, 16, 42 + (1 << 32), 0)
+    s = vo.random_cache_fill(200, 16, 42, 0)
+    for t in range(200, 300):
+        before = list(s)
+        vo.random_cache_append(s, 16, t, 42, 0)
+        changed = [i for i in range(16) if s[i] != before[i]]
+        assert len(changed) <= 1 and all(s[i] == t for i in changed)   # one arrival replaces at most one slot
+    assert s == a
+
+
+def test_base_sample_from_cache_is_a_uniform_subset_of_the_residual():
+    # tiny residual (7 tokens), b0 = 2, cache of 5 of the 12 tokens: over cache seeds every pair of residual
+    # tokens is (about) equally likely as base sample, whether it came from the cache or, when the cache holds
+    # fewer than two residual tokens, from the sampler
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal(4)
+    K = rng.standard_normal((12, 4))
+    V = rng.standard_normal((12, 4))
+    p = dict(sink=1, window=2, topk_abs=2, topk_frac=0.0, base_abs=2, base_frac=0.0, epsilon=0.5, delta=0.5,
+             target=vo.TARGET_D, sm_scale=0.5, budget_cap_frac=1.0)
+    counts = {}
+    trials = 8000
+    from_cache = 0
+    for t in range(trials):
+        cache = vo.random_cache_fill(12, 5, 610000 + 13 * t, 0)
+        r = vo.decode_head(q, K, V, seed=31000 + t, head=2, params=p, cache_tokens=cache)
+        plain = vo.decode_head(q, K, V, seed=31000 + t, head=2, params=p)
+        I_f = set(np.concatenate([r["I_s"], r["I_l"], r["I_t"]]).tolist())
+        in_cache = [x for x in cache if x not in I_f]
+        if len(in_cache) >= 2:
+            assert r["base_from_cache"] and r["I_bs"].tolist() == sorted(in_cache[:2])
+            from_cache += 1
+        else:
+            assert not r["base_from_cache"] and r["I_bs"].tolist() == plain["I_bs"].tolist()
+        # the final sample does not depend on where the base sample came from unless the budget does
+        if r["b"] == plain["b"]:
+            assert r["I_dyn"].tolist() == plain["I_dyn"].tolist()
+        key = tuple(r["I_bs"].tolist())
+        counts[key] = counts.get(key, 0) + 1
+    assert r["n_s"] == 7 and 0.5 * trials < from_cache < trials
+    assert len(counts) == math.comb(7, 2)
+    expect = trials / math.comb(7, 2)
+    chi2 = sum((c - expect) ** 2 / expect for c in counts.values())
+    assert chi2 < 50.0      # chi2(20): 99.97 % point is about 48
+
+
+def test_unbiased_with_the_base_sample_from_the_cache():
+    """The budget comes from cached tokens, the final sample from fresh draws: E[D_hat] = D as without a cache,
+    and the budget has the same distribution as with a drawn base sample."""
+    wl = workloads.make_workload("flat2", batch=1, n_q_heads=1, n_kv_heads=1, head_dim=64, n_max=2048,
+                                 seq_lens=[2048], seed=22, all_flat=True, flat_var=1.0,
+                                 params=workloads.configs.default_params(64, sink=4, window=32, topk_abs=16,
+                                                                         topk_frac=0.0, base_abs=16, base_frac=0.0,
+                                                                         epsilon=0.2, delta=0.2))
+    q, K, V = _head(wl)
+    s = vo.scores(q, K, wl.params["sm_scale"])
+    w = np.exp(s - s.max())
+    D_true = w.sum()
+    trials = 2000
+    Ds, bs, bs_plain = np.empty(trials), np.empty(trials), np.empty(trials)
+    used = 0
+    for t in range(trials):
+        cache = vo.random_cache_fill(2048, 48, 0xABCDEF000 + 7919 * t, 0)
+        r = vo.decode_head(q, K, V, seed=90000 + t, head=0, params=wl.params, s=s, cache_tokens=cache)
+        used += r["base_from_cache"]
+        Ds[t], bs[t] = r["D_out"], r["b"]
+        bs_plain[t] = vo.decode_head(q, K, V, seed=190000 + t, head=0, params=wl.params, s=s)["b"]
+    assert used == trials                     # 48 cached tokens of 2048, 52 of them not residual: 16 residual ones always
+    assert bs.std() > 5 and bs.min() >= 16
+    se = Ds.std(ddof=1) / math.sqrt(trials)
+    assert abs(Ds.mean() - D_true) < 3.5 * se
+    # same budget distribution: means within 4 standard errors of the difference
+    se_b = math.sqrt((bs.var(ddof=1) + bs_plain.var(ddof=1)) / trials)
+    assert abs(bs.mean() - bs_plain.mean()) < 4 * se_b
