@@ -395,6 +395,14 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
         def step(i):  # noqa: F811
             sess.decode_given_topk(topk_idx, topk_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
 
+        if args.cached:
+            # base samples from the random cache of base-sample rows (one cache serves every KV copy: the
+            # copies are identical)
+            sess.make_random_cache(np.arange(1, B + 1, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15))
+
+            def step(i):  # noqa: F811
+                sess.decode_given_topk_cached(topk_idx, topk_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
+
     def score_only(i):
         sess.score(k=ks[i % nbuf])
 
@@ -506,6 +514,7 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     us_layer = ms_step * 1e3
     out = {
         "metric": "vattention_decode_us_per_layer" + ("_given_topk" if args.given_topk else "")
+                  + ("_cached_base" if args.given_topk and args.cached else "")
                   + ("_nested_samples" if args.nested else "") + ("_ascending_samples" if args.ascending else "")
                   + ("_budget_multiple_%d" % args.budget_multiple if args.budget_multiple != 1 else ""),
         "value": us_layer,
@@ -592,6 +601,9 @@ def main():
     ap.add_argument("--given-topk", action="store_true",
                     help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
+    ap.add_argument("--cached", action="store_true",
+                    help="with --given-topk: base samples come from the random cache of base-sample rows "
+                         "(vatt_decode_given_topk_cached)")
     ap.add_argument("--ascending", action="store_true",
                     help="sample lists in ascending token order (VATT_OPT_ASCENDING_SAMPLES)")
     ap.add_argument("--nested", action="store_true",

@@ -146,8 +146,11 @@ int vatt_plan_query_len(const vatt_plan* plan);
  * are computed; they exist for the test suite.)
  */
 enum { VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_BUDGET_MULTIPLE = 7,
-       VATT_OPT_ASCENDING_SAMPLES = 12 };
+       VATT_OPT_ASCENDING_SAMPLES = 12, VATT_OPT_CACHE_SLOTS = 13 };
 /*
+ * VATT_OPT_CACHE_SLOTS = c (a multiple of 4 in 4 .. 8192): slots per (sequence, KV head) of the random cache of
+ * base-sample rows (see vatt_random_cache_fill); the default is the largest base sample of the plan plus a
+ * quarter plus 64, rounded up to a multiple of 64 and capped at 8192.  Set it before the cache buffer is sized.
  * VATT_OPT_ASCENDING_SAMPLES = 1: the base and final samples' segments of out_idx are written in ascending token
  * order (they are the same sets; by default they come in the order in which the sampler accepted the tokens).
  * The gather then walks every head's rows in address order.  Plans with this option keep selection and gather
@@ -216,7 +219,8 @@ int64_t vatt_plan_index_segment(const vatt_plan* plan, int segment);
  *   out_counts   device, int32 [B, Hq, 8] = { |I_s|, |I_l|, |I_t|, |I_bs|, b, n_s, n, flags }
  *                flags (informational): bit 0 base sample taken as a complement, bit 1 final sample taken as a
  *                complement, bit 2 base sample needed more than one batch of draws, bit 3 final sample did,
- *                bit 4 the draw limit was reached, bit 5 the top-k selection took its general path
+ *                bit 4 the draw limit was reached, bit 5 the top-k selection took its general path,
+ *                bit 6 the base sample came from the random cache
  *   out_budget_raw device, double [B, Hq] or NULL: b* before rounding and clamping
  *   out_stats    device, float [B, Hq, 4] or NULL = { D_hat, sigma^2, Tr Sigma, ||N_hat||^2 }, all in the
  *                scale where the largest score of the head has weight 1 (w_i = exp(s_i - max s))
@@ -263,6 +267,53 @@ int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const 
                            const int32_t* topk_idx, const int32_t* topk_cnt, void* workspace,
                            size_t workspace_bytes, float* out_o, float* out_lse, int32_t* out_idx,
                            int32_t* out_counts, double* out_budget_raw, float* out_stats, void* stream);
+
+/*
+ * Random cache of base-sample rows.  The implementation note after Theorem 4.3 observes that the base sample
+ * can be served from a small random cache that is populated and updated during generation, without giving a
+ * procedure; this library's reading: per (sequence, KV head) a cache of c slots holds a uniform random
+ * c-subset of the tokens seen so far, in uniformly random slot order, each with a copy of its K and V row.
+ * Token t (counted from 0) arrives with one draw r, uniform in [0, t]: while the cache is not full the entry
+ * of slot r moves to slot t and the token takes slot r; afterwards the token replaces slot r when r < c
+ * (reservoir sampling).  r comes from the four words of Philox4x32-10 under the counter (t, 2, KV head, 0)
+ * and the key (low, high half of the sequence's cache seed), mapped to [0, t] by the multiply-and-reject
+ * rule of the sampler (first accepted word, else the fourth).
+ * A decode step that uses the cache takes as base sample of a query head the first b0 cached tokens, in slot
+ * order, that are residual tokens of that head (outside sink, window and I_t): a uniform random subset in
+ * random order, filtered by a condition that does not depend on the order, is a uniform b0-subset of the
+ * residual.  The heads of a KV head then share most base-sample rows, and those rows are neighbours in
+ * memory.  A head whose cache holds fewer than b0 residual tokens draws its base sample as without a cache
+ * (flag bit 6 of out_counts is set where the cache was used).  The final sample is drawn afresh either way,
+ * so the estimate stays unbiased, and the budget has the distribution it has with a drawn base sample.
+ *
+ *   rcache       device, 256-byte aligned, vatt_random_cache_bytes(plan) bytes, owned by the caller; the
+ *                layout is the library's (one record per (sequence, KV head): slot count, token list,
+ *                K rows, V rows)
+ *   cache_seeds  device, uint64 [B]: one seed per sequence, the same for the whole life of the sequence
+ *
+ * vatt_random_cache_fill   builds the cache of sequences that exist already: the state after their tokens
+ *                          0 .. seq_lens[b]-1 have arrived one by one (rows copied from k, v).
+ * vatt_append_kv_cached    vatt_append_kv, and the appended token arrives in the cache (position
+ *                          seq_lens[b] before the increment).  A sequence at n_max is left unchanged.
+ * vatt_decode_given_topk_cached   vatt_decode_given_topk with the base sample taken from the cache.
+ *                          Single-token steps only (VATT_E_UNSUPPORTED_SHAPE for q_len > 1 and with
+ *                          VATT_OPT_ASCENDING_SAMPLES).  The cache has to hold tokens below seq_lens[b] only,
+ *                          which it does when every token went in through the two calls above.
+ * All three only enqueue kernels on `stream`; errors as in vatt_decode.
+ */
+size_t vatt_random_cache_bytes(const vatt_plan* plan);
+int vatt_random_cache_slots(const vatt_plan* plan);
+int vatt_random_cache_fill(vatt_plan* plan, const void* k, const void* v, const int32_t* block_table,
+                           const int32_t* seq_lens, const uint64_t* cache_seeds, void* rcache, void* stream);
+int vatt_append_kv_cached(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
+                          const int32_t* block_table, int32_t* seq_lens, const uint64_t* cache_seeds,
+                          void* rcache, void* stream);
+int vatt_decode_given_topk_cached(vatt_plan* plan, const void* q, const void* k, const void* v,
+                                  const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                                  const int32_t* topk_idx, const int32_t* topk_cnt, const void* rcache,
+                                  void* workspace, size_t workspace_bytes, float* out_o, float* out_lse,
+                                  int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                                  void* stream);
 
 /*
  * Dense decode attention (Eq. 1) on the same cache: the sparsity speed-up denominator.

@@ -53,6 +53,14 @@ enum { VATT_WS_DEBUG = 1 };
  */
 int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
+/*
+ * Token lists of a random cache of base-sample rows (vatt_random_cache_fill in vatt.h), for comparison with a
+ * reference: out_tokens (device, int32 [B, Hkv, vatt_random_cache_slots(plan)]) gets the token of every slot in
+ * slot order, -1 for slots not in use; out_counts (device, int32 [B, Hkv]) the number of slots in use.
+ */
+int vatt_random_cache_read(vatt_plan* plan, const void* rcache, int32_t* out_tokens, int32_t* out_counts,
+                           void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,7 @@ VATT_OPT_SCORE_ORDER = 8
 VATT_OPT_FUSED_GATHER = 9
 VATT_OPT_SCORE_PREWORK = 10
 VATT_OPT_ASCENDING_SAMPLES = 12
+VATT_OPT_CACHE_SLOTS = 13
 VATT_BOUND_CLT = 0
 VATT_BOUND_HOEFFDING = 1
 
@@ -42,6 +43,8 @@ EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
     "vatt_plan_index_segment", "vatt_decode", "vatt_decode_static", "vatt_static_scratch_bytes", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
+    "vatt_random_cache_bytes", "vatt_random_cache_slots", "vatt_random_cache_fill", "vatt_append_kv_cached",
+    "vatt_decode_given_topk_cached", "vatt_random_cache_read",
     "vatt_status_string",
 ]
 
@@ -108,6 +111,18 @@ def _load():
     lib.vatt_append_kv.restype = ctypes.c_int
     lib.vatt_stream_read.argtypes = [vp, sz, vp, vp]
     lib.vatt_stream_read.restype = ctypes.c_int
+    lib.vatt_random_cache_bytes.argtypes = [vp]
+    lib.vatt_random_cache_bytes.restype = sz
+    lib.vatt_random_cache_slots.argtypes = [vp]
+    lib.vatt_random_cache_slots.restype = ctypes.c_int
+    lib.vatt_random_cache_fill.argtypes = [vp] * 8
+    lib.vatt_random_cache_fill.restype = ctypes.c_int
+    lib.vatt_append_kv_cached.argtypes = [vp] * 10
+    lib.vatt_append_kv_cached.restype = ctypes.c_int
+    lib.vatt_decode_given_topk_cached.argtypes = [vp] * 11 + [sz] + [vp] * 7
+    lib.vatt_decode_given_topk_cached.restype = ctypes.c_int
+    lib.vatt_random_cache_read.argtypes = [vp] * 5
+    lib.vatt_random_cache_read.restype = ctypes.c_int
     lib.vatt_status_string.argtypes = [ctypes.c_int]
     lib.vatt_status_string.restype = ctypes.c_char_p
     return lib
@@ -249,6 +264,47 @@ def vatt_append_kv(plan, k_new, v_new, k, v, block_table, seq_lens, stream=None)
                              _ptr(seq_lens), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_append_kv")
+
+
+def vatt_random_cache_bytes(plan) -> int:
+    return int(_lib.vatt_random_cache_bytes(plan))
+
+
+def vatt_random_cache_slots(plan) -> int:
+    return int(_lib.vatt_random_cache_slots(plan))
+
+
+def vatt_random_cache_fill(plan, k, v, block_table, seq_lens, cache_seeds, rcache, stream=None) -> None:
+    rc = _lib.vatt_random_cache_fill(plan, _ptr(k), _ptr(v), _ptr(block_table), _ptr(seq_lens), _ptr(cache_seeds),
+                                     _ptr(rcache), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_random_cache_fill")
+
+
+def vatt_append_kv_cached(plan, k_new, v_new, k, v, block_table, seq_lens, cache_seeds, rcache, stream=None) -> None:
+    rc = _lib.vatt_append_kv_cached(plan, _ptr(k_new), _ptr(v_new), _ptr(k), _ptr(v), _ptr(block_table),
+                                    _ptr(seq_lens), _ptr(cache_seeds), _ptr(rcache), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_append_kv_cached")
+
+
+def vatt_decode_given_topk_cached(plan, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache,
+                                  workspace, out_o, out_lse, out_idx, out_counts, out_budget_raw, out_stats,
+                                  stream=None) -> None:
+    rc = _lib.vatt_decode_given_topk_cached(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(block_table), _ptr(seq_lens),
+                                            _ptr(seq_seeds), _ptr(topk_idx), _ptr(topk_cnt), _ptr(rcache),
+                                            _ptr(workspace), _nbytes(workspace), _ptr(out_o), _ptr(out_lse),
+                                            _ptr(out_idx), _ptr(out_counts), _ptr(out_budget_raw), _ptr(out_stats),
+                                            _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_decode_given_topk_cached")
+
+
+def vatt_random_cache_read(plan, rcache, out_tokens, out_counts, stream=None) -> None:
+    """Test hook: token of every cache slot (int32 [B, Hkv, slots], -1 where unused) and slots in use ([B, Hkv])."""
+    rc = _lib.vatt_random_cache_read(plan, _ptr(rcache), _ptr(out_tokens), _ptr(out_counts), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_random_cache_read")
 
 
 def vatt_stream_read(src, nbytes: int, sink, stream=None) -> None:

@@ -115,6 +115,8 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.b0_max = std::min(std::max(b0_max, 2), n_max);
   const int cap_max = (int)std::min((double)n_max, std::ceil((double)p.budget_cap_frac * (double)n_max));
   pl.b_max = std::max(pl.b0_max, cap_max);
+  // random cache: room for the base sample plus the cached tokens that fall into sink, window or top-k
+  pl.cache_slots = (int)std::min<size_t>(kCacheSlotsMax, align_up((size_t)pl.b0_max + pl.b0_max / 4 + 64, 64));
 
   // Rows of up to 32768 tokens keep their 8-key maxima in the registers of 512 threads, and two such workgroups
   // share a CU.  Longer rows get 1024 threads when that costs no parallelism: when only one workgroup fits a
@@ -163,6 +165,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_pre_tok = take((size_t)heads * kHeadThreads * sizeof(uint4));
   pl.off_pre_flags = take((size_t)heads * kHeadThreads * sizeof(uint32_t));
+  pl.off_base_slot = take((size_t)heads * pl.b0_max * sizeof(int32_t));
   pl.ws_bytes = off;
 
   KVLayout L;
@@ -238,6 +241,22 @@ int check_common(const vatt_plan* plan, const void* ws, size_t ws_bytes, const i
 }  // namespace vatt
 
 using namespace vatt;
+
+// The step with a caller-supplied top-k set; rcache (or nullptr) is the random cache the base sample may come from.
+static int decode_given(const vatt::Plan& pl, const void* q, const void* k, const void* v, const int32_t* block_table,
+                        const int32_t* seq_lens, const uint64_t* seq_seeds, const int32_t* topk_idx,
+                        const int32_t* topk_cnt, const void* rcache, void* workspace, float* out_o, float* out_lse,
+                        int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                        hipStream_t st) {
+  using namespace vatt;
+  VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache, workspace, out_idx,
+                                  out_counts, out_budget_raw, out_stats, st));
+  VATT_LAUNCH(launch_sparse_score(pl, q, k, v, block_table, rcache, workspace, out_idx, st));
+  VATT_LAUNCH(launch_given_select(pl, 1, seq_lens, seq_seeds, topk_idx, topk_cnt, nullptr, workspace, out_idx,
+                                  out_counts, out_budget_raw, out_stats, st));
+  VATT_LAUNCH(launch_given_gather(pl, q, k, v, block_table, workspace, out_idx, out_o, out_lse, st));
+  return VATT_OK;
+}
 
 extern "C" {
 
@@ -323,6 +342,11 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   if (option == VATT_OPT_FUSED_GATHER) {
     if (value != 0 && !fused_splits_fit(plan->pl, value)) return VATT_E_UNSUPPORTED_SHAPE;
     plan->pl.fuse_splits = value;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_CACHE_SLOTS) {
+    if (value < 1 || value > kCacheSlotsMax || (value & 3) != 0) return VATT_E_INVALID_ARG;
+    plan->pl.cache_slots = value;
     return VATT_OK;
   }
   if (option == VATT_OPT_ASCENDING_SAMPLES) {
@@ -434,14 +458,67 @@ int vatt_decode_given_topk(vatt_plan* plan, const void* q, const void* k, const 
   if (!q || !k || !v || !seq_lens || !seq_seeds || !topk_idx || !topk_cnt || !out_o || !out_idx || !out_counts)
     return VATT_E_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return VATT_E_INVALID_ARG;
-  const Plan& pl = plan->pl;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
-                                  out_budget_raw, out_stats, st));
-  VATT_LAUNCH(launch_sparse_score(pl, q, k, v, block_table, workspace, out_idx, st));
-  VATT_LAUNCH(launch_given_select(pl, 1, seq_lens, seq_seeds, topk_idx, topk_cnt, workspace, out_idx, out_counts,
-                                  out_budget_raw, out_stats, st));
-  VATT_LAUNCH(launch_given_gather(pl, q, k, v, block_table, workspace, out_idx, out_o, out_lse, st));
+  return decode_given(plan->pl, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, nullptr, workspace, out_o,
+                      out_lse, out_idx, out_counts, out_budget_raw, out_stats, static_cast<hipStream_t>(stream));
+}
+
+size_t vatt_random_cache_bytes(const vatt_plan* plan) {
+  if (!plan) return 0;
+  return (size_t)cache_layout(plan->pl).rec_bytes * (size_t)plan->pl.p.batch * (size_t)plan->pl.p.n_kv_heads;
+}
+
+int vatt_random_cache_slots(const vatt_plan* plan) { return plan ? plan->pl.cache_slots : 0; }
+
+int vatt_random_cache_fill(vatt_plan* plan, const void* k, const void* v, const int32_t* block_table,
+                           const int32_t* seq_lens, const uint64_t* cache_seeds, void* rcache, void* stream) {
+  if (!plan) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  if (plan->pl.p.kv_layout == VATT_LAYOUT_PAGED && !block_table) return VATT_E_INVALID_ARG;
+  if (!k || !v || !seq_lens || !cache_seeds || !rcache) return VATT_E_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || (reinterpret_cast<uintptr_t>(rcache) & 255u) != 0) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_cache_fill(plan->pl, k, v, block_table, seq_lens, cache_seeds, rcache,
+                                static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
+int vatt_append_kv_cached(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
+                          const int32_t* block_table, int32_t* seq_lens, const uint64_t* cache_seeds, void* rcache,
+                          void* stream) {
+  if (!plan) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  if (plan->pl.p.kv_layout == VATT_LAYOUT_PAGED && !block_table) return VATT_E_INVALID_ARG;
+  if (!k_new || !v_new || !k || !v || !seq_lens || !cache_seeds || !rcache) return VATT_E_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k) || !aligned16(v) ||
+      (reinterpret_cast<uintptr_t>(rcache) & 255u) != 0)
+    return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_append_cached(plan->pl, k_new, v_new, k, v, block_table, seq_lens, cache_seeds, rcache,
+                                   static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
+int vatt_decode_given_topk_cached(vatt_plan* plan, const void* q, const void* k, const void* v,
+                                  const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                                  const int32_t* topk_idx, const int32_t* topk_cnt, const void* rcache,
+                                  void* workspace, size_t workspace_bytes, float* out_o, float* out_lse,
+                                  int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                                  void* stream) {
+  int rc = check_common(plan, workspace, workspace_bytes, block_table);
+  if (rc != VATT_OK) return rc;
+  if (!q || !k || !v || !seq_lens || !seq_seeds || !topk_idx || !topk_cnt || !rcache || !out_o || !out_idx || !out_counts)
+    return VATT_E_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || (reinterpret_cast<uintptr_t>(rcache) & 255u) != 0)
+    return VATT_E_INVALID_ARG;
+  // the cache belongs to single-token steps of whole sequences, and its entries come in slot order
+  if (plan->pl.q_len != 1 || plan->pl.ascending_samples) return VATT_E_UNSUPPORTED_SHAPE;
+  return decode_given(plan->pl, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache, workspace, out_o,
+                      out_lse, out_idx, out_counts, out_budget_raw, out_stats, static_cast<hipStream_t>(stream));
+}
+
+int vatt_random_cache_read(vatt_plan* plan, const void* rcache, int32_t* out_tokens, int32_t* out_counts,
+                           void* stream) {
+  if (!plan || !rcache || !out_tokens || !out_counts) return VATT_E_INVALID_ARG;
+  if (plan->pl.device < 0) return VATT_E_NO_DEVICE;
+  VATT_LAUNCH(launch_cache_read(plan->pl, rcache, out_tokens, out_counts, static_cast<hipStream_t>(stream)));
   return VATT_OK;
 }
 

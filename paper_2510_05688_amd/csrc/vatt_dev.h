@@ -267,6 +267,45 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 }
 
 // ---------------------------------------------------------------------------
+// Random cache of base-sample rows (the implementation note after Theorem 4.3: the base sample can be served
+// from a small random cache kept up to date during generation).  One record per (sequence, KV head):
+//   int32 count (slots in use), 12 bytes of padding | int32 token[slots] | bf16 K rows [slots][d] |
+//   bf16 V rows [slots][d]
+// The slots hold a uniform random subset of the tokens seen so far, in uniformly random order (reservoir
+// sampling), each with a copy of its K and V row.
+// ---------------------------------------------------------------------------
+struct CacheLayout {
+  int32_t slots;
+  int32_t head_dim;
+  int64_t rec_bytes, off_k, off_v;  // bytes; the token list starts at byte 16 of a record
+};
+
+__device__ __forceinline__ unsigned char* cache_record(void* base, const CacheLayout& C, int b, int Hkv, int kvh) {
+  return static_cast<unsigned char*>(base) + ((int64_t)b * Hkv + kvh) * C.rec_bytes;
+}
+__device__ __forceinline__ const unsigned char* cache_record(const void* base, const CacheLayout& C, int b, int Hkv,
+                                                            int kvh) {
+  return static_cast<const unsigned char*>(base) + ((int64_t)b * Hkv + kvh) * C.rec_bytes;
+}
+
+// Uniform integer in [0, R) for the arrival of token t: the four words of Philox4x32-10 under the counter
+// (t, 2, KV head, 0) and the sequence's cache seed, each mapped by multiply-and-reject; the first accepted one
+// counts, the fourth is taken regardless.  1 <= R <= 2^31.
+constexpr uint32_t kCacheStream = 2u;
+__device__ __forceinline__ uint32_t cache_draw(uint32_t t, uint32_t R, uint64_t seed, uint32_t kvh) {
+  const Philox4 ph = philox4x32_10(t, kCacheStream, kvh, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+  const uint32_t thr = (uint32_t)((0x100000000ull - (uint64_t)R) % (uint64_t)R);
+  uint32_t val = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint64_t x = (uint64_t)ph.v[w] * (uint64_t)R;
+    val = (uint32_t)(x >> 32);
+    if ((uint32_t)x >= thr) break;
+  }
+  return val;
+}
+
+// ---------------------------------------------------------------------------
 // Per-head sizes of Algorithm 1's index sets, derived from the sequence length alone.
 // ---------------------------------------------------------------------------
 struct HeadSizes {

@@ -43,6 +43,11 @@ struct GivenArgs {
   int group_major;  // see head_of_block (the KV head count is Hq / group)
   int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
   float sm_scale;
+  // random cache of base-sample rows: heads whose HeadRec.base_cached is set read their base sample's rows from it
+  const void* rcache;
+  CacheLayout rc;
+  const int32_t* base_slot;  // [B*Hq][b0_max]
+  int b0_max;
 };
 
 // Place in the index lists (offset into a head's out_idx / sparse row) of list position p of
@@ -112,6 +117,8 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
   const int total = r.n_sink + r.n_win + r.k + r.b;
   const int per = (total + A.splits - 1) / A.splits;
   const int p_lo = split * per, p_hi = min(p_lo + per, total);
+  const unsigned char* cache_rec = r.base_cached ? cache_record(A.rcache, A.rc, b / A.q_len, A.Hq / A.group, kvh) : nullptr;
+  const int32_t* slots_of = A.base_slot + (int64_t)bh * A.b0_max;
   uint32_t qw[4];
   load_q<D>(A, bh, sub, qw);
   float acc_f[8], acc_b[8];
@@ -133,8 +140,18 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
         int tok;
         place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail[u]);
         tok = min(max(tok, 0), r.n - 1);
-        kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok) + sub * 8);
-        if (STATS) vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok) + sub * 8);
+        const uint16_t* kp = A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok);
+        const uint16_t* vp = A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok);
+        if (tail[u] && r.base_cached) {  // the copy of the row in the cache: rows of neighbouring slots, shared by the group's heads
+          const int slot = min(max(slots_of[place[u] - A.seg_base], 0), A.rc.slots - 1);
+          kp = reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_k) + (int64_t)slot * D;
+          vp = reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_v) + (int64_t)slot * D;
+          kv[u] = *reinterpret_cast<const uint4*>(kp + sub * 8);
+          if (STATS) vv[u] = *reinterpret_cast<const uint4*>(vp + sub * 8);
+        } else {
+          kv[u] = load_stream_16(kp + sub * 8);
+          if (STATS) vv[u] = load_stream_16(vp + sub * 8);
+        }
       }
     }
 #pragma unroll
@@ -344,8 +361,8 @@ __global__ __launch_bounds__(D) void given_merge_kernel(const float* __restrict_
 
 template <int D>
 hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* k, const void* v,
-                          const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
-                          float* out_lse, hipStream_t st) {
+                          const int32_t* block_table, const void* rcache, void* ws, const int32_t* out_idx,
+                          float* out_o, float* out_lse, hipStream_t st) {
   const vatt_params& p = pl.p;
   char* w = static_cast<char*>(ws);
   GivenArgs A;
@@ -375,6 +392,10 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.q_len = pl.q_len;
   A.group_major = pl.group_major;
   A.sm_scale = pl.sm_scale;
+  A.rcache = rcache;
+  A.rc = cache_layout(pl);
+  A.base_slot = reinterpret_cast<const int32_t*>(w + pl.off_base_slot);
+  A.b0_max = pl.b0_max;
   dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
   if (stage == 0) {
@@ -397,17 +418,18 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
 }  // namespace
 
 hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const void* v,
-                               const int32_t* block_table, void* ws, const int32_t* out_idx, hipStream_t st) {
-  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 0, q, k, v, block_table, ws, out_idx, nullptr, nullptr, st);
-  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 0, q, k, v, block_table, ws, out_idx, nullptr, nullptr, st);
+                               const int32_t* block_table, const void* rcache, void* ws, const int32_t* out_idx,
+                               hipStream_t st) {
+  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 0, q, k, v, block_table, rcache, ws, out_idx, nullptr, nullptr, st);
+  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 0, q, k, v, block_table, rcache, ws, out_idx, nullptr, nullptr, st);
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
                                const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
                                float* out_lse, hipStream_t st) {
-  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 1, q, k, v, block_table, ws, out_idx, out_o, out_lse, st);
-  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 1, q, k, v, block_table, ws, out_idx, out_o, out_lse, st);
+  if (pl.p.head_dim == 128) return launch_given_d<128>(pl, 1, q, k, v, block_table, nullptr, ws, out_idx, out_o, out_lse, st);
+  if (pl.p.head_dim == 64) return launch_given_d<64>(pl, 1, q, k, v, block_table, nullptr, ws, out_idx, out_o, out_lse, st);
   return hipErrorInvalidValue;
 }
 

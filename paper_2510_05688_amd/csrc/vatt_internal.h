@@ -21,6 +21,7 @@ constexpr int kGatherThreads = 256;
 // Launch orders of the score pass (see the score kernel); the values of VATT_OPT_SCORE_ORDER.
 constexpr int kScoreOrderTile = 0, kScoreOrderKvHead = 1, kScoreOrderBlocks = 2;
 constexpr int kDenseThreads = 256;
+constexpr int kCacheSlotsMax = 8192;   // slots of the random cache of base-sample rows, per (sequence, KV head)
 
 // What the per-head kernel leaves for the gather kernel.
 struct HeadRec {
@@ -28,6 +29,7 @@ struct HeadRec {
   float scale;    // n_s / b (0 when b == 0)
   int32_t n, n_sink, n_win, k, b, n_s;
   int32_t b_keep;  // leading entries of the final sample that repeat the base sample (nested samples), else 0
+  int32_t base_cached;  // the base sample's entries are slots of the random cache (their rows are read from it)
 };
 
 struct Plan {
@@ -61,9 +63,10 @@ struct Plan {
   int budget_multiple;            // the budget is rounded up to a multiple of this (1: the paper's rule)
   int prework;                    // the sampler streams' first batches are made by workgroups of the score launch
   int fuse_splits;                // > 0: the selection kernel also gathers, with this many workgroups per head
+  int cache_slots;                // slots per (sequence, KV head) of the random cache of base-sample rows
   // workspace offsets (bytes)
   size_t off_scores, off_sub_max, off_sparse, off_head_rec, off_gather_part,
-      off_debug, off_vstat_part, off_dense_part, off_pre_tok, off_pre_flags, ws_bytes;
+      off_debug, off_vstat_part, off_dense_part, off_pre_tok, off_pre_flags, off_base_slot, ws_bytes;
   KVLayout kv_k, kv_v;  // templates; base pointers are passed per call
 };
 
@@ -94,12 +97,26 @@ inline bool score_prework(const Plan& pl) {
 hipError_t launch_gather_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st);
 int fused_splits_for(const Plan& pl);           // the plan's own choice (0: separate kernels)
 bool fused_splits_fit(const Plan& pl, int splits);  // whether the fused kernel can run with that many
+// rcache (may be nullptr): random cache the base sample is taken from when it holds enough residual tokens;
+// the score kernel of the listed tokens then reads those tokens' rows from the cache.
 hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
-                               const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
-                               int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st);
+                               const int32_t* given_idx, const int32_t* given_cnt, const void* rcache, void* ws,
+                               int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                               hipStream_t st);
 // (with targets N and SDPA it also reads the V rows of the listed tokens and leaves the numerator statistics)
 hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const void* v,
-                               const int32_t* block_table, void* ws, const int32_t* out_idx, hipStream_t st);
+                               const int32_t* block_table, const void* rcache, void* ws, const int32_t* out_idx,
+                               hipStream_t st);
+// Random cache of base-sample rows: layout for a plan, state after the tokens of existing sequences have
+// arrived one by one, append of one token per sequence with its arrival in the cache, token lists for tests.
+CacheLayout cache_layout(const Plan& pl);
+hipError_t launch_cache_fill(const Plan& pl, const void* k, const void* v, const int32_t* block_table,
+                             const int32_t* seq_lens, const uint64_t* cache_seeds, void* rcache, hipStream_t st);
+hipError_t launch_append_cached(const Plan& pl, const void* k_new, const void* v_new, void* k, void* v,
+                                const int32_t* block_table, int32_t* seq_lens, const uint64_t* cache_seeds,
+                                void* rcache, hipStream_t st);
+hipError_t launch_cache_read(const Plan& pl, const void* rcache, int32_t* out_tok, int32_t* out_count,
+                             hipStream_t st);
 hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
                                const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
                                float* out_lse, hipStream_t st);

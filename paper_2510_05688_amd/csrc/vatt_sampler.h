@@ -71,7 +71,7 @@ constexpr int kSmallBatchBlocks = 64;  // Philox blocks of a small batch (256 dr
 
 // flag bits of out_counts[7]
 constexpr int kFlagBaseComplement = 1, kFlagDynComplement = 2, kFlagBaseBatches = 4, kFlagDynBatches = 8,
-              kFlagDrawCap = 16, kFlagTopkGeneral = 32;
+              kFlagDrawCap = 16, kFlagTopkGeneral = 32, kFlagBaseFromCache = 64;
 
 // One batch of the draw sequence as a thread sees it: the four draws of one Philox block.
 struct DrawBatch {

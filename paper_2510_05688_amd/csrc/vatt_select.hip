@@ -68,6 +68,10 @@ struct HeadArgs {
   // first batches of both sampler streams made ahead by prework_kernel (nullptr: made here)
   const uint4* pre_tok;       // [B*Hq][kHeadThreads]: the four proposed tokens of every thread
   const uint32_t* pre_flags;  // [B*Hq][kHeadThreads]: ok | first << 4 | (made ? 256 : 0)
+  // random cache of base-sample rows (nullptr: the base sample is drawn)
+  const void* rcache;
+  CacheLayout rc;
+  int32_t* base_slot;         // [B*Hq][b0_max]: cache slot of every base-sample entry taken from the cache
 };
 
 
@@ -1063,6 +1067,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       r.b = hs.n_s > 0 ? hs.b0 : 0;  // the statistics pass walks the base sample
       r.n_s = hs.n_s;
       r.b_keep = 0;
+      r.base_cached = 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -1184,6 +1189,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     r.b = bfin;
     r.n_s = hs.n_s;
     r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
+    r.base_cached = 0;
     A.head_rec[bh] = r;
   }
   VATT_STAMP(A.dbg, 9);
@@ -1355,7 +1361,36 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
     __syncthreads();
     int flags = 0;
-    if (hs.n_s > 0) {
+    bool cached = false;
+    if (hs.n_s > 0 && A.rcache) {
+      // base sample = the first b0 cached tokens, in slot order, that are residual tokens of this head; the
+      // cache is used only when it holds that many
+      const unsigned char* rec = cache_record(A.rcache, A.rc, seq, A.Hkv, h / A.group);
+      const int cnt = min(max(*reinterpret_cast<const int32_t*>(rec), 0), A.rc.slots);
+      const int32_t* ctok = reinterpret_cast<const int32_t*>(rec + 16);
+      const int per = (cnt + NT - 1) / NT;
+      const int s0 = min(tid * per, cnt), s1 = min(s0 + per, cnt);
+      auto residual = [&](int t) { return t >= hs.mid_lo && t < hs.mid_hi && !((bm_f[t >> 5] >> (t & 31)) & 1u); };
+      uint32_t mine = 0;
+      for (int s2 = s0; s2 < s1; ++s2) mine += residual(ctok[s2]) ? 1u : 0u;
+      uint32_t total;
+      uint32_t pos = block_exclusive_scan<NT>(mine, &total, sm.scan);
+      cached = total >= (uint32_t)hs.b0;
+      if (cached) {
+        int32_t* slot_of = A.base_slot + (int64_t)bh * A.b0_max;
+        const uint32_t lim = (uint32_t)min(hs.b0, A.b0_max);
+        for (int s2 = s0; s2 < s1 && pos < lim; ++s2) {
+          const int t = ctok[s2];
+          if (residual(t)) {
+            idx[A.seg_base + pos] = t;
+            slot_of[pos] = s2;
+            ++pos;
+          }
+        }
+        flags |= kFlagBaseFromCache;
+      }
+    }
+    if (hs.n_s > 0 && !cached) {
       const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches,
                                    emit_to(idx + A.seg_base, (uint32_t)A.b0_max), nullptr, nullptr, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
@@ -1373,6 +1408,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       r.b = hs.b0;  // the score pass walks the base sample
       r.n_s = hs.n_s;
       r.b_keep = 0;
+      r.base_cached = cached ? 1 : 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -1512,6 +1548,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     r.b = bfin;
     r.n_s = hs.n_s;
     r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
+    r.base_cached = 0;
     A.head_rec[bh] = r;
   }
 }
@@ -1575,12 +1612,15 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
                            float* out_stats);
 
 hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_lens, const uint64_t* seq_seeds,
-                               const int32_t* given_idx, const int32_t* given_cnt, void* ws, int32_t* out_idx,
-                               int32_t* out_counts, double* out_budget_raw, float* out_stats, hipStream_t st) {
+                               const int32_t* given_idx, const int32_t* given_cnt, const void* rcache, void* ws,
+                               int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                               hipStream_t st) {
   HeadArgs A;
   fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
   A.given_idx = given_idx;
   A.given_cnt = given_cnt;
+  A.rcache = rcache;
+  A.rc = cache_layout(pl);
   hipLaunchKernelGGL(given_topk_kernel<kHeadThreads>, dim3(pl.p.n_q_heads, pl.vbatch), dim3(kHeadThreads),
                      pl.head_lds_bytes, st, A);
   return hipGetLastError();
@@ -1701,6 +1741,9 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.dlist_cap = 0;
   A.pre_tok = nullptr;
   A.pre_flags = nullptr;
+  A.rcache = nullptr;
+  A.rc = CacheLayout{};
+  A.base_slot = reinterpret_cast<int32_t*>(w + pl.off_base_slot);
 }
 
 }  // namespace vatt

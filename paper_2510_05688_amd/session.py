@@ -97,6 +97,38 @@ class DecodeSession:
                                   self.workspace, self.out_o, self.out_lse, self.out_idx, self.out_counts,
                                   self.out_budget_raw, self.out_stats, self._stream())
 
+    # ---- random cache of base-sample rows ------------------------------------
+    def make_random_cache(self, cache_seeds, slots: Optional[int] = None):
+        """Allocates the cache buffer and fills it from the sequences as uploaded (vatt_random_cache_fill)."""
+        if slots is not None:
+            vb.vatt_plan_set_option(self.plan, vb.VATT_OPT_CACHE_SLOTS, int(slots))
+        self.cache_slots = vb.vatt_random_cache_slots(self.plan)
+        self.cache_seeds = torch.from_numpy(np.ascontiguousarray(cache_seeds, dtype=np.uint64).view(np.int64)).to(self.device)
+        self.rcache = torch.empty(vb.vatt_random_cache_bytes(self.plan), dtype=torch.uint8, device=self.device)
+        assert self.rcache.data_ptr() % 256 == 0
+        vb.vatt_random_cache_fill(self.plan, self.k, self.v, self.block_table, self.seq_lens, self.cache_seeds,
+                                  self.rcache, self._stream())
+
+    def random_cache_host(self):
+        """(tokens int32 [B, Hkv, slots] with -1 in unused slots, counts int32 [B, Hkv]) of the cache."""
+        B = self.params["batch"]
+        tok = torch.empty(B, self.Hkv, self.cache_slots, dtype=torch.int32, device=self.device)
+        cnt = torch.empty(B, self.Hkv, dtype=torch.int32, device=self.device)
+        vb.vatt_random_cache_read(self.plan, self.rcache, tok, cnt, self._stream())
+        torch.cuda.synchronize(self.device)
+        return tok.cpu().numpy(), cnt.cpu().numpy()
+
+    def append_device_cached(self, k_new, v_new):
+        vb.vatt_append_kv_cached(self.plan, k_new, v_new, self.k, self.v, self.block_table, self.seq_lens,
+                                 self.cache_seeds, self.rcache, self._stream())
+
+    def decode_given_topk_cached(self, topk_idx, topk_cnt, k=None, v=None):
+        vb.vatt_decode_given_topk_cached(self.plan, self.q, self.k if k is None else k,
+                                         self.v if v is None else v, self.block_table, self.seq_lens,
+                                         self.seq_seeds, topk_idx, topk_cnt, self.rcache, self.workspace,
+                                         self.out_o, self.out_lse, self.out_idx, self.out_counts,
+                                         self.out_budget_raw, self.out_stats, self._stream())
+
     def dense(self, q=None, k=None, v=None):
         vb.vatt_dense_decode(self.plan, self.q if q is None else q, self.k if k is None else k,
                              self.v if v is None else v, self.block_table, self.seq_lens, self.workspace,
