@@ -34,11 +34,16 @@ SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32827.5 * 262144.0 / 131084.4 + 46
                               "config3": int((524827.5 * 262144.0 / 131084.4 + 73728.0) * 1024)}
 # score_chunk_kernel, same two counters and scaling (config 2 with 4 query tokens)
 SCORE_CHUNK_TRAFFIC_BYTES = {("config2", 4): int((32928.6 * 262144.0 / 131084.4 + 18432.7) * 1024)}
-# HBM bytes of all kernels of one vatt_decode step, same two counters and scaling (profiles/decode_step_hbm_traffic.md)
-STEP_TRAFFIC_BYTES = {}
+# HBM bytes of all kernels of one vatt_decode step, same two counters, scaled by what they read for a 256 MiB
+# device copy (FETCH_SIZE x 1.99974, WRITE_SIZE x 1.0): profiles/decode_config{2,3,4}_kernel_stats.md
+STEP_TRAFFIC_BYTES = {"config2": 91280881, "config3": 1539533225, "config4": 1424527465}
 # rocprofv3 --kernel-trace --stats averages (us) of the kernels of one step, `python3 bench.py --no-cpu` under the
 # profiler (profiles/decode_config2_kernel_stats.md, profiles/decode_config3_kernel_stats.md)
-PROFILE_KERNEL_US = {}
+PROFILE_KERNEL_US = {
+    "config2": {"score_kernel": 13.43, "head_kernel (selection with the gather fused in)": 24.04, "gather_merge_kernel": 4.33},
+    "config3": {"score_kernel": 180.68, "head_kernel": 32.91, "gather_kernel": 50.43, "gather_merge_kernel": 4.45},
+    "config4": {"score_kernel": 177.11, "head_kernel": 39.74, "gather_kernel": 39.63, "gather_merge_kernel": 4.41},
+}
 LLAMA8B_LAYERS = 32
 
 
@@ -375,6 +380,13 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     if args.ascending:
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_ASCENDING_SAMPLES, 1)
+    for opt, val in (("VATT_OPT_GIVEN_SPLITS", args.given_splits), ("VATT_OPT_SPARSE_SPLITS", args.sparse_splits)):
+        if val > 0:
+            from paper_2510_05688_amd import binding as vb_
+            vb_.vatt_plan_set_option(sess.plan, getattr(vb_, opt), val)
+    if args.fused_gather >= 0:
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_FUSED_GATHER, args.fused_gather)
     sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
     B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
     kv_bytes = 2 * B * Hkv * n * d * 2
@@ -606,6 +618,11 @@ def main():
                          "(vatt_decode_given_topk_cached)")
     ap.add_argument("--ascending", action="store_true",
                     help="sample lists in ascending token order (VATT_OPT_ASCENDING_SAMPLES)")
+    ap.add_argument("--fused-gather", type=int, default=-1,
+                    help="workgroups per head of the selection kernel that also gathers (0: separate selection and "
+                         "gather kernels; default: the plan's own choice, 8 at config 2 and 0 at the batched configs)")
+    ap.add_argument("--given-splits", type=int, default=0, help="tuning aid: workgroups per head of given_gather_kernel")
+    ap.add_argument("--sparse-splits", type=int, default=0, help="tuning aid: workgroups per head of sparse_score_kernel")
     ap.add_argument("--nested", action="store_true",
                     help="nested samples (an option beyond the paper): the final sample keeps the base sample")
     ap.add_argument("--budget-multiple", type=int, default=1,

@@ -37,9 +37,13 @@ extern "C" {
  *   VATT_OPT_SCORE_PREWORK = 0 / 1: with the fused gather, whether the first batches of the sampler's draw
  *     sequences are made by the first workgroups of the score launch while the rest of it streams K (1, the
  *     default for such plans in the KV-head-major launch order) or by the selection kernel itself (0).
+ *   VATT_OPT_GIVEN_SPLITS, VATT_OPT_SPARSE_SPLITS = 1 .. the plan's gather split count: workgroups per head of
+ *     the gather kernel and of the score kernel of the listed tokens on the path with a caller-supplied top-k set
+ *     (tuning aids; the plan picks both).
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
-       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9, VATT_OPT_SCORE_PREWORK = 10 };
+       VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9, VATT_OPT_SCORE_PREWORK = 10,
+       VATT_OPT_GIVEN_SPLITS = 14, VATT_OPT_SPARSE_SPLITS = 15 };
 
 /* Workspace region (vatt_plan_workspace_offset): uint64 [512] of phase clock stamps, written only by builds
  * of the library made with -DVATT_TIMING. */

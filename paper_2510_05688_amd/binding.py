@@ -36,6 +36,8 @@ VATT_OPT_FUSED_GATHER = 9
 VATT_OPT_SCORE_PREWORK = 10
 VATT_OPT_ASCENDING_SAMPLES = 12
 VATT_OPT_CACHE_SLOTS = 13
+VATT_OPT_GIVEN_SPLITS = 14
+VATT_OPT_SPARSE_SPLITS = 15
 VATT_BOUND_CLT = 0
 VATT_BOUND_HOEFFDING = 1
 

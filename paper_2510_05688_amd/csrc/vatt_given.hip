@@ -396,10 +396,11 @@ hipError_t launch_given_d(const Plan& pl, int stage, const void* q, const void* 
   A.rc = cache_layout(pl);
   A.base_slot = reinterpret_cast<const int32_t*>(w + pl.off_base_slot);
   A.b0_max = pl.b0_max;
-  dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
+  const bool stats = p.target != VATT_TARGET_D;
+  if (stage == 0 && !stats) A.splits = pl.sparse_splits;  // scores only: no partial sums, any number of workgroups
+  dim3 grid(p.n_q_heads, A.splits, pl.vbatch);
   if (stage == 0) {
-    const bool stats = p.target != VATT_TARGET_D;
     if (paged && stats) hipLaunchKernelGGL((sparse_score_kernel<D, true, true>), grid, dim3(kGatherThreads), 0, st, A);
     else if (paged) hipLaunchKernelGGL((sparse_score_kernel<D, true, false>), grid, dim3(kGatherThreads), 0, st, A);
     else if (stats) hipLaunchKernelGGL((sparse_score_kernel<D, false, true>), grid, dim3(kGatherThreads), 0, st, A);

@@ -50,6 +50,7 @@ struct Plan {
   int k_max, b0_max, b_max;
   int head_threads;   // workgroup size of the per-head kernel
   int gather_splits, dense_splits, vstat_splits, given_splits;
+  int sparse_splits;  // workgroups per head of the score kernel of the listed tokens when it only writes scores
   size_t idx_cap;
   int64_t seg_off[5];
   size_t head_lds_bytes;
