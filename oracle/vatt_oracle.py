@@ -19,7 +19,8 @@ known-answer vectors, textbook normal quantiles, dense attention from library
 routines (Eq. 1), brute-force enumeration of all samples on tiny inputs,
 textbook simple-random-sampling variance, closed-form budgets on constructed
 populations, and the (epsilon, delta) coverage of Definition 4.1.
-No function in this file is "parity unpinned".
+One function is "parity unpinned": hoeffding_factor (the paper prints no formula for its Hoeffding-based
+budget, only a ratio; the ratio is pinned, the form is a reading fitted to it).  Every other function is pinned.
 
 Readings of the paper taken where it is silent (each also listed in the design
 notes): softmax scale is an explicit factor sm_scale; sink / window are absolute
@@ -35,9 +36,11 @@ independent of I_bs; in a step with several query tokens every (query token,
 head) is an independent instance on the causal prefix of that token; the
 Hoeffding-type budget is the sub-Gaussian form that reproduces the sample ratio
 the paper reports (hoeffding_factor: the formula is a reading, pinned by that
-ratio and by the tail inequality it comes from).  Two options go beyond the
-paper and are off unless asked for: nested samples (the final sample extends
-the base sample) and a budget rounded up to a multiple (clamp_budget).
+ratio and by the tail inequality it comes from); the random cache the paper
+says the base sample can come from is a reservoir sample in random slot order
+(random_cache_append).  Two options go beyond the paper and are off unless
+asked for: nested samples (the final sample extends the base sample) and a
+budget rounded up to a multiple (clamp_budget).
 """
 from __future__ import annotations
 
@@ -306,6 +309,10 @@ def hoeffding_factor(delta: float) -> float:
     sub-Gaussian form of the inequality, P(|mean - mu| >= t) <= 2 exp(-b t^2 / (2 sigma^2)), gives
     b >= 2 ln(2 / delta) (n_s sigma / (eps D))^2: the CLT budget with Phi^{-1}(1 - delta/2)^2 replaced by
     2 ln(2 / delta), a ratio of 2.80 at delta = 0.2.  That reading is taken; this returns sqrt(2 ln(2 / delta)).
+
+    Parity unpinned beyond that ratio: the form is fitted to the one printed number.  It uses the sample
+    variance where Hoeffding's inequality proper uses the range of the weights, so it has no distribution-free
+    finite-sample guarantee (the range-based form would ask for far more than 2.8 times the CLT budget).
     """
     return math.sqrt(2.0 * math.log(2.0 / float(delta)))
 
