@@ -88,8 +88,9 @@ typedef struct vatt_params {
   int32_t n_kv_heads;    /* Hkv; Hq % Hkv == 0 and Hq / Hkv in {1,2,4,8}                              */
   int32_t head_dim;      /* d in {64, 128}                                                            */
   int32_t n_max;         /* capacity in tokens per sequence; sizes workspace and index buffers.  The   */
-                         /* selection kernel keeps six bitmaps of n_max bits in LDS: up to about 170 K */
-                         /* tokens fit, beyond that vatt_plan_create returns VATT_E_UNSUPPORTED_SHAPE  */
+                         /* selection kernel keeps six bitmaps of n_max bits in LDS (eight in its      */
+                         /* 512-thread form): up to about 170 K tokens fit, beyond that                */
+                         /* vatt_plan_create returns VATT_E_UNSUPPORTED_SHAPE                          */
   int32_t kv_layout;     /* VATT_LAYOUT_*                                                             */
   int32_t page_size;     /* tokens per block when paged (power of two, 8..256); ignored otherwise     */
   int32_t num_blocks;    /* physical blocks in the paged cache; ignored when contiguous               */
