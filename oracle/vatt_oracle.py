@@ -20,7 +20,8 @@ routines (Eq. 1), brute-force enumeration of all samples on tiny inputs,
 textbook simple-random-sampling variance, closed-form budgets on constructed
 populations, and the (epsilon, delta) coverage of Definition 4.1.
 One function is "parity unpinned": hoeffding_factor (the paper prints no formula for its Hoeffding-based
-budget, only a ratio; the ratio is pinned, the form is a reading fitted to it).  Every other function is pinned.
+budget, only a ratio; the ratio is pinned, the form is a reading fitted to it).  Every other function is pinned,
+including the range-based Hoeffding budget (bound = "hoeffding_range"), which is the textbook inequality.
 
 Readings of the paper taken where it is silent (each also listed in the design
 notes): softmax scale is an explicit factor sm_scale; sink / window are absolute
@@ -317,8 +318,22 @@ def hoeffding_factor(delta: float) -> float:
     return math.sqrt(2.0 * math.log(2.0 / float(delta)))
 
 
+def residual_weight_range(s: np.ndarray, m: float, I_t: np.ndarray, supplied: bool = False) -> float:
+    """An interval length that holds every residual weight w_i = exp(s_i - m), known without looking at them.
+
+    Every residual token scores at most the smallest score of the exact top-k set, so its weight lies in
+    [0, exp(min_{I_t} s - m)].  Without a top-k set (k = 0) only w <= 1 is known.  A top-k set supplied by the
+    caller bounds nothing (a residual token may outscore it), so the range is undefined there.
+    """
+    if supplied:
+        raise ValueError("a caller-supplied top-k set does not bound the residual weights")
+    if len(I_t) == 0:
+        return 1.0
+    return float(math.exp(float(np.min(s[I_t])) - m))
+
+
 def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, target: int,
-               bound: str = "clt") -> float:
+               bound: str = "clt", w_range: Optional[float] = None) -> float:
     """b* of Algorithm 2.
 
     Denominator (Corollary for D):  b* = (Phi^{-1}(1 - delta/2) * n_s * sigma / (eps * D))^2.
@@ -328,9 +343,21 @@ def budget_raw(stats: Dict[str, float], n_s: int, epsilon: float, delta: float, 
     when the two are equal: eps' = eps * rho_D / (rho_D + rho_N), giving
     b* = (2 * Phi^{-1}(1 - delta/4) * (rho_D + rho_N) / eps)^2.  That choice is
     a feasible point of the theorem's minimum, so its guarantee applies.
+
+    bound = "hoeffding_range" (denominator target): Hoeffding's inequality proper, which also holds for
+    sampling without replacement: for weights in an interval of length R, P(|mean - mu| >= t) <=
+    2 exp(-2 b t^2 / R^2); the estimate n_s * mean misses the residual mass by at most eps * D when
+    t = eps * D / n_s, so b* = (ln(2 / delta) / 2) * (n_s * R / (eps * D))^2 with D the full estimate D_hat.
+    It needs no variance and holds for every distribution of the weights; w_range = R.
     """
     eps = float(np.float64(np.float32(epsilon)))
     dlt = float(np.float64(np.float32(delta)))
+    if bound == "hoeffding_range":
+        if target != TARGET_D:
+            raise ValueError("the Hoeffding budget is defined for the denominator target only")
+        if w_range is None:
+            raise ValueError("the range of the residual weights is needed")
+        return 0.5 * math.log(2.0 / dlt) * (n_s * float(w_range) / (eps * stats["D_hat"])) ** 2
     rho_D = n_s * math.sqrt(stats["sigma2"]) / stats["D_hat"]
     if bound == "hoeffding":
         if target != TARGET_D:
@@ -444,8 +471,9 @@ def decode_head(q: np.ndarray, K: np.ndarray, V: np.ndarray, *, seed: int, head:
         I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,
                               draw_cap=draw_cap, query=query)
     st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))
-    b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target,
-                        bound=str(params.get("bound", "clt")))
+    bound = str(params.get("bound", "clt"))
+    b_star = budget_raw(st, n_s, float(params["epsilon"]), float(params["delta"]), target, bound=bound,
+                        w_range=residual_weight_range(s, m, I_t, forced_topk is not None) if bound == "hoeffding_range" else None)
     b = clamp_budget(b_star, b0, n_s, float(params.get("budget_cap_frac", 1.0)),
                      int(params.get("budget_multiple", 1)))
     if forced_b is not None:

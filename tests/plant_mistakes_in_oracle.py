@@ -95,6 +95,13 @@ M = [
  ("base from cache lowest tokens", "got = [int(t) for t in cache_tokens if int(t) in is_res][:int(b0)]", "got = sorted(int(t) for t in cache_tokens if int(t) in is_res)[:int(b0)]"),
  ("base from cache short sample", "    if len(got) < int(b0):\n        return None", "    if len(got) < 1:\n        return None"),
  ("cache never used", "I_bs = base_sample_from_cache(cache_tokens, residual, b0) if cache_tokens is not None else None", "I_bs = None"),
+ ("range bound without the half", "return 0.5 * math.log(2.0 / dlt) * (n_s * float(w_range)", "return math.log(2.0 / dlt) * (n_s * float(w_range)"),
+ ("range bound ln(1/delta)", "return 0.5 * math.log(2.0 / dlt) * (n_s * float(w_range)", "return 0.5 * math.log(1.0 / dlt) * (n_s * float(w_range)"),
+ ("range bound not squared", "* (n_s * float(w_range) / (eps * stats[\"D_hat\"])) ** 2", "* (n_s * float(w_range) / (eps * stats[\"D_hat\"]))"),
+ ("range bound over D_f", "* (n_s * float(w_range) / (eps * stats[\"D_hat\"])) ** 2", "* (n_s * float(w_range) / (eps * stats[\"D_f\"])) ** 2"),
+ ("range from the largest top-k score", "return float(math.exp(float(np.min(s[I_t])) - m))", "return float(math.exp(float(np.max(s[I_t])) - m))"),
+ ("range without the shift", "return float(math.exp(float(np.min(s[I_t])) - m))", "return float(math.exp(float(np.min(s[I_t]))))"),
+ ("range for a supplied set", "    if supplied:\n        raise ValueError(\"a caller-supplied top-k set does not bound the residual weights\")", "    if False:\n        raise ValueError(\"a caller-supplied top-k set does not bound the residual weights\")"),
  ("base sample stream 1", "I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=0,", "I_bs = uniform_sample(residual, b0, mid_lo=mid_lo, mid_len=mid_len, seed=seed, head=head, stream=1,"),
  ("stats over I_dyn scale", "st = sample_stats(s, V, m, I_f, I_bs, n_s, need_num=(target != TARGET_D))", "st = sample_stats(s, V, m, I_f, I_bs, n_s - 1, need_num=(target != TARGET_D))"),
  ("m over I_f only", "    m = float(s.max())\n    k = topk_count", "    m = float(s[:1].max())\n    k = topk_count"),

@@ -761,9 +761,101 @@ def test_hoeffding_budget_meets_the_guarantee_on_a_bounded_population():
     assert hits / trials >= 1 - delta / 2
 
 
+def test_range_based_hoeffding_budget_by_hand_and_against_the_inequality():
+    # by hand: n_s = 1000, R = 0.2, D = 50, eps = 0.1, delta = 0.05:
+    #   t = eps D / n_s = 0.005; b* = R^2 ln(2 / delta) / (2 t^2) = 0.04 * 3.688879454 / 0.00005 = 2951.1035...
+    st = dict(D_f=10.0, w_bar=0.04, sigma2=123.0, D_hat=50.0, tr_sigma=0.0, N_hat_sq=0.0)
+    b = vo.budget_raw(st, 1000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range", w_range=0.2)
+    assert b == pytest.approx(0.04 * math.log(40.0) / 0.00005, rel=1e-6)     # (eps, delta pass through fp32)
+    # the variance plays no part, the range enters squared, D and eps inversely squared
+    assert vo.budget_raw(dict(st, sigma2=0.0), 1000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range", w_range=0.2) == b
+    assert vo.budget_raw(st, 1000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range", w_range=0.4) == pytest.approx(4 * b)
+    assert vo.budget_raw(dict(st, D_hat=100.0), 1000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range",
+                         w_range=0.2) == pytest.approx(b / 4)
+    assert vo.budget_raw(st, 2000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range", w_range=0.2) == pytest.approx(4 * b)
+    # inverting the inequality: with b = b* samples the bound 2 exp(-2 b t^2 / R^2) is exactly delta
+    t = 0.1 * 50.0 / 1000
+    assert 2.0 * math.exp(-2.0 * b * t * t / 0.04) == pytest.approx(0.05, rel=1e-6)
+    # it is the conservative one: never below the CLT budget for weights inside the range (sigma <= R / 2)
+    for sigma in (0.01, 0.05, 0.1):
+        clt = vo.budget_raw(dict(st, sigma2=sigma ** 2), 1000, 0.1, 0.05, vo.TARGET_D)
+        assert b > clt
+    with pytest.raises(ValueError):
+        vo.budget_raw(st, 1000, 0.1, 0.05, vo.TARGET_N, bound="hoeffding_range", w_range=0.2)
+    with pytest.raises(ValueError):
+        vo.budget_raw(st, 1000, 0.1, 0.05, vo.TARGET_D, bound="hoeffding_range")
+
+
+def test_residual_weight_range_bounds_every_residual_weight():
+    rng = np.random.default_rng(12)
+    for trial in range(20):
+        n = int(rng.integers(80, 400))
+        s = rng.normal(0.0, 2.0, size=n)
+        sink, window, k = int(rng.integers(0, 8)), int(rng.integers(0, 8)), int(rng.integers(0, 30))
+        I_s, I_l, I_t, residual = vo.deterministic_set(s, sink, window, k)
+        m = float(s.max())
+        R = vo.residual_weight_range(s, m, I_t)
+        w = np.exp(s[residual] - m)
+        assert np.all(w <= R * (1 + 1e-15)) and np.all(w >= 0.0) and R <= 1.0
+        if len(I_t):
+            # tight: it is the weight of the weakest member of the top-k set, which the best residual token approaches
+            assert R == pytest.approx(math.exp(s[I_t].min() - m))
+        else:
+            assert R == 1.0
+    with pytest.raises(ValueError):
+        vo.residual_weight_range(s, m, I_t, supplied=True)
+
+
+def test_range_based_hoeffding_budget_holds_on_the_worst_population_for_its_range():
+    # weights that are 0 or R, half each: the largest variance an interval of length R allows.  With R / t = 20
+    # (t = eps D / n_s) the budget is (ln(2 / delta) / 2) * 400 = 599 of 3000 tokens, and a sample of that size
+    # misses by more than eps D in well under delta of the draws (the inequality is not tight), while a quarter
+    # of it misses far more often than delta: the budget has the right order of magnitude, from above.
+    rng = np.random.default_rng(13)
+    n_s, eps, delta, R = 3000, 0.05, 0.1, 0.05
+    w = np.zeros(n_s)
+    w[rng.choice(n_s, n_s // 2, replace=False)] = R
+    D_f = 75.0
+    D = D_f + w.sum()
+    assert D == pytest.approx(150.0)
+    st = dict(D_f=D_f, w_bar=float(w.mean()), sigma2=float(w.var(ddof=1)), D_hat=D, tr_sigma=0.0, N_hat_sq=0.0)
+    b = int(math.ceil(vo.budget_raw(st, n_s, eps, delta, vo.TARGET_D, bound="hoeffding_range", w_range=R)))
+    assert b == 600          # 599.15 with eps, delta taken through fp32
+
+    def miss_rate(size, trials=3000):
+        miss = 0
+        for _ in range(trials):
+            pick = rng.choice(n_s, size=size, replace=False)
+            miss += abs(D_f + n_s / size * w[pick].sum() - D) > eps * D
+        return miss / trials
+    assert miss_rate(b) <= delta / 2
+    assert miss_rate(b // 8) > delta
+
+
+def test_decode_head_with_the_range_based_budget():
+    rng = np.random.default_rng(14)
+    n, d = 600, 8
+    q = rng.standard_normal(d)
+    K = rng.standard_normal((n, d)) * 0.5
+    V = rng.standard_normal((n, d))
+    p = dict(sink=4, window=8, topk_abs=20, topk_frac=0.0, base_abs=16, base_frac=0.0, epsilon=0.5, delta=0.1,
+             target=vo.TARGET_D, sm_scale=1.0, budget_cap_frac=1.0, bound="hoeffding_range")
+    r = vo.decode_head(q, K, V, seed=5, head=0, params=p)
+    s = r["scores"]
+    R = math.exp(s[r["I_t"]].min() - r["m"])
+    want = 0.5 * math.log(2.0 / float(np.float32(0.1))) * (r["n_s"] * R / (float(np.float32(0.5)) * r["stats"]["D_hat"])) ** 2
+    assert r["b_star"] == pytest.approx(want, rel=1e-12)
+    assert r["b0"] < r["b"] < r["n_s"] and r["b"] == math.ceil(want)
+    # same samples as the CLT run up to the budget: only the size of the final sample changes
+    c = vo.decode_head(q, K, V, seed=5, head=0, params=dict(p, bound="clt"))
+    assert np.array_equal(c["I_bs"], r["I_bs"]) and c["b_star"] < r["b_star"]
+    with pytest.raises(ValueError):
+        vo.decode_head(q, K, V, seed=5, head=0, params=p, forced_topk=r["I_t"])
+
+
 def test_planted_mistakes_list_follows_the_oracle():
     # tests/plant_mistakes_in_oracle.py (run by hand) replaces pieces of the oracle's text by mistakes; every
     # piece it names has to occur in the oracle as it stands, or the check silently shrinks
     import plant_mistakes_in_oracle as pm
     assert pm.stale_patterns() == []
-    assert len(pm.M) >= 88
+    assert len(pm.M) >= 95
