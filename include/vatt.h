@@ -182,9 +182,15 @@ enum { VATT_OPT_BUDGET_BOUND = 4, VATT_OPT_NESTED_SAMPLES = 5, VATT_OPT_BUDGET_M
  * uses the sample variance where Hoeffding's inequality proper uses the range of the weights, so it carries
  * no distribution-free finite-sample guarantee (the range-based form, (ln(2 / delta) / 2) (n_s R / (eps D))^2
  * with R <= 1 the weight range, would, and asks for far more samples than the appendix reports).
- * Denominator target only (VATT_E_UNSUPPORTED_SHAPE otherwise).
+ * VATT_BOUND_HOEFFDING_RANGE is that range-based form: Hoeffding's inequality proper (it also holds for
+ * sampling without replacement), b* = (ln(2 / delta) / 2) (n_s R / (eps D))^2 with R = exp(min_{I_t} s - m):
+ * every residual token scores at most the weakest member of the exact top-k set, so the residual weights
+ * lie in [0, R] (R = 1 when k = 0).  It needs no variance and holds for every distribution of the weights;
+ * on all but very concentrated heads it asks for the whole residual.  vatt_decode only: a top-k set supplied
+ * by the caller bounds nothing (vatt_decode_given_topk returns VATT_E_UNSUPPORTED_SHAPE under this bound).
+ * Both Hoeffding forms: denominator target only (VATT_E_UNSUPPORTED_SHAPE otherwise).
  */
-enum { VATT_BOUND_CLT = 0, VATT_BOUND_HOEFFDING = 1 };
+enum { VATT_BOUND_CLT = 0, VATT_BOUND_HOEFFDING = 1, VATT_BOUND_HOEFFDING_RANGE = 2 };
 int vatt_plan_set_option(vatt_plan* plan, int option, int value);
 
 /* Bytes of device workspace every launching call needs (256-byte aligned base). */

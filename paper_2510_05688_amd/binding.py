@@ -40,6 +40,7 @@ VATT_OPT_GIVEN_SPLITS = 14
 VATT_OPT_SPARSE_SPLITS = 15
 VATT_BOUND_CLT = 0
 VATT_BOUND_HOEFFDING = 1
+VATT_BOUND_HOEFFDING_RANGE = 2
 
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",

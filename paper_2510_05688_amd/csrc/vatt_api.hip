@@ -82,6 +82,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.eps = (double)p.epsilon;
   pl.cap_frac = (double)p.budget_cap_frac;
   pl.z_half = upper_tail_quantile((double)p.delta / 2.0);
+  pl.range_factor = 0.0;
   pl.z_quarter = upper_tail_quantile((double)p.delta / 4.0);
   pl.sel.sink = p.sink;
   pl.sel.window = p.window;
@@ -252,6 +253,8 @@ static int decode_given(const vatt::Plan& pl, const void* q, const void* k, cons
                         int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
                         hipStream_t st) {
   using namespace vatt;
+  // a supplied set need not hold the largest scores, so it gives no bound on the residual weights
+  if (pl.range_factor > 0.0) return VATT_E_UNSUPPORTED_SHAPE;
   VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache, workspace, out_idx,
                                   out_counts, out_budget_raw, out_stats, st));
   VATT_LAUNCH(launch_sparse_score(pl, q, k, v, block_table, rcache, workspace, out_idx, st));
@@ -369,12 +372,19 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     Plan& pl = plan->pl;
     if (value == VATT_BOUND_CLT) {
       pl.z_half = upper_tail_quantile((double)pl.p.delta / 2.0);
+      pl.range_factor = 0.0;
       return VATT_OK;
     }
-    if (value != VATT_BOUND_HOEFFDING) return VATT_E_INVALID_ARG;
+    if (value != VATT_BOUND_HOEFFDING && value != VATT_BOUND_HOEFFDING_RANGE) return VATT_E_INVALID_ARG;
     if (pl.p.target != VATT_TARGET_D) return VATT_E_UNSUPPORTED_SHAPE;
+    if (value == VATT_BOUND_HOEFFDING_RANGE) {
+      // Hoeffding's inequality for weights in [0, R]: 2 exp(-2 b t^2 / R^2) <= delta
+      pl.range_factor = 0.5 * std::log(2.0 / (double)pl.p.delta);
+      return VATT_OK;
+    }
     // sub-Gaussian tail 2 exp(-b t^2 / (2 sigma^2)) <= delta in place of the normal quantile
     pl.z_half = std::sqrt(2.0 * std::log(2.0 / (double)pl.p.delta));
+    pl.range_factor = 0.0;
     return VATT_OK;
   }
   if (option == VATT_OPT_BUDGET_MULTIPLE) {

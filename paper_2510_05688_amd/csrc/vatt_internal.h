@@ -41,6 +41,7 @@ struct Plan {
   int vbatch;         // batch * q_len: every (sequence, query token) pair is handled like a sequence of its own
   float sm_scale;
   double z_half;      // Phi^{-1}(1 - delta/2)
+  double range_factor;  // > 0: the range-based Hoeffding budget, ln(2 / delta) / 2 (denominator target)
   double z_quarter;   // Phi^{-1}(1 - delta/4)
   double eps, cap_frac;
   SelectParams sel;

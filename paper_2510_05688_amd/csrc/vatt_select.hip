@@ -46,6 +46,7 @@ struct HeadArgs {
   float* out_stats;
   SelectParams sp;
   double z_half, z_quarter, eps, cap_frac;
+  double range_factor;  // > 0: range-based Hoeffding budget for the denominator, ln(2 / delta) / 2
   int64_t seg_topk, seg_base, seg_dyn, seg_sink, seg_win;
   int64_t idx_cap;
   int n_pad, n_max, Hq, n_sub;
@@ -374,8 +375,9 @@ __device__ __forceinline__ double numerator_rho(int n_s, int b0, double sum_r_sq
   const double num = ns * sqrt(*tr_sigma), nn = sqrt(nhat_sq);
   return nn > 0.0 ? num / nn : (num > 0.0 ? INFINITY : 0.0);
 }
+// w_range: an interval length that holds every residual weight (only read for the range-based Hoeffding budget).
 __device__ __forceinline__ Budget algorithm2_budget(const HeadArgs& A, int n_s, int b0, double D_f, double sum_w,
-                                                    double sum_w2, double rho_N) {
+                                                    double sum_w2, double rho_N, double w_range) {
   Budget B;
   const double b0d = (double)b0, ns = (double)n_s;
   const double w_bar = sum_w / b0d;
@@ -383,7 +385,11 @@ __device__ __forceinline__ Budget algorithm2_budget(const HeadArgs& A, int n_s, 
   B.sigma2 = b0 > 1 ? fmax(sum_w2 - sum_w * w_bar, 0.0) / (b0d - 1.0) : 0.0;
   B.D_hat = D_f + ns * w_bar;
   const double rho_D = ns * sqrt(B.sigma2) / B.D_hat;
-  if (A.target == VATT_TARGET_D) {
+  if (A.target == VATT_TARGET_D && A.range_factor > 0.0) {
+    // Hoeffding's inequality proper: b* = (ln(2 / delta) / 2) (n_s R / (eps D))^2, no variance involved
+    const double t = ns * w_range / (A.eps * B.D_hat);
+    B.b_star = A.range_factor * t * t;
+  } else if (A.target == VATT_TARGET_D) {
     const double t = A.z_half * rho_D / A.eps;
     B.b_star = t * t;
   } else if (A.target == VATT_TARGET_N) {
@@ -649,6 +655,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 2);
 
   int topk_flag = 0;
+  uint32_t tau_key = 0u;  // largest composite key (~order key: the smallest score) among this thread's top-k members
   float acc_f32 = 0.f;  // this thread's share of D_f = sum over I_f of exp(s_i - m), kept in fp32 per thread
   double acc_f = 0.0;
   // ---- I_t (Algorithm 1, top-k step) ----
@@ -795,6 +802,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
               if (c <= T) {
                 const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
                 atomicOr(&bm_f[i >> 5], 1u << (i & 31));
+                tau_key = max(tau_key, (uint32_t)(c >> 32));
                 fixed_sum += (uint64_t)(__expf(float_from_order_key(~(uint32_t)(c >> 32)) - m) * 1099511627776.0f);
               }
             }
@@ -860,6 +868,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
             const uint64_t mask = __ballot(take);
             if ((tid & 63) == 0 && (kInside || first0 + u * NT < n)) bm64[(first0 + u * NT) >> 6] = mask;
             if (mask) acc_f32 += take ? __expf(s[u] - m) : 0.f;
+            tau_key = take ? max(tau_key, ~float_order_key(s[u])) : tau_key;
           }
         });
         __syncthreads();
@@ -1075,6 +1084,18 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   }
 
   // ---- statistics (Algorithm 2, get-stats): w_i = exp(s_i - m) ----
+  // For the range-based Hoeffding budget: every residual token scores at most the weakest top-k member, so the
+  // residual weights lie in [0, exp(min_{I_t} s - m)]; without a top-k set only w <= 1 is known.
+  double w_range = 1.0;
+  if (A.range_factor > 0.0 && hs.k > 0) {
+    const uint32_t wk = wave_max_u32(tau_key);
+    if ((tid & 63) == 0) ts.wu[0][tid >> 6] = wk;
+    __syncthreads();
+    uint32_t key = 0u;
+#pragma unroll
+    for (int w = 0; w < SW; ++w) key = max(key, ts.wu[0][w]);
+    w_range = exp((double)float_from_order_key(~key) - (double)m);
+  }
   double sums[3] = {acc_f, acc_w, acc_w2};
   O::block_sum(sums, sm);
   VATT_STAMP(A.dbg, 6);
@@ -1106,7 +1127,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       nhat_sq = t3[0];
       rho_N = numerator_rho(hs.n_s, hs.b0, t3[1], t3[2], nhat_sq, &tr_sigma);
     }
-    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N);
+    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N, w_range);
     sigma2 = bud.sigma2;
     b_star = bud.b_star;
     bfin = bud.b;
@@ -1503,7 +1524,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       nhat_sq = t3[0];
       rho_N = numerator_rho(hs.n_s, hs.b0, t3[1], t3[2], nhat_sq, &tr_sigma);
     }
-    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N);
+    const Budget bud = algorithm2_budget(A, hs.n_s, hs.b0, D_f, sums[1], sums[2], rho_N, 0.0);
     sigma2 = bud.sigma2;
     b_star = bud.b_star;
     bfin = bud.b;
@@ -1697,6 +1718,7 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.out_stats = out_stats;
   A.sp = pl.sel;
   A.z_half = pl.z_half;
+  A.range_factor = pl.range_factor;
   A.z_quarter = pl.z_quarter;
   A.eps = pl.eps;
   A.cap_frac = pl.cap_frac;

@@ -444,6 +444,39 @@ def test_hoeffding_type_budget():
     sess.close()
 
 
+@pytest.mark.parametrize("fused", [0, 8])
+def test_range_based_hoeffding_budget(fused):
+    say("range-based Hoeffding budget (fused gather: %d)" % fused)
+    from paper_2510_05688_amd import binding as vb
+    # flat heads get budgets of several hundred (between the base sample and the residual size); spiky heads,
+    # whose weight sits in the top-k set, have a tiny range and stay at the base sample
+    wl = workloads.small_gqa(seed=42, batch=2, n=6000, epsilon=0.1, delta=0.1)
+    sess = _session(wl)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_FUSED_GATHER, fused)
+    clt = _run(sess)
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING_RANGE)
+    rng_ = _run(sess)
+    reps = check_all(wl, rng_, params=dict(wl.params, bound="hoeffding_range"), label="hoeffding range")
+    assert any(r["b0"] < r["b"] < r["oracle"]["n_s"] for r in reps)
+    assert np.all(rng_["b_star"] >= clt["b_star"])
+    assert np.array_equal(rng_["stats"], clt["stats"])      # same base sample, same statistics
+    # the general top-k path finds the same range
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 1)
+    gen = _run(sess)
+    # (D_f is summed in another order there: b* agrees to rounding, the budgets exactly)
+    assert np.allclose(gen["b_star"], rng_["b_star"], rtol=1e-6, atol=0) and np.array_equal(gen["counts"][..., :7], rng_["counts"][..., :7])
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, 0)
+    # a supplied top-k set bounds nothing: refused
+    seg = rng_["seg"]
+    with pytest.raises(vb.VattError) as e:
+        sess.decode_given_topk(sess.out_idx[:, :, seg[2]:seg[3]].contiguous(), sess.out_counts[:, :, 2].contiguous())
+    assert e.value.status == vb.VATT_E_UNSUPPORTED_SHAPE
+    vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_CLT)
+    back = _run(sess)
+    assert np.array_equal(back["counts"], clt["counts"]) and np.array_equal(back["b_star"], clt["b_star"])
+    sess.close()
+
+
 @pytest.mark.parametrize("name,over", [
     ("default", dict()),                                       # budgets at the base sample: nothing more is drawn
     ("tight_eps", dict(epsilon=0.01, delta=0.01)),             # budgets well above the base sample

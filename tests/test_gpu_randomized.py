@@ -86,14 +86,17 @@ def test_random_configurations_match_the_oracle():
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_TOPK_GENERAL_PATH, int(o["general_topk"]))
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_HEAD_THREADS, 1024 if o["wide"] else 512)
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_NESTED_SAMPLES, int(o["nested"]))
+        # (which of the two Hoeffding forms: derived from what was drawn, so that adding it left the cases as they were)
+        range_form = o["hoeffding"] and (c["n_max"] + c["hkv"]) % 2 == 1
         if o["hoeffding"]:
-            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND, vb.VATT_BOUND_HOEFFDING)
+            vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_BOUND,
+                                    vb.VATT_BOUND_HOEFFDING_RANGE if range_form else vb.VATT_BOUND_HOEFFDING)
         multiple = _budget_multiple(c)
         vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_BUDGET_MULTIPLE, multiple)
         if q_len == 1:
             vb.vatt_plan_set_option(sess.plan, vb.VATT_OPT_SCORE_ORDER, (c["n_max"] // 7 + c["hkv"]) % 3)
-        oracle_params = dict(wl.params, nested=o["nested"], bound="hoeffding" if o["hoeffding"] else "clt",
-                             budget_multiple=multiple)
+        oracle_params = dict(wl.params, nested=o["nested"], budget_multiple=multiple,
+                             bound=("hoeffding_range" if range_form else "hoeffding") if o["hoeffding"] else "clt")
         sess.decode()
         res = sess.results_host()
         view = ChunkView(wl, q_bits, q_len) if q_len > 1 else wl
@@ -156,13 +159,31 @@ def test_random_configurations_with_caller_supplied_topk():
                 supplied[(v, h)] = lst
                 idx[v, h, :len(lst)] = lst
                 cnt[v, h] = len(lst)
-        sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
+        # a third of the single-token cases take their base samples from a random cache of base-sample rows
+        # (derived from what was drawn, so that adding it left the cases as they were); its slot count varies
+        # from far too few for any head to use it to plenty
+        use_cache = q_len == 1 and (c["n_max"] + c["hkv"] + c["batch"]) % 3 == 0
+        caches = None
+        if use_cache:
+            cache_seeds = np.arange(c["batch"], dtype=np.uint64) * np.uint64(0x1F123BB5) + np.uint64(99 + case)
+            sess.make_random_cache(cache_seeds, slots=(None, 8, 64, 512)[(c["n_max"] + case) % 4])
+            caches = {(b, kvh): vo.random_cache_fill(int(wl.seq_lens[b]), sess.cache_slots, int(cache_seeds[b]), kvh)
+                      for b in range(c["batch"]) for kvh in range(c["hkv"])}
+            sess.decode_given_topk_cached(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
+        else:
+            sess.decode_given_topk(torch.from_numpy(idx).to(sess.device), torch.from_numpy(cnt).to(sess.device))
         res = sess.results_host()
         params = dict(wl.params, nested=nested, budget_multiple=multiple)
+        from_cache = 0
         for v in range(rows):
             for h in range(Hq):
-                check_head_given(view, res, v, h, supplied[(v, h)], params=params, label="random given %d" % case)
+                r = check_head_given(view, res, v, h, supplied[(v, h)], params=params, label="random given %d" % case,
+                                     cache_tokens=caches[(v, h // g)] if use_cache else None)
+                from_cache += r["from_cache"]
                 heads_checked += 1
+        if use_cache:
+            say("    random cache of %d slots: %d of %d heads took their base sample from it" % (
+                sess.cache_slots, from_cache, rows * Hq))
         sess.close()
     say("random configurations with supplied top-k: %d cases, %d heads checked" % (n_cases, heads_checked))
 
