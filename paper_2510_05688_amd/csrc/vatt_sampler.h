@@ -122,6 +122,17 @@ struct HeadOps {
 
   static __device__ __forceinline__ void mark_bit(uint32_t* bm, uint32_t i) { atomicOr(&bm[i >> 5], 1u << (i & 31)); }
   static __device__ __forceinline__ bool test_bit(const uint32_t* bm, uint32_t i) { return (bm[i >> 5] >> (i & 31)) & 1u; }
+  // Bit e of the result: the bitmap bit of tok[e].  All four words are read before any is used (a test per token
+  // behind a condition compiles to four LDS round trips one after the other); every token has to be a valid one.
+  static __device__ __forceinline__ uint32_t test_bits4(const uint32_t* bm, const uint32_t (&tok)[4]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = bm[tok[e] >> 5];
+    uint32_t r = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r |= ((w[e] >> (tok[e] & 31)) & 1u) << e;
+    return r;
+  }
 
   // Exclusive prefix of the set-bit counts of bm[0, words) into wpre; returns the number of set bits.
   static __device__ uint32_t word_prefix(const uint32_t* bm, int words, uint32_t* wpre, HeadSmem& sm) {
@@ -206,25 +217,25 @@ struct HeadOps {
     }
     VATT_STAMP(S.dbg, 1);
     if (check_prev) __syncthreads();  // every test of `taken` comes before the marks of this batch
-    uint32_t lose = 0;
+    // (the four marks go out together: a void draw ORs in nothing)
+    uint32_t lose = 0, old[4] = {0u, 0u, 0u, 0u};
+    if (B.ok) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        old[e] = atomicOr(&S.taken[B.tok[e] >> 5], ((B.ok >> e) & 1u) << (B.tok[e] & 31));
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if ((B.ok >> e) & 1u) {
-        const uint32_t bit = 1u << (B.tok[e] & 31);
-        const uint32_t old = atomicOr(&S.taken[B.tok[e] >> 5], bit);
-        if (old & bit) {
-          lose |= 1u << e;
-          atomicOr(&S.scratch[B.tok[e] >> 5], bit);
-        }
+      const uint32_t bit = ((B.ok >> e) & 1u) << (B.tok[e] & 31);
+      if (old[e] & bit) {
+        lose |= 1u << e;
+        atomicOr(&S.scratch[B.tok[e] >> 5], bit);
       }
     }
     __syncthreads();
     VATT_STAMP(S.dbg, 2);
     // draws whose token is proposed more than once in this batch
-    uint32_t unresolved = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (((B.ok >> e) & 1u) && test_bit(S.scratch, B.tok[e])) unresolved |= 1u << e;
+    uint32_t unresolved = B.ok & test_bits4(S.scratch, B.tok);
     uint32_t later = 0;
     for (;;) {
 #pragma unroll
@@ -302,10 +313,7 @@ struct HeadOps {
       ++batches;
       VATT_STAMP(S.dbg, 10);
       // accept in draw order: first proposals of residual tokens, until the target is reached
-      uint32_t acc = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (((B.first >> e) & 1u) && !test_bit(S.bm_f, B.tok[e])) acc |= 1u << e;
+      const uint32_t acc = B.first & ~test_bits4(S.bm_f, B.tok);
       uint32_t total;
       uint32_t pos = block_exclusive_scan<NT>((uint32_t)__popc(acc), &total, sm.scan);
       const uint32_t room = target - have;

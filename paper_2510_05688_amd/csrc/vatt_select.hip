@@ -19,6 +19,8 @@
 //
 // Floating-point sums are taken in a fixed order, or as fixed-point integers where the order depends on
 // scheduling, so the statistics and the budget are reproducible too.
+#include <type_traits>
+
 #include "vatt_internal.h"
 #include "vatt_sampler.h"
 
@@ -946,36 +948,35 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   const uint16_t* v_head = (kFused && !PAGED)
                                ? A.v + (int64_t)seq * A.L.seq_stride + (int64_t)kvh * A.L.head_stride + g_sub * 8
                                : nullptr;
-  // UF rows of a list at once, without branches: the list entries are read first, then all scores and rows
-  // are requested; slots beyond the list read token 0 and get the score -inf (weight exp(-inf - m) = 0).
-  // (rounds that lie entirely beyond the list are skipped: the test is the same for the whole workgroup)
-  // list_sc: the scores of the listed tokens (LDS), or nullptr: read from the score row
-  auto load_rows = [&](const uint32_t* list, const float* list_sc, int j0, int count, int cap, float (&sc)[UF],
-                       uint4 (&vv)[UF]) {
-    int t[UF];
+  // UF rows of a list at once, without branches: all list entries (and their scores) are read from LDS first,
+  // then all rows are requested.  The lists are padded to whole calls, so the LDS reads need no bound; a slot
+  // beyond the list reads row 0 and gets the score -inf (weight exp(-inf - m) = 0).  (Written with a per-slot
+  // condition, every slot became a branch of its own with an LDS wait inside: sixteen serial LDS round trips.)
+  // HaveSc: the scores of the listed tokens are in LDS (list_sc), else they are read from the score row.
+  auto load_rows = [&](const uint32_t* list, const float* list_sc, int j0, int count, float (&sc)[UF], uint4 (&vv)[UF],
+                       auto have_sc) {
+    constexpr bool HaveSc = decltype(have_sc)::value;
+    uint32_t t[UF];
+    const int jb = j0 + g_grp;
 #pragma unroll
     for (int u = 0; u < UF; ++u) {
-      const int j = j0 + u * NG + g_grp;
-      t[u] = -1;
-      sc[u] = -INFINITY;
-      if (j0 + u * NG < count) {
-        t[u] = j < count ? min((int)list[min(j, cap - 1)], n - 1) : -1;
-        if (list_sc) sc[u] = list_sc[min(j, cap - 1)];
-      }
+      t[u] = list[jb + u * NG];
+      sc[u] = HaveSc ? list_sc[jb + u * NG] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < UF; ++u) {
-      vv[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (j0 + u * NG < count) {
-        const int tt = max(t[u], 0);
-        if (!list_sc) sc[u] = row[tt];
-        if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, tt) + g_sub * 8);
-        else vv[u] = load_stream_16(v_head + (uint32_t)tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
-      }
+      const bool valid = jb + u * NG < count;
+      const uint32_t tt = valid ? min(t[u], (uint32_t)(n - 1)) : 0u;
+      if constexpr (!HaveSc) sc[u] = row[tt];
+      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, (int)tt) + g_sub * 8);
+      else vv[u] = load_stream_16(v_head + tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
+      t[u] = valid ? 1u : 0u;
     }
 #pragma unroll
-    for (int u = 0; u < UF; ++u) sc[u] = t[u] >= 0 ? sc[u] : -INFINITY;
+    for (int u = 0; u < UF; ++u) sc[u] = t[u] ? sc[u] : -INFINITY;
   };
+  using ScInLds = std::true_type;
+  using ScInRow = std::false_type;
   if constexpr (kFused) {
     const int n_f = hs.n_sink + hs.n_win + hs.k;
     (void)n_f;
@@ -1008,9 +1009,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     const uint32_t ns = (uint32_t)hs.n_s, c0 = (uint32_t)hs.b0;
     if (pair_made && hs.n_s > 0 && c0 < ns && 2u * c0 <= ns) {
       const DrawBatch& B = half ? spec1 : spec0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (((B.first >> e) & 1u) && !O::test_bit(bm_f, B.tok[e])) acc_bits |= 1u << e;
+      acc_bits = B.first & ~O::test_bits4(bm_f, B.tok);
       uint32_t total;
       const uint32_t excl = block_exclusive_scan<NT>((uint32_t)__popc(acc_bits) << (half ? 16 : 0), &total, sm.scan);
       const uint32_t tot0 = total & 0xffffu;
@@ -1038,11 +1037,11 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       }
       __syncthreads();
       VATT_STAMP(A.dbg, 5);
-      load_rows(glist, glist_sc, 0, my_nf, A.glist_cap, fs, fv);
+      load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
       if (spec_dyn) {
         my_spec = hs.b0 > (int)split ? (int)(((uint32_t)hs.b0 - split + smask) >> shift) : 0;
         my_spec = min(my_spec, A.dlist_cap);
-        load_rows(dlist, dlist_sc, 0, my_spec, A.dlist_cap, ds, dv);
+        load_rows(dlist, dlist_sc, 0, my_spec, ds, dv, ScInLds{});
       }
     }
   }
@@ -1149,7 +1148,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   // ---- I_dyn (Algorithm 1, final sample) ----
   bool fast_dyn = false;
   if constexpr (kFused) {
-    if (!fast_base) load_rows(glist, glist_sc, 0, my_nf, A.glist_cap, fs, fv);
+    if (!fast_base) load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
     // the first batch of draws holds the whole final sample, and it is not taken as a complement: its members
     // are the accepted draws counted above, up to the budget
     fast_dyn = spec_dyn && (uint32_t)bfin <= tot1 && 2u * (uint32_t)bfin <= (uint32_t)hs.n_s;
@@ -1228,7 +1227,7 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
     };
     add_rows(gacc, gdsum, fs, fv);
     for (int j0 = UF * NG; j0 < my_nf; j0 += UF * NG) {
-      load_rows(glist, glist_sc, j0, my_nf, A.glist_cap, fs, fv);
+      load_rows(glist, glist_sc, j0, my_nf, fs, fv, ScInLds{});
       add_rows(gacc, gdsum, fs, fv);
     }
     int my_nd = bfin > (int)split ? (int)(((uint32_t)bfin - split + smask) >> shift) : 0;
@@ -1240,7 +1239,8 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       // rows requested ahead cover the first b0 tokens; what the budget adds comes after them in the list
     }
     for (int j0 = j_done; j0 < my_nd; j0 += UF * NG) {
-      load_rows(dlist, fast_dyn ? dlist_sc : nullptr, j0, my_nd, A.dlist_cap, ds, dv);
+      if (fast_dyn) load_rows(dlist, dlist_sc, j0, my_nd, ds, dv, ScInLds{});
+      else load_rows(dlist, dlist_sc, j0, my_nd, ds, dv, ScInRow{});
       add_rows(dacc, ddsum, ds, dv);
     }
     const float tail_scale = bfin > 0 ? (float)((double)hs.n_s / (double)bfin) : 0.f;
@@ -1617,8 +1617,10 @@ size_t head_kernel_lds_bytes(int n_max, int head_threads) {
 }
 
 // LDS entries of a workgroup's share of I_f and of the final sample when `splits` workgroups share a head.
-int fused_glist_cap(const Plan& pl, int splits) { return (pl.p.sink + pl.p.window + pl.k_max) / splits + 2; }
-int fused_dlist_cap(const Plan& pl, int splits) { return pl.b_max / splits + 2; }
+// (padded to whole calls of the row loader: 8 rounds of NT / (d / 8) rows, 512 entries at d = 64,
+// and one call more, since the final sample's list is also walked from a start that is not a multiple of a call)
+int fused_glist_cap(const Plan& pl, int splits) { return ((pl.p.sink + pl.p.window + pl.k_max) / splits + 2 + 1023) & ~511; }
+int fused_dlist_cap(const Plan& pl, int splits) { return (pl.b_max / splits + 2 + 1023) & ~511; }
 // Dynamic LDS of the selection kernel with the fused gather (512 threads).
 size_t fused_head_lds_bytes(const Plan& pl, int splits) {
   return head_kernel_lds_bytes(pl.p.n_max, kHeadThreads) +
