@@ -501,6 +501,28 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
         read_only(i)
     ms_read = time_calls(read_only, steps, torch)
 
+    # the same step with the top-k set supplied by the caller (here: the exact one found above, standing in for
+    # an approximate top-k method): no K scan, only the attended rows are read
+    given = None
+    if not args.given_topk and not args.ascending and args.q_len == 1 and not args.no_extra:
+        from paper_2510_05688_amd import binding as vb3
+        seg2, seg3 = vb3.vatt_plan_index_segment(sess.plan, 2), vb3.vatt_plan_index_segment(sess.plan, 3)
+        g_idx = sess.out_idx[:, :, seg2:seg3].contiguous()
+        g_cnt = sess.out_counts[:, :, 2].contiguous()
+
+        def given_step(i):
+            sess.decode_given_topk(g_idx, g_cnt, k=ks[i % nbuf], v=vs[i % nbuf])
+
+        for i in range(warmup):
+            given_step(i)
+        ms_given = time_calls(given_step, steps, torch)
+        gc = sess.out_counts.cpu().numpy().reshape(-1, 8).astype(np.int64)
+        g_rows = int((((gc[:, 0] + gc[:, 1] + gc[:, 2]) * 2 + gc[:, 3] + 2 * gc[:, 4]) * d * 2).sum())   # K and V rows read
+        given = {"entry_point": "vatt_decode_given_topk (top-k sets supplied by the caller: the exact ones of this workload)",
+                 "us_per_layer": ms_given * 1e3, "speedup_vs_dense": ms_dense / ms_given,
+                 "kv_row_bytes": g_rows, "achieved_gbps": g_rows / (ms_given * 1e-3) / 1e9,
+                 "frac_of_hbm_peak": g_rows / (ms_given * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
     # algorithmic bytes of one layer, from the returned counts
     n_f = counts[:, 0] + counts[:, 1] + counts[:, 2]
     b_dyn = counts[:, 4]
@@ -552,6 +574,7 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
         "dense_decode_us_per_layer": ms_dense * 1e3,
         "dense_hbm_gbps": dense_bytes / (ms_dense * 1e-3) / 1e9,
         "speedup_vs_dense": ms_dense / ms_step,
+        "given_topk": given,
         "token_density": float(((n_f + b_dyn) / np.repeat(seq_n, Hq)).mean()),
         "budget_b": {"min": int(b_dyn.min()), "mean": float(b_dyn.mean()), "max": int(b_dyn.max()),
                      "base_b0_mean": float(counts[:, 3].mean())},
@@ -609,7 +632,7 @@ def main():
     ap.add_argument("--buffers", type=int, default=0, help="distinct KV copies to cycle through (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-extra", action="store_true",
-                    help="config 2 only: skip the batched (config 3) and adaptive-budget legs of the default run")
+                    help="skip the extra legs of the default run: batched (config 3), adaptive budget, caller-supplied top-k")
     ap.add_argument("--given-topk", action="store_true",
                     help="time vatt_decode_given_topk (top-k set supplied by the caller: here the exact top-k that "
                          "vatt_decode found, standing in for an approximate top-k method) instead of vatt_decode")
@@ -666,7 +689,7 @@ def main():
         # the batched configuration (config 3, B = 16), where the path is bound by HBM rather than by latency
         b3 = measure_config(3, args, torch, np, workloads, DecodeSession, headline=False)
         out["batched"] = {k: b3[k] for k in ("config", "value", "unit", "ms_per_step", "steps", "tokens_per_s_attention_only",
-                                              "path_bytes", "dense_decode_us_per_layer", "speedup_vs_dense",
+                                              "path_bytes", "dense_decode_us_per_layer", "speedup_vs_dense", "given_topk",
                                               "token_density", "budget_b", "roofline")}
     if not args.no_cpu:
         wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
