@@ -132,11 +132,12 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   const int want_blocks = 2 * pl.num_cus;
   pl.gather_splits = std::min(32, std::max(1, (32 * pl.num_cus + heads - 1) / heads));  // measured: 32 workgroups per CU beat 8, 16 and 64
   pl.vstat_splits = pl.gather_splits;
-  // (the gather with a caller-supplied top-k also reads K rows and carries running maxima: fewer, longer splits,
-  // 4 workgroups per CU; its score kernel only writes scores and wants 16 per CU.  Measured at 512 heads:
-  // 168.3 us per step with 4 and 4 splits per head, 155.5 us with 2 and 8; at 128 heads 8 to 16 of each are equal)
-  pl.given_splits = std::min(pl.gather_splits, std::max(1, (4 * pl.num_cus + heads - 1) / heads));
-  pl.sparse_splits = std::min(pl.gather_splits, std::max(1, (16 * pl.num_cus + heads - 1) / heads));
+  // (the kernels of the path with a caller-supplied top-k, by measurement: its gather, which also reads K rows
+  // and carries running maxima, 16 workgroups per CU and at most 16 per head; its score kernel, which only
+  // writes scores, 32 per CU and at most 16 per head.  At 512 heads: 128.5 us per step with 8 and 2 per head,
+  // 122.4 us with 16 and 8; at 128 heads 8 to 16 of each are equal; at 32 heads 16 and 16 are best.)
+  pl.given_splits = std::min(std::min(pl.gather_splits, 16), std::max(1, (16 * pl.num_cus + heads - 1) / heads));
+  pl.sparse_splits = std::min(std::min(pl.gather_splits, 16), std::max(1, (32 * pl.num_cus + heads - 1) / heads));
   const int kv_heads = pl.vbatch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
   pl.dense_splits = std::min(std::min(64, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));

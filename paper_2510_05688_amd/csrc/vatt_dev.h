@@ -69,6 +69,20 @@ __device__ __forceinline__ int64_t kv_row_offset(const KVLayout& L, int b, int k
 }
 
 // ---------------------------------------------------------------------------
+// A head's index lists are walked by position p of [sink | window | top-k | tail).  Offset into the lists of a
+// position of the first three segments, by arithmetic alone: the kernels that gather rows compute the places
+// of all rows they have in flight, then read all tokens, then request all rows, with no branch per row (a
+// branch per row makes every index load wait for the row load before it).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int64_t fixed_place(int p, int n_sink, int n_win, int64_t seg_sink, int64_t seg_win,
+                                               int64_t seg_topk) {
+  // (the three segment shifts are uniform values: two selects and an add, all in 32 bits; list offsets are small)
+  const int o0 = (int)seg_sink, o1 = (int)seg_win - n_sink, o2 = (int)seg_topk - n_sink - n_win;
+  const int off = p < n_sink ? o0 : (p < n_sink + n_win ? o1 : o2);
+  return (int64_t)(p + off);
+}
+
+// ---------------------------------------------------------------------------
 // 16-byte load of data that is read once (K and V rows): the non-temporal hint keeps the stream from
 // displacing what the caches hold for reuse; measured +10 % on the K scan.
 // ---------------------------------------------------------------------------

@@ -14,6 +14,8 @@
 // grid = (query heads, splits, sequences) for both, head fastest and in head_of_block order: the splits of a
 // head, and the heads of a KV head, then share an XCD and its L2 (index lists, and the K and V rows they have in
 // common); d/8 adjacent lanes read one K or V row with one 16-byte load each.
+#include <type_traits>
+
 #include "vatt_internal.h"
 
 namespace vatt {
@@ -49,31 +51,6 @@ struct GivenArgs {
   const int32_t* base_slot;  // [B*Hq][b0_max]
   int b0_max;
 };
-
-// Place in the index lists (offset into a head's out_idx / sparse row) of list position p of
-// [sink | window | top-k | tail), and the token there.
-__device__ __forceinline__ int64_t list_place(const GivenArgs& A, const HeadRec& r, const int32_t* idx, int64_t seg_tail,
-                                              int p, int* token, bool* in_tail) {
-  *in_tail = false;
-  if (p < r.n_sink) {
-    *token = p;
-    return A.seg_sink + p;
-  }
-  p -= r.n_sink;
-  if (p < r.n_win) {
-    *token = r.n - r.n_win + p;
-    return A.seg_win + p;
-  }
-  p -= r.n_win;
-  if (p < r.k) {
-    *token = idx[A.seg_topk + p];
-    return A.seg_topk + p;
-  }
-  p -= r.k;
-  *in_tail = true;
-  *token = idx[seg_tail + p];
-  return seg_tail + p;
-}
 
 template <int D>
 __device__ __forceinline__ void load_q(const GivenArgs& A, int bh, int sub, uint32_t (&qw)[4]) {
@@ -125,67 +102,86 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc_f[c] = acc_b[c] = 0.f;
   float r2 = 0.f, m_run = -INFINITY;
-  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
-    int64_t place[U];
-    bool tail[U];
-    uint4 kv[U], vv[U];
+  // U rows per lane group at a time, without a branch per row: places in the lists (arithmetic), tokens (one
+  // load each; for a base sample that came from the random cache also its slots), rows (one or two loads each),
+  // then the arithmetic.  A slot beyond the range repeats the range's last row and writes nothing.  The base
+  // sample has its own walk: its rows may come from the cache, and its statistics go to sums of their own.
+  const int n_fix = r.n_sink + r.n_win + r.k;
+  const bool cached = r.base_cached != 0;
+  auto walk = [&](int lo, int hi, auto tail_tag) {
+    constexpr bool kTail = decltype(tail_tag)::value;
+    for (int p0 = lo + wave * RPW + rsub; p0 < hi; p0 += RPB * U) {
+      int64_t place[U];
+      bool valid[U];
+      int tok[U], slot[U];
+      uint4 kv[U], vv[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int p = p0 + u * RPB;
-      place[u] = -1;
-      tail[u] = false;
-      kv[u] = make_uint4(0u, 0u, 0u, 0u);
-      vv[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (p < p_hi) {
-        int tok;
-        place[u] = list_place(A, r, idx, A.seg_base, p, &tok, &tail[u]);
-        tok = min(max(tok, 0), r.n - 1);
-        const uint16_t* kp = A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok);
-        const uint16_t* vp = A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok);
-        if (tail[u] && r.base_cached) {  // the copy of the row in the cache: rows of neighbouring slots, shared by the group's heads
-          const int slot = min(max(slots_of[place[u] - A.seg_base], 0), A.rc.slots - 1);
-          kp = reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_k) + (int64_t)slot * D;
-          vp = reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_v) + (int64_t)slot * D;
-          kv[u] = *reinterpret_cast<const uint4*>(kp + sub * 8);
-          if (STATS) vv[u] = *reinterpret_cast<const uint4*>(vp + sub * 8);
-        } else {
-          kv[u] = load_stream_16(kp + sub * 8);
-          if (STATS) vv[u] = load_stream_16(vp + sub * 8);
+      for (int u = 0; u < U; ++u) {
+        const int p = p0 + u * RPB;
+        valid[u] = p < hi;
+        const int pc = min(p, hi - 1);
+        place[u] = kTail ? A.seg_base + (pc - n_fix)
+                         : fixed_place(pc, r.n_sink, r.n_win, A.seg_sink, A.seg_win, A.seg_topk);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        tok[u] = idx[place[u]];
+        slot[u] = 0;
+        vv[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
+      if (kTail && cached) {
+        // the copies of the rows in the cache: rows of neighbouring slots, shared by the group's heads
+#pragma unroll
+        for (int u = 0; u < U; ++u) slot[u] = slots_of[place[u] - A.seg_base];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int64_t so = (int64_t)min(max(slot[u], 0), A.rc.slots - 1) * D + sub * 8;
+          kv[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_k) + so);
+          if (STATS) vv[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_v) + so);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int t = min(max(tok[u], 0), r.n - 1);
+          kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, t) + sub * 8);
+          if (STATS) vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, t) + sub * 8);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float s = row_score<LPR>(kv[u], qw, A.sm_scale);
+        if (valid[u] && sub == 0) sp[place[u]] = s;
+        if (STATS && valid[u]) {
+          if (s > m_run) {
+            const float f = __expf(m_run - s);  // 0 when m_run is -inf
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              acc_f[c] *= f;
+              acc_b[c] *= f;
+            }
+            r2 *= f * f;
+            m_run = s;
+          }
+          const float wt = __expf(s - m_run);
+          const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float x = wt * bf16_lo(ww[c]), y = wt * bf16_hi(ww[c]);
+            if constexpr (kTail) {
+              acc_b[2 * c] += x;
+              acc_b[2 * c + 1] += y;
+              r2 += x * x + y * y;
+            } else {
+              acc_f[2 * c] += x;
+              acc_f[2 * c + 1] += y;
+            }
+          }
         }
       }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float s = row_score<LPR>(kv[u], qw, A.sm_scale);
-      if (place[u] >= 0 && sub == 0) sp[place[u]] = s;
-      if (STATS && place[u] >= 0) {
-        if (s > m_run) {
-          const float f = __expf(m_run - s);  // 0 when m_run is -inf
-#pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            acc_f[c] *= f;
-            acc_b[c] *= f;
-          }
-          r2 *= f * f;
-          m_run = s;
-        }
-        const float wt = __expf(s - m_run);
-        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float x = wt * bf16_lo(ww[c]), y = wt * bf16_hi(ww[c]);
-          if (tail[u]) {
-            acc_b[2 * c] += x;
-            acc_b[2 * c + 1] += y;
-            r2 += x * x + y * y;
-          } else {
-            acc_f[2 * c] += x;
-            acc_f[2 * c + 1] += y;
-          }
-        }
-      }
-    }
-  }
+  };
+  walk(p_lo, min(p_hi, n_fix), std::false_type{});
+  walk(max(p_lo, n_fix), p_hi, std::true_type{});
   if (!STATS) return;
   // every lane group has its own (maximum, N_f, R1, R2 share): bring them to the workgroup's maximum and add
   __shared__ float s_f[STATS ? GROUPS : 1][STATS ? D : 1], s_b[STATS ? GROUPS : 1][STATS ? D : 1];
@@ -257,54 +253,70 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
   for (int c = 0; c < 8; ++c) acc[c] = 0.f;
   float dsum = 0.f, m_run = -INFINITY;
 
-  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
-    bool have[U], tail[U], known[U];
-    float s[U];
-    uint4 kv[U], vv[U];
+  // U rows per lane group at a time, without a branch per row (places, then tokens and known scores, then
+  // rows, then the arithmetic); a slot beyond the range repeats the range's last row and adds nothing.  Three
+  // walks: I_f (scores in the sparse list), the leading entries of the final sample that repeat the base
+  // sample (nested samples: scores in the base sample's places of the sparse list), and the rest of the final
+  // sample, whose scores are computed here from their K rows.
+  const int n_fix = r.n_sink + r.n_win + r.k;
+  auto walk = [&](int lo, int hi, auto kind_tag) {
+    constexpr int kKind = decltype(kind_tag)::value;  // 0: I_f, 1: kept base-sample entries, 2: newly drawn
+    constexpr bool kTail = kKind != 0;
+    for (int p0 = lo + wave * RPW + rsub; p0 < hi; p0 += RPB * U) {
+      int64_t place[U];
+      bool valid[U];
+      int tok[U];
+      float s[U];
+      uint4 kv[U], vv[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int p = p0 + u * RPB;
-      have[u] = p < p_hi;
-      tail[u] = false;
-      known[u] = true;
-      s[u] = 0.f;
-      kv[u] = make_uint4(0u, 0u, 0u, 0u);
-      vv[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (have[u]) {
-        int tok;
-        const int64_t place = list_place(A, r, idx, A.seg_dyn, p, &tok, &tail[u]);
-        tok = min(max(tok, 0), r.n - 1);
-        // scores are at hand for I_f and, with nested samples, for the base-sample head of the final sample
-        known[u] = !tail[u] || place - A.seg_dyn < (int64_t)r.b_keep;
-        if (!known[u]) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, tok) + sub * 8);
-        else s[u] = sp[tail[u] ? A.seg_base + (place - A.seg_dyn) : place];
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, tok) + sub * 8);
+      for (int u = 0; u < U; ++u) {
+        const int p = p0 + u * RPB;
+        valid[u] = p < hi;
+        const int pc = min(p, hi - 1);
+        place[u] = kTail ? A.seg_dyn + (pc - n_fix)
+                         : fixed_place(pc, r.n_sink, r.n_win, A.seg_sink, A.seg_win, A.seg_topk);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        tok[u] = idx[place[u]];
+        s[u] = kKind == 2 ? 0.f : sp[kKind == 1 ? A.seg_base + (place[u] - A.seg_dyn) : place[u]];
+        kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = min(max(tok[u], 0), r.n - 1);
+        if (kKind == 2) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, t) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, t) + sub * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        // (the lanes of a group stay together: every lane of the group computes the row's score)
+        if (kKind == 2) s[u] = row_score<LPR>(kv[u], qw, A.sm_scale);
+        if (valid[u]) {
+          const float e = s[u] + (kTail ? tail_bias : 0.f);
+          if (e > m_run) {
+            const float f = __expf(m_run - e);  // 0 when m_run is -inf
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] *= f;
+            dsum *= f;
+            m_run = e;
+          }
+          const float wt = __expf(e - m_run);
+          const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            acc[2 * c] += wt * bf16_lo(ww[c]);
+            acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+          }
+          dsum += wt;
+        }
       }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      // (the lanes of a group stay together: every lane of the group computes the row's score)
-      const float sk = row_score<LPR>(kv[u], qw, A.sm_scale);
-      if (have[u]) {
-        const float e = (known[u] ? s[u] : sk) + (tail[u] ? tail_bias : 0.f);
-        if (e > m_run) {
-          const float f = __expf(m_run - e);  // 0 when m_run is -inf
-#pragma unroll
-          for (int c = 0; c < 8; ++c) acc[c] *= f;
-          dsum *= f;
-          m_run = e;
-        }
-        const float wt = __expf(e - m_run);
-        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          acc[2 * c] += wt * bf16_lo(ww[c]);
-          acc[2 * c + 1] += wt * bf16_hi(ww[c]);
-        }
-        dsum += wt;
-      }
-    }
-  }
+  };
+  const int n_kept = n_fix + min(max(r.b_keep, 0), r.b);
+  walk(p_lo, min(p_hi, n_fix), std::integral_constant<int, 0>{});
+  walk(max(p_lo, n_fix), min(p_hi, n_kept), std::integral_constant<int, 1>{});
+  walk(max(p_lo, n_kept), p_hi, std::integral_constant<int, 2>{});
 
   // every lane group has its own (maximum, D, N): bring them to the workgroup's maximum and add
   __shared__ float s_acc[GROUPS][D];
