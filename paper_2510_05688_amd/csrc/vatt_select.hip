@@ -1328,13 +1328,25 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   if (A.phase == 0) {
     const int cnt = min(max(A.given_cnt[bh], 0), A.k_max);
     const int32_t* given = A.given_idx + (int64_t)bh * A.k_max;
-    for (int t = tid; t < cnt; t += NT) {
-      const int i = given[t];
-      if (i >= hs.mid_lo && i < hs.mid_hi) O::mark_bit(bm_f, (uint32_t)i);
+    // (four entries per thread are read before any is used: a read behind a condition waits for the one before)
+    for (int t0 = 0; t0 < cnt; t0 += 4 * NT) {
+      int g[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) g[u] = given[min(t0 + u * NT + tid, cnt - 1)];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (t0 + u * NT + tid < cnt && g[u] >= hs.mid_lo && g[u] < hs.mid_hi) O::mark_bit(bm_f, (uint32_t)g[u]);
     }
   } else {
     const HeadRec r = A.head_rec[bh];
-    for (int t = tid; t < r.k; t += NT) O::mark_bit(bm_f, (uint32_t)O::list_tok(idx, A.seg_topk + t, n));
+    for (int t0 = 0; t0 < r.k; t0 += 4 * NT) {  // (four list entries per thread read together)
+      int g[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) g[u] = O::list_tok(idx, A.seg_topk + min(t0 + u * NT + tid, r.k - 1), n);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (t0 + u * NT + tid < r.k) O::mark_bit(bm_f, (uint32_t)g[u]);
+    }
   }
   __syncthreads();
   const int k_eff = A.phase == 0 ? (int)O::word_prefix(bm_f, words, wpre, sm) : A.head_rec[bh].k;
@@ -1391,21 +1403,40 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       const int32_t* ctok = reinterpret_cast<const int32_t*>(rec + 16);
       const int per = (cnt + NT - 1) / NT;
       const int s0 = min(tid * per, cnt), s1 = min(s0 + per, cnt);
-      auto residual = [&](int t) { return t >= hs.mid_lo && t < hs.mid_hi && !((bm_f[t >> 5] >> (t & 31)) & 1u); };
+      // a thread's slots four at a time: their tokens are read together, then their bitmap words together
+      // (bit j of the result: slot sb + j holds a residual token; the token comes back in tk[j])
+      auto residual4 = [&](int sb, int (&tk)[4]) -> uint32_t {
+        uint32_t w[4], r4 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tk[j] = ctok[min(sb + j, cnt - 1)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = bm_f[min(max(tk[j], 0), n - 1) >> 5];  // (a token outside the sequence fails the range test below)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          r4 |= ((sb + j < s1 && tk[j] >= hs.mid_lo && tk[j] < hs.mid_hi && !((w[j] >> (tk[j] & 31)) & 1u)) ? 1u : 0u) << j;
+        return r4;
+      };
       uint32_t mine = 0;
-      for (int s2 = s0; s2 < s1; ++s2) mine += residual(ctok[s2]) ? 1u : 0u;
+      for (int sb = s0; sb < s1; sb += 4) {
+        int tk[4];
+        mine += (uint32_t)__popc(residual4(sb, tk));
+      }
       uint32_t total;
       uint32_t pos = block_exclusive_scan<NT>(mine, &total, sm.scan);
       cached = total >= (uint32_t)hs.b0;
       if (cached) {
         int32_t* slot_of = A.base_slot + (int64_t)bh * A.b0_max;
         const uint32_t lim = (uint32_t)min(hs.b0, A.b0_max);
-        for (int s2 = s0; s2 < s1 && pos < lim; ++s2) {
-          const int t = ctok[s2];
-          if (residual(t)) {
-            idx[A.seg_base + pos] = t;
-            slot_of[pos] = s2;
-            ++pos;
+        for (int sb = s0; sb < s1 && pos < lim; sb += 4) {
+          int tk[4];
+          const uint32_t r4 = residual4(sb, tk);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (((r4 >> j) & 1u) && pos < lim) {
+              idx[A.seg_base + pos] = tk[j];
+              slot_of[pos] = sb + j;
+              ++pos;
+            }
           }
         }
         flags |= kFlagBaseFromCache;
@@ -1440,25 +1471,29 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   // scores of [sink | window | top-k | base sample], a few per thread, requested together
   const float* sp = A.sparse + (int64_t)bh * A.idx_cap;
   const int n_fix = hs.n_sink + hs.n_win + k_eff, n_all = n_fix + hs.b0;
+  // (places by arithmetic and loads without a condition around them, so that a thread's loads go out together;
+  // a slot beyond the list repeats the last entry and then counts as -inf)
   auto place_of = [&](int p) -> int64_t {
-    if (p < hs.n_sink) return A.seg_sink + p;
-    p -= hs.n_sink;
-    if (p < hs.n_win) return A.seg_win + p;
-    p -= hs.n_win;
-    if (p < k_eff) return A.seg_topk + p;
-    return A.seg_base + (p - k_eff);
+    const int64_t fixed = fixed_place(p, hs.n_sink, hs.n_win, A.seg_sink, A.seg_win, A.seg_topk);
+    return p < n_fix ? fixed : A.seg_base + (p - n_fix);
   };
   constexpr int U = 4;
+  auto load_batch = [&](int base, float (&v)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = sp[place_of(min(base + u * NT + tid, n_all - 1))];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = base + u * NT + tid < n_all ? v[u] : -INFINITY;
+  };
   float v_max = -INFINITY;
+  float v_first[U] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};  // the first batch stays in registers for the second pass
   for (int base = 0; base < n_all; base += NT * U) {
     float v[U];
+    load_batch(base, v);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int p = base + u * NT + tid;
-      v[u] = p < n_all ? sp[place_of(p)] : -INFINITY;
+      v_max = fmaxf(v_max, v[u]);
+      if (base == 0) v_first[u] = v[u];
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) v_max = fmaxf(v_max, v[u]);
   }
   v_max = wave_max(v_max);
   if ((tid & 63) == 0) s_wf[tid >> 6] = v_max;
@@ -1469,21 +1504,19 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   double acc_f = 0.0, acc_w = 0.0, acc_w2 = 0.0;
   for (int base = 0; base < n_all; base += NT * U) {
     float v[U];
+    if (base == 0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int p = base + u * NT + tid;
-      v[u] = p < n_all ? sp[place_of(p)] : -INFINITY;  // (a second read of the same few values: cache hits)
+      for (int u = 0; u < U; ++u) v[u] = v_first[u];
+    } else {
+      load_batch(base, v);  // (a second read of a few values, only for lists beyond 2048 entries)
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int p = base + u * NT + tid;
       const double w = (double)__expf(v[u] - m);  // 0 for the slots beyond the list
-      if (p < n_fix) {
-        acc_f += w;
-      } else {
-        acc_w += w;
-        acc_w2 += w * w;
-      }
+      acc_f += p < n_fix ? w : 0.0;
+      acc_w += p < n_fix ? 0.0 : w;
+      acc_w2 += p < n_fix ? 0.0 : w * w;
     }
   }
   double sums[3] = {acc_f, acc_w, acc_w2};
