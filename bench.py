@@ -615,6 +615,25 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
             "profile_us": PROFILE_KERNEL_US.get("config%d" % config),
         },
     }
+    # the kernels after the score pass one by one: durations are the rocprofv3 kernel-trace averages recorded under
+    # profiles/ (the profiler cannot run inside this timed loop), bytes are each kernel's share of the path's
+    # algorithmic bytes
+    prof = PROFILE_KERNEL_US.get("config%d" % config)
+    if prof and not args.given_topk:
+        fused = "gather_kernel" not in prof
+        sel_bytes = select_r + (v_rows + gather_r if fused else 0)
+        n_heads = int(counts.shape[0])
+        # partial sums per head that the merge adds: 8 workgroups of the fused kernel, else the plan's gather splits
+        # (enough for 32 workgroups per CU of a 256-CU chip, at most 32)
+        n_part = 8 if fused else min(32, max(1, -(-32 * 256 // n_heads)))
+        shares = [("head_kernel", sel_bytes)] + ([] if fused else [("gather_kernel", v_rows + gather_r)]) + \
+                 [("gather_merge_kernel", n_heads * n_part * (d + 4) * 4 + n_heads * d * 4)]
+        for key, nbytes in shares:
+            name = next(k for k in prof if k.startswith(key))
+            out["roofline"]["kernels"].append(
+                {"name": name, "us": prof[name], "us_source": "rocprofv3 --kernel-trace --stats average, profiles/decode_config%d_kernel_stats.md" % config,
+                 "bytes": int(nbytes), "achieved": nbytes / (prof[name] * 1e-6) / 1e9,
+                 "frac": nbytes / (prof[name] * 1e-6) / 1e9 / HBM_PEAK_GBPS})
     sess.close()
     del ks, vs, sess
     torch.cuda.empty_cache()
