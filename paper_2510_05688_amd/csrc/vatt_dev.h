@@ -68,6 +68,25 @@ __device__ __forceinline__ int64_t kv_row_offset(const KVLayout& L, int b, int k
   }
 }
 
+// The same in two steps, for kernels that have several rows in flight: the block-table entries of all rows are
+// requested first, then the rows (kv_row_offset in a loop leaves it to the compiler whether a row's table entry
+// is awaited before the next row's is requested).
+template <bool PAGED>
+__device__ __forceinline__ int kv_block(const KVLayout& L, int b, int i) {
+  if constexpr (PAGED) return L.block_table[(int64_t)b * L.pages_per_seq + (i >> L.page_shift)];
+  else return 0;
+}
+template <bool PAGED>
+__device__ __forceinline__ int64_t kv_row_offset_in(const KVLayout& L, int b, int kvh, int i, int blk) {
+  if constexpr (PAGED) {
+    blk = min(max(blk, 0), L.num_blocks - 1);
+    const int within = i & ((1 << L.page_shift) - 1);
+    return (int64_t)blk * L.block_stride + (int64_t)kvh * L.head_stride + (int64_t)within * L.head_dim;
+  } else {
+    return (int64_t)b * L.seq_stride + (int64_t)kvh * L.head_stride + (int64_t)i * L.head_dim;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // A head's index lists are walked by position p of [sink | window | top-k | tail).  Offset into the lists of a
 // position of the first three segments, by arithmetic alone: the kernels that gather rows compute the places

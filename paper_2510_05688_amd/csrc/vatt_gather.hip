@@ -36,22 +36,8 @@ struct GatherArgs {
   int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
 };
 
-// Token and weight factor of list position p for a head:
-// [sink | window | top-k | tail) where the tail is the final sample (scaled by n_s/b) or, for the
-// statistics pass, the base sample (unscaled).
-__device__ __forceinline__ int list_token(const HeadRec& r, const int32_t* idx, int64_t seg_topk, int64_t seg_tail,
-                                          int p, bool* in_tail) {
-  *in_tail = false;
-  if (p < r.n_sink) return p;
-  p -= r.n_sink;
-  if (p < r.n_win) return r.n - r.n_win + p;
-  p -= r.n_win;
-  if (p < r.k) return idx[seg_topk + p];
-  p -= r.k;
-  *in_tail = true;
-  return idx[seg_tail + p];
-}
-
+// A head's list is walked by position: [sink | window | top-k | tail) where the tail is the final sample
+// (scaled by n_s/b) or, for the statistics pass, the base sample (unscaled).
 template <int D, bool PAGED, bool STATS>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   constexpr int LPR = D / 8;
@@ -81,49 +67,54 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   for (int c = 0; c < 8; ++c) acc[c] = acc2[c] = 0.f;
   float dsum = 0.f, r2 = 0.f;
 
+  // U rows per lane group at a time, in stages without a branch per row, so that the loads of a stage go out
+  // together: tokens (sink and window tokens by arithmetic, the others from the lists; every slot issues the
+  // list load, at a harmless place where it is not needed), block-table entries on a paged cache, then scores
+  // and V rows.  A slot beyond the range repeats the range's last row with weight 0.
+  const int n_sw = r.n_sink + r.n_win;
   for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
-    int tok[U];
+    int tok[U], blk[U];
     float w[U];
-    bool tail[U];
+    bool tail[U], valid[U];
     uint4 vv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int p = p0 + u * RPB;
-      tok[u] = -1;
-      tail[u] = false;
-      if (p < p_hi) tok[u] = list_token(r, idx, A.seg_topk, seg_tail, p, &tail[u]);
+      valid[u] = p < p_hi;
+      const int pc = min(p, p_hi - 1);
+      const int t2 = pc - n_sw, t3 = t2 - r.k;
+      tail[u] = t3 >= 0;
+      const int64_t place = tail[u] ? seg_tail + t3 : A.seg_topk + max(t2, 0);
+      const int listed = idx[min(place, A.idx_cap - 1)];
+      const int by_rule = pc < r.n_sink ? pc : r.n - r.n_win + (pc - r.n_sink);
+      tok[u] = min(max(t2 >= 0 ? listed : by_rule, 0), r.n - 1);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) blk[u] = kv_block<PAGED>(A.L, seq, tok[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      w[u] = row[tok[u]];
+      vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.L, seq, kvh, tok[u], blk[u]) + sub * 8);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      w[u] = 0.f;
-      vv[u] = make_uint4(0u, 0u, 0u, 0u);
-      if (tok[u] >= 0) {
-        const int t = min(tok[u], r.n - 1);
-        w[u] = row[t];
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.L, seq, kvh, t) + sub * 8);
-      }
-    }
+      const float wt = valid[u] ? __expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f) : 0.f;
+      const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+      if (STATS && tail[u]) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (tok[u] >= 0) {
-        const float wt = __expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f);
-        const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
-        if (STATS && tail[u]) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const float a = wt * bf16_lo(ww[c]), bb = wt * bf16_hi(ww[c]);
-            acc2[2 * c] += a;
-            acc2[2 * c + 1] += bb;
-            r2 += a * a + bb * bb;
-          }
-        } else {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            acc[2 * c] += wt * bf16_lo(ww[c]);
-            acc[2 * c + 1] += wt * bf16_hi(ww[c]);
-          }
-          if (sub == 0) dsum += wt;
+        for (int c = 0; c < 4; ++c) {
+          const float a = wt * bf16_lo(ww[c]), bb = wt * bf16_hi(ww[c]);
+          acc2[2 * c] += a;
+          acc2[2 * c + 1] += bb;
+          r2 += a * a + bb * bb;
         }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          acc[2 * c] += wt * bf16_lo(ww[c]);
+          acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+        }
+        dsum += sub == 0 ? wt : 0.f;
       }
     }
   }

@@ -140,11 +140,16 @@ __global__ __launch_bounds__(kGatherThreads) void sparse_score_kernel(GivenArgs 
           if (STATS) vv[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(cache_rec + A.rc.off_v) + so);
         }
       } else {
+        int blk[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const int t = min(max(tok[u], 0), r.n - 1);
-          kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, t) + sub * 8);
-          if (STATS) vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, t) + sub * 8);
+          tok[u] = min(max(tok[u], 0), r.n - 1);
+          blk[u] = kv_block<PAGED>(A.Lk, b / A.q_len, tok[u]);  // (K and V share the block table)
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          kv[u] = load_stream_16(A.k + kv_row_offset_in<PAGED>(A.Lk, b / A.q_len, kvh, tok[u], blk[u]) + sub * 8);
+          if (STATS) vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.Lv, b / A.q_len, kvh, tok[u], blk[u]) + sub * 8);
         }
       }
 #pragma unroll
@@ -282,11 +287,16 @@ __global__ __launch_bounds__(kGatherThreads) void given_gather_kernel(GivenArgs 
         s[u] = kKind == 2 ? 0.f : sp[kKind == 1 ? A.seg_base + (place[u] - A.seg_dyn) : place[u]];
         kv[u] = make_uint4(0u, 0u, 0u, 0u);
       }
+      int blk[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int t = min(max(tok[u], 0), r.n - 1);
-        if (kKind == 2) kv[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, b / A.q_len, kvh, t) + sub * 8);
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, b / A.q_len, kvh, t) + sub * 8);
+        tok[u] = min(max(tok[u], 0), r.n - 1);
+        blk[u] = kv_block<PAGED>(A.Lv, b / A.q_len, tok[u]);  // (K and V share the block table)
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (kKind == 2) kv[u] = load_stream_16(A.k + kv_row_offset_in<PAGED>(A.Lk, b / A.q_len, kvh, tok[u], blk[u]) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.Lv, b / A.q_len, kvh, tok[u], blk[u]) + sub * 8);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {

@@ -963,17 +963,22 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
       t[u] = list[jb + u * NG];
       sc[u] = HaveSc ? list_sc[jb + u * NG] : 0.f;
     }
+    int blk[UF];
+    bool valid[UF];
 #pragma unroll
     for (int u = 0; u < UF; ++u) {
-      const bool valid = jb + u * NG < count;
-      const uint32_t tt = valid ? min(t[u], (uint32_t)(n - 1)) : 0u;
-      if constexpr (!HaveSc) sc[u] = row[tt];
-      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset<true>(A.L, seq, kvh, (int)tt) + g_sub * 8);
-      else vv[u] = load_stream_16(v_head + tt * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
-      t[u] = valid ? 1u : 0u;
+      valid[u] = jb + u * NG < count;
+      t[u] = valid[u] ? min(t[u], (uint32_t)(n - 1)) : 0u;
+      blk[u] = kv_block<PAGED>(A.L, seq, (int)t[u]);  // (paged cache: all block-table entries before any row)
     }
 #pragma unroll
-    for (int u = 0; u < UF; ++u) sc[u] = t[u] ? sc[u] : -INFINITY;
+    for (int u = 0; u < UF; ++u) {
+      if constexpr (!HaveSc) sc[u] = row[t[u]];
+      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset_in<true>(A.L, seq, kvh, (int)t[u], blk[u]) + g_sub * 8);
+      else vv[u] = load_stream_16(v_head + t[u] * (uint32_t)(kFused ? FD : 1));  // (n_max * d < 2^32)
+    }
+#pragma unroll
+    for (int u = 0; u < UF; ++u) sc[u] = valid[u] ? sc[u] : -INFINITY;
   };
   using ScInLds = std::true_type;
   using ScInRow = std::false_type;
