@@ -111,18 +111,20 @@ __global__ __launch_bounds__(256) void score_kernel(const uint16_t* __restrict__
 #pragma unroll
   for (int u0 = 0; u0 < LOADS; u0 += BATCH) {
     uint4 kv[BATCH];
+    // (paged cache: the block-table entries of a batch are requested together, outside the test on the row
+    // index; inside it, every row's entry would be awaited before the next row's is requested)
+    int64_t off[BATCH];
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
-      const int row = wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
-      const int i = tile_lo + row;
-      if (i < n) {
-        int64_t off;
-        if constexpr (PAGED) off = u0 == 0 ? first_off[u] : kv_row_offset<true>(L, b, kvh, i);
-        else off = kv_row_offset<false>(L, b, kvh, i);
-        kv[u] = load_stream_16(k + off + sub * 8);
-      } else {
-        kv[u] = make_uint4(0u, 0u, 0u, 0u);
-      }
+      const int i = tile_lo + wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
+      if constexpr (PAGED) off[u] = u0 == 0 ? first_off[u] : kv_row_offset<true>(L, b, kvh, min(i, n_max - 1));
+      else off[u] = kv_row_offset<false>(L, b, kvh, i);
+    }
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+      const int i = tile_lo + wave * ROWS_PER_WAVE + (u0 + u) * RPW + rsub;
+      kv[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (i < n) kv[u] = load_stream_16(k + off[u] + sub * 8);
     }
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
