@@ -40,9 +40,9 @@ STEP_TRAFFIC_BYTES = {"config2": 91280881, "config3": 1539533225, "config4": 142
 # rocprofv3 --kernel-trace --stats averages (us) of the kernels of one step, `python3 bench.py --no-cpu` under the
 # profiler (profiles/decode_config2_kernel_stats.md, profiles/decode_config3_kernel_stats.md)
 PROFILE_KERNEL_US = {
-    "config2": {"score_kernel": 13.43, "head_kernel (selection with the gather fused in)": 24.04, "gather_merge_kernel": 4.33},
-    "config3": {"score_kernel": 180.68, "head_kernel": 32.91, "gather_kernel": 50.43, "gather_merge_kernel": 4.45},
-    "config4": {"score_kernel": 177.11, "head_kernel": 39.74, "gather_kernel": 39.63, "gather_merge_kernel": 4.41},
+    "config2": {"score_kernel": 13.85, "head_kernel (selection with the gather fused in)": 23.57, "gather_merge_kernel": 4.13},
+    "config3": {"score_kernel": 180.50, "head_kernel": 32.77, "gather_kernel": 49.76, "gather_merge_kernel": 4.33},
+    "config4": {"score_kernel": 176.94, "head_kernel": 40.04, "gather_kernel": 40.56, "gather_merge_kernel": 4.31},
 }
 LLAMA8B_LAYERS = 32
 
