@@ -74,14 +74,19 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   for (int i0 = lo; i0 < hi; i0 += step) {
     uint4 kk[U], vv[U];
     bool ok[U];
+    int blk[U];
+    // (paged cache: the block-table entries of all rows first, outside the test on the row index, so that no
+    // row waits for the entry of the one before; K and V share the table)
+#pragma unroll
+    for (int u = 0; u < U; ++u) blk[u] = kv_block<PAGED>(A.Lk, seq, min(i0 + u * RPW + rsub, hi - 1));
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int i = i0 + u * RPW + rsub;
       ok[u] = i < hi;
       kk[u] = vv[u] = make_uint4(0u, 0u, 0u, 0u);
       if (ok[u]) {
-        kk[u] = load_stream_16(A.k + kv_row_offset<PAGED>(A.Lk, seq, kvh, i) + sub * 8);
-        vv[u] = load_stream_16(A.v + kv_row_offset<PAGED>(A.Lv, seq, kvh, i) + sub * 8);
+        kk[u] = load_stream_16(A.k + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, i, blk[u]) + sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.Lv, seq, kvh, i, blk[u]) + sub * 8);
       }
     }
     float s[G][U];
