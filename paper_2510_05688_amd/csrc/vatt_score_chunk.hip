@@ -82,13 +82,22 @@ __global__ __launch_bounds__(64 * kChunkWaves) void score_chunk_kernel(
   static_assert(16 / RPI == S, "a 16-key tile takes as many row loads as MFMA steps");
   const int lrow = lane / LPR, lchunk = lane % LPR;
   uint4 kc[KT][S];
+  // (row offsets first, for all rows and outside the test on the row index: on a paged cache each takes a
+  // block-table entry, and inside the test every row's entry would be awaited before the next row's is requested)
+  int64_t koff[KT][S];
+#pragma unroll
+  for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+      koff[kt][s] = kv_row_offset<PAGED>(L, b, kvh, min(tile_lo + kt * 16 + s * RPI + lrow, n_b - 1));
+  }
 #pragma unroll
   for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
     for (int s = 0; s < S; ++s) {
       const int i = tile_lo + kt * 16 + s * RPI + lrow;
-      kc[kt][s] = i < n_b ? load_stream_16(k + kv_row_offset<PAGED>(L, b, kvh, i) + lchunk * 8)
-                          : make_uint4(0u, 0u, 0u, 0u);
+      kc[kt][s] = make_uint4(0u, 0u, 0u, 0u);
+      if (i < n_b) kc[kt][s] = load_stream_16(k + koff[kt][s] + lchunk * 8);
     }
   }
   // ... and turned into A operands through a 16-row LDS tile of this wave (row stride LPR + 1 chunks keeps both
