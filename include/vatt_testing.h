@@ -40,10 +40,15 @@ extern "C" {
  *   VATT_OPT_GIVEN_SPLITS, VATT_OPT_SPARSE_SPLITS = 1 .. the plan's gather split count: workgroups per head of
  *     the gather kernel and of the score kernel of the listed tokens on the path with a caller-supplied top-k set
  *     (tuning aids; the plan picks both).
+ *   VATT_OPT_GIVEN_FUSED = 0, 1, 2, 4, 8 or 16: on that path, 0 keeps the second selection phase and the gather
+ *     in kernels of their own; S > 0 runs them as one kernel with S workgroups per head (denominator target and
+ *     fresh final samples only; VATT_E_UNSUPPORTED_SHAPE when the kernel's LDS does not hold that split).  The
+ *     plan picks S > 0 for batches with at most half as many heads as compute units.  Index sets, budgets and
+ *     statistics are identical; the output sums run in another order.
  */
 enum { VATT_OPT_SAMPLER_SMALL_BATCHES = 1, VATT_OPT_SAMPLER_DRAW_CAP = 2, VATT_OPT_TOPK_GENERAL_PATH = 3,
        VATT_OPT_HEAD_THREADS = 6, VATT_OPT_SCORE_ORDER = 8, VATT_OPT_FUSED_GATHER = 9, VATT_OPT_SCORE_PREWORK = 10,
-       VATT_OPT_GIVEN_SPLITS = 14, VATT_OPT_SPARSE_SPLITS = 15 };
+       VATT_OPT_GIVEN_SPLITS = 14, VATT_OPT_SPARSE_SPLITS = 15, VATT_OPT_GIVEN_FUSED = 16 };
 
 /* Workspace region (vatt_plan_workspace_offset): uint64 [512] of phase clock stamps, written only by builds
  * of the library made with -DVATT_TIMING. */

@@ -38,6 +38,7 @@ VATT_OPT_ASCENDING_SAMPLES = 12
 VATT_OPT_CACHE_SLOTS = 13
 VATT_OPT_GIVEN_SPLITS = 14
 VATT_OPT_SPARSE_SPLITS = 15
+VATT_OPT_GIVEN_FUSED = 16
 VATT_BOUND_CLT = 0
 VATT_BOUND_HOEFFDING = 1
 VATT_BOUND_HOEFFDING_RANGE = 2

@@ -144,6 +144,7 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
 
   pl.fuse_splits = fused_splits_for(pl);
   pl.prework = pl.fuse_splits > 0 ? 1 : 0;
+  pl.given_fuse_splits = given_fused_splits_for(pl);
 
   pl.seg_off[0] = 0;
   pl.seg_off[1] = p.sink;
@@ -256,6 +257,15 @@ static int decode_given(const vatt::Plan& pl, const void* q, const void* k, cons
   using namespace vatt;
   // a supplied set need not hold the largest scores, so it gives no bound on the residual weights
   if (pl.range_factor > 0.0) return VATT_E_UNSUPPORTED_SHAPE;
+  if (pl.given_fuse_splits > 0 && !pl.nested_samples && !pl.ascending_samples && pl.p.target == VATT_TARGET_D) {
+    // small batches: three launches (selection + scores of I_f and I_bs, selection + gather, merge)
+    VATT_LAUNCH(launch_given_fused(pl, 0, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache,
+                                   workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
+    VATT_LAUNCH(launch_given_fused(pl, 1, q, k, v, block_table, seq_lens, seq_seeds, topk_idx, topk_cnt, nullptr,
+                                   workspace, out_idx, out_counts, out_budget_raw, out_stats, st));
+    VATT_LAUNCH(launch_given_merge(pl, workspace, pl.given_fuse_splits, out_o, out_lse, st));
+    return VATT_OK;
+  }
   VATT_LAUNCH(launch_given_select(pl, 0, seq_lens, seq_seeds, topk_idx, topk_cnt, rcache, workspace, out_idx,
                                   out_counts, out_budget_raw, out_stats, st));
   VATT_LAUNCH(launch_sparse_score(pl, q, k, v, block_table, rcache, workspace, out_idx, st));
@@ -349,6 +359,11 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
   if (option == VATT_OPT_FUSED_GATHER) {
     if (value != 0 && !fused_splits_fit(plan->pl, value)) return VATT_E_UNSUPPORTED_SHAPE;
     plan->pl.fuse_splits = value;
+    return VATT_OK;
+  }
+  if (option == VATT_OPT_GIVEN_FUSED) {
+    if (value != 0 && !given_fused_fits(plan->pl, value)) return VATT_E_UNSUPPORTED_SHAPE;
+    plan->pl.given_fuse_splits = value;
     return VATT_OK;
   }
   if (option == VATT_OPT_GIVEN_SPLITS || option == VATT_OPT_SPARSE_SPLITS) {

@@ -448,6 +448,20 @@ hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, con
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_given_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st) {
+  const vatt_params& p = pl.p;
+  const float* part = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_gather_part);
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL((given_merge_kernel<128>), dim3(p.n_q_heads, pl.vbatch), dim3(128), 0, st, part, splits,
+                       p.n_q_heads, out_o, out_lse, pl.group_major, p.n_kv_heads);
+  else if (p.head_dim == 64)
+    hipLaunchKernelGGL((given_merge_kernel<64>), dim3(p.n_q_heads, pl.vbatch), dim3(64), 0, st, part, splits,
+                       p.n_q_heads, out_o, out_lse, pl.group_major, p.n_kv_heads);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 hipError_t launch_given_gather(const Plan& pl, const void* q, const void* k, const void* v,
                                const int32_t* block_table, void* ws, const int32_t* out_idx, float* out_o,
                                float* out_lse, hipStream_t st) {

@@ -51,6 +51,7 @@ struct Plan {
   int k_max, b0_max, b_max;
   int head_threads;   // workgroup size of the per-head kernel
   int gather_splits, dense_splits, vstat_splits, given_splits;
+  int given_fuse_splits;  // caller-supplied top-k: > 0, the second selection phase also gathers, with this many workgroups per head
   int sparse_splits;  // workgroups per head of the score kernel of the listed tokens when it only writes scores
   size_t idx_cap;
   int64_t seg_off[5];
@@ -105,6 +106,17 @@ hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_len
                                const int32_t* given_idx, const int32_t* given_cnt, const void* rcache, void* ws,
                                int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
                                hipStream_t st);
+// The second selection phase with the gather fused in (small batches, denominator target, fresh final sample),
+// followed by the merge of the per-workgroup partials.
+// (phase 0: first selection phase plus the scores of I_f and I_bs; phase 1: second phase plus the gather)
+hipError_t launch_given_fused(const Plan& pl, int phase, const void* q, const void* k, const void* v,
+                              const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                              const int32_t* given_idx, const int32_t* given_cnt, const void* rcache, void* ws,
+                              int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                              hipStream_t st);
+hipError_t launch_given_merge(const Plan& pl, void* ws, int splits, float* out_o, float* out_lse, hipStream_t st);
+int given_fused_splits_for(const Plan& pl);
+bool given_fused_fits(const Plan& pl, int splits);
 // (with targets N and SDPA it also reads the V rows of the listed tokens and leaves the numerator statistics)
 hipError_t launch_sparse_score(const Plan& pl, const void* q, const void* k, const void* v,
                                const int32_t* block_table, const void* rcache, void* ws, const int32_t* out_idx,

@@ -27,6 +27,8 @@
 namespace vatt {
 namespace {
 
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
 // ---------------------------------------------------------------------------
 // Per-head kernel.
 // ---------------------------------------------------------------------------
@@ -75,6 +77,11 @@ struct HeadArgs {
   const void* rcache;
   CacheLayout rc;
   int32_t* base_slot;         // [B*Hq][b0_max]: cache slot of every base-sample entry taken from the cache
+  // caller-supplied top-k, second selection phase with the gather fused in (given_topk_kernel<NT, FD>)
+  const uint16_t* gq;         // queries [B*Hq][d]
+  const uint16_t* gk;         // K cache
+  KVLayout Lk;
+  float sm_scale;
 };
 
 
@@ -1297,14 +1304,23 @@ __device__ __forceinline__ int base_count_of(int n_s, const SelectParams& p) {
   return b0 > n_s ? n_s : b0;
 }
 
-template <int NT>
+// FD = 0: selection only.  FD = head dimension (phase 1 only): the gather is fused in for small batches, as in
+// head_kernel: every head gets A.splits workgroups (blockIdx.z), each of which runs the whole second phase
+// (identical results in all of them), keeps every A.splits-th token of the final sample in LDS, and gathers
+// that share and a contiguous run of I_f: scores of I_f from the sparse list, scores of the sampled tokens from
+// their K rows, V rows, running maximum per lane group (no head maximum bounds the sampled scores); one partial
+// (N, D, maximum) per workgroup for given_merge_kernel.
+template <int NT, int FD, bool PAGED>
 __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   using O = HeadOps<NT>;
   using HeadSmem = typename O::HeadSmem;
   using Sampler = typename O::Sampler;
   constexpr int SW = NT / kWave;
+  constexpr bool kFused = FD > 0;
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   __shared__ float s_wf[16];
+  const uint32_t split = kFused ? blockIdx.z : 0u, shift = kFused ? (uint32_t)A.split_shift : 0u;
+  const bool writer = split == 0u;
   const int h = head_of_block((int)blockIdx.x, A.Hq, A.Hkv, A.group_major), b = blockIdx.y;
   const int bh = b * A.Hq + h;
   const int tid = threadIdx.x;
@@ -1320,6 +1336,16 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   uint32_t* scratch = taken + 2 * words_max;
   uint32_t* wpre = scratch + words_max;
   uint32_t* mail = wpre + words_max;
+  // fused gather (second phase): this workgroup's share of the final sample, and the cross-wave sums
+  uint32_t* dlist = mail + words_max;
+  float* g_red = reinterpret_cast<float*>(dlist + (kFused ? A.dlist_cap : 0));
+  // fused scores (first phase): this workgroup's run of I_f, its share of the base sample and, for a base sample
+  // from the random cache, the slots of that share
+  uint32_t* glist = mail + words_max;
+  uint32_t* blist = glist + (kFused ? A.glist_cap : 0);
+  uint32_t* bslot = blist + (kFused ? A.dlist_cap : 0);
+  const int n_fix0 = 0;
+  (void)n_fix0;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
   const int mid_len = hs.mid_hi - hs.mid_lo;
 
@@ -1379,6 +1405,14 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   S.m = 0.f;
   S.dbg = nullptr;
   const DrawBatch none = {};
+  // (first phase fused with the scores: the run of [sink | window | top-k) this workgroup scores)
+  int f0_lo = 0, f0_hi = 0;
+  if (kFused && A.phase == 0) {
+    const int n_f = hs.n_sink + hs.n_win + k_eff;
+    const int run = min((n_f + (int)A.splits - 1) >> shift, A.glist_cap);
+    f0_lo = min((int)split * run, n_f);
+    f0_hi = min(f0_lo + run, n_f);
+  }
 
   if (A.phase == 0) {
     {
@@ -1390,13 +1424,24 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
         while (bits) {
           const int i = (w << 5) + (__ffs(bits) - 1);
           bits &= bits - 1u;
-          if (pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+          if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
+          if (kFused) {
+            const int p = hs.n_sink + hs.n_win + (int)pos;  // place in [sink | window | top-k)
+            if (p >= f0_lo && p < f0_hi) glist[p - f0_lo] = (uint32_t)i;
+          }
           ++pos;
         }
       }
     }
-    for (int i = tid; i < hs.n_sink; i += NT) idx[A.seg_sink + i] = i;
-    for (int i = tid; i < hs.n_win; i += NT) idx[A.seg_win + i] = hs.mid_hi + i;
+    for (int i = tid; i < hs.n_sink; i += NT) {
+      if (writer) idx[A.seg_sink + i] = i;
+      if (kFused && i >= f0_lo && i < f0_hi) glist[i - f0_lo] = (uint32_t)i;
+    }
+    for (int i = tid; i < hs.n_win; i += NT) {
+      if (writer) idx[A.seg_win + i] = hs.mid_hi + i;
+      const int p = hs.n_sink + i;
+      if (kFused && p >= f0_lo && p < f0_hi) glist[p - f0_lo] = (uint32_t)(hs.mid_hi + i);
+    }
     __syncthreads();
     int flags = 0;
     bool cached = false;
@@ -1438,8 +1483,14 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             if (((r4 >> j) & 1u) && pos < lim) {
-              idx[A.seg_base + pos] = tk[j];
-              slot_of[pos] = sb + j;
+              if (writer) {
+                idx[A.seg_base + pos] = tk[j];
+                slot_of[pos] = sb + j;
+              }
+              if (kFused && (pos & ((1u << shift) - 1u)) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
+                blist[pos >> shift] = (uint32_t)tk[j];
+                bslot[pos >> shift] = (uint32_t)(sb + j);
+              }
               ++pos;
             }
           }
@@ -1448,13 +1499,20 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       }
     }
     if (hs.n_s > 0 && !cached) {
-      const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches,
-                                   emit_to(idx + A.seg_base, (uint32_t)A.b0_max), nullptr, nullptr, sm);
+      Emit E0 = emit_to(idx + A.seg_base, (uint32_t)A.b0_max);
+      if (kFused) {
+        E0.global = writer;
+        E0.lds = blist;
+        E0.lds_cap = (uint32_t)A.dlist_cap;
+        E0.shift = shift;
+        E0.split = split;
+      }
+      const int f = O::draw_sample(S, hs, (uint32_t)hs.b0, none, false, A.small_batches, E0, nullptr, nullptr, sm);
       flags |= ((f & 1) ? kFlagBaseComplement : 0) | ((f & 2) ? kFlagBaseBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
-      if (A.ascending && !(f & 1))
+      if (!kFused && A.ascending && !(f & 1))
         O::sort_ascending(idx + A.seg_base, (uint32_t)min(hs.b0, A.b0_max), scratch, wpre, n, sm);
     }
-    if (tid == 0) {
+    if (tid == 0 && writer) {
       HeadRec r;
       r.m = 0.f;
       r.scale = 0.f;
@@ -1468,6 +1526,83 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       r.base_cached = cached ? 1 : 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
+    }
+    if constexpr (kFused) {
+      // ---- the scores of this workgroup's share of I_f and of the base sample (denominator target) ----
+      // s_i = sm_scale <K[i], q>, written to the tokens' places of the sparse list; rows as in the gather below:
+      // tokens, block-table entries and rows each in a loop of their own over the slots in flight
+      constexpr int LPR = FD / 8;
+      constexpr int NG = NT / LPR;
+      constexpr int UF = 8;
+      const int g_sub = tid % LPR, g_grp = tid / LPR;
+      const int kvh = h / A.group;
+      __syncthreads();  // the lists of this workgroup's share are complete
+      float* spw = const_cast<float*>(A.sparse) + (int64_t)bh * A.idx_cap;
+      uint32_t qw[4];
+      {
+        const uint4 t = *reinterpret_cast<const uint4*>(A.gq + (int64_t)bh * FD + g_sub * 8);
+        qw[0] = t.x;
+        qw[1] = t.y;
+        qw[2] = t.z;
+        qw[3] = t.w;
+      }
+      auto score_of = [&](const uint4& kv) -> float {
+        float a = 0.f;
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv.x), __builtin_bit_cast(bf16x2_t, qw[0]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv.y), __builtin_bit_cast(bf16x2_t, qw[1]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv.z), __builtin_bit_cast(bf16x2_t, qw[2]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv.w), __builtin_bit_cast(bf16x2_t, qw[3]), a, false);
+        return group_sum<LPR>(a) * A.sm_scale + 0.0f;
+      };
+      const int my_nf = f0_hi - f0_lo;
+      for (int j0 = g_grp; j0 < my_nf; j0 += NG * UF) {
+        int tok[UF], blk[UF];
+        uint4 kv[UF];
+#pragma unroll
+        for (int u = 0; u < UF; ++u) tok[u] = (int)min(glist[min(j0 + u * NG, my_nf - 1)], (uint32_t)(n - 1));
+#pragma unroll
+        for (int u = 0; u < UF; ++u) blk[u] = kv_block<PAGED>(A.Lk, seq, tok[u]);
+#pragma unroll
+        for (int u = 0; u < UF; ++u)
+          kv[u] = load_stream_16(A.gk + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, tok[u], blk[u]) + g_sub * 8);
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+          const float sc = score_of(kv[u]);
+          const int j = j0 + u * NG;
+          if (j < my_nf && g_sub == 0)
+            spw[fixed_place(f0_lo + j, hs.n_sink, hs.n_win, A.seg_sink, A.seg_win, A.seg_topk)] = sc;
+        }
+      }
+      int my_nb = hs.n_s > 0 && hs.b0 > (int)split ? (int)(((uint32_t)hs.b0 - split + ((1u << shift) - 1u)) >> shift) : 0;
+      my_nb = min(my_nb, A.dlist_cap);
+      const unsigned char* crec = cached ? cache_record(A.rcache, A.rc, seq, A.Hkv, kvh) : nullptr;
+      for (int j0 = g_grp; j0 < my_nb; j0 += NG * UF) {
+        int tok[UF], blk[UF];
+        uint4 kv[UF];
+        if (cached) {
+          // the copies of the rows in the cache: rows of neighbouring slots, shared by the group's heads
+#pragma unroll
+          for (int u = 0; u < UF; ++u) tok[u] = (int)min(bslot[min(j0 + u * NG, my_nb - 1)], (uint32_t)(A.rc.slots - 1));
+#pragma unroll
+          for (int u = 0; u < UF; ++u)
+            kv[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(crec + A.rc.off_k) +
+                                                    (int64_t)tok[u] * FD + g_sub * 8);
+        } else {
+#pragma unroll
+          for (int u = 0; u < UF; ++u) tok[u] = (int)min(blist[min(j0 + u * NG, my_nb - 1)], (uint32_t)(n - 1));
+#pragma unroll
+          for (int u = 0; u < UF; ++u) blk[u] = kv_block<PAGED>(A.Lk, seq, tok[u]);
+#pragma unroll
+          for (int u = 0; u < UF; ++u)
+            kv[u] = load_stream_16(A.gk + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, tok[u], blk[u]) + g_sub * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+          const float sc = score_of(kv[u]);
+          const int j = j0 + u * NG;
+          if (j < my_nb && g_sub == 0) spw[A.seg_base + (((int64_t)j << shift) | split)] = sc;
+        }
+      }
     }
     return;
   }
@@ -1570,15 +1705,23 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
   }
   int flags = 0;
   if (bfin > 0) {
-    const int f = A.nested ? O::draw_nested(S, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
-                                            idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
-                           : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches,
-                                            emit_to(idx + A.seg_dyn, (uint32_t)A.b_max), nullptr, nullptr, sm);
+    Emit E1 = emit_to(idx + A.seg_dyn, (uint32_t)A.b_max);
+    if (kFused) {
+      E1.global = writer;
+      E1.lds = dlist;
+      E1.lds_cap = (uint32_t)A.dlist_cap;
+      E1.shift = shift;
+      E1.split = split;
+    }
+    const int f = (!kFused && A.nested)
+                      ? O::draw_nested(S, hs, (uint32_t)hs.b0, (uint32_t)bfin, bm_f, idx + A.seg_base,
+                                       idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
+                      : O::draw_sample(S, hs, (uint32_t)bfin, none, false, A.small_batches, E1, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
-    if (A.ascending && !A.nested && !(f & 1))
+    if (!kFused && A.ascending && !A.nested && !(f & 1))
       O::sort_ascending(idx + A.seg_dyn, (uint32_t)min(bfin, A.b_max), scratch, wpre, n, sm);
   }
-  if (tid == 0) {
+  if (tid == 0 && writer) {
     int32_t* c = A.out_counts + (int64_t)bh * 8;
     c[0] = hs.n_sink;
     c[1] = hs.n_win;
@@ -1608,7 +1751,143 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     r.n_s = hs.n_s;
     r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
     r.base_cached = 0;
-    A.head_rec[bh] = r;
+    // (with the gather fused in nothing reads the record again, and the head's other workgroups may still be
+    // reading the first phase's)
+    if (!kFused) A.head_rec[bh] = r;
+  }
+
+  if constexpr (kFused) {
+    // ---- the gather of this workgroup's share ----
+    // LPR adjacent lanes hold one row, NG rows per round, UF rounds in flight; places, tokens, block-table
+    // entries and rows each in a loop of their own over the UF slots (no branch per row); a slot beyond a list
+    // repeats its last entry and adds nothing.
+    constexpr int LPR = FD / 8;
+    constexpr int NG = NT / LPR;
+    constexpr int UF = 8;
+    const int g_sub = tid % LPR, g_grp = tid / LPR;
+    const int kvh = h / A.group;
+    __syncthreads();  // the final sample's share is complete in dlist
+    uint32_t qw[4];
+    {
+      const uint4 t = *reinterpret_cast<const uint4*>(A.gq + (int64_t)bh * FD + g_sub * 8);
+      qw[0] = t.x;
+      qw[1] = t.y;
+      qw[2] = t.z;
+      qw[3] = t.w;
+    }
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float dsum = 0.f, m_run = -INFINITY;
+    auto add_row = [&](float e, const uint4& vv) {
+      if (e > m_run) {
+        const float f = __expf(m_run - e);  // 0 when m_run is -inf
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c] *= f;
+        dsum *= f;
+        m_run = e;
+      }
+      const float wt = __expf(e - m_run);
+      add_weighted_row(acc, wt, vv);
+      dsum += wt;
+    };
+    // I_f: a contiguous run of [sink | window | top-k) per workgroup (the top-k part is in ascending token order)
+    const int n_fix2 = hs.n_sink + hs.n_win + k_eff;
+    const int run = (n_fix2 + (int)A.splits - 1) >> shift;
+    const int f_lo = min((int)split * run, n_fix2), f_hi = min(f_lo + run, n_fix2);
+    for (int j0 = f_lo + g_grp; j0 < f_hi; j0 += NG * UF) {
+      int64_t place[UF];
+      int tok[UF], blk[UF];
+      float sc[UF];
+      uint4 vv[UF];
+#pragma unroll
+      for (int u = 0; u < UF; ++u)
+        place[u] = fixed_place(min(j0 + u * NG, f_hi - 1), hs.n_sink, hs.n_win, A.seg_sink, A.seg_win, A.seg_topk);
+#pragma unroll
+      for (int u = 0; u < UF; ++u) {
+        tok[u] = min(max(idx[place[u]], 0), n - 1);
+        sc[u] = sp[place[u]];
+      }
+#pragma unroll
+      for (int u = 0; u < UF; ++u) blk[u] = kv_block<PAGED>(A.L, seq, tok[u]);
+#pragma unroll
+      for (int u = 0; u < UF; ++u)
+        vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.L, seq, kvh, tok[u], blk[u]) + g_sub * 8);
+#pragma unroll
+      for (int u = 0; u < UF; ++u)
+        if (j0 + u * NG < f_hi) add_row(sc[u], vv[u]);
+    }
+    // the final sample: every A.splits-th token, scores from the K rows, weights carry n_s / b
+    int my_nd = bfin > (int)split ? (int)(((uint32_t)bfin - split + ((1u << shift) - 1u)) >> shift) : 0;
+    my_nd = min(my_nd, A.dlist_cap);
+    const float tail_bias = bfin > 0 ? __logf((float)((double)hs.n_s / (double)bfin)) : 0.f;
+    for (int j0 = g_grp; j0 < my_nd; j0 += NG * UF) {
+      int tok[UF], blk[UF];
+      uint4 kv[UF], vv[UF];
+#pragma unroll
+      for (int u = 0; u < UF; ++u) tok[u] = (int)min(dlist[min(j0 + u * NG, my_nd - 1)], (uint32_t)(n - 1));
+#pragma unroll
+      for (int u = 0; u < UF; ++u) blk[u] = kv_block<PAGED>(A.L, seq, tok[u]);  // (K and V share the block table)
+#pragma unroll
+      for (int u = 0; u < UF; ++u) {
+        kv[u] = load_stream_16(A.gk + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, tok[u], blk[u]) + g_sub * 8);
+        vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.L, seq, kvh, tok[u], blk[u]) + g_sub * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < UF; ++u) {
+        // (the lanes of a group stay together: every lane of the group computes the row's score)
+        float a = 0.f;
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv[u].x), __builtin_bit_cast(bf16x2_t, qw[0]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv[u].y), __builtin_bit_cast(bf16x2_t, qw[1]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv[u].z), __builtin_bit_cast(bf16x2_t, qw[2]), a, false);
+        a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kv[u].w), __builtin_bit_cast(bf16x2_t, qw[3]), a, false);
+        const float s_row = group_sum<LPR>(a) * A.sm_scale + 0.0f;
+        if (j0 + u * NG < my_nd) add_row(s_row + tail_bias, vv[u]);
+      }
+    }
+    // the lane groups of a wave to their common maximum and added, then the waves through LDS
+    float M = m_run;
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+    {
+      const float f = m_run > -INFINITY ? __expf(m_run - M) : 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] *= f;
+      dsum *= f;
+    }
+#pragma unroll
+    for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[c] += __shfl_xor(acc[c], o);
+      dsum += __shfl_xor(dsum, o);
+    }
+    const int lane = tid & 63, wave = tid >> 6;
+    float* g_d = g_red + SW * FD;
+    float* g_m = g_d + SW;
+    if (lane < LPR) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) g_red[wave * FD + lane * 8 + c] = acc[c];
+    }
+    if (lane == 0) {
+      g_d[wave] = dsum;
+      g_m[wave] = M;
+    }
+    __syncthreads();
+    float Mall = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < SW; ++w2) Mall = fmaxf(Mall, g_m[w2]);
+    float* part = A.part + ((int64_t)bh * A.splits + split) * (FD + 4);
+    if (tid < FD) {
+      float a = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < SW; ++w2) a += g_red[w2 * FD + tid] * (g_m[w2] > -INFINITY ? __expf(g_m[w2] - Mall) : 0.f);
+      part[tid] = a;
+    }
+    if (tid == 0) {
+      float dt = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < SW; ++w2) dt += g_d[w2] * (g_m[w2] > -INFINITY ? __expf(g_m[w2] - Mall) : 0.f);
+      part[FD] = dt;
+      part[FD + 1] = Mall;
+    }
   }
 }
 
@@ -1632,13 +1911,21 @@ hipError_t set_kernel_attributes(const Plan& pl) {
   // kernels' static part), so that plans of different capacities can be used in any order.
   (void)pl;
   const int cap = 160 * 1024 - (int)head_kernel_static_lds_bytes();
+  const void* fused_given[4] = {reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads, 128, false>),
+                                reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads, 128, true>),
+                                reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads, 64, false>),
+                                reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads, 64, true>)};
+  for (const void* f : fused_given) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    if (e != hipSuccess) return e;
+  }
   const void* kernels[7] = {reinterpret_cast<const void*>(head_kernel<kHeadThreads, 0, false>),
                             reinterpret_cast<const void*>(head_kernel<kHeadThreadsLong, 0, false>),
                             reinterpret_cast<const void*>(head_kernel<kHeadThreads, 128, false>),
                             reinterpret_cast<const void*>(head_kernel<kHeadThreads, 128, true>),
                             reinterpret_cast<const void*>(head_kernel<kHeadThreads, 64, false>),
                             reinterpret_cast<const void*>(head_kernel<kHeadThreads, 64, true>),
-                            reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads>)};
+                            reinterpret_cast<const void*>(given_topk_kernel<kHeadThreads, 0, false>)};
   for (const void* f : kernels) {
     const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
     if (e != hipSuccess) return e;
@@ -1682,8 +1969,74 @@ hipError_t launch_given_select(const Plan& pl, int phase, const int32_t* seq_len
   A.given_cnt = given_cnt;
   A.rcache = rcache;
   A.rc = cache_layout(pl);
-  hipLaunchKernelGGL(given_topk_kernel<kHeadThreads>, dim3(pl.p.n_q_heads, pl.vbatch), dim3(kHeadThreads),
+  hipLaunchKernelGGL((given_topk_kernel<kHeadThreads, 0, false>), dim3(pl.p.n_q_heads, pl.vbatch), dim3(kHeadThreads),
                      pl.head_lds_bytes, st, A);
+  return hipGetLastError();
+}
+
+// Dynamic LDS of the selection phases of the caller-supplied-top-k path with scores / gather fused in: the first
+// phase keeps its run of I_f and its share of the base sample (tokens and cache slots), the second its share of
+// the final sample and the cross-wave sums.
+int given_glist_cap(const Plan& pl, int splits) { return (pl.p.sink + pl.p.window + pl.k_max) / splits + 2; }
+size_t given_fused_lds_bytes(const Plan& pl, int splits) {
+  const size_t dl = (size_t)fused_dlist_cap(pl, splits);
+  const size_t first = ((size_t)given_glist_cap(pl, splits) + 2 * dl) * sizeof(uint32_t);
+  const size_t second = dl * sizeof(uint32_t) + (size_t)(kHeadThreads / kWave) * (pl.p.head_dim + 2) * sizeof(float);
+  return head_kernel_lds_bytes(pl.p.n_max, kHeadThreads) + std::max(first, second);
+}
+
+bool given_fused_fits(const Plan& pl, int splits) {
+  if (splits < 1 || splits > 16 || (splits & (splits - 1)) != 0) return false;
+  if (pl.p.target != VATT_TARGET_D || (pl.p.head_dim != 64 && pl.p.head_dim != 128)) return false;
+  return given_fused_lds_bytes(pl, splits) + head_kernel_static_lds_bytes() <= 160 * 1024;
+}
+
+// The plan's own choice: as for the scored path, when there are at most half as many heads as compute units.
+int given_fused_splits_for(const Plan& pl) {
+  const int heads = pl.vbatch * pl.p.n_q_heads;
+  if (heads * 2 > pl.num_cus) return 0;
+  int s2 = 1;
+  while (s2 * 2 * heads <= pl.num_cus && s2 < 16) s2 *= 2;
+  while (s2 >= 1 && !given_fused_fits(pl, s2)) s2 /= 2;  // (fewer workgroups per head need longer LDS lists)
+  return given_fused_fits(pl, s2) ? s2 : 0;
+}
+
+hipError_t launch_given_fused(const Plan& pl, int phase, const void* q, const void* k, const void* v,
+                              const int32_t* block_table, const int32_t* seq_lens, const uint64_t* seq_seeds,
+                              const int32_t* given_idx, const int32_t* given_cnt, const void* rcache, void* ws,
+                              int32_t* out_idx, int32_t* out_counts, double* out_budget_raw, float* out_stats,
+                              hipStream_t st) {
+  HeadArgs A;
+  fill_head_args(A, pl, phase, seq_lens, seq_seeds, ws, out_idx, out_counts, out_budget_raw, out_stats);
+  const int S = pl.given_fuse_splits;
+  A.given_idx = given_idx;
+  A.given_cnt = given_cnt;
+  A.rcache = rcache;
+  A.rc = cache_layout(pl);
+  A.glist_cap = given_glist_cap(pl, S);
+  A.v = static_cast<const uint16_t*>(v);
+  A.L = pl.kv_v;
+  A.L.block_table = block_table;
+  A.gq = static_cast<const uint16_t*>(q);
+  A.gk = static_cast<const uint16_t*>(k);
+  A.Lk = pl.kv_k;
+  A.Lk.block_table = block_table;
+  A.sm_scale = pl.sm_scale;
+  A.part = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_gather_part);
+  A.splits = S;
+  A.split_shift = 0;
+  while ((1 << A.split_shift) < S) ++A.split_shift;
+  A.dlist_cap = fused_dlist_cap(pl, S);
+  const dim3 grid(pl.p.n_q_heads, pl.vbatch, S);
+  const size_t lds = given_fused_lds_bytes(pl, S);  // (the larger of the two phases' needs)
+  const bool paged = pl.p.kv_layout == VATT_LAYOUT_PAGED;
+  if (pl.p.head_dim == 128) {
+    if (paged) hipLaunchKernelGGL((given_topk_kernel<kHeadThreads, 128, true>), grid, dim3(kHeadThreads), lds, st, A);
+    else hipLaunchKernelGGL((given_topk_kernel<kHeadThreads, 128, false>), grid, dim3(kHeadThreads), lds, st, A);
+  } else {
+    if (paged) hipLaunchKernelGGL((given_topk_kernel<kHeadThreads, 64, true>), grid, dim3(kHeadThreads), lds, st, A);
+    else hipLaunchKernelGGL((given_topk_kernel<kHeadThreads, 64, false>), grid, dim3(kHeadThreads), lds, st, A);
+  }
   return hipGetLastError();
 }
 
@@ -1803,6 +2156,10 @@ static void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.dlist_cap = 0;
   A.pre_tok = nullptr;
   A.pre_flags = nullptr;
+  A.gq = nullptr;
+  A.gk = nullptr;
+  A.Lk = pl.kv_k;
+  A.sm_scale = pl.sm_scale;
   A.rcache = nullptr;
   A.rc = CacheLayout{};
   A.base_slot = reinterpret_cast<int32_t*>(w + pl.off_base_slot);
