@@ -374,6 +374,8 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     steps = args.steps if headline else max(20, min(args.steps, 60))
     warmup = args.warmup if headline else max(5, min(args.warmup, 10))
     wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[config]()
+    if args.batch > 0 and config == 3:
+        wl = workloads.config3(batch=args.batch)   # tuning aid: config 3's sequences at another batch size
     sess = DecodeSession(plan_params(wl))
     if args.budget_multiple != 1:
         from paper_2510_05688_amd import binding as vb_
@@ -388,6 +390,9 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
     if args.ascending:
         from paper_2510_05688_amd import binding as vb_
         vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_ASCENDING_SAMPLES, 1)
+    if args.given_fused >= 0:
+        from paper_2510_05688_amd import binding as vb_
+        vb_.vatt_plan_set_option(sess.plan, vb_.VATT_OPT_GIVEN_FUSED, args.given_fused)
     for opt, val in (("VATT_OPT_GIVEN_SPLITS", args.given_splits), ("VATT_OPT_SPARSE_SPLITS", args.sparse_splits)):
         if val > 0:
             from paper_2510_05688_amd import binding as vb_
@@ -671,6 +676,8 @@ def main():
     ap.add_argument("--fused-gather", type=int, default=-1,
                     help="workgroups per head of the selection kernel that also gathers (0: separate selection and "
                          "gather kernels; default: the plan's own choice, 8 at config 2 and 0 at the batched configs)")
+    ap.add_argument("--batch", type=int, default=0, help="tuning aid: with --config 3, another batch size than 16")
+    ap.add_argument("--given-fused", type=int, default=-1, help="tuning aid: VATT_OPT_GIVEN_FUSED (0: separate kernels)")
     ap.add_argument("--given-splits", type=int, default=0, help="tuning aid: workgroups per head of given_gather_kernel")
     ap.add_argument("--sparse-splits", type=int, default=0, help="tuning aid: workgroups per head of sparse_score_kernel")
     ap.add_argument("--nested", action="store_true",
