@@ -436,7 +436,7 @@ __device__ __forceinline__ void add_weighted_row(float (&acc)[8], float wt, cons
 // Only workgroup 0 of a head writes the index lists, counts, statistics and budget.  The rows of I_f are
 // requested as soon as the top-k set is known and are added after the samplers have run.
 template <int NT, int FD, bool PAGED>
-__global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
+__global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
   constexpr bool kFused = FD > 0;
   using O = HeadOps<NT>;
   using TKR = TopkOps<NT, RowView<NT>>;
@@ -1017,7 +1017,9 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   uint4 dv[UF];
   float ds[UF];
   int my_spec = 0;
-  if constexpr (kFused) {
+  // Without the fused gather the same shortcut saves the second scan and the samplers' own passes; the sorted
+  // and the nested forms of the lists are made by the general path only.
+  if (kTwoStreams && A.phase == 0 && (kFused || (!A.ascending && !A.nested))) {
     const uint32_t ns = (uint32_t)hs.n_s, c0 = (uint32_t)hs.b0;
     if (pair_made && hs.n_s > 0 && c0 < ns && 2u * c0 <= ns) {
       const DrawBatch& B = half ? spec1 : spec0;
@@ -1041,19 +1043,21 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
           const double w = take ? (double)__expf(spec0.sc[e] - m) : 0.0;
           acc_w += w;
           acc_w2 += w * w;
-        } else if (spec_dyn && take && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
+        } else if (kFused && spec_dyn && take && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
           dlist[pos >> shift] = spec1.tok[e];
           dlist_sc[pos >> shift] = spec1.sc[e];
         }
         pos += a ? 1u : 0u;
       }
-      __syncthreads();
-      VATT_STAMP(A.dbg, 5);
-      load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
-      if (spec_dyn) {
-        my_spec = hs.b0 > (int)split ? (int)(((uint32_t)hs.b0 - split + smask) >> shift) : 0;
-        my_spec = min(my_spec, A.dlist_cap);
-        load_rows(dlist, dlist_sc, 0, my_spec, ds, dv, ScInLds{});
+      if constexpr (kFused) {
+        __syncthreads();
+        VATT_STAMP(A.dbg, 5);
+        load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
+        if (spec_dyn) {
+          my_spec = hs.b0 > (int)split ? (int)(((uint32_t)hs.b0 - split + smask) >> shift) : 0;
+          my_spec = min(my_spec, A.dlist_cap);
+          load_rows(dlist, dlist_sc, 0, my_spec, ds, dv, ScInLds{});
+        }
       }
     }
   }
@@ -1159,8 +1163,10 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
   VATT_STAMP(A.dbg, 7);
   // ---- I_dyn (Algorithm 1, final sample) ----
   bool fast_dyn = false;
-  if constexpr (kFused) {
-    if (!fast_base) load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
+  {
+    if constexpr (kFused) {
+      if (!fast_base) load_rows(glist, glist_sc, 0, my_nf, fs, fv, ScInLds{});
+    }
     // the first batch of draws holds the whole final sample, and it is not taken as a complement: its members
     // are the accepted draws counted above, up to the budget
     fast_dyn = spec_dyn && (uint32_t)bfin <= tot1 && 2u * (uint32_t)bfin <= (uint32_t)hs.n_s;
@@ -1171,14 +1177,14 @@ __global__ __launch_bounds__(NT) void head_kernel(HeadArgs A) {
         const bool a = (acc_bits >> e) & 1u;
         if (half && a && pos < (uint32_t)bfin) {
           if (writer && pos < (uint32_t)A.b_max) idx[A.seg_dyn + pos] = (int32_t)spec1.tok[e];
-          if (pos >= (uint32_t)hs.b0 && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
+          if (kFused && pos >= (uint32_t)hs.b0 && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
             dlist[pos >> shift] = spec1.tok[e];
             dlist_sc[pos >> shift] = spec1.sc[e];
           }
         }
         pos += a ? 1u : 0u;
       }
-      __syncthreads();
+      if (kFused) __syncthreads();
     }
   }
   if (bfin > 0 && !fast_dyn) {
