@@ -255,6 +255,73 @@ def decode_loop(args, torch, np, workloads, DecodeSession):
     print(json.dumps(out))
 
 
+def host_kv_bench(args, torch, np, workloads, DecodeSession):
+    """The setting of the paper's efficiency experiment: K and V in pinned host memory, only the random cache of
+    base-sample rows (and the caller's top-k sets) on the GPU.  Times vatt_decode_given_topk_cached,
+    vatt_decode_given_topk, vatt_decode and vatt_dense_decode with every K / V row read over the host link, and
+    reports the bytes each moves over it.  The top-k sets are the exact ones of the workload (they stand in for an
+    approximate top-k method's)."""
+    from paper_2510_05688_amd import binding as vb
+    wl = {2: workloads.config2, 3: workloads.config3, 4: workloads.config4}[args.config]()
+    if args.batch > 0 and args.config == 3:
+        wl = workloads.config3(batch=args.batch)
+    sess = DecodeSession(plan_params(wl))
+    sess.upload(wl.q_bits, wl.k_bits, wl.v_bits, wl.seq_lens, wl.seeds)
+    B, Hq, Hkv, d, n = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_max
+    sess.decode()
+    seg2, seg3 = vb.vatt_plan_index_segment(sess.plan, 2), vb.vatt_plan_index_segment(sess.plan, 3)
+    topk_idx = sess.out_idx[:, :, seg2:seg3].contiguous()
+    topk_cnt = sess.out_counts[:, :, 2].contiguous()
+    sess.make_random_cache(np.arange(1, B + 1, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15))
+    legs = {"given_topk_cached": lambda i: sess.decode_given_topk_cached(topk_idx, topk_cnt),
+            "given_topk": lambda i: sess.decode_given_topk(topk_idx, topk_cnt),
+            "exact_scoring": lambda i: sess.decode(),
+            "dense": lambda i: sess.dense()}
+    steps = max(5, min(args.steps, 50))
+    on_device = {}
+    for name, fn in legs.items():
+        for i in range(3):
+            fn(i)
+        on_device[name] = time_calls(fn, steps, torch) * 1e3
+    sess.move_kv_to_host()
+    out = {"metric": "vattention_decode_us_per_layer_kv_on_host", "unit": "us", "n_gpus": 1, "steps": steps,
+           "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": wl.name, "kv_cache": "pinned host memory, read by the kernels over the host link",
+                      "on_gpu": "q, top-k lists, random cache of base-sample rows, workspace, outputs"}}
+    row = 2 * d
+    for name, fn in legs.items():
+        for i in range(2):
+            fn(i)
+        us = time_calls(fn, steps, torch) * 1e3
+        counts = sess.results_host()["counts"].reshape(-1, 8).astype(np.int64)
+        n_f = int((counts[:, 0] + counts[:, 1] + counts[:, 2]).sum())
+        b0, b = int(counts[:, 3].sum()), int(counts[:, 4].sum())
+        flags = counts[:, 7]
+        cached_heads = int(((flags & 64) != 0).sum())
+        if name == "dense":
+            link = 2 * int(np.asarray(wl.seq_lens).sum()) * Hkv * row
+        elif name == "exact_scoring":
+            link = int(np.asarray(wl.seq_lens).sum()) * Hkv * row + (n_f + b) * row
+        elif name == "given_topk":
+            # K and V rows of I_f and of the final sample; of the base sample its K rows (its scores), and its V
+            # rows too when the numerator is verified
+            link = (n_f + b) * 2 * row + b0 * row * (2 if int(wl.params.get("target", 0)) != 0 else 1)
+        else:
+            link = (n_f + b) * 2 * row                # the base sample's rows come from the cache on the GPU
+        out[name] = {"us_per_layer": us, "kv_on_device_us_per_layer": on_device[name], "host_link_bytes": link,
+                     "host_link_GBps": link / (us * 1e-6) / 1e9}
+        if name == "given_topk_cached":
+            out[name]["heads_with_base_sample_from_cache"] = cached_heads
+            out[name]["heads"] = int(counts.shape[0])
+    out["value"] = out["given_topk_cached"]["us_per_layer"]
+    out["ms_per_step"] = out["value"] * 1e-3
+    out["speedup_vs_dense"] = {k: out["dense"]["us_per_layer"] / out[k]["us_per_layer"]
+                               for k in ("given_topk_cached", "given_topk", "exact_scoring")}
+    out["bytes_ratio_vs_dense"] = {k: out["dense"]["host_link_bytes"] / out[k]["host_link_bytes"]
+                                   for k in ("given_topk_cached", "given_topk", "exact_scoring")}
+    print(json.dumps(out))
+
+
 def chunk_bench(args, torch, np, workloads, DecodeSession):
     """A multi-query step: the q_len newest tokens of every sequence are queries in one vatt_decode call.
 
@@ -691,6 +758,10 @@ def main():
                     help="query tokens per sequence and call (configs 2-4); above 1 times a multi-query step")
     ap.add_argument("--graph-steps", type=int, default=0,
                     help="time plain launches against replays of HIP graphs that hold this many steps each")
+    ap.add_argument("--host-kv", action="store_true",
+                    help="K and V in pinned host memory (the paper's efficiency experiment): times the caller-supplied-"
+                         "top-k step with the base sample from the random cache, the same without it, vatt_decode and "
+                         "dense decode, all reading the cache over the host link")
     ap.add_argument("--only", default="", help="profiling aid: run only 'decode', 'score', 'dense', 'read' (a kernel that only reads the K cache) or 'copy' (a 256 MiB device copy) in the timed loop")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -709,6 +780,9 @@ def main():
 
     if args.config == 5:
         decode_loop(args, torch, np, workloads, DecodeSession)
+        return
+    if args.host_kv:
+        host_kv_bench(args, torch, np, workloads, DecodeSession)
         return
     if args.q_len > 1:
         chunk_bench(args, torch, np, workloads, DecodeSession)

@@ -346,6 +346,26 @@ int vatt_score(vatt_plan* plan, const void* q, const void* k, const int32_t* blo
 int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
                    const int32_t* block_table, int32_t* seq_lens, void* stream);
 
+/*
+ * KV cache in host memory (the paper's efficiency experiment hosts the KV cache on the CPU and finds the time
+ * per step proportional to the amount of KV cache read; its implementation notes keep only the small random
+ * cache and the top-k method's own structures on the GPU).
+ *
+ * Wherever this header says "device" for k and v, the address of a cache that lives in pinned host memory
+ * (hipHostMalloc, or any allocator built on it) may be passed instead: the kernels then read the rows they
+ * need over the host link, and vatt_append_kv / vatt_append_kv_cached write the new rows there.  Every
+ * other buffer (q, lists, lengths, seeds, the random cache, workspace, outputs) stays in device memory.  With
+ * vatt_decode_given_topk_cached a step reads from the host only the K and V rows of I_f and of the final
+ * sample: the base sample comes from the cache on the device.
+ *
+ * This call translates a pointer into such an allocation to the address the kernels must be given (on this
+ * platform the same number) and is the check that the memory is of that kind: VATT_E_INVALID_ARG for ordinary
+ * process memory, which a kernel must never be handed.  Host only; nothing is launched.
+ *   host_ptr     host, anywhere inside a pinned allocation
+ *   device_ptr   host, receives the address to pass as k or v (NULL on error)
+ */
+int vatt_host_kv_device_pointer(const void* host_ptr, void** device_ptr);
+
 const char* vatt_status_string(int status);
 
 #ifdef __cplusplus

@@ -49,7 +49,7 @@ EXPORTS = [
     "vatt_plan_index_segment", "vatt_decode", "vatt_decode_static", "vatt_static_scratch_bytes", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
     "vatt_random_cache_bytes", "vatt_random_cache_slots", "vatt_random_cache_fill", "vatt_append_kv_cached",
     "vatt_decode_given_topk_cached", "vatt_random_cache_read",
-    "vatt_status_string",
+    "vatt_host_kv_device_pointer", "vatt_status_string",
 ]
 
 
@@ -113,6 +113,8 @@ def _load():
     lib.vatt_score.restype = ctypes.c_int
     lib.vatt_append_kv.argtypes = [vp] * 8
     lib.vatt_append_kv.restype = ctypes.c_int
+    lib.vatt_host_kv_device_pointer.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.vatt_host_kv_device_pointer.restype = ctypes.c_int
     lib.vatt_stream_read.argtypes = [vp, sz, vp, vp]
     lib.vatt_stream_read.restype = ctypes.c_int
     lib.vatt_random_cache_bytes.argtypes = [vp]
@@ -309,6 +311,15 @@ def vatt_random_cache_read(plan, rcache, out_tokens, out_counts, stream=None) ->
     rc = _lib.vatt_random_cache_read(plan, _ptr(rcache), _ptr(out_tokens), _ptr(out_counts), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_random_cache_read")
+
+
+def vatt_host_kv_device_pointer(host) -> int:
+    """Address to pass as k or v for a cache in pinned host memory (a tensor-like or an int address)."""
+    out = ctypes.c_void_p()
+    rc = _lib.vatt_host_kv_device_pointer(_ptr(host), ctypes.byref(out))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_host_kv_device_pointer")
+    return int(out.value)
 
 
 def vatt_stream_read(src, nbytes: int, sink, stream=None) -> None:

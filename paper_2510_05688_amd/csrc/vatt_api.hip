@@ -568,6 +568,24 @@ int vatt_dense_decode(vatt_plan* plan, const void* q, const void* k, const void*
   return VATT_OK;
 }
 
+int vatt_host_kv_device_pointer(const void* host_ptr, void** device_ptr) {
+  if (!host_ptr || !device_ptr) return VATT_E_INVALID_ARG;
+  *device_ptr = nullptr;
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, host_ptr) != hipSuccess) {
+    (void)hipGetLastError();  // ordinary process memory: not an error of the runtime's state, just not usable
+    return VATT_E_INVALID_ARG;
+  }
+  if (attr.type != hipMemoryTypeHost) return VATT_E_INVALID_ARG;
+  void* dev = nullptr;
+  if (hipHostGetDevicePointer(&dev, const_cast<void*>(host_ptr), 0) != hipSuccess || !dev) {
+    (void)hipGetLastError();
+    return VATT_E_INVALID_ARG;
+  }
+  *device_ptr = dev;
+  return VATT_OK;
+}
+
 int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink || !aligned16(src) || (bytes & 15u) != 0) return VATT_E_INVALID_ARG;
   VATT_LAUNCH(launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)));

@@ -77,6 +77,16 @@ class DecodeSession:
             self.block_table = torch.from_numpy(np.ascontiguousarray(block_table, dtype=np.int32)).to(dev)
         return self
 
+    def move_kv_to_host(self):
+        """Moves the uploaded K and V to pinned host memory; self.k / self.v become the addresses the kernels
+        read them at (vatt_host_kv_device_pointer), and the pinned tensors stay alive in self.k_host / v_host."""
+        torch.cuda.synchronize(self.device)
+        self.k_host = torch.empty(self.k.shape, dtype=self.k.dtype, pin_memory=True).copy_(self.k)
+        self.v_host = torch.empty(self.v.shape, dtype=self.v.dtype, pin_memory=True).copy_(self.v)
+        self.k = vb.vatt_host_kv_device_pointer(self.k_host)
+        self.v = vb.vatt_host_kv_device_pointer(self.v_host)
+        return self
+
     def set_seeds(self, seeds):
         self.seq_seeds = torch.from_numpy(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64)).to(self.device)
 
