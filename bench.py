@@ -41,7 +41,7 @@ STEP_TRAFFIC_BYTES = {"config2": 91280881, "config3": 1539533225, "config4": 142
 # profiler (profiles/decode_config2_kernel_stats.md, profiles/decode_config3_kernel_stats.md)
 PROFILE_KERNEL_US = {
     "config2": {"score_kernel": 13.85, "head_kernel (selection with the gather fused in)": 23.57, "gather_merge_kernel": 4.13},
-    "config3": {"score_kernel": 180.50, "head_kernel": 32.77, "gather_kernel": 49.76, "gather_merge_kernel": 4.33},
+    "config3": {"score_kernel": 180.50, "head_kernel": 31.88, "gather_kernel": 49.76, "gather_merge_kernel": 4.33},
     "config4": {"score_kernel": 176.94, "head_kernel": 40.04, "gather_kernel": 40.56, "gather_merge_kernel": 4.31},
 }
 LLAMA8B_LAYERS = 32
