@@ -989,11 +989,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
   };
   using ScInLds = std::true_type;
   using ScInRow = std::false_type;
-  if constexpr (kFused) {
-    const int n_f = hs.n_sink + hs.n_win + hs.k;
-    (void)n_f;
-    my_nf = (int)(g_hi - g_lo);
-  }
+  if constexpr (kFused) my_nf = (int)(g_hi - g_lo);
 
   VATT_STAMP(A.dbg, 32);
   if (want1 && !spec1_made) O::make_batch(spec1, S1, hs, 0u, ahead_blocks<NT>(A.small_batches), false, false, sm, tid);
