@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libvatt.so")
-SOURCES = ["vatt_api.hip", "vatt_score.hip", "vatt_score_chunk.hip", "vatt_select.hip", "vatt_gather.hip", "vatt_given.hip", "vatt_dense.hip", "vatt_rcache.hip", "vatt_util.hip"]
+SOURCES = ["vatt_api.hip", "vatt_score.hip", "vatt_score_chunk.hip", "vatt_select.hip", "vatt_select_given.hip", "vatt_gather.hip", "vatt_given.hip", "vatt_dense.hip", "vatt_rcache.hip", "vatt_util.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     # packed-fp32 VALU forms are kept out of the generated code on purpose

@@ -8,10 +8,6 @@
 #include "vatt_internal.h"
 
 namespace vatt {
-
-size_t head_kernel_lds_bytes(int n_max, int head_threads);
-size_t head_kernel_static_lds_bytes();
-
 namespace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

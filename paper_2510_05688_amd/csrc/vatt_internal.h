@@ -142,7 +142,12 @@ hipError_t launch_dense(const Plan& pl, const void* q, const void* k, const void
                         const int32_t* seq_lens, void* ws, float* out_o, float* out_lse, hipStream_t st);
 hipError_t launch_append(const Plan& pl, const void* k_new, const void* v_new, void* k, void* v,
                          const int32_t* block_table, int32_t* seq_lens, hipStream_t st);
-hipError_t set_kernel_attributes(const Plan& pl);
+hipError_t set_kernel_attributes(const Plan& pl);        // every selection kernel: dynamic LDS limit
+hipError_t set_given_kernel_attributes(const Plan& pl);  // (its part for the caller-supplied-top-k kernels)
+// Dynamic and static LDS of the selection kernels, and the LDS list entries of the fused gathers.
+size_t head_kernel_lds_bytes(int n_max, int head_threads);
+size_t head_kernel_static_lds_bytes();
+int fused_dlist_cap(const Plan& pl, int splits);
 // Reads `bytes` (a multiple of 16) from src and discards them; sink is 4 KiB of device memory.
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 
