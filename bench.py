@@ -581,6 +581,30 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
         read_only(i)
     ms_read = time_calls(read_only, steps, torch)
 
+    # what a kernel that only reads rows takes for the V rows this step gathers (the listed tokens of every
+    # head, in list order), on the same cycled buffers: the practical floor of the gather
+    seg_ = res["seg"]
+    row_list = []
+    for bh in range(counts.shape[0]):
+        b_, h_ = divmod(bh, Hq)
+        base_row = (b_ * Hkv + h_ // (Hq // Hkv)) * n
+        ix = res["idx"].reshape(-1, res["idx"].shape[-1])[bh]
+        toks = np.concatenate([ix[seg_[s_]:seg_[s_] + int(counts[bh, c_])] for s_, c_ in ((0, 0), (1, 1), (2, 2), (4, 4))])
+        row_list.append(base_row + toks.astype(np.int64))
+    row_list = np.concatenate(row_list)
+    rows_dev = torch.from_numpy(row_list.astype(np.int32)).to("cuda")
+    n_rows_total = B * Hkv * n
+
+    def rows_only(i):
+        vb2.vatt_row_read(vs[i % nbuf], n_rows_total, rows_dev, int(row_list.size), sink,
+                          torch.cuda.current_stream().cuda_stream)
+
+    ms_rows = None
+    if d == 128 and n_rows_total < 2 ** 31:
+        for i in range(warmup):
+            rows_only(i)
+        ms_rows = time_calls(rows_only, steps, torch)
+
     # the same step with the top-k set supplied by the caller (here: the exact one found above, standing in for
     # an approximate top-k method): no K scan, only the attended rows are read
     given = None
@@ -690,7 +714,12 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
                  "us": (ms_step - ms_score) * 1e3, "us_source": "step time minus the score kernel's",
                  "bytes": path_bytes - score_kernel_bytes,
                  "achieved": (path_bytes - score_kernel_bytes) / max((ms_step - ms_score) * 1e-3, 1e-9) / 1e9,
-                 "frac": (path_bytes - score_kernel_bytes) / max((ms_step - ms_score) * 1e-3, 1e-9) / 1e9 / HBM_PEAK_GBPS},
+                 "frac": (path_bytes - score_kernel_bytes) / max((ms_step - ms_score) * 1e-3, 1e-9) / 1e9 / HBM_PEAK_GBPS,
+                 # a kernel that only reads the V rows this step gathers (vatt_row_read), same buffers: the floor of
+                 # the gather part alone
+                 "read_only_gathered_rows_us": None if ms_rows is None else ms_rows * 1e3,
+                 "read_only_gathered_rows_gbps": None if ms_rows is None else row_list.size * d * 2 / (ms_rows * 1e-3) / 1e9,
+                 "gathered_rows": int(row_list.size)},
             ],
             "profile_us": PROFILE_KERNEL_US.get("config%d" % config),
         },

@@ -63,6 +63,17 @@ enum { VATT_WS_DEBUG = 1 };
 int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 
 /*
+ * Measurement aid: one kernel that reads `count` rows of 256 bytes (a K or V row at head_dim 128) of the
+ * 16-byte aligned device buffer src and discards them, in the access shape of the gather kernels (16 lanes per
+ * row, 8 rows in flight per lane group, row numbers taken from a list).  Its duration is the practical floor
+ * for gathering that many rows in one launch.
+ *   rows_total  rows in src (at most 2^31 - 1); listed row numbers outside [0, rows_total) are clamped into it
+ *   rows        device, int32 [count]
+ *   sink        device, at least 4 KiB, may be written (practically never is)
+ */
+int vatt_row_read(const void* src, size_t rows_total, const int32_t* rows, size_t count, void* sink, void* stream);
+
+/*
  * Token lists of a random cache of base-sample rows (vatt_random_cache_fill in vatt.h), for comparison with a
  * reference: out_tokens (device, int32 [B, Hkv, vatt_random_cache_slots(plan)]) gets the token of every slot in
  * slot order, -1 for slots not in use; out_counts (device, int32 [B, Hkv]) the number of slots in use.

@@ -46,7 +46,7 @@ VATT_BOUND_HOEFFDING_RANGE = 2
 EXPORTS = [
     "vatt_plan_create", "vatt_plan_create_chunk", "vatt_plan_query_len", "vatt_plan_destroy", "vatt_plan_set_option", "vatt_plan_workspace_bytes",
     "vatt_plan_workspace_offset", "vatt_plan_score_stride", "vatt_plan_index_capacity",
-    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_static", "vatt_static_scratch_bytes", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read",
+    "vatt_plan_index_segment", "vatt_decode", "vatt_decode_static", "vatt_static_scratch_bytes", "vatt_decode_given_topk", "vatt_dense_decode", "vatt_score", "vatt_append_kv", "vatt_stream_read", "vatt_row_read",
     "vatt_random_cache_bytes", "vatt_random_cache_slots", "vatt_random_cache_fill", "vatt_append_kv_cached",
     "vatt_decode_given_topk_cached", "vatt_random_cache_read",
     "vatt_host_kv_device_pointer", "vatt_status_string",
@@ -116,6 +116,8 @@ def _load():
     lib.vatt_host_kv_device_pointer.argtypes = [vp, ctypes.POINTER(vp)]
     lib.vatt_host_kv_device_pointer.restype = ctypes.c_int
     lib.vatt_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.vatt_row_read.argtypes = [vp, sz, vp, sz, vp, vp]
+    lib.vatt_row_read.restype = ctypes.c_int
     lib.vatt_stream_read.restype = ctypes.c_int
     lib.vatt_random_cache_bytes.argtypes = [vp]
     lib.vatt_random_cache_bytes.restype = sz
@@ -311,6 +313,13 @@ def vatt_random_cache_read(plan, rcache, out_tokens, out_counts, stream=None) ->
     rc = _lib.vatt_random_cache_read(plan, _ptr(rcache), _ptr(out_tokens), _ptr(out_counts), _ptr(stream))
     if rc != VATT_OK:
         raise VattError(rc, "vatt_random_cache_read")
+
+
+def vatt_row_read(src, rows_total: int, rows, count: int, sink, stream=None) -> None:
+    """Measurement aid: read the listed 256-byte rows of the device buffer src and discard them."""
+    rc = _lib.vatt_row_read(_ptr(src), int(rows_total), _ptr(rows), int(count), _ptr(sink), _ptr(stream))
+    if rc != VATT_OK:
+        raise VattError(rc, "vatt_row_read")
 
 
 def vatt_host_kv_device_pointer(host) -> int:

@@ -588,6 +588,12 @@ int vatt_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
   return VATT_OK;
 }
 
+int vatt_row_read(const void* src, size_t rows_total, const int32_t* rows, size_t count, void* sink, void* stream) {
+  if (!src || !rows || !sink || !aligned16(src) || rows_total == 0) return VATT_E_INVALID_ARG;
+  VATT_LAUNCH(launch_row_read(src, rows_total, rows, count, sink, static_cast<hipStream_t>(stream)));
+  return VATT_OK;
+}
+
 int vatt_append_kv(vatt_plan* plan, const void* k_new, const void* v_new, void* k, void* v,
                    const int32_t* block_table, int32_t* seq_lens, void* stream) {
   if (!plan) return VATT_E_INVALID_ARG;

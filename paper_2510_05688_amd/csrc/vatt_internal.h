@@ -150,6 +150,9 @@ size_t head_kernel_static_lds_bytes();
 int fused_dlist_cap(const Plan& pl, int splits);
 // Reads `bytes` (a multiple of 16) from src and discards them; sink is 4 KiB of device memory.
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+// Reads the 256-byte rows rows[0 .. count) (row numbers, clamped into [0, rows_total)) of src and discards them.
+hipError_t launch_row_read(const void* src, size_t rows_total, const int32_t* rows, size_t count, void* sink,
+                           hipStream_t st);
 
 }  // namespace vatt
 
