@@ -313,7 +313,7 @@ def test_append_to_a_contiguous_cache_then_decode():
     sess.close()
 
 
-@pytest.mark.parametrize("path", ["scored", "scored_sdpa_target", "given_topk", "multi_query"])
+@pytest.mark.parametrize("path", ["scored", "scored_sdpa_target", "given_topk", "given_topk_cached", "multi_query"])
 def test_decode_inside_a_hip_graph(path):
     say("%s step captured in a HIP graph and replayed" % path)
     import torch
@@ -332,6 +332,13 @@ def test_decode_inside_a_hip_graph(path):
         topk_idx = sess.out_idx[:, :, seg[2]:seg[3]].contiguous()
         topk_cnt = sess.out_counts[:, :, 2].contiguous()
         call = lambda: sess.decode_given_topk(topk_idx, topk_cnt)  # noqa: E731
+    if path == "given_topk_cached":
+        first = _run(sess)
+        seg = first["seg"]
+        topk_idx = sess.out_idx[:, :, seg[2]:seg[3]].contiguous()
+        topk_cnt = sess.out_counts[:, :, 2].contiguous()
+        sess.make_random_cache(np.array([11, 12], dtype=np.uint64))
+        call = lambda: sess.decode_given_topk_cached(topk_idx, topk_cnt)  # noqa: E731
     call()
     eager = sess.results_host()
     side = torch.cuda.Stream()
