@@ -24,13 +24,14 @@ struct GatherArgs {
   const uint16_t* v;
   KVLayout L;
   const float* scores;
+  const float* place_sc;  // [B*Hq][idx_cap]: scores of listed tokens at their list places (selection kernel)
   const HeadRec* head_rec;
   const int32_t* idx;
   float* part;        // [B*Hq][splits][d + 4]
   double* vpart;      // [B*Hq][splits][2d + 2]
   float* out_o;
   float* out_lse;
-  int64_t seg_topk, seg_base, seg_dyn, idx_cap;
+  int64_t seg_sink, seg_win, seg_topk, seg_base, seg_dyn, idx_cap;
   int n_pad, Hq, group, splits;
   int group_major, Hkv;  // see head_of_block
   int q_len;  // query tokens per sequence: blockIdx.z = sequence * q_len + query token
@@ -54,12 +55,18 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   const int sub = lane % LPR, rsub = lane / LPR;
 
   const HeadRec r = A.head_rec[bh];
+  // (pointers that are the same for the whole workgroup, indexed with 32-bit offsets: address arithmetic in 64
+  // bits for every row was most of this kernel's instructions, and the kernel was bound by issuing them)
   const int32_t* idx = A.idx + (int64_t)bh * A.idx_cap;
-  const float* row = A.scores + (int64_t)bh * A.n_pad;
+  const float* placed = A.place_sc + (int64_t)bh * A.idx_cap;  // scores by list place
+  const float* row = A.scores + (int64_t)bh * A.n_pad;          // scores by token
+  const bool tail_by_token = r.tail_by_token != 0;               // (the same for the whole workgroup)
+  const uint16_t* v_head = PAGED ? A.v : A.v + (int64_t)seq * A.L.seq_stride + (int64_t)kvh * A.L.head_stride;
   const int total = r.n_sink + r.n_win + r.k + r.b;
   const int per = (total + A.splits - 1) / A.splits;
   const int p_lo = split * per, p_hi = min(p_lo + per, total);
-  const int64_t seg_tail = STATS ? A.seg_base : A.seg_dyn;
+  const uint32_t seg_sink = (uint32_t)A.seg_sink, seg_win = (uint32_t)A.seg_win, seg_topk = (uint32_t)A.seg_topk;
+  const uint32_t seg_tail = (uint32_t)(STATS ? A.seg_base : A.seg_dyn), last_place = (uint32_t)A.idx_cap - 1u;
   const float tail_scale = STATS ? 1.0f : r.scale;
 
   float acc[8], acc2[8];
@@ -67,43 +74,66 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   for (int c = 0; c < 8; ++c) acc[c] = acc2[c] = 0.f;
   float dsum = 0.f, r2 = 0.f;
 
-  // U rows per lane group at a time, in stages without a branch per row, so that the loads of a stage go out
-  // together: tokens (sink and window tokens by arithmetic, the others from the lists; every slot issues the
-  // list load, at a harmless place where it is not needed), block-table entries on a paged cache, then scores
-  // and V rows.  A slot beyond the range repeats the range's last row with weight 0.
+  // A wave takes RPW * U rows per step: RPW lane groups of LPR lanes, U rows in flight per group.  The work
+  // that belongs to a row, not to a column, is done once per row by the row's own lane (lane L of the wave for row
+  // L of the step) instead of by every lane of the group that reads the row: list place, list entry and score
+  // (sink and window tokens follow from the place by arithmetic; their list load is issued all the same), the
+  // token and the weight.  Token and weight then reach the group's lanes through a wave shuffle, which leaves
+  // the vector ALU free: with all of it done per lane this kernel was bound by issuing instructions, not by
+  // memory.  Then, in stages without a branch per row, so that the loads of a stage go out together:
+  // block-table entries on a paged cache, the V rows, the sums.  A place beyond the range carries weight 0.
+  constexpr int ROWS_W = RPW * U;   // rows of a wave per step (32 at d = 128, 64 at d = 64)
+  static_assert(ROWS_W <= kWave, "one lane per row of a step");
   const int n_sw = r.n_sink + r.n_win;
-  for (int p0 = p_lo + wave * RPW + rsub; p0 < p_hi; p0 += RPB * U) {
+  const int win_shift = r.n - r.n_win - r.n_sink;  // window token = list position + this
+  const int u_mine = lane / RPW, g_mine = lane % RPW;   // the row this lane prepares: slot u_mine of lane group g_mine
+  for (int p0 = p_lo; p0 < p_hi; p0 += RPB * U) {
+    const int p = p0 + u_mine * RPB + wave * RPW + g_mine;
+    const bool valid = lane < ROWS_W && p < p_hi;
+    const int pc = min(p, p_hi - 1);
+    const int t2 = pc - n_sw, t3 = t2 - r.k;
+    const bool is_tail = t3 >= 0;
+    const uint32_t edge = pc < r.n_sink ? seg_sink + (uint32_t)pc : seg_win + (uint32_t)(pc - r.n_sink);
+    const uint32_t place = min(is_tail ? seg_tail + (uint32_t)t3 : t2 >= 0 ? seg_topk + (uint32_t)t2 : edge, last_place);
+    const int listed = idx[place];
+    float sc = placed[place];
+    const int by_rule = pc < r.n_sink ? pc : pc + win_shift;
+    const int tok_mine = min(max(t2 >= 0 ? listed : by_rule, 0), r.n - 1);
+    if (tail_by_token) {  // a sample whose scores were not at hand when its list was written
+      const float by_token = row[tok_mine];
+      sc = is_tail ? by_token : sc;
+    }
+    const float wt_mine = valid ? __expf(sc - r.m) * (is_tail ? tail_scale : 1.0f) : 0.f;
+    if (!(STATS && is_tail)) dsum += wt_mine;
+
     int tok[U], blk[U];
-    float w[U];
-    bool tail[U], valid[U];
+    float wt[U];
+    bool tail[U];
     uint4 vv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int p = p0 + u * RPB;
-      valid[u] = p < p_hi;
-      const int pc = min(p, p_hi - 1);
-      const int t2 = pc - n_sw, t3 = t2 - r.k;
-      tail[u] = t3 >= 0;
-      const int64_t place = tail[u] ? seg_tail + t3 : A.seg_topk + max(t2, 0);
-      const int listed = idx[min(place, A.idx_cap - 1)];
-      const int by_rule = pc < r.n_sink ? pc : r.n - r.n_win + (pc - r.n_sink);
-      tok[u] = min(max(t2 >= 0 ? listed : by_rule, 0), r.n - 1);
+      const int src = u * RPW + rsub;
+      tok[u] = __shfl(tok_mine, src);
+      wt[u] = __shfl(wt_mine, src);
+      tail[u] = STATS ? (__shfl((int)is_tail, src) != 0) : false;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) blk[u] = kv_block<PAGED>(A.L, seq, tok[u]);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      w[u] = row[tok[u]];
-      vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.L, seq, kvh, tok[u], blk[u]) + sub * 8);
+      if constexpr (PAGED) vv[u] = load_stream_16(A.v + kv_row_offset_in<true>(A.L, seq, kvh, tok[u], blk[u]) + sub * 8);
+      else vv[u] = load_stream_16(v_head + ((uint32_t)tok[u] * (uint32_t)D + (uint32_t)(sub * 8)));  // (n_max * d < 2^32)
     }
+    // (all U rows are requested before the first is used: left to itself the scheduler waits for the first rows
+    // in order to reuse their registers for the later ones)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float wt = valid[u] ? __expf(w[u] - r.m) * (tail[u] ? tail_scale : 1.0f) : 0.f;
       const uint32_t ww[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
       if (STATS && tail[u]) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const float a = wt * bf16_lo(ww[c]), bb = wt * bf16_hi(ww[c]);
+          const float a = wt[u] * bf16_lo(ww[c]), bb = wt[u] * bf16_hi(ww[c]);
           acc2[2 * c] += a;
           acc2[2 * c + 1] += bb;
           r2 += a * a + bb * bb;
@@ -111,10 +141,9 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          acc[2 * c] += wt * bf16_lo(ww[c]);
-          acc[2 * c + 1] += wt * bf16_hi(ww[c]);
+          acc[2 * c] += wt[u] * bf16_lo(ww[c]);
+          acc[2 * c + 1] += wt[u] * bf16_hi(ww[c]);
         }
-        dsum += sub == 0 ? wt : 0.f;
       }
     }
   }
@@ -223,12 +252,15 @@ hipError_t launch_gather_d(const Plan& pl, const void* v, const int32_t* block_t
   A.L = pl.kv_v;
   A.L.block_table = block_table;
   A.scores = reinterpret_cast<const float*>(w + pl.off_scores);
+  A.place_sc = reinterpret_cast<const float*>(w + pl.off_sparse);
   A.head_rec = reinterpret_cast<const HeadRec*>(w + pl.off_head_rec);
   A.idx = out_idx;
   A.part = reinterpret_cast<float*>(w + pl.off_gather_part);
   A.vpart = reinterpret_cast<double*>(w + pl.off_vstat_part);
   A.out_o = out_o;
   A.out_lse = out_lse;
+  A.seg_sink = pl.seg_off[0];
+  A.seg_win = pl.seg_off[1];
   A.seg_topk = pl.seg_off[2];
   A.seg_base = pl.seg_off[3];
   A.seg_dyn = pl.seg_off[4];

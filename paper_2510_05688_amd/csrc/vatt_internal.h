@@ -30,6 +30,9 @@ struct HeadRec {
   int32_t n, n_sink, n_win, k, b, n_s;
   int32_t b_keep;  // leading entries of the final sample that repeat the base sample (nested samples), else 0
   int32_t base_cached;  // the base sample's entries are slots of the random cache (their rows are read from it)
+  int32_t tail_by_token;  // the gather reads the sampled tokens' scores from the score row by token (else, like
+                          // those of sink, window and top-k, from where the selection kernel left them: at the
+                          // list places)
 };
 
 struct Plan {

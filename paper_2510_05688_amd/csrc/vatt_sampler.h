@@ -50,6 +50,7 @@ struct Emit {
   uint32_t lds_cap;
   uint32_t shift, split;
   bool global;
+  float* sc_dst;      // nullptr, or where the scores of the listed tokens go when the batch has them at hand
 };
 __device__ __forceinline__ void emit_tok(const Emit& E, uint32_t p, int32_t tok) {
   if (E.global && p < E.dst_cap) E.dst[p] = tok;
@@ -64,6 +65,7 @@ __device__ __forceinline__ Emit emit_to(int32_t* dst, uint32_t dst_cap) {
   E.shift = 0;
   E.split = 0;
   E.global = true;
+  E.sc_dst = nullptr;
   return E;
 }
 
@@ -325,6 +327,7 @@ struct HeadOps {
         const bool take = a && pos < room;
         if (!invert) {
           if (take) emit_tok(E, have + pos, (int32_t)B.tok[e]);
+          if (take && E.sc_dst && B.have_sc && have + pos < E.dst_cap) E.sc_dst[have + pos] = B.sc[e];
           if (sum_w) {
             const float sc = B.have_sc ? B.sc[e] : (take ? S.row[B.tok[e]] : 0.f);
             const double w = take ? (double)__expf(sc - S.m) : 0.0;

@@ -22,6 +22,8 @@ struct HeadArgs {
   const int32_t* given_idx;  // [B*Hq][k_max]: caller-supplied top-k tokens (given-top-k path)
   const int32_t* given_cnt;  // [B*Hq]
   const float* sparse;       // [B*Hq][idx_cap]: scores at the places of the index lists (given-top-k path)
+  float* place_sc;           // the same region on the scored path: the selection-only kernel leaves there the
+                             // score of every listed token, for the gather kernel
   const int32_t* seq_lens;
   const uint64_t* seq_seeds;
   HeadRec* head_rec;
@@ -466,6 +468,7 @@ inline void fill_head_args(HeadArgs& A, const Plan& pl, int phase, const int32_t
   A.given_vstat = reinterpret_cast<const float*>(w + pl.off_vstat_part);
   A.given_splits = pl.given_splits;
   A.sparse = reinterpret_cast<const float*>(w + pl.off_sparse);
+  A.place_sc = reinterpret_cast<float*>(w + pl.off_sparse);
   A.v = nullptr;
   A.L = pl.kv_v;
   A.part = nullptr;

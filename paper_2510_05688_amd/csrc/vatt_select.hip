@@ -115,6 +115,11 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
 
   const float* row = A.scores + (int64_t)bh * A.n_pad;
   int32_t* idx = A.out_idx + (int64_t)bh * A.idx_cap;
+  // Selection-only kernel: where a list is written with the scores at hand (sink, window, top-k, and a final
+  // sample that the first batch of draws holds) they are left at the list places, so that the gather kernel reads
+  // them next to the list entries instead of from the score row by token.  A sample made another way is read by
+  // token (HeadRec.tail_by_token).
+  float* place_sc = A.place_sc + (int64_t)bh * A.idx_cap;
   const uint64_t seed = A.seq_seeds[seq];
 
   VATT_STAMP(A.dbg, 0);
@@ -221,6 +226,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
     spec0.blocks = spec1.blocks = blocks;
     spec0.have_sc = true;
     if (half) spec1 = mine; else spec0 = mine;
+    spec1.have_sc = true;  // (the same answer in every thread; the lower half holds no draws of this stream)
     spec1_made = true;
     pair_made = true;
   } else if (want0) {
@@ -489,6 +495,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
             const uint32_t i = min((uint32_t)c, (uint32_t)(n - 1));
             const uint32_t pos = wpre[i >> 5] + (uint32_t)__popc(bm_f[i >> 5] & ((1u << (i & 31)) - 1u));
             if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = (int32_t)i;
+            if (!kFused && pos < (uint32_t)A.k_max) place_sc[A.seg_topk + pos] = float_from_order_key(~(uint32_t)(c >> 32));
             to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, i, float_from_order_key(~(uint32_t)(c >> 32)));
           }
         }
@@ -503,6 +510,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
             bits &= bits - 1u;
             if (writer && pos < (uint32_t)A.k_max) idx[A.seg_topk + pos] = i;
             if (kFused) to_glist((uint32_t)(hs.n_sink + hs.n_win) + pos, (uint32_t)i, row[i]);
+            else if (pos < (uint32_t)A.k_max) place_sc[A.seg_topk + pos] = row[i];
             ++pos;
           }
         }
@@ -516,10 +524,12 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
     for (int i = tid; i < hs.n_sink; i += NT) {
       if (writer) idx[A.seg_sink + i] = i;
       if (kFused) to_glist((uint32_t)i, (uint32_t)i, i == tid ? edge0 : row[i]);
+      else place_sc[A.seg_sink + i] = i == tid ? edge0 : row[i];
     }
     for (int i = tid; i < hs.n_win; i += NT) {
       if (writer) idx[A.seg_win + i] = hs.mid_hi + i;
       if (kFused) to_glist((uint32_t)(hs.n_sink + i), (uint32_t)(hs.mid_hi + i), i == tid ? edge1 : row[hs.mid_hi + i]);
+      else place_sc[A.seg_win + i] = i == tid ? edge1 : row[hs.mid_hi + i];
     }
   } else {
     // phase 2: rebuild the top-k bitmap from the list written in phase 1
@@ -684,6 +694,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
       r.n_s = hs.n_s;
       r.b_keep = 0;
       r.base_cached = 0;
+      r.tail_by_token = 1;  // (the statistics pass walks the base sample, whose scores are not at its places)
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -702,6 +713,17 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
 #pragma unroll
     for (int w = 0; w < SW; ++w) key = max(key, ts.wu[0][w]);
     w_range = exp((double)float_from_order_key(~key) - (double)m);
+  }
+  // Long rows (1024 threads; their samples hold thousands of tokens and the first batch of draws usually holds
+  // the whole final sample): the scores of that batch's proposals are requested now and arrive under the sums
+  // and the budget; they go to the list places with the accepted tokens.  (In the 512-thread kernel, which is
+  // short of registers, the same cost more than the gather gains: a sample that its shortcut above does not
+  // cover is read by token.)
+  constexpr bool kEmitScores = !kFused && NT >= 1024;
+  if (kEmitScores && want1 && !spec1.have_sc) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) spec1.sc[e] = row[min(spec1.tok[e], (uint32_t)(n - 1))];
+    spec1.have_sc = true;
   }
   double sums[3] = {acc_f, acc_w, acc_w2};
   O::block_sum(sums, sm);
@@ -769,6 +791,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
         const bool a = (acc_bits >> e) & 1u;
         if (half && a && pos < (uint32_t)bfin) {
           if (writer && pos < (uint32_t)A.b_max) idx[A.seg_dyn + pos] = (int32_t)spec1.tok[e];
+          if (!kFused && pos < (uint32_t)A.b_max) place_sc[A.seg_dyn + pos] = spec1.sc[e];
           if (kFused && pos >= (uint32_t)hs.b0 && (pos & smask) == split && (pos >> shift) < (uint32_t)A.dlist_cap) {
             dlist[pos >> shift] = spec1.tok[e];
             dlist_sc[pos >> shift] = spec1.sc[e];
@@ -779,9 +802,11 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
       if (kFused) __syncthreads();
     }
   }
+  bool dyn_placed = fast_dyn;  // the final sample's scores are at its list places
   if (bfin > 0 && !fast_dyn) {
     Emit E1 = emit_to(idx + A.seg_dyn, (uint32_t)A.b_max);
     E1.global = writer;
+    if (kEmitScores) E1.sc_dst = place_sc + A.seg_dyn;
     if (kFused) {
       E1.lds = dlist;
       E1.lds_cap = (uint32_t)A.dlist_cap;
@@ -793,6 +818,8 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
                                        idx + A.seg_dyn, (uint32_t)A.b_max, A.small_batches, sm)
                       : O::draw_sample(S1, hs, (uint32_t)bfin, spec1, want1, A.small_batches, E1, nullptr, nullptr, sm);
     flags |= ((f & 1) ? kFlagDynComplement : 0) | ((f & 2) ? kFlagDynBatches : 0) | ((f & 4) ? kFlagDrawCap : 0);
+    // (one batch made ahead with its scores held the whole sample, and the list stays in acceptance order)
+    dyn_placed = kEmitScores && !A.nested && !A.ascending && want1 && spec1.have_sc && f == 0;
     if (!kFused && A.ascending && !A.nested && !(f & 1))
       O::sort_ascending(idx + A.seg_dyn, (uint32_t)min(bfin, A.b_max), scratch, wpre, n, sm);
     VATT_STAMP(A.dbg, 8);
@@ -820,6 +847,7 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
     r.n_s = hs.n_s;
     r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
     r.base_cached = 0;
+    r.tail_by_token = dyn_placed ? 0 : 1;
     A.head_rec[bh] = r;
   }
   VATT_STAMP(A.dbg, 9);

@@ -240,6 +240,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
       r.n_s = hs.n_s;
       r.b_keep = 0;
       r.base_cached = cached ? 1 : 0;
+      r.tail_by_token = 0;
       A.head_rec[bh] = r;
       A.out_counts[(int64_t)bh * 8 + 7] = flags;
     }
@@ -467,6 +468,7 @@ __global__ __launch_bounds__(NT) void given_topk_kernel(HeadArgs A) {
     r.n_s = hs.n_s;
     r.b_keep = (A.nested && bfin > 0) ? hs.b0 : 0;
     r.base_cached = 0;
+    r.tail_by_token = 0;
     // (with the gather fused in nothing reads the record again, and the head's other workgroups may still be
     // reading the first phase's)
     if (!kFused) A.head_rec[bh] = r;
