@@ -221,7 +221,10 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
       mine.blocks = blocks;
       mine.have_sc = true;
     } else {
-      O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, true, sm, tid - half * (NT / 2));
+      // (selection-only kernel, which runs with every CU full: the scores of the final sample's proposals are
+      // requested later, after the top-k step; a million scattered 4-byte reads at once, from all workgroups in
+      // their first microseconds, held every workgroup up for five microseconds at config 3)
+      O::make_batch(mine, half ? S1 : S0, hs, 0u, blocks, false, kFused || !half, sm, tid - half * (NT / 2));
     }
     spec0.blocks = spec1.blocks = blocks;
     spec0.have_sc = true;
@@ -540,6 +543,10 @@ __global__ __launch_bounds__(NT, FD > 0 ? 1 : 4) void head_kernel(HeadArgs A) {
     }
     for (int i = tid; i < hs.n_sink; i += NT) acc_f += (double)__expf(row[i] - m);
     for (int i = tid; i < hs.n_win; i += NT) acc_f += (double)__expf(row[hs.mid_hi + i] - m);
+  }
+  if (!kFused && pair_made && tid >= NT / 2) {  // (whole waves: the upper half holds the final sample's proposals)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) spec1.sc[e] = row[spec1.tok[e]];
   }
   VATT_STAMP(A.dbg, 30);
   __syncthreads();
