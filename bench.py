@@ -733,8 +733,8 @@ def measure_config(config, args, torch, np, workloads, DecodeSession, headline):
         sel_bytes = select_r + (v_rows + gather_r if fused else 0)
         n_heads = int(counts.shape[0])
         # partial sums per head that the merge adds: 8 workgroups of the fused kernel, else the plan's gather splits
-        # (enough for 32 workgroups per CU of a 256-CU chip, at most 32)
-        n_part = 8 if fused else min(32, max(1, -(-32 * 256 // n_heads)))
+        # (enough for 16 workgroups per CU of a 256-CU chip, at most 16)
+        n_part = 8 if fused else min(16, max(1, -(-16 * 256 // n_heads)))
         shares = [("head_kernel", sel_bytes)] + ([] if fused else [("gather_kernel", v_rows + gather_r)]) + \
                  [("gather_merge_kernel", n_heads * n_part * (d + 4) * 4 + n_heads * d * 4)]
         for key, nbytes in shares:

@@ -37,7 +37,7 @@ extern "C" {
  *   VATT_OPT_SCORE_PREWORK = 0 / 1: with the fused gather, whether the first batches of the sampler's draw
  *     sequences are made by the first workgroups of the score launch while the rest of it streams K (1, the
  *     default for such plans in the KV-head-major launch order) or by the selection kernel itself (0).
- *   VATT_OPT_GIVEN_SPLITS, VATT_OPT_SPARSE_SPLITS = 1 .. the plan's gather split count: workgroups per head of
+ *   VATT_OPT_GIVEN_SPLITS, VATT_OPT_SPARSE_SPLITS = 1 .. enough for 32 workgroups per CU (at most 32): workgroups per head of
  *     the gather kernel and of the score kernel of the listed tokens on the path with a caller-supplied top-k set
  *     (tuning aids; the plan picks both).
  *   VATT_OPT_GIVEN_FUSED = 0, 1, 2, 4, 8 or 16: on that path, 0 keeps the second selection phase and the gather

@@ -126,14 +126,19 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
 
   const int heads = pl.vbatch * p.n_q_heads;
   const int want_blocks = 2 * pl.num_cus;
-  pl.gather_splits = std::min(32, std::max(1, (32 * pl.num_cus + heads - 1) / heads));  // measured: 32 workgroups per CU beat 8, 16 and 64
+  // most workgroups per head that any of the gathering kernels uses (sizes the regions of their partial sums)
+  pl.split_cap = std::min(32, std::max(1, (32 * pl.num_cus + heads - 1) / heads));
+  // measured (gather kernel alone, us, with 4 / 8 / 16 / 32 / 64 workgroups per head): 512 heads 42.4 / 41.2 / 41.3 /
+  // 52.7 / 84.7; 128 heads with long lists 32.3 / 31.1 / 30.5 / 32.1 / 33.3; 1024 heads on a paged cache 57.8 /
+  // 59.1 / 66.2 / 103.8 / 186.8: 16 workgroups per CU, at most 16 per head
+  pl.gather_splits = std::min(16, std::max(1, (16 * pl.num_cus + heads - 1) / heads));
   pl.vstat_splits = pl.gather_splits;
   // (the kernels of the path with a caller-supplied top-k, by measurement: its gather, which also reads K rows
   // and carries running maxima, 16 workgroups per CU and at most 16 per head; its score kernel, which only
   // writes scores, 32 per CU and at most 16 per head.  At 512 heads: 128.5 us per step with 8 and 2 per head,
   // 122.4 us with 16 and 8; at 128 heads 8 to 16 of each are equal; at 32 heads 16 and 16 are best.)
-  pl.given_splits = std::min(std::min(pl.gather_splits, 16), std::max(1, (16 * pl.num_cus + heads - 1) / heads));
-  pl.sparse_splits = std::min(std::min(pl.gather_splits, 16), std::max(1, (32 * pl.num_cus + heads - 1) / heads));
+  pl.given_splits = std::min(std::min(pl.split_cap, 16), std::max(1, (16 * pl.num_cus + heads - 1) / heads));
+  pl.sparse_splits = std::min(std::min(pl.split_cap, 16), std::max(1, (32 * pl.num_cus + heads - 1) / heads));
   const int kv_heads = pl.vbatch * p.n_kv_heads;
   const int max_dense = std::max(1, (n_max + 255) / 256);
   pl.dense_splits = std::min(std::min(64, max_dense), std::max(1, (2 * want_blocks + kv_heads - 1) / kv_heads));
@@ -161,9 +166,9 @@ int build_plan(Plan& pl, const vatt_params& p, int q_len, int device) {
   pl.off_sub_max = take((size_t)heads * pl.n_sub * sizeof(float));
   pl.off_sparse = take((size_t)heads * pl.idx_cap * sizeof(float));
   pl.off_head_rec = take((size_t)heads * sizeof(HeadRec));
-  pl.off_gather_part = take((size_t)heads * std::max(pl.gather_splits, 16) * (p.head_dim + 4) * sizeof(float));
+  pl.off_gather_part = take((size_t)heads * std::max(pl.split_cap, 16) * (p.head_dim + 4) * sizeof(float));
   pl.off_debug = take(512 * sizeof(uint64_t));
-  pl.off_vstat_part = take((size_t)heads * pl.vstat_splits * (2 * p.head_dim + 2) * sizeof(double));
+  pl.off_vstat_part = take((size_t)heads * pl.split_cap * (2 * p.head_dim + 2) * sizeof(double));
   pl.off_dense_part = take((size_t)heads * pl.dense_splits * (p.head_dim + 4) * sizeof(float));
   pl.off_pre_tok = take((size_t)heads * kHeadThreads * sizeof(uint4));
   pl.off_pre_flags = take((size_t)heads * kHeadThreads * sizeof(uint32_t));
@@ -363,7 +368,7 @@ int vatt_plan_set_option(vatt_plan* plan, int option, int value) {
     return VATT_OK;
   }
   if (option == VATT_OPT_GIVEN_SPLITS || option == VATT_OPT_SPARSE_SPLITS) {
-    if (value < 1 || value > plan->pl.gather_splits) return VATT_E_INVALID_ARG;
+    if (value < 1 || value > plan->pl.split_cap) return VATT_E_INVALID_ARG;
     (option == VATT_OPT_GIVEN_SPLITS ? plan->pl.given_splits : plan->pl.sparse_splits) = value;
     return VATT_OK;
   }

@@ -53,6 +53,7 @@ struct Plan {
   int n_sub;          // sub-tiles of kSubTile keys per row (the score kernel leaves each one's largest score)
   int k_max, b0_max, b_max;
   int head_threads;   // workgroup size of the per-head kernel
+  int split_cap;  // upper bound of the four split counts below that share the partial-sum regions
   int gather_splits, dense_splits, vstat_splits, given_splits;
   int given_fuse_splits;  // caller-supplied top-k: > 0, the second selection phase also gathers, with this many workgroups per head
   int sparse_splits;  // workgroups per head of the score kernel of the listed tokens when it only writes scores
