@@ -87,16 +87,34 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs A) {
   const int n_sw = r.n_sink + r.n_win;
   const int win_shift = r.n - r.n_win - r.n_sink;  // window token = list position + this
   const int u_mine = lane / RPW, g_mine = lane % RPW;   // the row this lane prepares: slot u_mine of lane group g_mine
+  // (the list entry and the score of the next step's row are requested one step ahead, so that a step starts
+  // with them at hand: one dependent round trip per step instead of two)
+  auto place_of = [&](int p0) {
+    const int pc = min(p0 + u_mine * RPB + wave * RPW + g_mine, p_hi - 1);
+    const int t2 = pc - n_sw, t3 = t2 - r.k;
+    const uint32_t edge = pc < r.n_sink ? seg_sink + (uint32_t)pc : seg_win + (uint32_t)(pc - r.n_sink);
+    return min(t3 >= 0 ? seg_tail + (uint32_t)t3 : t2 >= 0 ? seg_topk + (uint32_t)t2 : edge, last_place);
+  };
+  int listed_next = 0;
+  float sc_next = 0.f;
+  if (p_lo < p_hi) {
+    const uint32_t place0 = place_of(p_lo);
+    listed_next = idx[place0];
+    sc_next = placed[place0];
+  }
   for (int p0 = p_lo; p0 < p_hi; p0 += RPB * U) {
     const int p = p0 + u_mine * RPB + wave * RPW + g_mine;
     const bool valid = lane < ROWS_W && p < p_hi;
     const int pc = min(p, p_hi - 1);
     const int t2 = pc - n_sw, t3 = t2 - r.k;
     const bool is_tail = t3 >= 0;
-    const uint32_t edge = pc < r.n_sink ? seg_sink + (uint32_t)pc : seg_win + (uint32_t)(pc - r.n_sink);
-    const uint32_t place = min(is_tail ? seg_tail + (uint32_t)t3 : t2 >= 0 ? seg_topk + (uint32_t)t2 : edge, last_place);
-    const int listed = idx[place];
-    float sc = placed[place];
+    const int listed = listed_next;
+    float sc = sc_next;
+    {
+      const uint32_t place_n = place_of(p0 + RPB * U);  // (beyond the range: the range's last place once more)
+      listed_next = idx[place_n];
+      sc_next = placed[place_n];
+    }
     const int by_rule = pc < r.n_sink ? pc : pc + win_shift;
     const int tok_mine = min(max(t2 >= 0 ? listed : by_rule, 0), r.n - 1);
     if (tail_by_token) {  // a sample whose scores were not at hand when its list was written
