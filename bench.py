@@ -36,11 +36,11 @@ SCORE_KERNEL_TRAFFIC_BYTES = {"config2": int((32827.5 * 262144.0 / 131084.4 + 46
 SCORE_CHUNK_TRAFFIC_BYTES = {("config2", 4): int((32928.6 * 262144.0 / 131084.4 + 18432.7) * 1024)}
 # HBM bytes of all kernels of one vatt_decode step, same two counters, scaled by what they read for a 256 MiB
 # device copy (FETCH_SIZE x 1.99974, WRITE_SIZE x 1.0): profiles/decode_config{2,3,4}_kernel_stats.md
-STEP_TRAFFIC_BYTES = {"config2": 91280881, "config3": 1537473331, "config4": 1421102828}
+STEP_TRAFFIC_BYTES = {"config2": 91222118, "config3": 1537473331, "config4": 1421102828}
 # rocprofv3 --kernel-trace --stats averages (us) of the kernels of one step, `python3 bench.py --no-cpu` under the
 # profiler (profiles/decode_config2_kernel_stats.md, profiles/decode_config3_kernel_stats.md)
 PROFILE_KERNEL_US = {
-    "config2": {"score_kernel": 13.85, "head_kernel (selection with the gather fused in)": 23.57, "gather_merge_kernel": 4.13},
+    "config2": {"score_kernel": 13.61, "head_kernel (selection with the gather fused in)": 23.49, "gather_merge_kernel": 4.29},
     "config3": {"score_kernel": 181.11, "head_kernel": 31.20, "gather_kernel": 41.14, "gather_merge_kernel": 4.47},
     "config4": {"score_kernel": 177.42, "head_kernel": 44.03, "gather_kernel": 30.33, "gather_merge_kernel": 4.40},
 }
