@@ -34,14 +34,20 @@ struct DenseArgs {
   float sm_scale;
 };
 
-template <int D, int G, bool PAGED>
+// SHARE (multi-query steps): the query tokens of a sequence scan the same rows, so their workgroups for one
+// (KV head, split) are launched next to each other, eight apart in launch order and therefore on one XCD at
+// the same time, and read K and V with plain loads: the first to ask fetches a line from HBM, the others find
+// it in that XCD's L2.  blockIdx.y = split * q_len + query token, blockIdx.z = sequence.
+template <int D, int G, bool PAGED, bool SHARE>
 __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
   constexpr int LPR = D / 8;
   constexpr int RPW = kWave / LPR;
   constexpr int WAVES = kDenseThreads / kWave;
   constexpr int U = 4;
 
-  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int kvh = blockIdx.x;
+  const int split = SHARE ? (int)blockIdx.y / A.q_len : (int)blockIdx.y;
+  const int b = SHARE ? (int)blockIdx.z * A.q_len + (int)blockIdx.y % A.q_len : (int)blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rsub = lane / LPR;
   const int seq = b / A.q_len, qtok = b - seq * A.q_len;
@@ -85,8 +91,10 @@ __global__ __launch_bounds__(kDenseThreads) void dense_kernel(DenseArgs A) {
       ok[u] = i < hi;
       kk[u] = vv[u] = make_uint4(0u, 0u, 0u, 0u);
       if (ok[u]) {
-        kk[u] = load_stream_16(A.k + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, i, blk[u]) + sub * 8);
-        vv[u] = load_stream_16(A.v + kv_row_offset_in<PAGED>(A.Lv, seq, kvh, i, blk[u]) + sub * 8);
+        const uint16_t* pk = A.k + kv_row_offset_in<PAGED>(A.Lk, seq, kvh, i, blk[u]) + sub * 8;
+        const uint16_t* pv = A.v + kv_row_offset_in<PAGED>(A.Lv, seq, kvh, i, blk[u]) + sub * 8;
+        kk[u] = SHARE ? *reinterpret_cast<const uint4*>(pk) : load_stream_16(pk);
+        vv[u] = SHARE ? *reinterpret_cast<const uint4*>(pv) : load_stream_16(pv);
       }
     }
     float s[G][U];
@@ -214,11 +222,16 @@ __global__ __launch_bounds__(2 * D) void dense_merge_kernel(const float* __restr
 template <int D, int G>
 hipError_t launch_dense_dg(const Plan& pl, DenseArgs& A, hipStream_t st) {
   const vatt_params& p = pl.p;
-  dim3 grid(p.n_kv_heads, pl.dense_splits, pl.vbatch);
-  if (p.kv_layout == VATT_LAYOUT_PAGED)
-    hipLaunchKernelGGL((dense_kernel<D, G, true>), grid, dim3(kDenseThreads), 0, st, A);
-  else
-    hipLaunchKernelGGL((dense_kernel<D, G, false>), grid, dim3(kDenseThreads), 0, st, A);
+  const bool paged = p.kv_layout == VATT_LAYOUT_PAGED;
+  if (pl.q_len > 1) {
+    dim3 grid(p.n_kv_heads, pl.dense_splits * pl.q_len, p.batch);
+    if (paged) hipLaunchKernelGGL((dense_kernel<D, G, true, true>), grid, dim3(kDenseThreads), 0, st, A);
+    else hipLaunchKernelGGL((dense_kernel<D, G, false, true>), grid, dim3(kDenseThreads), 0, st, A);
+  } else {
+    dim3 grid(p.n_kv_heads, pl.dense_splits, pl.vbatch);
+    if (paged) hipLaunchKernelGGL((dense_kernel<D, G, true, false>), grid, dim3(kDenseThreads), 0, st, A);
+    else hipLaunchKernelGGL((dense_kernel<D, G, false, false>), grid, dim3(kDenseThreads), 0, st, A);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((dense_merge_kernel<D>), dim3(p.n_q_heads, pl.vbatch), dim3(2 * D), 0, st, A.part, pl.dense_splits,
