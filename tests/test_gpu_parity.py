@@ -6,7 +6,8 @@ import torch
 import workloads
 from workloads.configs import default_params, append_tokens
 from oracle import vatt_oracle as vo
-from parity import alternatives_used, check_all, check_head, gpu_segments, head_inputs, say, score_tolerance
+from parity import (alternatives_used, check_all, check_head, check_head_given, gpu_segments, head_inputs, say,
+                    score_tolerance)
 from util import plan_params
 
 pytestmark = pytest.mark.gpu
@@ -728,6 +729,41 @@ def test_tiny_caches(n_max):
     sess.dense()
     torch.cuda.synchronize()
     assert np.all(np.isfinite(sess.dense_o.cpu().numpy()))
+    sess.close()
+
+
+@pytest.mark.timeout(300)
+def test_largest_supported_capacity():
+    # the selection kernel's LDS bitmaps bound the capacity: 170752 tokens is the last one a plan accepts, one
+    # more is refused on the host; a full row and a ragged one at that capacity against the oracle, every head,
+    # on a contiguous and on a paged cache, and with the top-k sets handed back in
+    from paper_2510_05688_amd import binding as vb
+    from paper_2510_05688_amd.session import DecodeSession
+    n_max = 170752
+    say("largest capacity n_max=%d" % n_max)
+    p = default_params(128, sink=128, window=512, topk_frac=0.01)
+    wl = workloads.make_workload("cap_max", batch=2, n_q_heads=4, n_kv_heads=1, head_dim=128, n_max=n_max,
+                                 seq_lens=[n_max, n_max - 4097], seed=170, params=p)
+    with pytest.raises(vb.VattError) as e:
+        DecodeSession(plan_params(wl, n_max=n_max + 1))
+    assert e.value.status == vb.VATT_E_UNSUPPORTED_SHAPE
+    sess = _session(wl)
+    res = _run(sess)
+    reps = check_all(wl, res, gpu_scores=sess.scores_host(), label="cap_max")
+    assert len(reps) == 8 and alternatives_used(reps) == (0, 0)
+    seg2, seg3 = vb.vatt_plan_index_segment(sess.plan, 2), vb.vatt_plan_index_segment(sess.plan, 3)
+    topk_idx = sess.out_idx[:, :, seg2:seg3].contiguous()
+    topk_cnt = sess.out_counts[:, :, 2].contiguous()
+    sess.decode_given_topk(topk_idx, topk_cnt)
+    res_g = sess.results_host()
+    for b in range(2):
+        for h in range(4):
+            supplied = res["idx"][b, h][res["seg"][2]:res["seg"][2] + int(res["counts"][b, h, 2])]
+            check_head_given(wl, res_g, b, h, supplied, label="cap_max")
+    sess.close()
+    sess = _paged_session(wl, page=16, seed=5)
+    res_p = _run(sess)
+    _same_results(wl, res, res_p)
     sess.close()
 
 
